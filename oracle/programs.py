@@ -1,0 +1,105 @@
+"""The five benchmark programs written as compositions of oracle operators.
+
+TEST INFRASTRUCTURE (see the package docstring).  Each function takes a
+``workloads.Workload`` and returns a dict of numpy results.  Nothing here adds
+arithmetic of its own beyond the loss gradient the harness feeds in.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+from . import (dense_to_triples, damp_apply2_fwd, damp_apply2_bwd, filter_plan, damp_filter_fwd, damp_filter_bwd,
+               union_plan, damp_union_fwd, damp_union_bwd, reach_fwd, reach_bwd, dtkp_init, dtkp_apply2)
+
+
+def _sum_tri(sa, sb):
+    t = (np.asarray(sa, np.int32)[:, None] + np.asarray(sb, np.int32)[None, :]).astype(np.int32)
+    return dense_to_triples(t)
+
+
+def sum2_fwd(w):
+    """Config 1: apply(D1, D2, x+y) under DAMP (Fig. 2 with two digits)."""
+    syms, out = damp_apply2_fwd(dense_to_triples(w["table"]), 10, 10, w["pa"], w["pb"])
+    return dict(syms=syms, out=out)
+
+
+def nll_grad(p_final, target):
+    """Upstream gradient of loss = -log p[target] per sample (harness side)."""
+    g = np.zeros_like(p_final)
+    rows = np.arange(p_final.shape[0])
+    pt = np.maximum(p_final[rows, target], np.finfo(np.float32).tiny)
+    g[rows, target] = (-1.0 / pt.astype(np.float64)).astype(np.float32)
+    return g
+
+
+def sum_chain_fwd_bwd(w, want_bwd=True):
+    """Config 2: left fold of apply(D_res, D_i, x+y) (Fig. 2), then the reverse
+    sweep of vector-Jacobian products from loss = -log p[target]."""
+    p = w["p"]
+    n = p.shape[0]
+    sym = np.asarray(w["sym"], np.int32)
+    accs, syms_list, tris = [p[0]], [sym], []
+    for t in range(1, n):
+        tri = _sum_tri(syms_list[-1], sym)
+        s, o = damp_apply2_fwd(tri, syms_list[-1].size, sym.size, accs[-1], p[t])
+        tris.append(tri); syms_list.append(s); accs.append(o)
+    res = dict(syms=syms_list[-1], out=accs[-1], accs=accs)
+    if not want_bwd:
+        return res
+    g = nll_grad(accs[-1], w["target"])
+    res["g_out"] = g
+    grads = [None] * n
+    for t in range(n - 1, 0, -1):
+        ga, gb = damp_apply2_bwd(tris[t - 1], syms_list[t - 1].size, sym.size, accs[t - 1], p[t], g)
+        grads[t] = gb
+        g = ga
+    grads[0] = g
+    res["grad_p"] = np.stack(grads)
+    return res
+
+
+def hashed_pipeline_fwd_bwd(w):
+    """Config 3: apply with a hashed table, filter by a keep-mask over the output
+    ids, union with a second Distribution over all ids; then backward."""
+    na, nb, n_out = w["na"], w["nb"], w["n_out"]
+    tri = dense_to_triples(w["table"])
+    s1, o1 = damp_apply2_fwd(tri, na, nb, w["pa"], w["pb"])
+    pred = w["keep"][s1]                      # predicate evaluated on the symbols present
+    s2, _ = filter_plan(s1, pred)
+    o2 = damp_filter_fwd(pred, o1)
+    all_ids = np.arange(n_out, dtype=np.int32)
+    s3, ia, ib = union_plan(s2, all_ids)
+    o3 = damp_union_fwd(ia, ib, o2, w["p2"])
+    g3 = w["g"][:, :s3.size]
+    g2, gp2 = damp_union_bwd(ia, ib, o2, w["p2"], g3)
+    g1 = damp_filter_bwd(pred, g2)
+    ga, gb = damp_apply2_bwd(tri, na, nb, w["pa"], w["pb"], g1)
+    return dict(s1=s1, o1=o1, s2=s2, o2=o2, s3=s3, o3=o3, g2=g2, gp2=gp2, g1=g1, ga=ga, gb=gb)
+
+
+def dtkp_sum_chain(w):
+    """Config 4: the sum fold under DTKP-AM; digit slot n, value d is fact 10n+d."""
+    p = w["p"]
+    n, B = p.shape[0], p.shape[1]
+    k = w["k"]
+    sym = np.asarray(w["sym"], np.int32)
+    fp, grp = w["fact_prob"], w["fact_group"]
+    m, pp, pr = dtkp_init(np.arange(10, dtype=np.int32), fp, k)
+    syms = sym
+    stages = []
+    for t in range(1, n):
+        dm, _, _ = dtkp_init(10 * t + np.arange(10, dtype=np.int32), fp, k)
+        tri = _sum_tri(syms, sym)
+        syms2, m, pp, pr = dtkp_apply2(tri, syms.size, sym.size, k, grp, fp, m, dm)
+        syms = syms2
+        stages.append((syms, m, pp, pr))
+    return dict(syms=syms, mask=m, pprob=pp, prob=pr, stages=stages)
+
+
+def grid_reach_fwd_bwd(w):
+    """Config 5: fixed-round single-source reachability and its backward."""
+    side = w["side"]
+    n = side * side
+    hist = reach_fwd(n, w["edge_u"], w["edge_v"], w["src"], w["rounds"], w["p"])
+    gp = reach_bwd(n, w["edge_u"], w["edge_v"], w["rounds"], w["p"], hist, w["g"])
+    return dict(r=hist[-1], hist=hist, grad_p=gp)

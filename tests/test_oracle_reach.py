@@ -1,0 +1,136 @@
+"""Pins for the CPU oracle's grid-reachability program (no GPU)."""
+import numpy as np
+
+import oracle
+import workloads as W
+
+
+def dense_round_matrix(n, eu, ev, p):
+    """A[v,u] = p(u,v) (symmetric) in float64 for one sample."""
+    A = np.zeros((n, n))
+    for e, (u, v) in enumerate(zip(eu, ev)):
+        A[v, u] = p[e]
+        A[u, v] = p[e]
+    return A
+
+
+def f64_reach(n, eu, ev, src, rounds, p):
+    A = dense_round_matrix(n, eu, ev, p.astype(np.float64))
+    r = np.zeros(n); r[src] = 1.0
+    for _ in range(rounds):
+        r = np.minimum(1.0, r + A @ r)
+    return r
+
+
+def test_edge_numbering():
+    u, v = W.grid_edges(3)
+    assert list(zip(u, v)) == [(0, 1), (1, 2), (3, 4), (4, 5), (6, 7), (7, 8),
+                               (0, 3), (1, 4), (2, 5), (3, 6), (4, 7), (5, 8)]
+    u, v = W.grid_edges(32)
+    assert u.size == 2 * 32 * 31 == 1984
+
+
+def test_small_probabilities_match_matrix_power():
+    """No clamping when all p <= 0.01 (except the source, pinned at 1): r_t = min(1, (I+A)^t e_src)."""
+    side, rounds, B = 4, 6, 3
+    eu, ev = W.grid_edges(side)
+    p = (W.uniform01(3, B * eu.size) * 0.01).astype(np.float32).reshape(B, -1)
+    hist = oracle.reach_fwd(side * side, eu, ev, 0, rounds, p)
+    for s in range(B):
+        A = dense_round_matrix(side * side, eu, ev, p[s].astype(np.float64))
+        M = np.linalg.matrix_power(np.eye(side * side) + A, rounds)
+        ref = M[:, 0]
+        got = hist[-1, s].astype(np.float64)
+        assert got[0] == 1.0                      # the source saturates
+        # away from the source the clamp at the source perturbs by O(p^2): compare with the clamped recurrence too
+        np.testing.assert_allclose(got[1:], ref[1:], rtol=5e-4)
+        np.testing.assert_allclose(got, f64_reach(side * side, eu, ev, 0, rounds, p[s]), rtol=1e-6, atol=1e-12)
+
+
+def test_first_round_and_distance_and_monotone():
+    w = W.config5(batch=4, side=8, rounds=16, seed=1)
+    eu, ev = w["edge_u"], w["edge_v"]
+    hist = oracle.reach_fwd(64, eu, ev, 0, 16, w["p"])
+    assert np.all(hist[0, :, 0] == 1) and np.all(hist[0, :, 1:] == 0)
+    # r_1 at the two neighbours of the source equals the edge probability
+    np.testing.assert_array_equal(hist[1, :, 1], w["p"][:, 0])                 # edge (0,1) is horizontal edge 0
+    np.testing.assert_array_equal(hist[1, :, 8], w["p"][:, 8 * 7])             # edge (0,8) is the first vertical
+    for v in range(64):
+        d = v // 8 + v % 8
+        assert np.all(hist[:d, :, v] == 0) if d > 0 else True
+        if d <= 16:
+            assert np.all(hist[d, :, v] > 0)
+    assert np.all(np.diff(hist, axis=0) >= 0)
+    assert hist.min() >= 0 and hist.max() <= 1
+
+
+def test_full_size_all_nodes_reached():
+    w = W.config5(batch=2, seed=0)
+    hist = oracle.reach_fwd(1024, w["edge_u"], w["edge_v"], 0, 64, w["p"])
+    assert np.all(hist[-1] > 0)               # farthest node is 62 steps away
+    assert np.all(hist[61, :, 1023] == 0) and np.all(hist[62, :, 1023] > 0)
+
+
+def test_backward_matches_finite_differences_with_clamping():
+    side, rounds, B = 3, 5, 3
+    eu, ev = W.grid_edges(side)
+    p = W.beta22(7, B * eu.size).reshape(B, -1)
+    g = W.normal(8, B * 9).astype(np.float32).reshape(B, 9)
+    hist = oracle.reach_fwd(9, eu, ev, 0, rounds, p)
+    assert (hist[-1] == 1.0).sum() > B          # some nodes besides the source saturate
+    gp = oracle.reach_bwd(9, eu, ev, rounds, p, hist, g)
+    h = 1e-7
+    for s in range(B):
+        for e in range(eu.size):
+            d = np.zeros(eu.size); d[e] = h
+            p64 = p[s].astype(np.float64)
+            fp = (g[s].astype(np.float64) * f64_reach(9, eu, ev, 0, rounds, p64 + d)).sum()
+            fm = (g[s].astype(np.float64) * f64_reach(9, eu, ev, 0, rounds, p64 - d)).sum()
+            fd = (fp - fm) / (2 * h)
+            assert abs(fd - gp[s, e]) < 2e-5 + 1e-5 * abs(fd), (s, e, fd, gp[s, e])
+
+
+def test_backward_small_p_matches_matrix_calculus():
+    """Without clamping (source excluded) the result is linear in each single edge to first order:
+    check against finite differences of the float64 recurrence on a 4x4 grid."""
+    side, rounds, B = 4, 6, 2
+    eu, ev = W.grid_edges(side)
+    p = (W.uniform01(4, B * eu.size) * 0.05).astype(np.float32).reshape(B, -1)
+    g = W.normal(5, B * 16).astype(np.float32).reshape(B, 16)
+    hist = oracle.reach_fwd(16, eu, ev, 0, rounds, p)
+    gp = oracle.reach_bwd(16, eu, ev, rounds, p, hist, g)
+    h = 1e-6
+    for s in range(B):
+        for e in range(0, eu.size, 3):
+            d = np.zeros(eu.size); d[e] = h
+            p64 = p[s].astype(np.float64)
+            fd = ((g[s] * f64_reach(16, eu, ev, 0, rounds, p64 + d)).sum()
+                  - (g[s] * f64_reach(16, eu, ev, 0, rounds, p64 - d)).sum()) / (2 * h)
+            assert abs(fd - gp[s, e]) < 1e-6 + 1e-5 * abs(fd)
+
+
+def test_round_equals_apply_with_stay_symbol():
+    """One round is Apply over (node, edge-or-stay) tuples with a single disjunction per node:
+    union(paths, apply_if(paths, edges)) with the conjunction identity on the 'stay' symbol.
+    Values, the float decision quantity and gradients of the two formulations agree."""
+    side, B = 5, 4
+    w = W.config5(batch=B, side=side, rounds=3, seed=3)
+    n, E = side * side, w["edge_u"].size
+    tri = (w["tri_i"], w["tri_j"], w["tri_o"])
+    pe = np.concatenate([w["p"], np.ones((B, 1), np.float32)], axis=1)
+    hist = oracle.reach_fwd(n, w["edge_u"], w["edge_v"], 0, 3, w["p"])
+    r = hist[0]
+    outs = []
+    for t in range(3):
+        syms, r, pre32, _ = oracle.damp_apply2_fwd(tri, n, E + 1, r, pe, want_pre=True)
+        assert list(syms) == list(range(n))
+        np.testing.assert_array_equal(r, hist[t + 1])
+        outs.append(r)
+    g = w["g"]
+    gp = oracle.reach_bwd(n, w["edge_u"], w["edge_v"], 3, w["p"], hist, g)
+    acc = np.zeros((B, E), np.float64)
+    gr = g
+    for t in range(2, -1, -1):
+        gr, gb = oracle.damp_apply2_bwd(tri, n, E + 1, hist[t], pe, gr)
+        acc += gb[:, :E]
+    np.testing.assert_allclose(acc, gp, rtol=1e-5, atol=1e-7)
