@@ -1,0 +1,162 @@
+/*
+ * dolphin_hip.h -- C ABI of the MI355X (gfx950) hot path of the Dolphin
+ * neurosymbolic framework (arXiv 2410.03348): batched Distribution operators
+ * evaluated under a provenance.
+ *
+ * Vocabulary (Sec. 3.1): a Distribution maps a batch-invariant list of symbols
+ * to batched tags.  Symbols live on the host as ascending int32 ids; tags live
+ * on the device.  Under DAMP (Sec. 3.2, Table 1) a tag is one probability per
+ * (sample, symbol).  Under DTKP-AM (Sec. 3.2, App. A) a tag is up to k proofs;
+ * here a proof is a 64-bit set of input facts plus its probability, instead of
+ * the paper's (k x |I|) tensor of +-inf-padded probabilities.
+ *
+ * General rules
+ *   - "host" pointers are ordinary CPU memory, read during the call only
+ *     (unless stated otherwise).  "device" pointers are HIP device memory on
+ *     the current device, owned by the caller; the library never frees or
+ *     reallocates them.
+ *   - Every operator call is asynchronous on `hip_stream` (a hipStream_t cast
+ *     to void*, NULL = the default stream), never synchronises the device and
+ *     performs no allocation once its symbol-side plan exists (the first call
+ *     with a new fn_table / predicate / symbol-list pair builds and uploads a
+ *     small plan synchronously; later calls reuse it).
+ *   - Errors are reported as a non-zero dol_status; dol_last_error() gives a
+ *     thread-local message.  Argument and shape errors are detected before any
+ *     launch and leave the outputs untouched.  Nothing throws or aborts.
+ *   - batch == 0 or an empty symbol list is legal and does nothing.
+ *   - Tag tensors are row-major [batch, ld] float with ld >= n_sym (elements).
+ *   - DAMP tags must lie in [0, 1].
+ */
+#ifndef DOLPHIN_HIP_H
+#define DOLPHIN_HIP_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define DOL_MAX_K 8            /* DTKP: most proofs kept per tag */
+#define DOL_MAX_FACTS 63       /* DTKP: most input facts (bit 0..62); the all-ones mask marks an absent proof */
+#define DOL_MAX_SYMBOLS 65535  /* most symbols per Distribution / operand of a function table */
+#define DOL_ABSENT_PROOF UINT64_MAX
+
+typedef enum {
+    DOL_OK = 0,
+    DOL_EINVAL = 1,        /* NULL where data is needed, bad enum, unsorted symbol ids, ... */
+    DOL_ESHAPE = 2,        /* operand sizes do not fit each other or the table */
+    DOL_ENOMEM = 3,        /* host or device allocation of a plan failed */
+    DOL_EHIP = 4,          /* a HIP runtime call failed; message holds hipGetErrorString */
+    DOL_EUNSUPPORTED = 5   /* valid request the library does not implement */
+} dol_status;
+
+typedef enum { DOL_DAMP = 0, DOL_DTKP = 1 } dol_prov_kind;
+
+/* Provenance (Sec. 3.2): which (tag space, conjunction, disjunction) the operators use.
+ * DAMP: conjunction t*t', disjunction min(1, t+t').  Only `kind` is read.
+ * DTKP: conjunction = top-k over all pairs of proofs of the union of their fact sets,
+ *       disjunction = top-k of the concatenation (Table 1); repeated proofs count once;
+ *       order: higher probability first, ties by smaller mask.  A proof holding two
+ *       facts of one exclusion group is dropped.  A proof's probability is the float
+ *       product of fact_prob over its facts in ascending fact index, starting from 1. */
+typedef struct {
+    int32_t kind;                /* dol_prov_kind */
+    int32_t k;                   /* DTKP: 1..DOL_MAX_K */
+    int32_t n_facts;             /* DTKP: 0..DOL_MAX_FACTS */
+    const int32_t *fact_group;   /* DTKP, host [n_facts]: exclusion group of each fact (>=0), or NULL = none */
+    const float *fact_prob;      /* DTKP, device [batch, n_facts] row-major: probability of each input fact */
+} dol_prov;
+
+/* A Distribution (Sec. 3.1.1). */
+typedef struct {
+    int32_t batch;               /* samples */
+    int32_t n_sym;               /* symbols, 0..DOL_MAX_SYMBOLS */
+    int64_t ld;                  /* elements between consecutive rows of prob, >= n_sym */
+    const int32_t *sym_ids;      /* host [n_sym], strictly ascending */
+    float *prob;                 /* device [batch, ld]: DAMP tag; DTKP: the tag's probability (GetProbs) */
+    uint64_t *proof_mask;        /* DTKP, device [batch, n_sym, k]: kept proofs by rank, absent = DOL_ABSENT_PROOF */
+    float *proof_prob;           /* DTKP, device [batch, n_sym, k]: their probabilities, absent = 0 */
+} dol_dist;
+
+/* Symbol side of Apply / ApplyIf with K=2 (Sec. 3.1.2, Eq. 1-2): the user function evaluated
+ * once for the whole batch over operand positions (i, j), 0 <= i < na, 0 <= j < nb.
+ * The handle owns host and device copies of its index structures. */
+typedef struct dol_fn_table dol_fn_table;
+
+/* out_id: host [na*nb] row-major, the produced symbol id (>= 0) or -1 where the condition rejects (i, j). */
+dol_status dol_fn_table_create_dense(int32_t na, int32_t nb, const int32_t *out_id, dol_fn_table **table);
+/* The n admitted tuples (i[t], j[t]) -> out_id[t] >= 0, any order, each (i, j) at most once. */
+dol_status dol_fn_table_create_sparse(int32_t na, int32_t nb, int64_t n, const int32_t *i, const int32_t *j,
+                                      const int32_t *out_id, dol_fn_table **table);
+/* Number of distinct produced symbols S, and their ids ascending (host [S], valid until destroy).
+ * Column c of the result of dol_apply2 is symbol out_syms[c]. */
+int32_t dol_fn_table_n_out(const dol_fn_table *table);
+const int32_t *dol_fn_table_out_syms(const dol_fn_table *table);
+/* Synchronises the device before releasing the device copies.  NULL is ignored. */
+void dol_fn_table_destroy(dol_fn_table *table);
+
+/* Apply, K=2 (Eq. 1-3): out(s) = disjunction over admitted (i, j) with f(i, j) = s of a(i) conjunction b(j).
+ * a->n_sym == na, b->n_sym == nb, out->n_sym == S, equal batch.  prov NULL = DAMP.
+ * DAMP: out->prob[s,c] = min(1, sum a.prob[s,i] * b.prob[s,j]); the sum runs over the tuples of column c
+ *       in ascending (i, j) with one fused multiply-add each (this fixes the clamp decision of backward).
+ * DTKP: reads a/b->proof_mask, writes out->proof_mask, out->proof_prob and out->prob (all three required). */
+dol_status dol_apply2(const dol_dist *a, const dol_dist *b, const dol_fn_table *f, const dol_prov *prov,
+                      dol_dist *out, void *hip_stream);
+
+/* Filter (Sec. 3.1.2): symbols whose pred_mask entry is 0 are removed, the rest keep tags and order.
+ * pred_mask: host [d->n_sym].  dol_filter_plan returns the kept count and (if out_syms != NULL,
+ * room for d->n_sym) the kept ids, so that the caller can allocate `out`. */
+dol_status dol_filter_plan(const dol_dist *d, const uint8_t *pred_mask, int32_t *n_out, int32_t *out_syms);
+dol_status dol_filter(const dol_dist *d, const uint8_t *pred_mask, const dol_prov *prov, dol_dist *out,
+                      void *hip_stream);
+
+/* Union (Sec. 3.1.2): symbols of either input (ascending merge of the id lists); a symbol of both gets the
+ * disjunction of its two tags (DAMP min(1, a+b); DTKP top-k of both proof lists), others are copied.
+ * dol_union_plan: merged count and ids (out_syms has room for a->n_sym + b->n_sym). */
+dol_status dol_union_plan(const dol_dist *a, const dol_dist *b, int32_t *n_out, int32_t *out_syms);
+dol_status dol_union(const dol_dist *a, const dol_dist *b, const dol_prov *prov, dol_dist *out, void *hip_stream);
+
+/* DTKP natural initialisation (App. A.1): symbol i of `d` gets the single proof {fact_of_sym[i]}.
+ * fact_of_sym: host [d->n_sym].  Writes proof_mask, proof_prob and prob. */
+dol_status dol_dtkp_init(dol_dist *d, const int32_t *fact_of_sym, const dol_prov *prov, void *hip_stream);
+
+/* One recorded forward operator, for the backward pass. */
+typedef enum { DOL_OP_APPLY2 = 0, DOL_OP_FILTER = 1, DOL_OP_UNION = 2 } dol_op_kind;
+typedef struct {
+    int32_t op;                  /* dol_op_kind */
+    const dol_dist *a;           /* first (or only) input, as passed to the forward call, tags unchanged since */
+    const dol_dist *b;           /* second input (apply2, union) or NULL */
+    const dol_dist *out;         /* the forward result */
+    const dol_fn_table *f;       /* apply2 */
+    const uint8_t *pred_mask;    /* filter, host */
+    const dol_prov *prov;        /* NULL = DAMP */
+    int32_t accumulate;          /* bit 0: add into grad_a instead of overwriting it; bit 1: same for grad_b */
+} dol_op_record;
+
+/* Vector-Jacobian product of one DAMP operator (the paper relies on autograd, Sec. 3.1.1; the clamp passes
+ * gradient 1 inside and on its bounds, App. A.2).  grad_out: device [batch, out->ld].
+ * grad_a: device [batch, a->ld], grad_b: device [batch, b->ld]; the first n_sym entries of each row are
+ * OVERWRITTEN, or added to where rec->accumulate says so (a Distribution used by several operators sums the
+ * gradients of its uses); either may be NULL to skip it.
+ *   apply2: gh = grad_out * [pre <= 1];  grad_a[i] = sum_j gh[col(i,j)] * b[j];  grad_b[j] = sum_i gh[col(i,j)] * a[i]
+ *   filter: grad_a[i] = grad_out[position of i] for kept symbols, else 0
+ *   union:  common symbols pass grad_out * [a + b <= 1] to both sides, one-sided symbols pass grad_out.
+ * DTKP records return DOL_EUNSUPPORTED. */
+dol_status dol_backward(const dol_op_record *rec, const float *grad_out, float *grad_a, float *grad_b,
+                        void *hip_stream);
+
+/* Harness helper for loss = -log p[target] (Sec. 3.3 leaves the loss to the user): for every sample s,
+ * grad[s, c] = -1 / max(d->prob[s, c], FLT_MIN) at c = target_col[s] and 0 elsewhere (all n_sym columns written).
+ * target_col: device [batch] int32 column indices in 0..n_sym-1 (rows with an index outside get all zeros).
+ * grad: device [batch, d->ld]. */
+dol_status dol_nll_grad(const dol_dist *d, const int32_t *target_col, float *grad, void *hip_stream);
+
+/* Message of the calling thread's most recent failing call ("" if none). */
+const char *dol_last_error(void);
+/* Library version, e.g. "0.1.0". */
+const char *dol_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DOLPHIN_HIP_H */

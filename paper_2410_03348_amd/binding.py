@@ -1,0 +1,267 @@
+"""ctypes binding of libdolphin_hip.so: argument marshalling only.
+
+Every function here has the name of the C entry point it calls (minus the
+``dol_`` prefix where a class wraps a handle).  Device memory and the stream
+come from PyTorch-ROCm; all arithmetic runs in the library's HIP kernels.
+There is no fallback: if the shared library is missing, import fails.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libdolphin_hip.so")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        "libdolphin_hip.so is not built (%s). Run `python -c 'import __graft_entry__ as g; g.build()'` "
+        "or `python paper_2410_03348_amd/build.py`; there is no CPU fallback." % LIB_PATH)
+
+_lib = C.CDLL(LIB_PATH)
+
+DAMP, DTKP = 0, 1
+OP_APPLY2, OP_FILTER, OP_UNION = 0, 1, 2
+MAX_K, MAX_FACTS, MAX_SYMBOLS = 8, 63, 65535
+ABSENT_PROOF = 0xFFFFFFFFFFFFFFFF
+STATUS_NAMES = {0: "DOL_OK", 1: "DOL_EINVAL", 2: "DOL_ESHAPE", 3: "DOL_ENOMEM", 4: "DOL_EHIP", 5: "DOL_EUNSUPPORTED"}
+
+
+class DolError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__("%s: %s" % (STATUS_NAMES.get(status, str(status)), message))
+        self.status = status
+
+
+class _Prov(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("k", C.c_int32), ("n_facts", C.c_int32),
+                ("fact_group", C.POINTER(C.c_int32)), ("fact_prob", C.c_void_p)]
+
+
+class _Dist(C.Structure):
+    _fields_ = [("batch", C.c_int32), ("n_sym", C.c_int32), ("ld", C.c_int64),
+                ("sym_ids", C.POINTER(C.c_int32)), ("prob", C.c_void_p),
+                ("proof_mask", C.c_void_p), ("proof_prob", C.c_void_p)]
+
+
+class _OpRecord(C.Structure):
+    _fields_ = [("op", C.c_int32), ("a", C.POINTER(_Dist)), ("b", C.POINTER(_Dist)), ("out", C.POINTER(_Dist)),
+                ("f", C.c_void_p), ("pred_mask", C.POINTER(C.c_uint8)), ("prov", C.POINTER(_Prov)),
+                ("accumulate", C.c_int32)]
+
+
+_i32p = C.POINTER(C.c_int32)
+_u8p = C.POINTER(C.c_uint8)
+_lib.dol_fn_table_create_dense.argtypes = [C.c_int32, C.c_int32, _i32p, C.POINTER(C.c_void_p)]
+_lib.dol_fn_table_create_sparse.argtypes = [C.c_int32, C.c_int32, C.c_int64, _i32p, _i32p, _i32p, C.POINTER(C.c_void_p)]
+_lib.dol_fn_table_n_out.argtypes = [C.c_void_p]
+_lib.dol_fn_table_n_out.restype = C.c_int32
+_lib.dol_fn_table_out_syms.argtypes = [C.c_void_p]
+_lib.dol_fn_table_out_syms.restype = _i32p
+_lib.dol_fn_table_destroy.argtypes = [C.c_void_p]
+_lib.dol_fn_table_destroy.restype = None
+_lib.dol_apply2.argtypes = [C.POINTER(_Dist), C.POINTER(_Dist), C.c_void_p, C.POINTER(_Prov), C.POINTER(_Dist), C.c_void_p]
+_lib.dol_filter_plan.argtypes = [C.POINTER(_Dist), _u8p, _i32p, _i32p]
+_lib.dol_filter.argtypes = [C.POINTER(_Dist), _u8p, C.POINTER(_Prov), C.POINTER(_Dist), C.c_void_p]
+_lib.dol_union_plan.argtypes = [C.POINTER(_Dist), C.POINTER(_Dist), _i32p, _i32p]
+_lib.dol_union.argtypes = [C.POINTER(_Dist), C.POINTER(_Dist), C.POINTER(_Prov), C.POINTER(_Dist), C.c_void_p]
+_lib.dol_dtkp_init.argtypes = [C.POINTER(_Dist), _i32p, C.POINTER(_Prov), C.c_void_p]
+_lib.dol_backward.argtypes = [C.POINTER(_OpRecord), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+_lib.dol_nll_grad.argtypes = [C.POINTER(_Dist), C.c_void_p, C.c_void_p, C.c_void_p]
+_lib.dol_last_error.restype = C.c_char_p
+_lib.dol_version.restype = C.c_char_p
+
+
+def last_error() -> str:
+    return _lib.dol_last_error().decode()
+
+
+def version() -> str:
+    return _lib.dol_version().decode()
+
+
+def _check(status: int):
+    if status != 0:
+        raise DolError(status, last_error())
+
+
+def _np_i32(x) -> np.ndarray:
+    return np.ascontiguousarray(x, dtype=np.int32)
+
+
+def _ptr(a: Optional[np.ndarray], ct):
+    return None if a is None else a.ctypes.data_as(C.POINTER(ct))
+
+
+def _stream(stream) -> C.c_void_p:
+    """A torch stream, a raw handle, or None = torch's current stream."""
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    if isinstance(stream, torch.cuda.Stream):
+        return C.c_void_p(stream.cuda_stream)
+    return C.c_void_p(int(stream))
+
+
+class Prov:
+    """dol_prov.  fact_prob: float32 device tensor [batch, n_facts]; fact_group: host ints or None."""
+
+    def __init__(self, kind: int = DAMP, k: int = 0, fact_prob: Optional[torch.Tensor] = None, fact_group=None):
+        self.kind, self.k = kind, k
+        self.fact_prob = fact_prob
+        self._grp = None if fact_group is None else _np_i32(fact_group)
+        n_facts = 0
+        if fact_prob is not None:
+            assert fact_prob.dtype == torch.float32 and fact_prob.is_contiguous() and fact_prob.dim() == 2
+            n_facts = fact_prob.shape[1]
+        if self._grp is not None:
+            assert self._grp.size == n_facts
+        self.c = _Prov(kind, k, n_facts, _ptr(self._grp, C.c_int32),
+                       C.c_void_p(fact_prob.data_ptr()) if fact_prob is not None else None)
+
+    def ref(self):
+        return C.byref(self.c)
+
+
+class Dist:
+    """dol_dist over caller-owned torch tensors.  prob: float32 [batch, ld>=n_sym] (row stride = ld)."""
+
+    def __init__(self, sym_ids, prob: Optional[torch.Tensor], proof_mask: Optional[torch.Tensor] = None,
+                 proof_prob: Optional[torch.Tensor] = None, batch: Optional[int] = None):
+        self.sym_ids = _np_i32(sym_ids)
+        n = self.sym_ids.size
+        self.prob, self.proof_mask, self.proof_prob = prob, proof_mask, proof_prob
+        ld = n
+        if prob is not None:
+            assert prob.dtype == torch.float32 and prob.dim() == 2 and (prob.shape[1] == 0 or prob.stride(1) == 1)
+            assert prob.shape[1] == n
+            batch = prob.shape[0]
+            ld = max(int(prob.stride(0)), n)
+        for t, dt in ((proof_mask, (torch.int64, torch.uint64)), (proof_prob, (torch.float32,))):
+            if t is not None:
+                assert t.dtype in dt and t.is_contiguous() and t.dim() == 3 and t.shape[1] == n
+                batch = t.shape[0] if batch is None else batch
+        assert batch is not None
+        self.batch, self.n_sym, self.ld = batch, n, ld
+        self.c = _Dist(batch, n, ld, _ptr(self.sym_ids, C.c_int32),
+                       C.c_void_p(prob.data_ptr()) if prob is not None else None,
+                       C.c_void_p(proof_mask.data_ptr()) if proof_mask is not None else None,
+                       C.c_void_p(proof_prob.data_ptr()) if proof_prob is not None else None)
+
+    def ref(self):
+        return C.byref(self.c)
+
+    @staticmethod
+    def empty(sym_ids, batch: int, device="cuda", k: int = 0, ld: Optional[int] = None) -> "Dist":
+        """Allocate uninitialised tag tensors (torch is the allocator)."""
+        n = len(sym_ids)
+        ld = n if ld is None else ld
+        prob = torch.empty((batch, ld), dtype=torch.float32, device=device)[:, :n] if ld != n else \
+            torch.empty((batch, n), dtype=torch.float32, device=device)
+        pm = pp = None
+        if k > 0:
+            pm = torch.empty((batch, n, k), dtype=torch.int64, device=device)
+            pp = torch.empty((batch, n, k), dtype=torch.float32, device=device)
+        return Dist(sym_ids, prob, pm, pp, batch=batch)
+
+
+class FnTable:
+    """dol_fn_table handle."""
+
+    def __init__(self, handle: C.c_void_p, na: int, nb: int):
+        self._h, self.na, self.nb = handle, na, nb
+        self.n_out = int(_lib.dol_fn_table_n_out(handle))
+        p = _lib.dol_fn_table_out_syms(handle)
+        self.out_syms = np.ctypeslib.as_array(p, shape=(self.n_out,)).copy() if self.n_out else np.empty(0, np.int32)
+
+    @staticmethod
+    def create_dense(out_id) -> "FnTable":
+        t = _np_i32(out_id)
+        assert t.ndim == 2
+        h = C.c_void_p()
+        _check(_lib.dol_fn_table_create_dense(t.shape[0], t.shape[1], _ptr(t, C.c_int32), C.byref(h)))
+        return FnTable(h, t.shape[0], t.shape[1])
+
+    @staticmethod
+    def create_sparse(na: int, nb: int, i, j, out_id) -> "FnTable":
+        i, j, o = _np_i32(i), _np_i32(j), _np_i32(out_id)
+        assert i.shape == j.shape == o.shape and i.ndim == 1
+        h = C.c_void_p()
+        _check(_lib.dol_fn_table_create_sparse(na, nb, i.size, _ptr(i, C.c_int32), _ptr(j, C.c_int32),
+                                               _ptr(o, C.c_int32), C.byref(h)))
+        return FnTable(h, na, nb)
+
+    def destroy(self):
+        if self._h is not None:
+            _lib.dol_fn_table_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+def apply2(a: Dist, b: Dist, f: FnTable, prov: Optional[Prov], out: Dist, stream=None):
+    _check(_lib.dol_apply2(a.ref(), b.ref(), f._h, prov.ref() if prov else None, out.ref(), _stream(stream)))
+
+
+def filter_plan(d: Dist, pred_mask):
+    pm = np.ascontiguousarray(pred_mask, dtype=np.uint8)
+    n = C.c_int32()
+    syms = np.empty(max(d.n_sym, 1), np.int32)
+    _check(_lib.dol_filter_plan(d.ref(), _ptr(pm, C.c_uint8), C.byref(n), _ptr(syms, C.c_int32)))
+    return syms[:n.value].copy()
+
+
+def filter(d: Dist, pred_mask, prov: Optional[Prov], out: Dist, stream=None):  # noqa: A001 (the operator's name)
+    pm = np.ascontiguousarray(pred_mask, dtype=np.uint8)
+    _check(_lib.dol_filter(d.ref(), _ptr(pm, C.c_uint8), prov.ref() if prov else None, out.ref(), _stream(stream)))
+
+
+def union_plan(a: Dist, b: Dist):
+    n = C.c_int32()
+    syms = np.empty(max(a.n_sym + b.n_sym, 1), np.int32)
+    _check(_lib.dol_union_plan(a.ref(), b.ref(), C.byref(n), _ptr(syms, C.c_int32)))
+    return syms[:n.value].copy()
+
+
+def union(a: Dist, b: Dist, prov: Optional[Prov], out: Dist, stream=None):
+    _check(_lib.dol_union(a.ref(), b.ref(), prov.ref() if prov else None, out.ref(), _stream(stream)))
+
+
+def dtkp_init(d: Dist, fact_of_sym, prov: Prov, stream=None):
+    fos = _np_i32(fact_of_sym)
+    _check(_lib.dol_dtkp_init(d.ref(), _ptr(fos, C.c_int32), prov.ref(), _stream(stream)))
+
+
+class OpRecord:
+    """dol_op_record; keeps its operands alive."""
+
+    def __init__(self, op: int, a: Dist, b: Optional[Dist], out: Dist, f: Optional[FnTable] = None, pred_mask=None,
+                 prov: Optional[Prov] = None, accumulate: int = 0):
+        self.a, self.b, self.out, self.f, self.prov = a, b, out, f, prov
+        self.pred = None if pred_mask is None else np.ascontiguousarray(pred_mask, dtype=np.uint8)
+        self.c = _OpRecord(op, C.pointer(a.c), C.pointer(b.c) if b is not None else None, C.pointer(out.c),
+                           f._h if f is not None else None, _ptr(self.pred, C.c_uint8),
+                           C.pointer(prov.c) if prov is not None else None, accumulate)
+
+
+def _dptr(t: Optional[torch.Tensor]):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def backward(rec: OpRecord, grad_out: torch.Tensor, grad_a: Optional[torch.Tensor], grad_b: Optional[torch.Tensor],
+             stream=None):
+    """grad_out rows have stride rec.out.ld, grad_a rows rec.a.ld, grad_b rows rec.b.ld."""
+    _check(_lib.dol_backward(C.byref(rec.c), _dptr(grad_out), _dptr(grad_a), _dptr(grad_b), _stream(stream)))
+
+
+def nll_grad(d: Dist, target_col: torch.Tensor, grad: torch.Tensor, stream=None):
+    """target_col: int32 device tensor [batch]; grad rows have stride d.ld."""
+    assert target_col.dtype == torch.int32 and target_col.is_contiguous()
+    _check(_lib.dol_nll_grad(d.ref(), _dptr(target_col), _dptr(grad), _stream(stream)))

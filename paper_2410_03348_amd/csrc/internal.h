@@ -1,0 +1,147 @@
+// Internal declarations shared by the translation units of libdolphin_hip.so.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdint>
+#include <cstdio>
+#include <string>
+#include <vector>
+
+#include "dolphin_hip.h"
+
+namespace dol {
+
+// ---------------------------------------------------------------- errors
+
+void set_error(const char *fmt, ...) __attribute__((format(printf, 1, 2)));
+dol_status fail(dol_status st, const char *fmt, ...) __attribute__((format(printf, 2, 3)));
+dol_status hip_fail(hipError_t e, const char *what);
+
+#define DOL_HIP(call)                                        \
+    do {                                                     \
+        hipError_t e_ = (call);                              \
+        if (e_ != hipSuccess) return ::dol::hip_fail(e_, #call); \
+    } while (0)
+
+// ---------------------------------------------------------------- device arrays owned by plans
+
+template <typename T>
+struct DevArray {
+    T *ptr = nullptr;
+    size_t n = 0;
+    DevArray() = default;
+    DevArray(const DevArray &) = delete;
+    DevArray &operator=(const DevArray &) = delete;
+    ~DevArray() { release(); }
+    void release()
+    {
+        if (ptr) (void)hipFree(ptr);   // hipFree waits for work that may still read the array
+        ptr = nullptr;
+        n = 0;
+    }
+    // Synchronous upload; an empty vector leaves ptr == nullptr.
+    hipError_t upload(const std::vector<T> &h)
+    {
+        release();
+        if (h.empty()) return hipSuccess;
+        hipError_t e = hipMalloc(reinterpret_cast<void **>(&ptr), h.size() * sizeof(T));
+        if (e != hipSuccess) { ptr = nullptr; return e; }
+        n = h.size();
+        e = hipMemcpy(ptr, h.data(), h.size() * sizeof(T), hipMemcpyHostToDevice);
+        if (e != hipSuccess) release();
+        return e;
+    }
+};
+
+// ---------------------------------------------------------------- symbol-side plans
+
+// A tuple of the function table packed for the kernels: low 16 bits = first index, high 16 = second.
+static inline uint32_t pack16(uint32_t lo, uint32_t hi) { return lo | (hi << 16); }
+
+}  // namespace dol
+
+// Eq. 1-2: admitted tuples grouped by the output column they land in (the "shuffle" stage),
+// plus the two transposed groupings the vector-Jacobian products walk.
+struct dol_fn_table {
+    int32_t na = 0, nb = 0, n_out = 0;
+    int64_t n_tuples = 0;
+    int32_t max_col_len = 0;             // most tuples landing in one column
+    bool sum_like = false;               // every column's tuples have i ascending by 1 and j descending by 1
+    std::vector<int32_t> out_syms;       // [n_out] ascending ids
+    // host copies (kept for the chain planner)
+    std::vector<uint32_t> h_col_ptr, h_col_ij;
+    // forward: column c owns entries col_ptr[c] .. col_ptr[c+1] of col_ij = pack16(i, j), ascending (i, j)
+    dol::DevArray<uint32_t> col_ptr, col_ij;
+    // backward w.r.t. a: row i owns rowa_ptr[i] .. rowa_ptr[i+1] of rowa_jc = pack16(j, column), ascending j
+    dol::DevArray<uint32_t> rowa_ptr, rowa_jc;
+    // backward w.r.t. b: row j owns rowb_ptr[j] .. rowb_ptr[j+1] of rowb_ic = pack16(i, column), ascending i
+    dol::DevArray<uint32_t> rowb_ptr, rowb_ic;
+    int device = 0;
+};
+
+namespace dol {
+
+struct FilterPlan {
+    int32_t n_in = 0, n_out = 0;
+    std::vector<int32_t> keep_idx;        // [n_out] position in the input
+    DevArray<int32_t> d_keep_idx;         // same, device
+    DevArray<int32_t> d_pos;              // [n_in] position in the output or -1
+};
+
+struct UnionPlan {
+    int32_t na = 0, nb = 0, n_out = 0;
+    std::vector<int32_t> out_syms;
+    DevArray<int32_t> d_ia, d_ib;         // [n_out] position in a / b or -1
+    DevArray<int32_t> d_ca, d_cb;         // [na] / [nb] output column of each input position
+};
+
+// Content-addressed caches: the same predicate / symbol lists give the same plan object.
+// Returned pointers stay valid until the library is unloaded.
+dol_status get_filter_plan(int32_t n, const uint8_t *pred, const FilterPlan **plan);
+dol_status get_union_plan(int32_t na, const int32_t *sa, int32_t nb, const int32_t *sb, const UnionPlan **plan);
+
+// Masks of the exclusion groups that hold at least two facts (kernel argument, by value).
+struct GroupMasks {
+    int32_t n;
+    uint64_t m[32];
+};
+dol_status make_group_masks(const dol_prov *prov, GroupMasks *gm);
+// Device copy of a small host int32 array, cached by content.
+dol_status get_i32_array(int32_t n, const int32_t *data, const int32_t **dptr);
+
+// ---------------------------------------------------------------- launchers (damp.hip / dtkp.hip)
+
+dol_status launch_damp_apply2_fwd(const dol_fn_table *f, int32_t batch, const float *a, int64_t lda, const float *b,
+                                  int64_t ldb, float *out, int64_t ldo, hipStream_t st);
+dol_status launch_damp_apply2_bwd(const dol_fn_table *f, int32_t batch, const float *a, int64_t lda, const float *b,
+                                  int64_t ldb, const float *out, int64_t ldo, const float *g, int64_t ldg, float *ga,
+                                  float *gb, int32_t accumulate, hipStream_t st);
+dol_status launch_nll_grad(int32_t batch, int32_t n, const float *p, int64_t ld, const int32_t *target, float *grad,
+                           hipStream_t st);
+dol_status launch_zero_rows(int32_t batch, int32_t n, float *x, int64_t ld, hipStream_t st);
+dol_status launch_damp_filter_fwd(const FilterPlan *p, int32_t batch, const float *in, int64_t ldi, float *out,
+                                  int64_t ldo, hipStream_t st);
+dol_status launch_damp_filter_bwd(const FilterPlan *p, int32_t batch, const float *g, int64_t ldg, float *gin,
+                                  int64_t ldgi, int32_t accumulate, hipStream_t st);
+dol_status launch_damp_union_fwd(const UnionPlan *p, int32_t batch, const float *a, int64_t lda, const float *b,
+                                 int64_t ldb, float *out, int64_t ldo, hipStream_t st);
+dol_status launch_damp_union_bwd(const UnionPlan *p, int32_t batch, const float *a, int64_t lda, const float *b,
+                                 int64_t ldb, const float *g, int64_t ldg, float *ga, float *gb, int32_t accumulate,
+                                 hipStream_t st);
+
+dol_status launch_dtkp_init(int32_t batch, int32_t n_sym, int32_t k, int32_t n_facts, const int32_t *d_fact_of_sym,
+                            const float *fact_prob, uint64_t *mask, float *pprob, float *prob, int64_t ld,
+                            hipStream_t st);
+dol_status launch_dtkp_apply2(const dol_fn_table *f, int32_t batch, int32_t k, int32_t n_facts, const GroupMasks &gm,
+                              const float *fact_prob, const uint64_t *am, const uint64_t *bm, uint64_t *om, float *op,
+                              float *oprob, int64_t ldo, hipStream_t st);
+dol_status launch_dtkp_union(const UnionPlan *p, int32_t batch, int32_t k, const uint64_t *am, const float *ap,
+                             const uint64_t *bm, const float *bp, uint64_t *om, float *op, float *oprob, int64_t ldo,
+                             hipStream_t st);
+dol_status launch_dtkp_filter(const FilterPlan *p, int32_t batch, int32_t k, const uint64_t *im, const float *ip,
+                              const float *iprob, int64_t ldi, uint64_t *om, float *op, float *oprob, int64_t ldo,
+                              hipStream_t st);
+
+}  // namespace dol

@@ -1,0 +1,375 @@
+// Symbol side of the operators (Sec. 3.1.2): everything that depends only on the symbols and the
+// user function, computed once on the host for the whole batch and uploaded as index arrays.
+#include "internal.h"
+
+#include <algorithm>
+#include <cstring>
+#include <memory>
+#include <mutex>
+#include <new>
+#include <unordered_map>
+
+namespace dol {
+
+// ---------------------------------------------------------------- errors
+
+static thread_local std::string g_last_error;
+
+void set_error(const char *fmt, ...)
+{
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    g_last_error = buf;
+}
+
+dol_status fail(dol_status st, const char *fmt, ...)
+{
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    g_last_error = buf;
+    return st;
+}
+
+dol_status hip_fail(hipError_t e, const char *what)
+{
+    set_error("%s: %s", what, hipGetErrorString(e));
+    return e == hipErrorOutOfMemory ? DOL_ENOMEM : DOL_EHIP;
+}
+
+// ---------------------------------------------------------------- function tables
+
+struct Tuple {
+    int32_t i, j, id;
+};
+
+static dol_status build_table(int32_t na, int32_t nb, std::vector<Tuple> &tup, dol_fn_table **out)
+{
+    // ascending (i, j); a function has one value per argument tuple
+    std::sort(tup.begin(), tup.end(), [](const Tuple &x, const Tuple &y) { return x.i != y.i ? x.i < y.i : x.j < y.j; });
+    for (size_t t = 1; t < tup.size(); ++t)
+        if (tup[t].i == tup[t - 1].i && tup[t].j == tup[t - 1].j)
+            return fail(DOL_EINVAL, "function table lists the tuple (%d, %d) twice", tup[t].i, tup[t].j);
+
+    std::unique_ptr<dol_fn_table> tb(new (std::nothrow) dol_fn_table);
+    if (!tb) return fail(DOL_ENOMEM, "out of host memory");
+    tb->na = na;
+    tb->nb = nb;
+    tb->n_tuples = static_cast<int64_t>(tup.size());
+
+    // Eq. 2: the output symbols are the distinct produced ids, ascending
+    tb->out_syms.reserve(tup.size());
+    for (const Tuple &t : tup) tb->out_syms.push_back(t.id);
+    std::sort(tb->out_syms.begin(), tb->out_syms.end());
+    tb->out_syms.erase(std::unique(tb->out_syms.begin(), tb->out_syms.end()), tb->out_syms.end());
+    if (tb->out_syms.size() > DOL_MAX_SYMBOLS)
+        return fail(DOL_EUNSUPPORTED, "function table produces %zu symbols, more than %d", tb->out_syms.size(),
+                    DOL_MAX_SYMBOLS);
+    const int32_t S = tb->n_out = static_cast<int32_t>(tb->out_syms.size());
+
+    std::vector<uint32_t> col(tup.size());
+    for (size_t t = 0; t < tup.size(); ++t)
+        col[t] = static_cast<uint32_t>(std::lower_bound(tb->out_syms.begin(), tb->out_syms.end(), tup[t].id) -
+                                       tb->out_syms.begin());
+
+    // counting sorts (stable, so each group keeps ascending (i, j))
+    std::vector<uint32_t> col_ptr(S + 1, 0), rowa_ptr(na + 1, 0), rowb_ptr(nb + 1, 0);
+    for (size_t t = 0; t < tup.size(); ++t) {
+        col_ptr[col[t] + 1]++;
+        rowa_ptr[tup[t].i + 1]++;
+        rowb_ptr[tup[t].j + 1]++;
+    }
+    for (int32_t c = 0; c < S; ++c) {
+        tb->max_col_len = std::max<int32_t>(tb->max_col_len, static_cast<int32_t>(col_ptr[c + 1]));
+        col_ptr[c + 1] += col_ptr[c];
+    }
+    for (int32_t i = 0; i < na; ++i) rowa_ptr[i + 1] += rowa_ptr[i];
+    for (int32_t j = 0; j < nb; ++j) rowb_ptr[j + 1] += rowb_ptr[j];
+    std::vector<uint32_t> col_ij(tup.size()), rowa_jc(tup.size()), rowb_ic(tup.size());
+    {
+        std::vector<uint32_t> fc(col_ptr.begin(), col_ptr.end() - 1), fa(rowa_ptr.begin(), rowa_ptr.end() - 1),
+            fb(rowb_ptr.begin(), rowb_ptr.end() - 1);
+        for (size_t t = 0; t < tup.size(); ++t) {
+            const uint32_t i = static_cast<uint32_t>(tup[t].i), j = static_cast<uint32_t>(tup[t].j);
+            col_ij[fc[col[t]]++] = pack16(i, j);
+            rowa_jc[fa[i]++] = pack16(j, col[t]);
+            rowb_ic[fb[j]++] = pack16(i, col[t]);
+        }
+    }
+    // sum-like: inside every column i rises by one and j falls by one (f(i,j) depends on i+j only and is injective in it)
+    tb->sum_like = !tup.empty();
+    for (int32_t c = 0; c < S && tb->sum_like; ++c)
+        for (uint32_t q = col_ptr[c] + 1; q < col_ptr[c + 1]; ++q) {
+            const uint32_t p0 = col_ij[q - 1], p1 = col_ij[q];
+            if ((p1 & 0xffff) != (p0 & 0xffff) + 1 || (p1 >> 16) + 1 != (p0 >> 16)) { tb->sum_like = false; break; }
+        }
+
+    if (hipGetDevice(&tb->device) != hipSuccess) tb->device = 0;
+    hipError_t e;
+    if ((e = tb->col_ptr.upload(col_ptr)) != hipSuccess || (e = tb->col_ij.upload(col_ij)) != hipSuccess ||
+        (e = tb->rowa_ptr.upload(rowa_ptr)) != hipSuccess || (e = tb->rowa_jc.upload(rowa_jc)) != hipSuccess ||
+        (e = tb->rowb_ptr.upload(rowb_ptr)) != hipSuccess || (e = tb->rowb_ic.upload(rowb_ic)) != hipSuccess)
+        return hip_fail(e, "uploading the function table");
+    tb->h_col_ptr.swap(col_ptr);
+    tb->h_col_ij.swap(col_ij);
+    *out = tb.release();
+    return DOL_OK;
+}
+
+static dol_status check_table_dims(int32_t na, int32_t nb, dol_fn_table **table)
+{
+    if (!table) return fail(DOL_EINVAL, "table output pointer is NULL");
+    *table = nullptr;
+    if (na < 0 || nb < 0 || na > DOL_MAX_SYMBOLS || nb > DOL_MAX_SYMBOLS)
+        return fail(DOL_ESHAPE, "operand sizes %d x %d outside 0..%d", na, nb, DOL_MAX_SYMBOLS);
+    return DOL_OK;
+}
+
+// ---------------------------------------------------------------- content-addressed plan caches
+
+static uint64_t fnv1a(const void *data, size_t n, uint64_t h = 1469598103934665603ull)
+{
+    const unsigned char *p = static_cast<const unsigned char *>(data);
+    for (size_t x = 0; x < n; ++x) h = (h ^ p[x]) * 1099511628211ull;
+    return h;
+}
+
+template <typename Plan>
+struct Cache {
+    struct Entry {
+        std::vector<unsigned char> key;
+        std::unique_ptr<Plan> plan;
+    };
+    std::mutex mu;
+    std::unordered_multimap<uint64_t, Entry> map;
+
+    const Plan *find(uint64_t h, const std::vector<unsigned char> &key)
+    {
+        auto range = map.equal_range(h);
+        for (auto it = range.first; it != range.second; ++it)
+            if (it->second.key == key) return it->second.plan.get();
+        return nullptr;
+    }
+    const Plan *insert(uint64_t h, std::vector<unsigned char> &&key, std::unique_ptr<Plan> &&plan)
+    {
+        auto it = map.emplace(h, Entry{std::move(key), std::move(plan)});
+        return it->second.plan.get();
+    }
+};
+
+static std::vector<unsigned char> make_key(int device, std::initializer_list<std::pair<const void *, size_t>> parts)
+{
+    std::vector<unsigned char> key(sizeof(int));
+    std::memcpy(key.data(), &device, sizeof(int));
+    for (const auto &p : parts) {
+        const uint64_t n = p.second;
+        const unsigned char *nb = reinterpret_cast<const unsigned char *>(&n);
+        key.insert(key.end(), nb, nb + sizeof n);
+        const unsigned char *d = static_cast<const unsigned char *>(p.first);
+        if (n) key.insert(key.end(), d, d + n);
+    }
+    return key;
+}
+
+static Cache<FilterPlan> g_filter_cache;
+static Cache<UnionPlan> g_union_cache;
+
+dol_status get_filter_plan(int32_t n, const uint8_t *pred, const FilterPlan **plan)
+{
+    int device = 0;
+    (void)hipGetDevice(&device);
+    std::vector<uint8_t> norm(static_cast<size_t>(n));
+    for (int32_t i = 0; i < n; ++i) norm[i] = pred[i] ? 1 : 0;
+    std::vector<unsigned char> key = make_key(device, {{norm.data(), norm.size()}});
+    const uint64_t h = fnv1a(key.data(), key.size());
+    std::lock_guard<std::mutex> lock(g_filter_cache.mu);
+    if ((*plan = g_filter_cache.find(h, key)) != nullptr) return DOL_OK;
+
+    std::unique_ptr<FilterPlan> p(new (std::nothrow) FilterPlan);
+    if (!p) return fail(DOL_ENOMEM, "out of host memory");
+    p->n_in = n;
+    std::vector<int32_t> pos(static_cast<size_t>(n), -1);
+    for (int32_t i = 0; i < n; ++i)
+        if (norm[i]) {
+            pos[i] = static_cast<int32_t>(p->keep_idx.size());
+            p->keep_idx.push_back(i);
+        }
+    p->n_out = static_cast<int32_t>(p->keep_idx.size());
+    hipError_t e;
+    if ((e = p->d_keep_idx.upload(p->keep_idx)) != hipSuccess || (e = p->d_pos.upload(pos)) != hipSuccess)
+        return hip_fail(e, "uploading the filter plan");
+    *plan = g_filter_cache.insert(h, std::move(key), std::move(p));
+    return DOL_OK;
+}
+
+dol_status get_union_plan(int32_t na, const int32_t *sa, int32_t nb, const int32_t *sb, const UnionPlan **plan)
+{
+    int device = 0;
+    (void)hipGetDevice(&device);
+    std::vector<unsigned char> key =
+        make_key(device, {{sa, sizeof(int32_t) * static_cast<size_t>(na)}, {sb, sizeof(int32_t) * static_cast<size_t>(nb)}});
+    const uint64_t h = fnv1a(key.data(), key.size());
+    std::lock_guard<std::mutex> lock(g_union_cache.mu);
+    if ((*plan = g_union_cache.find(h, key)) != nullptr) return DOL_OK;
+
+    std::unique_ptr<UnionPlan> p(new (std::nothrow) UnionPlan);
+    if (!p) return fail(DOL_ENOMEM, "out of host memory");
+    p->na = na;
+    p->nb = nb;
+    std::vector<int32_t> ia, ib, ca(static_cast<size_t>(na)), cb(static_cast<size_t>(nb));
+    int32_t i = 0, j = 0;
+    while (i < na || j < nb) {            // ascending merge of two ascending id lists
+        const int32_t c = static_cast<int32_t>(ia.size());
+        if (j >= nb || (i < na && sa[i] < sb[j])) {
+            p->out_syms.push_back(sa[i]); ia.push_back(i); ib.push_back(-1); ca[i++] = c;
+        } else if (i >= na || sb[j] < sa[i]) {
+            p->out_syms.push_back(sb[j]); ia.push_back(-1); ib.push_back(j); cb[j++] = c;
+        } else {
+            p->out_syms.push_back(sa[i]); ia.push_back(i); ib.push_back(j); ca[i++] = c; cb[j++] = c;
+        }
+    }
+    p->n_out = static_cast<int32_t>(ia.size());
+    hipError_t e;
+    if ((e = p->d_ia.upload(ia)) != hipSuccess || (e = p->d_ib.upload(ib)) != hipSuccess ||
+        (e = p->d_ca.upload(ca)) != hipSuccess || (e = p->d_cb.upload(cb)) != hipSuccess)
+        return hip_fail(e, "uploading the union plan");
+    *plan = g_union_cache.insert(h, std::move(key), std::move(p));
+    return DOL_OK;
+}
+
+struct I32Array {
+    DevArray<int32_t> d;
+};
+static Cache<I32Array> g_i32_cache;
+
+// Device copy of a small host int32 array, cached by content.
+dol_status get_i32_array(int32_t n, const int32_t *data, const int32_t **dptr)
+{
+    int device = 0;
+    (void)hipGetDevice(&device);
+    std::vector<unsigned char> key = make_key(device, {{data, sizeof(int32_t) * static_cast<size_t>(n)}});
+    const uint64_t h = fnv1a(key.data(), key.size());
+    std::lock_guard<std::mutex> lock(g_i32_cache.mu);
+    const I32Array *hit = g_i32_cache.find(h, key);
+    if (!hit) {
+        std::unique_ptr<I32Array> p(new (std::nothrow) I32Array);
+        if (!p) return fail(DOL_ENOMEM, "out of host memory");
+        hipError_t e = p->d.upload(std::vector<int32_t>(data, data + n));
+        if (e != hipSuccess) return hip_fail(e, "uploading an index array");
+        hit = g_i32_cache.insert(h, std::move(key), std::move(p));
+    }
+    *dptr = hit->d.ptr;
+    return DOL_OK;
+}
+
+dol_status make_group_masks(const dol_prov *prov, GroupMasks *gm)
+{
+    gm->n = 0;
+    if (!prov->fact_group) return DOL_OK;
+    std::unordered_map<int32_t, uint64_t> by_group;
+    for (int32_t f = 0; f < prov->n_facts; ++f) {
+        if (prov->fact_group[f] < 0) return fail(DOL_EINVAL, "fact_group[%d] is negative", f);
+        by_group[prov->fact_group[f]] |= uint64_t(1) << f;
+    }
+    std::vector<uint64_t> masks;
+    for (const auto &kv : by_group)
+        if (__builtin_popcountll(kv.second) >= 2) masks.push_back(kv.second);
+    std::sort(masks.begin(), masks.end());
+    if (masks.size() > 32) return fail(DOL_EUNSUPPORTED, "more than 32 exclusion groups with two or more facts");
+    gm->n = static_cast<int32_t>(masks.size());
+    for (size_t x = 0; x < masks.size(); ++x) gm->m[x] = masks[x];
+    return DOL_OK;
+}
+
+}  // namespace dol
+
+// ---------------------------------------------------------------- C ABI: tables and plans
+
+extern "C" {
+
+dol_status dol_fn_table_create_dense(int32_t na, int32_t nb, const int32_t *out_id, dol_fn_table **table)
+{
+    if (dol_status st = dol::check_table_dims(na, nb, table)) return st;
+    if (!out_id && na > 0 && nb > 0) return dol::fail(DOL_EINVAL, "out_id is NULL");
+    std::vector<dol::Tuple> tup;
+    tup.reserve(static_cast<size_t>(na) * static_cast<size_t>(nb));
+    for (int32_t i = 0; i < na; ++i)
+        for (int32_t j = 0; j < nb; ++j) {
+            const int32_t id = out_id[static_cast<size_t>(i) * nb + j];
+            if (id < -1) return dol::fail(DOL_EINVAL, "out_id[%d,%d] = %d; ids are >= 0 or -1 for a rejected tuple", i, j, id);
+            if (id >= 0) tup.push_back({i, j, id});
+        }
+    return dol::build_table(na, nb, tup, table);
+}
+
+dol_status dol_fn_table_create_sparse(int32_t na, int32_t nb, int64_t n, const int32_t *i, const int32_t *j,
+                                      const int32_t *out_id, dol_fn_table **table)
+{
+    if (dol_status st = dol::check_table_dims(na, nb, table)) return st;
+    if (n < 0) return dol::fail(DOL_EINVAL, "negative tuple count");
+    if (n > 0 && (!i || !j || !out_id)) return dol::fail(DOL_EINVAL, "tuple arrays are NULL");
+    std::vector<dol::Tuple> tup;
+    tup.reserve(static_cast<size_t>(n));
+    for (int64_t t = 0; t < n; ++t) {
+        if (i[t] < 0 || i[t] >= na || j[t] < 0 || j[t] >= nb)
+            return dol::fail(DOL_ESHAPE, "tuple %lld = (%d, %d) outside %d x %d", static_cast<long long>(t), i[t], j[t], na, nb);
+        if (out_id[t] < 0) return dol::fail(DOL_EINVAL, "tuple %lld produces the negative id %d", static_cast<long long>(t), out_id[t]);
+        tup.push_back({i[t], j[t], out_id[t]});
+    }
+    return dol::build_table(na, nb, tup, table);
+}
+
+int32_t dol_fn_table_n_out(const dol_fn_table *table) { return table ? table->n_out : 0; }
+
+const int32_t *dol_fn_table_out_syms(const dol_fn_table *table) { return table ? table->out_syms.data() : nullptr; }
+
+void dol_fn_table_destroy(dol_fn_table *table) { delete table; }
+
+dol_status dol_filter_plan(const dol_dist *d, const uint8_t *pred_mask, int32_t *n_out, int32_t *out_syms)
+{
+    if (!d || !n_out) return dol::fail(DOL_EINVAL, "NULL argument");
+    if (d->n_sym < 0 || d->n_sym > DOL_MAX_SYMBOLS) return dol::fail(DOL_ESHAPE, "n_sym %d outside 0..%d", d->n_sym, DOL_MAX_SYMBOLS);
+    if (d->n_sym > 0 && (!pred_mask || (out_syms && !d->sym_ids))) return dol::fail(DOL_EINVAL, "pred_mask or sym_ids is NULL");
+    int32_t m = 0;
+    for (int32_t i = 0; i < d->n_sym; ++i)
+        if (pred_mask[i]) {
+            if (out_syms) out_syms[m] = d->sym_ids[i];
+            ++m;
+        }
+    *n_out = m;
+    return DOL_OK;
+}
+
+dol_status dol_union_plan(const dol_dist *a, const dol_dist *b, int32_t *n_out, int32_t *out_syms)
+{
+    if (!a || !b || !n_out) return dol::fail(DOL_EINVAL, "NULL argument");
+    if (a->n_sym < 0 || b->n_sym < 0 || a->n_sym > DOL_MAX_SYMBOLS || b->n_sym > DOL_MAX_SYMBOLS)
+        return dol::fail(DOL_ESHAPE, "n_sym outside 0..%d", DOL_MAX_SYMBOLS);
+    if ((a->n_sym > 0 && !a->sym_ids) || (b->n_sym > 0 && !b->sym_ids)) return dol::fail(DOL_EINVAL, "sym_ids is NULL");
+    for (int32_t i = 1; i < a->n_sym; ++i)
+        if (a->sym_ids[i - 1] >= a->sym_ids[i]) return dol::fail(DOL_EINVAL, "a.sym_ids not strictly ascending at %d", i);
+    for (int32_t j = 1; j < b->n_sym; ++j)
+        if (b->sym_ids[j - 1] >= b->sym_ids[j]) return dol::fail(DOL_EINVAL, "b.sym_ids not strictly ascending at %d", j);
+    int32_t i = 0, j = 0, m = 0;
+    while (i < a->n_sym || j < b->n_sym) {
+        int32_t id;
+        if (j >= b->n_sym || (i < a->n_sym && a->sym_ids[i] < b->sym_ids[j])) id = a->sym_ids[i++];
+        else if (i >= a->n_sym || b->sym_ids[j] < a->sym_ids[i]) id = b->sym_ids[j++];
+        else { id = a->sym_ids[i++]; ++j; }
+        if (out_syms) out_syms[m] = id;
+        ++m;
+    }
+    *n_out = m;
+    return DOL_OK;
+}
+
+const char *dol_last_error(void) { return dol::g_last_error.c_str(); }
+
+const char *dol_version(void) { return "0.1.0"; }
+
+}  // extern "C"

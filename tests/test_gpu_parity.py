@@ -1,0 +1,357 @@
+"""Parity of the HIP library against the CPU oracle, element by element, through the C ABI (needs an MI355X).
+
+Floating-point bar: |gpu - oracle| <= 1e-7 + 1e-5 * |oracle| (oracle accumulates in float64).
+Integer / index / proof-mask bar: bit-exact.
+"""
+import numpy as np
+import pytest
+
+import oracle
+import workloads as W
+from oracle import programs as OP
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def gp():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2410_03348_amd import programs
+    return programs
+
+
+@pytest.fixture(scope="module")
+def dol():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2410_03348_amd import binding
+    return binding
+
+
+def host(t):
+    torch.cuda.synchronize()
+    return t.detach().cpu().numpy()
+
+
+def assert_close(got, want, what=""):
+    got = np.asarray(got, np.float64)
+    want = np.asarray(want, np.float64)
+    assert got.shape == want.shape, (what, got.shape, want.shape)
+    err = np.abs(got - want)
+    tol = 1e-7 + 1e-5 * np.abs(want)
+    bad = err > tol
+    assert not bad.any(), "%s: %d of %d outside tolerance, worst excess %g at %s" % (
+        what, int(bad.sum()), bad.size, float((err - tol).max()), np.unravel_index(np.argmax(err - tol), err.shape))
+
+
+def dev(x):
+    return torch.from_numpy(np.ascontiguousarray(x)).cuda()
+
+
+# ---------------------------------------------------------------- config 1
+
+@pytest.mark.parametrize("batch", [64, 1, 257])
+def test_config1_sum2(gp, batch):
+    w = W.config1(batch=batch, seed=batch)
+    ref = OP.sum2_fwd(w)
+    prog = gp.Sum2Forward(w)
+    out = prog.forward()
+    np.testing.assert_array_equal(out.sym_ids, ref["syms"])
+    assert_close(host(out.prob), ref["out"], "sum2")
+
+
+# ---------------------------------------------------------------- config 2
+
+@pytest.mark.parametrize("batch,n", [(4096, 15), (300, 15), (37, 4), (1, 2)])
+def test_config2_sum_chain(gp, batch, n):
+    w = W.config2(batch=batch, n_digits=n, seed=n)
+    ref = OP.sum_chain_fwd_bwd(w)
+    prog = gp.SumChain(w)
+    prog.step()
+    np.testing.assert_array_equal(prog.accs[-1].sym_ids, ref["syms"])
+    for t in range(1, n):
+        assert_close(host(prog.accs[t].prob), ref["accs"][t], "chain stage %d" % t)
+    assert_close(host(prog.g_acc[-1]), ref["g_out"], "loss gradient")
+    assert_close(host(prog.grad_p), ref["grad_p"], "chain grad")
+
+
+# ---------------------------------------------------------------- config 3
+
+@pytest.mark.parametrize("batch,na,nb,n_out", [(16384, 64, 64, 256), (1000, 64, 64, 256), (129, 17, 33, 40), (3, 5, 2, 300)])
+def test_config3_hashed_pipeline(gp, batch, na, nb, n_out):
+    w = W.config3(batch=batch, na=na, nb=nb, n_out=n_out, seed=7)
+    ref = OP.hashed_pipeline_fwd_bwd(w)
+    prog = gp.HashedPipeline(w)
+    prog.step()
+    np.testing.assert_array_equal(prog.o1.sym_ids, ref["s1"])
+    np.testing.assert_array_equal(prog.o2.sym_ids, ref["s2"])
+    np.testing.assert_array_equal(prog.o3.sym_ids, ref["s3"])
+    assert_close(host(prog.o1.prob), ref["o1"], "apply")
+    np.testing.assert_array_equal(host(prog.o2.prob), host(prog.o1.prob)[:, prog.pred.astype(bool)])
+    assert_close(host(prog.o3.prob), ref["o3"], "union")
+    assert_close(host(prog.g2), ref["g2"], "union bwd a")
+    assert_close(host(prog.gp2), ref["gp2"], "union bwd b")
+    assert_close(host(prog.g1), ref["g1"], "filter bwd")
+    assert_close(host(prog.ga), ref["ga"], "apply bwd a")
+    assert_close(host(prog.gb), ref["gb"], "apply bwd b")
+
+
+# ---------------------------------------------------------------- config 4
+
+@pytest.mark.parametrize("batch,n,k", [(1024, 5, 3), (130, 5, 1), (65, 4, 8), (7, 3, 5), (1, 2, 2)])
+def test_config4_dtkp_sum(gp, batch, n, k):
+    w = W.config4(batch=batch, n_digits=n, k=k, seed=k)
+    ref = OP.dtkp_sum_chain(w)
+    prog = gp.DtkpSumChain(w)
+    prog.step()
+    for t in range(1, n):
+        syms, m, pp, pr = ref["stages"][t - 1]
+        d = prog.accs[t]
+        np.testing.assert_array_equal(d.sym_ids, syms)
+        np.testing.assert_array_equal(host(d.proof_mask).view(np.uint64), m, err_msg="masks stage %d" % t)
+        np.testing.assert_array_equal(host(d.proof_prob), pp, err_msg="proof probs stage %d" % t)
+        assert_close(host(d.prob), pr, "tag prob stage %d" % t)
+
+
+# ---------------------------------------------------------------- config 5
+
+@pytest.mark.parametrize("batch,side,rounds", [(256, 32, 64), (33, 7, 20), (2, 3, 5)])
+def test_config5_grid_reach(gp, batch, side, rounds):
+    w = W.config5(batch=batch, side=side, rounds=rounds, seed=side)
+    ref = OP.grid_reach_fwd_bwd(w)
+    prog = gp.GridReach(w)
+    prog.step()
+    hist = host(prog.hist)
+    assert_close(hist, ref["hist"], "reach history")
+    # the clamp decisions: saturated entries agree exactly
+    np.testing.assert_array_equal(hist == 1.0, ref["hist"] == 1.0)
+    assert_close(host(prog.grad_p), ref["grad_p"], "reach grad")
+
+
+# ---------------------------------------------------------------- operators on their own: edge cases
+
+def test_apply_with_rejected_tuples_and_padding(dol):
+    na, nb, B = 9, 6, 70
+    tab = W.hashed_table(3, na, nb, 11)
+    tab[0, :] = -1                     # symbol 0 of a never admitted
+    tab[4, 2] = -1
+    a = W.softmax_rows(W.normal(1, B * na).reshape(B, na))
+    b = W.softmax_rows(W.normal(2, B * nb).reshape(B, nb))
+    tri = oracle.dense_to_triples(tab)
+    syms, want = oracle.damp_apply2_fwd(tri, na, nb, a, b)
+    f = dol.FnTable.create_dense(tab)
+    np.testing.assert_array_equal(f.out_syms, syms)
+    # padded leading dimensions on every tensor
+    ta = torch.zeros((B, na + 3), device="cuda"); ta[:, :na] = dev(a)
+    tb = torch.zeros((B, nb + 5), device="cuda"); tb[:, :nb] = dev(b)
+    to = torch.full((B, f.n_out + 2), -7.0, device="cuda")
+    da, db, do = dol.Dist(np.arange(na), ta[:, :na]), dol.Dist(np.arange(nb), tb[:, :nb]), dol.Dist(syms, to[:, :f.n_out])
+    assert da.ld == na + 3 and do.ld == f.n_out + 2
+    dol.apply2(da, db, f, None, do)
+    assert_close(host(to)[:, :f.n_out], want, "apply padded")
+    assert np.all(host(to)[:, f.n_out:] == -7.0)          # padding untouched
+    g = W.normal(9, B * f.n_out).astype(np.float32).reshape(B, -1)
+    tg = torch.zeros((B, f.n_out + 2), device="cuda"); tg[:, :f.n_out] = dev(g)
+    ga = torch.full((B, na + 3), 5.0, device="cuda")
+    gb = torch.full((B, nb + 5), 5.0, device="cuda")
+    rec = dol.OpRecord(dol.OP_APPLY2, da, db, do, f=f)
+    dol.backward(rec, tg, ga, gb)
+    wa, wb = oracle.damp_apply2_bwd(tri, na, nb, a, b, g)
+    assert_close(host(ga)[:, :na], wa, "bwd a padded")
+    assert_close(host(gb)[:, :nb], wb, "bwd b padded")
+    assert np.all(host(ga)[:, 0] == 0) and np.all(host(ga)[:, na:] == 5.0) and np.all(host(gb)[:, nb:] == 5.0)
+    # accumulate flags add to what is there
+    rec2 = dol.OpRecord(dol.OP_APPLY2, da, db, do, f=f, accumulate=3)
+    dol.backward(rec2, tg, ga, gb)
+    assert_close(host(ga)[:, :na], 2 * wa.astype(np.float64), "bwd a accumulated")
+    assert_close(host(gb)[:, :nb], 2 * wb.astype(np.float64), "bwd b accumulated")
+
+
+def test_clamp_decisions_match_oracle(dol):
+    """Tags large enough that many columns exceed 1: values clamp, gradients gate, decisions agree bit for bit."""
+    na, nb, B = 12, 12, 200
+    tab = W.hashed_table(5, na, nb, 6)
+    a = (W.uniform01(1, B * na) * 0.4).astype(np.float32).reshape(B, na)
+    b = (W.uniform01(2, B * nb) * 0.4).astype(np.float32).reshape(B, nb)
+    # exact boundary cases: rows 0..2 make column sums of exactly 0.875, 1.0, 1.125
+    for r, tot in enumerate((0.875, 1.0, 1.125)):
+        a[r] = 0; b[r] = 0
+        a[r, 0] = 1.0; b[r, 0] = tot
+    tri = oracle.dense_to_triples(tab)
+    syms, want, pre32, _ = oracle.damp_apply2_fwd(tri, na, nb, a, b, want_pre=True)
+    assert 0.2 < (pre32 > 1).mean() < 0.8
+    f = dol.FnTable.create_dense(tab)
+    da, db = dol.Dist(np.arange(na), dev(a)), dol.Dist(np.arange(nb), dev(b))
+    do = dol.Dist.empty(syms, B)
+    dol.apply2(da, db, f, None, do)
+    got = host(do.prob)
+    assert_close(got, want, "clamped apply")
+    np.testing.assert_array_equal(got == 1.0, pre32 >= 1.0)
+    g = W.normal(3, B * syms.size).astype(np.float32).reshape(B, -1)
+    ga, gb = torch.empty_like(da.prob), torch.empty_like(db.prob)
+    dol.backward(dol.OpRecord(dol.OP_APPLY2, da, db, do, f=f), dev(g), ga, gb)
+    wa, wb = oracle.damp_apply2_bwd(tri, na, nb, a, b, g)
+    assert_close(host(ga), wa, "gated bwd a")
+    assert_close(host(gb), wb, "gated bwd b")
+
+
+def test_union_and_filter_edge_cases(dol):
+    B = 50
+    sa, sb = np.array([1, 4, 6, 8, 9], np.int32), np.array([0, 4, 9, 12], np.int32)
+    a = (W.uniform01(4, B * 5) * 0.9).astype(np.float32).reshape(B, 5)
+    b = (W.uniform01(5, B * 4) * 0.9).astype(np.float32).reshape(B, 4)
+    a[0, 1], b[0, 1] = 0.5, 0.5          # a+b == 1 exactly: passes gradient
+    a[1, 1], b[1, 1] = 0.75, 0.5         # clamps
+    da, db = dol.Dist(sa, dev(a)), dol.Dist(sb, dev(b))
+    syms = dol.union_plan(da, db)
+    want_syms, ia, ib = oracle.union_plan(sa, sb)
+    np.testing.assert_array_equal(syms, want_syms)
+    do = dol.Dist.empty(syms, B)
+    dol.union(da, db, None, do)
+    assert_close(host(do.prob), oracle.damp_union_fwd(ia, ib, a, b), "union")
+    g = W.normal(6, B * syms.size).astype(np.float32).reshape(B, -1)
+    ga, gb = torch.empty_like(da.prob), torch.empty_like(db.prob)
+    dol.backward(dol.OpRecord(dol.OP_UNION, da, db, do), dev(g), ga, gb)
+    wa, wb = oracle.damp_union_bwd(ia, ib, a, b, g)
+    np.testing.assert_array_equal(host(ga), wa)
+    np.testing.assert_array_equal(host(gb), wb)
+    # union with an empty Distribution is the identity
+    de = dol.Dist(np.empty(0, np.int32), torch.empty((B, 0), device="cuda"))
+    d2 = dol.Dist.empty(dol.union_plan(da, de), B)
+    dol.union(da, de, None, d2)
+    np.testing.assert_array_equal(host(d2.prob), a)
+    # filter: all kept = identity, none kept = empty result, and the transpose
+    d3 = dol.Dist.empty(sa, B)
+    dol.filter(da, np.ones(5, np.uint8), None, d3)
+    np.testing.assert_array_equal(host(d3.prob), a)
+    assert dol.filter_plan(da, np.zeros(5, np.uint8)).size == 0
+    d4 = dol.Dist(np.empty(0, np.int32), torch.empty((B, 0), device="cuda"))
+    dol.filter(da, np.zeros(5, np.uint8), None, d4)
+    pred = np.array([1, 0, 0, 1, 1], np.uint8)
+    d5 = dol.Dist.empty(dol.filter_plan(da, pred), B)
+    dol.filter(da, pred, None, d5)
+    np.testing.assert_array_equal(host(d5.prob), oracle.damp_filter_fwd(pred, a))
+    g5 = W.normal(7, B * 3).astype(np.float32).reshape(B, 3)
+    gi = torch.full((B, 5), 9.0, device="cuda")
+    dol.backward(dol.OpRecord(dol.OP_FILTER, da, None, d5, pred_mask=pred), dev(g5), gi, None)
+    np.testing.assert_array_equal(host(gi), oracle.damp_filter_bwd(pred, g5))
+
+
+def test_empty_batch_and_errors(dol):
+    f = dol.FnTable.create_dense(W.sum_table(range(3), range(3)))
+    e3 = dol.Dist(np.arange(3), torch.empty((0, 3), device="cuda"))
+    e5 = dol.Dist(f.out_syms, torch.empty((0, 5), device="cuda"))
+    dol.apply2(e3, e3, f, None, e5)                       # batch 0 is legal
+    a = dol.Dist(np.arange(3), torch.ones((2, 3), device="cuda"))
+    wrong = dol.Dist(np.arange(4), torch.ones((2, 4), device="cuda"))
+    out = dol.Dist.empty(f.out_syms, 2)
+    out.prob.fill_(-3.0)
+    with pytest.raises(dol.DolError) as ei:
+        dol.apply2(a, wrong, f, None, out)
+    assert ei.value.status == 2 and "table" in str(ei.value)
+    assert np.all(host(out.prob) == -3.0)                  # outputs untouched on error
+    with pytest.raises(dol.DolError) as ei:
+        dol.FnTable.create_sparse(2, 2, [0, 0], [1, 1], [5, 6])       # a function has one value per tuple
+    assert ei.value.status == 1
+    with pytest.raises(dol.DolError) as ei:
+        dol.FnTable.create_sparse(2, 2, [0, 2], [1, 1], [5, 6])       # index outside the operand
+    assert ei.value.status == 2
+    none = dol.FnTable.create_dense(np.full((3, 3), -1, np.int32))     # nothing admitted: empty result, zero gradients
+    assert none.n_out == 0
+    o0 = dol.Dist(np.empty(0, np.int32), torch.empty((2, 0), device="cuda"))
+    dol.apply2(a, a, none, None, o0)
+    ga = torch.full((2, 3), 4.0, device="cuda")
+    dol.backward(dol.OpRecord(dol.OP_APPLY2, a, a, o0, f=none), torch.empty((2, 0), device="cuda"), ga, None)
+    assert np.all(host(ga) == 0)
+    prov = dol.Prov(dol.DTKP, 3, torch.ones((2, 4), device="cuda"), None)
+    with pytest.raises(dol.DolError) as ei:
+        dol.backward(dol.OpRecord(dol.OP_APPLY2, a, a, out, f=f, prov=prov), out.prob, ga, None)
+    assert ei.value.status == 5
+
+
+def test_dtkp_general_conjunction_union_filter(dol):
+    """k x k conjunction with overlapping fact sets, exclusion groups, then union and filter under DTKP."""
+    B, k, n_facts = 40, 3, 12
+    fp = W.uniform01(11, B * n_facts).astype(np.float32).reshape(B, n_facts)
+    grp = np.array([0, 0, 0, 1, 1, 1, 2, 3, 4, 5, 6, 7], np.int32)
+    d_fp = dev(fp)
+    prov = dol.Prov(dol.DTKP, k, d_fp, grp)
+    # two stages of apply so that the second sees multi-proof tags on both sides
+    s0, s1 = np.arange(3, dtype=np.int32), np.arange(3, dtype=np.int32)
+    tabs = [W.hashed_table(21, 3, 3, 4), W.hashed_table(22, 3, 3, 4)]
+    facts = [[0, 1, 6], [3, 4, 7], [2, 8, 9], [5, 10, 11]]
+    o_m = [oracle.dtkp_init(f, fp, k) for f in facts]
+    g_d = []
+    for f in facts:
+        d = dol.Dist.empty(np.arange(3), B, k=k)
+        dol.dtkp_init(d, f, prov)
+        g_d.append(d)
+    for x in range(4):
+        np.testing.assert_array_equal(host(g_d[x].proof_mask).view(np.uint64), o_m[x][0])
+        np.testing.assert_array_equal(host(g_d[x].proof_prob), o_m[x][1])
+        np.testing.assert_array_equal(host(g_d[x].prob), o_m[x][2])
+    mids_o, mids_g = [], []
+    for x, tab in enumerate(tabs):
+        tri = oracle.dense_to_triples(tab)
+        so, om, op, opr = oracle.dtkp_apply2(tri, 3, 3, k, grp, fp, o_m[2 * x][0], o_m[2 * x + 1][0])
+        f = dol.FnTable.create_dense(tab)
+        out = dol.Dist.empty(f.out_syms, B, k=k)
+        dol.apply2(g_d[2 * x], g_d[2 * x + 1], f, prov, out)
+        np.testing.assert_array_equal(out.sym_ids, so)
+        np.testing.assert_array_equal(host(out.proof_mask).view(np.uint64), om)
+        np.testing.assert_array_equal(host(out.proof_prob), op)
+        assert_close(host(out.prob), opr, "dtkp apply")
+        mids_o.append((so, om, op, opr)); mids_g.append(out)
+    # k x k conjunction of the two multi-proof results (facts of groups 0 and 1 overlap across sides)
+    na, nb = mids_o[0][0].size, mids_o[1][0].size
+    tab2 = W.hashed_table(23, na, nb, 5)
+    tri2 = oracle.dense_to_triples(tab2)
+    so, om, op, opr = oracle.dtkp_apply2(tri2, na, nb, k, grp, fp, mids_o[0][1], mids_o[1][1])
+    f2 = dol.FnTable.create_dense(tab2)
+    out2 = dol.Dist.empty(f2.out_syms, B, k=k)
+    dol.apply2(mids_g[0], mids_g[1], f2, prov, out2)
+    np.testing.assert_array_equal(host(out2.proof_mask).view(np.uint64), om)
+    np.testing.assert_array_equal(host(out2.proof_prob), op)
+    assert_close(host(out2.prob), opr, "dtkp k x k apply")
+    assert (om[:, :, 1] != oracle.ABSENT).any()
+    # union of the two mid results (their symbol lists overlap)
+    usyms, ia, ib = oracle.union_plan(mids_o[0][0], mids_o[1][0])
+    um, up, upr = oracle.dtkp_union(ia, ib, mids_o[0][1], mids_o[0][2], mids_o[1][1], mids_o[1][2])
+    uo = dol.Dist.empty(dol.union_plan(mids_g[0], mids_g[1]), B, k=k)
+    np.testing.assert_array_equal(uo.sym_ids, usyms)
+    dol.union(mids_g[0], mids_g[1], prov, uo)
+    np.testing.assert_array_equal(host(uo.proof_mask).view(np.uint64), um)
+    np.testing.assert_array_equal(host(uo.proof_prob), up)
+    assert_close(host(uo.prob), upr, "dtkp union")
+    # filter
+    pred = (np.arange(usyms.size) % 2 == 0).astype(np.uint8)
+    fm, fpp, fpr = oracle.dtkp_filter(pred, um, up, upr)
+    fo = dol.Dist.empty(dol.filter_plan(uo, pred), B, k=k)
+    dol.filter(uo, pred, prov, fo)
+    np.testing.assert_array_equal(host(fo.proof_mask).view(np.uint64), fm)
+    np.testing.assert_array_equal(host(fo.proof_prob), fpp)
+    np.testing.assert_array_equal(host(fo.prob), fpr)
+
+
+def test_hip_graph_replay_matches_eager(gp):
+    """The chain issues only asynchronous launches, so it can be captured; replays equal the eager result."""
+    w = W.config2(batch=512, n_digits=6, seed=5)
+    prog = gp.SumChain(w)
+    prog.step()
+    eager = host(prog.grad_p).copy()
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        prog.step()
+    torch.cuda.current_stream().wait_stream(s)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        prog.step()
+    for _ in range(3):
+        prog.grad_p.fill_(-1.0)
+        torch.cuda.synchronize()
+        graph.replay()
+        np.testing.assert_array_equal(host(prog.grad_p), eager)
