@@ -92,6 +92,10 @@ dol_status dol_fn_table_create_sparse(int32_t na, int32_t nb, int64_t n, const i
  * Column c of the result of dol_apply2 is symbol out_syms[c]. */
 int32_t dol_fn_table_n_out(const dol_fn_table *table);
 const int32_t *dol_fn_table_out_syms(const dol_fn_table *table);
+/* Name of the HIP kernel that dol_apply2 (which = 0) or dol_backward (which = 1) launches for this table under
+ * DAMP, as a profiler prints it without namespace and arguments (valid until destroy).  The library picks the
+ * kernel from the table's structure (Sec. 3.1.2: the symbol side is known before any tag is touched). */
+const char *dol_fn_table_kernel(const dol_fn_table *table, int32_t which);
 /* Synchronises the device before releasing the device copies.  NULL is ignored. */
 void dol_fn_table_destroy(dol_fn_table *table);
 

@@ -62,6 +62,8 @@ _lib.dol_fn_table_n_out.argtypes = [C.c_void_p]
 _lib.dol_fn_table_n_out.restype = C.c_int32
 _lib.dol_fn_table_out_syms.argtypes = [C.c_void_p]
 _lib.dol_fn_table_out_syms.restype = _i32p
+_lib.dol_fn_table_kernel.argtypes = [C.c_void_p, C.c_int32]
+_lib.dol_fn_table_kernel.restype = C.c_char_p
 _lib.dol_fn_table_destroy.argtypes = [C.c_void_p]
 _lib.dol_fn_table_destroy.restype = None
 _lib.dol_apply2.argtypes = [C.POINTER(_Dist), C.POINTER(_Dist), C.c_void_p, C.POINTER(_Prov), C.POINTER(_Dist), C.c_void_p]
@@ -176,6 +178,8 @@ class FnTable:
         self.n_out = int(_lib.dol_fn_table_n_out(handle))
         p = _lib.dol_fn_table_out_syms(handle)
         self.out_syms = np.ctypeslib.as_array(p, shape=(self.n_out,)).copy() if self.n_out else np.empty(0, np.int32)
+        self.kernel_fwd = _lib.dol_fn_table_kernel(handle, 0).decode()
+        self.kernel_bwd = _lib.dol_fn_table_kernel(handle, 1).decode()
 
     @staticmethod
     def create_dense(out_id) -> "FnTable":

@@ -46,6 +46,7 @@ dol_status launch_damp_apply2_fwd(const dol_fn_table *f, int32_t batch, const fl
 {
     const int64_t total = static_cast<int64_t>(batch) * f->n_out;
     if (total == 0) return DOL_OK;
+    if (conv_path_ok(f)) return launch_damp_conv_fwd(f, batch, a, lda, b, ldb, out, ldo, st);
     hipLaunchKernelGGL(damp_apply2_fwd_kernel, dim3(grid_for(total)), dim3(kThreads), 0, st, total, f->n_out,
                        f->col_ptr.ptr, f->col_ij.ptr, a, lda, b, ldb, out, ldo);
     DOL_HIP(hipGetLastError());
@@ -110,6 +111,7 @@ dol_status launch_damp_apply2_bwd(const dol_fn_table *f, int32_t batch, const fl
 {
     const int64_t total = static_cast<int64_t>(batch) * (f->na + f->nb);
     if (total == 0 || (!ga && !gb)) return DOL_OK;
+    if (conv_path_ok(f)) return launch_damp_conv_bwd(f, batch, a, lda, b, ldb, g, ldg, ga, gb, accumulate, st);
     hipLaunchKernelGGL(damp_apply2_bwd_kernel, dim3(grid_for(total)), dim3(kThreads), 0, st, total, f->na, f->nb,
                        f->col_ptr.ptr, f->col_ij.ptr, f->rowa_ptr.ptr, f->rowa_jc.ptr, f->rowb_ptr.ptr,
                        f->rowb_ic.ptr, a, lda, b, ldb, out, ldo, g, ldg, ga, gb, accumulate);

@@ -69,7 +69,10 @@ struct dol_fn_table {
     int64_t n_tuples = 0;
     int32_t max_col_len = 0;             // most tuples landing in one column
     bool sum_like = false;               // every column's tuples have i ascending by 1 and j descending by 1
+    bool conv_like = false;              // all na*nb tuples admitted and tuple (i, j) lands in column i + j:
+                                         // the operator is a discrete convolution of the two tag rows
     std::vector<int32_t> out_syms;       // [n_out] ascending ids
+    std::string kernel_fwd, kernel_bwd;  // names of the DAMP kernels chosen for this table
     // host copies (kept for the chain planner)
     std::vector<uint32_t> h_col_ptr, h_col_ij;
     // forward: column c owns entries col_ptr[c] .. col_ptr[c+1] of col_ij = pack16(i, j), ascending (i, j)
@@ -120,6 +123,14 @@ dol_status launch_damp_apply2_bwd(const dol_fn_table *f, int32_t batch, const fl
                                   float *gb, int32_t accumulate, hipStream_t st);
 dol_status launch_nll_grad(int32_t batch, int32_t n, const float *p, int64_t ld, const int32_t *target, float *grad,
                            hipStream_t st);
+// Convolution-shaped tables with a short second operand (damp_conv.hip)
+bool conv_path_ok(const dol_fn_table *f);
+std::string damp_kernel_name(const dol_fn_table *f, bool backward);
+dol_status launch_damp_conv_fwd(const dol_fn_table *f, int32_t batch, const float *a, int64_t lda, const float *b,
+                                int64_t ldb, float *out, int64_t ldo, hipStream_t st);
+dol_status launch_damp_conv_bwd(const dol_fn_table *f, int32_t batch, const float *a, int64_t lda, const float *b,
+                                int64_t ldb, const float *g, int64_t ldg, float *ga, float *gb, int32_t accumulate,
+                                hipStream_t st);
 dol_status launch_zero_rows(int32_t batch, int32_t n, float *x, int64_t ld, hipStream_t st);
 dol_status launch_damp_filter_fwd(const FilterPlan *p, int32_t batch, const float *in, int64_t ldi, float *out,
                                   int64_t ldo, hipStream_t st);

@@ -109,12 +109,18 @@ static dol_status build_table(int32_t na, int32_t nb, std::vector<Tuple> &tup, d
             if ((p1 & 0xffff) != (p0 & 0xffff) + 1 || (p1 >> 16) + 1 != (p0 >> 16)) { tb->sum_like = false; break; }
         }
 
+    tb->conv_like = na > 0 && nb > 0 && tup.size() == static_cast<size_t>(na) * static_cast<size_t>(nb) && S == na + nb - 1;
+    for (size_t t = 0; t < tup.size() && tb->conv_like; ++t)
+        tb->conv_like = col[t] == static_cast<uint32_t>(tup[t].i + tup[t].j);
+
     if (hipGetDevice(&tb->device) != hipSuccess) tb->device = 0;
     hipError_t e;
     if ((e = tb->col_ptr.upload(col_ptr)) != hipSuccess || (e = tb->col_ij.upload(col_ij)) != hipSuccess ||
         (e = tb->rowa_ptr.upload(rowa_ptr)) != hipSuccess || (e = tb->rowa_jc.upload(rowa_jc)) != hipSuccess ||
         (e = tb->rowb_ptr.upload(rowb_ptr)) != hipSuccess || (e = tb->rowb_ic.upload(rowb_ic)) != hipSuccess)
         return hip_fail(e, "uploading the function table");
+    tb->kernel_fwd = damp_kernel_name(tb.get(), false);
+    tb->kernel_bwd = damp_kernel_name(tb.get(), true);
     tb->h_col_ptr.swap(col_ptr);
     tb->h_col_ij.swap(col_ij);
     *out = tb.release();
@@ -329,6 +335,12 @@ int32_t dol_fn_table_n_out(const dol_fn_table *table) { return table ? table->n_
 const int32_t *dol_fn_table_out_syms(const dol_fn_table *table) { return table ? table->out_syms.data() : nullptr; }
 
 void dol_fn_table_destroy(dol_fn_table *table) { delete table; }
+
+const char *dol_fn_table_kernel(const dol_fn_table *table, int32_t which)
+{
+    if (!table) return "";
+    return which ? table->kernel_bwd.c_str() : table->kernel_fwd.c_str();
+}
 
 dol_status dol_filter_plan(const dol_dist *d, const uint8_t *pred_mask, int32_t *n_out, int32_t *out_syms)
 {

@@ -2,18 +2,34 @@
 
 Each class uploads one workload, builds the symbol-side plans once (the user
 function is evaluated once per batch, Sec. 3.1.2 / App. B), allocates every
-intermediate Distribution up front, and then ``forward()`` / ``backward()`` only
-issue asynchronous ``dol_*`` calls on the current stream, so a step can be
-captured into a HIP graph.  No arithmetic happens in Python.
+intermediate Distribution up front, and lists its launches.  ``forward()`` /
+``backward()`` / ``step()`` then only issue asynchronous ``dol_*`` calls on the
+current stream, so a step can be captured into a HIP graph.  No arithmetic
+happens in Python.
+
+Every launch carries the name of the kernel it runs and its algorithmic cost:
+bytes the operator must move (each input element read once, each output element
+written once, 4 bytes per tag, 12 bytes per DTKP proof slot) and
+multiply-accumulates.  The bench turns these into roofline fractions.
 """
 from __future__ import annotations
 
-from typing import List, Optional
+from dataclasses import dataclass
+from typing import Callable, List
 
 import numpy as np
 import torch
 
 from . import binding as dol
+
+
+@dataclass
+class Launch:
+    kernel: str                 # name of the HIP kernel the call launches
+    call: Callable[[], None]
+    bytes: int                  # algorithmic HBM bytes of this launch
+    macs: int                   # multiply-accumulates (DAMP) or candidate proofs (DTKP)
+    phase: str                  # "fwd" or "bwd"
 
 
 def _dev(x: np.ndarray, device) -> torch.Tensor:
@@ -25,22 +41,63 @@ def sum_table_of(sym_a, sym_b) -> np.ndarray:
     return (np.asarray(sym_a, np.int32)[:, None] + np.asarray(sym_b, np.int32)[None, :]).astype(np.int32)
 
 
-class Sum2Forward:
+def _n_tuples(table: np.ndarray) -> int:
+    return int((np.asarray(table) >= 0).sum())
+
+
+class Program:
+    launches: List[Launch]
+    sample_ops: int
+    batch: int
+
+    def forward(self):
+        for l in self.launches:
+            if l.phase == "fwd":
+                l.call()
+
+    def backward(self):
+        for l in self.launches:
+            if l.phase == "bwd":
+                l.call()
+
+    def step(self):
+        for l in self.launches:
+            l.call()
+
+    def algorithmic_bytes(self) -> int:
+        return sum(l.bytes for l in self.launches)
+
+
+def _apply_fwd(a, b, f, out, n_tup, prov=None, dtkp_k=0):
+    B = a.batch
+    if dtkp_k:
+        return Launch("dtkp_apply2_kernel", lambda: dol.apply2(a, b, f, prov, out),
+                      B * (12 * dtkp_k * (a.n_sym + b.n_sym + out.n_sym) + 4 * out.n_sym), B * n_tup * dtkp_k, "fwd")
+    return Launch(f.kernel_fwd, lambda: dol.apply2(a, b, f, None, out),
+                  4 * B * (a.n_sym + b.n_sym + out.n_sym), B * n_tup, "fwd")
+
+
+def _apply_bwd(rec, g, ga, gb, n_tup):
+    a, b, out = rec.a, rec.b, rec.out
+    n_w = (a.n_sym if ga is not None else 0) + (b.n_sym if gb is not None else 0)
+    return Launch(rec.f.kernel_bwd, lambda: dol.backward(rec, g, ga, gb),
+                  4 * a.batch * (a.n_sym + b.n_sym + out.n_sym + n_w), 2 * a.batch * n_tup, "bwd")
+
+
+class Sum2Forward(Program):
     """Config 1 (Fig. 2 with two digits): one DAMP apply."""
 
     def __init__(self, w, device="cuda"):
         self.table = dol.FnTable.create_dense(w["table"])
         self.a = dol.Dist(w["sym"], _dev(w["pa"], device))
         self.b = dol.Dist(w["sym"], _dev(w["pb"], device))
-        self.out = dol.Dist.empty(self.table.out_syms, self.a.batch, device)
-        self.sample_ops = self.a.batch
-
-    def forward(self):
-        dol.apply2(self.a, self.b, self.table, None, self.out)
-        return self.out
+        self.batch = self.a.batch
+        self.out = dol.Dist.empty(self.table.out_syms, self.batch, device)
+        self.launches = [_apply_fwd(self.a, self.b, self.table, self.out, _n_tuples(w["table"]))]
+        self.sample_ops = self.batch
 
 
-class SumChain:
+class SumChain(Program):
     """Config 2 (Fig. 2): left fold of DAMP apply over N digit Distributions, then the reverse sweep of
     vector-Jacobian products from the harness-supplied gradient of -log p[target]."""
 
@@ -52,8 +109,11 @@ class SumChain:
         self.digits = [dol.Dist(sym, self.p_dev[t]) for t in range(self.n)]
         self.tables: List[dol.FnTable] = []
         self.accs: List[dol.Dist] = [self.digits[0]]
+        n_tup = []
         for t in range(1, self.n):
-            tb = dol.FnTable.create_dense(sum_table_of(self.accs[-1].sym_ids, sym))
+            tab = sum_table_of(self.accs[-1].sym_ids, sym)
+            tb = dol.FnTable.create_dense(tab)
+            n_tup.append(_n_tuples(tab))
             self.tables.append(tb)
             self.accs.append(dol.Dist.empty(tb.out_syms, self.batch, device))
         self.records = [dol.OpRecord(dol.OP_APPLY2, self.accs[t - 1], self.digits[t], self.accs[t], f=self.tables[t - 1])
@@ -61,31 +121,19 @@ class SumChain:
         self.target = _dev(w["target"].astype(np.int32), device)     # column index = the sum itself
         self.grad_p = torch.empty_like(self.p_dev)           # [n, B, 10]
         self.g_acc = [torch.empty((self.batch, d.n_sym), dtype=torch.float32, device=device) for d in self.accs]
-        self.sample_ops = 2 * (self.n - 1) * self.batch
-
-    def forward(self):
-        for t in range(1, self.n):
-            dol.apply2(self.accs[t - 1], self.digits[t], self.tables[t - 1], None, self.accs[t])
-        return self.accs[-1]
-
-    def loss_grad(self):
-        """Harness side: d(-log p[target]) / d p, written into the last gradient buffer."""
-        dol.nll_grad(self.accs[-1], self.target, self.g_acc[-1])
-        return self.g_acc[-1]
-
-    def backward(self):
+        self.launches = [_apply_fwd(self.accs[t - 1], self.digits[t], self.tables[t - 1], self.accs[t], n_tup[t - 1])
+                         for t in range(1, self.n)]
+        last = self.accs[-1]
+        # harness side: d(-log p[target]) / d p
+        self.launches.append(Launch("nll_grad_kernel", lambda: dol.nll_grad(last, self.target, self.g_acc[-1]),
+                                    4 * self.batch * (1 + 2 * last.n_sym), 0, "bwd"))
         for t in range(self.n - 1, 0, -1):
             ga = self.g_acc[t - 1] if t > 1 else self.grad_p[0]
-            dol.backward(self.records[t - 1], self.g_acc[t], ga, self.grad_p[t])
-        return self.grad_p
-
-    def step(self):
-        self.forward()
-        self.loss_grad()
-        return self.backward()
+            self.launches.append(_apply_bwd(self.records[t - 1], self.g_acc[t], ga, self.grad_p[t], n_tup[t - 1]))
+        self.sample_ops = 2 * (self.n - 1) * self.batch
 
 
-class HashedPipeline:
+class HashedPipeline(Program):
     """Config 3: apply with a hashed symbol table, filter by a keep-mask over the produced ids, union with a
     second Distribution over all ids; backward through all three."""
 
@@ -93,6 +141,7 @@ class HashedPipeline:
         B = w["pa"].shape[0]
         self.batch = B
         self.table = dol.FnTable.create_dense(w["table"])
+        n_tup = _n_tuples(w["table"])
         self.a = dol.Dist(np.arange(w["na"]), _dev(w["pa"], device))
         self.b = dol.Dist(np.arange(w["nb"]), _dev(w["pb"], device))
         self.o1 = dol.Dist.empty(self.table.out_syms, B, device)
@@ -109,55 +158,51 @@ class HashedPipeline:
         self.rec1 = dol.OpRecord(dol.OP_APPLY2, self.a, self.b, self.o1, f=self.table)
         self.rec2 = dol.OpRecord(dol.OP_FILTER, self.o1, None, self.o2, pred_mask=self.pred)
         self.rec3 = dol.OpRecord(dol.OP_UNION, self.o2, self.p2, self.o3)
+        n1, n2, n3, np2 = self.o1.n_sym, self.o2.n_sym, self.o3.n_sym, self.p2.n_sym
+        self.launches = [
+            _apply_fwd(self.a, self.b, self.table, self.o1, n_tup),
+            Launch("damp_gather_cols_kernel", lambda: dol.filter(self.o1, self.pred, None, self.o2),
+                   4 * B * (n1 + n2), 0, "fwd"),
+            Launch("damp_union_fwd_kernel", lambda: dol.union(self.o2, self.p2, None, self.o3),
+                   4 * B * (n2 + np2 + n3), 0, "fwd"),
+            Launch("damp_union_bwd_kernel", lambda: dol.backward(self.rec3, self.g3, self.g2, self.gp2),
+                   4 * B * (n3 + 2 * n2 + 2 * np2), 0, "bwd"),
+            Launch("damp_gather_cols_kernel", lambda: dol.backward(self.rec2, self.g2, self.g1, None),
+                   4 * B * (n2 + n1), 0, "bwd"),
+            _apply_bwd(self.rec1, self.g1, self.ga, self.gb, n_tup),
+        ]
         self.sample_ops = 6 * B
 
-    def forward(self):
-        dol.apply2(self.a, self.b, self.table, None, self.o1)
-        dol.filter(self.o1, self.pred, None, self.o2)
-        dol.union(self.o2, self.p2, None, self.o3)
-        return self.o3
 
-    def backward(self):
-        dol.backward(self.rec3, self.g3, self.g2, self.gp2)
-        dol.backward(self.rec2, self.g2, self.g1, None)
-        dol.backward(self.rec1, self.g1, self.ga, self.gb)
-        return self.ga, self.gb, self.gp2
-
-    def step(self):
-        self.forward()
-        return self.backward()
-
-
-class DtkpSumChain:
+class DtkpSumChain(Program):
     """Config 4: the sum fold under DTKP-AM with k proofs per tag; fact 10*n+d says "digit n is d"."""
 
     def __init__(self, w, device="cuda"):
         p = w["p"]
         self.n, self.batch, self.k = p.shape[0], p.shape[1], w["k"]
+        k, B = self.k, self.batch
         sym = np.asarray(w["sym"], np.int32)
         self.fact_prob = _dev(w["fact_prob"], device)
-        self.prov = dol.Prov(dol.DTKP, self.k, self.fact_prob, w["fact_group"])
-        self.digits = [dol.Dist.empty(sym, self.batch, device, k=self.k) for _ in range(self.n)]
+        self.prov = dol.Prov(dol.DTKP, k, self.fact_prob, w["fact_group"])
+        self.digits = [dol.Dist.empty(sym, B, device, k=k) for _ in range(self.n)]
         self.facts = [10 * t + np.arange(10, dtype=np.int32) for t in range(self.n)]
         self.tables, self.accs = [], [self.digits[0]]
-        for t in range(1, self.n):
-            tb = dol.FnTable.create_dense(sum_table_of(self.accs[-1].sym_ids, sym))
-            self.tables.append(tb)
-            self.accs.append(dol.Dist.empty(tb.out_syms, self.batch, device, k=self.k))
-        self.sample_ops = (self.n - 1) * self.batch
-
-    def forward(self):
+        self.launches = []
         for t in range(self.n):
-            dol.dtkp_init(self.digits[t], self.facts[t], self.prov)
+            d, f = self.digits[t], self.facts[t]
+            self.launches.append(Launch("dtkp_init_kernel", lambda d=d, f=f: dol.dtkp_init(d, f, self.prov),
+                                        B * 10 * (4 + 12 * k + 4), 0, "fwd"))
         for t in range(1, self.n):
-            dol.apply2(self.accs[t - 1], self.digits[t], self.tables[t - 1], self.prov, self.accs[t])
-        return self.accs[-1]
+            tab = sum_table_of(self.accs[-1].sym_ids, sym)
+            tb = dol.FnTable.create_dense(tab)
+            self.tables.append(tb)
+            out = dol.Dist.empty(tb.out_syms, B, device, k=k)
+            self.launches.append(_apply_fwd(self.accs[-1], self.digits[t], tb, out, _n_tuples(tab), self.prov, k))
+            self.accs.append(out)
+        self.sample_ops = (self.n - 1) * B
 
-    def step(self):
-        return self.forward()
 
-
-class GridReach:
+class GridReach(Program):
     """Config 5: fixed-round single-source reachability on a 4-neighbour grid (App. B, transitive closure
     restricted to one source).  One round is one apply over (node, edge-or-stay) tuples: node u with edge
     {u,v} yields v, node v with the "stay" symbol (tag 1, the conjunction identity) yields v; the
@@ -169,6 +214,7 @@ class GridReach:
         E = w["edge_u"].size
         self.table = dol.FnTable.create_sparse(n, E + 1, w["tri_i"], w["tri_j"], w["tri_o"])
         assert self.table.n_out == n
+        n_tup = int(w["tri_i"].size)
         pe = torch.ones((B, E + 1), dtype=torch.float32, device=device)
         pe[:, :E] = _dev(w["p"], device)
         self.edges = dol.Dist(np.arange(E + 1), pe)
@@ -184,22 +230,15 @@ class GridReach:
         self.g_r = [torch.empty((B, n), dtype=torch.float32, device=device) for _ in range(2)]
         self.g_e = torch.zeros((B, E + 1), dtype=torch.float32, device=device)
         self.grad_p = self.g_e[:, :E]                        # the last column belongs to the "stay" symbol
-        self.E = E
-        self.sample_ops = 2 * self.rounds * B
-
-    def forward(self):
-        for t in range(self.rounds):
-            dol.apply2(self.r[t], self.edges, self.table, None, self.r[t + 1])
-        return self.r[-1]
-
-    def backward(self):
+        self.launches = [_apply_fwd(self.r[t], self.edges, self.table, self.r[t + 1], n_tup)
+                         for t in range(self.rounds)]
         g = self.g_out
         for t in range(self.rounds - 1, -1, -1):
             gn = self.g_r[t % 2]
-            dol.backward(self.records[t], g, gn, self.g_e)
+            self.launches.append(_apply_bwd(self.records[t], g, gn, self.g_e, n_tup))
             g = gn
-        return self.grad_p
+        self.sample_ops = 2 * self.rounds * B
 
-    def step(self):
-        self.forward()
-        return self.backward()
+
+def make_program(config_id: int, workload, device="cuda") -> Program:
+    return {1: Sum2Forward, 2: SumChain, 3: HashedPipeline, 4: DtkpSumChain, 5: GridReach}[config_id](workload, device)

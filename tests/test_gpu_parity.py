@@ -58,7 +58,8 @@ def test_config1_sum2(gp, batch):
     w = W.config1(batch=batch, seed=batch)
     ref = OP.sum2_fwd(w)
     prog = gp.Sum2Forward(w)
-    out = prog.forward()
+    prog.forward()
+    out = prog.out
     np.testing.assert_array_equal(out.sym_ids, ref["syms"])
     assert_close(host(out.prob), ref["out"], "sum2")
 
@@ -196,6 +197,43 @@ def test_clamp_decisions_match_oracle(dol):
     wa, wb = oracle.damp_apply2_bwd(tri, na, nb, a, b, g)
     assert_close(host(ga), wa, "gated bwd a")
     assert_close(host(gb), wb, "gated bwd b")
+
+
+@pytest.mark.parametrize("na,nb,B", [(127, 10, 300), (10, 10, 65), (1, 3, 70), (200, 16, 130), (5, 7, 64), (70, 1, 33),
+                                      (9, 17, 40), (64, 4, 129), (300, 10, 50), (257, 2, 9), (256, 16, 5)])
+def test_sum_tables_with_clamping(dol, na, nb, B):
+    """Sum-shaped tables of every supported width, with unnormalised tags so that many columns exceed 1 and the
+    backward pass has to re-derive the clamp decisions; rows 0..2 hit 0.875 / 1.0 / 1.125 exactly."""
+    tab = W.sum_table(range(na), range(nb))
+    x = min(1.0, 2.2 / np.sqrt(min(na, nb)))        # column sums of min(na, nb) terms scatter around 1
+    a = (W.uniform01(na, B * na) * x).astype(np.float32).reshape(B, na)
+    b = (W.uniform01(nb + 100, B * nb) * x).astype(np.float32).reshape(B, nb)
+    for r, tot in enumerate((0.875, 1.0, 1.125)):
+        a[r] = 0; b[r] = 0
+        a[r, na - 1] = 1.0; b[r, 0] = tot
+    a[3] *= 0.01                       # a sample far below the clamp takes the shortcut
+    tri = oracle.dense_to_triples(tab)
+    syms, want, pre32, _ = oracle.damp_apply2_fwd(tri, na, nb, a, b, want_pre=True)
+    f = dol.FnTable.create_dense(tab)
+    da, db = dol.Dist(np.arange(na), dev(a)), dol.Dist(np.arange(nb), dev(b))
+    do = dol.Dist.empty(syms, B)
+    dol.apply2(da, db, f, None, do)
+    got = host(do.prob)
+    assert_close(got, want, "sum apply")
+    np.testing.assert_array_equal(got == 1.0, pre32 >= 1.0)
+    # one-signed upstream gradient: with tags of order 1 a float32 sum of mixed-sign terms cannot meet an
+    # absolute 1e-7 where it cancels to ~0, whatever the kernel; the clamp decisions are what is under test here
+    g = np.abs(W.normal(3, B * syms.size)).astype(np.float32).reshape(B, -1)
+    ga, gb = torch.empty_like(da.prob), torch.empty_like(db.prob)
+    dol.backward(dol.OpRecord(dol.OP_APPLY2, da, db, do, f=f), dev(g), ga, gb)
+    wa, wb = oracle.damp_apply2_bwd(tri, na, nb, a, b, g)
+    assert_close(host(ga), wa, "sum bwd a")
+    assert_close(host(gb), wb, "sum bwd b")
+    dol.backward(dol.OpRecord(dol.OP_APPLY2, da, db, do, f=f, accumulate=3), dev(g), ga, gb)
+    assert_close(host(ga), 2.0 * wa.astype(np.float64), "sum bwd a accumulated")
+    assert_close(host(gb), 2.0 * wb.astype(np.float64), "sum bwd b accumulated")
+    dol.backward(dol.OpRecord(dol.OP_APPLY2, da, db, do, f=f), dev(g), None, gb)      # one side only
+    assert_close(host(gb), wb, "sum bwd b alone")
 
 
 def test_union_and_filter_edge_cases(dol):
