@@ -1,13 +1,17 @@
-// DAMP apply2 for convolution-shaped function tables (f(i, j) lands in column i + j, every tuple admitted:
-// the SumN program of Fig. 2) with a short second operand (nb <= 16).
+// DAMP apply2 for convolution-shaped function tables (tuple (i, j) lands in column i + j, every tuple
+// admitted: the SumN program of Fig. 2) with a short second operand (nb <= 16):
+//     out[c] = min(1, sum_j a[c-j] * b[j]),
+//     ga[i]  = sum_j gh[i+j] * b[j],   gb[j] = sum_i gh[i+j] * a[i],   gh = g * [pre <= 1].
 //
-// One wavefront owns one sample at a time.  The long operand row is staged in LDS with a zero halo, the
-// short row sits in uniform registers, and lane c accumulates out[c] = sum_j a[c-j] * b[j] from LDS reads
-// at immediate offsets (conflict-free: consecutive lanes, consecutive words).  Workgroups are single
-// wavefronts, so the barriers that order LDS writes and reads cost nothing.  Summation runs over ascending
-// i (descending j), one fma per tuple, which is the order the operator's contract fixes; halo and padding
-// terms are exact no-ops.  While a sample is being computed the next one's rows are already in flight
-// (register prefetch), which is what keeps HBM busy with one-wave workgroups.
+// Tile kernels (contiguous rows, first operand up to 192 symbols): 32 lanes own a sample, a wavefront two,
+// a workgroup of 256 threads a tile of 8 or 16 samples.  The lanes first issue every load of their samples'
+// rows (many KB in flight per workgroup), park the rows in LDS with a zero halo, and then slide over them:
+// lane c reads a[c-9..c] at immediate offsets (conflict-free, rows are spaced so that the two samples of a
+// wavefront hit different banks) while the sample's short row sits in registers.  Nothing crosses
+// wavefronts, so the tile loop has no workgroup barrier.  Summation runs over ascending i (descending j), one fma per tuple,
+// which is the order the operator's contract fixes; halo and padding terms are exact no-ops.
+//
+// Loop kernels (any leading dimension, rows up to 6000, batch remainders): one wavefront per sample.
 #include "internal.h"
 
 namespace dol {
@@ -15,9 +19,18 @@ namespace dol {
 constexpr int kWave = 64;
 constexpr int kConvMaxNb = 16;
 constexpr int kConvMaxRow = 6000;       // longest first operand (backward keeps two rows, 48 KB of LDS)
-constexpr int kConvMaxP = 4;            // rows up to 64 * kConvMaxP take the register-prefetch kernels
+
+constexpr int kWG = 256;                // tile kernels: threads per workgroup
+constexpr int kTC = 32;                 // lanes per sample
+constexpr int kSlab = kWG / kTC;        // samples computed side by side
+constexpr int kTileMaxM = 192;          // longest first operand of the tile kernels
+constexpr int kPA = kTileMaxM / kTC;                                   // row pieces per lane: a
+constexpr int kPG = (kTileMaxM + kConvMaxNb - 1 + kTC - 1) / kTC;      // and g
 
 static int padded_nb(int nb) { return nb <= 4 ? 4 : nb <= 8 ? 8 : nb <= 10 ? 10 : 16; }
+
+// Smallest row stride >= n with stride % 64 == 32: the two samples of a wavefront then use disjoint banks.
+static int pad_row(int n) { return ((n + 31) / 64) * 64 + 32; }
 
 bool conv_path_ok(const dol_fn_table *f)
 {
@@ -27,16 +40,40 @@ bool conv_path_ok(const dol_fn_table *f)
 std::string damp_kernel_name(const dol_fn_table *f, bool backward)
 {
     if (!conv_path_ok(f)) return backward ? "damp_apply2_bwd_kernel" : "damp_apply2_fwd_kernel";
-    const int p = (f->na + kWave - 1) / kWave;
     char buf[96];
-    if (p <= kConvMaxP)
-        snprintf(buf, sizeof buf, "damp_conv_%s_kernel<%d, %d>", backward ? "bwd" : "fwd", padded_nb(f->nb), p);
-    else
-        snprintf(buf, sizeof buf, "damp_conv_%s_loop_kernel<%d>", backward ? "bwd" : "fwd", padded_nb(f->nb));
+    snprintf(buf, sizeof buf, "damp_conv_%s_%s_kernel<%d", backward ? "bwd" : "fwd",
+             f->na <= kTileMaxM ? "tile" : "loop", padded_nb(f->nb));   // a prefix: the tile size follows
     return buf;
 }
 
-static unsigned conv_grid(int32_t batch) { return static_cast<unsigned>(batch < 8192 ? batch : 8192); }
+// Samples per tile: 16 for large batches, 8 so that a small batch still covers the chip.
+static int tile_samples(int32_t batch) { return batch >= 16 * 1024 ? 16 : 8; }
+
+static unsigned loop_grid(int32_t batch) { return static_cast<unsigned>(batch < 8192 ? batch : 8192); }
+
+// ---------------------------------------------------------------- helpers
+
+template <int CTRL>
+__device__ __forceinline__ float dpp(float x)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xF, 0xF, false));
+}
+
+// All-reduce over the 32 lanes that share a sample (lanes 0-31 or 32-63 of a wavefront): quad butterflies,
+// mirrored halves of 8 and 16 lanes (every lane of a group already holds the group's value), then the
+// other row of 16.
+struct AddOp { __device__ static float f(float a, float b) { return a + b; } };
+struct MaxOp { __device__ static float f(float a, float b) { return fmaxf(a, b); } };
+template <typename Op>
+__device__ __forceinline__ float reduce32(float x)
+{
+    x = Op::f(x, dpp<0xB1>(x));          // quad_perm [1,0,3,2]
+    x = Op::f(x, dpp<0x4E>(x));          // quad_perm [2,3,0,1]
+    x = Op::f(x, dpp<0x141>(x));         // row_half_mirror
+    x = Op::f(x, dpp<0x140>(x));         // row_mirror
+    x = Op::f(x, __shfl_xor(x, 16, kWave));
+    return x;
+}
 
 __device__ __forceinline__ float wave_max(float x)
 {
@@ -45,62 +82,70 @@ __device__ __forceinline__ float wave_max(float x)
     return x;
 }
 
-// ---------------------------------------------------------------- forward, rows up to 64 * P
-
-template <int NBP, int P>
-__global__ void __launch_bounds__(kWave)
-damp_conv_fwd_kernel(int32_t batch, int32_t m, int32_t nb, const float *__restrict__ a, int64_t lda,
-                     const float *__restrict__ b, int64_t ldb, float *__restrict__ out, int64_t ldo)
+// A sample's LDS rows are written and read by the 32 lanes of one wavefront only, so program order within
+// the wavefront is all the ordering the tile kernels need: this keeps the compiler from moving LDS accesses
+// across the point and costs no instruction.
+__device__ __forceinline__ void wave_lds_fence()
 {
-    constexpr int H = NBP - 1, CAP = kWave * P;
-    __shared__ float lds[H + CAP + H];      // [H zeros][CAP values, zero beyond m][H zeros]
-    const int lane = threadIdx.x;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// ---------------------------------------------------------------- forward, tiles of 8 * U samples
+
+template <int NBP, int U>
+__global__ void __launch_bounds__(kWG)
+damp_conv_fwd_tile_kernel(int32_t n_tiles, int32_t m, int32_t nb, int32_t rs, const float *__restrict__ a,
+                          const float *__restrict__ b, float *__restrict__ out)
+{
+    extern __shared__ float lds[];          // TILE rows [H zeros][m][zeros to rs], then TILE rows of NBP
+    constexpr int H = NBP - 1, TILE = kSlab * U;
+    float *lds_b = lds + TILE * rs;
+    const int tid = threadIdx.x, tc = tid & (kTC - 1), ts = tid / kTC;
     const int S = m + nb - 1;
-    float *row = lds + H;
-    if (lane < H) { lds[lane] = 0.0f; row[CAP + lane] = 0.0f; }
-    int s = blockIdx.x;                     // the grid never exceeds the batch
-    float ca[P], cb[NBP];
-    {
-        const float *as = a + static_cast<int64_t>(s) * lda, *bs = b + static_cast<int64_t>(s) * ldb;
+    for (int e = tid; e < TILE * (rs + NBP); e += kWG) lds[e] = 0.0f;
+    __syncthreads();
+    for (int tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        const int64_t s0 = static_cast<int64_t>(tile) * TILE;
+        float va[U][kPA], vb[U];
 #pragma unroll
-        for (int p = 0; p < P; ++p) { const int i = lane + kWave * p; ca[p] = i < m ? as[i] : 0.0f; }
+        for (int u = 0; u < U; ++u) {
+            const float *ar = a + (s0 + ts + kSlab * u) * m;
 #pragma unroll
-        for (int j = 0; j < NBP; ++j) cb[j] = j < nb ? bs[j] : 0.0f;
-    }
-    for (;;) {
-#pragma unroll
-        for (int p = 0; p < P; ++p) row[lane + kWave * p] = ca[p];
-        const int sn = s + gridDim.x;
-        const bool more = sn < batch;
-        float bj[NBP];
-#pragma unroll
-        for (int j = 0; j < NBP; ++j) bj[j] = cb[j];
-        if (more) {                         // next sample's rows travel while this one is computed
-            const float *as = a + static_cast<int64_t>(sn) * lda, *bs = b + static_cast<int64_t>(sn) * ldb;
-#pragma unroll
-            for (int p = 0; p < P; ++p) { const int i = lane + kWave * p; ca[p] = i < m ? as[i] : 0.0f; }
-#pragma unroll
-            for (int j = 0; j < NBP; ++j) cb[j] = j < nb ? bs[j] : 0.0f;
+            for (int p = 0; p < kPA; ++p)
+                if (tc + kTC * p < m) va[u][p] = ar[tc + kTC * p];
+            if (tc < nb) vb[u] = b[(s0 + ts + kSlab * u) * nb + tc];
         }
-        __syncthreads();
-        float *os = out + static_cast<int64_t>(s) * ldo;
 #pragma unroll
-        for (int p = 0; p <= P; ++p) {
-            const int c = lane + kWave * p;
-            if (c < S) {
+        for (int u = 0; u < U; ++u) {
+            float *row = lds + (ts + kSlab * u) * rs + H;
+#pragma unroll
+            for (int p = 0; p < kPA; ++p)
+                if (tc + kTC * p < m) row[tc + kTC * p] = va[u][p];
+            if (tc < nb) lds_b[(ts + kSlab * u) * NBP + tc] = vb[u];
+        }
+        wave_lds_fence();
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int sl = ts + kSlab * u;
+            const float *row = lds + sl * rs + H;
+            float bj[NBP];
+#pragma unroll
+            for (int j = 0; j < NBP; ++j) bj[j] = lds_b[sl * NBP + j];
+            float *os = out + (s0 + sl) * S;
+            for (int c = tc; c < S; c += kTC) {
                 float acc = 0.0f;
 #pragma unroll
                 for (int j = NBP - 1; j >= 0; --j) acc = __builtin_fmaf(row[c - j], bj[j], acc);
                 os[c] = fminf(acc, 1.0f);
             }
         }
-        __syncthreads();
-        if (!more) break;
-        s = sn;
+        wave_lds_fence();
     }
 }
 
-// ---------------------------------------------------------------- forward, any row length
+// ---------------------------------------------------------------- forward, one wavefront per sample
 
 template <int NBP>
 __global__ void __launch_bounds__(kWave)
@@ -136,22 +181,27 @@ template <int NBP>
 static void launch_fwd_nbp(const dol_fn_table *f, int32_t batch, const float *a, int64_t lda, const float *b,
                            int64_t ldb, float *out, int64_t ldo, hipStream_t st)
 {
-    const dim3 grid(conv_grid(batch)), block(kWave);
-    const int p = (f->na + kWave - 1) / kWave;
-#define DOL_FWD(PP) \
-    hipLaunchKernelGGL((damp_conv_fwd_kernel<NBP, PP>), grid, block, 0, st, batch, f->na, f->nb, a, lda, b, ldb, out, ldo)
-    switch (p) {
-    case 1: DOL_FWD(1); break;
-    case 2: DOL_FWD(2); break;
-    case 3: DOL_FWD(3); break;
-    case 4: DOL_FWD(4); break;
-    default: {
-        const size_t lds = sizeof(float) * static_cast<size_t>(f->na + 2 * (NBP - 1));
-        hipLaunchKernelGGL(damp_conv_fwd_loop_kernel<NBP>, grid, block, lds, st, batch, f->na, f->nb, a, lda, b, ldb,
-                           out, ldo);
+    const int m = f->na, nb = f->nb, S = m + nb - 1;
+    int32_t done = 0;
+    const int tile_s = tile_samples(batch);
+    if (m <= kTileMaxM && batch >= tile_s && lda == m && ldb == nb && ldo == S) {
+        const int n_tiles = batch / tile_s;
+        const int rs = pad_row(m + 2 * (NBP - 1));
+        const size_t lds = sizeof(float) * static_cast<size_t>(tile_s) * (rs + NBP);
+        const unsigned grid = static_cast<unsigned>(n_tiles < 4096 ? n_tiles : 4096);
+        if (tile_s == 16)
+            hipLaunchKernelGGL((damp_conv_fwd_tile_kernel<NBP, 2>), dim3(grid), dim3(kWG), lds, st, n_tiles, m, nb, rs,
+                               a, b, out);
+        else
+            hipLaunchKernelGGL((damp_conv_fwd_tile_kernel<NBP, 1>), dim3(grid), dim3(kWG), lds, st, n_tiles, m, nb, rs,
+                               a, b, out);
+        done = n_tiles * tile_s;
     }
+    if (done < batch) {
+        const size_t lds = sizeof(float) * static_cast<size_t>(m + 2 * (NBP - 1));
+        hipLaunchKernelGGL(damp_conv_fwd_loop_kernel<NBP>, dim3(loop_grid(batch - done)), dim3(kWave), lds, st,
+                           batch - done, m, nb, a + done * lda, lda, b + done * ldb, ldb, out + done * ldo, ldo);
     }
-#undef DOL_FWD
 }
 
 dol_status launch_damp_conv_fwd(const dol_fn_table *f, int32_t batch, const float *a, int64_t lda, const float *b,
@@ -170,115 +220,106 @@ dol_status launch_damp_conv_fwd(const dol_fn_table *f, int32_t batch, const floa
 
 // ---------------------------------------------------------------- backward
 //
-// ga[i] = sum_j gh[i+j] * b[j],  gb[j] = sum_i gh[i+j] * a[i],  gh = g gated by the clamp decision [pre <= 1].
-// The decision needs pre only where it can exceed 1: pre[c] <= max(a) * sum(b) for non-negative tags, so a
-// sample whose bound stays below 1 passes g through; the others recompute pre in the forward kernel's order.
-// gb: lane (j, q) sums chunk q of the i range for its j, the Q partial sums meet in LDS.
+// The clamp decision needs pre only where it can exceed 1: pre[c] <= max(a) * sum(b) for non-negative tags,
+// so a sample whose bound stays below 1 passes g through; the others recompute pre in the forward order.
 
-template <int NBP>
-__device__ __forceinline__ void conv_bwd_body(int lane, int m, int nb, int S, float *row_a, float *row_g, float *part,
-                                              const float (&bj)[NBP], float amax, float *gas, float *gbs,
-                                              int32_t accumulate, int n_pass_a)
+template <int NBP, int U>
+__global__ void __launch_bounds__(kWG)
+damp_conv_bwd_tile_kernel(int32_t n_tiles, int32_t m, int32_t nb, int32_t rs_a, int32_t rs_g,
+                          const float *__restrict__ a, const float *__restrict__ b, const float *__restrict__ g,
+                          float *__restrict__ ga, float *__restrict__ gb, int32_t accumulate)
 {
-    constexpr int Q = kWave / NBP;
-    float sum_b = 0.0f;
+    extern __shared__ float lds[];          // a rows (halo on both sides), g rows (zero tail), b rows of NBP
+    constexpr int H = NBP - 1, TILE = kSlab * U;
+    float *lds_g = lds + TILE * rs_a;
+    float *lds_b = lds_g + TILE * rs_g;
+    const int tid = threadIdx.x, tc = tid & (kTC - 1), ts = tid / kTC;
+    const int S = m + nb - 1;
+    for (int e = tid; e < TILE * (rs_a + rs_g + NBP); e += kWG) lds[e] = 0.0f;
+    __syncthreads();
+    for (int tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        const int64_t s0 = static_cast<int64_t>(tile) * TILE;
+        float va[U][kPA], vg[U][kPG], vb[U];
 #pragma unroll
-    for (int j = 0; j < NBP; ++j) sum_b += bj[j];
-    if (!(amax * sum_b <= 0.9999f)) {        // uniform: some column of this sample may have been clamped
-        for (int c = lane; c < S; c += kWave) {
-            float pre = 0.0f;
+        for (int u = 0; u < U; ++u) {
+            const float *ar = a + (s0 + ts + kSlab * u) * m;
+            const float *gr = g + (s0 + ts + kSlab * u) * S;
 #pragma unroll
-            for (int j = NBP - 1; j >= 0; --j) pre = __builtin_fmaf(row_a[c - j], bj[j], pre);
-            if (!(pre <= 1.0f)) row_g[c] = 0.0f;
+            for (int p = 0; p < kPA; ++p)
+                if (tc + kTC * p < m) va[u][p] = ar[tc + kTC * p];
+#pragma unroll
+            for (int p = 0; p < kPG; ++p)
+                if (tc + kTC * p < S) vg[u][p] = gr[tc + kTC * p];
+            if (tc < nb) vb[u] = b[(s0 + ts + kSlab * u) * nb + tc];
         }
-        __syncthreads();
-    }
-    if (gas) {
-        for (int p = 0; p < n_pass_a; ++p) {
-            const int i = lane + kWave * p;
-            if (i < m) {
-                float acc = 0.0f;
 #pragma unroll
-                for (int j = 0; j < NBP; ++j) acc = __builtin_fmaf(row_g[i + j], bj[j], acc);
-                gas[i] = (accumulate & 1) ? gas[i] + acc : acc;
+        for (int u = 0; u < U; ++u) {
+            float *row_a = lds + (ts + kSlab * u) * rs_a + H;
+            float *row_g = lds_g + (ts + kSlab * u) * rs_g;
+#pragma unroll
+            for (int p = 0; p < kPA; ++p)
+                if (tc + kTC * p < m) row_a[tc + kTC * p] = va[u][p];
+#pragma unroll
+            for (int p = 0; p < kPG; ++p)
+                if (tc + kTC * p < S) row_g[tc + kTC * p] = vg[u][p];
+            if (tc < nb) lds_b[(ts + kSlab * u) * NBP + tc] = vb[u];
+        }
+        wave_lds_fence();
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int sl = ts + kSlab * u;
+            const float *row_a = lds + sl * rs_a + H;
+            float *row_g = lds_g + sl * rs_g;
+            float bj[NBP];
+            float sum_b = 0.0f;
+#pragma unroll
+            for (int j = 0; j < NBP; ++j) { bj[j] = lds_b[sl * NBP + j]; sum_b += bj[j]; }
+            float amax = 0.0f;
+#pragma unroll
+            for (int p = 0; p < kPA; ++p)
+                if (tc + kTC * p < m) amax = fmaxf(amax, va[u][p]);
+            amax = reduce32<MaxOp>(amax);
+            if (!(amax * sum_b <= 0.9999f)) {    // some column of this sample may have been clamped
+                for (int c = tc; c < S; c += kTC) {
+                    float pre = 0.0f;
+#pragma unroll
+                    for (int j = NBP - 1; j >= 0; --j) pre = __builtin_fmaf(row_a[c - j], bj[j], pre);
+                    if (!(pre <= 1.0f)) row_g[c] = 0.0f;
+                }
+                wave_lds_fence();
+            }
+            float pj[NBP];
+#pragma unroll
+            for (int j = 0; j < NBP; ++j) pj[j] = 0.0f;
+            float *gas = ga ? ga + (s0 + sl) * m : nullptr;
+            for (int i = tc; i < m; i += kTC) {
+                float gv[NBP];
+#pragma unroll
+                for (int j = 0; j < NBP; ++j) gv[j] = row_g[i + j];
+                if (gas) {
+                    float acc = 0.0f;
+#pragma unroll
+                    for (int j = 0; j < NBP; ++j) acc = __builtin_fmaf(gv[j], bj[j], acc);
+                    gas[i] = (accumulate & 1) ? gas[i] + acc : acc;
+                }
+                const float ai = row_a[i];
+#pragma unroll
+                for (int j = 0; j < NBP; ++j) pj[j] = __builtin_fmaf(gv[j], ai, pj[j]);
+            }
+            if (gb) {
+                float mine = 0.0f;
+#pragma unroll
+                for (int j = 0; j < NBP; ++j) {
+                    const float tot = reduce32<AddOp>(pj[j]);
+                    if (tc == j) mine = tot;
+                }
+                if (tc < nb) {
+                    float *dst = gb + (s0 + sl) * nb + tc;
+                    *dst = (accumulate & 2) ? *dst + mine : mine;
+                }
             }
         }
-    }
-    if (gbs) {
-        const int jq = lane % NBP, q = lane / NBP;
-        const int chunk = (m + Q - 1) / Q;
-        if (q < Q) {
-            float acc = 0.0f;
-            const int i1 = min(m, (q + 1) * chunk);
-            for (int i = q * chunk; i < i1; ++i) acc = __builtin_fmaf(row_g[i + jq], row_a[i], acc);
-            part[lane] = acc;
-        }
-        __syncthreads();
-        if (lane < nb) {
-            float tot = 0.0f;
-#pragma unroll
-            for (int x = 0; x < Q; ++x) tot += part[x * NBP + lane];
-            gbs[lane] = (accumulate & 2) ? gbs[lane] + tot : tot;
-        }
-    }
-}
-
-template <int NBP, int P>
-__global__ void __launch_bounds__(kWave)
-damp_conv_bwd_kernel(int32_t batch, int32_t m, int32_t nb, const float *__restrict__ a, int64_t lda,
-                     const float *__restrict__ b, int64_t ldb, const float *__restrict__ g, int64_t ldg,
-                     float *__restrict__ ga, float *__restrict__ gb, int32_t accumulate)
-{
-    constexpr int H = NBP - 1, CAP = kWave * P, CAPG = kWave * (P + 1);
-    __shared__ float lds[H + CAP + H + CAPG + NBP + kWave];
-    const int lane = threadIdx.x;
-    const int S = m + nb - 1;
-    float *row_a = lds + H;                 // [H zeros][CAP, zero beyond m][H zeros]
-    float *row_g = lds + H + CAP + H;       // [CAPG, zero beyond S][NBP zeros]
-    float *part = row_g + CAPG + NBP;
-    if (lane < H) { lds[lane] = 0.0f; row_a[CAP + lane] = 0.0f; }
-    if (lane < NBP) row_g[CAPG + lane] = 0.0f;
-    int s = blockIdx.x;
-    float ca[P], cg[P + 1], cb[NBP];
-    {
-        const float *as = a + static_cast<int64_t>(s) * lda, *bs = b + static_cast<int64_t>(s) * ldb;
-        const float *gs = g + static_cast<int64_t>(s) * ldg;
-#pragma unroll
-        for (int p = 0; p < P; ++p) { const int i = lane + kWave * p; ca[p] = i < m ? as[i] : 0.0f; }
-#pragma unroll
-        for (int p = 0; p <= P; ++p) { const int c = lane + kWave * p; cg[p] = c < S ? gs[c] : 0.0f; }
-#pragma unroll
-        for (int j = 0; j < NBP; ++j) cb[j] = j < nb ? bs[j] : 0.0f;
-    }
-    for (;;) {
-        float amax = 0.0f;
-#pragma unroll
-        for (int p = 0; p < P; ++p) { row_a[lane + kWave * p] = ca[p]; amax = fmaxf(amax, ca[p]); }
-#pragma unroll
-        for (int p = 0; p <= P; ++p) row_g[lane + kWave * p] = cg[p];
-        float bj[NBP];
-#pragma unroll
-        for (int j = 0; j < NBP; ++j) bj[j] = cb[j];
-        const int sn = s + gridDim.x;
-        const bool more = sn < batch;
-        if (more) {
-            const float *as = a + static_cast<int64_t>(sn) * lda, *bs = b + static_cast<int64_t>(sn) * ldb;
-            const float *gs = g + static_cast<int64_t>(sn) * ldg;
-#pragma unroll
-            for (int p = 0; p < P; ++p) { const int i = lane + kWave * p; ca[p] = i < m ? as[i] : 0.0f; }
-#pragma unroll
-            for (int p = 0; p <= P; ++p) { const int c = lane + kWave * p; cg[p] = c < S ? gs[c] : 0.0f; }
-#pragma unroll
-            for (int j = 0; j < NBP; ++j) cb[j] = j < nb ? bs[j] : 0.0f;
-        }
-        amax = wave_max(amax);
-        __syncthreads();
-        conv_bwd_body<NBP>(lane, m, nb, S, row_a, row_g, part, bj, amax,
-                           ga ? ga + static_cast<int64_t>(s) * lda : nullptr,
-                           gb ? gb + static_cast<int64_t>(s) * ldb : nullptr, accumulate, P);
-        __syncthreads();
-        if (!more) break;
-        s = sn;
+        wave_lds_fence();
     }
 }
 
@@ -290,6 +331,7 @@ damp_conv_bwd_loop_kernel(int32_t batch, int32_t m, int32_t nb, const float *__r
 {
     extern __shared__ float lds[];          // [H zeros][m: a][H zeros] [S: g][NBP zeros] [64: partial sums]
     constexpr int H = NBP - 1;
+    constexpr int Q = kWave / NBP;          // chunks of the gb reduction: lane (j, q) sums chunk q for its j
     const int lane = threadIdx.x;
     const int S = m + nb - 1;
     float *row_a = lds + H;
@@ -297,22 +339,55 @@ damp_conv_bwd_loop_kernel(int32_t batch, int32_t m, int32_t nb, const float *__r
     float *part = row_g + S + NBP;
     if (lane < H) { lds[lane] = 0.0f; row_a[m + lane] = 0.0f; }
     if (lane < NBP) row_g[S + lane] = 0.0f;
-    const int n_pass_a = (m + kWave - 1) / kWave;
+    const int jq = lane % NBP, q = lane / NBP;
+    const int chunk = (m + Q - 1) / Q;
     for (int s = blockIdx.x; s < batch; s += gridDim.x) {
         const float *as = a + static_cast<int64_t>(s) * lda;
         const float *bs = b + static_cast<int64_t>(s) * ldb;
         const float *gs = g + static_cast<int64_t>(s) * ldg;
         float bj[NBP];
+        float sum_b = 0.0f;
 #pragma unroll
-        for (int j = 0; j < NBP; ++j) bj[j] = j < nb ? bs[j] : 0.0f;
+        for (int j = 0; j < NBP; ++j) { bj[j] = j < nb ? bs[j] : 0.0f; sum_b += bj[j]; }
         float amax = 0.0f;
         for (int i = lane; i < m; i += kWave) { const float v = as[i]; row_a[i] = v; amax = fmaxf(amax, v); }
         for (int c = lane; c < S; c += kWave) row_g[c] = gs[c];
         amax = wave_max(amax);
         __syncthreads();
-        conv_bwd_body<NBP>(lane, m, nb, S, row_a, row_g, part, bj, amax,
-                           ga ? ga + static_cast<int64_t>(s) * lda : nullptr,
-                           gb ? gb + static_cast<int64_t>(s) * ldb : nullptr, accumulate, n_pass_a);
+        if (!(amax * sum_b <= 0.9999f)) {    // uniform: some column of this sample may have been clamped
+            for (int c = lane; c < S; c += kWave) {
+                float pre = 0.0f;
+#pragma unroll
+                for (int j = NBP - 1; j >= 0; --j) pre = __builtin_fmaf(row_a[c - j], bj[j], pre);
+                if (!(pre <= 1.0f)) row_g[c] = 0.0f;
+            }
+            __syncthreads();
+        }
+        if (ga) {
+            float *gas = ga + static_cast<int64_t>(s) * lda;
+            for (int i = lane; i < m; i += kWave) {
+                float acc = 0.0f;
+#pragma unroll
+                for (int j = 0; j < NBP; ++j) acc = __builtin_fmaf(row_g[i + j], bj[j], acc);
+                gas[i] = (accumulate & 1) ? gas[i] + acc : acc;
+            }
+        }
+        if (gb) {
+            if (q < Q) {
+                float acc = 0.0f;
+                const int i1 = min(m, (q + 1) * chunk);
+                for (int i = q * chunk; i < i1; ++i) acc = __builtin_fmaf(row_g[i + jq], row_a[i], acc);
+                part[lane] = acc;
+            }
+            __syncthreads();
+            if (lane < nb) {
+                float tot = 0.0f;
+#pragma unroll
+                for (int x = 0; x < Q; ++x) tot += part[x * NBP + lane];
+                float *gbs = gb + static_cast<int64_t>(s) * ldb;
+                gbs[lane] = (accumulate & 2) ? gbs[lane] + tot : tot;
+            }
+        }
         __syncthreads();
     }
 }
@@ -322,24 +397,28 @@ static void launch_bwd_nbp(const dol_fn_table *f, int32_t batch, const float *a,
                            int64_t ldb, const float *g, int64_t ldg, float *ga, float *gb, int32_t accumulate,
                            hipStream_t st)
 {
-    const dim3 grid(conv_grid(batch)), block(kWave);
-    const int p = (f->na + kWave - 1) / kWave;
-#define DOL_BWD(PP)                                                                                               \
-    hipLaunchKernelGGL((damp_conv_bwd_kernel<NBP, PP>), grid, block, 0, st, batch, f->na, f->nb, a, lda, b, ldb, g, \
-                       ldg, ga, gb, accumulate)
-    switch (p) {
-    case 1: DOL_BWD(1); break;
-    case 2: DOL_BWD(2); break;
-    case 3: DOL_BWD(3); break;
-    case 4: DOL_BWD(4); break;
-    default: {
-        const int S = f->na + f->nb - 1;
-        const size_t lds = sizeof(float) * static_cast<size_t>(f->na + 2 * (NBP - 1) + S + NBP + kWave);
-        hipLaunchKernelGGL(damp_conv_bwd_loop_kernel<NBP>, grid, block, lds, st, batch, f->na, f->nb, a, lda, b, ldb,
-                           g, ldg, ga, gb, accumulate);
+    const int m = f->na, nb = f->nb, S = m + nb - 1;
+    int32_t done = 0;
+    const int tile_s = tile_samples(batch);
+    if (m <= kTileMaxM && batch >= tile_s && lda == m && ldb == nb && ldg == S) {
+        const int n_tiles = batch / tile_s;
+        const int rs_a = pad_row(m + 2 * (NBP - 1)), rs_g = pad_row(S + NBP);
+        const size_t lds = sizeof(float) * static_cast<size_t>(tile_s) * (rs_a + rs_g + NBP);
+        const unsigned grid = static_cast<unsigned>(n_tiles < 4096 ? n_tiles : 4096);
+        if (tile_s == 16)
+            hipLaunchKernelGGL((damp_conv_bwd_tile_kernel<NBP, 2>), dim3(grid), dim3(kWG), lds, st, n_tiles, m, nb, rs_a,
+                               rs_g, a, b, g, ga, gb, accumulate);
+        else
+            hipLaunchKernelGGL((damp_conv_bwd_tile_kernel<NBP, 1>), dim3(grid), dim3(kWG), lds, st, n_tiles, m, nb, rs_a,
+                               rs_g, a, b, g, ga, gb, accumulate);
+        done = n_tiles * tile_s;
     }
+    if (done < batch) {
+        const size_t lds = sizeof(float) * static_cast<size_t>(m + 2 * (NBP - 1) + S + NBP + kWave);
+        hipLaunchKernelGGL(damp_conv_bwd_loop_kernel<NBP>, dim3(loop_grid(batch - done)), dim3(kWave), lds, st,
+                           batch - done, m, nb, a + done * lda, lda, b + done * ldb, ldb, g + done * ldg, ldg,
+                           ga ? ga + done * lda : nullptr, gb ? gb + done * ldb : nullptr, accumulate);
     }
-#undef DOL_BWD
 }
 
 dol_status launch_damp_conv_bwd(const dol_fn_table *f, int32_t batch, const float *a, int64_t lda, const float *b,
