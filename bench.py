@@ -22,6 +22,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+FP32_PEAK_TFLOPS = 157.3       # MI355X fp32 vector, published (256 CUs x 2.4 GHz x 128 lanes x 2 flop)
 SCALED_BATCH = {1: 1 << 22, 2: 1 << 19, 3: 1 << 18, 4: 1 << 18, 5: 1 << 13}
 
 
@@ -78,10 +79,15 @@ def roofline_of(per_kernel):
     name = max(per_kernel, key=lambda k: per_kernel[k]["ms"])
     k = per_kernel[name]
     avg_ms = k["ms"] / k["launches"]
-    achieved = (k["bytes"] / k["launches"]) / (avg_ms * 1e-3) / 1e9
-    return dict(bound="hbm", kernel=name, achieved=round(achieved, 2), peak=HBM_PEAK_GBS, unit="GB/s",
-                frac=round(achieved / HBM_PEAK_GBS, 4), traffic=None, launches_per_step=k["launches"],
+    gbs = (k["bytes"] / k["launches"]) / (avg_ms * 1e-3) / 1e9
+    tflops = 2.0 * (k["macs"] / k["launches"]) / (avg_ms * 1e-3) / 1e12
+    # the bound is the roof the kernel's algorithmic intensity puts it under
+    alu = 2.0 * k["macs"] / max(k["bytes"], 1) > FP32_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9)
+    achieved, peak, unit = (tflops, FP32_PEAK_TFLOPS, "TFLOP/s") if alu else (gbs, HBM_PEAK_GBS, "GB/s")
+    return dict(bound="alu" if alu else "hbm", kernel=name, achieved=round(achieved, 3), peak=peak, unit=unit,
+                frac=round(achieved / peak, 4), traffic=None, launches_per_step=k["launches"],
                 avg_launch_us=round(avg_ms * 1e3, 3), bytes_per_launch=k["bytes"] // k["launches"],
+                flop_per_launch=2 * k["macs"] // k["launches"], algorithmic_gbs=round(gbs, 1),
                 share_of_step=round(k["ms"] / sum(v["ms"] for v in per_kernel.values()), 3))
 
 
@@ -119,6 +125,8 @@ def main():
     ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--batch", type=int, default=0, help="override the config's batch size")
     ap.add_argument("--mode", default="graph", choices=["graph", "eager"])
+    ap.add_argument("--chain", default="fused", choices=["fused", "per-op"],
+                    help="config 2: one dol_fold_apply2 launch, or one dol_apply2 / dol_backward call per operator")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--repeats", type=int, default=20, help="back-to-back launches per event pair in the roofline pass")
     ap.add_argument("--scaled-batch", type=int, default=-1, help="batch of the B-scaled variant (0 = skip)")
@@ -140,7 +148,10 @@ def main():
     if args.batch:
         kw["batch"] = args.batch
     w = W.make_config(cfg, **kw)
-    prog = GP.make_program(cfg, w)
+
+    def build(wl):
+        return GP.SumChainFused(wl) if cfg == 2 and args.chain == "fused" else GP.make_program(cfg, wl)
+    prog = build(w)
     ms = time_step(prog, torch, args.steps, args.warmup, args.mode)
     per_kernel = time_launches(prog, torch, args.repeats)
     roof = roofline_of(per_kernel)
@@ -154,6 +165,7 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": w.name, "config_id": cfg, "batch": prog.batch, "sample_ops_per_step": prog.sample_ops,
                    "launches_per_step": len(prog.launches), "mode": args.mode, "seed": args.seed,
+                   "chain": args.chain if cfg == 2 else None,
                    "algorithmic_bytes_per_step": prog.algorithmic_bytes()},
         "roofline": roof,
         "kernels": kernel_table(per_kernel),
@@ -165,7 +177,7 @@ def main():
         torch.cuda.empty_cache()
         kw["batch"] = sb
         ws = W.make_config(cfg, **kw)
-        ps = GP.make_program(cfg, ws)
+        ps = build(ws)
         ms_s = time_step(ps, torch, 3, 1, "eager")
         pk = time_launches(ps, torch, 3)
         rs = roofline_of(pk)

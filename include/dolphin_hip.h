@@ -149,6 +149,32 @@ typedef struct {
 dol_status dol_backward(const dol_op_record *rec, const float *grad_out, float *grad_a, float *grad_b,
                         void *hip_stream);
 
+/* A left fold of Apply under DAMP (the loop of Fig. 2: D_res = apply(D_res, D_i, f)), forward and backward in
+ * ONE launch: acc_1 = apply2(inputs[0], inputs[1], tables[0]), acc_t = apply2(acc_{t-1}, inputs[t], tables[t-1]).
+ * Results are the same as n_inputs-1 dol_apply2 calls followed by the reverse sweep of dol_backward calls
+ * (same summation order, same clamp decisions); the intermediate Distributions never leave the chip.
+ *   inputs      host array of n_inputs Distributions (any ld), equal batch
+ *   tables      host array of n_inputs-1 tables; tables[t-1] is (symbols of acc_{t-1}) x (symbols of inputs[t])
+ *   out         the last acc (forward result), prob written; may be NULL to skip the store
+ *   target_col  device [batch] int32 or NULL: if given, the upstream gradient is that of -log out[target_col]
+ *               (as dol_nll_grad); else grad_out (device [batch, out_ld]) is used; both NULL = forward only
+ *   grad_inputs host array of n_inputs device pointers, grad_inputs[t] is [batch, inputs[t]->ld], overwritten;
+ *               NULL entries are skipped; the array itself may be NULL when no backward is asked for
+ * Supported when every table is convolution-shaped (tuple (i, j) lands in column i + j, all tuples admitted:
+ * sums of integer-valued symbols), inputs[t >= 1] have at most 16 symbols, n_inputs <= 32 and the per-sample
+ * working set fits in LDS; otherwise DOL_EUNSUPPORTED and the caller composes dol_apply2 / dol_backward. */
+typedef struct {
+    int32_t n_inputs;
+    const dol_dist *const *inputs;
+    const dol_fn_table *const *tables;
+    dol_dist *out;
+    const int32_t *target_col;
+    const float *grad_out;
+    int64_t grad_out_ld;
+    float *const *grad_inputs;
+} dol_fold;
+dol_status dol_fold_apply2(const dol_fold *fold, void *hip_stream);
+
 /* Harness helper for loss = -log p[target] (Sec. 3.3 leaves the loss to the user): for every sample s,
  * grad[s, c] = -1 / max(d->prob[s, c], FLT_MIN) at c = target_col[s] and 0 elsewhere (all n_sym columns written).
  * target_col: device [batch] int32 column indices in 0..n_sym-1 (rows with an index outside get all zeros).

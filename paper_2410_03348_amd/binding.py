@@ -265,6 +265,44 @@ def backward(rec: OpRecord, grad_out: torch.Tensor, grad_a: Optional[torch.Tenso
     _check(_lib.dol_backward(C.byref(rec.c), _dptr(grad_out), _dptr(grad_a), _dptr(grad_b), _stream(stream)))
 
 
+class _Fold(C.Structure):
+    _fields_ = [("n_inputs", C.c_int32), ("inputs", C.POINTER(C.POINTER(_Dist))), ("tables", C.POINTER(C.c_void_p)),
+                ("out", C.POINTER(_Dist)), ("target_col", C.c_void_p), ("grad_out", C.c_void_p),
+                ("grad_out_ld", C.c_int64), ("grad_inputs", C.POINTER(C.c_void_p))]
+
+
+_lib.dol_fold_apply2.argtypes = [C.POINTER(_Fold), C.c_void_p]
+
+
+class Fold:
+    """dol_fold: a left fold of DAMP applies run forward (and backward) in one launch.  Keeps its operands alive."""
+
+    def __init__(self, inputs, tables, out: Optional[Dist] = None, target_col: Optional[torch.Tensor] = None,
+                 grad_out: Optional[torch.Tensor] = None, grad_inputs=None):
+        n = len(inputs)
+        assert len(tables) == n - 1
+        self.keep = (inputs, tables, out, target_col, grad_out, grad_inputs)
+        self._in = (C.POINTER(_Dist) * n)(*[C.pointer(d.c) for d in inputs])
+        self._tb = (C.c_void_p * max(n - 1, 1))(*[t._h for t in tables])
+        self._gi = None
+        if grad_inputs is not None:
+            assert len(grad_inputs) == n
+            self._gi = (C.c_void_p * n)(*[None if g is None else g.data_ptr() for g in grad_inputs])
+        if target_col is not None:
+            assert target_col.dtype == torch.int32 and target_col.is_contiguous()
+        ldg = 0
+        if grad_out is not None:
+            assert grad_out.dtype == torch.float32 and grad_out.dim() == 2 and grad_out.stride(1) == 1
+            ldg = max(int(grad_out.stride(0)), grad_out.shape[1])
+        self.c = _Fold(n, self._in, self._tb, C.pointer(out.c) if out is not None else None,
+                       _dptr(target_col), _dptr(grad_out), ldg,
+                       C.cast(self._gi, C.POINTER(C.c_void_p)) if self._gi is not None else None)
+
+
+def fold_apply2(fold: Fold, stream=None):
+    _check(_lib.dol_fold_apply2(C.byref(fold.c), _stream(stream)))
+
+
 def nll_grad(d: Dist, target_col: torch.Tensor, grad: torch.Tensor, stream=None):
     """target_col: int32 device tensor [batch]; grad rows have stride d.ld."""
     assert target_col.dtype == torch.int32 and target_col.is_contiguous()

@@ -13,10 +13,10 @@
 //
 // Loop kernels (any leading dimension, rows up to 6000, batch remainders): one wavefront per sample.
 #include "internal.h"
+#include "wave_util.h"
 
 namespace dol {
 
-constexpr int kWave = 64;
 constexpr int kConvMaxNb = 16;
 constexpr int kConvMaxRow = 6000;       // longest first operand (backward keeps two rows, 48 KB of LDS)
 
@@ -50,47 +50,6 @@ std::string damp_kernel_name(const dol_fn_table *f, bool backward)
 static int tile_samples(int32_t batch) { return batch >= 16 * 1024 ? 16 : 8; }
 
 static unsigned loop_grid(int32_t batch) { return static_cast<unsigned>(batch < 8192 ? batch : 8192); }
-
-// ---------------------------------------------------------------- helpers
-
-template <int CTRL>
-__device__ __forceinline__ float dpp(float x)
-{
-    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xF, 0xF, false));
-}
-
-// All-reduce over the 32 lanes that share a sample (lanes 0-31 or 32-63 of a wavefront): quad butterflies,
-// mirrored halves of 8 and 16 lanes (every lane of a group already holds the group's value), then the
-// other row of 16.
-struct AddOp { __device__ static float f(float a, float b) { return a + b; } };
-struct MaxOp { __device__ static float f(float a, float b) { return fmaxf(a, b); } };
-template <typename Op>
-__device__ __forceinline__ float reduce32(float x)
-{
-    x = Op::f(x, dpp<0xB1>(x));          // quad_perm [1,0,3,2]
-    x = Op::f(x, dpp<0x4E>(x));          // quad_perm [2,3,0,1]
-    x = Op::f(x, dpp<0x141>(x));         // row_half_mirror
-    x = Op::f(x, dpp<0x140>(x));         // row_mirror
-    x = Op::f(x, __shfl_xor(x, 16, kWave));
-    return x;
-}
-
-__device__ __forceinline__ float wave_max(float x)
-{
-#pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) x = fmaxf(x, __shfl_xor(x, d, kWave));
-    return x;
-}
-
-// A sample's LDS rows are written and read by the 32 lanes of one wavefront only, so program order within
-// the wavefront is all the ordering the tile kernels need: this keeps the compiler from moving LDS accesses
-// across the point and costs no instruction.
-__device__ __forceinline__ void wave_lds_fence()
-{
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
 
 // ---------------------------------------------------------------- forward, tiles of 8 * U samples
 

@@ -133,6 +133,33 @@ class SumChain(Program):
         self.sample_ops = 2 * (self.n - 1) * self.batch
 
 
+class SumChainFused(Program):
+    """Config 2 through dol_fold_apply2: the whole fold, the loss gradient and the reverse sweep in one launch."""
+
+    def __init__(self, w, device="cuda"):
+        p = w["p"]
+        self.n, self.batch = p.shape[0], p.shape[1]
+        sym = np.asarray(w["sym"], np.int32)
+        self.p_dev = _dev(p, device)
+        self.digits = [dol.Dist(sym, self.p_dev[t]) for t in range(self.n)]
+        self.tables, syms, macs = [], sym, 0
+        for t in range(1, self.n):
+            tab = sum_table_of(syms, sym)
+            tb = dol.FnTable.create_dense(tab)
+            self.tables.append(tb)
+            syms = tb.out_syms
+            macs += 3 * _n_tuples(tab)
+        self.out = dol.Dist.empty(syms, self.batch, device)
+        self.target = _dev(w["target"].astype(np.int32), device)
+        self.grad_p = torch.empty_like(self.p_dev)
+        self.fold = dol.Fold(self.digits, self.tables, out=self.out, target_col=self.target,
+                             grad_inputs=[self.grad_p[t] for t in range(self.n)])
+        n_in = sum(d.n_sym for d in self.digits)
+        self.launches = [Launch("damp_fold_kernel<10>", lambda: dol.fold_apply2(self.fold),
+                                4 * self.batch * (2 * n_in + self.out.n_sym + 1), self.batch * macs, "fwd")]
+        self.sample_ops = 2 * (self.n - 1) * self.batch
+
+
 class HashedPipeline(Program):
     """Config 3: apply with a hashed symbol table, filter by a keep-mask over the produced ids, union with a
     second Distribution over all ids; backward through all three."""

@@ -79,6 +79,68 @@ def test_config2_sum_chain(gp, batch, n):
     assert_close(host(prog.grad_p), ref["grad_p"], "chain grad")
 
 
+@pytest.mark.parametrize("batch,n", [(4096, 15), (301, 15), (37, 4), (1, 2), (64, 32)])
+def test_config2_fused_fold(gp, batch, n):
+    """dol_fold_apply2: the same results as the chain of per-operator calls, and as the oracle."""
+    w = W.config2(batch=batch, n_digits=n, seed=n + 100)
+    ref = OP.sum_chain_fwd_bwd(w)
+    prog = gp.SumChainFused(w)
+    prog.step()
+    np.testing.assert_array_equal(prog.out.sym_ids, ref["syms"])
+    assert_close(host(prog.out.prob), ref["out"], "fold forward")
+    assert_close(host(prog.grad_p), ref["grad_p"], "fold grad")
+    chain = gp.SumChain(w)
+    chain.step()
+    np.testing.assert_array_equal(host(prog.out.prob), host(chain.accs[-1].prob))    # same arithmetic, bit for bit
+
+
+def test_fused_fold_with_clamping_and_explicit_gradient(dol):
+    """Unnormalised tags drive several stages over 1; the fold must gate exactly like the per-operator path.
+    Also: explicit upstream gradient, padded leading dimensions, mixed operand widths, forward-only call."""
+    B, widths = 77, [7, 3, 10, 16, 2]
+    ins = [(W.uniform01(10 + t, B * n) * 0.9).astype(np.float32).reshape(B, n) for t, n in enumerate(widths)]
+    syms = [np.arange(n, dtype=np.int32) for n in widths]
+    tabs, tris, accs, cur = [], [], [ins[0]], syms[0]
+    for t in range(1, len(widths)):
+        tab = W.sum_table(cur, syms[t])
+        tri = oracle.dense_to_triples(tab)
+        cur, o = oracle.damp_apply2_fwd(tri, tab.shape[0], tab.shape[1], accs[-1], ins[t])
+        tabs.append(tab); tris.append(tri); accs.append(o)
+    assert (accs[-1] == 1.0).any() and (accs[2] == 1.0).any()
+    g = np.abs(W.normal(5, B * cur.size)).astype(np.float32).reshape(B, -1)
+    want, gr = [None] * len(widths), g
+    for t in range(len(widths) - 1, 0, -1):
+        gr, want[t] = oracle.damp_apply2_bwd(tris[t - 1], tabs[t - 1].shape[0], tabs[t - 1].shape[1], accs[t - 1], ins[t], gr)
+    want[0] = gr
+    pad = 3
+    d_in = []
+    for t, n in enumerate(widths):
+        buf = torch.zeros((B, n + pad), device="cuda")
+        buf[:, :n] = dev(ins[t])
+        d_in.append(dol.Dist(syms[t], buf[:, :n]))
+    ftabs = [dol.FnTable.create_dense(t) for t in tabs]
+    out = dol.Dist.empty(cur, B)
+    gbuf = torch.zeros((B, cur.size + 5), device="cuda")
+    gbuf[:, :cur.size] = dev(g)
+    gins = [torch.full((B, n + pad), 7.0, device="cuda") for n in widths]
+    gins[2] = None                                   # a skipped gradient
+    dol.fold_apply2(dol.Fold(d_in, ftabs, out=out, grad_out=gbuf[:, :cur.size], grad_inputs=gins))
+    assert_close(host(out.prob), accs[-1], "fold forward (clamped)")
+    np.testing.assert_array_equal(host(out.prob) == 1.0, accs[-1] == 1.0)
+    for t, n in enumerate(widths):
+        if gins[t] is None:
+            continue
+        assert_close(host(gins[t])[:, :n], want[t], "fold grad %d" % t)
+        assert np.all(host(gins[t])[:, n:] == 7.0)
+    out2 = dol.Dist.empty(cur, B)
+    dol.fold_apply2(dol.Fold(d_in, ftabs, out=out2))                  # forward only
+    np.testing.assert_array_equal(host(out2.prob), host(out.prob))
+    hashed = dol.FnTable.create_dense(W.hashed_table(1, 7, 3, 9))
+    with pytest.raises(dol.DolError) as ei:
+        dol.fold_apply2(dol.Fold(d_in[:2], [hashed], out=dol.Dist.empty(hashed.out_syms, B)))
+    assert ei.value.status == 5
+
+
 # ---------------------------------------------------------------- config 3
 
 @pytest.mark.parametrize("batch,na,nb,n_out", [(16384, 64, 64, 256), (1000, 64, 64, 256), (129, 17, 33, 40), (3, 5, 2, 300)])
