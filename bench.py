@@ -126,7 +126,8 @@ def main():
     ap.add_argument("--batch", type=int, default=0, help="override the config's batch size")
     ap.add_argument("--mode", default="graph", choices=["graph", "eager"])
     ap.add_argument("--chain", default="fused", choices=["fused", "per-op"],
-                    help="config 2: one dol_fold_apply2 launch, or one dol_apply2 / dol_backward call per operator")
+                    help="configs 2 and 5: the fused entry points (dol_fold_apply2, dol_iterate_*), or one dol_apply2 / "
+                         "dol_backward call per operator")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--repeats", type=int, default=20, help="back-to-back launches per event pair in the roofline pass")
     ap.add_argument("--scaled-batch", type=int, default=-1, help="batch of the B-scaled variant (0 = skip)")
@@ -150,7 +151,11 @@ def main():
     w = W.make_config(cfg, **kw)
 
     def build(wl):
-        return GP.SumChainFused(wl) if cfg == 2 and args.chain == "fused" else GP.make_program(cfg, wl)
+        if args.chain == "fused" and cfg == 2:
+            return GP.SumChainFused(wl)
+        if args.chain == "fused" and cfg == 5:
+            return GP.GridReachFused(wl)
+        return GP.make_program(cfg, wl)
     prog = build(w)
     ms = time_step(prog, torch, args.steps, args.warmup, args.mode)
     per_kernel = time_launches(prog, torch, args.repeats)
@@ -165,7 +170,7 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": w.name, "config_id": cfg, "batch": prog.batch, "sample_ops_per_step": prog.sample_ops,
                    "launches_per_step": len(prog.launches), "mode": args.mode, "seed": args.seed,
-                   "chain": args.chain if cfg == 2 else None,
+                   "chain": args.chain if cfg in (2, 5) else None,
                    "algorithmic_bytes_per_step": prog.algorithmic_bytes()},
         "roofline": roof,
         "kernels": kernel_table(per_kernel),

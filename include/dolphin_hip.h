@@ -175,6 +175,23 @@ typedef struct {
 } dol_fold;
 dol_status dol_fold_apply2(const dol_fold *fold, void *hip_stream);
 
+/* Repeated Apply with feedback under DAMP (the recursion of App. B, Fig. 9, run for a fixed number of rounds):
+ *     r_0 = r0,   r_{t+1} = apply2(r_t, e, f)   for t = 0 .. rounds-1,
+ * all rounds in ONE launch, one workgroup per sample with r_t in LDS.  The table must be square: it produces
+ * exactly the symbols of its first operand (n_out == na and out_syms == r0->sym_ids), so that a round's result
+ * can be the next round's first operand.  Results equal `rounds` dol_apply2 calls (same order, same clamps).
+ *   hist  device [rounds+1, batch, na], contiguous: receives r_0 .. r_rounds; r_rounds is the result and the
+ *         whole history is what dol_iterate_backward reads.
+ * dol_iterate_backward: grad_out device [batch, grad_out_ld] w.r.t. r_rounds;
+ *   grad_r0 device [batch, na] contiguous or NULL; grad_e device [batch, e->ld] or NULL: the gradient w.r.t. e
+ *   summed over the rounds.  Both overwritten.
+ * DOL_EUNSUPPORTED when the table is not square or the rows do not fit in LDS (na, nb up to a few thousand). */
+dol_status dol_iterate_apply2(const dol_dist *r0, const dol_dist *e, const dol_fn_table *f, int32_t rounds, float *hist,
+                              void *hip_stream);
+dol_status dol_iterate_backward(const dol_dist *e, const dol_fn_table *f, int32_t rounds, const float *hist,
+                                const float *grad_out, int64_t grad_out_ld, float *grad_r0, float *grad_e,
+                                void *hip_stream);
+
 /* Harness helper for loss = -log p[target] (Sec. 3.3 leaves the loss to the user): for every sample s,
  * grad[s, c] = -1 / max(d->prob[s, c], FLT_MIN) at c = target_col[s] and 0 elsewhere (all n_sym columns written).
  * target_col: device [batch] int32 column indices in 0..n_sym-1 (rows with an index outside get all zeros).

@@ -303,6 +303,28 @@ def fold_apply2(fold: Fold, stream=None):
     _check(_lib.dol_fold_apply2(C.byref(fold.c), _stream(stream)))
 
 
+_lib.dol_iterate_apply2.argtypes = [C.POINTER(_Dist), C.POINTER(_Dist), C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
+_lib.dol_iterate_backward.argtypes = [C.POINTER(_Dist), C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_int64,
+                                      C.c_void_p, C.c_void_p, C.c_void_p]
+
+
+def iterate_apply2(r0: Dist, e: Dist, f: FnTable, rounds: int, hist: torch.Tensor, stream=None):
+    """hist: float32 [rounds+1, batch, na] contiguous; receives r_0 .. r_rounds."""
+    assert hist.dtype == torch.float32 and hist.is_contiguous() and hist.shape == (rounds + 1, r0.batch, f.na)
+    _check(_lib.dol_iterate_apply2(r0.ref(), e.ref(), f._h, rounds, _dptr(hist), _stream(stream)))
+
+
+def iterate_backward(e: Dist, f: FnTable, rounds: int, hist: torch.Tensor, grad_out: torch.Tensor,
+                     grad_r0: Optional[torch.Tensor], grad_e: Optional[torch.Tensor], stream=None):
+    """grad_out rows: stride grad_out.stride(0); grad_r0 [batch, na] contiguous; grad_e rows have stride e.ld."""
+    assert hist.dtype == torch.float32 and hist.is_contiguous() and hist.shape == (rounds + 1, e.batch, f.na)
+    assert grad_out.dtype == torch.float32 and grad_out.stride(1) == 1
+    assert grad_r0 is None or grad_r0.is_contiguous()
+    _check(_lib.dol_iterate_backward(e.ref(), f._h, rounds, _dptr(hist), _dptr(grad_out),
+                                     max(int(grad_out.stride(0)), grad_out.shape[1]), _dptr(grad_r0), _dptr(grad_e),
+                                     _stream(stream)))
+
+
 def nll_grad(d: Dist, target_col: torch.Tensor, grad: torch.Tensor, stream=None):
     """target_col: int32 device tensor [batch]; grad rows have stride d.ld."""
     assert target_col.dtype == torch.int32 and target_col.is_contiguous()

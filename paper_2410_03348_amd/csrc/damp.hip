@@ -1,17 +1,55 @@
-// DAMP provenance kernels (Sec. 3.2, Table 1: conjunction t*t', disjunction min(1, t+t')) for gfx950.
+// DAMP provenance kernels (Sec. 3.2, Table 1: conjunction t*t', disjunction min(1, t+t')) for gfx950:
+// Apply with an arbitrary function table, Filter, Union and their vector-Jacobian products.
 //
 // Thread mapping: one thread per (sample, output element), consecutive lanes on consecutive elements of one
-// row, so that every store is coalesced and, for tables with regular structure (sums, grids), lane-adjacent
-// gathers touch adjacent addresses.  Rows are short (tens to a few thousand floats) and every operand row is
-// re-read only by the threads of the same wavefronts, so gathers are served from L1/L2; HBM sees each
-// operand once.
+// row, so that every store is coalesced and, for tables with regular structure (grids), lane-adjacent gathers
+// touch adjacent addresses.  A workgroup owns a chunk of whole rows (about 2048 elements) and splits its
+// flat element index into (row, column) with a float reciprocal, which is exact for such small indices.
+// Sum-shaped tables take the LDS kernels of damp_conv.hip instead.
 #include "internal.h"
+#include "wave_util.h"
 
 namespace dol {
 
 constexpr int kThreads = 256;
+constexpr int kChunk = 2048;            // elements per workgroup (whole rows)
 
-static inline unsigned grid_for(int64_t work) { return static_cast<unsigned>((work + kThreads - 1) / kThreads); }
+struct Rows {                           // how a [batch, n] element space is cut into workgroup chunks
+    int32_t batch, n, rpb;
+    float inv_n;
+    unsigned grid;
+};
+
+static Rows rows_of(int32_t batch, int32_t n)
+{
+    Rows r;
+    r.batch = batch;
+    r.n = n;
+    r.rpb = n >= kChunk ? 1 : kChunk / n;
+    r.inv_n = 1.0f / static_cast<float>(n);
+    r.grid = static_cast<unsigned>((static_cast<int64_t>(batch) + r.rpb - 1) / r.rpb);
+    return r;
+}
+
+// Calls f(sample, column) for every element of this workgroup's chunk.
+template <typename F>
+__device__ __forceinline__ void for_each_element(const Rows &R, F f)
+{
+    const int64_t s0 = static_cast<int64_t>(blockIdx.x) * R.rpb;
+    if (R.rpb == 1) {
+        for (int c = threadIdx.x; c < R.n; c += kThreads) f(s0, c);
+        return;
+    }
+    const int rows = static_cast<int>(min(static_cast<int64_t>(R.rpb), R.batch - s0));
+    const int total = rows * R.n;
+#pragma unroll 4
+    for (int e = threadIdx.x; e < total; e += kThreads) {
+        int r = static_cast<int>(static_cast<float>(e) * R.inv_n);
+        int c = e - r * R.n;
+        if (c < 0) { c += R.n; --r; } else if (c >= R.n) { c -= R.n; ++r; }
+        f(s0 + r, c);
+    }
+}
 
 // ---------------------------------------------------------------- apply2 forward
 
@@ -29,26 +67,24 @@ __device__ __forceinline__ float column_sum(const float *__restrict__ ar, const 
 }
 
 __global__ void __launch_bounds__(kThreads)
-damp_apply2_fwd_kernel(int64_t total, int32_t S, const uint32_t *__restrict__ col_ptr,
-                       const uint32_t *__restrict__ col_ij, const float *__restrict__ a, int64_t lda,
-                       const float *__restrict__ b, int64_t ldb, float *__restrict__ out, int64_t ldo)
+damp_apply2_fwd_kernel(Rows R, const uint32_t *__restrict__ col_ptr, const uint32_t *__restrict__ col_ij,
+                       const float *__restrict__ a, int64_t lda, const float *__restrict__ b, int64_t ldb,
+                       float *__restrict__ out, int64_t ldo)
 {
-    const int64_t idx = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
-    if (idx >= total) return;
-    const int64_t s = idx / S;
-    const int32_t c = static_cast<int32_t>(idx - s * S);
-    const float pre = column_sum(a + s * lda, b + s * ldb, col_ij, col_ptr[c], col_ptr[c + 1]);
-    out[s * ldo + c] = fminf(pre, 1.0f);
+    for_each_element(R, [&](int64_t s, int c) {
+        const float pre = column_sum(a + s * lda, b + s * ldb, col_ij, col_ptr[c], col_ptr[c + 1]);
+        out[s * ldo + c] = fminf(pre, 1.0f);
+    });
 }
 
 dol_status launch_damp_apply2_fwd(const dol_fn_table *f, int32_t batch, const float *a, int64_t lda, const float *b,
                                   int64_t ldb, float *out, int64_t ldo, hipStream_t st)
 {
-    const int64_t total = static_cast<int64_t>(batch) * f->n_out;
-    if (total == 0) return DOL_OK;
+    if (batch == 0 || f->n_out == 0) return DOL_OK;
     if (conv_path_ok(f)) return launch_damp_conv_fwd(f, batch, a, lda, b, ldb, out, ldo, st);
-    hipLaunchKernelGGL(damp_apply2_fwd_kernel, dim3(grid_for(total)), dim3(kThreads), 0, st, total, f->n_out,
-                       f->col_ptr.ptr, f->col_ij.ptr, a, lda, b, ldb, out, ldo);
+    const Rows R = rows_of(batch, f->n_out);
+    hipLaunchKernelGGL(damp_apply2_fwd_kernel, dim3(R.grid), dim3(kThreads), 0, st, R, f->col_ptr.ptr, f->col_ij.ptr, a,
+                       lda, b, ldb, out, ldo);
     DOL_HIP(hipGetLastError());
     return DOL_OK;
 }
@@ -70,38 +106,66 @@ __device__ __forceinline__ float gated_grad(const float *__restrict__ gr, const 
     return g;
 }
 
+struct BwdTable {
+    const uint32_t *col_ptr, *col_ij, *rowa_ptr, *rowa_jc, *rowb_ptr, *rowb_ic;
+    int32_t na, nb;
+};
+
+// Element x of a sample is position x of a (x < na) or x - na of b.  Rows of the table with more than
+// kLongTableRow tuples are left to damp_apply2_bwd_long_kernel.
 __global__ void __launch_bounds__(kThreads)
-damp_apply2_bwd_kernel(int64_t total, int32_t na, int32_t nb, const uint32_t *__restrict__ col_ptr,
-                       const uint32_t *__restrict__ col_ij, const uint32_t *__restrict__ rowa_ptr,
-                       const uint32_t *__restrict__ rowa_jc, const uint32_t *__restrict__ rowb_ptr,
-                       const uint32_t *__restrict__ rowb_ic, const float *__restrict__ a, int64_t lda,
-                       const float *__restrict__ b, int64_t ldb, const float *__restrict__ out, int64_t ldo,
-                       const float *__restrict__ g, int64_t ldg, float *__restrict__ ga, float *__restrict__ gb,
-                       int32_t accumulate)
+damp_apply2_bwd_kernel(Rows R, BwdTable T, const float *__restrict__ a, int64_t lda, const float *__restrict__ b,
+                       int64_t ldb, const float *__restrict__ out, int64_t ldo, const float *__restrict__ g,
+                       int64_t ldg, float *__restrict__ ga, float *__restrict__ gb, int32_t accumulate)
 {
-    const int64_t idx = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
-    if (idx >= total) return;
-    const int32_t n = na + nb;
-    const int64_t s = idx / n;
-    const int32_t x = static_cast<int32_t>(idx - s * n);
+    for_each_element(R, [&](int64_t s, int x) {
+        const float *ar = a + s * lda, *br = b + s * ldb, *outr = out + s * ldo, *gr = g + s * ldg;
+        const bool is_a = x < T.na;
+        if (is_a ? !ga : !gb) return;
+        const int r = is_a ? x : x - T.na;
+        const uint32_t *ptr = is_a ? T.rowa_ptr : T.rowb_ptr;
+        const uint32_t *ent = is_a ? T.rowa_jc : T.rowb_ic;
+        const float *other = is_a ? br : ar;
+        const uint32_t q0 = ptr[r], q1 = ptr[r + 1];
+        if (q1 - q0 > kLongTableRow) return;
+        float acc = 0.0f;
+        for (uint32_t q = q0; q < q1; ++q) {
+            const uint32_t e = ent[q];
+            acc = __builtin_fmaf(gated_grad(gr, outr, ar, br, T.col_ptr, T.col_ij, e >> 16), other[e & 0xffffu], acc);
+        }
+        float *dst = is_a ? ga + s * lda + r : gb + s * ldb + r;
+        const bool add = is_a ? (accumulate & 1) : (accumulate & 2);
+        *dst = add ? *dst + acc : acc;
+    });
+}
+
+// One wavefront per (sample, long row): lanes stride over the row's tuples, the partial sums meet by shuffles.
+__global__ void __launch_bounds__(kWave)
+damp_apply2_bwd_long_kernel(int32_t n_long, const uint32_t *__restrict__ long_rows, BwdTable T,
+                            const float *__restrict__ a, int64_t lda, const float *__restrict__ b, int64_t ldb,
+                            const float *__restrict__ out, int64_t ldo, const float *__restrict__ g, int64_t ldg,
+                            float *__restrict__ ga, float *__restrict__ gb, int32_t accumulate)
+{
+    const int64_t s = blockIdx.x / n_long;
+    const int x = static_cast<int>(long_rows[blockIdx.x - s * n_long]);
     const float *ar = a + s * lda, *br = b + s * ldb, *outr = out + s * ldo, *gr = g + s * ldg;
-    if (x < na) {
-        if (!ga) return;
-        float acc = 0.0f;
-        for (uint32_t q = rowa_ptr[x], q1 = rowa_ptr[x + 1]; q < q1; ++q) {
-            const uint32_t jc = rowa_jc[q];
-            acc = __builtin_fmaf(gated_grad(gr, outr, ar, br, col_ptr, col_ij, jc >> 16), br[jc & 0xffffu], acc);
-        }
-        ga[s * lda + x] = (accumulate & 1) ? ga[s * lda + x] + acc : acc;
-    } else {
-        if (!gb) return;
-        const int32_t j = x - na;
-        float acc = 0.0f;
-        for (uint32_t q = rowb_ptr[j], q1 = rowb_ptr[j + 1]; q < q1; ++q) {
-            const uint32_t ic = rowb_ic[q];
-            acc = __builtin_fmaf(gated_grad(gr, outr, ar, br, col_ptr, col_ij, ic >> 16), ar[ic & 0xffffu], acc);
-        }
-        gb[s * ldb + j] = (accumulate & 2) ? gb[s * ldb + j] + acc : acc;
+    const bool is_a = x < T.na;
+    if (is_a ? !ga : !gb) return;
+    const int r = is_a ? x : x - T.na;
+    const uint32_t *ptr = is_a ? T.rowa_ptr : T.rowb_ptr;
+    const uint32_t *ent = is_a ? T.rowa_jc : T.rowb_ic;
+    const float *other = is_a ? br : ar;
+    float acc = 0.0f;
+    for (uint32_t q = ptr[r] + threadIdx.x, q1 = ptr[r + 1]; q < q1; q += kWave) {
+        const uint32_t e = ent[q];
+        acc = __builtin_fmaf(gated_grad(gr, outr, ar, br, T.col_ptr, T.col_ij, e >> 16), other[e & 0xffffu], acc);
+    }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) acc += __shfl_xor(acc, d, kWave);
+    if (threadIdx.x == 0) {
+        float *dst = is_a ? ga + s * lda + r : gb + s * ldb + r;
+        const bool add = is_a ? (accumulate & 1) : (accumulate & 2);
+        *dst = add ? *dst + acc : acc;
     }
 }
 
@@ -109,13 +173,23 @@ dol_status launch_damp_apply2_bwd(const dol_fn_table *f, int32_t batch, const fl
                                   int64_t ldb, const float *out, int64_t ldo, const float *g, int64_t ldg, float *ga,
                                   float *gb, int32_t accumulate, hipStream_t st)
 {
-    const int64_t total = static_cast<int64_t>(batch) * (f->na + f->nb);
-    if (total == 0 || (!ga && !gb)) return DOL_OK;
+    if (batch == 0 || f->na + f->nb == 0 || (!ga && !gb)) return DOL_OK;
     if (conv_path_ok(f)) return launch_damp_conv_bwd(f, batch, a, lda, b, ldb, g, ldg, ga, gb, accumulate, st);
-    hipLaunchKernelGGL(damp_apply2_bwd_kernel, dim3(grid_for(total)), dim3(kThreads), 0, st, total, f->na, f->nb,
-                       f->col_ptr.ptr, f->col_ij.ptr, f->rowa_ptr.ptr, f->rowa_jc.ptr, f->rowb_ptr.ptr,
-                       f->rowb_ic.ptr, a, lda, b, ldb, out, ldo, g, ldg, ga, gb, accumulate);
+    const BwdTable T{f->col_ptr.ptr, f->col_ij.ptr, f->rowa_ptr.ptr, f->rowa_jc.ptr, f->rowb_ptr.ptr, f->rowb_ic.ptr,
+                     f->na, f->nb};
+    const Rows R = rows_of(batch, f->na + f->nb);
+    hipLaunchKernelGGL(damp_apply2_bwd_kernel, dim3(R.grid), dim3(kThreads), 0, st, R, T, a, lda, b, ldb, out, ldo, g,
+                       ldg, ga, gb, accumulate);
     DOL_HIP(hipGetLastError());
+    const int64_t n_long = static_cast<int64_t>(f->long_rows.n);
+    if (n_long > 0) {
+        if (batch * n_long > 0x7fffffffLL)
+            return fail(DOL_EUNSUPPORTED, "batch x long table rows = %lld exceeds 2^31", static_cast<long long>(batch * n_long));
+        hipLaunchKernelGGL(damp_apply2_bwd_long_kernel, dim3(static_cast<unsigned>(batch * n_long)), dim3(kWave), 0, st,
+                           static_cast<int32_t>(n_long), f->long_rows.ptr, T, a, lda, b, ldb, out, ldo, g, ldg, ga, gb,
+                           accumulate);
+        DOL_HIP(hipGetLastError());
+    }
     return DOL_OK;
 }
 
@@ -123,44 +197,40 @@ dol_status launch_damp_apply2_bwd(const dol_fn_table *f, int32_t batch, const fl
 
 // x[s, 0..n) = 0 (a fill kernel rather than a memset node, so that callers may capture the stream)
 __global__ void __launch_bounds__(kThreads)
-zero_rows_kernel(int64_t total, int32_t n, float *__restrict__ x, int64_t ld)
+zero_rows_kernel(Rows R, float *__restrict__ x, int64_t ld)
 {
-    const int64_t idx = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
-    if (idx >= total) return;
-    const int64_t s = idx / n;
-    x[s * ld + (idx - s * n)] = 0.0f;
+    for_each_element(R, [&](int64_t s, int c) { x[s * ld + c] = 0.0f; });
 }
 
 dol_status launch_zero_rows(int32_t batch, int32_t n, float *x, int64_t ld, hipStream_t st)
 {
-    const int64_t total = static_cast<int64_t>(batch) * n;
-    if (total == 0) return DOL_OK;
-    hipLaunchKernelGGL(zero_rows_kernel, dim3(grid_for(total)), dim3(kThreads), 0, st, total, n, x, ld);
+    if (batch == 0 || n == 0) return DOL_OK;
+    const Rows R = rows_of(batch, n);
+    hipLaunchKernelGGL(zero_rows_kernel, dim3(R.grid), dim3(kThreads), 0, st, R, x, ld);
     DOL_HIP(hipGetLastError());
     return DOL_OK;
 }
 
+// out[s, c] = in[s, src_col[c]], or 0 where src_col[c] < 0: Filter forward (src_col = kept positions) and its
+// transpose (src_col = position in the filtered row or -1).
 __global__ void __launch_bounds__(kThreads)
-damp_gather_cols_kernel(int64_t total, int32_t n_out, const int32_t *__restrict__ src_col,
-                        const float *__restrict__ in, int64_t ldi, float *__restrict__ out, int64_t ldo,
-                        int32_t accumulate)
+damp_gather_cols_kernel(Rows R, const int32_t *__restrict__ src_col, const float *__restrict__ in, int64_t ldi,
+                        float *__restrict__ out, int64_t ldo, int32_t accumulate)
 {
-    const int64_t idx = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
-    if (idx >= total) return;
-    const int64_t s = idx / n_out;
-    const int32_t c = static_cast<int32_t>(idx - s * n_out);
-    const int32_t i = src_col[c];
-    const float v = i >= 0 ? in[s * ldi + i] : 0.0f;
-    out[s * ldo + c] = accumulate ? out[s * ldo + c] + v : v;
+    for_each_element(R, [&](int64_t s, int c) {
+        const int32_t i = src_col[c];
+        const float v = i >= 0 ? in[s * ldi + i] : 0.0f;
+        out[s * ldo + c] = accumulate ? out[s * ldo + c] + v : v;
+    });
 }
 
 dol_status launch_damp_filter_fwd(const FilterPlan *p, int32_t batch, const float *in, int64_t ldi, float *out,
                                   int64_t ldo, hipStream_t st)
 {
-    const int64_t total = static_cast<int64_t>(batch) * p->n_out;
-    if (total == 0) return DOL_OK;
-    hipLaunchKernelGGL(damp_gather_cols_kernel, dim3(grid_for(total)), dim3(kThreads), 0, st, total, p->n_out,
-                       p->d_keep_idx.ptr, in, ldi, out, ldo, 0);
+    if (batch == 0 || p->n_out == 0) return DOL_OK;
+    const Rows R = rows_of(batch, p->n_out);
+    hipLaunchKernelGGL(damp_gather_cols_kernel, dim3(R.grid), dim3(kThreads), 0, st, R, p->d_keep_idx.ptr, in, ldi, out,
+                       ldo, 0);
     DOL_HIP(hipGetLastError());
     return DOL_OK;
 }
@@ -168,10 +238,10 @@ dol_status launch_damp_filter_fwd(const FilterPlan *p, int32_t batch, const floa
 dol_status launch_damp_filter_bwd(const FilterPlan *p, int32_t batch, const float *g, int64_t ldg, float *gin,
                                   int64_t ldgi, int32_t accumulate, hipStream_t st)
 {
-    const int64_t total = static_cast<int64_t>(batch) * p->n_in;
-    if (total == 0) return DOL_OK;
-    hipLaunchKernelGGL(damp_gather_cols_kernel, dim3(grid_for(total)), dim3(kThreads), 0, st, total, p->n_in,
-                       p->d_pos.ptr, g, ldg, gin, ldgi, accumulate & 1);
+    if (batch == 0 || p->n_in == 0) return DOL_OK;
+    const Rows R = rows_of(batch, p->n_in);
+    hipLaunchKernelGGL(damp_gather_cols_kernel, dim3(R.grid), dim3(kThreads), 0, st, R, p->d_pos.ptr, g, ldg, gin, ldgi,
+                       accumulate & 1);
     DOL_HIP(hipGetLastError());
     return DOL_OK;
 }
@@ -179,64 +249,58 @@ dol_status launch_damp_filter_bwd(const FilterPlan *p, int32_t batch, const floa
 // ---------------------------------------------------------------- union
 
 __global__ void __launch_bounds__(kThreads)
-damp_union_fwd_kernel(int64_t total, int32_t S, const int32_t *__restrict__ ia, const int32_t *__restrict__ ib,
+damp_union_fwd_kernel(Rows R, const int32_t *__restrict__ ia, const int32_t *__restrict__ ib,
                       const float *__restrict__ a, int64_t lda, const float *__restrict__ b, int64_t ldb,
                       float *__restrict__ out, int64_t ldo)
 {
-    const int64_t idx = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
-    if (idx >= total) return;
-    const int64_t s = idx / S;
-    const int32_t c = static_cast<int32_t>(idx - s * S);
-    const int32_t i = ia[c], j = ib[c];
-    float v;
-    if (i >= 0 && j >= 0) v = fminf(a[s * lda + i] + b[s * ldb + j], 1.0f);
-    else if (i >= 0) v = a[s * lda + i];
-    else v = b[s * ldb + j];
-    out[s * ldo + c] = v;
+    for_each_element(R, [&](int64_t s, int c) {
+        const int32_t i = ia[c], j = ib[c];
+        float v;
+        if (i >= 0 && j >= 0) v = fminf(a[s * lda + i] + b[s * ldb + j], 1.0f);
+        else if (i >= 0) v = a[s * lda + i];
+        else v = b[s * ldb + j];
+        out[s * ldo + c] = v;
+    });
 }
 
 dol_status launch_damp_union_fwd(const UnionPlan *p, int32_t batch, const float *a, int64_t lda, const float *b,
                                  int64_t ldb, float *out, int64_t ldo, hipStream_t st)
 {
-    const int64_t total = static_cast<int64_t>(batch) * p->n_out;
-    if (total == 0) return DOL_OK;
-    hipLaunchKernelGGL(damp_union_fwd_kernel, dim3(grid_for(total)), dim3(kThreads), 0, st, total, p->n_out,
-                       p->d_ia.ptr, p->d_ib.ptr, a, lda, b, ldb, out, ldo);
+    if (batch == 0 || p->n_out == 0) return DOL_OK;
+    const Rows R = rows_of(batch, p->n_out);
+    hipLaunchKernelGGL(damp_union_fwd_kernel, dim3(R.grid), dim3(kThreads), 0, st, R, p->d_ia.ptr, p->d_ib.ptr, a, lda, b,
+                       ldb, out, ldo);
     DOL_HIP(hipGetLastError());
     return DOL_OK;
 }
 
-// Thread x of a sample handles input position x of a (x < na) or x - na of b.
+// Element x of a sample is input position x of a (x < na) or x - na of b.
 __global__ void __launch_bounds__(kThreads)
-damp_union_bwd_kernel(int64_t total, int32_t na, int32_t nb, const int32_t *__restrict__ ia,
-                      const int32_t *__restrict__ ib, const int32_t *__restrict__ ca, const int32_t *__restrict__ cb,
-                      const float *__restrict__ a, int64_t lda, const float *__restrict__ b, int64_t ldb,
-                      const float *__restrict__ g, int64_t ldg, float *__restrict__ ga, float *__restrict__ gb,
-                      int32_t accumulate)
+damp_union_bwd_kernel(Rows R, int32_t na, const int32_t *__restrict__ ia, const int32_t *__restrict__ ib,
+                      const int32_t *__restrict__ ca, const int32_t *__restrict__ cb, const float *__restrict__ a,
+                      int64_t lda, const float *__restrict__ b, int64_t ldb, const float *__restrict__ g, int64_t ldg,
+                      float *__restrict__ ga, float *__restrict__ gb, int32_t accumulate)
 {
-    const int64_t idx = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
-    if (idx >= total) return;
-    const int32_t n = na + nb;
-    const int64_t s = idx / n;
-    const int32_t x = static_cast<int32_t>(idx - s * n);
-    const bool is_a = x < na;
-    if (is_a ? !ga : !gb) return;
-    const int32_t c = is_a ? ca[x] : cb[x - na];
-    const int32_t i = ia[c], j = ib[c];
-    float gv = g[s * ldg + c];
-    if (i >= 0 && j >= 0 && !(a[s * lda + i] + b[s * ldb + j] <= 1.0f)) gv = 0.0f;
-    if (is_a) ga[s * lda + x] = (accumulate & 1) ? ga[s * lda + x] + gv : gv;
-    else gb[s * ldb + (x - na)] = (accumulate & 2) ? gb[s * ldb + (x - na)] + gv : gv;
+    for_each_element(R, [&](int64_t s, int x) {
+        const bool is_a = x < na;
+        if (is_a ? !ga : !gb) return;
+        const int32_t c = is_a ? ca[x] : cb[x - na];
+        const int32_t i = ia[c], j = ib[c];
+        float gv = g[s * ldg + c];
+        if (i >= 0 && j >= 0 && !(a[s * lda + i] + b[s * ldb + j] <= 1.0f)) gv = 0.0f;
+        if (is_a) ga[s * lda + x] = (accumulate & 1) ? ga[s * lda + x] + gv : gv;
+        else gb[s * ldb + (x - na)] = (accumulate & 2) ? gb[s * ldb + (x - na)] + gv : gv;
+    });
 }
 
 dol_status launch_damp_union_bwd(const UnionPlan *p, int32_t batch, const float *a, int64_t lda, const float *b,
                                  int64_t ldb, const float *g, int64_t ldg, float *ga, float *gb, int32_t accumulate,
                                  hipStream_t st)
 {
-    const int64_t total = static_cast<int64_t>(batch) * (p->na + p->nb);
-    if (total == 0 || (!ga && !gb)) return DOL_OK;
-    hipLaunchKernelGGL(damp_union_bwd_kernel, dim3(grid_for(total)), dim3(kThreads), 0, st, total, p->na, p->nb,
-                       p->d_ia.ptr, p->d_ib.ptr, p->d_ca.ptr, p->d_cb.ptr, a, lda, b, ldb, g, ldg, ga, gb, accumulate);
+    if (batch == 0 || p->na + p->nb == 0 || (!ga && !gb)) return DOL_OK;
+    const Rows R = rows_of(batch, p->na + p->nb);
+    hipLaunchKernelGGL(damp_union_bwd_kernel, dim3(R.grid), dim3(kThreads), 0, st, R, p->na, p->d_ia.ptr, p->d_ib.ptr,
+                       p->d_ca.ptr, p->d_cb.ptr, a, lda, b, ldb, g, ldg, ga, gb, accumulate);
     DOL_HIP(hipGetLastError());
     return DOL_OK;
 }
@@ -244,22 +308,20 @@ dol_status launch_damp_union_bwd(const UnionPlan *p, int32_t batch, const float 
 // ---------------------------------------------------------------- harness helper: gradient of -log p[target]
 
 __global__ void __launch_bounds__(kThreads)
-nll_grad_kernel(int64_t total, int32_t n, const float *__restrict__ p, int64_t ld, const int32_t *__restrict__ target,
+nll_grad_kernel(Rows R, const float *__restrict__ p, int64_t ld, const int32_t *__restrict__ target,
                 float *__restrict__ grad)
 {
-    const int64_t idx = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
-    if (idx >= total) return;
-    const int64_t s = idx / n;
-    const int32_t c = static_cast<int32_t>(idx - s * n);
-    grad[s * ld + c] = c == target[s] ? -1.0f / fmaxf(p[s * ld + c], 1.17549435e-38f) : 0.0f;
+    for_each_element(R, [&](int64_t s, int c) {
+        grad[s * ld + c] = c == target[s] ? -1.0f / fmaxf(p[s * ld + c], 1.17549435e-38f) : 0.0f;
+    });
 }
 
 dol_status launch_nll_grad(int32_t batch, int32_t n, const float *p, int64_t ld, const int32_t *target, float *grad,
                            hipStream_t st)
 {
-    const int64_t total = static_cast<int64_t>(batch) * n;
-    if (total == 0) return DOL_OK;
-    hipLaunchKernelGGL(nll_grad_kernel, dim3(grid_for(total)), dim3(kThreads), 0, st, total, n, p, ld, target, grad);
+    if (batch == 0 || n == 0) return DOL_OK;
+    const Rows R = rows_of(batch, n);
+    hipLaunchKernelGGL(nll_grad_kernel, dim3(R.grid), dim3(kThreads), 0, st, R, p, ld, target, grad);
     DOL_HIP(hipGetLastError());
     return DOL_OK;
 }

@@ -44,7 +44,10 @@ damp_fold_kernel(const FoldArgs A)
 {
     extern __shared__ float lds[];
     const int lane = threadIdx.x, tc = lane & (kFoldTC - 1), half = lane / kFoldTC;
-    const int64_t s_raw = static_cast<int64_t>(blockIdx.x) * 2 + half;
+    // Workgroups are dealt round-robin to the 8 XCDs (one L2 each); give every XCD a contiguous range of
+    // samples so that the 128-byte lines shared by neighbouring samples are fetched into one L2 only.
+    const int wg = xcd_contiguous(blockIdx.x, gridDim.x);
+    const int64_t s_raw = static_cast<int64_t>(wg) * 2 + half;
     const bool live = s_raw < A.batch;              // an odd batch leaves the last half-wavefront idle
     const int64_t s = live ? s_raw : A.batch - 1;   // it shadows the last sample and stores nothing
     float *base = lds + half * A.stride;

@@ -57,8 +57,10 @@ struct DevArray {
 
 // ---------------------------------------------------------------- symbol-side plans
 
+constexpr int kLongTableRow = 64;   // backward: table rows with more tuples are reduced by a whole wavefront
+
 // A tuple of the function table packed for the kernels: low 16 bits = first index, high 16 = second.
-static inline uint32_t pack16(uint32_t lo, uint32_t hi) { return lo | (hi << 16); }
+__host__ __device__ static inline uint32_t pack16(uint32_t lo, uint32_t hi) { return lo | (hi << 16); }
 
 }  // namespace dol
 
@@ -81,6 +83,8 @@ struct dol_fn_table {
     dol::DevArray<uint32_t> rowa_ptr, rowa_jc;
     // backward w.r.t. b: row j owns rowb_ptr[j] .. rowb_ptr[j+1] of rowb_ic = pack16(i, column), ascending i
     dol::DevArray<uint32_t> rowb_ptr, rowb_ic;
+    // rows with more than dol::kLongTableRow tuples (x < na: row x of a, else row x - na of b)
+    dol::DevArray<uint32_t> long_rows;
     int device = 0;
 };
 

@@ -113,8 +113,15 @@ static dol_status build_table(int32_t na, int32_t nb, std::vector<Tuple> &tup, d
     for (size_t t = 0; t < tup.size() && tb->conv_like; ++t)
         tb->conv_like = col[t] == static_cast<uint32_t>(tup[t].i + tup[t].j);
 
+    std::vector<uint32_t> long_rows;
+    for (int32_t i = 0; i < na; ++i)
+        if (rowa_ptr[i + 1] - rowa_ptr[i] > static_cast<uint32_t>(kLongTableRow)) long_rows.push_back(static_cast<uint32_t>(i));
+    for (int32_t j = 0; j < nb; ++j)
+        if (rowb_ptr[j + 1] - rowb_ptr[j] > static_cast<uint32_t>(kLongTableRow)) long_rows.push_back(static_cast<uint32_t>(na + j));
+
     if (hipGetDevice(&tb->device) != hipSuccess) tb->device = 0;
     hipError_t e;
+    if ((e = tb->long_rows.upload(long_rows)) != hipSuccess) return hip_fail(e, "uploading the function table");
     if ((e = tb->col_ptr.upload(col_ptr)) != hipSuccess || (e = tb->col_ij.upload(col_ij)) != hipSuccess ||
         (e = tb->rowa_ptr.upload(rowa_ptr)) != hipSuccess || (e = tb->rowa_jc.upload(rowa_jc)) != hipSuccess ||
         (e = tb->rowb_ptr.upload(rowb_ptr)) != hipSuccess || (e = tb->rowb_ic.upload(rowb_ic)) != hipSuccess)

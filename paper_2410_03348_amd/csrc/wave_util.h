@@ -7,6 +7,15 @@ namespace dol {
 
 constexpr int kWave = 64;
 
+// Workgroups are dealt round-robin to the 8 XCDs of the chip (one L2 each).  This maps workgroup `id` of a
+// grid of `n` to a work index such that each XCD walks one contiguous range of indices (a bijection on 0..n-1),
+// so that memory lines shared by neighbouring indices are fetched into one L2 only.
+__device__ __forceinline__ int xcd_contiguous(unsigned id, unsigned n)
+{
+    const unsigned x = id & 7u, k = id >> 3, q = n >> 3, r = n & 7u;
+    return static_cast<int>(x * q + (x < r ? x : r) + k);
+}
+
 template <int CTRL>
 __device__ __forceinline__ float dpp(float x)
 {

@@ -267,5 +267,37 @@ class GridReach(Program):
         self.sample_ops = 2 * self.rounds * B
 
 
+class GridReachFused(Program):
+    """Config 5 through dol_iterate_apply2 / dol_iterate_backward: all rounds of a sweep in one launch."""
+
+    def __init__(self, w, device="cuda"):
+        B, side = w["p"].shape[0], w["side"]
+        self.batch, self.rounds, n = B, w["rounds"], side * side
+        E = w["edge_u"].size
+        self.E = E
+        self.table = dol.FnTable.create_sparse(n, E + 1, w["tri_i"], w["tri_j"], w["tri_o"])
+        n_tup = int(w["tri_i"].size)
+        pe = torch.ones((B, E + 1), dtype=torch.float32, device=device)
+        pe[:, :E] = _dev(w["p"], device)
+        self.edges = dol.Dist(np.arange(E + 1), pe)
+        r0 = torch.zeros((B, n), dtype=torch.float32, device=device)
+        r0[:, w["src"]] = 1.0
+        self.r0 = dol.Dist(np.arange(n), r0)
+        self.hist = torch.empty((self.rounds + 1, B, n), dtype=torch.float32, device=device)
+        self.g_out = _dev(w["g"], device)
+        self.g_e = torch.empty((B, E + 1), dtype=torch.float32, device=device)
+        self.grad_p = self.g_e[:, :E]
+        R = self.rounds
+        self.launches = [
+            Launch("damp_iterate_fwd_kernel",
+                   lambda: dol.iterate_apply2(self.r0, self.edges, self.table, R, self.hist),
+                   4 * B * (n + E + 1 + (R + 1) * n), B * R * n_tup, "fwd"),
+            Launch("damp_iterate_bwd_kernel",
+                   lambda: dol.iterate_backward(self.edges, self.table, R, self.hist, self.g_out, None, self.g_e),
+                   4 * B * ((R + 1) * n + n + 2 * (E + 1)), 2 * B * R * n_tup, "bwd"),
+        ]
+        self.sample_ops = 2 * R * B
+
+
 def make_program(config_id: int, workload, device="cuda") -> Program:
     return {1: Sum2Forward, 2: SumChain, 3: HashedPipeline, 4: DtkpSumChain, 5: GridReach}[config_id](workload, device)

@@ -194,6 +194,57 @@ def test_config5_grid_reach(gp, batch, side, rounds):
     assert_close(host(prog.grad_p), ref["grad_p"], "reach grad")
 
 
+@pytest.mark.parametrize("batch,side,rounds", [(256, 32, 64), (33, 7, 20), (2, 3, 5), (5, 4, 1), (3, 3, 0)])
+def test_config5_fused_iteration(gp, dol, batch, side, rounds):
+    """dol_iterate_apply2 / dol_iterate_backward: all rounds in one launch, same results as round-by-round calls."""
+    w = W.config5(batch=batch, side=side, rounds=rounds, seed=side + 1)
+    ref = OP.grid_reach_fwd_bwd(w)
+    prog = gp.GridReachFused(w)
+    prog.step()
+    hist = host(prog.hist)
+    assert_close(hist, ref["hist"], "fused reach history")
+    np.testing.assert_array_equal(hist == 1.0, ref["hist"] == 1.0)
+    assert_close(host(prog.grad_p), ref["grad_p"], "fused reach grad")
+    if rounds:
+        per_round = gp.GridReach(w)
+        per_round.step()
+        np.testing.assert_array_equal(hist, host(per_round.hist))          # same arithmetic, bit for bit
+    g0 = torch.empty((batch, side * side), device="cuda")
+    dol.iterate_backward(prog.edges, prog.table, rounds, prog.hist, prog.g_out, g0, None)
+    if rounds == 0:
+        np.testing.assert_array_equal(host(g0), w["g"])
+    with pytest.raises(dol.DolError) as ei:                                 # a table that is not square
+        f = dol.FnTable.create_dense(W.sum_table(range(4), range(3)))
+        dol.iterate_apply2(dol.Dist(np.arange(4), torch.ones((2, 4), device="cuda")),
+                           dol.Dist(np.arange(3), torch.ones((2, 3), device="cuda")), f, 2,
+                           torch.empty((3, 2, 4), device="cuda"))
+    assert ei.value.status == 5
+
+
+def test_backward_of_tables_with_long_rows(dol):
+    """A table whose rows hold hundreds of tuples (one symbol of b combines with every symbol of a)."""
+    na, B = 300, 20
+    i = np.arange(na, dtype=np.int32)
+    tri = (np.concatenate([i, i]), np.concatenate([np.zeros(na, np.int32), np.ones(na, np.int32)]),
+           np.concatenate([i % 7, 7 + i % 5]))
+    order = np.lexsort((tri[1], tri[0]))
+    tri = tuple(x[order].astype(np.int32) for x in tri)
+    a = W.softmax_rows(W.normal(1, B * na).reshape(B, na))
+    b = (W.uniform01(2, B * 2)).astype(np.float32).reshape(B, 2)
+    syms, want = oracle.damp_apply2_fwd(tri, na, 2, a, b)
+    f = dol.FnTable.create_sparse(na, 2, *tri)
+    da, db = dol.Dist(np.arange(na), dev(a)), dol.Dist(np.arange(2), dev(b))
+    do = dol.Dist.empty(syms, B)
+    dol.apply2(da, db, f, None, do)
+    assert_close(host(do.prob), want, "long-row apply")
+    g = np.abs(W.normal(3, B * syms.size)).astype(np.float32).reshape(B, -1)
+    ga, gb = torch.empty_like(da.prob), torch.empty_like(db.prob)
+    dol.backward(dol.OpRecord(dol.OP_APPLY2, da, db, do, f=f), dev(g), ga, gb)
+    wa, wb = oracle.damp_apply2_bwd(tri, na, 2, a, b, g)
+    assert_close(host(ga), wa, "long-row bwd a")
+    assert_close(host(gb), wb, "long-row bwd b")
+
+
 # ---------------------------------------------------------------- operators on their own: edge cases
 
 def test_apply_with_rejected_tuples_and_padding(dol):
