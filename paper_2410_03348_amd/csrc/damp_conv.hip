@@ -39,7 +39,10 @@ bool conv_path_ok(const dol_fn_table *f)
 
 std::string damp_kernel_name(const dol_fn_table *f, bool backward)
 {
-    if (!conv_path_ok(f)) return backward ? "damp_apply2_bwd_kernel" : "damp_apply2_fwd_kernel";
+    if (!conv_path_ok(f)) {
+        if (f->lds_ok) return backward ? "damp_lds_bwd_kernel" : "damp_lds_fwd_kernel";
+        return backward ? "damp_apply2_bwd_kernel" : "damp_apply2_fwd_kernel";
+    }
     char buf[96];
     snprintf(buf, sizeof buf, "damp_conv_%s_%s_kernel<%d", backward ? "bwd" : "fwd",
              f->na <= kTileMaxM ? "tile" : "loop", padded_nb(f->nb));   // a prefix: the tile size follows

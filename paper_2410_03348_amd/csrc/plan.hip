@@ -126,6 +126,8 @@ static dol_status build_table(int32_t na, int32_t nb, std::vector<Tuple> &tup, d
         (e = tb->rowa_ptr.upload(rowa_ptr)) != hipSuccess || (e = tb->rowa_jc.upload(rowa_jc)) != hipSuccess ||
         (e = tb->rowb_ptr.upload(rowb_ptr)) != hipSuccess || (e = tb->rowb_ic.upload(rowb_ic)) != hipSuccess)
         return hip_fail(e, "uploading the function table");
+    if (!conv_path_ok(tb.get()))
+        if (dol_status s2 = lds_plan_build(tb.get(), col_ptr, col_ij, rowa_ptr, rowa_jc, rowb_ptr, rowb_ic)) return s2;
     tb->kernel_fwd = damp_kernel_name(tb.get(), false);
     tb->kernel_bwd = damp_kernel_name(tb.get(), true);
     tb->h_col_ptr.swap(col_ptr);

@@ -312,6 +312,44 @@ def test_clamp_decisions_match_oracle(dol):
     assert_close(host(gb), wb, "gated bwd b")
 
 
+@pytest.mark.parametrize("na,nb,n_out,B,scale", [(12, 12, 8, 200, 0.4), (64, 64, 256, 130, 0.7), (128, 4, 16, 64, 0.25),
+                                                  (16, 128, 100, 257, 0.2), (4, 4, 4, 4160, 1.0), (64, 64, 256, 64, 0.05)])
+def test_hashed_tables_in_lds_with_clamping(dol, na, nb, n_out, B, scale):
+    """Hashed tables whose sizes are multiples of four (whole tiles of 64 samples go through the LDS kernels, the
+    remainder through the direct ones), some tuples rejected, tags scaled so that columns land on both sides of
+    the clamp (the last case: all far below it); rows 0..2 hit 0.875 / 1.0 / 1.125 exactly."""
+    tab = W.hashed_table(7, na, nb, n_out)
+    tab[1, :] = -1
+    tab[na - 1, nb // 2] = -1
+    a = (W.uniform01(1, B * na) * scale).astype(np.float32).reshape(B, na)
+    b = (W.uniform01(2, B * nb) * scale).astype(np.float32).reshape(B, nb)
+    for r, tot in enumerate((0.875, 1.0, 1.125)):
+        a[r] = 0; b[r] = 0
+        a[r, 0] = 1.0; b[r, 0] = tot
+    tri = oracle.dense_to_triples(tab)
+    syms, want, pre32, _ = oracle.damp_apply2_fwd(tri, na, nb, a, b, want_pre=True)
+    f = dol.FnTable.create_dense(tab)
+    if syms.size % 4 == 0:
+        assert f.kernel_fwd == "damp_lds_fwd_kernel" and f.kernel_bwd == "damp_lds_bwd_kernel"
+    da, db = dol.Dist(np.arange(na), dev(a)), dol.Dist(np.arange(nb), dev(b))
+    do = dol.Dist.empty(syms, B)
+    dol.apply2(da, db, f, None, do)
+    got = host(do.prob)
+    assert_close(got, want, "lds apply")
+    np.testing.assert_array_equal(got == 1.0, pre32 >= 1.0)
+    g = np.abs(W.normal(3, B * syms.size)).astype(np.float32).reshape(B, -1)
+    ga, gb = torch.empty_like(da.prob), torch.empty_like(db.prob)
+    dol.backward(dol.OpRecord(dol.OP_APPLY2, da, db, do, f=f), dev(g), ga, gb)
+    wa, wb = oracle.damp_apply2_bwd(tri, na, nb, a, b, g)
+    assert_close(host(ga), wa, "lds bwd a")
+    assert_close(host(gb), wb, "lds bwd b")
+    dol.backward(dol.OpRecord(dol.OP_APPLY2, da, db, do, f=f, accumulate=3), dev(g), ga, gb)
+    assert_close(host(ga), 2.0 * wa.astype(np.float64), "lds bwd a accumulated")
+    assert_close(host(gb), 2.0 * wb.astype(np.float64), "lds bwd b accumulated")
+    dol.backward(dol.OpRecord(dol.OP_APPLY2, da, db, do, f=f, accumulate=1), dev(g), ga, None)     # one side only
+    assert_close(host(ga), 3.0 * wa.astype(np.float64), "lds bwd a alone")
+
+
 @pytest.mark.parametrize("na,nb,B", [(127, 10, 300), (10, 10, 65), (1, 3, 70), (200, 16, 130), (5, 7, 64), (70, 1, 33),
                                       (9, 17, 40), (64, 4, 129), (300, 10, 50), (257, 2, 9), (256, 16, 5)])
 def test_sum_tables_with_clamping(dol, na, nb, B):
