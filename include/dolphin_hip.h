@@ -174,6 +174,10 @@ typedef struct {
     float *const *grad_inputs;
 } dol_fold;
 dol_status dol_fold_apply2(const dol_fold *fold, void *hip_stream);
+/* Name of the kernel dol_fold_apply2 launches for this description, as a profiler prints it ("" if the
+ * description is rejected).  Host only; the string belongs to the library and is valid until the calling
+ * thread's next call of this function. */
+const char *dol_fold_kernel(const dol_fold *fold);
 
 /* Repeated Apply with feedback under DAMP (the recursion of App. B, Fig. 9, run for a fixed number of rounds):
  *     r_0 = r0,   r_{t+1} = apply2(r_t, e, f)   for t = 0 .. rounds-1,

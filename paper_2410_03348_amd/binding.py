@@ -272,6 +272,8 @@ class _Fold(C.Structure):
 
 
 _lib.dol_fold_apply2.argtypes = [C.POINTER(_Fold), C.c_void_p]
+_lib.dol_fold_kernel.argtypes = [C.POINTER(_Fold)]
+_lib.dol_fold_kernel.restype = C.c_char_p
 
 
 class Fold:
@@ -301,6 +303,10 @@ class Fold:
 
 def fold_apply2(fold: Fold, stream=None):
     _check(_lib.dol_fold_apply2(C.byref(fold.c), _stream(stream)))
+
+
+def fold_kernel(fold: Fold) -> str:
+    return _lib.dol_fold_kernel(C.byref(fold.c)).decode()
 
 
 _lib.dol_iterate_apply2.argtypes = [C.POINTER(_Dist), C.POINTER(_Dist), C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]

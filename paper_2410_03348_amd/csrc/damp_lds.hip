@@ -3,7 +3,7 @@
 //     out[s, c] = min(1, sum over the tuples (i, j) of column c, ascending (i, j), of a[s, i] * b[s, j])
 //     ga[s, i]  = sum_j gh[s, col(i, j)] * b[s, j],    gb[s, j] = sum_i gh[s, col(i, j)] * a[s, i]
 //
-// A workgroup of 256 threads owns a tile of 64 samples.  The operand rows are staged TRANSPOSED in LDS
+// A workgroup (256 threads forward, 512 backward) owns a tile of 64 samples.  The operand rows are staged TRANSPOSED in LDS
 // (one 256-byte row of 64 samples per symbol), so that a lane can pull four samples of one symbol with a
 // single 16-byte read; 16 lanes cover the 64 samples, and the 16 groups of 16 lanes of the workgroup each
 // own a share of the output columns and walk their tuple lists.  Every tuple costs two 16-byte LDS reads and
@@ -18,11 +18,11 @@
 
 namespace dol {
 
-constexpr int kLdsWG = 256;
+constexpr int kLdsFwdWG = 512, kLdsBwdWG = 1024;   // threads per workgroup
 constexpr int kLdsTile = 64;                     // samples per tile = floats per LDS row
-constexpr int kLdsGroups = kLdsWG / 16;          // groups of 16 lanes
 constexpr size_t kLdsBytesMax = 160 * 1024;
-constexpr int kLdsMaxQ = 8;                      // staging: float4 pieces per thread and operand (symbols <= 128)
+constexpr int kLdsMaxSym = 128;                  // most symbols of one operand
+
 
 // Row number -> 16-bit address word: row * 16 chunks, with the swizzle term in the low four bits.
 // A lane that wants chunk q of the row reads 16 bytes at ((word ^ q) << 4).
@@ -49,7 +49,7 @@ dol_status lds_plan_build(dol_fn_table *tb, const std::vector<uint32_t> &col_ptr
     const int32_t na = tb->na, nb = tb->nb, S = tb->n_out;
     tb->lds_ok = false;
     if (na < 4 || nb < 4 || S < 4 || na % 4 || nb % 4 || S % 4) return DOL_OK;
-    if (na > 16 * kLdsMaxQ || nb > 16 * kLdsMaxQ || S + na + nb + 1 > 4095) return DOL_OK;
+    if (na > kLdsMaxSym || nb > kLdsMaxSym || S + na + nb + 1 > 4095) return DOL_OK;
     std::vector<uint32_t> w(col_ij.size()), pk, pk_ptr, pka, pka_ptr, pkb, pkb_ptr;
     // forward: rows [a: na][b: nb][zeros]
     for (size_t q = 0; q < col_ij.size(); ++q)
@@ -82,9 +82,10 @@ bool lds_path_ok(const dol_fn_table *f) { return f->lds_ok; }
 // ---------------------------------------------------------------- device helpers
 
 // Copies n words from global memory into LDS (all threads of the workgroup).
+template <int WG>
 __device__ __forceinline__ void copy_words(uint32_t *dst, const uint32_t *__restrict__ src, int n)
 {
-    for (int e = threadIdx.x; e < n; e += kLdsWG) dst[e] = src[e];
+    for (int e = threadIdx.x; e < n; e += WG) dst[e] = src[e];
 }
 
 // Transposing store of four consecutive symbols (i .. i+3, i % 4 == 0) of sample s into rows row0 + i ..
@@ -130,21 +131,23 @@ __device__ __forceinline__ float4 gather_dot(const float *rows, const uint4 *pac
     return acc;
 }
 
-// Stages the [kLdsTile x n] tile of a contiguous [batch, n] tensor (n % 4 == 0, n <= 16 * kLdsMaxQ) into rows
+// Stages the [kLdsTile x n] tile of a contiguous [batch, n] tensor (n % 4 == 0, n <= kLdsMaxSym) into rows
 // row0 .. row0 + n - 1.  Every thread issues all of its loads before the first transposing store.
+template <int WG>
 __device__ __forceinline__ void stage_tile(float *rows, int row0, const float *__restrict__ src, int n)
 {
     const int n4 = n >> 2, total = kLdsTile * n4;
     const float4 *src4 = reinterpret_cast<const float4 *>(src);
-    float4 v[kLdsMaxQ];
+    constexpr int kQ = kLdsTile * (kLdsMaxSym / 4) / WG;
+    float4 v[kQ];
 #pragma unroll
-    for (int x = 0; x < kLdsMaxQ; ++x) {
-        const int f = threadIdx.x + kLdsWG * x;
+    for (int x = 0; x < kQ; ++x) {
+        const int f = threadIdx.x + WG * x;
         if (f < total) v[x] = src4[f];
     }
 #pragma unroll
-    for (int x = 0; x < kLdsMaxQ; ++x) {
-        const int f = threadIdx.x + kLdsWG * x;
+    for (int x = 0; x < kQ; ++x) {
+        const int f = threadIdx.x + WG * x;
         if (f < total) {
             const int s = f / n4;
             store_transposed(rows, row0, (f - s * n4) << 2, s, v[x]);
@@ -154,7 +157,7 @@ __device__ __forceinline__ void stage_tile(float *rows, int row0, const float *_
 
 // ---------------------------------------------------------------- forward
 
-__global__ void __launch_bounds__(kLdsWG)
+__global__ void __launch_bounds__(kLdsFwdWG)
 damp_lds_fwd_kernel(int32_t n_tiles, int32_t na, int32_t nb, int32_t S, int32_t n_pk, const uint32_t *__restrict__ g_pk,
                     const uint32_t *__restrict__ g_pk_ptr, const float *__restrict__ a, const float *__restrict__ b,
                     float *__restrict__ out)
@@ -163,19 +166,19 @@ damp_lds_fwd_kernel(int32_t n_tiles, int32_t na, int32_t nb, int32_t S, int32_t 
     float *rows = lds;
     uint32_t *pk = reinterpret_cast<uint32_t *>(rows + kLdsTile * (na + nb + 1));
     uint32_t *pk_ptr = pk + 4 * n_pk;
-    copy_words(pk, g_pk, 4 * n_pk);
-    copy_words(pk_ptr, g_pk_ptr, S + 1);
-    for (int e = threadIdx.x; e < kLdsTile; e += kLdsWG) rows[(na + nb) * kLdsTile + e] = 0.0f;
+    copy_words<kLdsFwdWG>(pk, g_pk, 4 * n_pk);
+    copy_words<kLdsFwdWG>(pk_ptr, g_pk_ptr, S + 1);
+    for (int e = threadIdx.x; e < kLdsTile; e += kLdsFwdWG) rows[(na + nb) * kLdsTile + e] = 0.0f;
     const uint32_t q = threadIdx.x & 15u;
     const int group = threadIdx.x >> 4;
     const int n_blocks = S >> 2;
     for (int tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
         const int64_t s0 = static_cast<int64_t>(tile) * kLdsTile;
         __syncthreads();                             // the previous tile's readers are done (and the lists are in)
-        stage_tile(rows, 0, a + s0 * na, na);
-        stage_tile(rows, na, b + s0 * nb, nb);
+        stage_tile<kLdsFwdWG>(rows, 0, a + s0 * na, na);
+        stage_tile<kLdsFwdWG>(rows, na, b + s0 * nb, nb);
         __syncthreads();
-        for (int blk = group; blk < n_blocks; blk += kLdsGroups) {
+        for (int blk = group; blk < n_blocks; blk += (kLdsFwdWG / 16)) {
             float4 o[4];
 #pragma unroll
             for (int cc = 0; cc < 4; ++cc) {
@@ -196,22 +199,23 @@ damp_lds_fwd_kernel(int32_t n_tiles, int32_t na, int32_t nb, int32_t S, int32_t 
 
 // Stages gh = g gated by the clamp: out < 1 means the clamp did not act.  Elements with out == 1 are decided
 // afterwards from pre (see the kernel); their positions are counted in *n_flag.
+template <int WG>
 __device__ __forceinline__ void stage_gated(float *rows, const float *__restrict__ g, const float *__restrict__ out,
                                             int S, int *n_flag)
 {
     const int n4 = S >> 2, total = kLdsTile * n4;
     const float4 *g4 = reinterpret_cast<const float4 *>(g), *o4 = reinterpret_cast<const float4 *>(out);
     int flagged = 0;
-    for (int f0 = 0; f0 < total; f0 += kLdsWG * 4) {     // four pieces of g and of out in flight per thread
+    for (int f0 = 0; f0 < total; f0 += WG * 4) {     // four pieces of g and of out in flight per thread
         float4 vg[4], vo[4];
 #pragma unroll
         for (int x = 0; x < 4; ++x) {
-            const int f = f0 + threadIdx.x + kLdsWG * x;
+            const int f = f0 + threadIdx.x + WG * x;
             if (f < total) { vg[x] = g4[f]; vo[x] = o4[f]; }
         }
 #pragma unroll
         for (int x = 0; x < 4; ++x) {
-            const int f = f0 + threadIdx.x + kLdsWG * x;
+            const int f = f0 + threadIdx.x + WG * x;
             if (f < total) {
                 const int s = f / n4;
                 flagged |= !(vo[x].x < 1.0f) | !(vo[x].y < 1.0f) | !(vo[x].z < 1.0f) | !(vo[x].w < 1.0f);
@@ -222,7 +226,7 @@ __device__ __forceinline__ void stage_gated(float *rows, const float *__restrict
     if (flagged) atomicOr(n_flag, 1);
 }
 
-__global__ void __launch_bounds__(kLdsWG)
+__global__ void __launch_bounds__(kLdsBwdWG)
 damp_lds_bwd_kernel(int32_t n_tiles, int32_t na, int32_t nb, int32_t S, int32_t n_pka, int32_t n_pkb,
                     const uint32_t *__restrict__ g_pka, const uint32_t *__restrict__ g_pka_ptr,
                     const uint32_t *__restrict__ g_pkb, const uint32_t *__restrict__ g_pkb_ptr,
@@ -238,11 +242,11 @@ damp_lds_bwd_kernel(int32_t n_tiles, int32_t na, int32_t nb, int32_t S, int32_t 
     uint32_t *pka_ptr = pkb + 4 * n_pkb;
     uint32_t *pkb_ptr = pka_ptr + na + 1;
     int *flag = reinterpret_cast<int *>(pkb_ptr + nb + 1);
-    copy_words(pka, g_pka, 4 * n_pka);
-    copy_words(pka_ptr, g_pka_ptr, na + 1);
-    copy_words(pkb, g_pkb, 4 * n_pkb);
-    copy_words(pkb_ptr, g_pkb_ptr, nb + 1);
-    for (int e = threadIdx.x; e < kLdsTile; e += kLdsWG) rows[(n_rows - 1) * kLdsTile + e] = 0.0f;
+    copy_words<kLdsBwdWG>(pka, g_pka, 4 * n_pka);
+    copy_words<kLdsBwdWG>(pka_ptr, g_pka_ptr, na + 1);
+    copy_words<kLdsBwdWG>(pkb, g_pkb, 4 * n_pkb);
+    copy_words<kLdsBwdWG>(pkb_ptr, g_pkb_ptr, nb + 1);
+    for (int e = threadIdx.x; e < kLdsTile; e += kLdsBwdWG) rows[(n_rows - 1) * kLdsTile + e] = 0.0f;
     const uint32_t q = threadIdx.x & 15u;
     const int group = threadIdx.x >> 4;
     const int blocks_a = na >> 2, n_blocks = (na + nb) >> 2;
@@ -251,12 +255,12 @@ damp_lds_bwd_kernel(int32_t n_tiles, int32_t na, int32_t nb, int32_t S, int32_t 
         __syncthreads();
         if (threadIdx.x == 0) *flag = 0;
         __syncthreads();
-        stage_gated(rows, g + s0 * S, out + s0 * S, S, flag);
-        stage_tile(rows, S, a + s0 * na, na);
-        stage_tile(rows, S + na, b + s0 * nb, nb);
+        stage_gated<kLdsBwdWG>(rows, g + s0 * S, out + s0 * S, S, flag);
+        stage_tile<kLdsBwdWG>(rows, S, a + s0 * na, na);
+        stage_tile<kLdsBwdWG>(rows, S + na, b + s0 * nb, nb);
         __syncthreads();
         if (*flag) {                                 // rare: some output of this tile sits on the clamp
-            for (int e = threadIdx.x; e < kLdsTile * S; e += kLdsWG) {
+            for (int e = threadIdx.x; e < kLdsTile * S; e += kLdsBwdWG) {
                 const int s = e / S, c = e - s * S;
                 if (!(out[(s0 + s) * S + c] < 1.0f)) {
                     float pre = 0.0f;
@@ -269,7 +273,7 @@ damp_lds_bwd_kernel(int32_t n_tiles, int32_t na, int32_t nb, int32_t S, int32_t 
             }
             __syncthreads();
         }
-        for (int blk = group; blk < n_blocks; blk += kLdsGroups) {
+        for (int blk = group; blk < n_blocks; blk += (kLdsBwdWG / 16)) {
             const bool is_a = blk < blocks_a;
             const int col0 = is_a ? 4 * blk : 4 * (blk - blocks_a);
             const uint4 *packets = reinterpret_cast<const uint4 *>(is_a ? pka : pkb);
@@ -321,7 +325,7 @@ dol_status launch_damp_lds_fwd(const dol_fn_table *f, int32_t batch, const float
         attr_set = true;
     }
     const int32_t n_pk = static_cast<int32_t>(f->lds_pk.n / 4);
-    hipLaunchKernelGGL(damp_lds_fwd_kernel, dim3(lds_grid(n_tiles, f->lds_fwd_bytes)), dim3(kLdsWG), f->lds_fwd_bytes, st,
+    hipLaunchKernelGGL(damp_lds_fwd_kernel, dim3(lds_grid(n_tiles, f->lds_fwd_bytes)), dim3(kLdsFwdWG), f->lds_fwd_bytes, st,
                        n_tiles, f->na, f->nb, f->n_out, n_pk, f->lds_pk.ptr, f->lds_pk_ptr.ptr, a, b, out);
     DOL_HIP(hipGetLastError());
     *done = n_tiles * kLdsTile;
@@ -344,7 +348,7 @@ dol_status launch_damp_lds_bwd(const dol_fn_table *f, int32_t batch, const float
         attr_set = true;
     }
     const size_t lds = f->lds_bwd_bytes + 16;
-    hipLaunchKernelGGL(damp_lds_bwd_kernel, dim3(lds_grid(n_tiles, lds)), dim3(kLdsWG), lds, st, n_tiles, f->na, f->nb,
+    hipLaunchKernelGGL(damp_lds_bwd_kernel, dim3(lds_grid(n_tiles, lds)), dim3(kLdsBwdWG), lds, st, n_tiles, f->na, f->nb,
                        f->n_out, static_cast<int32_t>(f->lds_pka.n / 4), static_cast<int32_t>(f->lds_pkb.n / 4),
                        f->lds_pka.ptr, f->lds_pka_ptr.ptr, f->lds_pkb.ptr, f->lds_pkb_ptr.ptr, f->col_ptr.ptr,
                        f->col_ij.ptr, a, b, out, g, ga, gb, accumulate);

@@ -44,6 +44,26 @@ __device__ __forceinline__ float reduce32(float x)
     return x;
 }
 
+// The same over the 16 lanes of one DPP row.
+template <typename Op>
+__device__ __forceinline__ float reduce16(float x)
+{
+    x = Op::f(x, dpp<0xB1>(x));
+    x = Op::f(x, dpp<0x4E>(x));
+    x = Op::f(x, dpp<0x141>(x));
+    x = Op::f(x, dpp<0x140>(x));
+    return x;
+}
+
+__device__ __forceinline__ int reduce16_or(int x)
+{
+    x |= dpp_i<0xB1>(x);
+    x |= dpp_i<0x4E>(x);
+    x |= dpp_i<0x141>(x);
+    x |= dpp_i<0x140>(x);
+    return x;
+}
+
 __device__ __forceinline__ int reduce32_or(int x)
 {
     x |= dpp_i<0xB1>(x);

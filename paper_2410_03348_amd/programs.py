@@ -155,7 +155,7 @@ class SumChainFused(Program):
         self.fold = dol.Fold(self.digits, self.tables, out=self.out, target_col=self.target,
                              grad_inputs=[self.grad_p[t] for t in range(self.n)])
         n_in = sum(d.n_sym for d in self.digits)
-        self.launches = [Launch("damp_fold_kernel<10>", lambda: dol.fold_apply2(self.fold),
+        self.launches = [Launch(dol.fold_kernel(self.fold), lambda: dol.fold_apply2(self.fold),
                                 4 * self.batch * (2 * n_in + self.out.n_sym + 1), self.batch * macs, "fwd")]
         self.sample_ops = 2 * (self.n - 1) * self.batch
 
