@@ -238,6 +238,9 @@ dol_status launch_damp_filter_fwd(const FilterPlan *p, int32_t batch, const floa
                                   int64_t ldo, hipStream_t st)
 {
     if (batch == 0 || p->n_out == 0) return DOL_OK;
+    bool done = false;
+    if (dol_status s2 = launch_rows_gather(batch, p->n_in, p->n_out, p->d_keep_idx.ptr, in, ldi, out, ldo, 0, st, &done)) return s2;
+    if (done) return DOL_OK;
     const Rows R = rows_of(batch, p->n_out);
     hipLaunchKernelGGL(damp_gather_cols_kernel, dim3(R.grid), dim3(kThreads), 0, st, R, p->d_keep_idx.ptr, in, ldi, out,
                        ldo, 0);
@@ -249,6 +252,10 @@ dol_status launch_damp_filter_bwd(const FilterPlan *p, int32_t batch, const floa
                                   int64_t ldgi, int32_t accumulate, hipStream_t st)
 {
     if (batch == 0 || p->n_in == 0) return DOL_OK;
+    bool done = false;
+    if (p->n_out > 0)
+        if (dol_status s2 = launch_rows_gather(batch, p->n_out, p->n_in, p->d_pos.ptr, g, ldg, gin, ldgi, accumulate & 1, st, &done)) return s2;
+    if (done) return DOL_OK;
     const Rows R = rows_of(batch, p->n_in);
     hipLaunchKernelGGL(damp_gather_cols_kernel, dim3(R.grid), dim3(kThreads), 0, st, R, p->d_pos.ptr, g, ldg, gin, ldgi,
                        accumulate & 1);
@@ -277,6 +284,9 @@ dol_status launch_damp_union_fwd(const UnionPlan *p, int32_t batch, const float 
                                  int64_t ldb, float *out, int64_t ldo, hipStream_t st)
 {
     if (batch == 0 || p->n_out == 0) return DOL_OK;
+    bool done = false;
+    if (dol_status s2 = launch_rows_union_fwd(p, batch, a, lda, b, ldb, out, ldo, st, &done)) return s2;
+    if (done) return DOL_OK;
     const Rows R = rows_of(batch, p->n_out);
     hipLaunchKernelGGL(damp_union_fwd_kernel, dim3(R.grid), dim3(kThreads), 0, st, R, p->d_ia.ptr, p->d_ib.ptr, a, lda, b,
                        ldb, out, ldo);
@@ -308,6 +318,9 @@ dol_status launch_damp_union_bwd(const UnionPlan *p, int32_t batch, const float 
                                  hipStream_t st)
 {
     if (batch == 0 || p->na + p->nb == 0 || (!ga && !gb)) return DOL_OK;
+    bool done = false;
+    if (dol_status s2 = launch_rows_union_bwd(p, batch, a, lda, b, ldb, g, ldg, ga, gb, accumulate, st, &done)) return s2;
+    if (done) return DOL_OK;
     const Rows R = rows_of(batch, p->na + p->nb);
     hipLaunchKernelGGL(damp_union_bwd_kernel, dim3(R.grid), dim3(kThreads), 0, st, R, p->na, p->d_ia.ptr, p->d_ib.ptr,
                        p->d_ca.ptr, p->d_cb.ptr, a, lda, b, ldb, g, ldg, ga, gb, accumulate);

@@ -150,6 +150,14 @@ dol_status launch_damp_lds_fwd(const dol_fn_table *f, int32_t batch, const float
 dol_status launch_damp_lds_bwd(const dol_fn_table *f, int32_t batch, const float *a, int64_t lda, const float *b,
                                int64_t ldb, const float *out, int64_t ldo, const float *g, int64_t ldg, float *ga,
                                float *gb, int32_t accumulate, hipStream_t st, int32_t *done);
+// Filter / Union on contiguous 16-byte aligned tensors (damp_rows.hip); *done = false: not taken
+dol_status launch_rows_gather(int32_t batch, int32_t n_in, int32_t n_out, const int32_t *src_col, const float *in,
+                              int64_t ldi, float *out, int64_t ldo, int32_t accumulate, hipStream_t st, bool *done);
+dol_status launch_rows_union_fwd(const UnionPlan *p, int32_t batch, const float *a, int64_t lda, const float *b,
+                                 int64_t ldb, float *out, int64_t ldo, hipStream_t st, bool *done);
+dol_status launch_rows_union_bwd(const UnionPlan *p, int32_t batch, const float *a, int64_t lda, const float *b,
+                                 int64_t ldb, const float *g, int64_t ldg, float *ga, float *gb, int32_t accumulate,
+                                 hipStream_t st, bool *done);
 dol_status launch_zero_rows(int32_t batch, int32_t n, float *x, int64_t ld, hipStream_t st);
 dol_status launch_damp_filter_fwd(const FilterPlan *p, int32_t batch, const float *in, int64_t ldi, float *out,
                                   int64_t ldo, hipStream_t st);

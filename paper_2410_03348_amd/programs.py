@@ -188,13 +188,13 @@ class HashedPipeline(Program):
         n1, n2, n3, np2 = self.o1.n_sym, self.o2.n_sym, self.o3.n_sym, self.p2.n_sym
         self.launches = [
             _apply_fwd(self.a, self.b, self.table, self.o1, n_tup),
-            Launch("damp_gather_cols_kernel", lambda: dol.filter(self.o1, self.pred, None, self.o2),
+            Launch("damp_rows_gather_kernel", lambda: dol.filter(self.o1, self.pred, None, self.o2),
                    4 * B * (n1 + n2), 0, "fwd"),
-            Launch("damp_union_fwd_kernel", lambda: dol.union(self.o2, self.p2, None, self.o3),
+            Launch("damp_rows_union_fwd_kernel", lambda: dol.union(self.o2, self.p2, None, self.o3),
                    4 * B * (n2 + np2 + n3), 0, "fwd"),
-            Launch("damp_union_bwd_kernel", lambda: dol.backward(self.rec3, self.g3, self.g2, self.gp2),
+            Launch("damp_rows_union_bwd_kernel", lambda: dol.backward(self.rec3, self.g3, self.g2, self.gp2),
                    4 * B * (n3 + 2 * n2 + 2 * np2), 0, "bwd"),
-            Launch("damp_gather_cols_kernel", lambda: dol.backward(self.rec2, self.g2, self.g1, None),
+            Launch("damp_rows_gather_kernel", lambda: dol.backward(self.rec2, self.g2, self.g1, None),
                    4 * B * (n2 + n1), 0, "bwd"),
             _apply_bwd(self.rec1, self.g1, self.ga, self.gb, n_tup),
         ]
