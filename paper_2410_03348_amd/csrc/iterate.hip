@@ -16,7 +16,6 @@ constexpr int kItWaves = kItThreads / kWave;
 constexpr int kItMaxK = 4;              // columns per thread: na, nb up to 2048
 constexpr int kItMaxRow = kItThreads * kItMaxK;
 constexpr int kItCacheA = 6;            // tuples of a column / of a row of the first operand kept in registers
-constexpr int kItCacheB = 4;            // tuples of a row of the second operand kept in registers
 
 // The tuples [q0, q1) of one column or row: the first N in registers, the rest behind `list`.
 template <int N>
@@ -114,130 +113,167 @@ __device__ __forceinline__ float block_sum(float x, float *red)
     return tot;
 }
 
-template <int K, int KB>                // columns of a / rows of b per thread
+// Reverse sweep, one barrier per round.  At the start of round t (t = rounds - 1 .. 0) LDS holds gh = the gradient
+// reaching the unclamped sums of round t + 1, r_t and r_{t-1}.  A thread owns the same symbols i of the first
+// operand in every round.  For each tuple (i, j, c) of its rows it reads e[j] and gh[c] once: e[j] * gh[c] goes
+// into g[i] = d loss / d r_t[i], and r_t[i] * gh[c], the tuple's share of d loss / d e[j], into a register that
+// belongs to the tuple and runs over all rounds; the shares meet in LDS after the last round.  g[i] is gated
+// with the clamp decision of round t (re-derived from r_{t-1} only where r_t[i] sits on the clamp) and becomes
+// the next round's gh.  r_{t-2} arrives from HBM through a ring of registers requested kItAhead rounds earlier.
+template <int K>                        // symbols of the first operand per thread
 __global__ void __launch_bounds__(kItThreads)
 damp_iterate_bwd_kernel(int32_t batch, int32_t na, int32_t nb, int32_t rounds, ItTable T,
                         const float *__restrict__ e, int64_t lde, const float *__restrict__ hist,
                         const float *__restrict__ gout, int64_t ldg, float *__restrict__ grad_r0,
                         float *__restrict__ grad_e, int64_t ldge)
 {
-    extern __shared__ float lds[];          // H[3], G[2], ghat: rows of na + 1; e, ge: nb + 1; red[2][kItWaves]
+    extern __shared__ float lds[];          // gh[2], r[3]: rows of na + 1; e, ge: nb + 1; red[kItLongCache][kItWaves]
     const int na1 = na + 1;                 // operand rows end with a zero entry (see load_cached)
-    float *H0 = lds, *H1 = lds + na1, *H2 = lds + 2 * na1, *G0 = lds + 3 * na1, *G1 = lds + 4 * na1, *ghat = lds + 5 * na1;
-    float *le = lds + 6 * na1, *ge = le + nb + 1, *red = ge + nb + 1;
+    float *gh_cur = lds, *gh_nxt = lds + na1, *h_cur = lds + 2 * na1, *h_pre = lds + 3 * na1, *h_in = lds + 4 * na1;
+    float *le = lds + 5 * na1, *ge = le + nb + 1, *red = ge + nb + 1;
     const int tid = threadIdx.x;
     const int64_t s = blockIdx.x;
     const int64_t plane = static_cast<int64_t>(batch) * na;
     const float *hs = hist + s * na;
-    float *g_cur = G0, *g_nxt = G1, *h_nxt = H0, *h_cur = H1, *h_pre = H2;
-    for (int c = tid; c < na; c += kItThreads) {
-        g_cur[c] = gout[s * ldg + c];
-        h_nxt[c] = hs[rounds * plane + c];
-        if (rounds > 0) h_cur[c] = hs[(rounds - 1) * plane + c];
+    if (rounds == 0) {
+        if (grad_r0)
+            for (int c = tid; c < na; c += kItThreads) grad_r0[s * na + c] = gout[s * ldg + c];
+        if (grad_e)
+            for (int j = tid; j < nb; j += kItThreads) grad_e[s * ldge + j] = 0.0f;
+        return;
     }
-    for (int j = tid; j < nb; j += kItThreads) { le[j] = e[s * lde + j]; ge[j] = 0.0f; }
-    if (tid == 0) { H0[na] = 0.0f; H1[na] = 0.0f; H2[na] = 0.0f; ghat[na] = 0.0f; le[nb] = 0.0f; }
-    constexpr int KL = K > KB ? K : KB;
+    for (int c = tid; c < na; c += kItThreads) {
+        h_cur[c] = hs[(rounds - 1) * plane + c];
+        h_pre[c] = hs[max(rounds - 2, 0) * plane + c];
+    }
+    for (int j = tid; j <= nb; j += kItThreads) { le[j] = j < nb ? e[s * lde + j] : 0.0f; ge[j] = 0.0f; }
+    if (tid == 0) { gh_cur[na] = 0.0f; gh_nxt[na] = 0.0f; h_cur[na] = 0.0f; h_pre[na] = 0.0f; h_in[na] = 0.0f; }
     Cached<kItCacheA> col[K], rowa[K];
-    Cached<kItCacheB> rowb[KB];
 #pragma unroll
     for (int k = 0; k < K; ++k) {
         load_cached(col[k], T.col_ptr, T.col_ij, tid + kItThreads * k, na, pack16(na, nb));
         load_cached(rowa[k], T.rowa_ptr, T.rowa_jc, tid + kItThreads * k, na, pack16(nb, na));
     }
-#pragma unroll
-    for (int k = 0; k < KB; ++k) load_cached(rowb[k], T.rowb_ptr, T.rowb_ic, tid + kItThreads * k, nb, pack16(na, na));
-    // long rows: which they are, and this thread's share of their tuples, are the same in every round
+    // The first kItLongCache rows of the first operand with many tuples are summed by the whole workgroup: which
+    // rows they are and this thread's share of their tuples are the same in every round.
     int lx[kItLongCache];
-    uint32_t len_l[kItLongCache], ent_l[kItLongCache][KL];
+    bool l_on[kItLongCache];
+    uint32_t ent_l[kItLongCache][kItMaxK];
+    int n_long_a = 0;
+    for (int l = 0; l < T.n_long; ++l) n_long_a += static_cast<int>(T.long_rows[l]) < na;   // rows of a come first
 #pragma unroll
     for (int l = 0; l < kItLongCache; ++l) {
-        lx[l] = l < T.n_long ? static_cast<int>(T.long_rows[l]) : 0;
-        const bool is_a = lx[l] < na;
-        const int r = is_a ? lx[l] : lx[l] - na;
-        const uint32_t *ptr = is_a ? T.rowa_ptr : T.rowb_ptr;
-        const uint32_t *ent = is_a ? T.rowa_jc : T.rowb_ic;
-        const uint32_t q0 = l < T.n_long ? ptr[r] : 0u;
-        len_l[l] = l < T.n_long ? ptr[r + 1] - q0 : 0u;
+        l_on[l] = l < n_long_a;
+        lx[l] = l_on[l] ? static_cast<int>(T.long_rows[l]) : -1;
+        const uint32_t q0 = l_on[l] ? T.rowa_ptr[lx[l]] : 0u;
+        const uint32_t len = l_on[l] ? T.rowa_ptr[lx[l] + 1] - q0 : 0u;
 #pragma unroll
-        for (int k = 0; k < KL; ++k)
-            ent_l[l][k] = static_cast<uint32_t>(tid + kItThreads * k) < len_l[l] ? ent[q0 + tid + kItThreads * k] : 0u;
+        for (int k = 0; k < kItMaxK; ++k)          // a row has at most nb <= kItMaxRow tuples
+            ent_l[l][k] = static_cast<uint32_t>(tid + kItThreads * k) < len ? T.rowa_jc[q0 + tid + kItThreads * k] : pack16(nb, na);
+    }
+    int wide_a[K];                          // index of the workgroup-summed row that is this thread's, or -1
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        wide_a[k] = -1;
+#pragma unroll
+        for (int l = 0; l < kItLongCache; ++l)
+            if (l_on[l] && lx[l] == tid + kItThreads * k) wide_a[k] = l;
+    }
+    float share[K][kItCacheA], share_l[kItLongCache][kItMaxK];
+#pragma unroll
+    for (int k = 0; k < K; ++k)
+#pragma unroll
+        for (int x = 0; x < kItCacheA; ++x) share[k][x] = 0.0f;
+#pragma unroll
+    for (int l = 0; l < kItLongCache; ++l)
+#pragma unroll
+        for (int k = 0; k < kItMaxK; ++k) share_l[l][k] = 0.0f;
+    __syncthreads();
+    // gradient reaching the unclamped sums of the last round: r_rounds < 1 means the clamp did not act
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        const int c = tid + kItThreads * k;
+        if (c < na) {
+            float gv = gout[s * ldg + c];
+            if (hs[rounds * plane + c] >= 1.0f && !(dot_lo_hi(col[k], T.col_ij, h_cur, le) <= 1.0f)) gv = 0.0f;
+            gh_cur[c] = gv;
+        }
     }
     __syncthreads();
-    // One round of the reverse sweep.  `slot` carries this thread's piece of r_{t-1} from memory: with `primed`
-    // it was requested kItAhead rounds ago and is re-armed here for round t - kItAhead; otherwise it is
-    // requested at the start of the round.  The requests are unconditional (indices clamped) so that the
-    // wait in front of their use counts exactly the younger requests in flight.
+    // One round.  `slot` carries this thread's piece of r_{t-2} from memory: with `primed` it was requested
+    // kItAhead rounds ago and is re-armed here for round t - kItAhead; otherwise it is requested at the start of
+    // the round.  The requests are unconditional (indices clamped) so that the wait in front of their use counts
+    // exactly the younger requests in flight.
     auto round_body = [&](int t, float (&slot)[K], bool primed) {
         if (!primed) {
 #pragma unroll
             for (int k = 0; k < K; ++k)
-                slot[k] = hs[max(t - 1, 0) * plane + min(tid + kItThreads * k, na - 1)];
+                slot[k] = hs[max(t - 2, 0) * plane + min(tid + kItThreads * k, na - 1)];
         }
-        // gradient reaching the unclamped sums of round t: h_nxt < 1 means the clamp did not act
+        float wide_tot[kItLongCache];
 #pragma unroll
-        for (int k = 0; k < K; ++k) {
-            const int c = tid + kItThreads * k;
-            if (c < na) {
-                float gv = g_cur[c];
-                if (h_nxt[c] >= 1.0f && !(dot_lo_hi(col[k], T.col_ij, h_cur, le) <= 1.0f)) gv = 0.0f;
-                ghat[c] = gv;
+        for (int l = 0; l < kItLongCache; ++l) {
+            wide_tot[l] = 0.0f;
+            if (l_on[l]) {
+                const float ri = h_cur[lx[l]];
+                float acc = 0.0f;
+#pragma unroll
+                for (int k = 0; k < kItMaxK; ++k) {
+                    const float ghc = gh_cur[ent_l[l][k] >> 16];
+                    acc = __builtin_fmaf(le[ent_l[l][k] & 0xffffu], ghc, acc);
+                    share_l[l][k] = __builtin_fmaf(ri, ghc, share_l[l][k]);
+                }
+                wide_tot[l] = block_sum(acc, red + l * kItWaves);
             }
         }
-        __syncthreads();
+        float g[K], ri[K];
 #pragma unroll
-        for (int k = 0; k < K; ++k) {
-            const int i = tid + kItThreads * k;         // rowa tuples are (j | column << 16)
-            if (i < na && rowa[k].q1 - rowa[k].q0 <= kLongTableRow) g_nxt[i] = dot_lo_hi(rowa[k], T.rowa_jc, le, ghat);
-        }
-#pragma unroll
-        for (int k = 0; k < KB; ++k) {
-            const int j = tid + kItThreads * k;         // rowb tuples are (i | column << 16)
-            if (j < nb && rowb[k].q1 - rowb[k].q0 <= kLongTableRow) ge[j] += dot_lo_hi(rowb[k], T.rowb_ic, h_cur, ghat);
-        }
-        for (int l = 0; l < T.n_long; ++l) {     // rows with many tuples: the whole workgroup sums one row
-            const int x = l < kItLongCache ? lx[l < kItLongCache ? l : 0] : static_cast<int>(T.long_rows[l]);
-            const bool is_a = x < na;
-            const int r = is_a ? x : x - na;
-            const float *other = is_a ? le : h_cur;
+        for (int k = 0; k < K; ++k) {           // rowa tuples are (j | column << 16)
+            const int i = tid + kItThreads * k;
+            ri[k] = h_cur[min(i, na)];
             float acc = 0.0f;
-            if (l < kItLongCache) {
+            if (wide_a[k] < 0) {
 #pragma unroll
-                for (int k = 0; k < KL; ++k) {
-                    const uint32_t en = l == 0 ? ent_l[0][k] : ent_l[kItLongCache - 1][k];
-                    const uint32_t len = l == 0 ? len_l[0] : len_l[kItLongCache - 1];
-                    if (static_cast<uint32_t>(tid + kItThreads * k) < len) acc = __builtin_fmaf(ghat[en >> 16], other[en & 0xffffu], acc);
+                for (int x = 0; x < kItCacheA; ++x) {
+                    const float ghc = gh_cur[rowa[k].t[x] >> 16];
+                    acc = __builtin_fmaf(le[rowa[k].t[x] & 0xffffu], ghc, acc);
+                    share[k][x] = __builtin_fmaf(ri[k], ghc, share[k][x]);
+                }
+                for (uint32_t q = rowa[k].q0 + kItCacheA; q < rowa[k].q1; ++q) {   // tuples past the registers
+                    const uint32_t tu = T.rowa_jc[q];
+                    const float ghc = gh_cur[tu >> 16];
+                    acc = __builtin_fmaf(le[tu & 0xffffu], ghc, acc);
+                    atomicAdd(&ge[tu & 0xffffu], ri[k] * ghc);
                 }
             } else {
-                const uint32_t *ptr = is_a ? T.rowa_ptr : T.rowb_ptr;
-                const uint32_t *ent = is_a ? T.rowa_jc : T.rowb_ic;
-                for (uint32_t q = ptr[r] + tid, q1 = ptr[r + 1]; q < q1; q += kItThreads) {
-                    const uint32_t en = ent[q];
-                    acc = __builtin_fmaf(ghat[en >> 16], other[en & 0xffffu], acc);
-                }
-                __syncthreads();                // rows past the first two share one scratch row
+                acc = wide_a[k] == 0 ? wide_tot[0] : wide_tot[kItLongCache - 1];
             }
-            const float tot = block_sum(acc, red + (l < kItLongCache ? l : kItLongCache - 1) * kItWaves);
-            if (tid == 0) {
-                if (is_a) g_nxt[r] = tot;
-                else ge[r] += tot;
-            }
+            g[k] = acc;
         }
-        if (t > 0) {                            // r_{t-1} goes to the buffer no thread reads in this round
+        if (t > 0) {
 #pragma unroll
             for (int k = 0; k < K; ++k) {
                 const int c = tid + kItThreads * k;
-                if (c < na) h_pre[c] = slot[k];
+                if (c < na) {
+                    float gv = g[k];
+                    if (ri[k] >= 1.0f && !(dot_lo_hi(col[k], T.col_ij, h_pre, le) <= 1.0f)) gv = 0.0f;
+                    gh_nxt[c] = gv;
+                    h_in[c] = slot[k];          // r_{t-2} goes to the row no thread reads in this round
+                }
             }
+        } else if (grad_r0) {
+#pragma unroll
+            for (int k = 0; k < K; ++k)
+                if (tid + kItThreads * k < na) grad_r0[s * na + tid + kItThreads * k] = g[k];
         }
         if (primed) {
 #pragma unroll
             for (int k = 0; k < K; ++k)
-                slot[k] = hs[max(t - 1 - kItAhead, 0) * plane + min(tid + kItThreads * k, na - 1)];
+                slot[k] = hs[max(t - 2 - kItAhead, 0) * plane + min(tid + kItThreads * k, na - 1)];
         }
         __syncthreads();
-        float *sw = g_cur; g_cur = g_nxt; g_nxt = sw;
-        sw = h_nxt; h_nxt = h_cur; h_cur = h_pre; h_pre = sw;
+        float *sw = gh_cur; gh_cur = gh_nxt; gh_nxt = sw;
+        sw = h_cur; h_cur = h_pre; h_pre = h_in; h_in = sw;
     };
     float ring[kItAhead][K];
     int t = rounds - 1;
@@ -247,7 +283,7 @@ damp_iterate_bwd_kernel(int32_t batch, int32_t na, int32_t nb, int32_t rounds, I
         for (int x = 0; x < kItAhead; ++x)
 #pragma unroll
             for (int k = 0; k < K; ++k)
-                ring[x][k] = hs[max(t - 1 - x, 0) * plane + min(tid + kItThreads * k, na - 1)];
+                ring[x][k] = hs[max(t - 2 - x, 0) * plane + min(tid + kItThreads * k, na - 1)];
     }
     for (; t >= 0; t -= kItAhead) {
         round_body(t, ring[0], true);
@@ -255,10 +291,44 @@ damp_iterate_bwd_kernel(int32_t batch, int32_t na, int32_t nb, int32_t rounds, I
         round_body(t - 2, ring[2], true);
         round_body(t - 3, ring[3], true);
     }
-    if (grad_r0)
-        for (int c = tid; c < na; c += kItThreads) grad_r0[s * na + c] = g_cur[c];
-    if (grad_e)
-        for (int j = tid; j < nb; j += kItThreads) grad_e[s * ldge + j] = ge[j];
+    if (!grad_e) return;
+    // The tuples' shares meet per symbol of e.  Symbols whose row is long (met by most threads) are summed over
+    // the workgroup first, two of them; every other share is added to its symbol's entry in LDS.
+    int jw[kItLongCache];
+#pragma unroll
+    for (int l = 0; l < kItLongCache; ++l) {
+        const int x = n_long_a + l;
+        jw[l] = x < T.n_long ? static_cast<int>(T.long_rows[x]) - na : -1;
+    }
+    float wide_e[kItLongCache];
+#pragma unroll
+    for (int l = 0; l < kItLongCache; ++l) wide_e[l] = 0.0f;
+    auto deposit = [&](uint32_t tu, float v) {
+        const int j = static_cast<int>(tu & 0xffffu);
+        if (j >= nb) return;                    // an empty register slot
+        if (j == jw[0]) wide_e[0] += v;
+        else if (j == jw[kItLongCache - 1]) wide_e[kItLongCache - 1] += v;
+        else atomicAdd(&ge[j], v);
+    };
+#pragma unroll
+    for (int k = 0; k < K; ++k)
+        if (wide_a[k] < 0)
+#pragma unroll
+            for (int x = 0; x < kItCacheA; ++x) deposit(rowa[k].t[x], share[k][x]);
+#pragma unroll
+    for (int l = 0; l < kItLongCache; ++l)
+        if (l_on[l])
+#pragma unroll
+            for (int k = 0; k < kItMaxK; ++k) deposit(ent_l[l][k], share_l[l][k]);
+#pragma unroll
+    for (int l = 0; l < kItLongCache; ++l) {
+        if (jw[l] >= 0) {
+            const float tot = block_sum(wide_e[l], red + l * kItWaves);
+            if (tid == 0) atomicAdd(&ge[jw[l]], tot);
+        }
+    }
+    __syncthreads();
+    for (int j = tid; j < nb; j += kItThreads) grad_e[s * ldge + j] = ge[j];
 }
 
 static dol_status check_iterate(const dol_dist *e, const dol_fn_table *f, int32_t rounds, size_t lds_bytes)
@@ -314,7 +384,7 @@ dol_status dol_iterate_backward(const dol_dist *e, const dol_fn_table *f, int32_
                                 const float *grad_out, int64_t grad_out_ld, float *grad_r0, float *grad_e,
                                 void *hip_stream)
 {
-    const size_t lds = f ? sizeof(float) * (6 * static_cast<size_t>(f->na) + 2 * static_cast<size_t>(f->nb) + 8 + kItLongCache * kItWaves) : 0;
+    const size_t lds = f ? sizeof(float) * (5 * static_cast<size_t>(f->na) + 2 * static_cast<size_t>(f->nb) + 7 + kItLongCache * kItWaves) : 0;
     if (dol_status st = check_iterate(e, f, rounds, lds)) return st;
     if (e->batch == 0 || f->na == 0 || (!grad_r0 && !grad_e)) return DOL_OK;
     if (!hist || !grad_out) return fail(DOL_EINVAL, "hist or grad_out is NULL");
@@ -323,19 +393,13 @@ dol_status dol_iterate_backward(const dol_dist *e, const dol_fn_table *f, int32_
                     f->long_rows.ptr, static_cast<int32_t>(f->long_rows.n)};
     const dim3 grid(static_cast<unsigned>(e->batch)), block(kItThreads);
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-#define DOL_IT_BWD(KA, KB)                                                                                          \
-    hipLaunchKernelGGL((damp_iterate_bwd_kernel<KA, KB>), grid, block, lds, st, e->batch, f->na, f->nb, rounds, T,       \
+#define DOL_IT_BWD(KA)                                                                                              \
+    hipLaunchKernelGGL((damp_iterate_bwd_kernel<KA>), grid, block, lds, st, e->batch, f->na, f->nb, rounds, T,            \
                        e->prob, e->ld, hist, grad_out, grad_out_ld, grad_r0, grad_e, e->ld)
-    switch (iterate_k(f->na) * 10 + iterate_k(f->nb)) {
-    case 11: DOL_IT_BWD(1, 1); break;
-    case 12: DOL_IT_BWD(1, 2); break;
-    case 14: DOL_IT_BWD(1, 4); break;
-    case 21: DOL_IT_BWD(2, 1); break;
-    case 22: DOL_IT_BWD(2, 2); break;
-    case 24: DOL_IT_BWD(2, 4); break;
-    case 41: DOL_IT_BWD(4, 1); break;
-    case 42: DOL_IT_BWD(4, 2); break;
-    default: DOL_IT_BWD(4, 4); break;
+    switch (iterate_k(f->na)) {
+    case 1: DOL_IT_BWD(1); break;
+    case 2: DOL_IT_BWD(2); break;
+    default: DOL_IT_BWD(4); break;
     }
 #undef DOL_IT_BWD
     DOL_HIP(hipGetLastError());

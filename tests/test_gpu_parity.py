@@ -221,6 +221,49 @@ def test_config5_fused_iteration(gp, dol, batch, side, rounds):
     assert ei.value.status == 5
 
 
+@pytest.mark.parametrize("long_a,long_b", [((5, 9), (0, 1, 2)), ((5,), (0,)), ((), (0, 1, 2))])
+def test_fused_iteration_with_long_rows(dol, long_a, long_b):
+    """A square table in which some symbols of either operand meet more than 64 tuples: the fused sweeps sum the
+    first two such rows with the whole workgroup and leave the others to single threads."""
+    na, nb, B, rounds = 150, 80, 9, 5
+    ti, tj, to = [], [], []
+    for j in long_b:                                   # symbol j of e combines with every symbol of r
+        for i in range(na):
+            ti.append(i); tj.append(j); to.append((i * (2 * j + 1) + j) % na)
+    for i in long_a:                                   # symbol i of r combines with every remaining symbol of e
+        for j in range(3, nb):
+            ti.append(i); tj.append(j); to.append((i + 3 * j) % na)
+    for i in range(20, 140):                           # a few ordinary tuples
+        ti.append(i); tj.append(3 + i % 70); to.append((i + 1) % na)
+    order = np.lexsort((tj, ti))
+    tri = tuple(np.asarray(x, np.int32)[order] for x in (ti, tj, to))
+    assert np.unique(tri[2]).size == na
+    r0 = (W.uniform01(1, B * na) * 0.3).astype(np.float32).reshape(B, na)
+    r0[:, 7] = 1.0                                     # stays on the clamp in every round
+    e = (W.uniform01(2, B * nb) * 0.02).astype(np.float32).reshape(B, nb)
+    e[:, 0] = 1.0
+    hist = [r0]
+    for t in range(rounds):
+        hist.append(oracle.damp_apply2_fwd(tri, na, nb, hist[-1], e)[1])
+    g = np.abs(W.normal(3, B * na)).astype(np.float32).reshape(B, na)
+    want_ge = np.zeros((B, nb), np.float64)
+    gr = g
+    for t in reversed(range(rounds)):
+        gr, ge = oracle.damp_apply2_bwd(tri, na, nb, hist[t], e, gr)
+        want_ge += ge
+    f = dol.FnTable.create_sparse(na, nb, *tri)
+    d0, de = dol.Dist(np.arange(na), dev(r0)), dol.Dist(np.arange(nb), dev(e))
+    dh = torch.empty((rounds + 1, B, na), device="cuda")
+    dol.iterate_apply2(d0, de, f, rounds, dh)
+    got = host(dh)
+    assert_close(got, np.stack(hist), "iterated apply")
+    np.testing.assert_array_equal(got == 1.0, np.stack(hist) == 1.0)
+    g0, ge = torch.empty((B, na), device="cuda"), torch.empty((B, nb), device="cuda")
+    dol.iterate_backward(de, f, rounds, dh, dev(g), g0, ge)
+    assert_close(host(g0), gr, "iterated apply: gradient of r0")
+    assert_close(host(ge), want_ge, "iterated apply: gradient of e")
+
+
 def test_backward_of_tables_with_long_rows(dol):
     """A table whose rows hold hundreds of tuples (one symbol of b combines with every symbol of a)."""
     na, B = 300, 20
