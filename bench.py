@@ -75,7 +75,23 @@ def time_launches(prog, torch, repeats):
     return per_kernel
 
 
-def roofline_of(per_kernel):
+def measured_traffic(cfg, batch, kernel):
+    """HBM bytes per launch of `kernel` on this workload as the profiler's FETCH_SIZE / WRITE_SIZE counters gave
+    them (a table written from separate rocprofv3 --pmc runs: the counters cannot be read from inside this
+    program), or None when this workload was not profiled."""
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2410_03348_amd", "hbm_traffic.json")
+    try:
+        entries = json.load(open(path))["entries"]
+    except (OSError, ValueError, KeyError):
+        return None
+    for key, v in entries.items():
+        c, b, name = key.split(":", 2)
+        if int(c) == cfg and int(b) == batch and (name.startswith(kernel) or kernel.startswith(name)):
+            return v
+    return None
+
+
+def roofline_of(per_kernel, cfg, batch):
     name = max(per_kernel, key=lambda k: per_kernel[k]["ms"])
     k = per_kernel[name]
     avg_ms = k["ms"] / k["launches"]
@@ -84,8 +100,11 @@ def roofline_of(per_kernel):
     # the bound is the roof the kernel's algorithmic intensity puts it under
     alu = 2.0 * k["macs"] / max(k["bytes"], 1) > FP32_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9)
     achieved, peak, unit = (tflops, FP32_PEAK_TFLOPS, "TFLOP/s") if alu else (gbs, HBM_PEAK_GBS, "GB/s")
+    tr = measured_traffic(cfg, batch, name)
     return dict(bound="alu" if alu else "hbm", kernel=name, achieved=round(achieved, 3), peak=peak, unit=unit,
-                frac=round(achieved / peak, 4), traffic=None, launches_per_step=k["launches"],
+                frac=round(achieved / peak, 4), traffic=tr["fetch"] + tr["write"] if tr else None,
+                traffic_fetch=tr["fetch"] if tr else None, traffic_write=tr["write"] if tr else None,
+                launches_per_step=k["launches"],
                 avg_launch_us=round(avg_ms * 1e3, 3), bytes_per_launch=k["bytes"] // k["launches"],
                 flop_per_launch=2 * k["macs"] // k["launches"], algorithmic_gbs=round(gbs, 1),
                 share_of_step=round(k["ms"] / sum(v["ms"] for v in per_kernel.values()), 3))
@@ -159,7 +178,7 @@ def main():
     prog = build(w)
     ms = time_step(prog, torch, args.steps, args.warmup, args.mode)
     per_kernel = time_launches(prog, torch, args.repeats)
-    roof = roofline_of(per_kernel)
+    roof = roofline_of(per_kernel, cfg, prog.batch)
 
     out = {
         "metric": "batched apply sample-ops/sec (DAMP fwd+bwd, DTKP)",
@@ -185,7 +204,7 @@ def main():
         ps = build(ws)
         ms_s = time_step(ps, torch, 3, 1, "eager")
         pk = time_launches(ps, torch, 3)
-        rs = roofline_of(pk)
+        rs = roofline_of(pk, cfg, sb)
         rs.update(batch=sb, ms_per_step=round(ms_s, 4), value=round(ps.sample_ops / (ms_s * 1e-3), 1),
                   step_gbs=round(ps.algorithmic_bytes() / (ms_s * 1e-3) / 1e9, 1), kernels=kernel_table(pk))
         out["roofline_scaled"] = rs
