@@ -256,6 +256,18 @@ def dtkp_union(ia, ib, am, ap, bm, bp):
     return om, op, pr
 
 
+def dtkp_prob_bwd(mask, fact_prob, g):
+    """Gradient of the tag probabilities w.r.t. the fact probabilities: returns gfact[B,n_facts]."""
+    mask = np.ascontiguousarray(mask, np.uint64)
+    fp, g = _f32(fact_prob), _f32(g)
+    B, n, k = mask.shape
+    assert g.shape == (B, n) and fp.shape[0] == B
+    out = np.empty((B, fp.shape[1]), np.float32)
+    _chk(lib().orc_dtkp_prob_bwd(C.c_int(B), C.c_int(n), C.c_int(k), C.c_int(fp.shape[1]), _p(mask, C.c_uint64),
+                                 _p(fp, C.c_float), _p(g, C.c_float), C.c_int64(n), _p(out, C.c_float)), "dtkp_prob_bwd")
+    return out
+
+
 def dtkp_filter(pred, im, ip, iprob):
     pred = np.ascontiguousarray(pred, np.uint8)
     im = np.ascontiguousarray(im, np.uint64)

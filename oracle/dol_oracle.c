@@ -571,3 +571,43 @@ int orc_dtkp_filter(int B, int n, int k, const uint8_t *pred, const uint64_t *im
     }
     return ORC_OK;
 }
+
+/* Gradient of the tag probabilities w.r.t. the probabilities of the input
+ * facts (Sec. 3.2: Pr(t) = sum_i prod_j norm(t_ij), clamped at 1 as every
+ * disjunction of probabilities is; App. A.2: the clamp passes gradient inside
+ * and on its bounds).  Which proofs top_k kept is a constant of the
+ * differentiation.  d Pr / d p_f = sum over the kept proofs that hold fact f of
+ * the product of the proof's other facts.  The clamp decision is taken on the
+ * float sum of the kept proofs' float probabilities in rank order, the quantity
+ * the forward pass clamps.
+ * mask [B,n,k]; g [B,ldg]; gfact [B,n_facts], overwritten. */
+int orc_dtkp_prob_bwd(int B, int n, int k, int n_facts, const uint64_t *mask, const float *fact_prob,
+                      const float *g, int64_t ldg, float *gfact)
+{
+    if (n_facts < 0 || n_facts > 63 || k < 1) return ORC_EINVAL;
+    for (int s = 0; s < B; ++s) {
+        const float *fp = fact_prob + (int64_t)s * n_facts;
+        double acc[64];
+        for (int f = 0; f < n_facts; ++f) acc[f] = 0.0;
+        for (int i = 0; i < n; ++i) {
+            const uint64_t *m = mask + ((int64_t)s * n + i) * k;
+            float sum = 0.0f;
+            for (int x = 0; x < k; ++x)
+                if (m[x] != ABSENT) sum = sum + proof_prob(m[x], fp, n_facts);
+            if (!(sum <= 1.0f)) continue;
+            const double gi = (double)g[(int64_t)s * ldg + i];
+            for (int x = 0; x < k; ++x) {
+                if (m[x] == ABSENT) continue;
+                for (int f = 0; f < n_facts; ++f) {
+                    if (!((m[x] >> f) & 1u)) continue;
+                    double others = 1.0;
+                    for (int f2 = 0; f2 < n_facts; ++f2)
+                        if (f2 != f && ((m[x] >> f2) & 1u)) others *= (double)fp[f2];
+                    acc[f] += gi * others;
+                }
+            }
+        }
+        for (int f = 0; f < n_facts; ++f) gfact[(int64_t)s * n_facts + f] = (float)acc[f];
+    }
+    return ORC_OK;
+}

@@ -248,3 +248,87 @@ def test_filter_copies_tags():
     np.testing.assert_array_equal(om, r["mask"][:, sel])
     np.testing.assert_array_equal(op, r["pprob"][:, sel])
     np.testing.assert_array_equal(pr, r["prob"][:, sel])
+
+
+# ---------------------------------------------------------------- gradient of the tag probabilities
+
+def _masks(rows, k):
+    """[[proof bit lists per symbol]] -> mask[1, n, k]"""
+    m = np.full((1, len(rows), k), ABSENT, np.uint64)
+    for i, proofs in enumerate(rows):
+        for x, bits in enumerate(proofs):
+            m[0, i, x] = np.uint64(sum(1 << b for b in bits))
+    return m
+
+
+def test_prob_gradient_by_hand():
+    """Pr = p0*p1 + p2 for the first symbol, p3 for the second: d/dp = (p1, p0, 1 | 1), scaled by the upstream
+    gradient; a symbol over 1 passes nothing, a symbol at exactly 1 passes (App. A.2)."""
+    m = _masks([[[0, 1], [2]], [[3]]], 3)
+    fp = np.array([[0.5, 0.25, 0.125, 0.75]], np.float32)
+    g = np.array([[2.0, -3.0]], np.float32)
+    np.testing.assert_array_equal(oracle.dtkp_prob_bwd(m, fp, g), [[0.5, 1.0, 2.0, -3.0]])
+    over = np.array([[1.0, 0.75, 0.5, 0.75]], np.float32)           # 0.75 + 0.5 > 1
+    np.testing.assert_array_equal(oracle.dtkp_prob_bwd(m, over, g), [[0.0, 0.0, 0.0, -3.0]])
+    edge = np.array([[1.0, 0.5, 0.5, 1.0]], np.float32)             # exactly 1 on both symbols
+    np.testing.assert_array_equal(oracle.dtkp_prob_bwd(m, edge, g), [[1.0, 2.0, 2.0, -3.0]])
+    shared = _masks([[[0, 1], [0, 2]]], 2)                          # a fact in two proofs: p0*(p1 + p2)
+    np.testing.assert_allclose(oracle.dtkp_prob_bwd(shared, fp[:, :3], np.array([[1.0]], np.float32)),
+                               [[0.375, 0.5, 0.5]], rtol=1e-7)
+
+
+def test_prob_gradient_matches_finite_differences_of_the_definition():
+    """Central differences of sum_i prod_j p_j over the proof sets the forward pass kept (held fixed)."""
+    w = W.config4(batch=4, n_digits=4, k=3, seed=5)
+    ref = P.dtkp_sum_chain(w)
+    mask, fp = ref["mask"], w["fact_prob"].astype(np.float64)
+    B, n, k = mask.shape
+    g = W.normal(9, B * n).astype(np.float32).reshape(B, n)
+
+    def loss(s, q):
+        tot = 0.0
+        for i in range(n):
+            pr = 0.0
+            for x in range(k):
+                mm = int(mask[s, i, x])
+                if mm == int(ABSENT):
+                    continue
+                pr += np.prod([q[f] for f in range(q.size) if (mm >> f) & 1])
+            assert pr < 1.0
+            tot += float(g[s, i]) * pr
+        return tot
+
+    got = oracle.dtkp_prob_bwd(mask, w["fact_prob"], g)
+    for s in range(B):
+        for f in range(fp.shape[1]):
+            hi, lo = fp[s].copy(), fp[s].copy()
+            hi[f] += 1e-6; lo[f] -= 1e-6
+            fd = (loss(s, hi) - loss(s, lo)) / 2e-6
+            assert abs(got[s, f] - fd) <= 1e-6 + 1e-5 * abs(fd), (s, f, got[s, f], fd)
+
+
+def test_prob_gradient_equals_damp_gradient_when_nothing_is_pruned():
+    """With k >= the number of proofs of every symbol the tag probabilities are DAMP's (pinned above), and so are
+    their gradients w.r.t. the digit probabilities: fact 3n+d is digit slot n taking value d."""
+    n_dig, k, B = 3, 8, 5
+    p = np.stack([rand_probs(60 + t, B, 3) for t in range(n_dig)])
+    fp = np.ascontiguousarray(p.transpose(1, 0, 2).reshape(B, 9))
+    grp = (np.arange(9) // 3).astype(np.int32)
+    sym = np.arange(3, dtype=np.int32)
+    m, _, _ = oracle.dtkp_init(np.arange(3), fp, k)
+    syms, accs, tris = sym, [p[0]], []
+    for t in range(1, n_dig):
+        dm, _, _ = oracle.dtkp_init(3 * t + np.arange(3), fp, k)
+        tri = oracle.dense_to_triples(W.sum_table(syms, sym))
+        s2, m, _, _ = oracle.dtkp_apply2(tri, syms.size, 3, k, grp, fp, m, dm)
+        accs.append(oracle.damp_apply2_fwd(tri, syms.size, 3, accs[-1], p[t])[1])
+        tris.append((tri, syms.size))
+        syms = s2
+    g = W.normal(7, B * syms.size).astype(np.float32).reshape(B, syms.size)
+    got = oracle.dtkp_prob_bwd(m, fp, g)
+    want, gr = [None] * n_dig, g
+    for t in range(n_dig - 1, 0, -1):
+        gr, want[t] = oracle.damp_apply2_bwd(tris[t - 1][0], tris[t - 1][1], 3, accs[t - 1], p[t], gr)
+    want[0] = gr
+    want = np.stack(want).transpose(1, 0, 2).reshape(B, 9)
+    np.testing.assert_allclose(got, want, rtol=2e-5, atol=1e-7)
