@@ -145,9 +145,23 @@ typedef struct {
  *   apply2: gh = grad_out * [pre <= 1];  grad_a[i] = sum_j gh[col(i,j)] * b[j];  grad_b[j] = sum_i gh[col(i,j)] * a[i]
  *   filter: grad_a[i] = grad_out[position of i] for kept symbols, else 0
  *   union:  common symbols pass grad_out * [a + b <= 1] to both sides, one-sided symbols pass grad_out.
- * DTKP records return DOL_EUNSUPPORTED. */
+ * DTKP records return DOL_EUNSUPPORTED: see dol_dtkp_backward. */
 dol_status dol_backward(const dol_op_record *rec, const float *grad_out, float *grad_a, float *grad_b,
                         void *hip_stream);
+
+/* Gradient of a DTKP Distribution's tag probabilities w.r.t. the probabilities of the input facts (Sec. 3.2:
+ * Pr(t) = min(1, sum_i prod_j norm(t_ij)); App. A.2: the clamp passes gradient inside and on its bounds).  A DTKP tag
+ * names the input facts it rests on, so one call on the final Distribution of a program replaces the reverse sweep
+ * over its operators; the proofs top-k kept are constants of the differentiation.
+ *   d               the Distribution (proof_mask, proof_prob as the forward calls left them)
+ *   prov            the provenance the forward calls used (same fact_prob contents)
+ *   grad_prob       device [batch, grad_prob_ld]: d loss / d prob of each symbol of d
+ *   grad_fact_prob  device [batch, n_facts], OVERWRITTEN:
+ *                   sum over symbols with unclamped probability and their proofs holding fact f of
+ *                   grad_prob * (product of the proof's other facts' probabilities)
+ * Asynchronous on the stream; errors as for the other calls. */
+dol_status dol_dtkp_backward(const dol_dist *d, const dol_prov *prov, const float *grad_prob, int64_t grad_prob_ld,
+                             float *grad_fact_prob, void *hip_stream);
 
 /* A left fold of Apply under DAMP (the loop of Fig. 2: D_res = apply(D_res, D_i, f)), forward and backward in
  * ONE launch: acc_1 = apply2(inputs[0], inputs[1], tables[0]), acc_t = apply2(acc_{t-1}, inputs[t], tables[t-1]).

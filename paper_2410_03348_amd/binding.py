@@ -73,6 +73,7 @@ _lib.dol_union_plan.argtypes = [C.POINTER(_Dist), C.POINTER(_Dist), _i32p, _i32p
 _lib.dol_union.argtypes = [C.POINTER(_Dist), C.POINTER(_Dist), C.POINTER(_Prov), C.POINTER(_Dist), C.c_void_p]
 _lib.dol_dtkp_init.argtypes = [C.POINTER(_Dist), _i32p, C.POINTER(_Prov), C.c_void_p]
 _lib.dol_backward.argtypes = [C.POINTER(_OpRecord), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+_lib.dol_dtkp_backward.argtypes = [C.POINTER(_Dist), C.POINTER(_Prov), C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
 _lib.dol_nll_grad.argtypes = [C.POINTER(_Dist), C.c_void_p, C.c_void_p, C.c_void_p]
 _lib.dol_last_error.restype = C.c_char_p
 _lib.dol_version.restype = C.c_char_p
@@ -263,6 +264,14 @@ def backward(rec: OpRecord, grad_out: torch.Tensor, grad_a: Optional[torch.Tenso
              stream=None):
     """grad_out rows have stride rec.out.ld, grad_a rows rec.a.ld, grad_b rows rec.b.ld."""
     _check(_lib.dol_backward(C.byref(rec.c), _dptr(grad_out), _dptr(grad_a), _dptr(grad_b), _stream(stream)))
+
+
+def dtkp_backward(d: Dist, prov: Prov, grad_prob: torch.Tensor, grad_fact_prob: torch.Tensor, stream=None):
+    """grad_prob [batch, >= n_sym] (row stride = its stride(0)); grad_fact_prob [batch, n_facts] contiguous, overwritten."""
+    assert grad_prob.dtype == torch.float32 and grad_prob.dim() == 2 and grad_prob.stride(1) == 1
+    assert grad_fact_prob.dtype == torch.float32 and grad_fact_prob.is_contiguous()
+    _check(_lib.dol_dtkp_backward(d.ref(), prov.ref(), _dptr(grad_prob), max(int(grad_prob.stride(0)), grad_prob.shape[1]),
+                                  _dptr(grad_fact_prob), _stream(stream)))
 
 
 class _Fold(C.Structure):

@@ -141,11 +141,28 @@ dol_status dol_dtkp_init(dol_dist *d, const int32_t *fact_of_sym, const dol_prov
                             d->proof_prob, d->prob, d->ld, static_cast<hipStream_t>(hip_stream));
 }
 
+dol_status dol_dtkp_backward(const dol_dist *d, const dol_prov *prov, const float *grad_prob, int64_t grad_prob_ld,
+                             float *grad_fact_prob, void *hip_stream)
+{
+    if (!is_dtkp(prov)) return fail(DOL_EINVAL, "dol_dtkp_backward needs a DTKP provenance");
+    if (dol_status st = check_dist(d, "d", true, false, false)) return st;
+    if (dol_status st = check_prov(prov, d->batch)) return st;
+    if (d->batch == 0 || prov->n_facts == 0) return DOL_OK;
+    if (!grad_fact_prob) return fail(DOL_EINVAL, "grad_fact_prob is NULL");
+    if (d->n_sym > 0) {
+        if (!d->proof_prob) return fail(DOL_EINVAL, "d.proof_prob is NULL");
+        if (!grad_prob) return fail(DOL_EINVAL, "grad_prob is NULL");
+        if (grad_prob_ld < d->n_sym) return fail(DOL_ESHAPE, "grad_prob_ld = %lld is smaller than n_sym = %d", static_cast<long long>(grad_prob_ld), d->n_sym);
+    }
+    return launch_dtkp_prob_bwd(d->batch, d->n_sym, prov->k, prov->n_facts, d->proof_mask, d->proof_prob, prov->fact_prob,
+                                grad_prob, grad_prob_ld, grad_fact_prob, static_cast<hipStream_t>(hip_stream));
+}
+
 dol_status dol_backward(const dol_op_record *rec, const float *grad_out, float *grad_a, float *grad_b,
                         void *hip_stream)
 {
     if (!rec) return fail(DOL_EINVAL, "record is NULL");
-    if (is_dtkp(rec->prov)) return fail(DOL_EUNSUPPORTED, "backward of DTKP operators is not implemented");
+    if (is_dtkp(rec->prov)) return fail(DOL_EUNSUPPORTED, "DTKP tags carry their input facts: differentiate the final Distribution with dol_dtkp_backward");
     if (dol_status st = check_prov(rec->prov, 0)) return st;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const dol_dist *a = rec->a, *b = rec->b, *out = rec->out;

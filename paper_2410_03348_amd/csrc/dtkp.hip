@@ -263,4 +263,53 @@ dol_status launch_dtkp_filter(const FilterPlan *p, int32_t batch, int32_t k, con
     return DOL_OK;
 }
 
+// ---------------------------------------------------------------- gradient of the tag probabilities
+
+// Pr(symbol) = min(1, sum over its kept proofs of the product of their facts' probabilities) (Sec. 3.2); which
+// proofs top-k kept is a constant of the differentiation and the clamp passes gradient inside and on its bound
+// (App. A.2).  One wavefront per sample, lane f owns fact f and walks every proof of the sample: the control flow
+// is the same in all lanes (the proof's own fact multiplies by 1), the sums run in ascending (symbol, rank) order.
+__global__ void __launch_bounds__(64)
+dtkp_prob_bwd_kernel(int32_t n_sym, int32_t k, int32_t n_facts, const uint64_t *__restrict__ mask,
+                     const float *__restrict__ pprob, const float *__restrict__ fact_prob,
+                     const float *__restrict__ g, int64_t ldg, float *__restrict__ gfact)
+{
+    const int64_t s = blockIdx.x;
+    const int f = threadIdx.x;
+    const uint64_t mine = uint64_t(1) << f;
+    const float *fp = fact_prob + s * n_facts;
+    float acc = 0.0f;
+    for (int32_t i = 0; i < n_sym; ++i) {
+        const uint64_t *m = mask + (s * n_sym + i) * k;
+        const float *pp = pprob + (s * n_sym + i) * k;
+        float sum = 0.0f;                   // the quantity the forward pass clamped: kept proofs in rank order
+        for (int x = 0; x < k; ++x)
+            if (m[x] != kAbsent) sum = sum + pp[x];
+        if (!(sum <= 1.0f)) continue;
+        const float gi = g[s * ldg + i];
+        for (int x = 0; x < k; ++x) {
+            const uint64_t mm = m[x];
+            if (mm == kAbsent) continue;
+            float others = 1.0f;
+            for (uint64_t r = mm; r; r &= r - 1) {
+                const int j = __builtin_ctzll(r);
+                others = others * (j == f ? 1.0f : fp[j]);
+            }
+            if (mm & mine) acc = __builtin_fmaf(gi, others, acc);
+        }
+    }
+    if (f < n_facts) gfact[s * n_facts + f] = acc;
+}
+
+dol_status launch_dtkp_prob_bwd(int32_t batch, int32_t n_sym, int32_t k, int32_t n_facts, const uint64_t *mask,
+                                const float *pprob, const float *fact_prob, const float *g, int64_t ldg, float *gfact,
+                                hipStream_t st)
+{
+    if (batch == 0 || n_facts == 0) return DOL_OK;
+    hipLaunchKernelGGL(dtkp_prob_bwd_kernel, dim3(static_cast<unsigned>(batch)), dim3(64), 0, st, n_sym, k, n_facts, mask,
+                       pprob, fact_prob, g, ldg, gfact);
+    DOL_HIP(hipGetLastError());
+    return DOL_OK;
+}
+
 }  // namespace dol

@@ -178,6 +178,9 @@ dol_status launch_dtkp_apply2(const dol_fn_table *f, int32_t batch, int32_t k, i
 dol_status launch_dtkp_union(const UnionPlan *p, int32_t batch, int32_t k, const uint64_t *am, const float *ap,
                              const uint64_t *bm, const float *bp, uint64_t *om, float *op, float *oprob, int64_t ldo,
                              hipStream_t st);
+dol_status launch_dtkp_prob_bwd(int32_t batch, int32_t n_sym, int32_t k, int32_t n_facts, const uint64_t *mask,
+                                const float *pprob, const float *fact_prob, const float *g, int64_t ldg, float *gfact,
+                                hipStream_t st);
 dol_status launch_dtkp_filter(const FilterPlan *p, int32_t batch, int32_t k, const uint64_t *im, const float *ip,
                               const float *iprob, int64_t ldi, uint64_t *om, float *op, float *oprob, int64_t ldo,
                               hipStream_t st);

@@ -165,7 +165,7 @@ def test_config3_hashed_pipeline(gp, batch, na, nb, n_out):
 # ---------------------------------------------------------------- config 4
 
 @pytest.mark.parametrize("batch,n,k", [(1024, 5, 3), (130, 5, 1), (65, 4, 8), (7, 3, 5), (1, 2, 2)])
-def test_config4_dtkp_sum(gp, batch, n, k):
+def test_config4_dtkp_sum(gp, dol, batch, n, k):
     w = W.config4(batch=batch, n_digits=n, k=k, seed=k)
     ref = OP.dtkp_sum_chain(w)
     prog = gp.DtkpSumChain(w)
@@ -177,6 +177,22 @@ def test_config4_dtkp_sum(gp, batch, n, k):
         np.testing.assert_array_equal(host(d.proof_mask).view(np.uint64), m, err_msg="masks stage %d" % t)
         np.testing.assert_array_equal(host(d.proof_prob), pp, err_msg="proof probs stage %d" % t)
         assert_close(host(d.prob), pr, "tag prob stage %d" % t)
+    # gradient of -log Pr(target sum) w.r.t. the digit probabilities through the kept proofs
+    last = prog.accs[-1]
+    S = last.n_sym
+    target = (W.splitmix64(77, np.arange(batch)) % np.uint64(S)).astype(np.int64)
+    g = np.zeros((batch, S), np.float32)
+    g[np.arange(batch), target] = -1.0 / np.maximum(ref["prob"][np.arange(batch), target], np.float32(1e-30))
+    want = oracle.dtkp_prob_bwd(ref["mask"], w["fact_prob"], g)
+    gpad = torch.zeros((batch, S + 3), device="cuda")             # a padded gradient tensor
+    gpad[:, :S] = dev(g)
+    gf = torch.empty((batch, 10 * n), device="cuda")
+    dol.dtkp_backward(last, prog.prov, gpad, gf)
+    assert_close(host(gf), want, "dtkp gradient of the digit probabilities")
+    with pytest.raises(dol.DolError) as ei:                        # the per-operator backward does not take DTKP
+        dol.backward(dol.OpRecord(dol.OP_APPLY2, prog.accs[0], prog.digits[1], prog.accs[1], f=prog.tables[0],
+                                  prov=prog.prov), gpad, None, None)
+    assert ei.value.status == 5
 
 
 # ---------------------------------------------------------------- config 5
@@ -558,6 +574,15 @@ def test_dtkp_general_conjunction_union_filter(dol):
     np.testing.assert_array_equal(host(uo.proof_mask).view(np.uint64), um)
     np.testing.assert_array_equal(host(uo.proof_prob), up)
     assert_close(host(uo.prob), upr, "dtkp union")
+    # gradient of the k x k result's and the union's tag probabilities w.r.t. the facts (uniform fact probabilities
+    # put several symbols over 1, so the clamp gate is exercised; proofs share facts across slots)
+    for name, dist, masks, prob in (("k x k", out2, om, opr), ("union", uo, um, upr)):
+        gsym = W.normal(31, B * masks.shape[1]).astype(np.float32).reshape(B, -1)
+        want = oracle.dtkp_prob_bwd(masks, fp, gsym)
+        gf = torch.full((B, n_facts), 7.0, device="cuda")
+        dol.dtkp_backward(dist, prov, dev(gsym), gf)
+        assert_close(host(gf), want, "dtkp gradient, " + name)
+    assert (upr == 1.0).any() and (upr < 1.0).any()
     # filter
     pred = (np.arange(usyms.size) % 2 == 0).astype(np.uint8)
     fm, fpp, fpr = oracle.dtkp_filter(pred, um, up, upr)
