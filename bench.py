@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the Dolphin hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--batch B] [--mode graph|eager]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--batch B] [--mode auto|graph|eager]
 
 A step is one pass of a whole program (all its operator launches, forward and backward) over one batch of
 seeded synthetic input already resident in HBM.  The default program is BASELINE config 2, the Sum-15 DAMP
@@ -143,9 +143,12 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--batch", type=int, default=0, help="override the config's batch size")
-    ap.add_argument("--mode", default="graph", choices=["graph", "eager"])
+    ap.add_argument("--mode", default="auto", choices=["auto", "graph", "eager"],
+                    help="how a step is issued: the launches one by one on the stream, or a HIP-graph replay of them; "
+                         "auto = graph for steps of several launches, plain launches for a single-launch step (a graph "
+                         "replay of one kernel only adds its own submission gap)")
     ap.add_argument("--chain", default="fused", choices=["fused", "per-op"],
-                    help="configs 2 and 5: the fused entry points (dol_fold_apply2, dol_iterate_*), or one dol_apply2 / "
+                    help="configs 2, 4 and 5: the fused entry points (dol_fold_apply2, dol_dtkp_fold_apply2, dol_iterate_*), or one dol_apply2 / "
                          "dol_backward call per operator")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--repeats", type=int, default=20, help="back-to-back launches per event pair in the roofline pass")
@@ -174,8 +177,12 @@ def main():
             return GP.SumChainFused(wl)
         if args.chain == "fused" and cfg == 5:
             return GP.GridReachFused(wl)
+        if args.chain == "fused" and cfg == 4:
+            return GP.DtkpSumChainFused(wl)
         return GP.make_program(cfg, wl)
     prog = build(w)
+    if args.mode == "auto":
+        args.mode = "graph" if len(prog.launches) > 1 else "eager"
     ms = time_step(prog, torch, args.steps, args.warmup, args.mode)
     per_kernel = time_launches(prog, torch, args.repeats)
     roof = roofline_of(per_kernel, cfg, prog.batch)
@@ -189,11 +196,14 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": w.name, "config_id": cfg, "batch": prog.batch, "sample_ops_per_step": prog.sample_ops,
                    "launches_per_step": len(prog.launches), "mode": args.mode, "seed": args.seed,
-                   "chain": args.chain if cfg in (2, 5) else None,
+                   "chain": args.chain if cfg in (2, 4, 5) else None,
                    "algorithmic_bytes_per_step": prog.algorithmic_bytes()},
         "roofline": roof,
         "kernels": kernel_table(per_kernel),
     }
+    if getattr(prog, "candidate_slots", 0):     # DTKP: proof pairs offered to the top-k lists, per second
+        out["config"]["candidate_slots_per_step"] = prog.candidate_slots
+        out["candidate_slots_per_s"] = round(prog.candidate_slots / (ms * 1e-3), 1)
 
     sb = SCALED_BATCH[cfg] if args.scaled_batch < 0 else args.scaled_batch
     if sb:

@@ -103,7 +103,9 @@ void dol_fn_table_destroy(dol_fn_table *table);
  * a->n_sym == na, b->n_sym == nb, out->n_sym == S, equal batch.  prov NULL = DAMP.
  * DAMP: out->prob[s,c] = min(1, sum a.prob[s,i] * b.prob[s,j]); the sum runs over the tuples of column c
  *       in ascending (i, j) with one fused multiply-add each (this fixes the clamp decision of backward).
- * DTKP: reads a/b->proof_mask, writes out->proof_mask, out->proof_prob and out->prob (all three required). */
+ * DTKP: reads a/b->proof_mask and, where not NULL, a/b->proof_prob (each entry must be its proof's probability as
+ * this library computes it: the product of the fact probabilities in ascending fact index; with NULL the kernel
+ * derives every probability from the masks); writes out->proof_mask, out->proof_prob and out->prob (all required). */
 dol_status dol_apply2(const dol_dist *a, const dol_dist *b, const dol_fn_table *f, const dol_prov *prov,
                       dol_dist *out, void *hip_stream);
 
@@ -192,6 +194,32 @@ dol_status dol_fold_apply2(const dol_fold *fold, void *hip_stream);
  * description is rejected).  Host only; the string belongs to the library and is valid until the calling
  * thread's next call of this function. */
 const char *dol_fold_kernel(const dol_fold *fold);
+
+/* A left fold of Apply under DTKP-AM over naturally initialised inputs (the loop of Fig. 2 with the top-k proofs
+ * provenance of Sec. 3.2 / App. A), in ONE launch: symbol i of inputs[t] carries the single proof
+ * {fact_of_sym[t][i]} (as dol_dtkp_init would write it), acc_1 = apply2(inputs[0], inputs[1], tables[0]),
+ * acc_t = apply2(acc_{t-1}, inputs[t], tables[t-1]).  The result equals dol_dtkp_init on every input followed by
+ * n_inputs-1 dol_apply2 calls, bit for bit; neither the inputs' tags nor the intermediate Distributions touch HBM.
+ *   inputs          host array of n_inputs Distributions: only batch and n_sym are read
+ *   fact_of_sym     host array of n_inputs host arrays [inputs[t]->n_sym]
+ *   tables          host array of n_inputs-1 tables; tables[t-1] is (symbols of acc_{t-1}) x (symbols of inputs[t])
+ *   out             the last acc: proof_mask, proof_prob and prob written (all required)
+ *   grad_fact_prob  device [batch, n_facts] or NULL: if given, also the gradient of the loss w.r.t. the fact
+ *                   probabilities as dol_dtkp_backward defines it, OVERWRITTEN; the upstream gradient is that of
+ *                   -log out[target_col] (target_col: device [batch] int32) or grad_out (device [batch, grad_out_ld])
+ * DOL_EUNSUPPORTED when n_inputs > 32 or two generations of proofs (2 * max symbols * k * 12 bytes) exceed 64 KB. */
+typedef struct {
+    int32_t n_inputs;
+    const dol_dist *const *inputs;
+    const int32_t *const *fact_of_sym;
+    const dol_fn_table *const *tables;
+    dol_dist *out;
+    const int32_t *target_col;
+    const float *grad_out;
+    int64_t grad_out_ld;
+    float *grad_fact_prob;
+} dol_dtkp_fold;
+dol_status dol_dtkp_fold_apply2(const dol_dtkp_fold *fold, const dol_prov *prov, void *hip_stream);
 
 /* Repeated Apply with feedback under DAMP (the recursion of App. B, Fig. 9, run for a fixed number of rounds):
  *     r_0 = r0,   r_{t+1} = apply2(r_t, e, f)   for t = 0 .. rounds-1,

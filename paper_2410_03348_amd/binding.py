@@ -318,6 +318,43 @@ def fold_kernel(fold: Fold) -> str:
     return _lib.dol_fold_kernel(C.byref(fold.c)).decode()
 
 
+class _DtkpFold(C.Structure):
+    _fields_ = [("n_inputs", C.c_int32), ("inputs", C.POINTER(C.POINTER(_Dist))), ("fact_of_sym", C.POINTER(_i32p)),
+                ("tables", C.POINTER(C.c_void_p)), ("out", C.POINTER(_Dist)), ("target_col", C.c_void_p),
+                ("grad_out", C.c_void_p), ("grad_out_ld", C.c_int64), ("grad_fact_prob", C.c_void_p)]
+
+
+_lib.dol_dtkp_fold_apply2.argtypes = [C.POINTER(_DtkpFold), C.POINTER(_Prov), C.c_void_p]
+
+
+class DtkpFold:
+    """dol_dtkp_fold: a left fold of DTKP applies over naturally initialised inputs, one launch.  Keeps its operands alive."""
+
+    def __init__(self, inputs, facts, tables, out: Dist, target_col: Optional[torch.Tensor] = None,
+                 grad_out: Optional[torch.Tensor] = None, grad_fact_prob: Optional[torch.Tensor] = None):
+        n = len(inputs)
+        assert len(tables) == n - 1 and len(facts) == n
+        self._facts = [_np_i32(f) for f in facts]
+        self.keep = (inputs, tables, out, target_col, grad_out, grad_fact_prob)
+        self._in = (C.POINTER(_Dist) * n)(*[C.pointer(d.c) for d in inputs])
+        self._fo = (_i32p * n)(*[_ptr(f, C.c_int32) for f in self._facts])
+        self._tb = (C.c_void_p * max(n - 1, 1))(*[t._h for t in tables])
+        if target_col is not None:
+            assert target_col.dtype == torch.int32 and target_col.is_contiguous()
+        ldg = 0
+        if grad_out is not None:
+            assert grad_out.dtype == torch.float32 and grad_out.dim() == 2 and grad_out.stride(1) == 1
+            ldg = max(int(grad_out.stride(0)), grad_out.shape[1])
+        if grad_fact_prob is not None:
+            assert grad_fact_prob.dtype == torch.float32 and grad_fact_prob.is_contiguous()
+        self.c = _DtkpFold(n, self._in, self._fo, self._tb, C.pointer(out.c), _dptr(target_col), _dptr(grad_out), ldg,
+                           _dptr(grad_fact_prob))
+
+
+def dtkp_fold_apply2(fold: DtkpFold, prov: Prov, stream=None):
+    _check(_lib.dol_dtkp_fold_apply2(C.byref(fold.c), prov.ref(), _stream(stream)))
+
+
 _lib.dol_iterate_apply2.argtypes = [C.POINTER(_Dist), C.POINTER(_Dist), C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
 _lib.dol_iterate_backward.argtypes = [C.POINTER(_Dist), C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_int64,
                                       C.c_void_p, C.c_void_p, C.c_void_p]

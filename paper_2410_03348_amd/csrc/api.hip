@@ -71,8 +71,8 @@ dol_status dol_apply2(const dol_dist *a, const dol_dist *b, const dol_fn_table *
     if (out->batch > 0 && out->n_sym > 0 && !out->proof_prob) return fail(DOL_EINVAL, "out.proof_prob is NULL");
     GroupMasks gm;
     if (dol_status s2 = make_group_masks(prov, &gm)) return s2;
-    return launch_dtkp_apply2(f, a->batch, prov->k, prov->n_facts, gm, prov->fact_prob, a->proof_mask, b->proof_mask,
-                              out->proof_mask, out->proof_prob, out->prob, out->ld, st);
+    return launch_dtkp_apply2(f, a->batch, prov->k, prov->n_facts, gm, prov->fact_prob, a->proof_mask, a->proof_prob,
+                              b->proof_mask, b->proof_prob, out->proof_mask, out->proof_prob, out->prob, out->ld, st);
 }
 
 dol_status dol_filter(const dol_dist *d, const uint8_t *pred_mask, const dol_prov *prov, dol_dist *out,

@@ -7,79 +7,13 @@
 // list held in registers.  Repeated proofs are one proof, so insertion first looks the mask up; the list
 // order (higher probability first, ties by smaller mask) is total on distinct masks, which makes the
 // result independent of the order candidates arrive in.
-#include "internal.h"
+#include "dtkp_util.h"
 
 namespace dol {
 
 constexpr int kThreadsT = 128;
-constexpr uint64_t kAbsent = ~uint64_t(0);
 
 static inline unsigned grid_t(int64_t work) { return static_cast<unsigned>((work + kThreadsT - 1) / kThreadsT); }
-
-template <int K>
-struct TopK {
-    uint64_t m[K];
-    float p[K];   // absent slots carry -1 so that every real proof (probability >= 0) ranks before them
-
-    __device__ __forceinline__ void clear()
-    {
-#pragma unroll
-        for (int x = 0; x < K; ++x) { m[x] = kAbsent; p[x] = -1.0f; }
-    }
-
-    static __device__ __forceinline__ bool before(uint64_t ma, float pa, uint64_t mb, float pb)
-    {
-        return pa > pb || (pa == pb && ma < mb);
-    }
-
-    __device__ __forceinline__ void insert(uint64_t mask, float prob)
-    {
-        bool dup = false;
-#pragma unroll
-        for (int x = 0; x < K; ++x) dup |= (m[x] == mask);
-        if (dup) return;
-        if (!before(mask, prob, m[K - 1], p[K - 1])) return;
-#pragma unroll
-        for (int x = K - 1; x >= 0; --x) {
-            const bool here = before(mask, prob, m[x], p[x]);
-            const bool above = x > 0 ? before(mask, prob, m[x - 1], p[x - 1]) : false;
-            if (above) { m[x] = m[x - 1]; p[x] = p[x - 1]; }
-            else if (here) { m[x] = mask; p[x] = prob; }
-        }
-    }
-
-    // Writes the k slots and returns the tag probability min(1, sum in rank order) (App. A.1).
-    __device__ __forceinline__ float store(uint64_t *__restrict__ om, float *__restrict__ op) const
-    {
-        float sum = 0.0f;
-#pragma unroll
-        for (int x = 0; x < K; ++x) {
-            const bool present = m[x] != kAbsent;
-            om[x] = m[x];
-            op[x] = present ? p[x] : 0.0f;
-            if (present) sum = sum + p[x];
-        }
-        return fminf(sum, 1.0f);
-    }
-};
-
-__device__ __forceinline__ float proof_prob(uint64_t mask, const float *__restrict__ fp)
-{
-    float pr = 1.0f;
-    while (mask) {
-        const int j = __builtin_ctzll(mask);
-        pr = pr * fp[j];
-        mask &= mask - 1;
-    }
-    return pr;
-}
-
-__device__ __forceinline__ bool proof_conflict(uint64_t mask, const GroupMasks &gm)
-{
-    bool bad = false;
-    for (int g = 0; g < gm.n; ++g) bad |= __builtin_popcountll(mask & gm.m[g]) > 1;
-    return bad;
-}
 
 // ---------------------------------------------------------------- init
 
@@ -119,34 +53,38 @@ __global__ void __launch_bounds__(kThreadsT)
 dtkp_apply2_kernel(int64_t total, int32_t S, int32_t na, int32_t nb, int32_t n_facts,
                    const uint32_t *__restrict__ col_ptr, const uint32_t *__restrict__ col_ij, GroupMasks gm,
                    const float *__restrict__ fact_prob, const uint64_t *__restrict__ am,
-                   const uint64_t *__restrict__ bm, uint64_t *__restrict__ om, float *__restrict__ op,
-                   float *__restrict__ oprob, int64_t ldo)
+                   const float *__restrict__ ap, const uint64_t *__restrict__ bm, const float *__restrict__ bp,
+                   uint64_t *__restrict__ om, float *__restrict__ op, float *__restrict__ oprob, int64_t ldo)
 {
     const int64_t idx = static_cast<int64_t>(blockIdx.x) * kThreadsT + threadIdx.x;
     if (idx >= total) return;
     const int64_t s = idx / S;
     const int32_t c = static_cast<int32_t>(idx - s * S);
     const float *fp = fact_prob + s * n_facts;
-    const uint64_t *ams = am + s * na * K, *bms = bm + s * nb * K;
+    const int64_t a0 = s * na * K, b0 = s * nb * K;
     TopK<K> top;
     top.clear();
     for (uint32_t q = col_ptr[c], q1 = col_ptr[c + 1]; q < q1; ++q) {
         const uint32_t ij = col_ij[q];
-        const uint64_t *pa = ams + static_cast<int64_t>(ij & 0xffffu) * K;
-        const uint64_t *pb = bms + static_cast<int64_t>(ij >> 16) * K;
-        uint64_t mb[K];
-#pragma unroll
-        for (int y = 0; y < K; ++y) mb[y] = pb[y];
+        const int64_t ia = a0 + static_cast<int64_t>(ij & 0xffffu) * K, ib = b0 + static_cast<int64_t>(ij >> 16) * K;
+        uint64_t ma[K], mb[K];
+        float pa[K], pb[K];
 #pragma unroll
         for (int x = 0; x < K; ++x) {
-            const uint64_t ma = pa[x];
-            if (ma == kAbsent) continue;
+            ma[x] = am[ia + x];
+            mb[x] = bm[ib + x];
+            pa[x] = ap ? ap[ia + x] : -1.0f;
+            pb[x] = bp ? bp[ib + x] : -1.0f;
+        }
+#pragma unroll
+        for (int x = 0; x < K; ++x) {
+            if (ma[x] == kAbsent) continue;
 #pragma unroll
             for (int y = 0; y < K; ++y) {
                 if (mb[y] == kAbsent) continue;
-                const uint64_t m = ma | mb[y];
+                const uint64_t m = ma[x] | mb[y];
                 if (proof_conflict(m, gm)) continue;
-                top.insert(m, proof_prob(m, fp));
+                top.insert(m, union_prob(ma[x], pa[x], mb[y], pb[y], fp));
             }
         }
     }
@@ -155,11 +93,11 @@ dtkp_apply2_kernel(int64_t total, int32_t S, int32_t na, int32_t nb, int32_t n_f
 
 template <int K>
 static void launch_apply2_k(int64_t total, const dol_fn_table *f, int32_t n_facts, const GroupMasks &gm,
-                            const float *fact_prob, const uint64_t *am, const uint64_t *bm, uint64_t *om, float *op,
-                            float *oprob, int64_t ldo, hipStream_t st)
+                            const float *fact_prob, const uint64_t *am, const float *ap, const uint64_t *bm,
+                            const float *bp, uint64_t *om, float *op, float *oprob, int64_t ldo, hipStream_t st)
 {
     hipLaunchKernelGGL(dtkp_apply2_kernel<K>, dim3(grid_t(total)), dim3(kThreadsT), 0, st, total, f->n_out, f->na,
-                       f->nb, n_facts, f->col_ptr.ptr, f->col_ij.ptr, gm, fact_prob, am, bm, om, op, oprob, ldo);
+                       f->nb, n_facts, f->col_ptr.ptr, f->col_ij.ptr, gm, fact_prob, am, ap, bm, bp, om, op, oprob, ldo);
 }
 
 #define DOL_DISPATCH_K(k, CALL)                                      \
@@ -176,12 +114,12 @@ static void launch_apply2_k(int64_t total, const dol_fn_table *f, int32_t n_fact
     }
 
 dol_status launch_dtkp_apply2(const dol_fn_table *f, int32_t batch, int32_t k, int32_t n_facts, const GroupMasks &gm,
-                              const float *fact_prob, const uint64_t *am, const uint64_t *bm, uint64_t *om, float *op,
-                              float *oprob, int64_t ldo, hipStream_t st)
+                              const float *fact_prob, const uint64_t *am, const float *ap, const uint64_t *bm,
+                              const float *bp, uint64_t *om, float *op, float *oprob, int64_t ldo, hipStream_t st)
 {
     const int64_t total = static_cast<int64_t>(batch) * f->n_out;
     if (total == 0) return DOL_OK;
-#define CALL(KK) launch_apply2_k<KK>(total, f, n_facts, gm, fact_prob, am, bm, om, op, oprob, ldo, st)
+#define CALL(KK) launch_apply2_k<KK>(total, f, n_facts, gm, fact_prob, am, ap, bm, bp, om, op, oprob, ldo, st)
     DOL_DISPATCH_K(k, CALL)
 #undef CALL
     DOL_HIP(hipGetLastError());

@@ -1,0 +1,99 @@
+// Device helpers shared by the DTKP kernels: the bitmask encoding of proofs, their probabilities, the exclusion
+// test and the k-entry sorted list (Sec. 3.2, Table 1, App. A).
+#pragma once
+
+#include "internal.h"
+
+namespace dol {
+
+constexpr uint64_t kAbsent = ~uint64_t(0);
+
+template <int K>
+struct TopK {
+    uint64_t m[K];
+    float p[K];   // absent slots carry -1 so that every real proof (probability >= 0) ranks before them
+
+    __device__ __forceinline__ void clear()
+    {
+#pragma unroll
+        for (int x = 0; x < K; ++x) { m[x] = kAbsent; p[x] = -1.0f; }
+    }
+
+    static __device__ __forceinline__ bool before(uint64_t ma, float pa, uint64_t mb, float pb)
+    {
+        return pa > pb || (pa == pb && ma < mb);
+    }
+
+    __device__ __forceinline__ void insert(uint64_t mask, float prob)
+    {
+        bool dup = false;
+#pragma unroll
+        for (int x = 0; x < K; ++x) dup |= (m[x] == mask);
+        if (dup) return;
+        if (!before(mask, prob, m[K - 1], p[K - 1])) return;
+#pragma unroll
+        for (int x = K - 1; x >= 0; --x) {
+            const bool here = before(mask, prob, m[x], p[x]);
+            const bool above = x > 0 ? before(mask, prob, m[x - 1], p[x - 1]) : false;
+            if (above) { m[x] = m[x - 1]; p[x] = p[x - 1]; }
+            else if (here) { m[x] = mask; p[x] = prob; }
+        }
+    }
+
+    // Writes the k slots and returns the tag probability min(1, sum in rank order) (App. A.1).
+    __device__ __forceinline__ float store(uint64_t *__restrict__ om, float *__restrict__ op) const
+    {
+        float sum = 0.0f;
+#pragma unroll
+        for (int x = 0; x < K; ++x) {
+            const bool present = m[x] != kAbsent;
+            om[x] = m[x];
+            op[x] = present ? p[x] : 0.0f;
+            if (present) sum = sum + p[x];
+        }
+        return fminf(sum, 1.0f);
+    }
+};
+
+__device__ __forceinline__ float proof_prob(uint64_t mask, const float *__restrict__ fp)
+{
+    float pr = 1.0f;
+    while (mask) {
+        const int j = __builtin_ctzll(mask);
+        pr = pr * fp[j];
+        mask &= mask - 1;
+    }
+    return pr;
+}
+
+__device__ __forceinline__ bool proof_conflict(uint64_t mask, const GroupMasks &gm)
+{
+    bool bad = false;
+    for (int g = 0; g < gm.n; ++g) bad |= __builtin_popcountll(mask & gm.m[g]) > 1;
+    return bad;
+}
+
+// pr * (probabilities of the facts in `bits`, ascending)
+__device__ __forceinline__ float extend_prob(float pr, uint64_t bits, const float *__restrict__ fp)
+{
+    while (bits) {
+        pr = pr * fp[__builtin_ctzll(bits)];
+        bits &= bits - 1;
+    }
+    return pr;
+}
+
+// Probability of the union of two proofs.  The product runs over the facts in ascending index; when every fact
+// that one side adds lies above the other side's highest fact, that side's stored probability is exactly the
+// product's prefix and only the added facts remain to be multiplied (the case of a fold whose new operand brings
+// new input slots).  pa / pb < 0: that side's probabilities are not available.
+__device__ __forceinline__ float union_prob(uint64_t ma, float pa, uint64_t mb, float pb, const float *__restrict__ fp)
+{
+    const uint64_t add_b = mb & ~ma, add_a = ma & ~mb;
+    const int hi_a = ma ? 63 - __builtin_clzll(ma) : -1, hi_b = mb ? 63 - __builtin_clzll(mb) : -1;
+    if (pa >= 0.0f && (add_b == 0 || __builtin_ctzll(add_b) > hi_a)) return extend_prob(pa, add_b, fp);
+    if (pb >= 0.0f && (add_a == 0 || __builtin_ctzll(add_a) > hi_b)) return extend_prob(pb, add_a, fp);
+    return proof_prob(ma | mb, fp);
+}
+
+}  // namespace dol

@@ -173,8 +173,8 @@ dol_status launch_dtkp_init(int32_t batch, int32_t n_sym, int32_t k, int32_t n_f
                             const float *fact_prob, uint64_t *mask, float *pprob, float *prob, int64_t ld,
                             hipStream_t st);
 dol_status launch_dtkp_apply2(const dol_fn_table *f, int32_t batch, int32_t k, int32_t n_facts, const GroupMasks &gm,
-                              const float *fact_prob, const uint64_t *am, const uint64_t *bm, uint64_t *om, float *op,
-                              float *oprob, int64_t ldo, hipStream_t st);
+                              const float *fact_prob, const uint64_t *am, const float *ap, const uint64_t *bm,
+                              const float *bp, uint64_t *om, float *op, float *oprob, int64_t ldo, hipStream_t st);
 dol_status launch_dtkp_union(const UnionPlan *p, int32_t batch, int32_t k, const uint64_t *am, const float *ap,
                              const uint64_t *bm, const float *bp, uint64_t *om, float *op, float *oprob, int64_t ldo,
                              hipStream_t st);

@@ -229,6 +229,39 @@ class DtkpSumChain(Program):
         self.sample_ops = (self.n - 1) * B
 
 
+class DtkpSumChainFused(Program):
+    """Config 4 through dol_dtkp_fold_apply2: initialisation and every apply in one launch."""
+
+    def __init__(self, w, device="cuda", with_gradient=False):
+        p = w["p"]
+        self.n, self.batch, self.k = p.shape[0], p.shape[1], w["k"]
+        k, B = self.k, self.batch
+        sym = np.asarray(w["sym"], np.int32)
+        self.fact_prob = _dev(w["fact_prob"], device)
+        self.prov = dol.Prov(dol.DTKP, k, self.fact_prob, w["fact_group"])
+        self.digits = [dol.Dist(sym, torch.empty((B, sym.size), device=device)) for _ in range(self.n)]
+        self.facts = [10 * t + np.arange(10, dtype=np.int32) for t in range(self.n)]
+        self.tables, syms, slots = [], sym, 0
+        for t in range(1, self.n):
+            tab = sum_table_of(syms, sym)
+            tb = dol.FnTable.create_dense(tab)
+            self.tables.append(tb)
+            syms = tb.out_syms
+            slots += _n_tuples(tab) * (1 if t == 1 else k)      # proof pairs a tuple can offer
+        self.candidate_slots = B * slots
+        self.out = dol.Dist.empty(syms, B, device, k=k)
+        self.target = self.grad_fact = None
+        if with_gradient:
+            self.target = _dev((np.arange(B) % syms.size).astype(np.int32), device)
+            self.grad_fact = torch.empty_like(self.fact_prob)
+        self.fold = dol.DtkpFold(self.digits, self.facts, self.tables, self.out, target_col=self.target,
+                                 grad_fact_prob=self.grad_fact)
+        n_facts = self.fact_prob.shape[1]
+        self.launches = [Launch("dtkp_fold_kernel<%d>" % k, lambda: dol.dtkp_fold_apply2(self.fold, self.prov),
+                                B * (4 * n_facts + syms.size * (12 * k + 4)), 0, "fwd")]
+        self.sample_ops = (self.n - 1) * B
+
+
 class GridReach(Program):
     """Config 5: fixed-round single-source reachability on a 4-neighbour grid (App. B, transitive closure
     restricted to one source).  One round is one apply over (node, edge-or-stay) tuples: node u with edge

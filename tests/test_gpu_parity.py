@@ -195,6 +195,38 @@ def test_config4_dtkp_sum(gp, dol, batch, n, k):
     assert ei.value.status == 5
 
 
+@pytest.mark.parametrize("batch,n,k", [(1024, 5, 3), (130, 5, 1), (65, 4, 8), (7, 3, 5), (1, 2, 2), (3, 6, 2)])
+def test_config4_fused_dtkp_fold(gp, dol, batch, n, k):
+    """dol_dtkp_fold_apply2: initialisation + all applies (+ the gradient of -log Pr(target)) in one launch."""
+    w = W.config4(batch=batch, n_digits=n, k=k, seed=k + 10)
+    ref = OP.dtkp_sum_chain(w)
+    prog = gp.DtkpSumChainFused(w, with_gradient=True)
+    prog.step()
+    np.testing.assert_array_equal(prog.out.sym_ids, ref["syms"])
+    np.testing.assert_array_equal(host(prog.out.proof_mask).view(np.uint64), ref["mask"])
+    np.testing.assert_array_equal(host(prog.out.proof_prob), ref["pprob"])
+    assert_close(host(prog.out.prob), ref["prob"], "fused dtkp tag prob")
+    S = ref["syms"].size
+    target = np.arange(batch) % S
+    g = np.zeros((batch, S), np.float32)
+    g[np.arange(batch), target] = -1.0 / np.maximum(ref["prob"][np.arange(batch), target], np.float32(1.17549435e-38))
+    assert_close(host(prog.grad_fact), oracle.dtkp_prob_bwd(ref["mask"], w["fact_prob"], g), "fused dtkp gradient")
+    per_op = gp.DtkpSumChain(w)
+    per_op.step()
+    np.testing.assert_array_equal(host(prog.out.proof_mask), host(per_op.accs[-1].proof_mask))
+    np.testing.assert_array_equal(host(prog.out.proof_prob), host(per_op.accs[-1].proof_prob))
+    np.testing.assert_array_equal(host(prog.out.prob), host(per_op.accs[-1].prob))
+    # an explicit upstream gradient instead of a target; forward only
+    gsym = W.normal(5, batch * S).astype(np.float32).reshape(batch, S)
+    gf = torch.empty((batch, 10 * n), device="cuda")
+    out2 = dol.Dist.empty(ref["syms"], batch, k=k)
+    dol.dtkp_fold_apply2(dol.DtkpFold(prog.digits, prog.facts, prog.tables, out2, grad_out=dev(gsym), grad_fact_prob=gf), prog.prov)
+    assert_close(host(gf), oracle.dtkp_prob_bwd(ref["mask"], w["fact_prob"], gsym), "fused dtkp gradient, explicit")
+    out3 = dol.Dist.empty(ref["syms"], batch, k=k)
+    dol.dtkp_fold_apply2(dol.DtkpFold(prog.digits, prog.facts, prog.tables, out3), prog.prov)
+    np.testing.assert_array_equal(host(out3.proof_mask), host(prog.out.proof_mask))
+
+
 # ---------------------------------------------------------------- config 5
 
 @pytest.mark.parametrize("batch,side,rounds", [(256, 32, 64), (33, 7, 20), (2, 3, 5)])
