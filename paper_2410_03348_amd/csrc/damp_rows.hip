@@ -12,7 +12,7 @@
 namespace dol {
 
 constexpr int kRowsWG = 256;
-constexpr int kRowsTileFloats = 4096;          // floats of the widest tensor in one tile
+constexpr int kRowsTileFloats = 2048;          // floats of the widest tensor in one tile
 constexpr size_t kRowsLdsMax = 64 * 1024;
 
 // Copies `total` floats (src 16-byte aligned) into LDS: 16-byte pieces, four in flight per lane, then the tail.
