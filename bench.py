@@ -148,7 +148,7 @@ def main():
                          "auto = graph for steps of several launches, plain launches for a single-launch step (a graph "
                          "replay of one kernel only adds its own submission gap)")
     ap.add_argument("--chain", default="fused", choices=["fused", "per-op"],
-                    help="configs 2, 4 and 5: the fused entry points (dol_fold_apply2, dol_dtkp_fold_apply2, dol_iterate_*), or one dol_apply2 / "
+                    help="configs 2-5: the fused entry points (dol_fold_apply2, dol_filter_union, dol_dtkp_fold_apply2, dol_iterate_*), or one dol_apply2 / "
                          "dol_backward call per operator")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--repeats", type=int, default=20, help="back-to-back launches per event pair in the roofline pass")
@@ -177,6 +177,8 @@ def main():
             return GP.SumChainFused(wl)
         if args.chain == "fused" and cfg == 5:
             return GP.GridReachFused(wl)
+        if args.chain == "fused" and cfg == 3:
+            return GP.HashedPipelineFused(wl)
         if args.chain == "fused" and cfg == 4:
             return GP.DtkpSumChainFused(wl)
         return GP.make_program(cfg, wl)
@@ -196,7 +198,7 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": w.name, "config_id": cfg, "batch": prog.batch, "sample_ops_per_step": prog.sample_ops,
                    "launches_per_step": len(prog.launches), "mode": args.mode, "seed": args.seed,
-                   "chain": args.chain if cfg in (2, 4, 5) else None,
+                   "chain": args.chain if cfg in (2, 3, 4, 5) else None,
                    "algorithmic_bytes_per_step": prog.algorithmic_bytes()},
         "roofline": roof,
         "kernels": kernel_table(per_kernel),

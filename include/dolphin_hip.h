@@ -122,12 +122,22 @@ dol_status dol_filter(const dol_dist *d, const uint8_t *pred_mask, const dol_pro
 dol_status dol_union_plan(const dol_dist *a, const dol_dist *b, int32_t *n_out, int32_t *out_syms);
 dol_status dol_union(const dol_dist *a, const dol_dist *b, const dol_prov *prov, dol_dist *out, void *hip_stream);
 
+/* union(filter(d, pred_mask), c) in one launch, DAMP only (the apply_if-then-union step of the recursion of App. B,
+ * Fig. 9, once the Apply has run): the filtered Distribution is never materialised.  Same values as dol_filter
+ * followed by dol_union.  dol_filter_union_plan: resulting count and ids (out_syms has room for d->n_sym + c->n_sym).
+ * Backward: dol_backward with op = DOL_OP_FILTER_UNION, a = d, b = c, pred_mask and out as here; grad_a is
+ * [batch, d->ld] (dropped symbols get 0). */
+dol_status dol_filter_union_plan(const dol_dist *d, const uint8_t *pred_mask, const dol_dist *c, int32_t *n_out,
+                                 int32_t *out_syms);
+dol_status dol_filter_union(const dol_dist *d, const uint8_t *pred_mask, const dol_dist *c, const dol_prov *prov,
+                            dol_dist *out, void *hip_stream);
+
 /* DTKP natural initialisation (App. A.1): symbol i of `d` gets the single proof {fact_of_sym[i]}.
  * fact_of_sym: host [d->n_sym].  Writes proof_mask, proof_prob and prob. */
 dol_status dol_dtkp_init(dol_dist *d, const int32_t *fact_of_sym, const dol_prov *prov, void *hip_stream);
 
 /* One recorded forward operator, for the backward pass. */
-typedef enum { DOL_OP_APPLY2 = 0, DOL_OP_FILTER = 1, DOL_OP_UNION = 2 } dol_op_kind;
+typedef enum { DOL_OP_APPLY2 = 0, DOL_OP_FILTER = 1, DOL_OP_UNION = 2, DOL_OP_FILTER_UNION = 3 } dol_op_kind;
 typedef struct {
     int32_t op;                  /* dol_op_kind */
     const dol_dist *a;           /* first (or only) input, as passed to the forward call, tags unchanged since */
@@ -147,6 +157,7 @@ typedef struct {
  *   apply2: gh = grad_out * [pre <= 1];  grad_a[i] = sum_j gh[col(i,j)] * b[j];  grad_b[j] = sum_i gh[col(i,j)] * a[i]
  *   filter: grad_a[i] = grad_out[position of i] for kept symbols, else 0
  *   union:  common symbols pass grad_out * [a + b <= 1] to both sides, one-sided symbols pass grad_out.
+ *   filter-union: as union over the kept symbols of a; the dropped symbols of a get 0.
  * DTKP records return DOL_EUNSUPPORTED: see dol_dtkp_backward. */
 dol_status dol_backward(const dol_op_record *rec, const float *grad_out, float *grad_a, float *grad_b,
                         void *hip_stream);

@@ -25,7 +25,7 @@ if not os.path.exists(LIB_PATH):
 _lib = C.CDLL(LIB_PATH)
 
 DAMP, DTKP = 0, 1
-OP_APPLY2, OP_FILTER, OP_UNION = 0, 1, 2
+OP_APPLY2, OP_FILTER, OP_UNION, OP_FILTER_UNION = 0, 1, 2, 3
 MAX_K, MAX_FACTS, MAX_SYMBOLS = 8, 63, 65535
 ABSENT_PROOF = 0xFFFFFFFFFFFFFFFF
 STATUS_NAMES = {0: "DOL_OK", 1: "DOL_EINVAL", 2: "DOL_ESHAPE", 3: "DOL_ENOMEM", 4: "DOL_EHIP", 5: "DOL_EUNSUPPORTED"}
@@ -71,6 +71,8 @@ _lib.dol_filter_plan.argtypes = [C.POINTER(_Dist), _u8p, _i32p, _i32p]
 _lib.dol_filter.argtypes = [C.POINTER(_Dist), _u8p, C.POINTER(_Prov), C.POINTER(_Dist), C.c_void_p]
 _lib.dol_union_plan.argtypes = [C.POINTER(_Dist), C.POINTER(_Dist), _i32p, _i32p]
 _lib.dol_union.argtypes = [C.POINTER(_Dist), C.POINTER(_Dist), C.POINTER(_Prov), C.POINTER(_Dist), C.c_void_p]
+_lib.dol_filter_union_plan.argtypes = [C.POINTER(_Dist), _u8p, C.POINTER(_Dist), _i32p, _i32p]
+_lib.dol_filter_union.argtypes = [C.POINTER(_Dist), _u8p, C.POINTER(_Dist), C.POINTER(_Prov), C.POINTER(_Dist), C.c_void_p]
 _lib.dol_dtkp_init.argtypes = [C.POINTER(_Dist), _i32p, C.POINTER(_Prov), C.c_void_p]
 _lib.dol_backward.argtypes = [C.POINTER(_OpRecord), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
 _lib.dol_dtkp_backward.argtypes = [C.POINTER(_Dist), C.POINTER(_Prov), C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
@@ -237,6 +239,20 @@ def union_plan(a: Dist, b: Dist):
 
 def union(a: Dist, b: Dist, prov: Optional[Prov], out: Dist, stream=None):
     _check(_lib.dol_union(a.ref(), b.ref(), prov.ref() if prov else None, out.ref(), _stream(stream)))
+
+
+def filter_union_plan(d: Dist, pred_mask, c: Dist):
+    pm = np.ascontiguousarray(pred_mask, dtype=np.uint8)
+    n = C.c_int32()
+    syms = np.empty(max(d.n_sym + c.n_sym, 1), np.int32)
+    _check(_lib.dol_filter_union_plan(d.ref(), _ptr(pm, C.c_uint8), c.ref(), C.byref(n), _ptr(syms, C.c_int32)))
+    return syms[:n.value].copy()
+
+
+def filter_union(d: Dist, pred_mask, c: Dist, prov: Optional[Prov], out: Dist, stream=None):
+    pm = np.ascontiguousarray(pred_mask, dtype=np.uint8)
+    _check(_lib.dol_filter_union(d.ref(), _ptr(pm, C.c_uint8), c.ref(), prov.ref() if prov else None, out.ref(),
+                                 _stream(stream)))
 
 
 def dtkp_init(d: Dist, fact_of_sym, prov: Prov, stream=None):

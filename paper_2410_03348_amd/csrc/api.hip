@@ -124,6 +124,27 @@ dol_status dol_union(const dol_dist *a, const dol_dist *b, const dol_prov *prov,
                              out->proof_mask, out->proof_prob, out->prob, out->ld, st);
 }
 
+dol_status dol_filter_union(const dol_dist *d, const uint8_t *pred_mask, const dol_dist *c, const dol_prov *prov,
+                            dol_dist *out, void *hip_stream)
+{
+    if (is_dtkp(prov)) return fail(DOL_EUNSUPPORTED, "dol_filter_union is DAMP only: call dol_filter and dol_union");
+    if (!pred_mask) return fail(DOL_EINVAL, "pred_mask is NULL");
+    if (dol_status st = check_dist(d, "d", false, true, true)) return st;
+    if (dol_status st = check_dist(c, "c", false, true, true)) return st;
+    if (dol_status st = check_dist(out, "out", false, false, true)) return st;
+    if (d->batch != c->batch || d->batch != out->batch) return fail(DOL_ESHAPE, "batch sizes differ: %d, %d, %d", d->batch, c->batch, out->batch);
+    const UnionPlan *plan = nullptr;
+    if (dol_status st = get_filter_union_plan(d->n_sym, d->sym_ids, pred_mask, c->n_sym, c->sym_ids, &plan)) return st;
+    if (plan->n_out > DOL_MAX_SYMBOLS) return fail(DOL_EUNSUPPORTED, "the union has %d symbols, more than %d", plan->n_out, DOL_MAX_SYMBOLS);
+    if (out->n_sym != plan->n_out) return fail(DOL_ESHAPE, "out.n_sym = %d, the result has %d symbols", out->n_sym, plan->n_out);
+    if (out->sym_ids)
+        for (int32_t u = 0; u < plan->n_out; ++u)
+            if (out->sym_ids[u] != plan->out_syms[u]) return fail(DOL_EINVAL, "out.sym_ids[%d] = %d, the result has %d there", u, out->sym_ids[u], plan->out_syms[u]);
+    if (dol_status st = check_work(d->batch, plan->n_out)) return st;
+    return launch_damp_union_fwd(plan, d->batch, d->prob, d->ld, c->prob, c->ld, out->prob, out->ld,
+                                 static_cast<hipStream_t>(hip_stream));
+}
+
 dol_status dol_dtkp_init(dol_dist *d, const int32_t *fact_of_sym, const dol_prov *prov, void *hip_stream)
 {
     if (!is_dtkp(prov)) return fail(DOL_EINVAL, "dol_dtkp_init needs a DTKP provenance");
@@ -166,7 +187,7 @@ dol_status dol_backward(const dol_op_record *rec, const float *grad_out, float *
     if (dol_status st = check_prov(rec->prov, 0)) return st;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const dol_dist *a = rec->a, *b = rec->b, *out = rec->out;
-    if (dol_status s2 = check_dist(a, "rec.a", false, rec->op == DOL_OP_UNION, true)) return s2;
+    if (dol_status s2 = check_dist(a, "rec.a", false, rec->op == DOL_OP_UNION || rec->op == DOL_OP_FILTER_UNION, true)) return s2;
     if (dol_status s2 = check_dist(out, "rec.out", false, false, rec->op == DOL_OP_APPLY2)) return s2;
     if (a->batch != out->batch) return fail(DOL_ESHAPE, "batch sizes differ: %d, %d", a->batch, out->batch);
     if (!grad_out && out->batch > 0 && out->n_sym > 0) return fail(DOL_EINVAL, "grad_out is NULL");
@@ -204,6 +225,17 @@ dol_status dol_backward(const dol_op_record *rec, const float *grad_out, float *
         const UnionPlan *plan = nullptr;
         if (dol_status s2 = get_union_plan(a->n_sym, a->sym_ids, b->n_sym, b->sym_ids, &plan)) return s2;
         if (out->n_sym != plan->n_out) return fail(DOL_ESHAPE, "rec.out.n_sym = %d, the union has %d symbols", out->n_sym, plan->n_out);
+        if (dol_status s2 = check_work(a->batch, a->n_sym + b->n_sym)) return s2;
+        return launch_damp_union_bwd(plan, a->batch, a->prob, a->ld, b->prob, b->ld, grad_out, out->ld, grad_a, grad_b,
+                                     rec->accumulate, st);
+    }
+    case DOL_OP_FILTER_UNION: {
+        if (!rec->pred_mask) return fail(DOL_EINVAL, "rec.pred_mask is NULL");
+        if (dol_status s2 = check_dist(b, "rec.b", false, true, true)) return s2;
+        if (a->batch != b->batch) return fail(DOL_ESHAPE, "batch sizes differ: %d, %d", a->batch, b->batch);
+        const UnionPlan *plan = nullptr;
+        if (dol_status s2 = get_filter_union_plan(a->n_sym, a->sym_ids, rec->pred_mask, b->n_sym, b->sym_ids, &plan)) return s2;
+        if (out->n_sym != plan->n_out) return fail(DOL_ESHAPE, "rec.out.n_sym = %d, the result has %d symbols", out->n_sym, plan->n_out);
         if (dol_status s2 = check_work(a->batch, a->n_sym + b->n_sym)) return s2;
         return launch_damp_union_bwd(plan, a->batch, a->prob, a->ld, b->prob, b->ld, grad_out, out->ld, grad_a, grad_b,
                                      rec->accumulate, st);

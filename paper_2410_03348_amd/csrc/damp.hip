@@ -305,9 +305,12 @@ damp_union_bwd_kernel(Rows R, int32_t na, const int32_t *__restrict__ ia, const 
         const bool is_a = x < na;
         if (is_a ? !ga : !gb) return;
         const int32_t c = is_a ? ca[x] : cb[x - na];
-        const int32_t i = ia[c], j = ib[c];
-        float gv = g[s * ldg + c];
-        if (i >= 0 && j >= 0 && !(a[s * lda + i] + b[s * ldb + j] <= 1.0f)) gv = 0.0f;
+        float gv = 0.0f;
+        if (c >= 0) {                       // -1: a symbol the fused filter drops
+            const int32_t i = ia[c], j = ib[c];
+            gv = g[s * ldg + c];
+            if (i >= 0 && j >= 0 && !(a[s * lda + i] + b[s * ldb + j] <= 1.0f)) gv = 0.0f;
+        }
         if (is_a) ga[s * lda + x] = (accumulate & 1) ? ga[s * lda + x] + gv : gv;
         else gb[s * ldb + (x - na)] = (accumulate & 2) ? gb[s * ldb + (x - na)] + gv : gv;
     });

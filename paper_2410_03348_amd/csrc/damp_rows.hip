@@ -159,7 +159,10 @@ damp_rows_union_bwd_kernel(RowTiles T, int32_t na, int32_t nb, int32_t n_out, fl
             const float gv = tg[r * n_out + c];
             return i >= 0 && j >= 0 && !(ta[r * na + i] + tb[r * nb + j] <= 1.0f) ? 0.0f : gv;
         };
-        if (ga) emit_flat(ga + s0 * na, rows, na, inv_na, (accumulate & 1) != 0, [&](int r, int x) { return gated(r, ca[x]); });
+        if (ga) emit_flat(ga + s0 * na, rows, na, inv_na, (accumulate & 1) != 0, [&](int r, int x) {
+            const int32_t c = ca[x];                // -1: a symbol the fused filter drops
+            return c >= 0 ? gated(r, c) : 0.0f;
+        });
         if (gb) emit_flat(gb + s0 * nb, rows, nb, inv_nb, (accumulate & 2) != 0, [&](int r, int x) { return gated(r, cb[x]); });
     }
 }

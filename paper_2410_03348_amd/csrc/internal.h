@@ -106,13 +106,16 @@ struct UnionPlan {
     int32_t na = 0, nb = 0, n_out = 0;
     std::vector<int32_t> out_syms;
     DevArray<int32_t> d_ia, d_ib;         // [n_out] position in a / b or -1
-    DevArray<int32_t> d_ca, d_cb;         // [na] / [nb] output column of each input position
+    DevArray<int32_t> d_ca, d_cb;         // [na] / [nb] output column of each input position (-1: none, filter-union only)
 };
 
 // Content-addressed caches: the same predicate / symbol lists give the same plan object.
 // Returned pointers stay valid until the library is unloaded.
 dol_status get_filter_plan(int32_t n, const uint8_t *pred, const FilterPlan **plan);
 dol_status get_union_plan(int32_t na, const int32_t *sa, int32_t nb, const int32_t *sb, const UnionPlan **plan);
+// union(filter(d, pred), c) as one merge plan: na = symbols of d, ia points into d, ca is -1 for dropped symbols.
+dol_status get_filter_union_plan(int32_t n, const int32_t *sd, const uint8_t *pred, int32_t nc, const int32_t *sc,
+                                 const UnionPlan **plan);
 
 // Masks of the exclusion groups that hold at least two facts (kernel argument, by value).
 struct GroupMasks {

@@ -257,6 +257,51 @@ dol_status get_union_plan(int32_t na, const int32_t *sa, int32_t nb, const int32
     return DOL_OK;
 }
 
+static Cache<UnionPlan> g_filter_union_cache;
+
+// union(filter(d, pred), c) as ONE merge plan over the unfiltered operand: ia[u] is a position in d (of a kept
+// symbol) or -1, ca[x] is the output column of d's symbol x or -1 when the predicate drops it.
+dol_status get_filter_union_plan(int32_t n, const int32_t *sd, const uint8_t *pred, int32_t nc, const int32_t *sc,
+                                 const UnionPlan **plan)
+{
+    int device = 0;
+    (void)hipGetDevice(&device);
+    std::vector<uint8_t> norm(static_cast<size_t>(n));
+    for (int32_t i = 0; i < n; ++i) norm[i] = pred[i] ? 1 : 0;
+    std::vector<unsigned char> key = make_key(device, {{norm.data(), norm.size()},
+                                                       {sd, sizeof(int32_t) * static_cast<size_t>(n)},
+                                                       {sc, sizeof(int32_t) * static_cast<size_t>(nc)}});
+    const uint64_t h = fnv1a(key.data(), key.size());
+    std::lock_guard<std::mutex> lock(g_filter_union_cache.mu);
+    if ((*plan = g_filter_union_cache.find(h, key)) != nullptr) return DOL_OK;
+
+    std::unique_ptr<UnionPlan> p(new (std::nothrow) UnionPlan);
+    if (!p) return fail(DOL_ENOMEM, "out of host memory");
+    p->na = n;
+    p->nb = nc;
+    std::vector<int32_t> ia, ib, ca(static_cast<size_t>(n), -1), cb(static_cast<size_t>(nc));
+    int32_t i = 0, j = 0;
+    while (true) {                          // ascending merge of the kept ids of d with the ids of c
+        while (i < n && !norm[i]) ++i;
+        if (i >= n && j >= nc) break;
+        const int32_t col = static_cast<int32_t>(ia.size());
+        if (j >= nc || (i < n && sd[i] < sc[j])) {
+            p->out_syms.push_back(sd[i]); ia.push_back(i); ib.push_back(-1); ca[i++] = col;
+        } else if (i >= n || sc[j] < sd[i]) {
+            p->out_syms.push_back(sc[j]); ia.push_back(-1); ib.push_back(j); cb[j++] = col;
+        } else {
+            p->out_syms.push_back(sd[i]); ia.push_back(i); ib.push_back(j); ca[i++] = col; cb[j++] = col;
+        }
+    }
+    p->n_out = static_cast<int32_t>(ia.size());
+    hipError_t e;
+    if ((e = p->d_ia.upload(ia)) != hipSuccess || (e = p->d_ib.upload(ib)) != hipSuccess ||
+        (e = p->d_ca.upload(ca)) != hipSuccess || (e = p->d_cb.upload(cb)) != hipSuccess)
+        return hip_fail(e, "uploading the filter-union plan");
+    *plan = g_filter_union_cache.insert(h, std::move(key), std::move(p));
+    return DOL_OK;
+}
+
 struct I32Array {
     DevArray<int32_t> d;
 };
@@ -362,6 +407,32 @@ dol_status dol_filter_plan(const dol_dist *d, const uint8_t *pred_mask, int32_t 
             if (out_syms) out_syms[m] = d->sym_ids[i];
             ++m;
         }
+    *n_out = m;
+    return DOL_OK;
+}
+
+dol_status dol_filter_union_plan(const dol_dist *d, const uint8_t *pred_mask, const dol_dist *c, int32_t *n_out,
+                                 int32_t *out_syms)
+{
+    if (!d || !c || !n_out || !pred_mask) return dol::fail(DOL_EINVAL, "NULL argument");
+    if (d->n_sym < 0 || c->n_sym < 0 || d->n_sym > DOL_MAX_SYMBOLS || c->n_sym > DOL_MAX_SYMBOLS)
+        return dol::fail(DOL_ESHAPE, "n_sym outside 0..%d", DOL_MAX_SYMBOLS);
+    if ((d->n_sym > 0 && !d->sym_ids) || (c->n_sym > 0 && !c->sym_ids)) return dol::fail(DOL_EINVAL, "sym_ids is NULL");
+    for (int32_t i = 1; i < d->n_sym; ++i)
+        if (d->sym_ids[i - 1] >= d->sym_ids[i]) return dol::fail(DOL_EINVAL, "d.sym_ids not strictly ascending at %d", i);
+    for (int32_t j = 1; j < c->n_sym; ++j)
+        if (c->sym_ids[j - 1] >= c->sym_ids[j]) return dol::fail(DOL_EINVAL, "c.sym_ids not strictly ascending at %d", j);
+    int32_t i = 0, j = 0, m = 0;
+    while (true) {
+        while (i < d->n_sym && !pred_mask[i]) ++i;
+        if (i >= d->n_sym && j >= c->n_sym) break;
+        int32_t id;
+        if (j >= c->n_sym || (i < d->n_sym && d->sym_ids[i] < c->sym_ids[j])) id = d->sym_ids[i++];
+        else if (i >= d->n_sym || c->sym_ids[j] < d->sym_ids[i]) id = c->sym_ids[j++];
+        else { id = d->sym_ids[i++]; ++j; }
+        if (out_syms) out_syms[m] = id;
+        ++m;
+    }
     *n_out = m;
     return DOL_OK;
 }

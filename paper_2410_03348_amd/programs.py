@@ -201,6 +201,26 @@ class HashedPipeline(Program):
         self.sample_ops = 6 * B
 
 
+class HashedPipelineFused(HashedPipeline):
+    """Config 3 with filter and union as one launch each way (dol_filter_union): the filtered Distribution and its
+    gradient are never materialised."""
+
+    def __init__(self, w, device="cuda"):
+        super().__init__(w, device)
+        B = self.batch
+        assert list(dol.filter_union_plan(self.o1, self.pred, self.p2)) == list(self.o3.sym_ids)
+        self.rec23 = dol.OpRecord(dol.OP_FILTER_UNION, self.o1, self.p2, self.o3, pred_mask=self.pred)
+        n1, n3, np2 = self.o1.n_sym, self.o3.n_sym, self.p2.n_sym
+        self.launches = [
+            self.launches[0],
+            Launch("damp_rows_union_fwd_kernel", lambda: dol.filter_union(self.o1, self.pred, self.p2, None, self.o3),
+                   4 * B * (n1 + np2 + n3), 0, "fwd"),
+            Launch("damp_rows_union_bwd_kernel", lambda: dol.backward(self.rec23, self.g3, self.g1, self.gp2),
+                   4 * B * (n3 + 2 * n1 + 2 * np2), 0, "bwd"),
+            self.launches[-1],
+        ]
+
+
 class DtkpSumChain(Program):
     """Config 4: the sum fold under DTKP-AM with k proofs per tag; fact 10*n+d says "digit n is d"."""
 

@@ -162,6 +162,64 @@ def test_config3_hashed_pipeline(gp, batch, na, nb, n_out):
     assert_close(host(prog.gb), ref["gb"], "apply bwd b")
 
 
+@pytest.mark.parametrize("batch,na,nb,n_out", [(16384, 64, 64, 256), (1000, 64, 64, 256), (129, 17, 33, 40), (3, 5, 2, 300)])
+def test_config3_fused_filter_union(gp, batch, na, nb, n_out):
+    """dol_filter_union and its backward: the same results as filter then union, without the filtered tensor."""
+    w = W.config3(batch=batch, na=na, nb=nb, n_out=n_out, seed=9)
+    ref = OP.hashed_pipeline_fwd_bwd(w)
+    prog = gp.HashedPipelineFused(w)
+    prog.step()
+    np.testing.assert_array_equal(prog.o3.sym_ids, ref["s3"])
+    assert_close(host(prog.o3.prob), ref["o3"], "filter-union")
+    assert_close(host(prog.gp2), ref["gp2"], "filter-union bwd b")
+    assert_close(host(prog.g1), ref["g1"], "filter-union bwd a")
+    assert_close(host(prog.ga), ref["ga"], "apply bwd a")
+    assert_close(host(prog.gb), ref["gb"], "apply bwd b")
+    per_op = gp.HashedPipeline(w)
+    per_op.step()
+    np.testing.assert_array_equal(host(prog.o3.prob), host(per_op.o3.prob))
+    np.testing.assert_array_equal(host(prog.g1), host(per_op.g1))
+    np.testing.assert_array_equal(host(prog.gp2), host(per_op.gp2))
+
+
+def test_filter_union_edge_cases(dol):
+    """Everything dropped, nothing dropped, disjoint and empty second operand, padded rows, clamped sums, accumulate."""
+    B = 37
+    sd = np.array([1, 4, 6, 8, 9], np.int32)
+    sc = np.array([0, 4, 9, 12], np.int32)
+    a = (W.uniform01(1, B * 5) * 0.9).astype(np.float32).reshape(B, 5)
+    c = (W.uniform01(2, B * 4) * 0.9).astype(np.float32).reshape(B, 4)
+    g_all = np.abs(W.normal(3, B * 9)).astype(np.float32).reshape(B, 9)
+    for pred in ([1, 1, 1, 1, 1], [0, 0, 0, 0, 0], [0, 1, 0, 1, 1], [1, 0, 1, 0, 0]):
+        pred = np.array(pred, np.uint8)
+        kept, fa = oracle.filter_plan(sd, pred)[0], np.ascontiguousarray(a[:, pred.astype(bool)])
+        usyms, ia, ib = oracle.union_plan(kept, sc)
+        want = oracle.damp_union_fwd(ia, ib, fa, c)
+        ta = torch.zeros((B, 8), device="cuda"); ta[:, :5] = dev(a)            # padded rows
+        da, dc = dol.Dist(sd, ta[:, :5]), dol.Dist(sc, dev(c))
+        np.testing.assert_array_equal(dol.filter_union_plan(da, pred, dc), usyms)
+        out = dol.Dist.empty(usyms, B)
+        dol.filter_union(da, pred, dc, None, out)
+        assert_close(host(out.prob), want, "filter-union %s" % pred)
+        np.testing.assert_array_equal(host(out.prob) == 1.0, want == 1.0)
+        g = g_all[:, :usyms.size]
+        wfa, wc = oracle.damp_union_bwd(ia, ib, fa, c, g)
+        wa = np.zeros((B, 5), np.float32); wa[:, pred.astype(bool)] = wfa
+        ga, gc = torch.full((B, 8), 3.0, device="cuda"), torch.zeros((B, 4), device="cuda")
+        rec = dol.OpRecord(dol.OP_FILTER_UNION, da, dc, out, pred_mask=pred)
+        dol.backward(rec, dev(g), ga, gc)
+        assert_close(host(ga)[:, :5], wa, "filter-union bwd a %s" % pred)
+        assert np.all(host(ga)[:, 5:] == 3.0)
+        assert_close(host(gc), wc, "filter-union bwd c %s" % pred)
+        dol.backward(dol.OpRecord(dol.OP_FILTER_UNION, da, dc, out, pred_mask=pred, accumulate=2), dev(g), None, gc)
+        assert_close(host(gc), 2.0 * wc.astype(np.float64), "filter-union bwd c accumulated")
+    empty = dol.Dist(np.zeros(0, np.int32), torch.zeros((B, 0), device="cuda"))
+    da = dol.Dist(sd, dev(a))
+    out = dol.Dist.empty(dol.filter_union_plan(da, np.ones(5, np.uint8), empty), B)
+    dol.filter_union(da, np.ones(5, np.uint8), empty, None, out)
+    np.testing.assert_array_equal(host(out.prob), a)
+
+
 # ---------------------------------------------------------------- config 4
 
 @pytest.mark.parametrize("batch,n,k", [(1024, 5, 3), (130, 5, 1), (65, 4, 8), (7, 3, 5), (1, 2, 2)])
