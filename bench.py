@@ -4,7 +4,7 @@
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--batch B] [--mode auto|graph|eager]
 
 A step is one pass of a whole program (all its operator launches, forward and backward) over one batch of
-seeded synthetic input already resident in HBM.  The default program is BASELINE config 2, the Sum-15 DAMP
+seeded synthetic input already resident in HBM.  The default program is workload 2, the Sum-15 DAMP
 chain forward + backward at B=4096.  Prints ONE JSON line: whole-job sample-ops/s, the roofline of the
 dominant kernel (measured live with HIP events on the launch stream), the same at a B-scaled variant of the
 workload, and the CPU oracle timed on this host's cores.
@@ -156,8 +156,8 @@ def main():
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="budget of the cpu_baseline leg (0 = skip)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py measures one GPU: the path has no multi-GPU step (samples are independent; see DESIGN.md). "
-              "Run with --gpus 1.", file=sys.stderr)
+        print("bench.py measures one GPU: the path has no multi-GPU step (samples are independent, so a job shards by "
+              "splitting the batch and replicating the symbol tables, with no exchange).  Run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
 
     import torch

@@ -683,12 +683,24 @@ def test_dtkp_general_conjunction_union_filter(dol):
     np.testing.assert_array_equal(host(fo.prob), fpr)
 
 
-def test_hip_graph_replay_matches_eager(gp):
-    """The chain issues only asynchronous launches, so it can be captured; replays equal the eager result."""
-    w = W.config2(batch=512, n_digits=6, seed=5)
-    prog = gp.SumChain(w)
+@pytest.mark.parametrize("which", ["chain", "fold", "hashed", "hashed-fused", "dtkp-fold", "reach-fused"])
+def test_hip_graph_replay_matches_eager(gp, which):
+    """Every entry point issues only asynchronous launches once its symbol-side plans exist, so a whole step can be
+    captured; replays (with eager work and synchronisations between them) equal the eager result."""
+    if which == "chain":
+        prog = gp.SumChain(W.config2(batch=512, n_digits=6, seed=5)); key = lambda: prog.grad_p
+    elif which == "fold":
+        prog = gp.SumChainFused(W.config2(batch=512, n_digits=6, seed=5)); key = lambda: prog.grad_p
+    elif which == "hashed":
+        prog = gp.HashedPipeline(W.config3(batch=320, seed=5)); key = lambda: prog.ga
+    elif which == "hashed-fused":
+        prog = gp.HashedPipelineFused(W.config3(batch=320, seed=5)); key = lambda: prog.ga
+    elif which == "dtkp-fold":
+        prog = gp.DtkpSumChainFused(W.config4(batch=200, seed=5), with_gradient=True); key = lambda: prog.grad_fact
+    else:
+        prog = gp.GridReachFused(W.config5(batch=16, side=8, rounds=12, seed=5)); key = lambda: prog.grad_p
     prog.step()
-    eager = host(prog.grad_p).copy()
+    eager = host(key()).copy()
     s = torch.cuda.Stream()
     s.wait_stream(torch.cuda.current_stream())
     with torch.cuda.stream(s):
@@ -698,7 +710,7 @@ def test_hip_graph_replay_matches_eager(gp):
     with torch.cuda.graph(graph):
         prog.step()
     for _ in range(3):
-        prog.grad_p.fill_(-1.0)
+        key().fill_(-1.0)
         torch.cuda.synchronize()
         graph.replay()
-        np.testing.assert_array_equal(host(prog.grad_p), eager)
+        np.testing.assert_array_equal(host(key()), eager)
