@@ -18,7 +18,7 @@
 
 namespace dol {
 
-constexpr int kLdsFwdWG = 512, kLdsBwdWG = 1024;   // threads per workgroup
+constexpr int kLdsFwdWG = 1024, kLdsBwdWG = 1024;   // threads per workgroup
 constexpr int kLdsTile = 64;                     // samples per tile = floats per LDS row
 constexpr size_t kLdsBytesMax = 160 * 1024;
 constexpr int kLdsMaxSym = 128;                  // most symbols of one operand
