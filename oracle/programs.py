@@ -96,6 +96,33 @@ def dtkp_sum_chain(w):
     return dict(syms=syms, mask=m, pprob=pp, prob=pr, stages=stages)
 
 
+def transitive_closure_fwd_bwd(w, join_triples):
+    """The recursion of App. B, Fig. 9: new = apply_if(paths, edges, join); merged = union(paths, new); stop when the
+    merge adds no symbol and return it.  Then the reverse sweep from the upstream gradient over the final paths.
+    `join_triples(path_ids, edge_ids, n_nodes)` is the symbol-side table of one step (workloads)."""
+    n, eids, p = w["n_nodes"], np.asarray(w["edge_ids"], np.int32), w["p"]
+    paths, tags, tape = eids, p, []
+    while True:
+        tri = join_triples(paths, eids, n)
+        nsyms, new = damp_apply2_fwd(tri, paths.size, eids.size, tags, p)
+        msyms, ia, ib = union_plan(paths, nsyms)
+        merged = damp_union_fwd(ia, ib, tags, new)
+        tape.append((tri, paths.size, tags, new, ia, ib))
+        grew = msyms.size != paths.size
+        paths, tags = msyms, merged
+        if not grew:
+            break
+    g = np.ascontiguousarray(w["g"][:, paths])
+    ge = np.zeros(p.shape, np.float64)
+    for tri, n_paths, t_in, new, ia, ib in reversed(tape):
+        g_paths, g_new = damp_union_bwd(ia, ib, t_in, new, g)
+        ga, gb = damp_apply2_bwd(tri, n_paths, eids.size, t_in, p, g_new)
+        ge += gb
+        g = (g_paths.astype(np.float64) + ga).astype(np.float32)
+    ge += g                                  # the first paths are the edges themselves
+    return dict(syms=paths, out=tags, rounds=len(tape), grad_p=ge.astype(np.float32))
+
+
 def grid_reach_fwd_bwd(w):
     """Config 5: fixed-round single-source reachability and its backward."""
     side = w["side"]

@@ -352,5 +352,53 @@ class GridReachFused(Program):
         self.sample_ops = 2 * R * B
 
 
+class TransitiveClosure(Program):
+    """All-pairs transitive closure (App. B, Fig. 9): new = apply_if(paths, edges, join), merged = union(paths, new),
+    repeated until the merge adds no symbol.  The symbol side (which paths exist after each step, the join table of
+    each step) is worked out on the host when the program is built; a step of the program is then a fixed list of
+    dol_apply2 / dol_union launches followed by the reverse sweep of dol_backward calls, in which a Distribution
+    used twice (paths feed both the join and the union) sums the gradients of its uses through the accumulate flags."""
+
+    def __init__(self, w, join_triples, device="cuda"):
+        n, B = w["n_nodes"], w["p"].shape[0]
+        self.batch = B
+        eids = np.asarray(w["edge_ids"], np.int32)
+        self.edges = dol.Dist(eids, _dev(w["p"], device))
+        paths, self.rounds, fwd = self.edges, [], []
+        while True:
+            tri = join_triples(paths.sym_ids, eids, n)
+            table = dol.FnTable.create_sparse(paths.n_sym, eids.size, *tri)
+            new = dol.Dist.empty(table.out_syms, B, device)
+            merged = dol.Dist.empty(dol.union_plan(paths, new), B, device)
+            self.rounds.append((paths, table, new, merged, int(tri[0].size)))
+            fwd.append(_apply_fwd(paths, self.edges, table, new, int(tri[0].size)))
+            fwd.append(Launch("damp_union_fwd", lambda a=paths, b=new, o=merged: dol.union(a, b, None, o),
+                              4 * B * (paths.n_sym + new.n_sym + merged.n_sym), 0, "fwd"))
+            grew = merged.n_sym != paths.n_sym
+            paths = merged
+            if not grew:
+                break
+        self.out = paths
+        self.g_out = _dev(np.ascontiguousarray(w["g"][:, paths.sym_ids]), device)
+        self.grad_p = torch.empty_like(self.edges.prob)
+        bwd, g, first = [], self.g_out, True
+        for a, table, new, merged, n_tup in reversed(self.rounds):
+            g_a = torch.empty((B, a.n_sym), dtype=torch.float32, device=device)
+            g_new = torch.empty((B, new.n_sym), dtype=torch.float32, device=device)
+            rec_u = dol.OpRecord(dol.OP_UNION, a, new, merged)
+            rec_a = dol.OpRecord(dol.OP_APPLY2, a, self.edges, new, f=table, accumulate=1 if first else 3)
+            bwd.append(Launch("damp_union_bwd", lambda r=rec_u, g=g, x=g_a, y=g_new: dol.backward(r, g, x, y),
+                              4 * B * (merged.n_sym + 2 * a.n_sym + 2 * new.n_sym), 0, "bwd"))
+            bwd.append(_apply_bwd(rec_a, g_new, g_a, self.grad_p, n_tup))
+            g, first = g_a, False
+        # the first paths are the edges themselves: their gradient joins the edges' (an all-true filter's backward adds)
+        keep_all = np.ones(self.edges.n_sym, np.uint8)
+        rec_id = dol.OpRecord(dol.OP_FILTER, self.edges, None, self.edges, pred_mask=keep_all, accumulate=1)
+        bwd.append(Launch("damp_rows_gather_kernel", lambda r=rec_id, g=g: dol.backward(r, g, self.grad_p, None),
+                          4 * B * 3 * self.edges.n_sym, 0, "bwd"))
+        self.launches = fwd + bwd
+        self.sample_ops = 4 * len(self.rounds) * B
+
+
 def make_program(config_id: int, workload, device="cuda") -> Program:
     return {1: Sum2Forward, 2: SumChain, 3: HashedPipeline, 4: DtkpSumChain, 5: GridReach}[config_id](workload, device)

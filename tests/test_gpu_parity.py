@@ -2,6 +2,8 @@
 
 Floating-point bar: |gpu - oracle| <= 1e-7 + 1e-5 * |oracle| (oracle accumulates in float64).
 Integer / index / proof-mask bar: bit-exact.
+Stress cases with unnormalised tags use a one-signed upstream gradient: a float32 sum of mixed-sign terms of order 1
+cannot meet an absolute 1e-7 where it cancels to ~0, whatever the kernel.
 """
 import numpy as np
 import pytest
@@ -325,6 +327,22 @@ def test_config5_fused_iteration(gp, dol, batch, side, rounds):
                            dol.Dist(np.arange(3), torch.ones((2, 3), device="cuda")), f, 2,
                            torch.empty((3, 2, 4), device="cuda"))
     assert ei.value.status == 5
+
+
+@pytest.mark.parametrize("batch,n_nodes,n_edges,scale", [(64, 10, 16, 0.5), (130, 12, 30, 1.0), (3, 5, 4, 0.9), (70, 16, 40, 0.3)])
+def test_transitive_closure_program(gp, batch, n_nodes, n_edges, scale):
+    """The recursion of App. B, Fig. 9 over a random directed graph: symbol sets grow step by step, tags pile up
+    towards the clamp, gradients of Distributions used twice are summed with the accumulate flags."""
+    w = W.closure_workload(batch=batch, n_nodes=n_nodes, n_edges=n_edges, scale=scale, seed=n_nodes)
+    w.arrays["g"] = np.abs(w["g"])         # one-signed upstream gradient: see the tolerance note in the module docstring
+    ref = OP.transitive_closure_fwd_bwd(w, W.join_triples)
+    prog = gp.TransitiveClosure(w, W.join_triples)
+    prog.step()
+    assert len(prog.rounds) == ref["rounds"]
+    np.testing.assert_array_equal(prog.out.sym_ids, ref["syms"])
+    assert_close(host(prog.out.prob), ref["out"], "closure tags")
+    np.testing.assert_array_equal(host(prog.out.prob) == 1.0, ref["out"] == 1.0)
+    assert_close(host(prog.grad_p), ref["grad_p"], "closure gradient of the edge probabilities")
 
 
 @pytest.mark.parametrize("long_a,long_b", [((5, 9), (0, 1, 2)), ((5,), (0,)), ((), (0, 1, 2))])

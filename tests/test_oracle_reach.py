@@ -134,3 +134,63 @@ def test_round_equals_apply_with_stay_symbol():
         gr, gb = oracle.damp_apply2_bwd(tri, n, E + 1, hist[t], pe, gr)
         acc += gb[:, :E]
     np.testing.assert_allclose(acc, gp, rtol=1e-5, atol=1e-7)
+
+
+# ---------------------------------------------------------------- all-pairs transitive closure (App. B, Fig. 9)
+
+def _closure_matrices(w):
+    n, B = w["n_nodes"], w["p"].shape[0]
+    E = np.zeros((B, n, n))
+    E[:, w["edge_u"], w["edge_v"]] = w["p"].astype(np.float64)
+    return E
+
+
+def test_closure_symbols_are_the_boolean_closure_and_tags_a_matrix_recurrence():
+    """Without clamping one step is P <- P + P.E on the matrices of path and edge tags, so after R steps
+    P = E (I + E)^R; the symbols are the reachable pairs (Warshall)."""
+    from oracle import programs as P
+    w = W.closure_workload(batch=5, n_nodes=9, n_edges=12, scale=0.05, seed=3)
+    res = P.transitive_closure_fwd_bwd(w, W.join_triples)
+    n = w["n_nodes"]
+    reach = np.zeros((n, n), bool)
+    reach[w["edge_u"], w["edge_v"]] = True
+    for k in range(n):
+        reach |= reach[:, [k]] & reach[[k], :]
+    np.testing.assert_array_equal(res["syms"], np.flatnonzero(reach.ravel()))
+    E = _closure_matrices(w)
+    want = E @ np.linalg.matrix_power(np.eye(n)[None] + E, res["rounds"])
+    assert want.max() < 1.0
+    got = np.zeros_like(want).reshape(5, -1)
+    got[:, res["syms"]] = res["out"]
+    np.testing.assert_allclose(got.reshape(want.shape), want, rtol=2e-6, atol=1e-12)
+    # the last step adds no symbol, every earlier one does
+    assert 2 <= res["rounds"] <= n
+
+
+def test_closure_gradient_matches_finite_differences_of_the_matrix_recurrence():
+    from oracle import programs as P
+    w = W.closure_workload(batch=2, n_nodes=6, n_edges=8, scale=0.05, seed=4)
+    res = P.transitive_closure_fwd_bwd(w, W.join_triples)
+    n, R = w["n_nodes"], res["rounds"]
+    g = np.zeros((2, n * n))
+    g[:, res["syms"]] = w["g"][:, res["syms"]]
+
+    def loss(s, pe):
+        E = np.zeros((n, n)); E[w["edge_u"], w["edge_v"]] = pe
+        return float((g[s].reshape(n, n) * (E @ np.linalg.matrix_power(np.eye(n) + E, R))).sum())
+
+    for s in range(2):
+        p0 = w["p"][s].astype(np.float64)
+        for e in range(p0.size):
+            hi, lo = p0.copy(), p0.copy()
+            hi[e] += 1e-6; lo[e] -= 1e-6
+            fd = (loss(s, hi) - loss(s, lo)) / 2e-6
+            assert abs(res["grad_p"][s, e] - fd) <= 1e-6 + 2e-5 * abs(fd), (s, e, res["grad_p"][s, e], fd)
+
+
+def test_closure_with_clamping_stays_in_range():
+    from oracle import programs as P
+    w = W.closure_workload(batch=4, n_nodes=8, n_edges=20, scale=1.0, seed=5)
+    res = P.transitive_closure_fwd_bwd(w, W.join_triples)
+    assert res["out"].min() >= 0.0 and res["out"].max() == 1.0       # dense graph: re-derivations pile up to the clamp
+    assert np.isfinite(res["grad_p"]).all()

@@ -110,6 +110,40 @@ def grid_reach_triples(side: int):
     return i[order].astype(np.int32), j[order].astype(np.int32), o[order].astype(np.int32)
 
 
+def random_digraph(seed: int, n_nodes: int, n_edges: int):
+    """n_edges distinct directed edges (u != v) on n_nodes nodes, as ascending symbol ids u * n_nodes + v and the
+    (u, v) arrays in that order."""
+    ids, k = [], 0
+    while len(ids) < n_edges:
+        x = int(splitmix64(seed, np.array([k], dtype=np.uint64))[0] % np.uint64(n_nodes * n_nodes))
+        k += 1
+        if x // n_nodes != x % n_nodes and x not in ids:
+            ids.append(x)
+    ids = np.array(sorted(ids), np.int32)
+    return ids, (ids // n_nodes).astype(np.int32), (ids % n_nodes).astype(np.int32)
+
+
+def join_triples(path_ids, edge_ids, n_nodes: int):
+    """Symbol-side table of one step of a transitive closure: path (x, y) at position i joined with edge (y, z)
+    at position j yields the path with id x * n_nodes + z.  Tuples in ascending (i, j)."""
+    ti, tj, to = [], [], []
+    for i, p in enumerate(np.asarray(path_ids).tolist()):
+        for j, e in enumerate(np.asarray(edge_ids).tolist()):
+            if p % n_nodes == e // n_nodes:
+                ti.append(i); tj.append(j); to.append((p // n_nodes) * n_nodes + e % n_nodes)
+    return np.array(ti, np.int32), np.array(tj, np.int32), np.array(to, np.int32)
+
+
+def closure_workload(batch: int = 64, n_nodes: int = 10, n_edges: int = 16, scale: float = 0.5, seed: int = 0) -> "Workload":
+    """A seeded random directed graph with one probability per edge and sample, and an upstream gradient over the
+    n_nodes^2 possible paths (the program uses the columns of the paths it derives)."""
+    ids, u, v = random_digraph(_sd(seed, 6, 0), n_nodes, n_edges)
+    p = (uniform01(_sd(seed, 6, 1), batch * n_edges) * scale).astype(np.float32).reshape(batch, n_edges)
+    g = normal(_sd(seed, 6, 2), batch * n_nodes * n_nodes).astype(np.float32).reshape(batch, n_nodes * n_nodes)
+    return Workload("transitive_closure_damp_fwd_bwd", dict(batch=batch, n_nodes=n_nodes, n_edges=n_edges),
+                    dict(p=p, g=g, edge_ids=ids, edge_u=u, edge_v=v))
+
+
 @dataclass
 class Workload:
     """A named bundle of input arrays plus the scalar parameters of a config."""
