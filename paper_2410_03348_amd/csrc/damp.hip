@@ -82,10 +82,9 @@ dol_status launch_damp_apply2_fwd(const dol_fn_table *f, int32_t batch, const fl
 {
     if (batch == 0 || f->n_out == 0) return DOL_OK;
     if (conv_path_ok(f)) return launch_damp_conv_fwd(f, batch, a, lda, b, ldb, out, ldo, st);
-    int32_t done = 0;
+    bool done = false;
     if (dol_status s2 = launch_damp_lds_fwd(f, batch, a, lda, b, ldb, out, ldo, st, &done)) return s2;
-    if (done == batch) return DOL_OK;
-    batch -= done, a += done * lda, b += done * ldb, out += done * ldo;
+    if (done) return DOL_OK;
     const Rows R = rows_of(batch, f->n_out);
     hipLaunchKernelGGL(damp_apply2_fwd_kernel, dim3(R.grid), dim3(kThreads), 0, st, R, f->col_ptr.ptr, f->col_ij.ptr, a,
                        lda, b, ldb, out, ldo);
@@ -179,12 +178,9 @@ dol_status launch_damp_apply2_bwd(const dol_fn_table *f, int32_t batch, const fl
 {
     if (batch == 0 || f->na + f->nb == 0 || (!ga && !gb)) return DOL_OK;
     if (conv_path_ok(f)) return launch_damp_conv_bwd(f, batch, a, lda, b, ldb, g, ldg, ga, gb, accumulate, st);
-    int32_t done = 0;
+    bool done = false;
     if (dol_status s2 = launch_damp_lds_bwd(f, batch, a, lda, b, ldb, out, ldo, g, ldg, ga, gb, accumulate, st, &done)) return s2;
-    if (done == batch) return DOL_OK;
-    batch -= done, a += done * lda, b += done * ldb, out += done * ldo, g += done * ldg;
-    if (ga) ga += done * lda;
-    if (gb) gb += done * ldb;
+    if (done) return DOL_OK;
     const BwdTable T{f->col_ptr.ptr, f->col_ij.ptr, f->rowa_ptr.ptr, f->rowa_jc.ptr, f->rowb_ptr.ptr, f->rowb_ic.ptr,
                      f->na, f->nb};
     const Rows R = rows_of(batch, f->na + f->nb);

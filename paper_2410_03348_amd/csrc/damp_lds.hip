@@ -1,16 +1,19 @@
-// DAMP apply2 for arbitrary (hashed, dense) function tables whose operand rows fit in LDS.
+// DAMP apply2 for arbitrary (hashed, dense or sparse) function tables whose operand rows fit in LDS.
 //
 //     out[s, c] = min(1, sum over the tuples (i, j) of column c, ascending (i, j), of a[s, i] * b[s, j])
 //     ga[s, i]  = sum_j gh[s, col(i, j)] * b[s, j],    gb[s, j] = sum_i gh[s, col(i, j)] * a[s, i]
 //
-// A workgroup (256 threads forward, 512 backward) owns a tile of 64 samples.  The operand rows are staged TRANSPOSED in LDS
-// (one 256-byte row of 64 samples per symbol), so that a lane can pull four samples of one symbol with a
-// single 16-byte read; 16 lanes cover the 64 samples, and the 16 groups of 16 lanes of the workgroup each
-// own a share of the output columns and walk their tuple lists.  Every tuple costs two 16-byte LDS reads and
-// four fma per lane; the 16-byte chunks of a row are XOR-swizzled by the row number so that both the
-// transposing writes and the reads are free of bank conflicts.  Tuple lists live in LDS too, as packets of
-// four tuples (one 16-byte broadcast read), each tuple being the pre-swizzled addresses of its two rows;
-// short lists are padded with a tuple that points at a row of zeros, whose product is an exact +0.
+// A workgroup owns a tile of 64 samples.  The operand rows are staged TRANSPOSED in LDS (one 256-byte row of
+// 64 samples per symbol), so that a lane can pull four samples of one symbol with a single 16-byte read; 16
+// lanes cover the 64 samples, and the groups of 16 lanes of the workgroup each own a share of the output columns
+// and walk their tuple lists.  Every tuple costs two 16-byte LDS reads and four fma per lane; the 16-byte chunks
+// of a row are XOR-swizzled by the row number so that the reads are free of bank conflicts.  Tuple lists live in
+// LDS too, as packets of four tuples (one 16-byte broadcast read), each tuple being the pre-swizzled addresses of
+// its two rows; short lists are padded with a tuple that points at a row of zeros, whose product is an exact +0.
+//
+// Any shape is taken: symbol counts need not be multiples of four, rows may be padded (ld > n_sym), the batch
+// need not be a multiple of the tile.  Contiguous 16-byte aligned tensors are staged with 16-byte loads and
+// written with 16-byte stores; others element by element.
 #include "internal.h"
 #include "wave_util.h"
 
@@ -21,65 +24,82 @@ namespace dol {
 constexpr int kLdsFwdWG = 1024, kLdsBwdWG = 1024;   // threads per workgroup
 constexpr int kLdsTile = 64;                     // samples per tile = floats per LDS row
 constexpr size_t kLdsBytesMax = 160 * 1024;
-constexpr int kLdsMaxSym = 128;                  // most symbols of one operand
-
 
 // Row number -> 16-bit address word: row * 16 chunks, with the swizzle term in the low four bits.
 // A lane that wants chunk q of the row reads 16 bytes at ((word ^ q) << 4).
 static inline uint32_t row_word(uint32_t row) { return row * 16u | ((row >> 2) & 15u); }
 
+// Packet lists of n_cols columns, padded with empty columns to a multiple of four.
 static void make_packets(int32_t n_cols, const std::vector<uint32_t> &ptr, const std::vector<uint32_t> &words,
                          uint32_t dummy, std::vector<uint32_t> &pk, std::vector<uint32_t> &pk_ptr)
 {
-    pk_ptr.assign(static_cast<size_t>(n_cols) + 1, 0);
+    const int32_t padded = (n_cols + 3) & ~3;
+    pk_ptr.assign(static_cast<size_t>(padded) + 1, 0);
     pk.clear();
-    for (int32_t c = 0; c < n_cols; ++c) {
-        for (uint32_t q = ptr[c]; q < ptr[c + 1]; ++q) pk.push_back(words[q]);
-        while (pk.size() % 4) pk.push_back(dummy);
+    for (int32_t c = 0; c < padded; ++c) {
+        if (c < n_cols) {
+            for (uint32_t q = ptr[c]; q < ptr[c + 1]; ++q) pk.push_back(words[q]);
+            while (pk.size() % 4) pk.push_back(dummy);
+        }
         pk_ptr[c + 1] = static_cast<uint32_t>(pk.size() / 4);
     }
 }
 
-// Builds the packet lists of the three gather products.  Leaves tb->lds_ok false when the table does not
-// qualify (operand sizes not multiples of four, rows or lists too large for LDS): the direct kernels serve it.
+// Builds the packet lists of the three gather products.  Leaves tb->lds_fwd_ok / lds_bwd_ok false when the rows
+// and lists are too large for LDS: the direct kernels serve those.
 dol_status lds_plan_build(dol_fn_table *tb, const std::vector<uint32_t> &col_ptr, const std::vector<uint32_t> &col_ij,
                           const std::vector<uint32_t> &rowa_ptr, const std::vector<uint32_t> &rowa_jc,
                           const std::vector<uint32_t> &rowb_ptr, const std::vector<uint32_t> &rowb_ic)
 {
     const int32_t na = tb->na, nb = tb->nb, S = tb->n_out;
-    tb->lds_ok = false;
-    if (na < 4 || nb < 4 || S < 4 || na % 4 || nb % 4 || S % 4) return DOL_OK;
-    if (na > kLdsMaxSym || nb > kLdsMaxSym || S + na + nb + 1 > 4095) return DOL_OK;
+    tb->lds_fwd_ok = tb->lds_bwd_ok = false;
+    if (na < 1 || nb < 1 || S < 1 || col_ij.empty()) return DOL_OK;
     std::vector<uint32_t> w(col_ij.size()), pk, pk_ptr, pka, pka_ptr, pkb, pkb_ptr;
-    // forward: rows [a: na][b: nb][zeros]
-    for (size_t q = 0; q < col_ij.size(); ++q)
-        w[q] = pack16(row_word(col_ij[q] & 0xffffu), row_word(na + (col_ij[q] >> 16)));
-    make_packets(S, col_ptr, w, pack16(row_word(na + nb), row_word(na + nb)), pk, pk_ptr);
-    // backward: rows [gh: S][a: na][b: nb][zeros]
-    const uint32_t zero = row_word(S + na + nb);
-    for (size_t q = 0; q < rowa_jc.size(); ++q)      // (j | column << 16): gh[column] * b[j]
-        w[q] = pack16(row_word(rowa_jc[q] >> 16), row_word(S + na + (rowa_jc[q] & 0xffffu)));
-    make_packets(na, rowa_ptr, w, pack16(zero, zero), pka, pka_ptr);
-    for (size_t q = 0; q < rowb_ic.size(); ++q)      // (i | column << 16): gh[column] * a[i]
-        w[q] = pack16(row_word(rowb_ic[q] >> 16), row_word(S + (rowb_ic[q] & 0xffffu)));
-    make_packets(nb, rowb_ptr, w, pack16(zero, zero), pkb, pkb_ptr);
-
-    tb->lds_fwd_bytes = sizeof(float) * kLdsTile * static_cast<size_t>(na + nb + 1) + sizeof(uint32_t) * (pk.size() + pk_ptr.size());
-    tb->lds_bwd_bytes = sizeof(float) * kLdsTile * static_cast<size_t>(S + na + nb + 1) +
-                        sizeof(uint32_t) * (pka.size() + pka_ptr.size() + pkb.size() + pkb_ptr.size());
-    if (tb->lds_fwd_bytes > kLdsBytesMax || tb->lds_bwd_bytes > kLdsBytesMax) return DOL_OK;
     hipError_t e;
-    if ((e = tb->lds_pk.upload(pk)) != hipSuccess || (e = tb->lds_pk_ptr.upload(pk_ptr)) != hipSuccess ||
-        (e = tb->lds_pka.upload(pka)) != hipSuccess || (e = tb->lds_pka_ptr.upload(pka_ptr)) != hipSuccess ||
-        (e = tb->lds_pkb.upload(pkb)) != hipSuccess || (e = tb->lds_pkb_ptr.upload(pkb_ptr)) != hipSuccess)
-        return hip_fail(e, "uploading the LDS packet lists");
-    tb->lds_ok = true;
+    // forward: rows [a: na][b: nb][zeros]
+    const size_t fwd_rows = sizeof(float) * kLdsTile * (static_cast<size_t>(na) + nb + 1);
+    if (fwd_rows + sizeof(uint32_t) * (col_ij.size() + S + 8) <= kLdsBytesMax) {
+        for (size_t q = 0; q < col_ij.size(); ++q)
+            w[q] = pack16(row_word(col_ij[q] & 0xffffu), row_word(na + (col_ij[q] >> 16)));
+        make_packets(S, col_ptr, w, pack16(row_word(na + nb), row_word(na + nb)), pk, pk_ptr);
+        tb->lds_fwd_bytes = fwd_rows + sizeof(uint32_t) * (pk.size() + pk_ptr.size());
+        if (tb->lds_fwd_bytes <= kLdsBytesMax) {
+            if ((e = tb->lds_pk.upload(pk)) != hipSuccess || (e = tb->lds_pk_ptr.upload(pk_ptr)) != hipSuccess)
+                return hip_fail(e, "uploading the LDS packet lists");
+            tb->lds_fwd_ok = true;
+        }
+    }
+    // backward: rows [gh: S][a: na][b: nb][zeros]
+    const size_t bwd_rows = sizeof(float) * kLdsTile * (static_cast<size_t>(S) + na + nb + 1);
+    if (bwd_rows + sizeof(uint32_t) * (2 * col_ij.size() + na + nb + 16) <= kLdsBytesMax) {
+        const uint32_t zero = row_word(S + na + nb);
+        for (size_t q = 0; q < rowa_jc.size(); ++q)      // (j | column << 16): gh[column] * b[j]
+            w[q] = pack16(row_word(rowa_jc[q] >> 16), row_word(S + na + (rowa_jc[q] & 0xffffu)));
+        make_packets(na, rowa_ptr, w, pack16(zero, zero), pka, pka_ptr);
+        for (size_t q = 0; q < rowb_ic.size(); ++q)      // (i | column << 16): gh[column] * a[i]
+            w[q] = pack16(row_word(rowb_ic[q] >> 16), row_word(S + (rowb_ic[q] & 0xffffu)));
+        make_packets(nb, rowb_ptr, w, pack16(zero, zero), pkb, pkb_ptr);
+        tb->lds_bwd_bytes = bwd_rows + sizeof(uint32_t) * (pka.size() + pka_ptr.size() + pkb.size() + pkb_ptr.size()) + 16;
+        if (tb->lds_bwd_bytes <= kLdsBytesMax) {
+            if ((e = tb->lds_pka.upload(pka)) != hipSuccess || (e = tb->lds_pka_ptr.upload(pka_ptr)) != hipSuccess ||
+                (e = tb->lds_pkb.upload(pkb)) != hipSuccess || (e = tb->lds_pkb_ptr.upload(pkb_ptr)) != hipSuccess)
+                return hip_fail(e, "uploading the LDS packet lists");
+            tb->lds_bwd_ok = true;
+        }
+    }
     return DOL_OK;
 }
 
-bool lds_path_ok(const dol_fn_table *f) { return f->lds_ok; }
-
 // ---------------------------------------------------------------- device helpers
+
+// A [batch, n] tensor with row stride ld; vec: rows are contiguous (ld == n) and the base is 16-byte aligned.
+struct Rows2D {
+    const float *p;
+    int64_t ld;
+    int32_t n;
+    int32_t vec;
+    float inv_n;
+};
 
 // Copies n words from global memory into LDS (all threads of the workgroup).
 template <int WG>
@@ -88,26 +108,15 @@ __device__ __forceinline__ void copy_words(uint32_t *dst, const uint32_t *__rest
     for (int e = threadIdx.x; e < n; e += WG) dst[e] = src[e];
 }
 
-// Transposing store of four consecutive symbols (i .. i+3, i % 4 == 0) of sample s into rows row0 + i ..
-__device__ __forceinline__ void store_transposed(float *rows, int row0, int i, int s, const float4 &v)
+// Position of (row, sample) inside the transposed, swizzled rows.
+__device__ __forceinline__ int slot_of(int row, int s)
 {
-    const float e[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-        const int row = row0 + i + k;
-        rows[row * kLdsTile + ((((s >> 2) ^ (row >> 2)) & 15) << 2) + (s & 3)] = e[k];
-    }
+    return row * kLdsTile + ((((s >> 2) ^ (row >> 2)) & 15) << 2) + (s & 3);
 }
 
 __device__ __forceinline__ float4 read_chunk(const float *rows, uint32_t word, uint32_t q)
 {
     return *reinterpret_cast<const float4 *>(reinterpret_cast<const char *>(rows) + ((word ^ q) << 4));
-}
-
-// One float of the transposed rows (slow path of the clamp gate).
-__device__ __forceinline__ float read_one(const float *rows, int row, int s)
-{
-    return rows[row * kLdsTile + ((((s >> 2) ^ (row >> 2)) & 15) << 2) + (s & 3)];
 }
 
 // acc += x * y for the four samples of this lane, over the packets [p0, p1) of one output column.
@@ -118,182 +127,227 @@ __device__ __forceinline__ float4 gather_dot(const float *rows, const uint4 *pac
     for (uint32_t p = p0; p < p1; ++p) {
         const uint4 t = packets[p];
         const uint32_t tw[4] = {t.x, t.y, t.z, t.w};
+        float4 x[4], y[4];                  // all eight reads of the packet are requested before the first fma
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
-            const float4 x = read_chunk(rows, tw[k] & 0xffffu, q);
-            const float4 y = read_chunk(rows, tw[k] >> 16, q);
-            acc.x = __builtin_fmaf(x.x, y.x, acc.x);
-            acc.y = __builtin_fmaf(x.y, y.y, acc.y);
-            acc.z = __builtin_fmaf(x.z, y.z, acc.z);
-            acc.w = __builtin_fmaf(x.w, y.w, acc.w);
+            x[k] = read_chunk(rows, tw[k] & 0xffffu, q);
+            y[k] = read_chunk(rows, tw[k] >> 16, q);
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            acc.x = __builtin_fmaf(x[k].x, y[k].x, acc.x);
+            acc.y = __builtin_fmaf(x[k].y, y[k].y, acc.y);
+            acc.z = __builtin_fmaf(x[k].z, y[k].z, acc.z);
+            acc.w = __builtin_fmaf(x[k].w, y[k].w, acc.w);
         }
     }
     return acc;
 }
 
-// Stages the [kLdsTile x n] tile of a contiguous [batch, n] tensor (n % 4 == 0, n <= kLdsMaxSym) into rows
-// row0 .. row0 + n - 1.  Every thread issues all of its loads before the first transposing store.
-template <int WG>
-__device__ __forceinline__ void stage_tile(float *rows, int row0, const float *__restrict__ src, int n)
+// Element e of a flat [valid x n] tile -> (sample, symbol); exact for the small integers involved.
+__device__ __forceinline__ void split(int e, int n, float inv_n, int &s, int &i)
 {
-    const int n4 = n >> 2, total = kLdsTile * n4;
-    const float4 *src4 = reinterpret_cast<const float4 *>(src);
-    constexpr int kQ = kLdsTile * (kLdsMaxSym / 4) / WG;
-    float4 v[kQ];
+    s = static_cast<int>(static_cast<float>(e) * inv_n);
+    i = e - s * n;
+    const int d = (i >= n ? 1 : 0) - (i < 0 ? 1 : 0);   // the float quotient may be off by one: fix without a branch
+    s += d;
+    i -= d * n;
+}
+
+// Stages samples s0 .. s0 + valid - 1 of T into rows row0 .. row0 + T.n - 1 as f(value, aux value, s, i); X is a
+// second tensor of the same shape read in step with T (AUX), e.g. the forward result beside the upstream gradient.
+// Contiguous tensors: the tile is one flat run of valid * n floats starting on a 16-byte boundary (64 samples per
+// tile), read in 16-byte pieces, several in flight per lane.
+// FAST: the caller vouches for contiguous aligned tensors, n % 4 == 0 and a full tile; only that path is compiled.
+template <int WG, bool AUX, bool FAST, typename F>
+__device__ __forceinline__ void stage_tile(float *rows, int row0, const Rows2D &T, const Rows2D &X, int64_t s0, int valid, F f)
+{
+    const int n = T.n, total = valid * n;
+    const float4 zero4 = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    constexpr int kInFlight = AUX ? 4 : 2;     // 16-byte pieces a lane requests before it stores the first
+    if (FAST || (T.vec && (!AUX || X.vec))) {
+        const float4 *src4 = reinterpret_cast<const float4 *>(T.p + s0 * n);
+        const float4 *aux4 = reinterpret_cast<const float4 *>(X.p + s0 * n);
+        const int n4 = total >> 2;
+        for (int f0 = 0; f0 < n4; f0 += kInFlight * WG) {
+            float4 v[kInFlight], u[kInFlight];
 #pragma unroll
-    for (int x = 0; x < kQ; ++x) {
-        const int f = threadIdx.x + WG * x;
-        if (f < total) v[x] = src4[f];
+            for (int x = 0; x < kInFlight; ++x) {
+                const int q = min(f0 + static_cast<int>(threadIdx.x) + WG * x, n4 - 1);   // clamped: no branch
+                v[x] = src4[q];
+                u[x] = AUX ? aux4[q] : zero4;
+            }
+#pragma unroll
+            for (int x = 0; x < kInFlight; ++x) {
+                const int q = f0 + threadIdx.x + WG * x;
+                if (q < n4) {
+                    int s, i;
+                    split(q << 2, n, T.inv_n, s, i);
+                    const float e[4] = {v[x].x, v[x].y, v[x].z, v[x].w}, a[4] = {u[x].x, u[x].y, u[x].z, u[x].w};
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        rows[slot_of(row0 + i, s)] = f(e[k], a[k], s, i);
+                        ++i;
+                        if (!FAST && i == n) { i = 0; ++s; }     // n % 4 != 0: the piece may span two samples
+                    }
+                }
+            }
+        }
+        if (FAST) return;
+        for (int e = (n4 << 2) + threadIdx.x; e < total; e += WG) {
+            int s, i;
+            split(e, n, T.inv_n, s, i);
+            rows[slot_of(row0 + i, s)] = f(T.p[s0 * n + e], AUX ? X.p[s0 * n + e] : 0.0f, s, i);
+        }
+    } else {
+        for (int e = threadIdx.x; e < total; e += WG) {
+            int s, i;
+            split(e, n, T.inv_n, s, i);
+            rows[slot_of(row0 + i, s)] = f(T.p[(s0 + s) * T.ld + i], AUX ? X.p[(s0 + s) * X.ld + i] : 0.0f, s, i);
+        }
     }
+}
+
+// Writes the lane's block: o[cc] holds columns col0 + cc of samples 4q .. 4q + 3 (in x, y, z, w).
+template <bool CLAMP, bool FAST>
+__device__ __forceinline__ void store_block(float *__restrict__ base, int64_t ld, int32_t n, int32_t vec, int64_t s0, int valid,
+                                            uint32_t q, int col0, const float4 (&o)[4], bool add)
+{
+    float r[4][4] = {{o[0].x, o[1].x, o[2].x, o[3].x}, {o[0].y, o[1].y, o[2].y, o[3].y},
+                     {o[0].z, o[1].z, o[2].z, o[3].z}, {o[0].w, o[1].w, o[2].w, o[3].w}};
 #pragma unroll
-    for (int x = 0; x < kQ; ++x) {
-        const int f = threadIdx.x + WG * x;
-        if (f < total) {
-            const int s = f / n4;
-            store_transposed(rows, row0, (f - s * n4) << 2, s, v[x]);
+    for (int k = 0; k < 4; ++k) {
+        const int s = 4 * static_cast<int>(q) + k;
+        if (!FAST && s >= valid) continue;
+        float *dst = base + (s0 + s) * ld + col0;
+        if (CLAMP) {
+#pragma unroll
+            for (int cc = 0; cc < 4; ++cc) r[k][cc] = fminf(r[k][cc], 1.0f);
+        }
+        if (FAST || (vec && col0 + 3 < n)) {
+            float4 v = make_float4(r[k][0], r[k][1], r[k][2], r[k][3]);
+            if (add) { const float4 old = *reinterpret_cast<float4 *>(dst); v.x += old.x; v.y += old.y; v.z += old.z; v.w += old.w; }
+            *reinterpret_cast<float4 *>(dst) = v;
+        } else {
+#pragma unroll
+            for (int cc = 0; cc < 4; ++cc)
+                if (col0 + cc < n) dst[cc] = add ? dst[cc] + r[k][cc] : r[k][cc];
         }
     }
 }
 
 // ---------------------------------------------------------------- forward
 
-__global__ void __launch_bounds__(kLdsFwdWG)
-damp_lds_fwd_kernel(int32_t n_tiles, int32_t na, int32_t nb, int32_t S, int32_t n_pk, const uint32_t *__restrict__ g_pk,
-                    const uint32_t *__restrict__ g_pk_ptr, const float *__restrict__ a, const float *__restrict__ b,
-                    float *__restrict__ out)
+// (16 wavefronts per workgroup and one workgroup or two per CU: at most 4 wavefronts per SIMD can be resident, so
+// the register allocator is told not to save registers for more, which would serialise the LDS reads of a packet)
+template <bool FAST>
+__global__ void __launch_bounds__(kLdsFwdWG) __attribute__((amdgpu_waves_per_eu(1, 4)))
+damp_lds_fwd_kernel(int32_t batch, int32_t n_tiles, int32_t S, int32_t n_pk, const uint32_t *__restrict__ g_pk,
+                    const uint32_t *__restrict__ g_pk_ptr, Rows2D A, Rows2D B, float *__restrict__ out, int64_t ldo,
+                    int32_t vec_out)
 {
     extern __shared__ __align__(16) float lds[];     // rows [a][b][zeros], packets, packet pointers
+    const int na = A.n, nb = B.n, n_blocks = (S + 3) >> 2;
     float *rows = lds;
     uint32_t *pk = reinterpret_cast<uint32_t *>(rows + kLdsTile * (na + nb + 1));
     uint32_t *pk_ptr = pk + 4 * n_pk;
     copy_words<kLdsFwdWG>(pk, g_pk, 4 * n_pk);
-    copy_words<kLdsFwdWG>(pk_ptr, g_pk_ptr, S + 1);
+    copy_words<kLdsFwdWG>(pk_ptr, g_pk_ptr, 4 * n_blocks + 1);
     for (int e = threadIdx.x; e < kLdsTile; e += kLdsFwdWG) rows[(na + nb) * kLdsTile + e] = 0.0f;
     const uint32_t q = threadIdx.x & 15u;
     const int group = threadIdx.x >> 4;
-    const int n_blocks = S >> 2;
+    auto plain = [](float v, float, int, int) { return v; };
     for (int tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
         const int64_t s0 = static_cast<int64_t>(tile) * kLdsTile;
+        const int valid = FAST ? kLdsTile : static_cast<int>(min(static_cast<int64_t>(kLdsTile), batch - s0));
         __syncthreads();                             // the previous tile's readers are done (and the lists are in)
-        stage_tile<kLdsFwdWG>(rows, 0, a + s0 * na, na);
-        stage_tile<kLdsFwdWG>(rows, na, b + s0 * nb, nb);
+        stage_tile<kLdsFwdWG, false, FAST>(rows, 0, A, A, s0, valid, plain);
+        stage_tile<kLdsFwdWG, false, FAST>(rows, na, B, B, s0, valid, plain);
         __syncthreads();
-        for (int blk = group; blk < n_blocks; blk += (kLdsFwdWG / 16)) {
+        for (int blk = group; blk < n_blocks; blk += kLdsFwdWG / 16) {
             float4 o[4];
 #pragma unroll
             for (int cc = 0; cc < 4; ++cc) {
                 const int c = 4 * blk + cc;
                 o[cc] = gather_dot(rows, reinterpret_cast<const uint4 *>(pk), pk_ptr[c], pk_ptr[c + 1], q);
             }
-            // lane holds [4 samples][4 columns]: one 16-byte store per sample
-            float *dst = out + (s0 + 4 * q) * S + 4 * blk;
-            *reinterpret_cast<float4 *>(dst) = make_float4(fminf(o[0].x, 1.0f), fminf(o[1].x, 1.0f), fminf(o[2].x, 1.0f), fminf(o[3].x, 1.0f));
-            *reinterpret_cast<float4 *>(dst + S) = make_float4(fminf(o[0].y, 1.0f), fminf(o[1].y, 1.0f), fminf(o[2].y, 1.0f), fminf(o[3].y, 1.0f));
-            *reinterpret_cast<float4 *>(dst + 2 * S) = make_float4(fminf(o[0].z, 1.0f), fminf(o[1].z, 1.0f), fminf(o[2].z, 1.0f), fminf(o[3].z, 1.0f));
-            *reinterpret_cast<float4 *>(dst + 3 * S) = make_float4(fminf(o[0].w, 1.0f), fminf(o[1].w, 1.0f), fminf(o[2].w, 1.0f), fminf(o[3].w, 1.0f));
+            store_block<true, FAST>(out, ldo, S, vec_out, s0, valid, q, 4 * blk, o, false);
         }
     }
 }
 
 // ---------------------------------------------------------------- backward
 
-// Stages gh = g gated by the clamp: out < 1 means the clamp did not act.  Elements with out == 1 are decided
-// afterwards from pre (see the kernel); their positions are counted in *n_flag.
-template <int WG>
-__device__ __forceinline__ void stage_gated(float *rows, const float *__restrict__ g, const float *__restrict__ out,
-                                            int S, int *n_flag)
-{
-    const int n4 = S >> 2, total = kLdsTile * n4;
-    const float4 *g4 = reinterpret_cast<const float4 *>(g), *o4 = reinterpret_cast<const float4 *>(out);
-    int flagged = 0;
-    for (int f0 = 0; f0 < total; f0 += WG * 4) {     // four pieces of g and of out in flight per thread
-        float4 vg[4], vo[4];
-#pragma unroll
-        for (int x = 0; x < 4; ++x) {
-            const int f = f0 + threadIdx.x + WG * x;
-            if (f < total) { vg[x] = g4[f]; vo[x] = o4[f]; }
-        }
-#pragma unroll
-        for (int x = 0; x < 4; ++x) {
-            const int f = f0 + threadIdx.x + WG * x;
-            if (f < total) {
-                const int s = f / n4;
-                flagged |= !(vo[x].x < 1.0f) | !(vo[x].y < 1.0f) | !(vo[x].z < 1.0f) | !(vo[x].w < 1.0f);
-                store_transposed(rows, 0, (f - s * n4) << 2, s, vg[x]);
-            }
-        }
-    }
-    if (flagged) atomicOr(n_flag, 1);
-}
-
-__global__ void __launch_bounds__(kLdsBwdWG)
-damp_lds_bwd_kernel(int32_t n_tiles, int32_t na, int32_t nb, int32_t S, int32_t n_pka, int32_t n_pkb,
+template <bool FAST>
+__global__ void __launch_bounds__(kLdsBwdWG) __attribute__((amdgpu_waves_per_eu(1, 4)))
+damp_lds_bwd_kernel(int32_t batch, int32_t n_tiles, int32_t n_pka, int32_t n_pkb,
                     const uint32_t *__restrict__ g_pka, const uint32_t *__restrict__ g_pka_ptr,
                     const uint32_t *__restrict__ g_pkb, const uint32_t *__restrict__ g_pkb_ptr,
-                    const uint32_t *__restrict__ col_ptr, const uint32_t *__restrict__ col_ij,
-                    const float *__restrict__ a, const float *__restrict__ b, const float *__restrict__ out,
-                    const float *__restrict__ g, float *__restrict__ ga, float *__restrict__ gb, int32_t accumulate)
+                    const uint32_t *__restrict__ col_ptr, const uint32_t *__restrict__ col_ij, Rows2D A, Rows2D B,
+                    Rows2D G, Rows2D O, float *__restrict__ ga, float *__restrict__ gb,
+                    int32_t vec_ga, int32_t vec_gb, int32_t accumulate)
 {
     extern __shared__ __align__(16) float lds[];     // rows [gh: S][a: na][b: nb][zeros], lists, flag
+    const int na = A.n, nb = B.n, S = G.n;
+    const int blocks_a = (na + 3) >> 2, blocks_b = (nb + 3) >> 2;
     float *rows = lds;
     const int n_rows = S + na + nb + 1;
     uint32_t *pka = reinterpret_cast<uint32_t *>(rows + kLdsTile * n_rows);
     uint32_t *pkb = pka + 4 * n_pka;
     uint32_t *pka_ptr = pkb + 4 * n_pkb;
-    uint32_t *pkb_ptr = pka_ptr + na + 1;
-    int *flag = reinterpret_cast<int *>(pkb_ptr + nb + 1);
+    uint32_t *pkb_ptr = pka_ptr + 4 * blocks_a + 1;
+    int *flag = reinterpret_cast<int *>(pkb_ptr + 4 * blocks_b + 1);
     copy_words<kLdsBwdWG>(pka, g_pka, 4 * n_pka);
-    copy_words<kLdsBwdWG>(pka_ptr, g_pka_ptr, na + 1);
+    copy_words<kLdsBwdWG>(pka_ptr, g_pka_ptr, 4 * blocks_a + 1);
     copy_words<kLdsBwdWG>(pkb, g_pkb, 4 * n_pkb);
-    copy_words<kLdsBwdWG>(pkb_ptr, g_pkb_ptr, nb + 1);
+    copy_words<kLdsBwdWG>(pkb_ptr, g_pkb_ptr, 4 * blocks_b + 1);
     for (int e = threadIdx.x; e < kLdsTile; e += kLdsBwdWG) rows[(n_rows - 1) * kLdsTile + e] = 0.0f;
     const uint32_t q = threadIdx.x & 15u;
     const int group = threadIdx.x >> 4;
-    const int blocks_a = na >> 2, n_blocks = (na + nb) >> 2;
+    auto plain = [](float v, float, int, int) { return v; };
     for (int tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
         const int64_t s0 = static_cast<int64_t>(tile) * kLdsTile;
+        const int valid = FAST ? kLdsTile : static_cast<int>(min(static_cast<int64_t>(kLdsTile), batch - s0));
         __syncthreads();
         if (threadIdx.x == 0) *flag = 0;
         __syncthreads();
-        stage_gated<kLdsBwdWG>(rows, g + s0 * S, out + s0 * S, S, flag);
-        stage_tile<kLdsBwdWG>(rows, S, a + s0 * na, na);
-        stage_tile<kLdsBwdWG>(rows, S + na, b + s0 * nb, nb);
+        // gh = g gated by the clamp: out < 1 means the clamp did not act; elements with out == 1 are decided below
+        int flagged = 0;
+        stage_tile<kLdsBwdWG, true, FAST>(rows, 0, G, O, s0, valid, [&](float v, float o, int, int) {
+            flagged |= !(o < 1.0f);
+            return v;
+        });
+        if (flagged) atomicOr(flag, 1);
+        stage_tile<kLdsBwdWG, false, FAST>(rows, S, A, A, s0, valid, plain);
+        stage_tile<kLdsBwdWG, false, FAST>(rows, S + na, B, B, s0, valid, plain);
         __syncthreads();
         if (*flag) {                                 // rare: some output of this tile sits on the clamp
-            for (int e = threadIdx.x; e < kLdsTile * S; e += kLdsBwdWG) {
-                const int s = e / S, c = e - s * S;
-                if (!(out[(s0 + s) * S + c] < 1.0f)) {
+            for (int e = threadIdx.x; e < valid * S; e += kLdsBwdWG) {
+                int s, c;
+                split(e, S, G.inv_n, s, c);
+                if (!(O.p[(s0 + s) * O.ld + c] < 1.0f)) {
                     float pre = 0.0f;
                     for (uint32_t t = col_ptr[c], t1 = col_ptr[c + 1]; t < t1; ++t) {
                         const uint32_t ij = col_ij[t];
-                        pre = __builtin_fmaf(read_one(rows, S + (ij & 0xffffu), s), read_one(rows, S + na + (ij >> 16), s), pre);
+                        pre = __builtin_fmaf(rows[slot_of(S + (ij & 0xffffu), s)], rows[slot_of(S + na + (ij >> 16), s)], pre);
                     }
-                    if (!(pre <= 1.0f)) rows[c * kLdsTile + ((((s >> 2) ^ (c >> 2)) & 15) << 2) + (s & 3)] = 0.0f;
+                    if (!(pre <= 1.0f)) rows[slot_of(c, s)] = 0.0f;
                 }
             }
             __syncthreads();
         }
-        for (int blk = group; blk < n_blocks; blk += (kLdsBwdWG / 16)) {
+        for (int blk = group; blk < blocks_a + blocks_b; blk += kLdsBwdWG / 16) {
             const bool is_a = blk < blocks_a;
+            float *base = is_a ? ga : gb;
+            if (!base) continue;
             const int col0 = is_a ? 4 * blk : 4 * (blk - blocks_a);
             const uint4 *packets = reinterpret_cast<const uint4 *>(is_a ? pka : pkb);
             const uint32_t *ptr = is_a ? pka_ptr : pkb_ptr;
-            float *base = is_a ? ga : gb;
-            if (!base) continue;
             float4 o[4];
 #pragma unroll
             for (int cc = 0; cc < 4; ++cc) o[cc] = gather_dot(rows, packets, ptr[col0 + cc], ptr[col0 + cc + 1], q);
-            const int n = is_a ? na : nb;
-            const bool add = is_a ? (accumulate & 1) : (accumulate & 2);
-            float *dst = base + (s0 + 4 * q) * n + col0;
-            float4 r[4] = {make_float4(o[0].x, o[1].x, o[2].x, o[3].x), make_float4(o[0].y, o[1].y, o[2].y, o[3].y),
-                           make_float4(o[0].z, o[1].z, o[2].z, o[3].z), make_float4(o[0].w, o[1].w, o[2].w, o[3].w)};
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                float4 *p = reinterpret_cast<float4 *>(dst + k * n);
-                if (add) { const float4 old = *p; r[k].x += old.x; r[k].y += old.y; r[k].z += old.z; r[k].w += old.w; }
-                *p = r[k];
-            }
+            store_block<false, FAST>(base, is_a ? A.ld : B.ld, is_a ? na : nb, is_a ? vec_ga : vec_gb, s0, valid, q, col0, o,
+                               is_a ? (accumulate & 1) : (accumulate & 2));
         }
     }
 }
@@ -302,6 +356,17 @@ damp_lds_bwd_kernel(int32_t n_tiles, int32_t na, int32_t nb, int32_t S, int32_t 
 
 static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+static Rows2D rows2d(const float *p, int64_t ld, int32_t n)
+{
+    Rows2D r;
+    r.p = p;
+    r.ld = ld;
+    r.n = n;
+    r.vec = ld == n && aligned16(p);
+    r.inv_n = 1.0f / static_cast<float>(n);
+    return r;
+}
+
 static unsigned lds_grid(int n_tiles, size_t lds_bytes)
 {
     const int per_cu = static_cast<int>(kLdsBytesMax / lds_bytes) > 0 ? static_cast<int>(kLdsBytesMax / lds_bytes) : 1;
@@ -309,51 +374,66 @@ static unsigned lds_grid(int n_tiles, size_t lds_bytes)
     return static_cast<unsigned>(n_tiles < cap ? n_tiles : cap);
 }
 
-// Number of samples the LDS forward kernel took (a multiple of the tile), 0 when the call does not qualify.
+// *done = the call was taken (otherwise the caller uses the direct kernels).
 dol_status launch_damp_lds_fwd(const dol_fn_table *f, int32_t batch, const float *a, int64_t lda, const float *b,
-                               int64_t ldb, float *out, int64_t ldo, hipStream_t st, int32_t *done)
+                               int64_t ldb, float *out, int64_t ldo, hipStream_t st, bool *done)
 {
-    *done = 0;
-    const int n_tiles = batch / kLdsTile;
-    if (!f->lds_ok || n_tiles == 0 || lda != f->na || ldb != f->nb || ldo != f->n_out || !aligned16(a) || !aligned16(b) ||
-        !aligned16(out))
-        return DOL_OK;
+    *done = false;
+    if (!f->lds_fwd_ok || batch < 1) return DOL_OK;
+    const int n_tiles = (batch + kLdsTile - 1) / kLdsTile;
     static bool attr_set = false;
     if (!attr_set) {
-        DOL_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(damp_lds_fwd_kernel),
+        DOL_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(damp_lds_fwd_kernel<true>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(kLdsBytesMax)));
+        DOL_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(damp_lds_fwd_kernel<false>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(kLdsBytesMax)));
         attr_set = true;
     }
     const int32_t n_pk = static_cast<int32_t>(f->lds_pk.n / 4);
-    hipLaunchKernelGGL(damp_lds_fwd_kernel, dim3(lds_grid(n_tiles, f->lds_fwd_bytes)), dim3(kLdsFwdWG), f->lds_fwd_bytes, st,
-                       n_tiles, f->na, f->nb, f->n_out, n_pk, f->lds_pk.ptr, f->lds_pk_ptr.ptr, a, b, out);
+    const int32_t vec_out = (ldo % 4 == 0) && aligned16(out);
+    const Rows2D A = rows2d(a, lda, f->na), B = rows2d(b, ldb, f->nb);
+    const dim3 grid(lds_grid(n_tiles, f->lds_fwd_bytes)), block(kLdsFwdWG);
+    // whole tiles of contiguous aligned tensors whose sizes are multiples of four take the specialised build
+    if (A.vec && B.vec && vec_out && ldo == f->n_out && !((f->na | f->nb | f->n_out) & 3) && batch % kLdsTile == 0)
+        hipLaunchKernelGGL(damp_lds_fwd_kernel<true>, grid, block, f->lds_fwd_bytes, st, batch, n_tiles, f->n_out, n_pk,
+                           f->lds_pk.ptr, f->lds_pk_ptr.ptr, A, B, out, ldo, vec_out);
+    else
+        hipLaunchKernelGGL(damp_lds_fwd_kernel<false>, grid, block, f->lds_fwd_bytes, st, batch, n_tiles, f->n_out, n_pk,
+                           f->lds_pk.ptr, f->lds_pk_ptr.ptr, A, B, out, ldo, vec_out);
     DOL_HIP(hipGetLastError());
-    *done = n_tiles * kLdsTile;
+    *done = true;
     return DOL_OK;
 }
 
 dol_status launch_damp_lds_bwd(const dol_fn_table *f, int32_t batch, const float *a, int64_t lda, const float *b,
                                int64_t ldb, const float *out, int64_t ldo, const float *g, int64_t ldg, float *ga,
-                               float *gb, int32_t accumulate, hipStream_t st, int32_t *done)
+                               float *gb, int32_t accumulate, hipStream_t st, bool *done)
 {
-    *done = 0;
-    const int n_tiles = batch / kLdsTile;
-    if (!f->lds_ok || n_tiles == 0 || lda != f->na || ldb != f->nb || ldo != f->n_out || ldg != f->n_out ||
-        ga == gb || !aligned16(a) || !aligned16(b) || !aligned16(out) || !aligned16(g) || !aligned16(ga) || !aligned16(gb))
-        return DOL_OK;
+    *done = false;
+    if (!f->lds_bwd_ok || batch < 1 || (ga && ga == gb)) return DOL_OK;
+    const int n_tiles = (batch + kLdsTile - 1) / kLdsTile;
     static bool attr_set = false;
     if (!attr_set) {
-        DOL_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(damp_lds_bwd_kernel),
+        DOL_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(damp_lds_bwd_kernel<true>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(kLdsBytesMax)));
+        DOL_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(damp_lds_bwd_kernel<false>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(kLdsBytesMax)));
         attr_set = true;
     }
-    const size_t lds = f->lds_bwd_bytes + 16;
-    hipLaunchKernelGGL(damp_lds_bwd_kernel, dim3(lds_grid(n_tiles, lds)), dim3(kLdsBwdWG), lds, st, n_tiles, f->na, f->nb,
-                       f->n_out, static_cast<int32_t>(f->lds_pka.n / 4), static_cast<int32_t>(f->lds_pkb.n / 4),
-                       f->lds_pka.ptr, f->lds_pka_ptr.ptr, f->lds_pkb.ptr, f->lds_pkb_ptr.ptr, f->col_ptr.ptr,
-                       f->col_ij.ptr, a, b, out, g, ga, gb, accumulate);
+    const int32_t vec_ga = (lda % 4 == 0) && aligned16(ga), vec_gb = (ldb % 4 == 0) && aligned16(gb);
+    const Rows2D A = rows2d(a, lda, f->na), B = rows2d(b, ldb, f->nb), G = rows2d(g, ldg, f->n_out), O = rows2d(out, ldo, f->n_out);
+    const dim3 grid(lds_grid(n_tiles, f->lds_bwd_bytes)), block(kLdsBwdWG);
+    const int32_t n_pka = static_cast<int32_t>(f->lds_pka.n / 4), n_pkb = static_cast<int32_t>(f->lds_pkb.n / 4);
+    if (A.vec && B.vec && G.vec && O.vec && vec_ga && vec_gb && !((f->na | f->nb | f->n_out) & 3) && batch % kLdsTile == 0)
+        hipLaunchKernelGGL(damp_lds_bwd_kernel<true>, grid, block, f->lds_bwd_bytes, st, batch, n_tiles, n_pka, n_pkb,
+                           f->lds_pka.ptr, f->lds_pka_ptr.ptr, f->lds_pkb.ptr, f->lds_pkb_ptr.ptr, f->col_ptr.ptr,
+                           f->col_ij.ptr, A, B, G, O, ga, gb, vec_ga, vec_gb, accumulate);
+    else
+        hipLaunchKernelGGL(damp_lds_bwd_kernel<false>, grid, block, f->lds_bwd_bytes, st, batch, n_tiles, n_pka, n_pkb,
+                           f->lds_pka.ptr, f->lds_pka_ptr.ptr, f->lds_pkb.ptr, f->lds_pkb_ptr.ptr, f->col_ptr.ptr,
+                           f->col_ij.ptr, A, B, G, O, ga, gb, vec_ga, vec_gb, accumulate);
     DOL_HIP(hipGetLastError());
-    *done = n_tiles * kLdsTile;
+    *done = true;
     return DOL_OK;
 }
 

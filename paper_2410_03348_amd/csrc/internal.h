@@ -87,7 +87,7 @@ struct dol_fn_table {
     dol::DevArray<uint32_t> long_rows;
     // LDS gather kernels (damp_lds.hip): per output column (forward), row of a, row of b (backward) a list of
     // 16-byte packets of four tuples; *_ptr[x] .. *_ptr[x+1] are the packets of x
-    bool lds_ok = false;
+    bool lds_fwd_ok = false, lds_bwd_ok = false;
     size_t lds_fwd_bytes = 0, lds_bwd_bytes = 0;
     dol::DevArray<uint32_t> lds_pk, lds_pk_ptr, lds_pka, lds_pka_ptr, lds_pkb, lds_pkb_ptr;
     int device = 0;
@@ -143,16 +143,15 @@ dol_status launch_damp_conv_fwd(const dol_fn_table *f, int32_t batch, const floa
 dol_status launch_damp_conv_bwd(const dol_fn_table *f, int32_t batch, const float *a, int64_t lda, const float *b,
                                 int64_t ldb, const float *g, int64_t ldg, float *ga, float *gb, int32_t accumulate,
                                 hipStream_t st);
-// Arbitrary tables whose operand rows fit in LDS (damp_lds.hip).  The launchers take the leading whole tiles
-// of the batch and report how many samples that was (0: the call does not qualify).
+// Arbitrary tables whose operand rows fit in LDS (damp_lds.hip); *done = false: the call was not taken.
 dol_status lds_plan_build(dol_fn_table *tb, const std::vector<uint32_t> &col_ptr, const std::vector<uint32_t> &col_ij,
                           const std::vector<uint32_t> &rowa_ptr, const std::vector<uint32_t> &rowa_jc,
                           const std::vector<uint32_t> &rowb_ptr, const std::vector<uint32_t> &rowb_ic);
 dol_status launch_damp_lds_fwd(const dol_fn_table *f, int32_t batch, const float *a, int64_t lda, const float *b,
-                               int64_t ldb, float *out, int64_t ldo, hipStream_t st, int32_t *done);
+                               int64_t ldb, float *out, int64_t ldo, hipStream_t st, bool *done);
 dol_status launch_damp_lds_bwd(const dol_fn_table *f, int32_t batch, const float *a, int64_t lda, const float *b,
                                int64_t ldb, const float *out, int64_t ldo, const float *g, int64_t ldg, float *ga,
-                               float *gb, int32_t accumulate, hipStream_t st, int32_t *done);
+                               float *gb, int32_t accumulate, hipStream_t st, bool *done);
 // Filter / Union on contiguous 16-byte aligned tensors (damp_rows.hip); *done = false: not taken
 dol_status launch_rows_gather(int32_t batch, int32_t n_in, int32_t n_out, const int32_t *src_col, const float *in,
                               int64_t ldi, float *out, int64_t ldo, int32_t accumulate, hipStream_t st, bool *done);
