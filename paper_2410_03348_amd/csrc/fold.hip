@@ -359,13 +359,34 @@ damp_fold4_kernel(const FoldArgs A)
             *reinterpret_cast<float4 *>(g_nxt + i0) = make_float4(o[0], o[1], o[2], o[3]);
         }
         if (tc < HB / 4) *reinterpret_cast<float4 *>(g_nxt + ((m + 3) & ~3) + 4 * tc) = zero4;
-        float mine = 0.0f;
+        // Sum the NBR partial rows over the sample's lanes.  Two halving exchanges inside each quad (a lane keeps
+        // half of the entries and hands the other half to its partner), then the quads of a row are added by
+        // rotations of 4 and 8 lanes and the two rows by one shuffle: lane (b1, b0) ends with the totals of
+        // entries H1 * b0 + H2 * b1 + [0, H2).
+        {
+            constexpr int H1 = NBR / 2, H2 = NBR / 4;
+            const bool b0 = tc & 1, b1 = tc & 2;
+            float w1[H1], w2[H2];
 #pragma unroll
-        for (int j = 0; j < NBP; ++j) {
-            const float tot = TC == 16 ? reduce16<AddOp>(pj[j]) : reduce32<AddOp>(pj[j]);
-            if (tc == j) mine = tot;
+            for (int k = 0; k < H1; ++k) {
+                const float lo = k < NBP ? pj[k < NBP ? k : 0] : 0.0f, hi = k + H1 < NBP ? pj[k + H1 < NBP ? k + H1 : 0] : 0.0f;
+                w1[k] = (b0 ? hi : lo) + dpp<0xB1>(b0 ? lo : hi);            // partner: lane ^ 1
+            }
+#pragma unroll
+            for (int k = 0; k < H2; ++k) {
+                float x = (b1 ? w1[k + H2] : w1[k]) + dpp<0x4E>(b1 ? w1[k] : w1[k + H2]);   // partner: lane ^ 2
+                x += dpp<0x124>(x);                                           // row_ror:4
+                x += dpp<0x128>(x);                                           // row_ror:8
+                if (TC == 32) x += __shfl_xor(x, 16, kWave);
+                w2[k] = x;
+            }
+            // the stage's short row is spent: its gradient takes its place
+            if (tc < 4) {
+                float *dst = base + A.off_d + t * NBR + H1 * (tc & 1) + H2 * (tc >> 1);
+#pragma unroll
+                for (int k = 0; k < H2; ++k) dst[k] = w2[k];
+            }
         }
-        if (tc < NBR) base[A.off_d + t * NBR + tc] = mine;   // the stage's short row is spent: its gradient takes its place
         wave_lds_fence();
         float *sw = g_cur; g_cur = g_nxt; g_nxt = sw;
     }
