@@ -154,36 +154,53 @@ __device__ __forceinline__ void split(int e, int n, float inv_n, int &s, int &i)
     i -= d * n;
 }
 
+// 16-byte pieces of a tile (and of its companion tensor) on their way from memory to one lane.
+template <bool AUX>
+struct Chunk {
+    static constexpr int kPieces = AUX ? 2 : 1;
+    float4 v[kPieces], u[AUX ? kPieces : 1];
+};
+
+// Requests the pieces f0 + lane + WG * x of the flat tile (contiguous tensors only; indices clamped, no branch).
+template <int WG, bool AUX, bool FAST>
+__device__ __forceinline__ void stage_request(Chunk<AUX> &c, const Rows2D &T, const Rows2D &X, int64_t s0, int valid, int f0)
+{
+    const int n4 = (valid * T.n) >> 2;
+    if (!(FAST || (T.vec && (!AUX || X.vec))) || n4 == 0) return;
+    const float4 *src4 = reinterpret_cast<const float4 *>(T.p + s0 * T.n);
+    const float4 *aux4 = reinterpret_cast<const float4 *>(X.p + s0 * T.n);
+#pragma unroll
+    for (int x = 0; x < Chunk<AUX>::kPieces; ++x) {
+        const int q = min(f0 + static_cast<int>(threadIdx.x) + WG * x, n4 - 1);
+        c.v[x] = src4[q];
+        if (AUX) c.u[x] = aux4[q];
+    }
+}
+
 // Stages samples s0 .. s0 + valid - 1 of T into rows row0 .. row0 + T.n - 1 as f(value, aux value, s, i); X is a
 // second tensor of the same shape read in step with T (AUX), e.g. the forward result beside the upstream gradient.
 // Contiguous tensors: the tile is one flat run of valid * n floats starting on a 16-byte boundary (64 samples per
-// tile), read in 16-byte pieces, several in flight per lane.
+// tile), read in 16-byte pieces; the caller has already requested the first chunk (stage_request with f0 = 0), so
+// that the requests of all tensors of a tile are in flight together.
 // FAST: the caller vouches for contiguous aligned tensors, n % 4 == 0 and a full tile; only that path is compiled.
 template <int WG, bool AUX, bool FAST, typename F>
-__device__ __forceinline__ void stage_tile(float *rows, int row0, const Rows2D &T, const Rows2D &X, int64_t s0, int valid, F f)
+__device__ __forceinline__ void stage_tile(float *rows, int row0, const Rows2D &T, const Rows2D &X, int64_t s0, int valid,
+                                           Chunk<AUX> &c, F f)
 {
     const int n = T.n, total = valid * n;
-    const float4 zero4 = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-    constexpr int kInFlight = AUX ? 4 : 2;     // 16-byte pieces a lane requests before it stores the first
+    constexpr int kPieces = Chunk<AUX>::kPieces;
     if (FAST || (T.vec && (!AUX || X.vec))) {
-        const float4 *src4 = reinterpret_cast<const float4 *>(T.p + s0 * n);
-        const float4 *aux4 = reinterpret_cast<const float4 *>(X.p + s0 * n);
         const int n4 = total >> 2;
-        for (int f0 = 0; f0 < n4; f0 += kInFlight * WG) {
-            float4 v[kInFlight], u[kInFlight];
+        for (int f0 = 0; f0 < n4; f0 += kPieces * WG) {
+            if (f0 > 0) stage_request<WG, AUX, FAST>(c, T, X, s0, valid, f0);
 #pragma unroll
-            for (int x = 0; x < kInFlight; ++x) {
-                const int q = min(f0 + static_cast<int>(threadIdx.x) + WG * x, n4 - 1);   // clamped: no branch
-                v[x] = src4[q];
-                u[x] = AUX ? aux4[q] : zero4;
-            }
-#pragma unroll
-            for (int x = 0; x < kInFlight; ++x) {
+            for (int x = 0; x < kPieces; ++x) {
                 const int q = f0 + threadIdx.x + WG * x;
                 if (q < n4) {
                     int s, i;
                     split(q << 2, n, T.inv_n, s, i);
-                    const float e[4] = {v[x].x, v[x].y, v[x].z, v[x].w}, a[4] = {u[x].x, u[x].y, u[x].z, u[x].w};
+                    const float e[4] = {c.v[x].x, c.v[x].y, c.v[x].z, c.v[x].w};
+                    const float a[4] = {AUX ? c.u[x].x : 0.0f, AUX ? c.u[x].y : 0.0f, AUX ? c.u[x].z : 0.0f, AUX ? c.u[x].w : 0.0f};
 #pragma unroll
                     for (int k = 0; k < 4; ++k) {
                         rows[slot_of(row0 + i, s)] = f(e[k], a[k], s, i);
@@ -260,9 +277,12 @@ damp_lds_fwd_kernel(int32_t batch, int32_t n_tiles, int32_t S, int32_t n_pk, con
     for (int tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
         const int64_t s0 = static_cast<int64_t>(tile) * kLdsTile;
         const int valid = FAST ? kLdsTile : static_cast<int>(min(static_cast<int64_t>(kLdsTile), batch - s0));
+        Chunk<false> ca, cb;
+        stage_request<kLdsFwdWG, false, FAST>(ca, A, A, s0, valid, 0);
+        stage_request<kLdsFwdWG, false, FAST>(cb, B, B, s0, valid, 0);
         __syncthreads();                             // the previous tile's readers are done (and the lists are in)
-        stage_tile<kLdsFwdWG, false, FAST>(rows, 0, A, A, s0, valid, plain);
-        stage_tile<kLdsFwdWG, false, FAST>(rows, na, B, B, s0, valid, plain);
+        stage_tile<kLdsFwdWG, false, FAST>(rows, 0, A, A, s0, valid, ca, plain);
+        stage_tile<kLdsFwdWG, false, FAST>(rows, na, B, B, s0, valid, cb, plain);
         __syncthreads();
         for (int blk = group; blk < n_blocks; blk += kLdsFwdWG / 16) {
             float4 o[4];
@@ -308,18 +328,23 @@ damp_lds_bwd_kernel(int32_t batch, int32_t n_tiles, int32_t n_pka, int32_t n_pkb
     for (int tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
         const int64_t s0 = static_cast<int64_t>(tile) * kLdsTile;
         const int valid = FAST ? kLdsTile : static_cast<int>(min(static_cast<int64_t>(kLdsTile), batch - s0));
+        Chunk<true> cg;
+        Chunk<false> ca, cb;
+        stage_request<kLdsBwdWG, true, FAST>(cg, G, O, s0, valid, 0);
+        stage_request<kLdsBwdWG, false, FAST>(ca, A, A, s0, valid, 0);
+        stage_request<kLdsBwdWG, false, FAST>(cb, B, B, s0, valid, 0);
         __syncthreads();
         if (threadIdx.x == 0) *flag = 0;
         __syncthreads();
         // gh = g gated by the clamp: out < 1 means the clamp did not act; elements with out == 1 are decided below
         int flagged = 0;
-        stage_tile<kLdsBwdWG, true, FAST>(rows, 0, G, O, s0, valid, [&](float v, float o, int, int) {
+        stage_tile<kLdsBwdWG, true, FAST>(rows, 0, G, O, s0, valid, cg, [&](float v, float o, int, int) {
             flagged |= !(o < 1.0f);
             return v;
         });
         if (flagged) atomicOr(flag, 1);
-        stage_tile<kLdsBwdWG, false, FAST>(rows, S, A, A, s0, valid, plain);
-        stage_tile<kLdsBwdWG, false, FAST>(rows, S + na, B, B, s0, valid, plain);
+        stage_tile<kLdsBwdWG, false, FAST>(rows, S, A, A, s0, valid, ca, plain);
+        stage_tile<kLdsBwdWG, false, FAST>(rows, S + na, B, B, s0, valid, cb, plain);
         __syncthreads();
         if (*flag) {                                 // rare: some output of this tile sits on the clamp
             for (int e = threadIdx.x; e < valid * S; e += kLdsBwdWG) {
