@@ -388,6 +388,39 @@ def test_fused_iteration_with_long_rows(dol, long_a, long_b):
     assert_close(host(ge), want_ge, "iterated apply: gradient of e")
 
 
+def test_fused_iteration_with_more_than_1024_symbols(dol):
+    """Four symbols of the first operand per thread (the widest build of the fused sweeps)."""
+    na, nb, B, rounds = 1100, 40, 3, 4
+    i = np.arange(na, dtype=np.int32)
+    ti = np.concatenate([i, i]); tj = np.concatenate([np.zeros(na, np.int32), 1 + i % 39])
+    to = np.concatenate([i, (i * 7 + 3) % na]).astype(np.int32)
+    order = np.lexsort((tj, ti))
+    tri = tuple(x[order].astype(np.int32) for x in (ti, tj, to))
+    r0 = (W.uniform01(1, B * na) * 0.3).astype(np.float32).reshape(B, na)
+    r0[:, 11] = 1.0
+    e = (W.uniform01(2, B * nb) * 0.3).astype(np.float32).reshape(B, nb)
+    e[:, 0] = 1.0
+    hist = [r0]
+    for t in range(rounds):
+        hist.append(oracle.damp_apply2_fwd(tri, na, nb, hist[-1], e)[1])
+    g = np.abs(W.normal(3, B * na)).astype(np.float32).reshape(B, na)
+    want_ge, gr = np.zeros((B, nb), np.float64), g
+    for t in reversed(range(rounds)):
+        gr, ge = oracle.damp_apply2_bwd(tri, na, nb, hist[t], e, gr)
+        want_ge += ge
+    f = dol.FnTable.create_sparse(na, nb, *tri)
+    d0, de = dol.Dist(np.arange(na), dev(r0)), dol.Dist(np.arange(nb), dev(e))
+    dh = torch.empty((rounds + 1, B, na), device="cuda")
+    dol.iterate_apply2(d0, de, f, rounds, dh)
+    got = host(dh)
+    assert_close(got, np.stack(hist), "iterated apply, 1100 symbols")
+    np.testing.assert_array_equal(got == 1.0, np.stack(hist) == 1.0)
+    g0, ge = torch.empty((B, na), device="cuda"), torch.empty((B, nb), device="cuda")
+    dol.iterate_backward(de, f, rounds, dh, dev(g), g0, ge)
+    assert_close(host(g0), gr, "iterated apply, 1100 symbols: gradient of r0")
+    assert_close(host(ge), want_ge, "iterated apply, 1100 symbols: gradient of e")
+
+
 def test_backward_of_tables_with_long_rows(dol):
     """A table whose rows hold hundreds of tuples (one symbol of b combines with every symbol of a)."""
     na, B = 300, 20
