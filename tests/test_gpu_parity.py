@@ -765,3 +765,55 @@ def test_hip_graph_replay_matches_eager(gp, which):
         torch.cuda.synchronize()
         graph.replay()
         np.testing.assert_array_equal(host(key()), eager)
+
+
+# ---------------------------------------------------------------- large batches: sampled rows against the oracle
+
+def _rows_of(w, idx, per_sample):
+    """A sub-workload holding only the samples `idx` (samples are independent, so the oracle can run on them alone)."""
+    arrays = {}
+    for name, arr in w.arrays.items():
+        axis = per_sample.get(name)
+        arrays[name] = arr if axis is None else np.ascontiguousarray(np.take(arr, idx, axis=axis))
+    params = dict(w.params, batch=len(idx))
+    return W.Workload(w.name, params, arrays)
+
+
+def _sample_rows(batch, n=48):
+    picks = (W.splitmix64(batch, np.arange(n, dtype=np.uint64)) % np.uint64(batch)).astype(np.int64)
+    return np.unique(np.concatenate([[0, 1, 63, 64, batch // 2, batch - 2, batch - 1], picks]))
+
+
+@pytest.mark.parametrize("cfg,batch", [(2, 200003), (3, 70001), (4, 50021), (5, 1031)])
+def test_large_batches_sampled_rows(gp, cfg, batch):
+    """The launch shapes of the B-scaled bench variants (odd batches, many tiles per workgroup, grids of 10^5
+    workgroups): rows sampled over the whole batch against the oracle run on those samples alone."""
+    w = W.make_config(cfg, batch=batch, seed=11)
+    idx = _sample_rows(batch)
+    if cfg == 2:
+        prog = gp.SumChainFused(w)
+        prog.step()
+        ref = OP.sum_chain_fwd_bwd(_rows_of(w, idx, dict(p=1, target=0)))
+        assert_close(host(prog.out.prob)[idx], ref["out"], "fold forward, sampled rows")
+        assert_close(host(prog.grad_p)[:, idx], ref["grad_p"], "fold gradient, sampled rows")
+    elif cfg == 3:
+        prog = gp.HashedPipelineFused(w)
+        prog.step()
+        ref = OP.hashed_pipeline_fwd_bwd(_rows_of(w, idx, dict(pa=0, pb=0, p2=0, g=0)))
+        assert_close(host(prog.o3.prob)[idx], ref["o3"], "hashed pipeline forward, sampled rows")
+        assert_close(host(prog.ga)[idx], ref["ga"], "hashed pipeline grad a, sampled rows")
+        assert_close(host(prog.gb)[idx], ref["gb"], "hashed pipeline grad b, sampled rows")
+        assert_close(host(prog.gp2)[idx], ref["gp2"], "hashed pipeline grad p2, sampled rows")
+    elif cfg == 4:
+        prog = gp.DtkpSumChainFused(w)
+        prog.step()
+        ref = OP.dtkp_sum_chain(_rows_of(w, idx, dict(p=1, fact_prob=0)))
+        np.testing.assert_array_equal(host(prog.out.proof_mask).view(np.uint64)[idx], ref["mask"])
+        np.testing.assert_array_equal(host(prog.out.proof_prob)[idx], ref["pprob"])
+        assert_close(host(prog.out.prob)[idx], ref["prob"], "dtkp fold, sampled rows")
+    else:
+        prog = gp.GridReachFused(w)
+        prog.step()
+        ref = OP.grid_reach_fwd_bwd(_rows_of(w, idx, dict(p=0, g=0)))
+        assert_close(host(prog.hist)[-1][idx], ref["r"], "reachability, sampled rows")
+        assert_close(host(prog.grad_p)[idx], ref["grad_p"], "reachability gradient, sampled rows")
