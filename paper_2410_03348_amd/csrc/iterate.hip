@@ -1,6 +1,6 @@
 // Repeated DAMP Apply with feedback (the fixed-round form of the recursion of App. B, Fig. 9):
 //     r_{t+1}[c] = min(1, sum over the tuples (i, j) of column c of r_t[i] * e[j]),
-// every round in one launch.  One workgroup of 512 threads owns a sample: r_t, r_{t+1} and the second
+// every round in one launch.  One workgroup of 1024 threads owns a sample: r_t, r_{t+1} and the second
 // operand sit in LDS; the function table never changes between rounds, so every thread keeps the tuples of
 // its own columns (rows, for the reverse sweep) in registers and a round is one burst of LDS reads, a short
 // fma chain and a barrier.  Tuples beyond the first few of a column are read through the caches; rows with
@@ -11,7 +11,7 @@
 
 namespace dol {
 
-constexpr int kItThreads = 512;
+constexpr int kItThreads = 1024;
 constexpr int kItWaves = kItThreads / kWave;
 constexpr int kItMaxK = 4;              // columns per thread: na, nb up to 2048
 constexpr int kItMaxRow = kItThreads * kItMaxK;
