@@ -280,10 +280,10 @@ damp_lds_fwd_kernel(int32_t batch, int32_t n_tiles, int32_t S, int32_t n_pk, con
         Chunk<false> ca, cb;
         stage_request<kLdsFwdWG, false, FAST>(ca, A, A, s0, valid, 0);
         stage_request<kLdsFwdWG, false, FAST>(cb, B, B, s0, valid, 0);
-        __syncthreads();                             // the previous tile's readers are done (and the lists are in)
+        lds_barrier();                             // the previous tile's readers are done (and the lists are in)
         stage_tile<kLdsFwdWG, false, FAST>(rows, 0, A, A, s0, valid, ca, plain);
         stage_tile<kLdsFwdWG, false, FAST>(rows, na, B, B, s0, valid, cb, plain);
-        __syncthreads();
+        lds_barrier();
         for (int blk = group; blk < n_blocks; blk += kLdsFwdWG / 16) {
             float4 o[4];
 #pragma unroll
@@ -333,9 +333,9 @@ damp_lds_bwd_kernel(int32_t batch, int32_t n_tiles, int32_t n_pka, int32_t n_pkb
         stage_request<kLdsBwdWG, true, FAST>(cg, G, O, s0, valid, 0);
         stage_request<kLdsBwdWG, false, FAST>(ca, A, A, s0, valid, 0);
         stage_request<kLdsBwdWG, false, FAST>(cb, B, B, s0, valid, 0);
-        __syncthreads();
+        lds_barrier();
         if (threadIdx.x == 0) *flag = 0;
-        __syncthreads();
+        lds_barrier();
         // gh = g gated by the clamp: out < 1 means the clamp did not act; elements with out == 1 are decided below
         int flagged = 0;
         stage_tile<kLdsBwdWG, true, FAST>(rows, 0, G, O, s0, valid, cg, [&](float v, float o, int, int) {
@@ -345,7 +345,7 @@ damp_lds_bwd_kernel(int32_t batch, int32_t n_tiles, int32_t n_pka, int32_t n_pkb
         if (flagged) atomicOr(flag, 1);
         stage_tile<kLdsBwdWG, false, FAST>(rows, S, A, A, s0, valid, ca, plain);
         stage_tile<kLdsBwdWG, false, FAST>(rows, S + na, B, B, s0, valid, cb, plain);
-        __syncthreads();
+        lds_barrier();
         if (*flag) {                                 // rare: some output of this tile sits on the clamp
             for (int e = threadIdx.x; e < valid * S; e += kLdsBwdWG) {
                 int s, c;
@@ -359,7 +359,7 @@ damp_lds_bwd_kernel(int32_t batch, int32_t n_tiles, int32_t n_pka, int32_t n_pkb
                     if (!(pre <= 1.0f)) rows[slot_of(c, s)] = 0.0f;
                 }
             }
-            __syncthreads();
+            lds_barrier();
         }
         for (int blk = group; blk < blocks_a + blocks_b; blk += kLdsBwdWG / 16) {
             const bool is_a = blk < blocks_a;

@@ -93,9 +93,9 @@ damp_rows_gather_kernel(RowTiles T, int32_t n_in, int32_t n_out, float inv_n_out
     for (int tile = blockIdx.x; tile < T.n_tiles; tile += gridDim.x) {
         const int64_t s0 = static_cast<int64_t>(tile) * T.rows_per_tile;
         const int rows = static_cast<int>(min(static_cast<int64_t>(T.rows_per_tile), T.batch - s0));
-        __syncthreads();
+        lds_barrier();
         stage_flat(tin, in + s0 * n_in, rows * n_in);
-        __syncthreads();
+        lds_barrier();
         emit_flat(out + s0 * n_out, rows, n_out, inv_n_out, accumulate != 0, [&](int r, int c) {
             const int32_t i = col[c];
             return i >= 0 ? tin[r * n_in + i] : 0.0f;
@@ -118,10 +118,10 @@ damp_rows_union_fwd_kernel(RowTiles T, int32_t na, int32_t nb, int32_t n_out, fl
     for (int tile = blockIdx.x; tile < T.n_tiles; tile += gridDim.x) {
         const int64_t s0 = static_cast<int64_t>(tile) * T.rows_per_tile;
         const int rows = static_cast<int>(min(static_cast<int64_t>(T.rows_per_tile), T.batch - s0));
-        __syncthreads();
+        lds_barrier();
         stage_flat(ta, a + s0 * na, rows * na);
         stage_flat(tb, b + s0 * nb, rows * nb);
-        __syncthreads();
+        lds_barrier();
         emit_flat(out + s0 * n_out, rows, n_out, inv_n_out, false, [&](int r, int c) {
             const int32_t i = ia[c], j = ib[c];
             if (i >= 0 && j >= 0) return fminf(ta[r * na + i] + tb[r * nb + j], 1.0f);
@@ -148,11 +148,11 @@ damp_rows_union_bwd_kernel(RowTiles T, int32_t na, int32_t nb, int32_t n_out, fl
     for (int tile = blockIdx.x; tile < T.n_tiles; tile += gridDim.x) {
         const int64_t s0 = static_cast<int64_t>(tile) * T.rows_per_tile;
         const int rows = static_cast<int>(min(static_cast<int64_t>(T.rows_per_tile), T.batch - s0));
-        __syncthreads();
+        lds_barrier();
         stage_flat(ta, a + s0 * na, rows * na);
         stage_flat(tb, b + s0 * nb, rows * nb);
         stage_flat(tg, g + s0 * n_out, rows * n_out);
-        __syncthreads();
+        lds_barrier();
         // the gradient of column c passes unless both operands are present and their sum exceeds 1
         auto gated = [&](int r, int c) {
             const int32_t i = ia[c], j = ib[c];

@@ -72,7 +72,7 @@ damp_iterate_fwd_kernel(int32_t batch, int32_t na, int32_t nb, int32_t rounds, c
     Cached<kItCacheA> col[K];
 #pragma unroll
     for (int k = 0; k < K; ++k) load_cached(col[k], col_ptr, col_ij, tid + kItThreads * k, na, pack16(na, nb));
-    __syncthreads();
+    lds_barrier();
     for (int t = 0; t < rounds; ++t) {
         float *ht = hs + (t + 1) * plane;
 #pragma unroll
@@ -84,7 +84,7 @@ damp_iterate_fwd_kernel(int32_t batch, int32_t na, int32_t nb, int32_t rounds, c
                 ht[c] = v;
             }
         }
-        __syncthreads();
+        lds_barrier();
         float *sw = r_cur; r_cur = r_nxt; r_nxt = sw;
     }
 }
@@ -106,7 +106,7 @@ __device__ __forceinline__ float block_sum(float x, float *red)
 #pragma unroll
     for (int d = 32; d >= 1; d >>= 1) x += __shfl_xor(x, d, kWave);
     if ((threadIdx.x & (kWave - 1)) == 0) red[threadIdx.x / kWave] = x;
-    __syncthreads();
+    lds_barrier();
     float tot = 0.0f;
 #pragma unroll
     for (int w = 0; w < kItWaves; ++w) tot += red[w];
@@ -188,7 +188,7 @@ damp_iterate_bwd_kernel(int32_t batch, int32_t na, int32_t nb, int32_t rounds, I
     for (int l = 0; l < kItLongCache; ++l)
 #pragma unroll
         for (int k = 0; k < kItMaxK; ++k) share_l[l][k] = 0.0f;
-    __syncthreads();
+    lds_barrier();
     // gradient reaching the unclamped sums of the last round: r_rounds < 1 means the clamp did not act
 #pragma unroll
     for (int k = 0; k < K; ++k) {
@@ -199,7 +199,7 @@ damp_iterate_bwd_kernel(int32_t batch, int32_t na, int32_t nb, int32_t rounds, I
             gh_cur[c] = gv;
         }
     }
-    __syncthreads();
+    lds_barrier();
     // One round.  `slot` carries this thread's piece of r_{t-2} from memory: with `primed` it was requested
     // kItAhead rounds ago and is re-armed here for round t - kItAhead; otherwise it is requested at the start of
     // the round.  The requests are unconditional (indices clamped) so that the wait in front of their use counts
@@ -271,7 +271,7 @@ damp_iterate_bwd_kernel(int32_t batch, int32_t na, int32_t nb, int32_t rounds, I
             for (int k = 0; k < K; ++k)
                 slot[k] = hs[max(t - 2 - kItAhead, 0) * plane + min(tid + kItThreads * k, na - 1)];
         }
-        __syncthreads();
+        lds_barrier();
         float *sw = gh_cur; gh_cur = gh_nxt; gh_nxt = sw;
         sw = h_cur; h_cur = h_pre; h_pre = h_in; h_in = sw;
     };
@@ -327,7 +327,7 @@ damp_iterate_bwd_kernel(int32_t batch, int32_t na, int32_t nb, int32_t rounds, I
             if (tid == 0) atomicAdd(&ge[jw[l]], tot);
         }
     }
-    __syncthreads();
+    lds_barrier();
     for (int j = tid; j < nb; j += kItThreads) grad_e[s * ldge + j] = ge[j];
 }
 
