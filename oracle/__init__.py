@@ -282,3 +282,78 @@ def dtkp_filter(pred, im, ip, iprob):
                                _p(ip, C.c_float), _p(iprob, C.c_float), C.c_int64(iprob.shape[1]),
                                _p(om, C.c_uint64), _p(op, C.c_float), _p(pr, C.c_float), C.c_int64(K)), "dtkp_filter")
     return om, op, pr
+
+
+def _ptr_array(arrs, ct):
+    return (C.POINTER(ct) * len(arrs))(*[_p(a, ct) for a in arrs])
+
+
+def dense_to_tuples(table):
+    """All index tuples of a dense int32 K-dimensional symbol table whose entry is >= 0, ascending: (idx[n,K], ids[n])."""
+    t = np.ascontiguousarray(table, np.int32)
+    idx = np.argwhere(t >= 0).astype(np.int32).reshape(-1, t.ndim)
+    return np.ascontiguousarray(idx), _i32(t[tuple(idx.T)])
+
+
+def damp_applyk_fwd(idx, to, ins, want_pre=False):
+    """Apply over K = len(ins) Distributions.  idx [n,K], to [n]; returns as damp_apply2_fwd."""
+    ins = [_f32(x) for x in ins]
+    K, B = len(ins), ins[0].shape[0]
+    idx = np.ascontiguousarray(idx, np.int32).reshape(-1, K)
+    to = _i32(to)
+    syms = out_syms(to)
+    S = syms.size
+    n_sym = _i32([x.shape[1] for x in ins])
+    ld = np.asarray([x.shape[1] for x in ins], np.int64)
+    out = np.empty((B, S), np.float32)
+    pre32 = np.empty((B, S), np.float32)
+    pre64 = np.empty((B, S), np.float64)
+    _chk(lib().orc_damp_applyk_fwd(
+        C.c_int(B), C.c_int(K), C.c_int64(to.size), _p(idx, C.c_int32), _p(to, C.c_int32), _p(n_sym, C.c_int32),
+        C.c_int(S), _p(syms, C.c_int32), _ptr_array(ins, C.c_float), _p(ld, C.c_int64),
+        _p(out, C.c_float), C.c_int64(S), _p(pre32, C.c_float), _p(pre64, C.c_double)), "damp_applyk_fwd")
+    return (syms, out, pre32, pre64) if want_pre else (syms, out)
+
+
+def damp_applyk_bwd(idx, to, ins, g):
+    """Returns the list of gradients, one [B, n_l] per operand."""
+    ins = [_f32(x) for x in ins]
+    g = _f32(g)
+    K, B = len(ins), ins[0].shape[0]
+    idx = np.ascontiguousarray(idx, np.int32).reshape(-1, K)
+    to = _i32(to)
+    syms = out_syms(to)
+    S = syms.size
+    assert g.shape == (B, S)
+    n_sym = _i32([x.shape[1] for x in ins])
+    ld = np.asarray([x.shape[1] for x in ins], np.int64)
+    gin = [np.empty_like(x) for x in ins]
+    _chk(lib().orc_damp_applyk_bwd(
+        C.c_int(B), C.c_int(K), C.c_int64(to.size), _p(idx, C.c_int32), _p(to, C.c_int32), _p(n_sym, C.c_int32),
+        C.c_int(S), _p(syms, C.c_int32), _ptr_array(ins, C.c_float), _p(ld, C.c_int64),
+        _p(g, C.c_float), C.c_int64(S), _ptr_array(gin, C.c_float), _p(ld, C.c_int64)), "damp_applyk_bwd")
+    return gin
+
+
+def dtkp_applyk(idx, to, k, fact_group, fact_prob, masks):
+    """Returns (out_syms, mask[B,S,k], pprob[B,S,k], prob[B,S]); masks: one [B,n_l,k] per operand."""
+    masks = [np.ascontiguousarray(m, np.uint64) for m in masks]
+    fp = _f32(fact_prob)
+    grp = None if fact_group is None else _i32(fact_group)
+    K, B = len(masks), fp.shape[0]
+    idx = np.ascontiguousarray(idx, np.int32).reshape(-1, K)
+    to = _i32(to)
+    syms = out_syms(to)
+    S = syms.size
+    for m in masks:
+        assert m.shape[0] == B and m.shape[2] == k
+    n_sym = _i32([m.shape[1] for m in masks])
+    om = np.empty((B, S, k), np.uint64)
+    op = np.empty((B, S, k), np.float32)
+    pr = np.empty((B, S), np.float32)
+    _chk(lib().orc_dtkp_applyk(
+        C.c_int(B), C.c_int(K), C.c_int64(to.size), _p(idx, C.c_int32), _p(to, C.c_int32), _p(n_sym, C.c_int32),
+        C.c_int(S), _p(syms, C.c_int32), C.c_int(k), C.c_int(fp.shape[1]), _p(grp, C.c_int32), _p(fp, C.c_float),
+        _ptr_array(masks, C.c_uint64), _p(om, C.c_uint64), _p(op, C.c_float), _p(pr, C.c_float), C.c_int64(S)),
+        "dtkp_applyk")
+    return syms, om, op, pr

@@ -2,8 +2,9 @@
  * dol_oracle.c -- TEST INFRASTRUCTURE, NOT PRODUCT CODE.
  *
  * A plain, slow, obviously-correct CPU statement of what the Dolphin hot path
- * computes (arXiv 2410.03348): the Distribution operators Apply (K=2), Filter
- * and Union (Sec. 3.1.2, Eq. 1-3) under the two provenances of Sec. 3.2 /
+ * computes (arXiv 2410.03348): the Distribution operators Apply / ApplyIf (two
+ * operands, and any number K >= 1 of them at the end of the file), Filter and
+ * Union (Sec. 3.1.2, Eq. 1-3) under the two provenances of Sec. 3.2 /
  * Table 1: DAMP (add-mult probabilities) with its vector-Jacobian products,
  * and DTKP-AM top-k proofs (App. A) in a fact-bitmask encoding.
  *
@@ -30,7 +31,9 @@
  *
  * Parity pins: every function here is pinned by tests/test_oracle_*.py
  * (worked examples of Ex. 3.1-3.3 and App. A.1, brute-force enumeration,
- * convolution and matrix-power closed forms, finite differences, invariants).
+ * convolution and matrix-power closed forms, finite differences, invariants;
+ * the K-operand routines also by agreement with the two-operand ones and by
+ * composition through an injective pairing function).
  */
 #include <math.h>
 #include <stdint.h>
@@ -609,5 +612,183 @@ int orc_dtkp_prob_bwd(int B, int n, int k, int n_facts, const uint64_t *mask, co
         }
         for (int f = 0; f < n_facts; ++f) gfact[(int64_t)s * n_facts + f] = (float)acc[f];
     }
+    return ORC_OK;
+}
+
+/* ------------------------------------------------------------------ Apply over K Distributions */
+
+/* Symbol side of Apply / ApplyIf for any arity K >= 1 (Sec. 3.1.2, Eq. 1-2): the
+ * admitted tuples arrive as idx[t*K + l] = position of the t-th tuple's symbol in
+ * operand l, ascending lexicographically, each once; to[t] is the produced symbol
+ * id (negative: the condition of ApplyIf rejects the tuple). */
+static int *ktuple_columns(int K, int64_t n, const int32_t *idx, const int32_t *to, const int32_t *n_sym,
+                           int S, const int32_t *out_syms, int *err)
+{
+    int *col = (int *)malloc(sizeof(int) * (size_t)(n > 0 ? n : 1));
+    *err = ORC_OK;
+    if (!col) { *err = ORC_ENOMEM; return NULL; }
+    if (K < 1) *err = ORC_EINVAL;
+    for (int64_t t = 0; t < n && !*err; ++t) {
+        for (int l = 0; l < K; ++l)
+            if (idx[t * K + l] < 0 || idx[t * K + l] >= n_sym[l]) *err = ORC_EINVAL;
+        if (t > 0) {
+            int order = 0;
+            for (int l = 0; l < K && order == 0; ++l)
+                order = (idx[t * K + l] > idx[(t - 1) * K + l]) - (idx[t * K + l] < idx[(t - 1) * K + l]);
+            if (order <= 0) *err = ORC_EINVAL;
+        }
+        col[t] = to[t] < 0 ? -1 : find_col(S, out_syms, to[t]);
+        if (to[t] >= 0 && col[t] < 0) *err = ORC_EINVAL;
+    }
+    if (*err) { free(col); return NULL; }
+    return col;
+}
+
+/* Eq. 1-3 under DAMP for K operands: the tag of a tuple is the product of its K
+ * input tags, the tag of an output symbol the clamped sum over the tuples that
+ * produce it.  The decision quantity pre32 is the float sum in tuple order from 0
+ * of one term per tuple: for K = 1 the tag itself is added; for K >= 2 the first
+ * K-1 tags are multiplied left to right in float and the product enters through
+ * one fused multiply-add with the last tag (K = 2 is then exactly the two-operand
+ * rule above).
+ * in[l] [B, ld[l]]; out [B,ldo]; pre32 / pre64 [B,S] optional. */
+int orc_damp_applyk_fwd(int B, int K, int64_t n, const int32_t *idx, const int32_t *to, const int32_t *n_sym,
+                        int S, const int32_t *out_syms, const float *const *in, const int64_t *ld,
+                        float *out, int64_t ldo, float *pre32, double *pre64)
+{
+    int err;
+    int *col = ktuple_columns(K, n, idx, to, n_sym, S, out_syms, &err);
+    if (!col) return err;
+#pragma omp parallel for schedule(static) num_threads(g_threads)
+    for (int s = 0; s < B; ++s) {
+        double *acc = (double *)calloc((size_t)(S > 0 ? S : 1), sizeof(double));
+        float *accf = (float *)calloc((size_t)(S > 0 ? S : 1), sizeof(float));
+        for (int64_t t = 0; t < n; ++t) {
+            if (col[t] < 0) continue;
+            double prod = 1.0;
+            for (int l = 0; l < K; ++l) prod *= (double)in[l][(int64_t)s * ld[l] + idx[t * K + l]];
+            acc[col[t]] += prod;
+            float head = in[0][(int64_t)s * ld[0] + idx[t * K]];
+            for (int l = 1; l + 1 < K; ++l) head = head * in[l][(int64_t)s * ld[l] + idx[t * K + l]];
+            if (K == 1) accf[col[t]] = accf[col[t]] + head;
+            else accf[col[t]] = fmaf(head, in[K - 1][(int64_t)s * ld[K - 1] + idx[t * K + K - 1]], accf[col[t]]);
+        }
+        for (int c = 0; c < S; ++c) {
+            out[(int64_t)s * ldo + c] = (float)(acc[c] < 1.0 ? acc[c] : 1.0);
+            if (pre32) pre32[(int64_t)s * S + c] = accf[c];
+            if (pre64) pre64[(int64_t)s * S + c] = acc[c];
+        }
+        free(acc); free(accf);
+    }
+    free(col);
+    return ORC_OK;
+}
+
+/* Vector-Jacobian product of the above: with gh[c] = g[c] * [pre32[c] <= 1],
+ *     gin_l[i] = sum over admitted tuples t with idx[t][l] = i of gh[col(t)] * prod_{m != l} in_m[idx[t][m]].
+ * gin[l] [B, ldgi[l]] is overwritten (a NULL entry is skipped). */
+int orc_damp_applyk_bwd(int B, int K, int64_t n, const int32_t *idx, const int32_t *to, const int32_t *n_sym,
+                        int S, const int32_t *out_syms, const float *const *in, const int64_t *ld,
+                        const float *g, int64_t ldg, float *const *gin, const int64_t *ldgi)
+{
+    int err;
+    int *col = ktuple_columns(K, n, idx, to, n_sym, S, out_syms, &err);
+    if (!col) return err;
+    int total = 0;
+    for (int l = 0; l < K; ++l) total += n_sym[l];
+    float *pre32 = (float *)malloc(sizeof(float) * (size_t)(B > 0 ? B : 1) * (size_t)(S > 0 ? S : 1));
+    float *tmp = (float *)malloc(sizeof(float) * (size_t)(B > 0 ? B : 1) * (size_t)(S > 0 ? S : 1));
+    err = orc_damp_applyk_fwd(B, K, n, idx, to, n_sym, S, out_syms, in, ld, tmp, S, pre32, NULL);
+    if (!err) {
+#pragma omp parallel for schedule(static) num_threads(g_threads)
+        for (int s = 0; s < B; ++s) {
+            double *d = (double *)calloc((size_t)(total > 0 ? total : 1), sizeof(double));
+            for (int64_t t = 0; t < n; ++t) {
+                if (col[t] < 0) continue;
+                if (!(pre32[(int64_t)s * S + col[t]] <= 1.0f)) continue;
+                const double gh = (double)g[(int64_t)s * ldg + col[t]];
+                int base = 0;
+                for (int l = 0; l < K; ++l) {
+                    double others = 1.0;
+                    for (int m = 0; m < K; ++m)
+                        if (m != l) others *= (double)in[m][(int64_t)s * ld[m] + idx[t * K + m]];
+                    d[base + idx[t * K + l]] += gh * others;
+                    base += n_sym[l];
+                }
+            }
+            int base = 0;
+            for (int l = 0; l < K; ++l) {
+                if (gin[l])
+                    for (int i = 0; i < n_sym[l]; ++i) gin[l][(int64_t)s * ldgi[l] + i] = (float)d[base + i];
+                base += n_sym[l];
+            }
+            free(d);
+        }
+    }
+    free(pre32); free(tmp); free(col);
+    return err;
+}
+
+/* Eq. 1-3 under DTKP-AM for K operands.  Table 1 gives the conjunction as a
+ * binary operation; the tag of a tuple is taken as that operation folded over the
+ * operands left to right, every intermediate result pruned to its top k proofs
+ * (K = 1: the operand's tag unchanged).  The disjunction over the tuples producing
+ * one symbol is one top_k over all their proofs, as in the two-operand routine.
+ * im[l] [B, n_sym[l], k]; outputs om/op [B,S,k], oprob [B,ldo]. */
+int orc_dtkp_applyk(int B, int K, int64_t n, const int32_t *idx, const int32_t *to, const int32_t *n_sym,
+                    int S, const int32_t *out_syms, int k, int n_facts, const int32_t *group,
+                    const float *fact_prob, const uint64_t *const *im,
+                    uint64_t *om, float *op, float *oprob, int64_t ldo)
+{
+    int err;
+    if (n_facts < 0 || n_facts > 63 || k < 1) return ORC_EINVAL;
+    int *col = ktuple_columns(K, n, idx, to, n_sym, S, out_syms, &err);
+    if (!col) return err;
+    int64_t *cnt = (int64_t *)calloc((size_t)(S + 1), sizeof(int64_t));
+    for (int64_t t = 0; t < n; ++t) if (col[t] >= 0) cnt[col[t] + 1]++;
+    for (int c = 0; c < S; ++c) cnt[c + 1] += cnt[c];
+#pragma omp parallel for schedule(static) num_threads(g_threads)
+    for (int s = 0; s < B; ++s) {
+        const float *fp = fact_prob + (int64_t)s * n_facts;
+        proof_t *cand = (proof_t *)malloc(sizeof(proof_t) * (size_t)(cnt[S] > 0 ? cnt[S] : 1) * (size_t)k);
+        proof_t *pairs = (proof_t *)malloc(sizeof(proof_t) * (size_t)k * (size_t)k);
+        uint64_t *cm = (uint64_t *)malloc(sizeof(uint64_t) * (size_t)k);
+        float *cp = (float *)malloc(sizeof(float) * (size_t)k);
+        int64_t *fill = (int64_t *)calloc((size_t)(S > 0 ? S : 1), sizeof(int64_t));
+        for (int64_t t = 0; t < n; ++t) {
+            int c = col[t];
+            if (c < 0) continue;
+            for (int x = 0; x < k; ++x) {
+                cm[x] = im[0][((int64_t)s * n_sym[0] + idx[t * K]) * k + x];
+                cp[x] = cm[x] == ABSENT ? 0.0f : proof_prob(cm[x], fp, n_facts);
+            }
+            for (int l = 1; l < K; ++l) {
+                int m = 0;
+                for (int x = 0; x < k; ++x) {
+                    if (cm[x] == ABSENT) continue;
+                    for (int y = 0; y < k; ++y) {
+                        uint64_t mb = im[l][((int64_t)s * n_sym[l] + idx[t * K + l]) * k + y];
+                        if (mb == ABSENT) continue;
+                        uint64_t u = cm[x] | mb;
+                        if (proof_conflict(u, n_facts, group)) continue;
+                        pairs[m].mask = u; pairs[m].prob = proof_prob(u, fp, n_facts); ++m;
+                    }
+                }
+                keep_top_k(pairs, m, k, cm, cp);
+            }
+            for (int x = 0; x < k; ++x) {
+                if (cm[x] == ABSENT) continue;
+                proof_t *q = cand + cnt[c] * k + fill[c]++;
+                q->mask = cm[x]; q->prob = cp[x];
+            }
+        }
+        for (int c = 0; c < S; ++c) {
+            int64_t o = ((int64_t)s * S + c) * k;
+            float pr = keep_top_k(cand + cnt[c] * k, (int)fill[c], k, om + o, op + o);
+            if (oprob) oprob[(int64_t)s * ldo + c] = pr;
+        }
+        free(cand); free(pairs); free(cm); free(cp); free(fill);
+    }
+    free(cnt); free(col);
     return ORC_OK;
 }
