@@ -38,6 +38,7 @@ extern "C" {
 
 #define DOL_MAX_K 8            /* DTKP: most proofs kept per tag */
 #define DOL_MAX_FACTS 63       /* DTKP: most input facts (bit 0..62); the all-ones mask marks an absent proof */
+#define DOL_MAX_ARITY 6        /* most operands of dol_apply_k */
 #define DOL_MAX_SYMBOLS 65535  /* most symbols per Distribution / operand of a function table */
 #define DOL_ABSENT_PROOF UINT64_MAX
 
@@ -98,6 +99,12 @@ const int32_t *dol_fn_table_out_syms(const dol_fn_table *table);
 const char *dol_fn_table_kernel(const dol_fn_table *table, int32_t which);
 /* Synchronises the device before releasing the device copies.  NULL is ignored. */
 void dol_fn_table_destroy(dol_fn_table *table);
+
+/* ApplyIf with K=2 (Sec. 3.1.2): the table of f_apply restricted to the tuples f_cond admits.
+ * out_id: host [na*nb] row-major, f_apply(i, j) (>= 0; entries where cond is 0 are not read);
+ * cond: host [na*nb], non-zero where f_cond(i, j) holds.  dol_apply2 with this table is ApplyIf. */
+dol_status dol_fn_table_create_if(int32_t na, int32_t nb, const int32_t *out_id, const uint8_t *cond,
+                                  dol_fn_table **table);
 
 /* Apply, K=2 (Eq. 1-3): out(s) = disjunction over admitted (i, j) with f(i, j) = s of a(i) conjunction b(j).
  * a->n_sym == na, b->n_sym == nb, out->n_sym == S, equal batch.  prov NULL = DAMP.
@@ -175,6 +182,39 @@ dol_status dol_backward(const dol_op_record *rec, const float *grad_out, float *
  * Asynchronous on the stream; errors as for the other calls. */
 dol_status dol_dtkp_backward(const dol_dist *d, const dol_prov *prov, const float *grad_prob, int64_t grad_prob_ld,
                              float *grad_fact_prob, void *hip_stream);
+
+/* ---- Apply / ApplyIf over K Distributions, K = 1..DOL_MAX_ARITY (Sec. 3.1.2: Apply: D^K x (S^K -> S) -> D,
+ * ApplyIf: D^K x (S^K -> S) x (S^K -> B) -> D; Eq. 1-3).  K = 1 is the unary Apply that maps every symbol through f
+ * and disjoins the tags of symbols with one image.
+ * Symbol side: the admitted tuples, once for the whole batch.  idx: host [n*K], idx[t*K + l] = position of tuple t's
+ * symbol in operand l (0 <= . < n_sym[l]); out_id: host [n], f(tuple) >= 0, or < 0 where f_cond rejects the tuple
+ * (such tuples are dropped).  Any order, each index tuple at most once.  The handle owns host and device copies. */
+typedef struct dol_fnk_table dol_fnk_table;
+dol_status dol_fnk_table_create(int32_t K, const int32_t *n_sym, int64_t n, const int32_t *idx,
+                                const int32_t *out_id, dol_fnk_table **table);
+/* Distinct produced symbols S and their ids ascending (host [S], valid until destroy): column c of the result. */
+int32_t dol_fnk_table_n_out(const dol_fnk_table *table);
+const int32_t *dol_fnk_table_out_syms(const dol_fnk_table *table);
+/* Synchronises the device before releasing the device copies.  NULL is ignored. */
+void dol_fnk_table_destroy(dol_fnk_table *table);
+
+/* out(s) = disjunction over admitted tuples with f(tuple) = s of in[0](i_0) conjunction ... conjunction in[K-1](i_{K-1}).
+ * in: host array of K Distributions, in[l]->n_sym == n_sym[l]; out->n_sym == S; equal batch.  prov NULL = DAMP.
+ * DAMP: out->prob[s,c] = min(1, pre), pre = float sum over the tuples of column c in ascending index order of one
+ *       term each: K = 1 adds the tag; K >= 2 multiplies the first K-1 tags left to right and enters the product
+ *       through one fused multiply-add with the last tag (K = 2 is dol_apply2's rule).  This fixes [pre <= 1].
+ * DTKP: the conjunction of Table 1 is binary; a tuple's tag is that operation folded over the operands left to
+ *       right, each intermediate pruned to its top k proofs; the disjunction is one top-k over the tuples' proofs.
+ *       Reads in[l]->proof_mask and, where not NULL, proof_prob (canonical, see dol_apply2); writes out->proof_mask,
+ *       out->proof_prob, out->prob. */
+dol_status dol_apply_k(int32_t K, const dol_dist *const *in, const dol_fnk_table *f, const dol_prov *prov,
+                       dol_dist *out, void *hip_stream);
+/* Vector-Jacobian product of dol_apply_k under DAMP: gh = grad_out * [pre <= 1],
+ *   grad_in[l][s, i] = sum over admitted tuples t with idx[t][l] = i of gh[s, col(t)] * prod_{m != l} in[m][s, idx[t][m]].
+ * out: the forward result (prob read); grad_out: device [batch, grad_out_ld]; grad_in: host array of K device
+ * pointers [batch, in[l]->ld], first n_sym[l] entries of each row OVERWRITTEN; a NULL entry is skipped. */
+dol_status dol_apply_k_backward(int32_t K, const dol_dist *const *in, const dol_fnk_table *f, const dol_dist *out,
+                                const float *grad_out, int64_t grad_out_ld, float *const *grad_in, void *hip_stream);
 
 /* A left fold of Apply under DAMP (the loop of Fig. 2: D_res = apply(D_res, D_i, f)), forward and backward in
  * ONE launch: acc_1 = apply2(inputs[0], inputs[1], tables[0]), acc_t = apply2(acc_{t-1}, inputs[t], tables[t-1]).

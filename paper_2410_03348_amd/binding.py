@@ -58,6 +58,17 @@ _i32p = C.POINTER(C.c_int32)
 _u8p = C.POINTER(C.c_uint8)
 _lib.dol_fn_table_create_dense.argtypes = [C.c_int32, C.c_int32, _i32p, C.POINTER(C.c_void_p)]
 _lib.dol_fn_table_create_sparse.argtypes = [C.c_int32, C.c_int32, C.c_int64, _i32p, _i32p, _i32p, C.POINTER(C.c_void_p)]
+_lib.dol_fn_table_create_if.argtypes = [C.c_int32, C.c_int32, _i32p, _u8p, C.POINTER(C.c_void_p)]
+_lib.dol_fnk_table_create.argtypes = [C.c_int32, _i32p, C.c_int64, _i32p, _i32p, C.POINTER(C.c_void_p)]
+_lib.dol_fnk_table_n_out.argtypes = [C.c_void_p]
+_lib.dol_fnk_table_n_out.restype = C.c_int32
+_lib.dol_fnk_table_out_syms.argtypes = [C.c_void_p]
+_lib.dol_fnk_table_out_syms.restype = _i32p
+_lib.dol_fnk_table_destroy.argtypes = [C.c_void_p]
+_lib.dol_fnk_table_destroy.restype = None
+_lib.dol_apply_k.argtypes = [C.c_int32, C.POINTER(C.POINTER(_Dist)), C.c_void_p, C.POINTER(_Prov), C.POINTER(_Dist), C.c_void_p]
+_lib.dol_apply_k_backward.argtypes = [C.c_int32, C.POINTER(C.POINTER(_Dist)), C.c_void_p, C.POINTER(_Dist), C.c_void_p,
+                                      C.c_int64, C.POINTER(C.c_void_p), C.c_void_p]
 _lib.dol_fn_table_n_out.argtypes = [C.c_void_p]
 _lib.dol_fn_table_n_out.restype = C.c_int32
 _lib.dol_fn_table_out_syms.argtypes = [C.c_void_p]
@@ -193,6 +204,16 @@ class FnTable:
         return FnTable(h, t.shape[0], t.shape[1])
 
     @staticmethod
+    def create_if(out_id, cond) -> "FnTable":
+        """ApplyIf: the table of out_id restricted to the tuples where cond is non-zero."""
+        t = _np_i32(out_id)
+        c = np.ascontiguousarray(cond, dtype=np.uint8)
+        assert t.ndim == 2 and c.shape == t.shape
+        h = C.c_void_p()
+        _check(_lib.dol_fn_table_create_if(t.shape[0], t.shape[1], _ptr(t, C.c_int32), _ptr(c, C.c_uint8), C.byref(h)))
+        return FnTable(h, t.shape[0], t.shape[1])
+
+    @staticmethod
     def create_sparse(na: int, nb: int, i, j, out_id) -> "FnTable":
         i, j, o = _np_i32(i), _np_i32(j), _np_i32(out_id)
         assert i.shape == j.shape == o.shape and i.ndim == 1
@@ -215,6 +236,59 @@ class FnTable:
 
 def apply2(a: Dist, b: Dist, f: FnTable, prov: Optional[Prov], out: Dist, stream=None):
     _check(_lib.dol_apply2(a.ref(), b.ref(), f._h, prov.ref() if prov else None, out.ref(), _stream(stream)))
+
+
+class FnkTable:
+    """dol_fnk_table handle: the admitted tuples of a function over K Distributions."""
+
+    def __init__(self, n_sym, idx, out_id):
+        n_sym, o = _np_i32(n_sym), _np_i32(out_id)
+        self.K = int(n_sym.size)
+        idx = _np_i32(idx).reshape(-1, self.K)
+        assert idx.shape[0] == o.size
+        h = C.c_void_p()
+        _check(_lib.dol_fnk_table_create(self.K, _ptr(n_sym, C.c_int32), o.size, _ptr(idx, C.c_int32),
+                                         _ptr(o, C.c_int32), C.byref(h)))
+        self._h, self.n_sym = h, n_sym
+        self.n_out = int(_lib.dol_fnk_table_n_out(h))
+        p = _lib.dol_fnk_table_out_syms(h)
+        self.out_syms = np.ctypeslib.as_array(p, shape=(self.n_out,)).copy() if self.n_out else np.empty(0, np.int32)
+
+    @staticmethod
+    def create_dense(out_id, cond=None) -> "FnkTable":
+        """out_id: int array with one axis per operand; entries < 0, or where cond is zero, are rejected tuples."""
+        t = _np_i32(out_id)
+        if cond is not None:
+            t = np.where(np.asarray(cond) != 0, t, -1).astype(np.int32)
+        idx = np.argwhere(t >= 0).astype(np.int32).reshape(-1, t.ndim)
+        return FnkTable(t.shape, idx, t[tuple(idx.T)])
+
+    def destroy(self):
+        if self._h is not None:
+            _lib.dol_fnk_table_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+def _dist_array(dists):
+    return (C.POINTER(_Dist) * len(dists))(*[C.pointer(d.c) for d in dists])
+
+
+def apply_k(ins, f: FnkTable, prov: Optional[Prov], out: Dist, stream=None):
+    _check(_lib.dol_apply_k(len(ins), _dist_array(ins), f._h, prov.ref() if prov else None, out.ref(), _stream(stream)))
+
+
+def apply_k_backward(ins, f: FnkTable, out: Dist, grad_out: torch.Tensor, grad_in, stream=None):
+    """grad_out [batch, >= n_out] (row stride = its stride(0)); grad_in: one tensor (rows of stride ins[l].ld) or None per operand."""
+    assert grad_out.dtype == torch.float32 and grad_out.dim() == 2 and grad_out.stride(1) == 1
+    ptrs = (C.c_void_p * len(ins))(*[None if g is None else g.data_ptr() for g in grad_in])
+    _check(_lib.dol_apply_k_backward(len(ins), _dist_array(ins), f._h, out.ref(), _dptr(grad_out),
+                                     max(int(grad_out.stride(0)), grad_out.shape[1]), ptrs, _stream(stream)))
 
 
 def filter_plan(d: Dist, pred_mask):

@@ -3,9 +3,9 @@
 
 namespace dol {
 
-static bool is_dtkp(const dol_prov *prov) { return prov && prov->kind == DOL_DTKP; }
+bool is_dtkp(const dol_prov *prov) { return prov && prov->kind == DOL_DTKP; }
 
-static dol_status check_prov(const dol_prov *prov, int32_t batch)
+dol_status check_prov(const dol_prov *prov, int32_t batch)
 {
     if (!prov) return DOL_OK;
     if (prov->kind != DOL_DAMP && prov->kind != DOL_DTKP) return fail(DOL_EINVAL, "unknown provenance kind %d", prov->kind);
@@ -19,7 +19,7 @@ static dol_status check_prov(const dol_prov *prov, int32_t batch)
 }
 
 // Shape and pointer checks of one Distribution.  need_ids: the call reads sym_ids.
-static dol_status check_dist(const dol_dist *d, const char *name, bool dtkp, bool need_ids, bool need_prob)
+dol_status check_dist(const dol_dist *d, const char *name, bool dtkp, bool need_ids, bool need_prob)
 {
     if (!d) return fail(DOL_EINVAL, "%s is NULL", name);
     if (d->batch < 0) return fail(DOL_ESHAPE, "%s.batch is negative", name);
@@ -36,7 +36,7 @@ static dol_status check_dist(const dol_dist *d, const char *name, bool dtkp, boo
     return DOL_OK;
 }
 
-static dol_status check_work(int64_t batch, int64_t per_sample)
+dol_status check_work(int64_t batch, int64_t per_sample)
 {
     // one thread per element, at most 2^31-1 workgroups of >= 128 threads
     if (batch * per_sample > (int64_t(1) << 37)) return fail(DOL_EUNSUPPORTED, "batch * symbols = %lld exceeds 2^37", static_cast<long long>(batch * per_sample));

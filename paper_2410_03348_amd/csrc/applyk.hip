@@ -1,0 +1,409 @@
+// Apply / ApplyIf over K Distributions, K = 1..DOL_MAX_ARITY, and the unary Apply (Sec. 3.1.2, Eq. 1-3) for gfx950:
+// symbol-side plan, DAMP forward and vector-Jacobian product, DTKP-AM forward.
+//
+// The admitted tuples are kept as 16-bit operand positions, grouped by the output column they land in and, inside a
+// column, in ascending index order (the order the float sum of a column is defined in).  For the backward pass every
+// operand row lists the tuples it takes part in.  One thread owns one (sample, output symbol) in the forward kernels
+// and one (sample, operand symbol) in the backward kernel; lanes run along a row, so stores are coalesced and the
+// gathers of neighbouring lanes fall into the same few cache lines of the sample's tag rows.
+#include "dtkp_util.h"
+#include "element_map.h"
+#include "internal.h"
+
+#include <algorithm>
+#include <memory>
+#include <new>
+#include <numeric>
+
+struct dol_fnk_table {
+    int32_t K = 0;
+    int32_t n_sym[DOL_MAX_ARITY] = {};
+    int32_t row_base[DOL_MAX_ARITY + 1] = {};   // operand l owns rows row_base[l] .. row_base[l+1] of row_ptr
+    int32_t n_out = 0;
+    int64_t n_tuples = 0;
+    std::vector<int32_t> out_syms;
+    dol::DevArray<uint32_t> col_ptr;     // [n_out+1] tuples of a column
+    dol::DevArray<uint16_t> tup;         // [n_tuples*K] operand positions, column-grouped
+    dol::DevArray<uint32_t> tup_col;     // [n_tuples] column of each grouped tuple
+    dol::DevArray<uint32_t> row_ptr;     // [sum n_sym + 1]
+    dol::DevArray<uint32_t> row_tup;     // [n_tuples*K] grouped-tuple numbers of each operand row, ascending
+    int device = 0;
+};
+
+namespace dol {
+
+struct KOperands {
+    const float *p[DOL_MAX_ARITY];
+    int64_t ld[DOL_MAX_ARITY];
+};
+
+struct KGrads {
+    float *p[DOL_MAX_ARITY];
+    int32_t row_base[DOL_MAX_ARITY + 1];
+};
+
+struct KProofs {
+    const uint64_t *m[DOL_MAX_ARITY];
+    const float *p[DOL_MAX_ARITY];
+    int32_t n[DOL_MAX_ARITY];
+};
+
+// ---------------------------------------------------------------- DAMP
+
+// pre of one column: tuples in ascending index order, one term each (the order fixes the clamp decision).
+template <int K>
+__device__ __forceinline__ float column_sum_k(const float *const *row, const uint16_t *__restrict__ tup,
+                                              uint32_t q0, uint32_t q1)
+{
+    float acc = 0.0f;
+    for (uint32_t q = q0; q < q1; ++q) {
+        const uint16_t *t = tup + static_cast<size_t>(q) * K;
+        float head = row[0][t[0]];
+#pragma unroll
+        for (int l = 1; l + 1 < K; ++l) head = head * row[l][t[l]];
+        if (K == 1) acc = acc + head;
+        else acc = __builtin_fmaf(head, row[K - 1][t[K - 1]], acc);
+    }
+    return acc;
+}
+
+template <int K>
+__global__ void __launch_bounds__(kThreads)
+damp_applyk_fwd_kernel(Rows R, KOperands in, const uint32_t *__restrict__ col_ptr, const uint16_t *__restrict__ tup,
+                       float *__restrict__ out, int64_t ldo)
+{
+    for_each_element(R, [&](int64_t s, int c) {
+        const float *row[K];
+#pragma unroll
+        for (int l = 0; l < K; ++l) row[l] = in.p[l] + s * in.ld[l];
+        out[s * ldo + c] = fminf(column_sum_k<K>(row, tup, col_ptr[c], col_ptr[c + 1]), 1.0f);
+    });
+}
+
+template <int K>
+__global__ void __launch_bounds__(kThreads)
+damp_applyk_bwd_kernel(Rows R, KOperands in, KGrads gin, const uint32_t *__restrict__ col_ptr,
+                       const uint16_t *__restrict__ tup, const uint32_t *__restrict__ tup_col,
+                       const uint32_t *__restrict__ row_ptr, const uint32_t *__restrict__ row_tup,
+                       const float *__restrict__ out, int64_t ldo, const float *__restrict__ g, int64_t ldg)
+{
+    for_each_element(R, [&](int64_t s, int x) {
+        int l = 0;
+#pragma unroll
+        for (int m = 1; m < K; ++m) l = x >= gin.row_base[m] ? m : l;
+        float *dst = nullptr;
+#pragma unroll
+        for (int m = 0; m < K; ++m) dst = l == m ? gin.p[m] : dst;
+        if (!dst) return;
+        const float *row[K];
+#pragma unroll
+        for (int m = 0; m < K; ++m) row[m] = in.p[m] + s * in.ld[m];
+        float acc = 0.0f;
+        for (uint32_t q = row_ptr[x], q1 = row_ptr[x + 1]; q < q1; ++q) {
+            const uint32_t tn = row_tup[q], c = tup_col[tn];
+            float gh = g[s * ldg + c];
+            // out < 1: the clamp did not act; out == 1 leaves pre == 1 (passes) and pre > 1 (blocks) apart only by pre
+            if (out[s * ldo + c] >= 1.0f && !(column_sum_k<K>(row, tup, col_ptr[c], col_ptr[c + 1]) <= 1.0f)) gh = 0.0f;
+            const uint16_t *t = tup + static_cast<size_t>(tn) * K;
+            float others = 1.0f;
+#pragma unroll
+            for (int m = 0; m < K; ++m)
+                if (m != l) others = others * row[m][t[m]];
+            acc = __builtin_fmaf(gh, others, acc);
+        }
+        int64_t ld = 0;
+        int32_t base = 0;
+#pragma unroll
+        for (int m = 0; m < K; ++m)
+            if (l == m) { ld = in.ld[m]; base = gin.row_base[m]; }
+        dst[s * ld + (x - base)] = acc;
+    });
+}
+
+template <int K>
+static void launch_fwd_k(const Rows &R, const KOperands &in, const dol_fnk_table *f, float *out, int64_t ldo, hipStream_t st)
+{
+    hipLaunchKernelGGL(damp_applyk_fwd_kernel<K>, dim3(R.grid), dim3(kThreads), 0, st, R, in, f->col_ptr.ptr, f->tup.ptr,
+                       out, ldo);
+}
+
+template <int K>
+static void launch_bwd_k(const Rows &R, const KOperands &in, const KGrads &gin, const dol_fnk_table *f, const float *out,
+                         int64_t ldo, const float *g, int64_t ldg, hipStream_t st)
+{
+    hipLaunchKernelGGL(damp_applyk_bwd_kernel<K>, dim3(R.grid), dim3(kThreads), 0, st, R, in, gin, f->col_ptr.ptr,
+                       f->tup.ptr, f->tup_col.ptr, f->row_ptr.ptr, f->row_tup.ptr, out, ldo, g, ldg);
+}
+
+#define DOL_DISPATCH_ARITY(K, CALL)  \
+    switch (K) {                     \
+    case 1: CALL(1); break;          \
+    case 2: CALL(2); break;          \
+    case 3: CALL(3); break;          \
+    case 4: CALL(4); break;          \
+    case 5: CALL(5); break;          \
+    default: CALL(6); break;         \
+    }
+
+// ---------------------------------------------------------------- DTKP-AM
+
+constexpr int kThreadsP = 128;
+
+// One thread per (sample, output symbol).  A tuple's tag is the binary conjunction of Table 1 folded over the
+// operands left to right, each intermediate pruned to k proofs; the tuples' proofs then meet in one k-entry list.
+template <int KP>
+__global__ void __launch_bounds__(kThreadsP)
+dtkp_applyk_kernel(int64_t total, int32_t S, int32_t arity, KProofs in, const uint32_t *__restrict__ col_ptr,
+                   const uint16_t *__restrict__ tup, GroupMasks gm, int32_t n_facts, const float *__restrict__ fact_prob,
+                   uint64_t *__restrict__ om, float *__restrict__ op, float *__restrict__ oprob, int64_t ldo)
+{
+    const int64_t idx = static_cast<int64_t>(blockIdx.x) * kThreadsP + threadIdx.x;
+    if (idx >= total) return;
+    const int64_t s = idx / S;
+    const int32_t c = static_cast<int32_t>(idx - s * S);
+    const float *fp = fact_prob + s * n_facts;
+    TopK<KP> top;
+    top.clear();
+    for (uint32_t q = col_ptr[c], q1 = col_ptr[c + 1]; q < q1; ++q) {
+        const uint16_t *t = tup + static_cast<size_t>(q) * arity;
+        TopK<KP> cur;
+        {
+            const int64_t o = (s * in.n[0] + t[0]) * KP;
+#pragma unroll
+            for (int x = 0; x < KP; ++x) {
+                const uint64_t m = in.m[0][o + x];
+                cur.m[x] = m;
+                cur.p[x] = m == kAbsent ? -1.0f : in.p[0] ? in.p[0][o + x] : proof_prob(m, fp);
+            }
+        }
+        for (int l = 1; l < arity; ++l) {
+            const int64_t o = (s * in.n[l] + t[l]) * KP;
+            uint64_t mb[KP];
+            float pb[KP];
+#pragma unroll
+            for (int y = 0; y < KP; ++y) {
+                mb[y] = in.m[l][o + y];
+                pb[y] = in.p[l] ? in.p[l][o + y] : -1.0f;
+            }
+            TopK<KP> nxt;
+            nxt.clear();
+#pragma unroll
+            for (int x = 0; x < KP; ++x) {
+                if (cur.m[x] == kAbsent) continue;
+#pragma unroll
+                for (int y = 0; y < KP; ++y) {
+                    if (mb[y] == kAbsent) continue;
+                    const uint64_t u = cur.m[x] | mb[y];
+                    if (proof_conflict(u, gm)) continue;
+                    nxt.insert(u, union_prob(cur.m[x], cur.p[x], mb[y], pb[y], fp));
+                }
+            }
+            cur = nxt;
+        }
+#pragma unroll
+        for (int x = 0; x < KP; ++x)
+            if (cur.m[x] != kAbsent) top.insert(cur.m[x], cur.p[x]);
+    }
+    oprob[s * ldo + c] = top.store(om + idx * KP, op + idx * KP);
+}
+
+template <int KP>
+static void launch_dtkp_k(int64_t total, const dol_fnk_table *f, const KProofs &in, const GroupMasks &gm, int32_t n_facts,
+                          const float *fact_prob, uint64_t *om, float *op, float *oprob, int64_t ldo, hipStream_t st)
+{
+    hipLaunchKernelGGL(dtkp_applyk_kernel<KP>, dim3(static_cast<unsigned>((total + kThreadsP - 1) / kThreadsP)),
+                       dim3(kThreadsP), 0, st, total, f->n_out, f->K, in, f->col_ptr.ptr, f->tup.ptr, gm, n_facts,
+                       fact_prob, om, op, oprob, ldo);
+}
+
+// ---------------------------------------------------------------- plan
+
+static dol_status build_k(int32_t K, const int32_t *n_sym, int64_t n, const int32_t *idx, const int32_t *out_id,
+                          dol_fnk_table **out)
+{
+    std::unique_ptr<dol_fnk_table> tb(new (std::nothrow) dol_fnk_table);
+    if (!tb) return fail(DOL_ENOMEM, "out of host memory");
+    tb->K = K;
+    for (int l = 0; l < K; ++l) {
+        tb->n_sym[l] = n_sym[l];
+        tb->row_base[l + 1] = tb->row_base[l] + n_sym[l];
+    }
+    // admitted tuples in ascending index order; a function has one value per argument tuple
+    std::vector<int64_t> order;
+    order.reserve(static_cast<size_t>(n));
+    for (int64_t t = 0; t < n; ++t) {
+        for (int l = 0; l < K; ++l)
+            if (idx[t * K + l] < 0 || idx[t * K + l] >= n_sym[l])
+                return fail(DOL_ESHAPE, "tuple %lld: position %d outside operand %d with %d symbols",
+                            static_cast<long long>(t), idx[t * K + l], l, n_sym[l]);
+        if (out_id[t] >= 0) order.push_back(t);
+    }
+    auto less = [&](int64_t x, int64_t y) { return std::lexicographical_compare(idx + x * K, idx + x * K + K, idx + y * K, idx + y * K + K); };
+    std::sort(order.begin(), order.end(), less);
+    for (size_t t = 1; t < order.size(); ++t)
+        if (!less(order[t - 1], order[t])) return fail(DOL_EINVAL, "the tuple list names one index tuple twice (entries %lld and %lld)",
+                                                       static_cast<long long>(order[t - 1]), static_cast<long long>(order[t]));
+    const size_t m = order.size();
+    if (m * static_cast<size_t>(K) > (size_t(1) << 31)) return fail(DOL_EUNSUPPORTED, "more than 2^31 tuple entries");
+    tb->n_tuples = static_cast<int64_t>(m);
+
+    // Eq. 2: the output symbols are the distinct produced ids, ascending
+    for (int64_t t : order) tb->out_syms.push_back(out_id[t]);
+    std::sort(tb->out_syms.begin(), tb->out_syms.end());
+    tb->out_syms.erase(std::unique(tb->out_syms.begin(), tb->out_syms.end()), tb->out_syms.end());
+    if (tb->out_syms.size() > DOL_MAX_SYMBOLS)
+        return fail(DOL_EUNSUPPORTED, "the function produces %zu symbols, more than %d", tb->out_syms.size(), DOL_MAX_SYMBOLS);
+    const int32_t S = tb->n_out = static_cast<int32_t>(tb->out_syms.size());
+
+    // stable counting sort by column
+    std::vector<uint32_t> col(m), col_ptr(S + 1, 0);
+    for (size_t t = 0; t < m; ++t) {
+        col[t] = static_cast<uint32_t>(std::lower_bound(tb->out_syms.begin(), tb->out_syms.end(), out_id[order[t]]) - tb->out_syms.begin());
+        col_ptr[col[t] + 1]++;
+    }
+    for (int32_t c = 0; c < S; ++c) col_ptr[c + 1] += col_ptr[c];
+    std::vector<uint16_t> tup(m * K);
+    std::vector<uint32_t> tup_col(m);
+    {
+        std::vector<uint32_t> fill(col_ptr.begin(), col_ptr.end() - 1);
+        for (size_t t = 0; t < m; ++t) {
+            const uint32_t pos = fill[col[t]]++;
+            for (int l = 0; l < K; ++l) tup[static_cast<size_t>(pos) * K + l] = static_cast<uint16_t>(idx[order[t] * K + l]);
+            tup_col[pos] = col[t];
+        }
+    }
+    // rows of every operand: the grouped tuples they take part in, ascending
+    const int32_t rows = tb->row_base[K];
+    std::vector<uint32_t> row_ptr(rows + 1, 0), row_tup(m * K);
+    for (size_t t = 0; t < m; ++t)
+        for (int l = 0; l < K; ++l) row_ptr[tb->row_base[l] + tup[t * K + l] + 1]++;
+    for (int32_t r = 0; r < rows; ++r) row_ptr[r + 1] += row_ptr[r];
+    {
+        std::vector<uint32_t> fill(row_ptr.begin(), row_ptr.end() - 1);
+        for (size_t t = 0; t < m; ++t)
+            for (int l = 0; l < K; ++l) row_tup[fill[tb->row_base[l] + tup[t * K + l]]++] = static_cast<uint32_t>(t);
+    }
+
+    DOL_HIP(hipGetDevice(&tb->device));
+    DOL_HIP(tb->col_ptr.upload(col_ptr));
+    DOL_HIP(tb->tup.upload(tup));
+    DOL_HIP(tb->tup_col.upload(tup_col));
+    DOL_HIP(tb->row_ptr.upload(row_ptr));
+    DOL_HIP(tb->row_tup.upload(row_tup));
+    *out = tb.release();
+    return DOL_OK;
+}
+
+static dol_status check_operands(int32_t K, const dol_dist *const *in, const dol_fnk_table *f, bool dtkp)
+{
+    if (!f) return fail(DOL_EINVAL, "function table is NULL");
+    if (K != f->K) return fail(DOL_ESHAPE, "K = %d, the table was built for %d operands", K, f->K);
+    if (!in) return fail(DOL_EINVAL, "in is NULL");
+    for (int l = 0; l < K; ++l) {
+        char name[16];
+        snprintf(name, sizeof name, "in[%d]", l);
+        if (dol_status st = check_dist(in[l], name, dtkp, false, !dtkp)) return st;
+        if (in[l]->batch != in[0]->batch) return fail(DOL_ESHAPE, "batch sizes differ: in[0] has %d, in[%d] has %d", in[0]->batch, l, in[l]->batch);
+        if (in[l]->n_sym != f->n_sym[l]) return fail(DOL_ESHAPE, "in[%d] has %d symbols, the table expects %d", l, in[l]->n_sym, f->n_sym[l]);
+    }
+    return DOL_OK;
+}
+
+}  // namespace dol
+
+using namespace dol;
+
+extern "C" {
+
+dol_status dol_fnk_table_create(int32_t K, const int32_t *n_sym, int64_t n, const int32_t *idx, const int32_t *out_id,
+                                dol_fnk_table **table)
+{
+    if (!table) return fail(DOL_EINVAL, "table is NULL");
+    *table = nullptr;
+    if (K < 1 || K > DOL_MAX_ARITY) return fail(DOL_EINVAL, "K = %d outside 1..%d", K, DOL_MAX_ARITY);
+    if (!n_sym) return fail(DOL_EINVAL, "n_sym is NULL");
+    for (int l = 0; l < K; ++l)
+        if (n_sym[l] < 0 || n_sym[l] > DOL_MAX_SYMBOLS) return fail(DOL_ESHAPE, "n_sym[%d] = %d outside 0..%d", l, n_sym[l], DOL_MAX_SYMBOLS);
+    if (n < 0) return fail(DOL_EINVAL, "negative tuple count");
+    if (n > 0 && (!idx || !out_id)) return fail(DOL_EINVAL, "tuple arrays are NULL");
+    return build_k(K, n_sym, n, idx, out_id, table);
+}
+
+int32_t dol_fnk_table_n_out(const dol_fnk_table *table) { return table ? table->n_out : 0; }
+
+const int32_t *dol_fnk_table_out_syms(const dol_fnk_table *table) { return table ? table->out_syms.data() : nullptr; }
+
+void dol_fnk_table_destroy(dol_fnk_table *table) { delete table; }
+
+dol_status dol_apply_k(int32_t K, const dol_dist *const *in, const dol_fnk_table *f, const dol_prov *prov, dol_dist *out,
+                       void *hip_stream)
+{
+    const bool dtkp = is_dtkp(prov);
+    if (dol_status st = check_operands(K, in, f, dtkp)) return st;
+    if (dol_status st = check_dist(out, "out", dtkp, false, true)) return st;
+    const int32_t batch = in[0]->batch;
+    if (dol_status st = check_prov(prov, batch)) return st;
+    if (out->batch != batch) return fail(DOL_ESHAPE, "batch sizes differ: in[0] has %d, out has %d", batch, out->batch);
+    if (out->n_sym != f->n_out) return fail(DOL_ESHAPE, "out.n_sym = %d, the table produces %d symbols", out->n_sym, f->n_out);
+    if (out->sym_ids)
+        for (int32_t c = 0; c < f->n_out; ++c)
+            if (out->sym_ids[c] != f->out_syms[c]) return fail(DOL_EINVAL, "out.sym_ids[%d] = %d, the table produces %d there", c, out->sym_ids[c], f->out_syms[c]);
+    if (dol_status st = check_work(batch, f->n_out)) return st;
+    if (batch == 0 || f->n_out == 0) return DOL_OK;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (!dtkp) {
+        KOperands ops{};
+        for (int l = 0; l < K; ++l) { ops.p[l] = in[l]->prob; ops.ld[l] = in[l]->ld; }
+        const Rows R = rows_of(batch, f->n_out);
+#define CALL(KK) launch_fwd_k<KK>(R, ops, f, out->prob, out->ld, st)
+        DOL_DISPATCH_ARITY(K, CALL)
+#undef CALL
+        DOL_HIP(hipGetLastError());
+        return DOL_OK;
+    }
+    if (!out->proof_prob) return fail(DOL_EINVAL, "out.proof_prob is NULL");
+    GroupMasks gm;
+    if (dol_status s2 = make_group_masks(prov, &gm)) return s2;
+    KProofs pr{};
+    for (int l = 0; l < K; ++l) { pr.m[l] = in[l]->proof_mask; pr.p[l] = in[l]->proof_prob; pr.n[l] = in[l]->n_sym; }
+    const int64_t total = static_cast<int64_t>(batch) * f->n_out;
+    switch (prov->k) {
+#define CASE(KP) case KP: launch_dtkp_k<KP>(total, f, pr, gm, prov->n_facts, prov->fact_prob, out->proof_mask, out->proof_prob, out->prob, out->ld, st); break;
+        CASE(1) CASE(2) CASE(3) CASE(4) CASE(5) CASE(6) CASE(7) CASE(8)
+#undef CASE
+    default: return fail(DOL_EINVAL, "k = %d outside 1..%d", prov->k, DOL_MAX_K);
+    }
+    DOL_HIP(hipGetLastError());
+    return DOL_OK;
+}
+
+dol_status dol_apply_k_backward(int32_t K, const dol_dist *const *in, const dol_fnk_table *f, const dol_dist *out,
+                                const float *grad_out, int64_t grad_out_ld, float *const *grad_in, void *hip_stream)
+{
+    if (dol_status st = check_operands(K, in, f, false)) return st;
+    if (dol_status st = check_dist(out, "out", false, false, true)) return st;
+    const int32_t batch = in[0]->batch;
+    if (out->batch != batch) return fail(DOL_ESHAPE, "batch sizes differ: in[0] has %d, out has %d", batch, out->batch);
+    if (out->n_sym != f->n_out) return fail(DOL_ESHAPE, "out.n_sym = %d, the table produces %d symbols", out->n_sym, f->n_out);
+    if (!grad_in) return fail(DOL_EINVAL, "grad_in is NULL");
+    if (grad_out_ld < f->n_out) return fail(DOL_ESHAPE, "grad_out_ld = %lld smaller than %d symbols", static_cast<long long>(grad_out_ld), f->n_out);
+    const int32_t rows = f->row_base[K];
+    if (dol_status st = check_work(batch, rows)) return st;
+    bool any = false;
+    for (int l = 0; l < K; ++l) any |= grad_in[l] != nullptr && f->n_sym[l] > 0;
+    if (batch == 0 || rows == 0 || !any) return DOL_OK;
+    if (f->n_out > 0 && !grad_out) return fail(DOL_EINVAL, "grad_out is NULL");
+    KOperands ops{};
+    KGrads gr{};
+    for (int l = 0; l < K; ++l) { ops.p[l] = in[l]->prob; ops.ld[l] = in[l]->ld; gr.p[l] = grad_in[l]; }
+    for (int l = 0; l <= K; ++l) gr.row_base[l] = f->row_base[l];
+    const Rows R = rows_of(batch, rows);
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+#define CALL(KK) launch_bwd_k<KK>(R, ops, gr, f, out->prob, out->ld, grad_out, grad_out_ld, st)
+    DOL_DISPATCH_ARITY(K, CALL)
+#undef CALL
+    DOL_HIP(hipGetLastError());
+    return DOL_OK;
+}
+
+}  // extern "C"

@@ -6,50 +6,11 @@
 // touch adjacent addresses.  A workgroup owns a chunk of whole rows (about 2048 elements) and splits its
 // flat element index into (row, column) with a float reciprocal, which is exact for such small indices.
 // Sum-shaped tables take the LDS kernels of damp_conv.hip instead.
+#include "element_map.h"
 #include "internal.h"
 #include "wave_util.h"
 
 namespace dol {
-
-constexpr int kThreads = 256;
-constexpr int kChunk = 2048;            // elements per workgroup (whole rows)
-
-struct Rows {                           // how a [batch, n] element space is cut into workgroup chunks
-    int32_t batch, n, rpb;
-    float inv_n;
-    unsigned grid;
-};
-
-static Rows rows_of(int32_t batch, int32_t n)
-{
-    Rows r;
-    r.batch = batch;
-    r.n = n;
-    r.rpb = n >= kChunk ? 1 : kChunk / n;
-    r.inv_n = 1.0f / static_cast<float>(n);
-    r.grid = static_cast<unsigned>((static_cast<int64_t>(batch) + r.rpb - 1) / r.rpb);
-    return r;
-}
-
-// Calls f(sample, column) for every element of this workgroup's chunk.
-template <typename F>
-__device__ __forceinline__ void for_each_element(const Rows &R, F f)
-{
-    const int64_t s0 = static_cast<int64_t>(blockIdx.x) * R.rpb;
-    if (R.rpb == 1) {
-        for (int c = threadIdx.x; c < R.n; c += kThreads) f(s0, c);
-        return;
-    }
-    const int rows = static_cast<int>(min(static_cast<int64_t>(R.rpb), R.batch - s0));
-    const int total = rows * R.n;
-#pragma unroll 4
-    for (int e = threadIdx.x; e < total; e += kThreads) {
-        int r = static_cast<int>(static_cast<float>(e) * R.inv_n);
-        int c = e - r * R.n;
-        if (c < 0) { c += R.n; --r; } else if (c >= R.n) { c -= R.n; ++r; }
-        f(s0 + r, c);
-    }
-}
 
 // ---------------------------------------------------------------- apply2 forward
 

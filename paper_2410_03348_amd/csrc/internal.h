@@ -126,6 +126,14 @@ dol_status make_group_masks(const dol_prov *prov, GroupMasks *gm);
 // Device copy of a small host int32 array, cached by content.
 dol_status get_i32_array(int32_t n, const int32_t *data, const int32_t **dptr);
 
+// ---------------------------------------------------------------- argument checks (api.hip)
+
+bool is_dtkp(const dol_prov *prov);
+dol_status check_prov(const dol_prov *prov, int32_t batch);
+// Shape and pointer checks of one Distribution.  need_ids: the call reads sym_ids.
+dol_status check_dist(const dol_dist *d, const char *name, bool dtkp, bool need_ids, bool need_prob);
+dol_status check_work(int64_t batch, int64_t per_sample);
+
 // ---------------------------------------------------------------- launchers (damp.hip / dtkp.hip)
 
 dol_status launch_damp_apply2_fwd(const dol_fn_table *f, int32_t batch, const float *a, int64_t lda, const float *b,

@@ -367,6 +367,22 @@ dol_status dol_fn_table_create_dense(int32_t na, int32_t nb, const int32_t *out_
     return dol::build_table(na, nb, tup, table);
 }
 
+dol_status dol_fn_table_create_if(int32_t na, int32_t nb, const int32_t *out_id, const uint8_t *cond,
+                                  dol_fn_table **table)
+{
+    if (dol_status st = dol::check_table_dims(na, nb, table)) return st;
+    if ((!out_id || !cond) && na > 0 && nb > 0) return dol::fail(DOL_EINVAL, "out_id or cond is NULL");
+    std::vector<dol::Tuple> tup;
+    for (int32_t i = 0; i < na; ++i)
+        for (int32_t j = 0; j < nb; ++j) {
+            const size_t e = static_cast<size_t>(i) * nb + j;
+            if (!cond[e]) continue;
+            if (out_id[e] < 0) return dol::fail(DOL_EINVAL, "out_id[%d,%d] = %d is negative where the condition holds", i, j, out_id[e]);
+            tup.push_back({i, j, out_id[e]});
+        }
+    return dol::build_table(na, nb, tup, table);
+}
+
 dol_status dol_fn_table_create_sparse(int32_t na, int32_t nb, int64_t n, const int32_t *i, const int32_t *j,
                                       const int32_t *out_id, dol_fn_table **table)
 {

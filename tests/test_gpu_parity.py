@@ -817,3 +817,177 @@ def test_large_batches_sampled_rows(gp, cfg, batch):
         ref = OP.grid_reach_fwd_bwd(_rows_of(w, idx, dict(p=0, g=0)))
         assert_close(host(prog.hist)[-1][idx], ref["r"], "reachability, sampled rows")
         assert_close(host(prog.grad_p)[idx], ref["grad_p"], "reachability gradient, sampled rows")
+
+
+# ---------------------------------------------------------------- Apply over K Distributions, unary Apply, ApplyIf
+
+def _rand_table(seed, shape, n_ids, drop_every=0):
+    t = (W.splitmix64(seed, np.arange(int(np.prod(shape)))) % np.uint64(n_ids)).astype(np.int32).reshape(shape)
+    if drop_every:
+        t.reshape(-1)[::drop_every] = -1
+    return t
+
+
+@pytest.mark.parametrize("shape,n_ids,scale,batch", [
+    ((37,), 6, 1.0, 300), ((37,), 6, 9.0, 45),                      # unary, second one clamps
+    ((10, 10), 19, 1.0, 129), ((10, 10, 10), 28, 1.0, 513),         # sums of two and three digits
+    ((9, 5, 7), 40, 3.2, 200), ((4, 3, 5, 4), 23, 1.0, 77), ((3, 2, 3, 2, 3), 11, 2.0, 64),
+    ((2, 3, 2, 2, 3, 2), 9, 1.0, 33), ((300, 4, 3), 500, 1.0, 1000), ((2100,), 2100, 1.0, 3)])
+def test_apply_k_damp_forward_and_backward(dol, shape, n_ids, scale, batch):
+    K = len(shape)
+    if n_ids in (19, 28):      # digit sums
+        table = np.zeros(shape, np.int32)
+        for l in range(K):
+            table = table + np.arange(10).reshape([-1 if m == l else 1 for m in range(K)])
+        table = table.astype(np.int32)
+    else:
+        table = _rand_table(300 + K, shape, n_ids, drop_every=5)
+    ins = [(W.softmax_rows(W.normal(310 + l, batch * n).reshape(batch, n)) * scale).astype(np.float32)
+           for l, n in enumerate(shape)]
+    idx, to = oracle.dense_to_tuples(table)
+    syms, want, pre32, _ = oracle.damp_applyk_fwd(idx, to, ins, want_pre=True)
+    f = dol.FnkTable.create_dense(table)
+    np.testing.assert_array_equal(f.out_syms, syms)
+    lds = [n + (3 if l % 2 else 0) for l, n in enumerate(shape)]       # some operands with padded rows
+    d_in = []
+    for x, n, ld in zip(ins, shape, lds):
+        buf = torch.zeros((batch, ld), device="cuda")
+        buf[:, :n] = dev(x)
+        d_in.append(dol.Dist(np.arange(n), buf[:, :n]))
+    out = dol.Dist.empty(f.out_syms, batch)
+    dol.apply_k(d_in, f, None, out)
+    assert_close(host(out.prob), want, "apply_k forward")
+    if scale > 1.0:
+        assert (pre32 > 1).any() and (pre32 < 1).any()
+    sign = np.float32(1.0) if scale > 1.0 else None
+    g = W.normal(320, batch * syms.size).astype(np.float32).reshape(batch, -1)
+    if sign is not None:
+        g = np.abs(g)
+    wants = oracle.damp_applyk_bwd(idx, to, ins, g)
+    grads = [torch.full((batch, ld), 5.0, device="cuda") for ld in lds]
+    skip = 1 if K >= 3 else None
+    dol.apply_k_backward(d_in, f, out, dev(g), [None if l == skip else gr for l, gr in enumerate(grads)])
+    for l, n in enumerate(shape):
+        got = host(grads[l])
+        if l == skip:
+            assert np.all(got == 5.0)
+            continue
+        assert_close(got[:, :n], wants[l], "apply_k grad of operand %d" % l)
+        assert np.all(got[:, n:] == 5.0)
+
+
+def test_apply_k_two_operands_equal_apply2_bit_for_bit(dol):
+    B = 150
+    table = W.hashed_table(41, 30, 20, 64)
+    a = (W.softmax_rows(W.normal(42, B * 30).reshape(B, 30)) * 2).astype(np.float32)
+    b = (W.softmax_rows(W.normal(43, B * 20).reshape(B, 20)) * 2).astype(np.float32)
+    da, db = dol.Dist(np.arange(30), dev(a)), dol.Dist(np.arange(20), dev(b))
+    f2, fk = dol.FnTable.create_dense(table), dol.FnkTable.create_dense(table)
+    np.testing.assert_array_equal(f2.out_syms, fk.out_syms)
+    o2, ok = dol.Dist.empty(f2.out_syms, B), dol.Dist.empty(fk.out_syms, B)
+    dol.apply2(da, db, f2, None, o2)
+    dol.apply_k([da, db], fk, None, ok)
+    np.testing.assert_array_equal(host(o2.prob), host(ok.prob))
+
+
+def test_apply_if_table(dol):
+    B, na, nb = 90, 12, 9
+    table = W.hashed_table(51, na, nb, 16)
+    cond = ((np.arange(na)[:, None] + np.arange(nb)[None, :]) % 3 != 1)
+    a = W.softmax_rows(W.normal(52, B * na).reshape(B, na))
+    b = W.softmax_rows(W.normal(53, B * nb).reshape(B, nb))
+    tri = oracle.dense_to_triples(np.where(cond, table, -1))
+    syms, want = oracle.damp_apply2_fwd(tri, na, nb, a, b)
+    g = W.normal(54, B * syms.size).astype(np.float32).reshape(B, -1)
+    wa, wb = oracle.damp_apply2_bwd(tri, na, nb, a, b, g)
+    junk = np.where(cond, table, -7).astype(np.int32)               # entries the condition rejects are never read
+    f = dol.FnTable.create_if(junk, cond)
+    np.testing.assert_array_equal(f.out_syms, syms)
+    da, db = dol.Dist(np.arange(na), dev(a)), dol.Dist(np.arange(nb), dev(b))
+    out = dol.Dist.empty(f.out_syms, B)
+    dol.apply2(da, db, f, None, out)
+    assert_close(host(out.prob), want, "apply_if forward")
+    ga, gb = torch.empty((B, na), device="cuda"), torch.empty((B, nb), device="cuda")
+    dol.backward(dol.OpRecord(dol.OP_APPLY2, da, db, out, f=f), dev(g), ga, gb)
+    assert_close(host(ga), wa, "apply_if grad a")
+    assert_close(host(gb), wb, "apply_if grad b")
+    with pytest.raises(dol.DolError):
+        dol.FnTable.create_if(np.full((2, 2), -1, np.int32), np.ones((2, 2), np.uint8))
+
+
+@pytest.mark.parametrize("k", [1, 3, 8])
+def test_apply_k_dtkp(dol, k):
+    """Three operands with multi-proof tags and exclusion groups, then a unary Apply that merges symbols."""
+    B, nv = 60, 4
+    fp = np.concatenate([W.softmax_rows(W.normal(60 + t, B * nv).reshape(B, nv)) for t in range(4)], axis=1)
+    grp = np.repeat(np.arange(4), nv).astype(np.int32)
+    prov = dol.Prov(dol.DTKP, k, dev(fp), grp)
+    o_tags, g_tags = [], []
+    for t in range(4):
+        o_tags.append(oracle.dtkp_init(np.arange(nv) + nv * t, fp, k)[0])
+        d = dol.Dist.empty(np.arange(nv), B, k=k)
+        dol.dtkp_init(d, np.arange(nv) + nv * t, prov)
+        g_tags.append(d)
+    # operand 0: sum of slots 0 and 1 (several proofs per symbol)
+    sum_t = np.add.outer(np.arange(nv), np.arange(nv)).astype(np.int32)
+    s0, m0, p0, _ = oracle.dtkp_apply2(oracle.dense_to_triples(sum_t), nv, nv, k, grp, fp, o_tags[0], o_tags[1])
+    f0 = dol.FnTable.create_dense(sum_t)
+    a = dol.Dist.empty(f0.out_syms, B, k=k)
+    dol.apply2(g_tags[0], g_tags[1], f0, prov, a)
+    table = _rand_table(70, (s0.size, nv, nv), 9, drop_every=6)
+    idx, to = oracle.dense_to_tuples(table)
+    syms, om, op, opr = oracle.dtkp_applyk(idx, to, k, grp, fp, [m0, o_tags[2], o_tags[3]])
+    f = dol.FnkTable.create_dense(table)
+    np.testing.assert_array_equal(f.out_syms, syms)
+    out = dol.Dist.empty(f.out_syms, B, k=k)
+    dol.apply_k([a, g_tags[2], g_tags[3]], f, prov, out)
+    np.testing.assert_array_equal(host(out.proof_mask).view(np.uint64), om)
+    np.testing.assert_array_equal(host(out.proof_prob), op)
+    assert_close(host(out.prob), opr, "dtkp apply_k")
+    # the same call with the operands' stored proof probabilities withheld
+    bare = [dol.Dist(d.sym_ids, d.prob, d.proof_mask, None) for d in (a, g_tags[2], g_tags[3])]
+    out_b = dol.Dist.empty(f.out_syms, B, k=k)
+    dol.apply_k(bare, f, prov, out_b)
+    np.testing.assert_array_equal(host(out_b.proof_mask).view(np.uint64), om)
+    np.testing.assert_array_equal(host(out_b.proof_prob), op)
+    # unary Apply over the result
+    f1 = (np.arange(syms.size) % 3).astype(np.int32)
+    f1[2] = -1
+    idx1, to1 = oracle.dense_to_tuples(f1)
+    s1, m1, p1, pr1 = oracle.dtkp_applyk(idx1, to1, k, grp, fp, [om])
+    fu = dol.FnkTable.create_dense(f1)
+    np.testing.assert_array_equal(fu.out_syms, s1)
+    out1 = dol.Dist.empty(fu.out_syms, B, k=k)
+    dol.apply_k([out], fu, prov, out1)
+    np.testing.assert_array_equal(host(out1.proof_mask).view(np.uint64), m1)
+    np.testing.assert_array_equal(host(out1.proof_prob), p1)
+    assert_close(host(out1.prob), pr1, "dtkp unary apply")
+    if k > 1:
+        assert (m1[:, :, 1] != oracle.ABSENT).any()
+
+
+def test_apply_k_argument_errors_and_empty(dol):
+    with pytest.raises(dol.DolError):
+        dol.FnkTable([3, 3], [[0, 0], [0, 0]], [1, 2])              # one index tuple twice
+    with pytest.raises(dol.DolError):
+        dol.FnkTable([3, 3], [[0, 3]], [1])                         # position outside the operand
+    with pytest.raises(dol.DolError):
+        dol.FnkTable([2] * 7, np.zeros((1, 7), np.int32), [1])      # too many operands
+    f = dol.FnkTable.create_dense(np.arange(6, dtype=np.int32).reshape(2, 3))
+    a, b = dol.Dist(np.arange(2), torch.ones((4, 2), device="cuda")), dol.Dist(np.arange(3), torch.ones((4, 3), device="cuda"))
+    with pytest.raises(dol.DolError) as ei:
+        dol.apply_k([a, b], f, None, dol.Dist.empty(np.arange(5), 4))
+    assert ei.value.status == 2
+    with pytest.raises(dol.DolError):
+        dol.apply_k([b, a], f, None, dol.Dist.empty(f.out_syms, 4))
+    with pytest.raises(dol.DolError):
+        dol.apply_k([a], f, None, dol.Dist.empty(f.out_syms, 4))
+    none = dol.FnkTable.create_dense(np.full((2, 3), -1, np.int32))
+    assert none.n_out == 0
+    o0 = dol.Dist.empty(none.out_syms, 4)
+    dol.apply_k([a, b], none, None, o0)
+    ga = torch.full((4, 2), 3.0, device="cuda")
+    dol.apply_k_backward([a, b], none, o0, torch.empty((4, 0), device="cuda"), [ga, None])
+    assert np.all(host(ga) == 0)
+    e = dol.Dist.empty(f.out_syms, 0)
+    dol.apply_k([dol.Dist(np.arange(2), torch.ones((0, 2), device="cuda")), dol.Dist(np.arange(3), torch.ones((0, 3), device="cuda"))], f, None, e)
