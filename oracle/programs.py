@@ -58,6 +58,33 @@ def sum_chain_fwd_bwd(w, want_bwd=True):
     return res
 
 
+def product_chain_fwd_bwd(w, want_bwd=True):
+    """Product-N (appendix on combinatorial explosions): the fold of Fig. 2 with f(x, y) = x * y over interned
+    product symbols; the workload carries the symbol tables of its stages.  target is a column of the last stage."""
+    p = w["p"]
+    n = p.shape[0]
+    tables, stage_ids = w["tables"], w["stage_ids"]
+    accs, tris = [p[0]], []
+    for t in range(1, n):
+        tri = dense_to_triples(tables[t - 1])
+        s, o = damp_apply2_fwd(tri, tables[t - 1].shape[0], 10, accs[-1], p[t])
+        assert np.array_equal(s, stage_ids[t])
+        tris.append(tri); accs.append(o)
+    res = dict(syms=stage_ids[n - 1], out=accs[-1], accs=accs)
+    if not want_bwd:
+        return res
+    g = nll_grad(accs[-1], w["target"])
+    res["g_out"] = g
+    grads = [None] * n
+    for t in range(n - 1, 0, -1):
+        ga, gb = damp_apply2_bwd(tris[t - 1], tables[t - 1].shape[0], 10, accs[t - 1], p[t], g)
+        grads[t] = gb
+        g = ga
+    grads[0] = g
+    res["grad_p"] = np.stack(grads)
+    return res
+
+
 def hashed_pipeline_fwd_bwd(w):
     """Config 3: apply with a hashed table, filter by a keep-mask over the output
     ids, union with a second Distribution over all ids; then backward."""

@@ -296,3 +296,61 @@ def test_config3_pipeline_shapes_and_mass():
     tot = r["o3"].astype(np.float64).sum(1)
     np.testing.assert_allclose(tot, 1.0 + r["o2"].astype(np.float64).sum(1), rtol=1e-6)
     assert r["ga"].shape == (8, 64) and r["gb"].shape == (8, 64) and r["gp2"].shape == (8, 256)
+
+
+# ---------------------------------------------------------------- Product-N fold
+
+def test_product_chain_zero_probability_closed_form_and_enumeration():
+    """Pr(product = 0) = 1 - prod_t (1 - p_t[0]); every other value by enumeration of all digit tuples."""
+    B, n = 4, 4
+    w = W.product_workload(batch=B, n_digits=n, seed=3)
+    r = P.product_chain_fwd_bwd(w, want_bwd=False)
+    p = w["p"].astype(np.float64)
+    values = w["values"]
+    assert values[0] == 0 and list(r["syms"]) == list(range(len(values)))
+    np.testing.assert_allclose(r["out"][:, 0], 1.0 - np.prod(1.0 - p[:, :, 0], axis=0), rtol=1e-6)
+    want = np.zeros((B, len(values)))
+    col = {v: c for c, v in enumerate(values)}
+    for tup in itertools.product(range(10), repeat=n):
+        v = int(np.prod(tup))
+        pr = np.ones(B)
+        for t, d in enumerate(tup):
+            pr = pr * p[t, :, d]
+        want[:, col[v]] += pr
+    np.testing.assert_allclose(r["out"], want, rtol=1e-6, atol=1e-10)
+    np.testing.assert_allclose(r["out"].sum(1), 1.0, rtol=1e-6)
+
+
+def test_product_stage_symbol_counts():
+    """Distinct products of t digits: 10, 37, 101, 226 (counted here from scratch by enumeration)."""
+    _, stage_ids, tables = W.product_stage_tables(4)
+    for t, ids in enumerate(stage_ids):
+        vals = {int(np.prod(tup)) for tup in itertools.product(range(10), repeat=t + 1)}
+        assert ids.size == len(vals)
+    assert [tb.shape for tb in tables] == [(10, 10), (37, 10), (101, 10)]
+
+
+def test_product_chain_gradient_matches_finite_differences():
+    B, n = 2, 3
+    w = W.product_workload(batch=B, n_digits=n, seed=5)
+    r = P.product_chain_fwd_bwd(w)
+    p = w["p"].astype(np.float64)
+    values = w["values"]
+    tgt = w["target"]
+
+    def loss(pp, s):
+        tot = 0.0
+        for tup in itertools.product(range(10), repeat=n):
+            if int(np.prod(tup)) == values[tgt[s]]:
+                tot += np.prod([pp[t, s, d] for t, d in enumerate(tup)])
+        return -np.log(tot)
+
+    h = 1e-6
+    for s in range(B):
+        for t in range(n):
+            for d in (0, 3, 7):
+                hi, lo = p.copy(), p.copy()
+                hi[t, s, d] += h
+                lo[t, s, d] -= h
+                fd = (loss(hi, s) - loss(lo, s)) / (2 * h)
+                assert abs(fd - r["grad_p"][t, s, d]) <= 2e-4 * max(1.0, abs(fd))

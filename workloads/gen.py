@@ -144,6 +144,37 @@ def closure_workload(batch: int = 64, n_nodes: int = 10, n_edges: int = 16, scal
                     dict(p=p, g=g, edge_ids=ids, edge_u=u, edge_v=v))
 
 
+def product_stage_tables(n_digits: int):
+    """Symbol side of the fold apply(D_res, D_i, lambda x, y: x * y) over digit Distributions (the Product-N
+    program of the appendix on combinatorial explosions).  The symbols of stage t are the distinct products of
+    t + 1 digits; they are interned as their rank in the last stage's sorted value list (every earlier stage's
+    values occur there, since multiplying by 1 keeps a value), because the values outgrow 32 bits.
+    Returns (values, stage_ids, tables): the last stage's values (Python ints), per stage the ascending id list
+    int32 [m_t], and per apply the dense table int32 [m_t, 10] of produced ids."""
+    stages = [list(range(10))]
+    for _ in range(1, n_digits):
+        stages.append(sorted({v * d for v in stages[-1] for d in range(10)}))
+    values = stages[-1]
+    rank = {v: r for r, v in enumerate(values)}
+    stage_ids = [np.asarray([rank[v] for v in st], np.int32) for st in stages]
+    tables = [np.asarray([[rank[v * d] for d in range(10)] for v in stages[t]], np.int32) for t in range(n_digits - 1)]
+    return values, stage_ids, tables
+
+
+def product_workload(batch: int = 256, n_digits: int = 16, seed: int = 0) -> "Workload":
+    """Product-N chain: n_digits digit Distributions (softmax of N(0, variance 2) logits) and a target column of
+    the last stage per sample."""
+    p = np.stack([
+        softmax_rows(normal(_sd(seed, 7, t), batch * 10, sigma=np.sqrt(2.0)).reshape(batch, 10))
+        for t in range(n_digits)])
+    values, stage_ids, tables = product_stage_tables(n_digits)
+    tgt = (splitmix64(_sd(seed, 7, 100), np.arange(batch, dtype=np.uint64)) % np.uint64(len(values))).astype(np.int32)
+    w = Workload("product%d_damp_chain_fwd_bwd" % n_digits, dict(batch=batch, n_digits=n_digits, values=values,
+                                                                 stage_ids=stage_ids, tables=tables),
+                 dict(p=p, target=tgt))
+    return w
+
+
 @dataclass
 class Workload:
     """A named bundle of input arrays plus the scalar parameters of a config."""
