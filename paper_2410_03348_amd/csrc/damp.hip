@@ -33,9 +33,42 @@ damp_apply2_fwd_kernel(Rows R, const uint32_t *__restrict__ col_ptr, const uint3
                        float *__restrict__ out, int64_t ldo)
 {
     for_each_element(R, [&](int64_t s, int c) {
-        const float pre = column_sum(a + s * lda, b + s * ldb, col_ij, col_ptr[c], col_ptr[c + 1]);
-        out[s * ldo + c] = fminf(pre, 1.0f);
+        const uint32_t q0 = col_ptr[c], q1 = col_ptr[c + 1];
+        if (q1 - q0 > static_cast<uint32_t>(kLongTableCol)) return;        // left to the wavefront-per-column kernel
+        out[s * ldo + c] = fminf(column_sum(a + s * lda, b + s * ldb, col_ij, q0, q1), 1.0f);
     });
+}
+
+// One wavefront per (sample, long column).  The lanes stride over the column's tuples and their partial sums meet
+// by shuffles; this is not the order the clamp decision is defined in, so alongside the sum the lanes add up the
+// terms' magnitudes, which bounds how far the two orders can lie apart (n roundings of relative size 2^-24 each
+// way).  Only a sum within that distance of 1 is taken again in the defining order, by every lane alike.
+__global__ void __launch_bounds__(kWave)
+damp_apply2_fwd_long_kernel(int32_t n_long, const uint32_t *__restrict__ long_cols,
+                            const uint32_t *__restrict__ col_ptr, const uint32_t *__restrict__ col_ij,
+                            const float *__restrict__ a, int64_t lda, const float *__restrict__ b, int64_t ldb,
+                            float *__restrict__ out, int64_t ldo)
+{
+    const int64_t s = blockIdx.x / n_long;
+    const uint32_t c = long_cols[blockIdx.x - s * n_long];
+    const float *ar = a + s * lda, *br = b + s * ldb;
+    const uint32_t q0 = col_ptr[c], q1 = col_ptr[c + 1];
+    float acc = 0.0f, mag = 0.0f;
+    for (uint32_t q = q0 + threadIdx.x; q < q1; q += kWave) {
+        const uint32_t ij = col_ij[q];
+        const float x = ar[ij & 0xffffu], y = br[ij >> 16];
+        acc = __builtin_fmaf(x, y, acc);
+        mag = __builtin_fmaf(fabsf(x), fabsf(y), mag);
+    }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+        acc += __shfl_xor(acc, d, kWave);
+        mag += __shfl_xor(mag, d, kWave);
+    }
+    const float slack = mag * (static_cast<float>(q1 - q0 + kWave) * 1.1920929e-7f);
+    float pre = acc;
+    if (fabsf(acc - 1.0f) <= slack) pre = column_sum(ar, br, col_ij, q0, q1);
+    if (threadIdx.x == 0) out[s * ldo + c] = fminf(pre, 1.0f);
 }
 
 dol_status launch_damp_apply2_fwd(const dol_fn_table *f, int32_t batch, const float *a, int64_t lda, const float *b,
@@ -50,6 +83,15 @@ dol_status launch_damp_apply2_fwd(const dol_fn_table *f, int32_t batch, const fl
     hipLaunchKernelGGL(damp_apply2_fwd_kernel, dim3(R.grid), dim3(kThreads), 0, st, R, f->col_ptr.ptr, f->col_ij.ptr, a,
                        lda, b, ldb, out, ldo);
     DOL_HIP(hipGetLastError());
+    const int64_t n_long = static_cast<int64_t>(f->long_cols.n);
+    if (n_long > 0) {
+        if (batch * n_long > 0x7fffffffLL)
+            return fail(DOL_EUNSUPPORTED, "batch x long table columns = %lld exceeds 2^31", static_cast<long long>(batch * n_long));
+        hipLaunchKernelGGL(damp_apply2_fwd_long_kernel, dim3(static_cast<unsigned>(batch * n_long)), dim3(kWave), 0, st,
+                           static_cast<int32_t>(n_long), f->long_cols.ptr, f->col_ptr.ptr, f->col_ij.ptr, a, lda, b, ldb,
+                           out, ldo);
+        DOL_HIP(hipGetLastError());
+    }
     return DOL_OK;
 }
 

@@ -58,6 +58,7 @@ struct DevArray {
 // ---------------------------------------------------------------- symbol-side plans
 
 constexpr int kLongTableRow = 64;   // backward: table rows with more tuples are reduced by a whole wavefront
+constexpr int kLongTableCol = 256;  // forward: output columns with more tuples are summed by a whole wavefront
 
 // A tuple of the function table packed for the kernels: low 16 bits = first index, high 16 = second.
 __host__ __device__ static inline uint32_t pack16(uint32_t lo, uint32_t hi) { return lo | (hi << 16); }
@@ -85,6 +86,8 @@ struct dol_fn_table {
     dol::DevArray<uint32_t> rowb_ptr, rowb_ic;
     // rows with more than dol::kLongTableRow tuples (x < na: row x of a, else row x - na of b)
     dol::DevArray<uint32_t> long_rows;
+    // output columns with more than dol::kLongTableCol tuples
+    dol::DevArray<uint32_t> long_cols;
     // LDS gather kernels (damp_lds.hip): per output column (forward), row of a, row of b (backward) a list of
     // 16-byte packets of four tuples; *_ptr[x] .. *_ptr[x+1] are the packets of x
     bool lds_fwd_ok = false, lds_bwd_ok = false;

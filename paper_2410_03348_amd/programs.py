@@ -101,24 +101,29 @@ class SumChain(Program):
     """Config 2 (Fig. 2): left fold of DAMP apply over N digit Distributions, then the reverse sweep of
     vector-Jacobian products from the harness-supplied gradient of -log p[target]."""
 
+    @staticmethod
+    def stage_table(w, t, acc_syms, sym):
+        """Symbol side of stage t: the user function over the accumulator's and the digit's symbols."""
+        return sum_table_of(acc_syms, sym)
+
     def __init__(self, w, device="cuda"):
         p = w["p"]
         self.n, self.batch = p.shape[0], p.shape[1]
-        sym = np.asarray(w["sym"], np.int32)
+        sym = np.arange(10, dtype=np.int32) if "sym" not in w.arrays else np.asarray(w["sym"], np.int32)
         self.p_dev = _dev(p, device)                         # [n, B, 10]
         self.digits = [dol.Dist(sym, self.p_dev[t]) for t in range(self.n)]
         self.tables: List[dol.FnTable] = []
         self.accs: List[dol.Dist] = [self.digits[0]]
         n_tup = []
         for t in range(1, self.n):
-            tab = sum_table_of(self.accs[-1].sym_ids, sym)
+            tab = self.stage_table(w, t, self.accs[-1].sym_ids, sym)
             tb = dol.FnTable.create_dense(tab)
             n_tup.append(_n_tuples(tab))
             self.tables.append(tb)
             self.accs.append(dol.Dist.empty(tb.out_syms, self.batch, device))
         self.records = [dol.OpRecord(dol.OP_APPLY2, self.accs[t - 1], self.digits[t], self.accs[t], f=self.tables[t - 1])
                         for t in range(1, self.n)]
-        self.target = _dev(w["target"].astype(np.int32), device)     # column index = the sum itself
+        self.target = _dev(w["target"].astype(np.int32), device)     # column of the last stage (for sums: the sum itself)
         self.grad_p = torch.empty_like(self.p_dev)           # [n, B, 10]
         self.g_acc = [torch.empty((self.batch, d.n_sym), dtype=torch.float32, device=device) for d in self.accs]
         self.launches = [_apply_fwd(self.accs[t - 1], self.digits[t], self.tables[t - 1], self.accs[t], n_tup[t - 1])
@@ -131,6 +136,16 @@ class SumChain(Program):
             ga = self.g_acc[t - 1] if t > 1 else self.grad_p[0]
             self.launches.append(_apply_bwd(self.records[t - 1], self.g_acc[t], ga, self.grad_p[t], n_tup[t - 1]))
         self.sample_ops = 2 * (self.n - 1) * self.batch
+
+
+class ProductChain(SumChain):
+    """Product-N (appendix on combinatorial explosions): the same fold with f(x, y) = x * y; the product values
+    outgrow 32 bits, so the workload interns them and carries the id table of every stage."""
+
+    @staticmethod
+    def stage_table(w, t, acc_syms, sym):
+        assert np.array_equal(acc_syms, w["stage_ids"][t - 1])
+        return w["tables"][t - 1]
 
 
 class SumChainFused(Program):

@@ -991,3 +991,45 @@ def test_apply_k_argument_errors_and_empty(dol):
     assert np.all(host(ga) == 0)
     e = dol.Dist.empty(f.out_syms, 0)
     dol.apply_k([dol.Dist(np.arange(2), torch.ones((0, 2), device="cuda")), dol.Dist(np.arange(3), torch.ones((0, 3), device="cuda"))], f, None, e)
+
+
+# ---------------------------------------------------------------- Product-N fold (irregular growing symbol sets)
+
+@pytest.mark.parametrize("batch,n", [(64, 4), (256, 8), (33, 11)])
+def test_product_chain(gp, batch, n):
+    """The fold of Fig. 2 with f = x * y: tables without structure, a zero column that every row feeds (summed by a
+    wavefront once it is long), operand rows longer than a thread's share in the backward pass."""
+    w = W.product_workload(batch=batch, n_digits=n, seed=n)
+    ref = OP.product_chain_fwd_bwd(w)
+    prog = gp.ProductChain(w)
+    prog.step()
+    np.testing.assert_array_equal(prog.accs[-1].sym_ids, ref["syms"])
+    for t in range(1, n):
+        assert_close(host(prog.accs[t].prob), ref["accs"][t], "product stage %d" % t)
+    assert_close(host(prog.g_acc[-1]), ref["g_out"], "loss gradient")
+    assert_close(host(prog.grad_p), ref["grad_p"], "product chain grad")
+
+
+def test_long_column_near_the_clamp_takes_the_defining_order(dol):
+    """A column of 3000 tuples whose sum lies within rounding of 1: the clamp decision (seen through backward) must be
+    the one of the sequential float sum, on either side of 1."""
+    B, na = 48, 3000
+    table = np.zeros((na, 1), np.int32)                      # every symbol maps to 0: one long column
+    a = W.uniform01(81, B * na).astype(np.float32).reshape(B, na)
+    a = (a / a.sum(1, keepdims=True, dtype=np.float64)).astype(np.float32)       # rows sum to 1 up to rounding
+    a[::3] *= np.float32(1.0 + 2e-7)
+    b = np.ones((B, 1), np.float32)
+    tri = oracle.dense_to_triples(table)
+    syms, want, pre32, pre64 = oracle.damp_apply2_fwd(tri, na, 1, a, b, want_pre=True)
+    assert (pre32 > 1).any() and (pre32 <= 1).any() and np.abs(pre64 - 1).max() < 1e-5
+    g = np.ones((B, 1), np.float32)
+    wa, wb = oracle.damp_apply2_bwd(tri, na, 1, a, b, g)
+    f = dol.FnTable.create_dense(table)
+    da, db = dol.Dist(np.arange(na), dev(a)), dol.Dist(np.arange(1), dev(b))
+    out = dol.Dist.empty(f.out_syms, B)
+    dol.apply2(da, db, f, None, out)
+    assert_close(host(out.prob), want, "long column forward")
+    ga, gb = torch.empty((B, na), device="cuda"), torch.empty((B, 1), device="cuda")
+    dol.backward(dol.OpRecord(dol.OP_APPLY2, da, db, out, f=f), dev(g), ga, gb)
+    np.testing.assert_array_equal(host(ga), wa)              # 0 or 1 per sample: the decision itself
+    assert_close(host(gb), wb, "long column grad b")
