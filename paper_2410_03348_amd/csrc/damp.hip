@@ -16,13 +16,27 @@ namespace dol {
 
 // pre[c] = sum over the tuples of column c, ascending (i, j), one fma each.  This order is part of the
 // operator's contract: the backward pass re-derives the clamp decision [pre <= 1] from it.
+// The loads of kGather tuples are issued together (index words first, then the tags they name) so that a column
+// costs a few memory round trips rather than two per tuple; the adds keep their order.
+constexpr int kGather = 4;
+
 __device__ __forceinline__ float column_sum(const float *__restrict__ ar, const float *__restrict__ br,
                                             const uint32_t *__restrict__ col_ij, uint32_t q0, uint32_t q1)
 {
     float acc = 0.0f;
-    for (uint32_t q = q0; q < q1; ++q) {
-        const uint32_t ij = col_ij[q];
-        acc = __builtin_fmaf(ar[ij & 0xffffu], br[ij >> 16], acc);
+    for (uint32_t q = q0; q < q1; q += kGather) {
+        uint32_t ij[kGather];
+        float x[kGather], y[kGather];
+#pragma unroll
+        for (int u = 0; u < kGather; ++u) ij[u] = col_ij[min(q + u, q1 - 1)];
+#pragma unroll
+        for (int u = 0; u < kGather; ++u) {
+            x[u] = ar[ij[u] & 0xffffu];
+            y[u] = br[ij[u] >> 16];
+        }
+#pragma unroll
+        for (int u = 0; u < kGather; ++u)
+            if (q + u < q1) acc = __builtin_fmaf(x[u], y[u], acc);
     }
     return acc;
 }
@@ -54,11 +68,22 @@ damp_apply2_fwd_long_kernel(int32_t n_long, const uint32_t *__restrict__ long_co
     const float *ar = a + s * lda, *br = b + s * ldb;
     const uint32_t q0 = col_ptr[c], q1 = col_ptr[c + 1];
     float acc = 0.0f, mag = 0.0f;
-    for (uint32_t q = q0 + threadIdx.x; q < q1; q += kWave) {
-        const uint32_t ij = col_ij[q];
-        const float x = ar[ij & 0xffffu], y = br[ij >> 16];
-        acc = __builtin_fmaf(x, y, acc);
-        mag = __builtin_fmaf(fabsf(x), fabsf(y), mag);
+    for (uint32_t q = q0 + threadIdx.x; q < q1; q += kGather * kWave) {
+        uint32_t ij[kGather];
+        float x[kGather], y[kGather];
+#pragma unroll
+        for (int u = 0; u < kGather; ++u) ij[u] = col_ij[min(q + u * kWave, q1 - 1)];
+#pragma unroll
+        for (int u = 0; u < kGather; ++u) {
+            x[u] = ar[ij[u] & 0xffffu];
+            y[u] = br[ij[u] >> 16];
+        }
+#pragma unroll
+        for (int u = 0; u < kGather; ++u)
+            if (q + u * kWave < q1) {
+                acc = __builtin_fmaf(x[u], y[u], acc);
+                mag = __builtin_fmaf(fabsf(x[u]), fabsf(y[u]), mag);
+            }
     }
 #pragma unroll
     for (int d = 32; d >= 1; d >>= 1) {
@@ -99,17 +124,42 @@ dol_status launch_damp_apply2_fwd(const dol_fn_table *f, int32_t batch, const fl
 
 // Gradient reaching the unclamped sum of column c.  out < 1 means the clamp did not act (pre = out);
 // out == 1 leaves pre == 1 (passes) and pre > 1 (blocks) apart only by recomputing pre.
-__device__ __forceinline__ float gated_grad(const float *__restrict__ gr, const float *__restrict__ outr,
-                                            const float *__restrict__ ar, const float *__restrict__ br,
-                                            const uint32_t *__restrict__ col_ptr,
+__device__ __forceinline__ float gated_grad(float g, float out_c, const float *__restrict__ ar,
+                                            const float *__restrict__ br, const uint32_t *__restrict__ col_ptr,
                                             const uint32_t *__restrict__ col_ij, uint32_t c)
 {
-    float g = gr[c];
-    if (outr[c] >= 1.0f) {
+    if (out_c >= 1.0f) {
         const float pre = column_sum(ar, br, col_ij, col_ptr[c], col_ptr[c + 1]);
         if (!(pre <= 1.0f)) g = 0.0f;
     }
     return g;
+}
+
+// acc += sum over entries q0 + k * stride < q1 of gated gradient of the entry's column times the other operand's
+// tag, in entry order; the loads of kGather entries are issued together.
+__device__ __forceinline__ float row_sum(float acc, const uint32_t *__restrict__ ent, uint32_t q0, uint32_t q1,
+                                         uint32_t stride, const float *__restrict__ gr, const float *__restrict__ outr,
+                                         const float *__restrict__ other, const float *__restrict__ ar,
+                                         const float *__restrict__ br, const uint32_t *__restrict__ col_ptr,
+                                         const uint32_t *__restrict__ col_ij)
+{
+    for (uint32_t q = q0; q < q1; q += kGather * stride) {
+        uint32_t e[kGather];
+        float gv[kGather], ov[kGather], xv[kGather];
+#pragma unroll
+        for (int u = 0; u < kGather; ++u) e[u] = ent[min(q + u * stride, q1 - 1)];
+#pragma unroll
+        for (int u = 0; u < kGather; ++u) {
+            gv[u] = gr[e[u] >> 16];
+            ov[u] = outr[e[u] >> 16];
+            xv[u] = other[e[u] & 0xffffu];
+        }
+#pragma unroll
+        for (int u = 0; u < kGather; ++u)
+            if (q + u * stride < q1)
+                acc = __builtin_fmaf(gated_grad(gv[u], ov[u], ar, br, col_ptr, col_ij, e[u] >> 16), xv[u], acc);
+    }
+    return acc;
 }
 
 struct BwdTable {
@@ -134,11 +184,7 @@ damp_apply2_bwd_kernel(Rows R, BwdTable T, const float *__restrict__ a, int64_t 
         const float *other = is_a ? br : ar;
         const uint32_t q0 = ptr[r], q1 = ptr[r + 1];
         if (q1 - q0 > kLongTableRow) return;
-        float acc = 0.0f;
-        for (uint32_t q = q0; q < q1; ++q) {
-            const uint32_t e = ent[q];
-            acc = __builtin_fmaf(gated_grad(gr, outr, ar, br, T.col_ptr, T.col_ij, e >> 16), other[e & 0xffffu], acc);
-        }
+        const float acc = row_sum(0.0f, ent, q0, q1, 1, gr, outr, other, ar, br, T.col_ptr, T.col_ij);
         float *dst = is_a ? ga + s * lda + r : gb + s * ldb + r;
         const bool add = is_a ? (accumulate & 1) : (accumulate & 2);
         *dst = add ? *dst + acc : acc;
@@ -161,11 +207,7 @@ damp_apply2_bwd_long_kernel(int32_t n_long, const uint32_t *__restrict__ long_ro
     const uint32_t *ptr = is_a ? T.rowa_ptr : T.rowb_ptr;
     const uint32_t *ent = is_a ? T.rowa_jc : T.rowb_ic;
     const float *other = is_a ? br : ar;
-    float acc = 0.0f;
-    for (uint32_t q = ptr[r] + threadIdx.x, q1 = ptr[r + 1]; q < q1; q += kWave) {
-        const uint32_t e = ent[q];
-        acc = __builtin_fmaf(gated_grad(gr, outr, ar, br, T.col_ptr, T.col_ij, e >> 16), other[e & 0xffffu], acc);
-    }
+    float acc = row_sum(0.0f, ent, ptr[r] + threadIdx.x, ptr[r + 1], kWave, gr, outr, other, ar, br, T.col_ptr, T.col_ij);
 #pragma unroll
     for (int d = 32; d >= 1; d >>= 1) acc += __shfl_xor(acc, d, kWave);
     if (threadIdx.x == 0) {

@@ -416,4 +416,5 @@ class TransitiveClosure(Program):
 
 
 def make_program(config_id: int, workload, device="cuda") -> Program:
-    return {1: Sum2Forward, 2: SumChain, 3: HashedPipeline, 4: DtkpSumChain, 5: GridReach}[config_id](workload, device)
+    return {1: Sum2Forward, 2: SumChain, 3: HashedPipeline, 4: DtkpSumChain, 5: GridReach,
+            6: ProductChain}[config_id](workload, device)
