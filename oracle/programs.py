@@ -9,7 +9,8 @@ from __future__ import annotations
 import numpy as np
 
 from . import (dense_to_triples, damp_apply2_fwd, damp_apply2_bwd, filter_plan, damp_filter_fwd, damp_filter_bwd,
-               union_plan, damp_union_fwd, damp_union_bwd, reach_fwd, reach_bwd, dtkp_init, dtkp_apply2)
+               union_plan, damp_union_fwd, damp_union_bwd, reach_fwd, reach_bwd, dtkp_init, dtkp_apply2,
+               dense_to_tuples, damp_applyk_fwd, damp_applyk_bwd, dtkp_applyk, dtkp_prob_bwd)
 
 
 def _sum_tri(sa, sb):
@@ -157,3 +158,52 @@ def grid_reach_fwd_bwd(w):
     hist = reach_fwd(n, w["edge_u"], w["edge_v"], w["src"], w["rounds"], w["p"])
     gp = reach_bwd(n, w["edge_u"], w["edge_v"], w["rounds"], w["p"], hist, w["g"])
     return dict(r=hist[-1], hist=hist, grad_p=gp)
+
+
+def hwf_pipeline_damp(w):
+    """Formula pipeline (appendix on the HWF model) under DAMP: Filter every position to its admissible classes,
+    fold Apply over the positions with the formula-building function, evaluate with a unary Apply; then the
+    reverse sweep from the upstream gradient over the formula values back to the 14 class probabilities."""
+    p, L = w["p"], w["length"]
+    xs = [damp_filter_fwd(w["keep"][pos], np.ascontiguousarray(p[:, pos, :])) for pos in range(L)]
+    accs, tris = [xs[0]], []
+    for pos in range(1, L):
+        tab = w["tables"][pos - 1]
+        tri = dense_to_triples(tab)
+        _, o = damp_apply2_fwd(tri, tab.shape[0], tab.shape[1], accs[-1], xs[pos])
+        tris.append(tri); accs.append(o)
+    idx, to = dense_to_tuples(w["final_map"])
+    syms, out = damp_applyk_fwd(idx, to, [accs[-1]])
+    (g,) = damp_applyk_bwd(idx, to, [accs[-1]], w["g"])
+    grad_p = np.zeros_like(p)
+    for pos in range(L - 1, 0, -1):
+        tab = w["tables"][pos - 1]
+        g, gx = damp_apply2_bwd(tris[pos - 1], tab.shape[0], tab.shape[1], accs[pos - 1], xs[pos], g)
+        grad_p[:, pos, :] = damp_filter_bwd(w["keep"][pos], gx)
+    grad_p[:, 0, :] = damp_filter_bwd(w["keep"][0], g)
+    return dict(syms=syms, out=out, accs=accs, grad_p=grad_p)
+
+
+def hwf_pipeline_dtkp(w):
+    """The same pipeline under DTKP-AM: the kept classes of all positions are the input facts (one exclusion group
+    per position); tags are initialised after the Filter, so only admissible classes take fact numbers."""
+    p, L, k = w["p"], w["length"], w["k"]
+    xs = [damp_filter_fwd(w["keep"][pos], np.ascontiguousarray(p[:, pos, :])) for pos in range(L)]
+    fp = np.ascontiguousarray(np.concatenate(xs, axis=1))
+    off = np.concatenate([[0], np.cumsum([x.shape[1] for x in xs])]).astype(np.int32)
+    grp = np.concatenate([np.full(x.shape[1], pos, np.int32) for pos, x in enumerate(xs)])
+    m, _, _ = dtkp_init(np.arange(off[0], off[1]), fp, k)
+    stages = []
+    for pos in range(1, L):
+        tab = w["tables"][pos - 1]
+        dm, _, _ = dtkp_init(np.arange(off[pos], off[pos + 1]), fp, k)
+        _, m, pp, pr = dtkp_apply2(dense_to_triples(tab), tab.shape[0], tab.shape[1], k, grp, fp, m, dm)
+        stages.append((m, pp, pr))
+    idx, to = dense_to_tuples(w["final_map"])
+    syms, om, op, opr = dtkp_applyk(idx, to, k, grp, fp, [m])
+    gfact = dtkp_prob_bwd(om, fp, w["g"])
+    grad_p = np.zeros_like(p)
+    for pos in range(L):
+        grad_p[:, pos, :] = damp_filter_bwd(w["keep"][pos], np.ascontiguousarray(gfact[:, off[pos]:off[pos + 1]]))
+    return dict(syms=syms, mask=om, pprob=op, prob=opr, stages=stages, fact_prob=fp, fact_group=grp, fact_offset=off,
+                gfact=gfact, grad_p=grad_p)

@@ -10,5 +10,5 @@ from .gen import (  # noqa: F401
     splitmix64, uniform01, normal, softmax_rows, beta22, hashed_table,
     keep_mask, sum_table, grid_edges, grid_reach_triples, Workload,
     config1, config2, config3, config4, config5, make_config, CONFIG_NAMES,
-    random_digraph, join_triples, closure_workload, product_stage_tables, product_workload,
+    random_digraph, join_triples, closure_workload, product_stage_tables, product_workload, hwf_symbol_tables, hwf_workload, HWF_OPS,
 )

@@ -12,6 +12,8 @@ from __future__ import annotations
 from dataclasses import dataclass, field
 from typing import Dict, Any
 
+from fractions import Fraction
+
 import numpy as np
 
 _GOLDEN = np.uint64(0x9E3779B97F4A7C15)
@@ -173,6 +175,87 @@ def product_workload(batch: int = 256, n_digits: int = 16, seed: int = 0) -> "Wo
                                                                  stage_ids=stage_ids, tables=tables),
                  dict(p=p, target=tgt))
     return w
+
+
+# ---- a formula-evaluation pipeline in the shape of the hand-written-formula task (App. on the HWF model): symbols of
+# 14 classes per position (digits 0-9 and + - * /), digits kept at even positions and operators at odd ones, the
+# formula built by one Apply per position over host-interned formula states, one unary Apply evaluating it.
+
+HWF_OPS = "+-*/"
+_HWF_NAN = ("nan",)
+
+
+def _hwf_add_digit(state, d):
+    """User function of the digit positions.  A state is () | (T,) | (A, s, T) | one of these plus a trailing
+    operator, T the term in progress, A the folded prefix, s in '+-'; products and quotients are folded as they
+    complete, sums and differences as soon as the next operator shows that precedence allows it."""
+    if state == _HWF_NAN:
+        return _HWF_NAN
+    if state == ():
+        return (Fraction(d),)
+    op = state[-1]
+    if op in "+-":
+        return state + (Fraction(d),)
+    if op == "/" and d == 0:
+        return _HWF_NAN
+    return state[:-2] + (state[-2] * d if op == "*" else state[-2] / d,)
+
+
+def _hwf_add_op(state, op):
+    if state == _HWF_NAN:
+        return _HWF_NAN
+    if op in "+-" and len(state) == 3:
+        a, s, t = state
+        state = (a + t if s == "+" else a - t,)
+    return state + (op,)
+
+
+def _hwf_value(state):
+    if state == _HWF_NAN:
+        return None
+    if len(state) == 3:
+        a, s, t = state
+        return a + t if s == "+" else a - t
+    return state[0]
+
+
+def hwf_symbol_tables(length: int):
+    """Symbol side of the pipeline for formulas of `length` positions (odd).  Returns
+    (states, tables, values, final_map): per position the list of formula states (interned id = index, sorted by
+    their printed form), per position >= 1 the dense int32 table [states before, kept symbols of the position] of
+    next-state ids, the sorted list of distinct formula values (None = division by zero, last), and int32
+    [last states] mapping a state to its value's index."""
+    assert length % 2 == 1
+
+    def key(st):
+        return " ".join(str(x) for x in st)
+
+    states = [sorted({_hwf_add_digit((), d) for d in range(10)}, key=key)]
+    tables = []
+    for pos in range(1, length):
+        step, alphabet = (_hwf_add_digit, range(10)) if pos % 2 == 0 else (_hwf_add_op, HWF_OPS)
+        nxt = [[step(st, x) for x in alphabet] for st in states[-1]]
+        new_states = sorted({v for row in nxt for v in row}, key=key)
+        idx = {st: i for i, st in enumerate(new_states)}
+        tables.append(np.asarray([[idx[v] for v in row] for row in nxt], np.int32))
+        states.append(new_states)
+    vals = {_hwf_value(st) for st in states[-1]}
+    values = sorted(v for v in vals if v is not None) + ([None] if None in vals else [])
+    vidx = {v: i for i, v in enumerate(values)}
+    final_map = np.asarray([vidx[_hwf_value(st)] for st in states[-1]], np.int32)
+    return states, tables, values, final_map
+
+
+def hwf_workload(batch: int = 64, length: int = 7, k: int = 3, seed: int = 0) -> "Workload":
+    """Per position a softmax of N(0,1) logits over the 14 classes, and an N(0,1) upstream gradient over the
+    distinct formula values."""
+    p = softmax_rows(normal(_sd(seed, 8, 0), batch * length * 14).reshape(batch * length, 14)).reshape(batch, length, 14)
+    states, tables, values, final_map = hwf_symbol_tables(length)
+    g = normal(_sd(seed, 8, 1), batch * len(values)).astype(np.float32).reshape(batch, len(values))
+    keep = [(np.arange(14) < 10 if pos % 2 == 0 else np.arange(14) >= 10).astype(np.uint8) for pos in range(length)]
+    return Workload("hwf%d_filter_concat_eval" % length,
+                    dict(batch=batch, length=length, k=k, states=states, tables=tables, values=values, keep=keep),
+                    dict(p=p, g=g, final_map=final_map))
 
 
 @dataclass
