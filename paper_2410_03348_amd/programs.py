@@ -415,6 +415,90 @@ class TransitiveClosure(Program):
         self.sample_ops = 4 * len(self.rounds) * B
 
 
+class HwfPipeline(Program):
+    """Formula pipeline (appendix on the HWF model): Filter every position's 14 classes to the admissible ones
+    (digits at even positions, operators at odd ones), fold Apply over the positions with the formula-building
+    function over host-interned formula states, evaluate with a unary Apply.  provenance "damp": reverse sweep of
+    vector-Jacobian products down to the class probabilities; "dtkp": the kept classes are the input facts (tags
+    initialised after the Filter), one dol_dtkp_backward on the result, then the Filters' transposes."""
+
+    def __init__(self, w, provenance="damp", device="cuda"):
+        p = w["p"]
+        B, L = p.shape[0], p.shape[1]
+        self.batch, self.L, self.provenance = B, L, provenance
+        dtkp = provenance == "dtkp"
+        k = w["k"] if dtkp else 0
+        self.p_dev = _dev(p, device)                                   # [B, L, 14]
+        self.grad_p = torch.empty_like(self.p_dev)
+        self.g = _dev(w["g"], device)
+        self.pos = [dol.Dist(np.arange(14), self.p_dev[:, t, :]) for t in range(L)]
+        self.keep = [np.ascontiguousarray(m, np.uint8) for m in w["keep"]]
+        kept = [dol.filter_plan(self.pos[t], self.keep[t]) for t in range(L)]
+        off = np.concatenate([[0], np.cumsum([len(x) for x in kept])]).astype(np.int64)
+        self.launches = []
+        if dtkp:
+            self.fact_prob = torch.empty((B, int(off[-1])), dtype=torch.float32, device=device)
+            self.gfact = torch.empty_like(self.fact_prob)
+            grp = np.concatenate([np.full(len(x), t, np.int32) for t, x in enumerate(kept)])
+            self.prov = dol.Prov(dol.DTKP, k, self.fact_prob, grp)
+            self.xs = [dol.Dist(kept[t], self.fact_prob[:, off[t]:off[t + 1]]) for t in range(L)]
+            self.tags = [dol.Dist.empty(kept[t], B, device, k=k) for t in range(L)]
+        else:
+            self.prov = None
+            self.xs = [dol.Dist.empty(kept[t], B, device) for t in range(L)]
+            self.tags = self.xs
+        self.filters = [dol.OpRecord(dol.OP_FILTER, self.pos[t], None, self.xs[t], pred_mask=self.keep[t]) for t in range(L)]
+        for t in range(L):
+            self.launches.append(Launch("damp_gather_cols_kernel", lambda t=t: dol.filter(self.pos[t], self.keep[t], None, self.xs[t]),
+                                        4 * B * (14 + self.xs[t].n_sym), 0, "fwd"))
+        if dtkp:
+            for t in range(L):
+                facts = np.arange(off[t], off[t + 1], dtype=np.int32)
+                self.launches.append(Launch("dtkp_init_kernel", lambda t=t, f=facts: dol.dtkp_init(self.tags[t], f, self.prov),
+                                            B * self.tags[t].n_sym * (4 + 12 * k + 4), 0, "fwd"))
+        self.tables, self.accs, n_tup = [], [self.tags[0]], []
+        for t in range(1, L):
+            tb = dol.FnTable.create_dense(w["tables"][t - 1])
+            self.tables.append(tb)
+            n_tup.append(_n_tuples(w["tables"][t - 1]))
+            out = dol.Dist.empty(tb.out_syms, B, device, k=k)
+            self.launches.append(_apply_fwd(self.accs[-1], self.tags[t], tb, out, n_tup[-1], self.prov, k))
+            self.accs.append(out)
+        self.final = dol.FnkTable.create_dense(w["final_map"])
+        self.out = dol.Dist.empty(self.final.out_syms, B, device, k=k)
+        last = self.accs[-1]
+        per = 12 * k + 4 if dtkp else 4
+        self.launches.append(Launch("dtkp_applyk_kernel" if dtkp else "damp_applyk_fwd_kernel",
+                                    lambda: dol.apply_k([last], self.final, self.prov, self.out),
+                                    B * per * (last.n_sym + self.out.n_sym), B * last.n_sym * max(k, 1), "fwd"))
+        n_ops = 2 * L + (L if dtkp else 0)
+        if dtkp:
+            self.launches.append(Launch("dtkp_prob_bwd_kernel", lambda: dol.dtkp_backward(self.out, self.prov, self.g, self.gfact),
+                                        B * (self.out.n_sym * (12 * k + 4) + 8 * int(off[-1])), 0, "bwd"))
+            for t in range(L):
+                self.launches.append(Launch("damp_gather_cols_kernel",
+                                            lambda t=t: dol.backward(self.filters[t], self.gfact[:, off[t]:off[t + 1]], self.grad_p[:, t, :], None),
+                                            4 * B * (14 + self.xs[t].n_sym), 0, "bwd"))
+            n_ops += 1 + L
+        else:
+            self.g_acc = [torch.empty((B, d.n_sym), dtype=torch.float32, device=device) for d in self.accs]
+            self.g_x = [torch.empty((B, d.n_sym), dtype=torch.float32, device=device) for d in self.xs]
+            self.g_acc[0] = self.g_x[0]                                # the first accumulator is position 0 itself
+            self.launches.append(Launch("damp_applyk_bwd_kernel",
+                                        lambda: dol.apply_k_backward([last], self.final, self.out, self.g, [self.g_acc[-1]]),
+                                        4 * B * (2 * last.n_sym + 2 * self.out.n_sym), B * last.n_sym, "bwd"))
+            self.records = [dol.OpRecord(dol.OP_APPLY2, self.accs[t - 1], self.xs[t], self.accs[t], f=self.tables[t - 1])
+                            for t in range(1, L)]
+            for t in range(L - 1, 0, -1):
+                self.launches.append(_apply_bwd(self.records[t - 1], self.g_acc[t], self.g_acc[t - 1], self.g_x[t], n_tup[t - 1]))
+            for t in range(L):
+                self.launches.append(Launch("damp_gather_cols_kernel",
+                                            lambda t=t: dol.backward(self.filters[t], self.g_x[t], self.grad_p[:, t, :], None),
+                                            4 * B * (14 + self.xs[t].n_sym), 0, "bwd"))
+            n_ops += 2 * L
+        self.sample_ops = n_ops * B
+
+
 def make_program(config_id: int, workload, device="cuda") -> Program:
     return {1: Sum2Forward, 2: SumChain, 3: HashedPipeline, 4: DtkpSumChain, 5: GridReach,
             6: ProductChain}[config_id](workload, device)

@@ -1033,3 +1033,36 @@ def test_long_column_near_the_clamp_takes_the_defining_order(dol):
     dol.backward(dol.OpRecord(dol.OP_APPLY2, da, db, out, f=f), dev(g), ga, gb)
     np.testing.assert_array_equal(host(ga), wa)              # 0 or 1 per sample: the decision itself
     assert_close(host(gb), wb, "long column grad b")
+
+
+# ---------------------------------------------------------------- formula pipeline (filter -> chained apply -> unary apply)
+
+@pytest.mark.parametrize("batch,length", [(64, 7), (33, 5), (5, 1)])
+def test_formula_pipeline_damp(gp, batch, length):
+    w = W.hwf_workload(batch=batch, length=length, seed=length)
+    ref = OP.hwf_pipeline_damp(w)
+    prog = gp.HwfPipeline(w, "damp")
+    prog.step()
+    np.testing.assert_array_equal(prog.out.sym_ids, ref["syms"])
+    for t in range(1, length):
+        assert_close(host(prog.accs[t].prob), ref["accs"][t], "formula stage %d" % t)
+    assert_close(host(prog.out.prob), ref["out"], "formula values")
+    assert_close(host(prog.grad_p), ref["grad_p"], "formula grad")
+
+
+@pytest.mark.parametrize("batch,length,k", [(64, 7, 3), (20, 5, 1), (9, 3, 8)])
+def test_formula_pipeline_dtkp(gp, batch, length, k):
+    w = W.hwf_workload(batch=batch, length=length, k=k, seed=40 + length)
+    ref = OP.hwf_pipeline_dtkp(w)
+    prog = gp.HwfPipeline(w, "dtkp")
+    prog.step()
+    np.testing.assert_array_equal(host(prog.fact_prob), ref["fact_prob"])
+    for t in range(1, length):
+        m, pp, pr = ref["stages"][t - 1]
+        np.testing.assert_array_equal(host(prog.accs[t].proof_mask).view(np.uint64), m)
+        np.testing.assert_array_equal(host(prog.accs[t].proof_prob), pp)
+    np.testing.assert_array_equal(host(prog.out.proof_mask).view(np.uint64), ref["mask"])
+    np.testing.assert_array_equal(host(prog.out.proof_prob), ref["pprob"])
+    assert_close(host(prog.out.prob), ref["prob"], "formula value probabilities")
+    assert_close(host(prog.gfact), ref["gfact"], "formula fact gradient")
+    assert_close(host(prog.grad_p), ref["grad_p"], "formula class gradient")
