@@ -23,7 +23,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 FP32_PEAK_TFLOPS = 157.3       # MI355X fp32 vector, published (256 CUs x 2.4 GHz x 128 lanes x 2 flop)
-SCALED_BATCH = {1: 1 << 22, 2: 1 << 19, 3: 1 << 18, 4: 1 << 18, 5: 1 << 13, 6: 1 << 11}
+SCALED_BATCH = {1: 1 << 22, 2: 1 << 19, 3: 1 << 18, 4: 1 << 18, 5: 1 << 13, 6: 1 << 11, 7: 1 << 11, 8: 1 << 12}
 
 
 def time_step(prog, torch, steps, warmup, mode):
@@ -121,7 +121,7 @@ def cpu_baseline(cfg, w, sample_ops, budget_s):
     import oracle
     from oracle import programs as OP
     run = {1: OP.sum2_fwd, 2: OP.sum_chain_fwd_bwd, 3: OP.hashed_pipeline_fwd_bwd, 4: OP.dtkp_sum_chain,
-           5: OP.grid_reach_fwd_bwd, 6: OP.product_chain_fwd_bwd}[cfg]
+           5: OP.grid_reach_fwd_bwd, 6: OP.product_chain_fwd_bwd, 7: OP.hwf_pipeline_dtkp, 8: OP.hwf_pipeline_damp}[cfg]
     want = int(os.environ.get("OMP_NUM_THREADS", "0") or 0) or (os.cpu_count() or 1)
     cores = oracle.set_threads(min(want, os.cpu_count() or 1))
     run(w)                                   # build + page in
@@ -141,8 +141,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4, 5, 6],
-                    help="1-5: the baseline configs; 6: Product-16 chain at B=256 (per-operator calls)")
+    ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4, 5, 6, 7, 8],
+                    help="1-5: the baseline configs; 6: Product-16 chain at B=256; 7 / 8: formula pipeline of 7 positions "
+                         "at B=64 under DTKP-AM top-3 / DAMP (6-8: per-operator calls)")
     ap.add_argument("--batch", type=int, default=0, help="override the config's batch size")
     ap.add_argument("--mode", default="auto", choices=["auto", "graph", "eager"],
                     help="how a step is issued: the launches one by one on the stream, or a HIP-graph replay of them; "

@@ -8,6 +8,9 @@
 // order (higher probability first, ties by smaller mask) is total on distinct masks, which makes the
 // result independent of the order candidates arrive in.
 #include "dtkp_util.h"
+#include "wave_util.h"
+
+#include <algorithm>
 
 namespace dol {
 
@@ -48,6 +51,36 @@ dol_status launch_dtkp_init(int32_t batch, int32_t n_sym, int32_t k, int32_t n_f
 
 // ---------------------------------------------------------------- apply2
 
+// Offers every consistent union of a proof of a's symbol with a proof of b's symbol (tuple ij) to the list.
+template <int K>
+__device__ __forceinline__ void offer_tuple(TopK<K> &top, uint32_t ij, int64_t a0, int64_t b0, const GroupMasks &gm,
+                                            const float *__restrict__ fp, const uint64_t *__restrict__ am,
+                                            const float *__restrict__ ap, const uint64_t *__restrict__ bm,
+                                            const float *__restrict__ bp)
+{
+    const int64_t ia = a0 + static_cast<int64_t>(ij & 0xffffu) * K, ib = b0 + static_cast<int64_t>(ij >> 16) * K;
+    uint64_t ma[K], mb[K];
+    float pa[K], pb[K];
+#pragma unroll
+    for (int x = 0; x < K; ++x) {
+        ma[x] = am[ia + x];
+        mb[x] = bm[ib + x];
+        pa[x] = ap ? ap[ia + x] : -1.0f;
+        pb[x] = bp ? bp[ib + x] : -1.0f;
+    }
+#pragma unroll
+    for (int x = 0; x < K; ++x) {
+        if (ma[x] == kAbsent) continue;
+#pragma unroll
+        for (int y = 0; y < K; ++y) {
+            if (mb[y] == kAbsent) continue;
+            const uint64_t m = ma[x] | mb[y];
+            if (proof_conflict(m, gm)) continue;
+            top.insert(m, union_prob(ma[x], pa[x], mb[y], pb[y], fp));
+        }
+    }
+}
+
 template <int K>
 __global__ void __launch_bounds__(kThreadsT)
 dtkp_apply2_kernel(int64_t total, int32_t S, int32_t na, int32_t nb, int32_t n_facts,
@@ -62,33 +95,53 @@ dtkp_apply2_kernel(int64_t total, int32_t S, int32_t na, int32_t nb, int32_t n_f
     const int32_t c = static_cast<int32_t>(idx - s * S);
     const float *fp = fact_prob + s * n_facts;
     const int64_t a0 = s * na * K, b0 = s * nb * K;
+    const uint32_t q0 = col_ptr[c], q1 = col_ptr[c + 1];
+    if (q1 - q0 > static_cast<uint32_t>(kLongTableCol)) return;          // left to the wavefront-per-column kernel
     TopK<K> top;
     top.clear();
-    for (uint32_t q = col_ptr[c], q1 = col_ptr[c + 1]; q < q1; ++q) {
-        const uint32_t ij = col_ij[q];
-        const int64_t ia = a0 + static_cast<int64_t>(ij & 0xffffu) * K, ib = b0 + static_cast<int64_t>(ij >> 16) * K;
-        uint64_t ma[K], mb[K];
-        float pa[K], pb[K];
-#pragma unroll
-        for (int x = 0; x < K; ++x) {
-            ma[x] = am[ia + x];
-            mb[x] = bm[ib + x];
-            pa[x] = ap ? ap[ia + x] : -1.0f;
-            pb[x] = bp ? bp[ib + x] : -1.0f;
-        }
-#pragma unroll
-        for (int x = 0; x < K; ++x) {
-            if (ma[x] == kAbsent) continue;
-#pragma unroll
-            for (int y = 0; y < K; ++y) {
-                if (mb[y] == kAbsent) continue;
-                const uint64_t m = ma[x] | mb[y];
-                if (proof_conflict(m, gm)) continue;
-                top.insert(m, union_prob(ma[x], pa[x], mb[y], pb[y], fp));
-            }
-        }
-    }
+    for (uint32_t q = q0; q < q1; ++q) offer_tuple<K>(top, col_ij[q], a0, b0, gm, fp, am, ap, bm, bp);
     oprob[s * ldo + c] = top.store(om + idx * K, op + idx * K);
+}
+
+// One wavefront per (sample, long column): every lane streams a share of the column's tuples through a list of its
+// own; the lists then meet by log2(64) exchange rounds in which each lane offers its partner's entries to its own
+// list.  The list order is total on distinct proofs and repeated proofs are one proof, so the result does not depend
+// on how the candidates were split.
+template <int K>
+__global__ void __launch_bounds__(kWave)
+dtkp_apply2_long_kernel(int32_t n_long, const uint32_t *__restrict__ long_cols, int32_t S, int32_t na, int32_t nb,
+                        int32_t n_facts, const uint32_t *__restrict__ col_ptr, const uint32_t *__restrict__ col_ij,
+                        GroupMasks gm, const float *__restrict__ fact_prob, const uint64_t *__restrict__ am,
+                        const float *__restrict__ ap, const uint64_t *__restrict__ bm, const float *__restrict__ bp,
+                        uint64_t *__restrict__ om, float *__restrict__ op, float *__restrict__ oprob, int64_t ldo)
+{
+    const int64_t s = blockIdx.x / n_long;
+    const uint32_t c = long_cols[blockIdx.x - s * n_long];
+    const float *fp = fact_prob + s * n_facts;
+    const int64_t a0 = s * na * K, b0 = s * nb * K;
+    TopK<K> top;
+    top.clear();
+    for (uint32_t q = col_ptr[c] + threadIdx.x, q1 = col_ptr[c + 1]; q < q1; q += kWave)
+        offer_tuple<K>(top, col_ij[q], a0, b0, gm, fp, am, ap, bm, bp);
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+        uint64_t pm[K];
+        float pp[K];
+#pragma unroll
+        for (int x = 0; x < K; ++x) {
+            const uint32_t lo = __shfl_xor(static_cast<uint32_t>(top.m[x]), d, kWave);
+            const uint32_t hi = __shfl_xor(static_cast<uint32_t>(top.m[x] >> 32), d, kWave);
+            pm[x] = (static_cast<uint64_t>(hi) << 32) | lo;
+            pp[x] = __shfl_xor(top.p[x], d, kWave);
+        }
+#pragma unroll
+        for (int x = 0; x < K; ++x)
+            if (pm[x] != kAbsent) top.insert(pm[x], pp[x]);
+    }
+    if (threadIdx.x == 0) {
+        const int64_t idx = s * S + c;
+        oprob[s * ldo + c] = top.store(om + idx * K, op + idx * K);
+    }
 }
 
 template <int K>
@@ -98,6 +151,11 @@ static void launch_apply2_k(int64_t total, const dol_fn_table *f, int32_t n_fact
 {
     hipLaunchKernelGGL(dtkp_apply2_kernel<K>, dim3(grid_t(total)), dim3(kThreadsT), 0, st, total, f->n_out, f->na,
                        f->nb, n_facts, f->col_ptr.ptr, f->col_ij.ptr, gm, fact_prob, am, ap, bm, bp, om, op, oprob, ldo);
+    const int64_t n_long = static_cast<int64_t>(f->long_cols.n);
+    if (n_long > 0)
+        hipLaunchKernelGGL(dtkp_apply2_long_kernel<K>, dim3(static_cast<unsigned>(total / f->n_out * n_long)), dim3(kWave),
+                           0, st, static_cast<int32_t>(n_long), f->long_cols.ptr, f->n_out, f->na, f->nb, n_facts,
+                           f->col_ptr.ptr, f->col_ij.ptr, gm, fact_prob, am, ap, bm, bp, om, op, oprob, ldo);
 }
 
 #define DOL_DISPATCH_K(k, CALL)                                      \
@@ -119,6 +177,8 @@ dol_status launch_dtkp_apply2(const dol_fn_table *f, int32_t batch, int32_t k, i
 {
     const int64_t total = static_cast<int64_t>(batch) * f->n_out;
     if (total == 0) return DOL_OK;
+    if (static_cast<int64_t>(batch) * static_cast<int64_t>(f->long_cols.n) > 0x7fffffffLL)
+        return fail(DOL_EUNSUPPORTED, "batch x long table columns exceeds 2^31");
 #define CALL(KK) launch_apply2_k<KK>(total, f, n_facts, gm, fact_prob, am, ap, bm, bp, om, op, oprob, ldo, st)
     DOL_DISPATCH_K(k, CALL)
 #undef CALL
@@ -205,38 +265,56 @@ dol_status launch_dtkp_filter(const FilterPlan *p, int32_t batch, int32_t k, con
 
 // Pr(symbol) = min(1, sum over its kept proofs of the product of their facts' probabilities) (Sec. 3.2); which
 // proofs top-k kept is a constant of the differentiation and the clamp passes gradient inside and on its bound
-// (App. A.2).  One wavefront per sample, lane f owns fact f and walks every proof of the sample: the control flow
-// is the same in all lanes (the proof's own fact multiplies by 1), the sums run in ascending (symbol, rank) order.
-__global__ void __launch_bounds__(64)
+// (App. A.2).  One workgroup per sample, one lane per symbol (coalesced loads of the proof lists); a lane walks the
+// facts of each of its proofs and adds gradient * (product of the proof's other facts, ascending) to the fact's
+// accumulator of its wavefront in LDS; the wavefronts' accumulators are then summed in wavefront order.
+constexpr int kGradWaves = 16;
+
+__global__ void __launch_bounds__(kGradWaves * 64)
 dtkp_prob_bwd_kernel(int32_t n_sym, int32_t k, int32_t n_facts, const uint64_t *__restrict__ mask,
                      const float *__restrict__ pprob, const float *__restrict__ fact_prob,
                      const float *__restrict__ g, int64_t ldg, float *__restrict__ gfact)
 {
+    __shared__ float part[kGradWaves][64];
+    __shared__ float fp[64];
     const int64_t s = blockIdx.x;
-    const int f = threadIdx.x;
-    const uint64_t mine = uint64_t(1) << f;
-    const float *fp = fact_prob + s * n_facts;
-    float acc = 0.0f;
-    for (int32_t i = 0; i < n_sym; ++i) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, n_waves = blockDim.x >> 6;
+    part[wave][lane] = 0.0f;
+    if (wave == 0) fp[lane] = lane < n_facts ? fact_prob[s * n_facts + lane] : 1.0f;
+    __syncthreads();
+    for (int32_t i = threadIdx.x; i < n_sym; i += blockDim.x) {
         const uint64_t *m = mask + (s * n_sym + i) * k;
         const float *pp = pprob + (s * n_sym + i) * k;
-        float sum = 0.0f;                   // the quantity the forward pass clamped: kept proofs in rank order
-        for (int x = 0; x < k; ++x)
-            if (m[x] != kAbsent) sum = sum + pp[x];
-        if (!(sum <= 1.0f)) continue;
+        uint64_t mm[DOL_MAX_K];
+        float pv[DOL_MAX_K];
+#pragma unroll
+        for (int x = 0; x < DOL_MAX_K; ++x) {
+            mm[x] = x < k ? m[x] : kAbsent;
+            pv[x] = x < k ? pp[x] : 0.0f;
+        }
         const float gi = g[s * ldg + i];
-        for (int x = 0; x < k; ++x) {
-            const uint64_t mm = m[x];
-            if (mm == kAbsent) continue;
-            float others = 1.0f;
-            for (uint64_t r = mm; r; r &= r - 1) {
+        float sum = 0.0f;                   // the quantity the forward pass clamped: kept proofs in rank order
+#pragma unroll
+        for (int x = 0; x < DOL_MAX_K; ++x)
+            if (mm[x] != kAbsent) sum = sum + pv[x];
+        if (!(sum <= 1.0f)) continue;
+#pragma unroll
+        for (int x = 0; x < DOL_MAX_K; ++x) {
+            if (mm[x] == kAbsent) continue;
+            for (uint64_t r = mm[x]; r; r &= r - 1) {
                 const int j = __builtin_ctzll(r);
-                others = others * (j == f ? 1.0f : fp[j]);
+                float others = 1.0f;
+                for (uint64_t q = mm[x] & ~(uint64_t(1) << j); q; q &= q - 1) others = others * fp[__builtin_ctzll(q)];
+                atomicAdd(&part[wave][j], gi * others);
             }
-            if (mm & mine) acc = __builtin_fmaf(gi, others, acc);
         }
     }
-    if (f < n_facts) gfact[s * n_facts + f] = acc;
+    __syncthreads();
+    if (wave == 0 && lane < n_facts) {
+        float tot = 0.0f;
+        for (int w = 0; w < n_waves; ++w) tot = tot + part[w][lane];
+        gfact[s * n_facts + lane] = tot;
+    }
 }
 
 dol_status launch_dtkp_prob_bwd(int32_t batch, int32_t n_sym, int32_t k, int32_t n_facts, const uint64_t *mask,
@@ -244,8 +322,9 @@ dol_status launch_dtkp_prob_bwd(int32_t batch, int32_t n_sym, int32_t k, int32_t
                                 hipStream_t st)
 {
     if (batch == 0 || n_facts == 0) return DOL_OK;
-    hipLaunchKernelGGL(dtkp_prob_bwd_kernel, dim3(static_cast<unsigned>(batch)), dim3(64), 0, st, n_sym, k, n_facts, mask,
-                       pprob, fact_prob, g, ldg, gfact);
+    const int waves = std::max(1, std::min(kGradWaves, (n_sym + 63) / 64));
+    hipLaunchKernelGGL(dtkp_prob_bwd_kernel, dim3(static_cast<unsigned>(batch)), dim3(64 * waves), 0, st, n_sym, k,
+                       n_facts, mask, pprob, fact_prob, g, ldg, gfact);
     DOL_HIP(hipGetLastError());
     return DOL_OK;
 }

@@ -500,5 +500,7 @@ class HwfPipeline(Program):
 
 
 def make_program(config_id: int, workload, device="cuda") -> Program:
+    if config_id in (7, 8):
+        return HwfPipeline(workload, "dtkp" if config_id == 7 else "damp", device)
     return {1: Sum2Forward, 2: SumChain, 3: HashedPipeline, 4: DtkpSumChain, 5: GridReach,
             6: ProductChain}[config_id](workload, device)

@@ -334,8 +334,10 @@ def config5(batch: int = 256, side: int = 32, rounds: int = 64, seed: int = 0) -
 
 CONFIG_NAMES = {1: "sum2_damp_fwd", 2: "sum15_damp_chain_fwd_bwd", 3: "hashed_apply_filter_union_damp_fwd_bwd",
                 4: "dtkp_top3_sum5_fwd", 5: "grid32_reach_damp_fwd_bwd",
-                6: "product16_damp_chain_fwd_bwd"}
+                6: "product16_damp_chain_fwd_bwd", 7: "hwf7_filter_concat_eval_dtkp_top3",
+                8: "hwf7_filter_concat_eval_damp"}
 
 
 def make_config(cid: int, **kw) -> Workload:
-    return {1: config1, 2: config2, 3: config3, 4: config4, 5: config5, 6: product_workload}[cid](**kw)
+    return {1: config1, 2: config2, 3: config3, 4: config4, 5: config5, 6: product_workload, 7: hwf_workload,
+            8: hwf_workload}[cid](**kw)
