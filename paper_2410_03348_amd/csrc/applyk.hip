@@ -9,6 +9,7 @@
 #include "dtkp_util.h"
 #include "element_map.h"
 #include "internal.h"
+#include "wave_util.h"
 
 #include <algorithm>
 #include <memory>
@@ -27,6 +28,7 @@ struct dol_fnk_table {
     dol::DevArray<uint32_t> tup_col;     // [n_tuples] column of each grouped tuple
     dol::DevArray<uint32_t> row_ptr;     // [sum n_sym + 1]
     dol::DevArray<uint32_t> row_tup;     // [n_tuples*K] grouped-tuple numbers of each operand row, ascending
+    dol::DevArray<uint32_t> long_cols;   // columns with more than dol::kLongTableCol tuples
     int device = 0;
 };
 
@@ -50,19 +52,37 @@ struct KProofs {
 
 // ---------------------------------------------------------------- DAMP
 
-// pre of one column: tuples in ascending index order, one term each (the order fixes the clamp decision).
+// pre of one column: tuples in ascending index order, one term each (the order fixes the clamp decision).  The
+// loads of kGatherK tuples are issued together (positions first, then the tags they name); the adds keep their order.
+constexpr int kGatherK = 4;
+
 template <int K>
 __device__ __forceinline__ float column_sum_k(const float *const *row, const uint16_t *__restrict__ tup,
                                               uint32_t q0, uint32_t q1)
 {
     float acc = 0.0f;
-    for (uint32_t q = q0; q < q1; ++q) {
-        const uint16_t *t = tup + static_cast<size_t>(q) * K;
-        float head = row[0][t[0]];
+    for (uint32_t q = q0; q < q1; q += kGatherK) {
+        uint16_t pos[kGatherK][K];
+        float v[kGatherK][K];
 #pragma unroll
-        for (int l = 1; l + 1 < K; ++l) head = head * row[l][t[l]];
-        if (K == 1) acc = acc + head;
-        else acc = __builtin_fmaf(head, row[K - 1][t[K - 1]], acc);
+        for (int u = 0; u < kGatherK; ++u) {
+            const uint16_t *t = tup + static_cast<size_t>(min(q + u, q1 - 1)) * K;
+#pragma unroll
+            for (int l = 0; l < K; ++l) pos[u][l] = t[l];
+        }
+#pragma unroll
+        for (int u = 0; u < kGatherK; ++u)
+#pragma unroll
+            for (int l = 0; l < K; ++l) v[u][l] = row[l][pos[u][l]];
+#pragma unroll
+        for (int u = 0; u < kGatherK; ++u) {
+            if (q + u >= q1) break;
+            float head = v[u][0];
+#pragma unroll
+            for (int l = 1; l + 1 < K; ++l) head = head * v[u][l];
+            if (K == 1) acc = acc + head;
+            else acc = __builtin_fmaf(head, v[u][K - 1], acc);
+        }
     }
     return acc;
 }
@@ -76,8 +96,47 @@ damp_applyk_fwd_kernel(Rows R, KOperands in, const uint32_t *__restrict__ col_pt
         const float *row[K];
 #pragma unroll
         for (int l = 0; l < K; ++l) row[l] = in.p[l] + s * in.ld[l];
-        out[s * ldo + c] = fminf(column_sum_k<K>(row, tup, col_ptr[c], col_ptr[c + 1]), 1.0f);
+        const uint32_t q0 = col_ptr[c], q1 = col_ptr[c + 1];
+        if (q1 - q0 > static_cast<uint32_t>(kLongTableCol)) return;        // left to the wavefront-per-column kernel
+        out[s * ldo + c] = fminf(column_sum_k<K>(row, tup, q0, q1), 1.0f);
     });
+}
+
+// One wavefront per (sample, long column): lanes stride over the tuples and their partial sums meet by shuffles.
+// That is not the order the clamp decision is defined in, so the lanes also add up the terms' magnitudes, which
+// bounds how far the two orders can lie apart (about n roundings of relative size 2^-24 each way); only a sum within
+// that distance of 1 is taken again in the defining order.
+template <int K>
+__global__ void __launch_bounds__(kWave)
+damp_applyk_fwd_long_kernel(int32_t n_long, const uint32_t *__restrict__ long_cols, KOperands in,
+                            const uint32_t *__restrict__ col_ptr, const uint16_t *__restrict__ tup,
+                            float *__restrict__ out, int64_t ldo)
+{
+    const int64_t s = blockIdx.x / n_long;
+    const uint32_t c = long_cols[blockIdx.x - s * n_long];
+    const float *row[K];
+#pragma unroll
+    for (int l = 0; l < K; ++l) row[l] = in.p[l] + s * in.ld[l];
+    const uint32_t q0 = col_ptr[c], q1 = col_ptr[c + 1];
+    float acc = 0.0f, mag = 0.0f;
+    for (uint32_t q = q0 + threadIdx.x; q < q1; q += kWave) {
+        const uint16_t *t = tup + static_cast<size_t>(q) * K;
+        float term = row[0][t[0]];
+#pragma unroll
+        for (int l = 1; l < K; ++l) term = term * row[l][t[l]];
+        acc = acc + term;
+        mag = mag + fabsf(term);
+    }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+        acc += __shfl_xor(acc, d, kWave);
+        mag += __shfl_xor(mag, d, kWave);
+    }
+    // the per-term products differ from the defining order's by at most K roundings each
+    const float slack = mag * (static_cast<float>(q1 - q0 + kWave + 2 * K) * 1.1920929e-7f);
+    float pre = acc;
+    if (fabsf(acc - 1.0f) <= slack) pre = column_sum_k<K>(row, tup, q0, q1);
+    if (threadIdx.x == 0) out[s * ldo + c] = fminf(pre, 1.0f);
 }
 
 template <int K>
@@ -125,6 +184,10 @@ static void launch_fwd_k(const Rows &R, const KOperands &in, const dol_fnk_table
 {
     hipLaunchKernelGGL(damp_applyk_fwd_kernel<K>, dim3(R.grid), dim3(kThreads), 0, st, R, in, f->col_ptr.ptr, f->tup.ptr,
                        out, ldo);
+    const int64_t n_long = static_cast<int64_t>(f->long_cols.n);
+    if (n_long > 0)
+        hipLaunchKernelGGL(damp_applyk_fwd_long_kernel<K>, dim3(static_cast<unsigned>(R.batch * n_long)), dim3(kWave), 0, st,
+                           static_cast<int32_t>(n_long), f->long_cols.ptr, in, f->col_ptr.ptr, f->tup.ptr, out, ldo);
 }
 
 template <int K>
@@ -149,8 +212,52 @@ static void launch_bwd_k(const Rows &R, const KOperands &in, const KGrads &gin, 
 
 constexpr int kThreadsP = 128;
 
-// One thread per (sample, output symbol).  A tuple's tag is the binary conjunction of Table 1 folded over the
-// operands left to right, each intermediate pruned to k proofs; the tuples' proofs then meet in one k-entry list.
+// Offers the proofs of one tuple's tag to the list: the binary conjunction of Table 1 folded over the operands left
+// to right, each intermediate pruned to k proofs.
+template <int KP>
+__device__ __forceinline__ void offer_tuple_k(TopK<KP> &top, const uint16_t *__restrict__ t, int64_t s, int32_t arity,
+                                              const KProofs &in, const GroupMasks &gm, const float *__restrict__ fp)
+{
+    TopK<KP> cur;
+    {
+        const int64_t o = (s * in.n[0] + t[0]) * KP;
+#pragma unroll
+        for (int x = 0; x < KP; ++x) {
+            const uint64_t m = in.m[0][o + x];
+            cur.m[x] = m;
+            cur.p[x] = m == kAbsent ? -1.0f : in.p[0] ? in.p[0][o + x] : proof_prob(m, fp);
+        }
+    }
+    for (int l = 1; l < arity; ++l) {
+        const int64_t o = (s * in.n[l] + t[l]) * KP;
+        uint64_t mb[KP];
+        float pb[KP];
+#pragma unroll
+        for (int y = 0; y < KP; ++y) {
+            mb[y] = in.m[l][o + y];
+            pb[y] = in.p[l] ? in.p[l][o + y] : -1.0f;
+        }
+        TopK<KP> nxt;
+        nxt.clear();
+#pragma unroll
+        for (int x = 0; x < KP; ++x) {
+            if (cur.m[x] == kAbsent) continue;
+#pragma unroll
+            for (int y = 0; y < KP; ++y) {
+                if (mb[y] == kAbsent) continue;
+                const uint64_t u = cur.m[x] | mb[y];
+                if (proof_conflict(u, gm)) continue;
+                nxt.insert(u, union_prob(cur.m[x], cur.p[x], mb[y], pb[y], fp));
+            }
+        }
+        cur = nxt;
+    }
+#pragma unroll
+    for (int x = 0; x < KP; ++x)
+        if (cur.m[x] != kAbsent) top.insert(cur.m[x], cur.p[x]);
+}
+
+// One thread per (sample, output symbol): the proofs of the column's tuples meet in one k-entry list.
 template <int KP>
 __global__ void __launch_bounds__(kThreadsP)
 dtkp_applyk_kernel(int64_t total, int32_t S, int32_t arity, KProofs in, const uint32_t *__restrict__ col_ptr,
@@ -162,49 +269,51 @@ dtkp_applyk_kernel(int64_t total, int32_t S, int32_t arity, KProofs in, const ui
     const int64_t s = idx / S;
     const int32_t c = static_cast<int32_t>(idx - s * S);
     const float *fp = fact_prob + s * n_facts;
+    const uint32_t q0 = col_ptr[c], q1 = col_ptr[c + 1];
+    if (q1 - q0 > static_cast<uint32_t>(kLongTableCol)) return;            // left to the wavefront-per-column kernel
     TopK<KP> top;
     top.clear();
-    for (uint32_t q = col_ptr[c], q1 = col_ptr[c + 1]; q < q1; ++q) {
-        const uint16_t *t = tup + static_cast<size_t>(q) * arity;
-        TopK<KP> cur;
-        {
-            const int64_t o = (s * in.n[0] + t[0]) * KP;
+    for (uint32_t q = q0; q < q1; ++q) {
+        offer_tuple_k<KP>(top, tup + static_cast<size_t>(q) * arity, s, arity, in, gm, fp);
+    }
+    oprob[s * ldo + c] = top.store(om + idx * KP, op + idx * KP);
+}
+
+// One wavefront per (sample, long column): every lane streams a share of the tuples through a list of its own; the
+// lists meet by exchange rounds (the list order is total on distinct proofs, so the split does not matter).
+template <int KP>
+__global__ void __launch_bounds__(kWave)
+dtkp_applyk_long_kernel(int32_t n_long, const uint32_t *__restrict__ long_cols, int32_t S, int32_t arity, KProofs in,
+                        const uint32_t *__restrict__ col_ptr, const uint16_t *__restrict__ tup, GroupMasks gm,
+                        int32_t n_facts, const float *__restrict__ fact_prob, uint64_t *__restrict__ om,
+                        float *__restrict__ op, float *__restrict__ oprob, int64_t ldo)
+{
+    const int64_t s = blockIdx.x / n_long;
+    const uint32_t c = long_cols[blockIdx.x - s * n_long];
+    const float *fp = fact_prob + s * n_facts;
+    TopK<KP> top;
+    top.clear();
+    for (uint32_t q = col_ptr[c] + threadIdx.x, q1 = col_ptr[c + 1]; q < q1; q += kWave)
+        offer_tuple_k<KP>(top, tup + static_cast<size_t>(q) * arity, s, arity, in, gm, fp);
 #pragma unroll
-            for (int x = 0; x < KP; ++x) {
-                const uint64_t m = in.m[0][o + x];
-                cur.m[x] = m;
-                cur.p[x] = m == kAbsent ? -1.0f : in.p[0] ? in.p[0][o + x] : proof_prob(m, fp);
-            }
-        }
-        for (int l = 1; l < arity; ++l) {
-            const int64_t o = (s * in.n[l] + t[l]) * KP;
-            uint64_t mb[KP];
-            float pb[KP];
+    for (int d = 32; d >= 1; d >>= 1) {
+        uint64_t pm[KP];
+        float pp[KP];
 #pragma unroll
-            for (int y = 0; y < KP; ++y) {
-                mb[y] = in.m[l][o + y];
-                pb[y] = in.p[l] ? in.p[l][o + y] : -1.0f;
-            }
-            TopK<KP> nxt;
-            nxt.clear();
-#pragma unroll
-            for (int x = 0; x < KP; ++x) {
-                if (cur.m[x] == kAbsent) continue;
-#pragma unroll
-                for (int y = 0; y < KP; ++y) {
-                    if (mb[y] == kAbsent) continue;
-                    const uint64_t u = cur.m[x] | mb[y];
-                    if (proof_conflict(u, gm)) continue;
-                    nxt.insert(u, union_prob(cur.m[x], cur.p[x], mb[y], pb[y], fp));
-                }
-            }
-            cur = nxt;
+        for (int x = 0; x < KP; ++x) {
+            const uint32_t lo = __shfl_xor(static_cast<uint32_t>(top.m[x]), d, kWave);
+            const uint32_t hi = __shfl_xor(static_cast<uint32_t>(top.m[x] >> 32), d, kWave);
+            pm[x] = (static_cast<uint64_t>(hi) << 32) | lo;
+            pp[x] = __shfl_xor(top.p[x], d, kWave);
         }
 #pragma unroll
         for (int x = 0; x < KP; ++x)
-            if (cur.m[x] != kAbsent) top.insert(cur.m[x], cur.p[x]);
+            if (pm[x] != kAbsent) top.insert(pm[x], pp[x]);
     }
-    oprob[s * ldo + c] = top.store(om + idx * KP, op + idx * KP);
+    if (threadIdx.x == 0) {
+        const int64_t idx = s * S + c;
+        oprob[s * ldo + c] = top.store(om + idx * KP, op + idx * KP);
+    }
 }
 
 template <int KP>
@@ -214,6 +323,11 @@ static void launch_dtkp_k(int64_t total, const dol_fnk_table *f, const KProofs &
     hipLaunchKernelGGL(dtkp_applyk_kernel<KP>, dim3(static_cast<unsigned>((total + kThreadsP - 1) / kThreadsP)),
                        dim3(kThreadsP), 0, st, total, f->n_out, f->K, in, f->col_ptr.ptr, f->tup.ptr, gm, n_facts,
                        fact_prob, om, op, oprob, ldo);
+    const int64_t n_long = static_cast<int64_t>(f->long_cols.n);
+    if (n_long > 0)
+        hipLaunchKernelGGL(dtkp_applyk_long_kernel<KP>, dim3(static_cast<unsigned>(total / f->n_out * n_long)), dim3(kWave),
+                           0, st, static_cast<int32_t>(n_long), f->long_cols.ptr, f->n_out, f->K, in, f->col_ptr.ptr,
+                           f->tup.ptr, gm, n_facts, fact_prob, om, op, oprob, ldo);
 }
 
 // ---------------------------------------------------------------- plan
@@ -284,7 +398,12 @@ static dol_status build_k(int32_t K, const int32_t *n_sym, int64_t n, const int3
             for (int l = 0; l < K; ++l) row_tup[fill[tb->row_base[l] + tup[t * K + l]]++] = static_cast<uint32_t>(t);
     }
 
+    std::vector<uint32_t> long_cols;
+    for (int32_t c = 0; c < S; ++c)
+        if (col_ptr[c + 1] - col_ptr[c] > static_cast<uint32_t>(kLongTableCol)) long_cols.push_back(static_cast<uint32_t>(c));
+
     DOL_HIP(hipGetDevice(&tb->device));
+    DOL_HIP(tb->long_cols.upload(long_cols));
     DOL_HIP(tb->col_ptr.upload(col_ptr));
     DOL_HIP(tb->tup.upload(tup));
     DOL_HIP(tb->tup_col.upload(tup_col));
@@ -350,6 +469,8 @@ dol_status dol_apply_k(int32_t K, const dol_dist *const *in, const dol_fnk_table
             if (out->sym_ids[c] != f->out_syms[c]) return fail(DOL_EINVAL, "out.sym_ids[%d] = %d, the table produces %d there", c, out->sym_ids[c], f->out_syms[c]);
     if (dol_status st = check_work(batch, f->n_out)) return st;
     if (batch == 0 || f->n_out == 0) return DOL_OK;
+    if (static_cast<int64_t>(batch) * static_cast<int64_t>(f->long_cols.n) > 0x7fffffffLL)
+        return fail(DOL_EUNSUPPORTED, "batch x long table columns exceeds 2^31");
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     if (!dtkp) {
         KOperands ops{};

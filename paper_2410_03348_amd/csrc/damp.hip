@@ -96,6 +96,56 @@ damp_apply2_fwd_long_kernel(int32_t n_long, const uint32_t *__restrict__ long_co
     if (threadIdx.x == 0) out[s * ldo + c] = fminf(pre, 1.0f);
 }
 
+// Tables with a short second operand: one thread per (sample, column) walks the dense map one j at a time (index
+// loads coalesced, the gathers of neighbouring lanes adjacent wherever the function is monotone in i).  That is
+// not the order the clamp decision is defined in; the terms' magnitudes bound how far the two sums can lie apart,
+// and only a sum within that distance of 1 is taken again in the defining order.
+__global__ void __launch_bounds__(kThreads)
+damp_byj_fwd_kernel(Rows R, int32_t nb, const int32_t *__restrict__ src, const uint32_t *__restrict__ col_ptr,
+                    const uint32_t *__restrict__ col_ij, const float *__restrict__ a, int64_t lda,
+                    const float *__restrict__ b, int64_t ldb, float *__restrict__ out, int64_t ldo)
+{
+    for_each_element(R, [&](int64_t s, int c) {
+        const float *ar = a + s * lda, *br = b + s * ldb;
+        int32_t i[kByJMax];
+        float x[kByJMax];
+#pragma unroll
+        for (int j = 0; j < kByJMax; ++j) i[j] = j < nb ? src[static_cast<size_t>(j) * R.n + c] : -1;
+        if (i[0] == -2) return;                                           // left to the wavefront-per-column kernel
+        if (i[0] == -3) {                                                 // some j twice: the tuple list itself
+            out[s * ldo + c] = fminf(column_sum(ar, br, col_ij, col_ptr[c], col_ptr[c + 1]), 1.0f);
+            return;
+        }
+#pragma unroll
+        for (int j = 0; j < kByJMax; ++j) x[j] = i[j] >= 0 ? ar[i[j]] : 0.0f;
+        float acc = 0.0f, mag = 0.0f;
+#pragma unroll
+        for (int j = 0; j < kByJMax; ++j)
+            if (i[j] >= 0) {
+                const float y = br[j];
+                acc = __builtin_fmaf(x[j], y, acc);
+                mag = __builtin_fmaf(fabsf(x[j]), fabsf(y), mag);
+            }
+        float pre = acc;
+        if (fabsf(acc - 1.0f) <= mag * (static_cast<float>(nb + 2) * 1.1920929e-7f))
+            pre = column_sum(ar, br, col_ij, col_ptr[c], col_ptr[c + 1]);
+        out[s * ldo + c] = fminf(pre, 1.0f);
+    });
+}
+
+static dol_status launch_fwd_waves(const dol_fn_table *f, const DevArray<uint32_t> &cols, int32_t batch, const float *a,
+                                   int64_t lda, const float *b, int64_t ldb, float *out, int64_t ldo, hipStream_t st)
+{
+    const int64_t n_long = static_cast<int64_t>(cols.n);
+    if (n_long == 0) return DOL_OK;
+    if (batch * n_long > 0x7fffffffLL)
+        return fail(DOL_EUNSUPPORTED, "batch x long table columns = %lld exceeds 2^31", static_cast<long long>(batch * n_long));
+    hipLaunchKernelGGL(damp_apply2_fwd_long_kernel, dim3(static_cast<unsigned>(batch * n_long)), dim3(kWave), 0, st,
+                       static_cast<int32_t>(n_long), cols.ptr, f->col_ptr.ptr, f->col_ij.ptr, a, lda, b, ldb, out, ldo);
+    DOL_HIP(hipGetLastError());
+    return DOL_OK;
+}
+
 dol_status launch_damp_apply2_fwd(const dol_fn_table *f, int32_t batch, const float *a, int64_t lda, const float *b,
                                   int64_t ldb, float *out, int64_t ldo, hipStream_t st)
 {
@@ -105,19 +155,16 @@ dol_status launch_damp_apply2_fwd(const dol_fn_table *f, int32_t batch, const fl
     if (dol_status s2 = launch_damp_lds_fwd(f, batch, a, lda, b, ldb, out, ldo, st, &done)) return s2;
     if (done) return DOL_OK;
     const Rows R = rows_of(batch, f->n_out);
+    if (f->byj_fwd) {
+        hipLaunchKernelGGL(damp_byj_fwd_kernel, dim3(R.grid), dim3(kThreads), 0, st, R, f->nb, f->byj_src.ptr, f->col_ptr.ptr,
+                           f->col_ij.ptr, a, lda, b, ldb, out, ldo);
+        DOL_HIP(hipGetLastError());
+        return launch_fwd_waves(f, f->byj_wave_cols, batch, a, lda, b, ldb, out, ldo, st);
+    }
     hipLaunchKernelGGL(damp_apply2_fwd_kernel, dim3(R.grid), dim3(kThreads), 0, st, R, f->col_ptr.ptr, f->col_ij.ptr, a,
                        lda, b, ldb, out, ldo);
     DOL_HIP(hipGetLastError());
-    const int64_t n_long = static_cast<int64_t>(f->long_cols.n);
-    if (n_long > 0) {
-        if (batch * n_long > 0x7fffffffLL)
-            return fail(DOL_EUNSUPPORTED, "batch x long table columns = %lld exceeds 2^31", static_cast<long long>(batch * n_long));
-        hipLaunchKernelGGL(damp_apply2_fwd_long_kernel, dim3(static_cast<unsigned>(batch * n_long)), dim3(kWave), 0, st,
-                           static_cast<int32_t>(n_long), f->long_cols.ptr, f->col_ptr.ptr, f->col_ij.ptr, a, lda, b, ldb,
-                           out, ldo);
-        DOL_HIP(hipGetLastError());
-    }
-    return DOL_OK;
+    return launch_fwd_waves(f, f->long_cols, batch, a, lda, b, ldb, out, ldo, st);
 }
 
 // ---------------------------------------------------------------- apply2 backward
@@ -191,6 +238,112 @@ damp_apply2_bwd_kernel(Rows R, BwdTable T, const float *__restrict__ a, int64_t 
     });
 }
 
+// The same for tables with a short second operand: a row i of a reads its columns from the dense map, one j at a
+// time (ascending j, the order of the row's tuple list); rows of b walk their lists as above.
+__global__ void __launch_bounds__(kThreads)
+damp_byj_bwd_kernel(Rows R, BwdTable T, const int32_t *__restrict__ col_of, const float *__restrict__ a, int64_t lda,
+                    const float *__restrict__ b, int64_t ldb, const float *__restrict__ out, int64_t ldo,
+                    const float *__restrict__ g, int64_t ldg, float *__restrict__ ga, float *__restrict__ gb,
+                    int32_t accumulate)
+{
+    for_each_element(R, [&](int64_t s, int x) {
+        const float *ar = a + s * lda, *br = b + s * ldb, *outr = out + s * ldo, *gr = g + s * ldg;
+        if (x < T.na) {
+            if (!ga) return;
+            int32_t c[kByJMax];
+            float gv[kByJMax], ov[kByJMax];
+#pragma unroll
+            for (int j = 0; j < kByJMax; ++j) c[j] = j < T.nb ? col_of[static_cast<size_t>(j) * T.na + x] : -1;
+#pragma unroll
+            for (int j = 0; j < kByJMax; ++j) {
+                gv[j] = c[j] >= 0 ? gr[c[j]] : 0.0f;
+                ov[j] = c[j] >= 0 ? outr[c[j]] : 0.0f;
+            }
+            float acc = 0.0f;
+#pragma unroll
+            for (int j = 0; j < kByJMax; ++j)
+                if (c[j] >= 0)
+                    acc = __builtin_fmaf(gated_grad(gv[j], ov[j], ar, br, T.col_ptr, T.col_ij, static_cast<uint32_t>(c[j])), br[j], acc);
+            float *dst = ga + s * lda + x;
+            *dst = (accumulate & 1) ? *dst + acc : acc;
+            return;
+        }
+        if (!gb) return;
+        const int r = x - T.na;
+        const uint32_t q0 = T.rowb_ptr[r], q1 = T.rowb_ptr[r + 1];
+        if (q1 - q0 > kLongTableRow) return;
+        const float acc = row_sum(0.0f, T.rowb_ic, q0, q1, 1, gr, outr, ar, ar, br, T.col_ptr, T.col_ij);
+        float *dst = gb + s * ldb + r;
+        *dst = (accumulate & 2) ? *dst + acc : acc;
+    });
+}
+
+// The same for wide operands (na + nb >= 2048): one workgroup of 1024 threads owns a whole sample.  A first pass
+// over the sample's result row tells whether any column sits at the clamp; if none does, the gate is open
+// everywhere and `out` is not gathered again.  Each thread also adds its rows' shares g^[col(i, j)] * a[i] of the
+// gradient w.r.t. b[j] into registers; the workgroup sums them, so the long rows of b need no launch of their own.
+constexpr int kByJRowThreads = 1024;
+
+__global__ void __launch_bounds__(kByJRowThreads)
+damp_byj_bwd_row_kernel(BwdTable T, int32_t S, const int32_t *__restrict__ col_of, const float *__restrict__ a,
+                        int64_t lda, const float *__restrict__ b, int64_t ldb, const float *__restrict__ out, int64_t ldo,
+                        const float *__restrict__ g, int64_t ldg, float *__restrict__ ga, float *__restrict__ gb,
+                        int32_t accumulate)
+{
+    __shared__ float red[kByJMax][kByJRowThreads / kWave];
+    const int64_t s = blockIdx.x;
+    const float *ar = a + s * lda, *br = b + s * ldb, *outr = out + s * ldo, *gr = g + s * ldg;
+    int hit = 0;
+    for (int c = threadIdx.x; c < S; c += kByJRowThreads) hit |= outr[c] >= 1.0f;
+    const bool clamped = __syncthreads_or(hit) != 0;
+    float bj[kByJMax], pb[kByJMax];
+#pragma unroll
+    for (int j = 0; j < kByJMax; ++j) {
+        bj[j] = j < T.nb ? br[j] : 0.0f;
+        pb[j] = 0.0f;
+    }
+    for (int i = threadIdx.x; i < T.na; i += kByJRowThreads) {
+        int32_t c[kByJMax];
+        float gv[kByJMax], ov[kByJMax];
+#pragma unroll
+        for (int j = 0; j < kByJMax; ++j) c[j] = j < T.nb ? col_of[static_cast<size_t>(j) * T.na + i] : -1;
+        const float ai = ar[i];
+#pragma unroll
+        for (int j = 0; j < kByJMax; ++j) {
+            gv[j] = c[j] >= 0 ? gr[c[j]] : 0.0f;
+            ov[j] = clamped && c[j] >= 0 ? outr[c[j]] : 0.0f;
+        }
+        float acc = 0.0f;
+#pragma unroll
+        for (int j = 0; j < kByJMax; ++j)
+            if (c[j] >= 0) {
+                const float gh = gated_grad(gv[j], ov[j], ar, br, T.col_ptr, T.col_ij, static_cast<uint32_t>(c[j]));
+                acc = __builtin_fmaf(gh, bj[j], acc);
+                pb[j] = __builtin_fmaf(gh, ai, pb[j]);
+            }
+        if (ga) {
+            float *dst = ga + s * lda + i;
+            *dst = (accumulate & 1) ? *dst + acc : acc;
+        }
+    }
+    if (!gb) return;
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+#pragma unroll
+    for (int j = 0; j < kByJMax; ++j) {
+        float v = pb[j];
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, kWave);
+        if (lane == 0) red[j][wave] = v;
+    }
+    __syncthreads();
+    if (threadIdx.x < static_cast<unsigned>(T.nb)) {
+        float tot = 0.0f;
+        for (int w = 0; w < kByJRowThreads / kWave; ++w) tot = tot + red[threadIdx.x][w];
+        float *dst = gb + s * ldb + threadIdx.x;
+        *dst = (accumulate & 2) ? *dst + tot : tot;
+    }
+}
+
 // One wavefront per (sample, long row): lanes stride over the row's tuples, the partial sums meet by shuffles.
 __global__ void __launch_bounds__(kWave)
 damp_apply2_bwd_long_kernel(int32_t n_long, const uint32_t *__restrict__ long_rows, BwdTable T,
@@ -229,8 +382,18 @@ dol_status launch_damp_apply2_bwd(const dol_fn_table *f, int32_t batch, const fl
     const BwdTable T{f->col_ptr.ptr, f->col_ij.ptr, f->rowa_ptr.ptr, f->rowa_jc.ptr, f->rowb_ptr.ptr, f->rowb_ic.ptr,
                      f->na, f->nb};
     const Rows R = rows_of(batch, f->na + f->nb);
-    hipLaunchKernelGGL(damp_apply2_bwd_kernel, dim3(R.grid), dim3(kThreads), 0, st, R, T, a, lda, b, ldb, out, ldo, g,
-                       ldg, ga, gb, accumulate);
+    if (f->byj_ok && R.rpb == 1) {
+        hipLaunchKernelGGL(damp_byj_bwd_row_kernel, dim3(static_cast<unsigned>(batch)), dim3(kByJRowThreads), 0, st, T,
+                           f->n_out, f->byj_col.ptr, a, lda, b, ldb, out, ldo, g, ldg, ga, gb, accumulate);
+        DOL_HIP(hipGetLastError());
+        return DOL_OK;
+    }
+    if (f->byj_ok)
+        hipLaunchKernelGGL(damp_byj_bwd_kernel, dim3(R.grid), dim3(kThreads), 0, st, R, T, f->byj_col.ptr, a, lda, b, ldb, out,
+                           ldo, g, ldg, ga, gb, accumulate);
+    else
+        hipLaunchKernelGGL(damp_apply2_bwd_kernel, dim3(R.grid), dim3(kThreads), 0, st, R, T, a, lda, b, ldb, out, ldo, g,
+                           ldg, ga, gb, accumulate);
     DOL_HIP(hipGetLastError());
     const int64_t n_long = static_cast<int64_t>(f->long_rows.n);
     if (n_long > 0) {

@@ -40,8 +40,8 @@ bool conv_path_ok(const dol_fn_table *f)
 std::string damp_kernel_name(const dol_fn_table *f, bool backward)
 {
     if (!conv_path_ok(f)) {
-        if (backward) return f->lds_bwd_ok ? "damp_lds_bwd_kernel" : "damp_apply2_bwd_kernel";
-        return f->lds_fwd_ok ? "damp_lds_fwd_kernel" : "damp_apply2_fwd_kernel";
+        if (backward) return f->lds_bwd_ok ? "damp_lds_bwd_kernel" : !f->byj_ok ? "damp_apply2_bwd_kernel" : f->na + f->nb > 1024 ? "damp_byj_bwd_row_kernel" : "damp_byj_bwd_kernel";
+        return f->lds_fwd_ok ? "damp_lds_fwd_kernel" : f->byj_fwd ? "damp_byj_fwd_kernel" : "damp_apply2_fwd_kernel";
     }
     char buf[96];
     snprintf(buf, sizeof buf, "damp_conv_%s_%s_kernel<%d", backward ? "bwd" : "fwd",

@@ -59,6 +59,7 @@ struct DevArray {
 
 constexpr int kLongTableRow = 64;   // backward: table rows with more tuples are reduced by a whole wavefront
 constexpr int kLongTableCol = 256;  // forward: output columns with more tuples are summed by a whole wavefront
+constexpr int kByJMax = 16;         // tables whose second operand has at most this many symbols get dense per-j maps
 
 // A tuple of the function table packed for the kernels: low 16 bits = first index, high 16 = second.
 __host__ __device__ static inline uint32_t pack16(uint32_t lo, uint32_t hi) { return lo | (hi << 16); }
@@ -93,6 +94,16 @@ struct dol_fn_table {
     bool lds_fwd_ok = false, lds_bwd_ok = false;
     size_t lds_fwd_bytes = 0, lds_bwd_bytes = 0;
     dol::DevArray<uint32_t> lds_pk, lds_pk_ptr, lds_pka, lds_pka_ptr, lds_pkb, lds_pkb_ptr;
+    // Tables with a short second operand (nb <= dol::kByJMax) that take neither path above: dense maps walked one j
+    // at a time, so that lane-adjacent elements read the operand through one map each (adjacent addresses for
+    // monotone functions).  byj_src[j * n_out + c] = the i with f(i, j) = column c, or -1; a long column
+    // has -2 at j = 0 and is listed in byj_wave_cols (summed by a wavefront); a short column where some j occurs
+    // twice has -3 there and is summed from its tuple list.
+    // byj_col[j * na + i] = column of (i, j) or -1.
+    bool byj_ok = false;
+    bool byj_fwd = false;              // forward uses the map only where it is at least half full (else the tuple lists)
+    dol::DevArray<int32_t> byj_src, byj_col;
+    dol::DevArray<uint32_t> byj_wave_cols;
     int device = 0;
 };
 

@@ -734,7 +734,8 @@ def test_dtkp_general_conjunction_union_filter(dol):
     np.testing.assert_array_equal(host(fo.prob), fpr)
 
 
-@pytest.mark.parametrize("which", ["chain", "fold", "hashed", "hashed-fused", "dtkp-fold", "reach-fused"])
+@pytest.mark.parametrize("which", ["chain", "fold", "hashed", "hashed-fused", "dtkp-fold", "reach-fused", "product",
+                                   "formula-damp", "formula-dtkp"])
 def test_hip_graph_replay_matches_eager(gp, which):
     """Every entry point issues only asynchronous launches once its symbol-side plans exist, so a whole step can be
     captured; replays (with eager work and synchronisations between them) equal the eager result."""
@@ -748,6 +749,12 @@ def test_hip_graph_replay_matches_eager(gp, which):
         prog = gp.HashedPipelineFused(W.config3(batch=320, seed=5)); key = lambda: prog.ga
     elif which == "dtkp-fold":
         prog = gp.DtkpSumChainFused(W.config4(batch=200, seed=5), with_gradient=True); key = lambda: prog.grad_fact
+    elif which == "product":
+        prog = gp.ProductChain(W.product_workload(batch=40, n_digits=7, seed=5)); key = lambda: prog.grad_p
+    elif which == "formula-damp":
+        prog = gp.HwfPipeline(W.hwf_workload(batch=24, length=5, seed=5), "damp"); key = lambda: prog.grad_p
+    elif which == "formula-dtkp":
+        prog = gp.HwfPipeline(W.hwf_workload(batch=24, length=5, seed=5), "dtkp"); key = lambda: prog.grad_p
     else:
         prog = gp.GridReachFused(W.config5(batch=16, side=8, rounds=12, seed=5)); key = lambda: prog.grad_p
     prog.step()
@@ -1066,3 +1073,70 @@ def test_formula_pipeline_dtkp(gp, batch, length, k):
     assert_close(host(prog.out.prob), ref["prob"], "formula value probabilities")
     assert_close(host(prog.gfact), ref["gfact"], "formula fact gradient")
     assert_close(host(prog.grad_p), ref["grad_p"], "formula class gradient")
+
+
+def test_apply_k_long_columns(dol):
+    """Columns of hundreds to thousands of tuples (summed by a wavefront): a unary map onto one symbol whose sum lies
+    within rounding of 1, where the clamp decision must still be the sequential float sum's, and a three-operand
+    function with two images."""
+    B, n = 40, 3000
+    x = W.uniform01(91, B * n).astype(np.float32).reshape(B, n)
+    x = (x / x.sum(1, keepdims=True, dtype=np.float64)).astype(np.float32)
+    x[::3] *= np.float32(1.0 + 2e-7)
+    idx, to = oracle.dense_to_tuples(np.zeros(n, np.int32))
+    syms, want, pre32, pre64 = oracle.damp_applyk_fwd(idx, to, [x], want_pre=True)
+    assert (pre32 > 1).any() and (pre32 <= 1).any() and np.abs(pre64 - 1).max() < 1e-5
+    (wg,) = oracle.damp_applyk_bwd(idx, to, [x], np.ones((B, 1), np.float32))
+    f = dol.FnkTable.create_dense(np.zeros(n, np.int32))
+    d = dol.Dist(np.arange(n), dev(x))
+    out = dol.Dist.empty(f.out_syms, B)
+    dol.apply_k([d], f, None, out)
+    assert_close(host(out.prob), want, "long unary column")
+    gx = torch.empty((B, n), device="cuda")
+    dol.apply_k_backward([d], f, out, torch.ones((B, 1), device="cuda"), [gx])
+    np.testing.assert_array_equal(host(gx), wg)
+    # three operands, two images: columns of about 500 tuples, one side of them over 1
+    shape = (40, 5, 5)
+    table = _rand_table(95, shape, 2)
+    ins = [(W.softmax_rows(W.normal(96 + l, B * m).reshape(B, m)) * (1.3 if l == 0 else 1.0)).astype(np.float32)
+           for l, m in enumerate(shape)]
+    idx, to = oracle.dense_to_tuples(table)
+    syms, want, pre32, _ = oracle.damp_applyk_fwd(idx, to, ins, want_pre=True)
+    g = np.abs(W.normal(99, B * 2)).astype(np.float32).reshape(B, 2)
+    wants = oracle.damp_applyk_bwd(idx, to, ins, g)
+    f3 = dol.FnkTable.create_dense(table)
+    d3 = [dol.Dist(np.arange(m), dev(v)) for m, v in zip(shape, ins)]
+    out3 = dol.Dist.empty(f3.out_syms, B)
+    dol.apply_k(d3, f3, None, out3)
+    assert_close(host(out3.prob), want, "long three-operand columns")
+    grads = [torch.empty((B, m), device="cuda") for m in shape]
+    dol.apply_k_backward(d3, f3, out3, dev(g), grads)
+    for l in range(3):
+        assert_close(host(grads[l]), wants[l], "long three-operand grad %d" % l)
+
+
+def test_short_second_operand_tables_near_the_clamp(dol):
+    """f(i, j) = i + 2j over 800 x 4 symbols: columns of four tuples whose defining order (ascending i) is the
+    reverse of the order the per-j kernel adds them in, with sums within rounding of 1; clamp decisions (seen
+    through backward) must be those of the defining order."""
+    B, na, nb = 96, 800, 4
+    table = (np.arange(na)[:, None] + 2 * np.arange(nb)[None, :]).astype(np.int32)
+    a = np.ones((B, na), np.float32)
+    b = W.softmax_rows(W.normal(71, B * nb).reshape(B, nb))
+    b[::4] *= np.float32(1.0 + 1.2e-7)
+    tri = oracle.dense_to_triples(table)
+    syms, want, pre32, pre64 = oracle.damp_apply2_fwd(tri, na, nb, a, b, want_pre=True)
+    inner = pre32[:, 6:na]
+    assert (inner > 1).any() and (inner <= 1).any() and np.abs(pre64[:, 6:na] - 1).max() < 1e-6
+    g = np.abs(W.normal(72, B * syms.size)).astype(np.float32).reshape(B, -1)
+    wa, wb = oracle.damp_apply2_bwd(tri, na, nb, a, b, g)
+    f = dol.FnTable.create_dense(table)
+    assert f.kernel_fwd == "damp_byj_fwd_kernel" and f.kernel_bwd == "damp_byj_bwd_kernel"
+    da, db = dol.Dist(np.arange(na), dev(a)), dol.Dist(np.arange(nb), dev(b))
+    out = dol.Dist.empty(f.out_syms, B)
+    dol.apply2(da, db, f, None, out)
+    assert_close(host(out.prob), want, "per-j forward")
+    ga, gb = torch.empty((B, na), device="cuda"), torch.empty((B, nb), device="cuda")
+    dol.backward(dol.OpRecord(dol.OP_APPLY2, da, db, out, f=f), dev(g), ga, gb)
+    assert_close(host(ga), wa, "per-j grad a")
+    assert_close(host(gb), wb, "per-j grad b")
