@@ -29,6 +29,7 @@ struct dol_fnk_table {
     dol::DevArray<uint32_t> row_ptr;     // [sum n_sym + 1]
     dol::DevArray<uint32_t> row_tup;     // [n_tuples*K] grouped-tuple numbers of each operand row, ascending
     dol::DevArray<uint32_t> long_cols;   // columns with more than dol::kLongTableCol tuples
+    dol::DevArray<uint32_t> dtkp_long_cols;   // ... more than dol::kLongDtkpCol
     int device = 0;
 };
 
@@ -270,7 +271,7 @@ dtkp_applyk_kernel(int64_t total, int32_t S, int32_t arity, KProofs in, const ui
     const int32_t c = static_cast<int32_t>(idx - s * S);
     const float *fp = fact_prob + s * n_facts;
     const uint32_t q0 = col_ptr[c], q1 = col_ptr[c + 1];
-    if (q1 - q0 > static_cast<uint32_t>(kLongTableCol)) return;            // left to the wavefront-per-column kernel
+    if (q1 - q0 > static_cast<uint32_t>(kLongDtkpCol)) return;             // left to the wavefront-per-column kernel
     TopK<KP> top;
     top.clear();
     for (uint32_t q = q0; q < q1; ++q) {
@@ -323,10 +324,10 @@ static void launch_dtkp_k(int64_t total, const dol_fnk_table *f, const KProofs &
     hipLaunchKernelGGL(dtkp_applyk_kernel<KP>, dim3(static_cast<unsigned>((total + kThreadsP - 1) / kThreadsP)),
                        dim3(kThreadsP), 0, st, total, f->n_out, f->K, in, f->col_ptr.ptr, f->tup.ptr, gm, n_facts,
                        fact_prob, om, op, oprob, ldo);
-    const int64_t n_long = static_cast<int64_t>(f->long_cols.n);
+    const int64_t n_long = static_cast<int64_t>(f->dtkp_long_cols.n);
     if (n_long > 0)
         hipLaunchKernelGGL(dtkp_applyk_long_kernel<KP>, dim3(static_cast<unsigned>(total / f->n_out * n_long)), dim3(kWave),
-                           0, st, static_cast<int32_t>(n_long), f->long_cols.ptr, f->n_out, f->K, in, f->col_ptr.ptr,
+                           0, st, static_cast<int32_t>(n_long), f->dtkp_long_cols.ptr, f->n_out, f->K, in, f->col_ptr.ptr,
                            f->tup.ptr, gm, n_facts, fact_prob, om, op, oprob, ldo);
 }
 
@@ -398,12 +399,15 @@ static dol_status build_k(int32_t K, const int32_t *n_sym, int64_t n, const int3
             for (int l = 0; l < K; ++l) row_tup[fill[tb->row_base[l] + tup[t * K + l]]++] = static_cast<uint32_t>(t);
     }
 
-    std::vector<uint32_t> long_cols;
-    for (int32_t c = 0; c < S; ++c)
+    std::vector<uint32_t> long_cols, dtkp_long_cols;
+    for (int32_t c = 0; c < S; ++c) {
         if (col_ptr[c + 1] - col_ptr[c] > static_cast<uint32_t>(kLongTableCol)) long_cols.push_back(static_cast<uint32_t>(c));
+        if (col_ptr[c + 1] - col_ptr[c] > static_cast<uint32_t>(kLongDtkpCol)) dtkp_long_cols.push_back(static_cast<uint32_t>(c));
+    }
 
     DOL_HIP(hipGetDevice(&tb->device));
     DOL_HIP(tb->long_cols.upload(long_cols));
+    DOL_HIP(tb->dtkp_long_cols.upload(dtkp_long_cols));
     DOL_HIP(tb->col_ptr.upload(col_ptr));
     DOL_HIP(tb->tup.upload(tup));
     DOL_HIP(tb->tup_col.upload(tup_col));
@@ -469,7 +473,7 @@ dol_status dol_apply_k(int32_t K, const dol_dist *const *in, const dol_fnk_table
             if (out->sym_ids[c] != f->out_syms[c]) return fail(DOL_EINVAL, "out.sym_ids[%d] = %d, the table produces %d there", c, out->sym_ids[c], f->out_syms[c]);
     if (dol_status st = check_work(batch, f->n_out)) return st;
     if (batch == 0 || f->n_out == 0) return DOL_OK;
-    if (static_cast<int64_t>(batch) * static_cast<int64_t>(f->long_cols.n) > 0x7fffffffLL)
+    if (static_cast<int64_t>(batch) * static_cast<int64_t>(std::max(f->long_cols.n, f->dtkp_long_cols.n)) > 0x7fffffffLL)
         return fail(DOL_EUNSUPPORTED, "batch x long table columns exceeds 2^31");
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     if (!dtkp) {

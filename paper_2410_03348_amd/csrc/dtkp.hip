@@ -96,7 +96,7 @@ dtkp_apply2_kernel(int64_t total, int32_t S, int32_t na, int32_t nb, int32_t n_f
     const float *fp = fact_prob + s * n_facts;
     const int64_t a0 = s * na * K, b0 = s * nb * K;
     const uint32_t q0 = col_ptr[c], q1 = col_ptr[c + 1];
-    if (q1 - q0 > static_cast<uint32_t>(kLongTableCol)) return;          // left to the wavefront-per-column kernel
+    if (q1 - q0 > static_cast<uint32_t>(kLongDtkpCol)) return;           // left to the wavefront-per-column kernel
     TopK<K> top;
     top.clear();
     for (uint32_t q = q0; q < q1; ++q) offer_tuple<K>(top, col_ij[q], a0, b0, gm, fp, am, ap, bm, bp);
@@ -151,10 +151,10 @@ static void launch_apply2_k(int64_t total, const dol_fn_table *f, int32_t n_fact
 {
     hipLaunchKernelGGL(dtkp_apply2_kernel<K>, dim3(grid_t(total)), dim3(kThreadsT), 0, st, total, f->n_out, f->na,
                        f->nb, n_facts, f->col_ptr.ptr, f->col_ij.ptr, gm, fact_prob, am, ap, bm, bp, om, op, oprob, ldo);
-    const int64_t n_long = static_cast<int64_t>(f->long_cols.n);
+    const int64_t n_long = static_cast<int64_t>(f->dtkp_long_cols.n);
     if (n_long > 0)
         hipLaunchKernelGGL(dtkp_apply2_long_kernel<K>, dim3(static_cast<unsigned>(total / f->n_out * n_long)), dim3(kWave),
-                           0, st, static_cast<int32_t>(n_long), f->long_cols.ptr, f->n_out, f->na, f->nb, n_facts,
+                           0, st, static_cast<int32_t>(n_long), f->dtkp_long_cols.ptr, f->n_out, f->na, f->nb, n_facts,
                            f->col_ptr.ptr, f->col_ij.ptr, gm, fact_prob, am, ap, bm, bp, om, op, oprob, ldo);
 }
 
@@ -177,7 +177,7 @@ dol_status launch_dtkp_apply2(const dol_fn_table *f, int32_t batch, int32_t k, i
 {
     const int64_t total = static_cast<int64_t>(batch) * f->n_out;
     if (total == 0) return DOL_OK;
-    if (static_cast<int64_t>(batch) * static_cast<int64_t>(f->long_cols.n) > 0x7fffffffLL)
+    if (static_cast<int64_t>(batch) * static_cast<int64_t>(f->dtkp_long_cols.n) > 0x7fffffffLL)
         return fail(DOL_EUNSUPPORTED, "batch x long table columns exceeds 2^31");
 #define CALL(KK) launch_apply2_k<KK>(total, f, n_facts, gm, fact_prob, am, ap, bm, bp, om, op, oprob, ldo, st)
     DOL_DISPATCH_K(k, CALL)

@@ -58,7 +58,8 @@ struct DevArray {
 // ---------------------------------------------------------------- symbol-side plans
 
 constexpr int kLongTableRow = 64;   // backward: table rows with more tuples are reduced by a whole wavefront
-constexpr int kLongTableCol = 256;  // forward: output columns with more tuples are summed by a whole wavefront
+constexpr int kLongTableCol = 64;   // forward: output columns with more tuples are summed by a whole wavefront
+constexpr int kLongDtkpCol = 16;    // the same under DTKP, where a tuple costs a few hundred instructions
 constexpr int kByJMax = 16;         // tables whose second operand has at most this many symbols get dense per-j maps
 
 // A tuple of the function table packed for the kernels: low 16 bits = first index, high 16 = second.
@@ -87,8 +88,8 @@ struct dol_fn_table {
     dol::DevArray<uint32_t> rowb_ptr, rowb_ic;
     // rows with more than dol::kLongTableRow tuples (x < na: row x of a, else row x - na of b)
     dol::DevArray<uint32_t> long_rows;
-    // output columns with more than dol::kLongTableCol tuples
-    dol::DevArray<uint32_t> long_cols;
+    // output columns with more than dol::kLongTableCol / dol::kLongDtkpCol tuples
+    dol::DevArray<uint32_t> long_cols, dtkp_long_cols;
     // LDS gather kernels (damp_lds.hip): per output column (forward), row of a, row of b (backward) a list of
     // 16-byte packets of four tuples; *_ptr[x] .. *_ptr[x+1] are the packets of x
     bool lds_fwd_ok = false, lds_bwd_ok = false;

@@ -119,14 +119,17 @@ static dol_status build_table(int32_t na, int32_t nb, std::vector<Tuple> &tup, d
     for (int32_t j = 0; j < nb; ++j)
         if (rowb_ptr[j + 1] - rowb_ptr[j] > static_cast<uint32_t>(kLongTableRow)) long_rows.push_back(static_cast<uint32_t>(na + j));
 
-    std::vector<uint32_t> long_cols;
-    for (int32_t c = 0; c < S; ++c)
+    std::vector<uint32_t> long_cols, dtkp_long_cols;
+    for (int32_t c = 0; c < S; ++c) {
         if (col_ptr[c + 1] - col_ptr[c] > static_cast<uint32_t>(kLongTableCol)) long_cols.push_back(static_cast<uint32_t>(c));
+        if (col_ptr[c + 1] - col_ptr[c] > static_cast<uint32_t>(kLongDtkpCol)) dtkp_long_cols.push_back(static_cast<uint32_t>(c));
+    }
 
     if (hipGetDevice(&tb->device) != hipSuccess) tb->device = 0;
     hipError_t e;
     if ((e = tb->long_rows.upload(long_rows)) != hipSuccess) return hip_fail(e, "uploading the function table");
-    if ((e = tb->long_cols.upload(long_cols)) != hipSuccess) return hip_fail(e, "uploading the function table");
+    if ((e = tb->long_cols.upload(long_cols)) != hipSuccess || (e = tb->dtkp_long_cols.upload(dtkp_long_cols)) != hipSuccess)
+        return hip_fail(e, "uploading the function table");
     if ((e = tb->col_ptr.upload(col_ptr)) != hipSuccess || (e = tb->col_ij.upload(col_ij)) != hipSuccess ||
         (e = tb->rowa_ptr.upload(rowa_ptr)) != hipSuccess || (e = tb->rowa_jc.upload(rowa_jc)) != hipSuccess ||
         (e = tb->rowb_ptr.upload(rowb_ptr)) != hipSuccess || (e = tb->rowb_ic.upload(rowb_ic)) != hipSuccess)
