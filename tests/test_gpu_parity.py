@@ -1140,3 +1140,97 @@ def test_short_second_operand_tables_near_the_clamp(dol):
     dol.backward(dol.OpRecord(dol.OP_APPLY2, da, db, out, f=f), dev(g), ga, gb)
     assert_close(host(ga), wa, "per-j grad a")
     assert_close(host(gb), wb, "per-j grad b")
+
+
+# ---------------------------------------------------------------- seeded random tables over every kernel choice
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_tables_differential(dol, seed):
+    """Random table shapes, densities, image counts, batch sizes and paddings (drawn from a seeded stream), so that
+    every kernel the library can pick for dol_apply2 / dol_backward (LDS gather, per-j maps with and without the
+    workgroup-per-sample backward, tuple lists, wavefront columns and rows) meets the oracle on shapes nobody chose
+    by hand.  One-signed upstream gradient (see the module docstring)."""
+    r = W.splitmix64(5000 + seed, np.arange(16)).astype(np.uint64)
+    pick = lambda k, lo, hi: int(lo + r[k] % np.uint64(hi - lo + 1))
+    na = [pick(0, 1, 40), pick(0, 100, 700), pick(0, 1025, 3000)][seed % 3]
+    nb = [pick(1, 1, 16), pick(1, 17, 60), pick(1, 1, 4)][(seed // 3) % 3]
+    n_ids = max(1, [pick(2, 1, 8), pick(2, na // 2 + 1, na + nb), pick(2, 2 * na, 3 * na)][(seed // 9) % 3])
+    batch = pick(3, 1, 70)
+    table = (W.splitmix64(6000 + seed, np.arange(na * nb)) % np.uint64(n_ids)).astype(np.int32).reshape(na, nb)
+    drop = pick(4, 0, 3)
+    if drop:
+        table.reshape(-1)[::drop + 1] = -1
+    scale = [1.0, 1.0, float(max(1.0, 0.7 * n_ids))][pick(5, 0, 2)]
+    a = (W.softmax_rows(W.normal(7000 + seed, batch * na).reshape(batch, na)) * scale).astype(np.float32)
+    b = W.softmax_rows(W.normal(8000 + seed, batch * nb).reshape(batch, nb))
+    tri = oracle.dense_to_triples(table)
+    syms, want, pre32, _ = oracle.damp_apply2_fwd(tri, na, nb, a, b, want_pre=True)
+    g = np.abs(W.normal(9000 + seed, batch * max(syms.size, 1))).astype(np.float32).reshape(batch, -1)[:, :syms.size]
+    g = np.ascontiguousarray(g)
+    wa, wb = oracle.damp_apply2_bwd(tri, na, nb, a, b, g)
+    f = dol.FnTable.create_dense(table)
+    np.testing.assert_array_equal(f.out_syms, syms)
+    pad = pick(6, 0, 5)
+    abuf = torch.zeros((batch, na + pad), device="cuda")
+    abuf[:, :na] = dev(a)
+    da, db = dol.Dist(np.arange(na), abuf[:, :na]), dol.Dist(np.arange(nb), dev(b))
+    out = dol.Dist.empty(f.out_syms, batch)
+    dol.apply2(da, db, f, None, out)
+    what = "seed %d: %d x %d -> %d, batch %d, %s / %s" % (seed, na, nb, syms.size, batch, f.kernel_fwd, f.kernel_bwd)
+    assert_close(host(out.prob), want, what + " forward")
+    ga = torch.full((batch, na + pad), 3.0, device="cuda")
+    gb = torch.empty((batch, nb), device="cuda")
+    dol.backward(dol.OpRecord(dol.OP_APPLY2, da, db, out, f=f), dev(g), ga, gb)
+    assert_close(host(ga)[:, :na], wa, what + " grad a")
+    assert np.all(host(ga)[:, na:] == 3.0)
+    assert_close(host(gb), wb, what + " grad b")
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_random_tables_differential_dtkp(dol, seed):
+    """The same under DTKP-AM: multi-proof operands (results of earlier applies over shared exclusion groups), few
+    images so that columns run from a handful to hundreds of tuples (thread and wavefront kernels), k from 1 to 5;
+    also the K-operand call on the same table."""
+    r = W.splitmix64(5100 + seed, np.arange(8)).astype(np.uint64)
+    k = [1, 2, 3, 5][seed % 4]
+    B, nv = int(3 + r[0] % np.uint64(40)), 6
+    fp = np.concatenate([W.softmax_rows(W.normal(5200 + seed * 4 + t, B * nv).reshape(B, nv)) for t in range(4)], axis=1)
+    grp = np.repeat(np.arange(4), nv).astype(np.int32)
+    prov = dol.Prov(dol.DTKP, k, dev(fp), grp)
+    o_ops, g_ops = [], []
+    for side in range(2):
+        n_mid = int(8 + r[1 + side] % np.uint64(25))
+        tab = (W.splitmix64(5300 + seed * 2 + side, np.arange(nv * nv)) % np.uint64(n_mid)).astype(np.int32).reshape(nv, nv)
+        m0 = oracle.dtkp_init(np.arange(nv) + nv * (2 * side), fp, k)[0]
+        m1 = oracle.dtkp_init(np.arange(nv) + nv * (2 * side + 1), fp, k)[0]
+        s, m, p, _ = oracle.dtkp_apply2(oracle.dense_to_triples(tab), nv, nv, k, grp, fp, m0, m1)
+        d0, d1 = dol.Dist.empty(np.arange(nv), B, k=k), dol.Dist.empty(np.arange(nv), B, k=k)
+        dol.dtkp_init(d0, np.arange(nv) + nv * (2 * side), prov)
+        dol.dtkp_init(d1, np.arange(nv) + nv * (2 * side + 1), prov)
+        ft = dol.FnTable.create_dense(tab)
+        d = dol.Dist.empty(ft.out_syms, B, k=k)
+        dol.apply2(d0, d1, ft, prov, d)
+        o_ops.append((s, m)); g_ops.append(d)
+    na, nb = o_ops[0][0].size, o_ops[1][0].size
+    n_ids = int(1 + r[3] % np.uint64(6))
+    table = (W.splitmix64(5400 + seed, np.arange(na * nb)) % np.uint64(n_ids)).astype(np.int32).reshape(na, nb)
+    table.reshape(-1)[::7] = -1
+    tri = oracle.dense_to_triples(table)
+    syms, om, op, opr = oracle.dtkp_apply2(tri, na, nb, k, grp, fp, o_ops[0][1], o_ops[1][1])
+    f = dol.FnTable.create_dense(table)
+    out = dol.Dist.empty(f.out_syms, B, k=k)
+    dol.apply2(g_ops[0], g_ops[1], f, prov, out)
+    np.testing.assert_array_equal(out.sym_ids, syms)
+    np.testing.assert_array_equal(host(out.proof_mask).view(np.uint64), om)
+    np.testing.assert_array_equal(host(out.proof_prob), op)
+    assert_close(host(out.prob), opr, "dtkp random table, seed %d" % seed)
+    fk = dol.FnkTable.create_dense(table)
+    outk = dol.Dist.empty(fk.out_syms, B, k=k)
+    dol.apply_k(g_ops, fk, prov, outk)
+    np.testing.assert_array_equal(host(outk.proof_mask).view(np.uint64), om)
+    np.testing.assert_array_equal(host(outk.proof_prob), op)
+    gsym = W.normal(5500 + seed, B * syms.size).astype(np.float32).reshape(B, -1)
+    want = oracle.dtkp_prob_bwd(om, fp, gsym)
+    gf = torch.empty((B, fp.shape[1]), device="cuda")
+    dol.dtkp_backward(out, prov, dev(gsym), gf)
+    assert_close(host(gf), want, "dtkp random table gradient, seed %d" % seed)
