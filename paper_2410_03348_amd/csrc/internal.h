@@ -61,6 +61,8 @@ constexpr int kLongTableRow = 64;   // backward: table rows with more tuples are
 constexpr int kLongTableCol = 64;   // forward: output columns with more tuples are summed by a whole wavefront
 constexpr int kLongDtkpCol = 16;    // the same under DTKP, where a tuple costs a few hundred instructions
 constexpr int kByJMax = 16;         // tables whose second operand has at most this many symbols get dense per-j maps
+constexpr int kByJMaxNa = 65000;    // ... and whose first operand leaves room for the three marks below
+constexpr uint16_t kByJNone = 0xFFFF, kByJWave = 0xFFFE, kByJList = 0xFFFD;
 
 // A tuple of the function table packed for the kernels: low 16 bits = first index, high 16 = second.
 __host__ __device__ static inline uint32_t pack16(uint32_t lo, uint32_t hi) { return lo | (hi << 16); }
@@ -95,15 +97,15 @@ struct dol_fn_table {
     bool lds_fwd_ok = false, lds_bwd_ok = false;
     size_t lds_fwd_bytes = 0, lds_bwd_bytes = 0;
     dol::DevArray<uint32_t> lds_pk, lds_pk_ptr, lds_pka, lds_pka_ptr, lds_pkb, lds_pkb_ptr;
-    // Tables with a short second operand (nb <= dol::kByJMax) that take neither path above: dense maps walked one j
-    // at a time, so that lane-adjacent elements read the operand through one map each (adjacent addresses for
-    // monotone functions).  byj_src[j * n_out + c] = the i with f(i, j) = column c, or -1; a long column
-    // has -2 at j = 0 and is listed in byj_wave_cols (summed by a wavefront); a short column where some j occurs
-    // twice has -3 there and is summed from its tuple list.
-    // byj_col[j * na + i] = column of (i, j) or -1.
+    // Tables with a short second operand (nb <= dol::kByJMax, na <= dol::kByJMaxNa) that take neither path above:
+    // dense 16-bit maps walked one j at a time, so that lane-adjacent elements read the operand through one map each
+    // (adjacent addresses for monotone functions).  byj_src[j * n_out + c] = the i with f(i, j) = column c, or
+    // dol::kByJNone; a long column has dol::kByJWave at j = 0 and is listed in byj_wave_cols (summed by a wavefront); a
+    // short column where some j occurs twice has dol::kByJList there and is summed from its tuple list.
+    // byj_col[j * na + i] = column of (i, j) or dol::kByJNone.
     bool byj_ok = false;
     bool byj_fwd = false;              // forward uses the map only where it is at least half full (else the tuple lists)
-    dol::DevArray<int32_t> byj_src, byj_col;
+    dol::DevArray<uint16_t> byj_src, byj_col;
     dol::DevArray<uint32_t> byj_wave_cols;
     int device = 0;
 };

@@ -136,24 +136,25 @@ static dol_status build_table(int32_t na, int32_t nb, std::vector<Tuple> &tup, d
         return hip_fail(e, "uploading the function table");
     if (!conv_path_ok(tb.get()))
         if (dol_status s2 = lds_plan_build(tb.get(), col_ptr, col_ij, rowa_ptr, rowa_jc, rowb_ptr, rowb_ic)) return s2;
-    if (!conv_path_ok(tb.get()) && !tb->lds_fwd_ok && !tb->lds_bwd_ok && nb >= 1 && nb <= kByJMax && na >= 1 && S >= 1) {
-        std::vector<int32_t> src(static_cast<size_t>(nb) * S, -1), colof(static_cast<size_t>(nb) * na, -1);
+    if (!conv_path_ok(tb.get()) && !tb->lds_fwd_ok && !tb->lds_bwd_ok && nb >= 1 && nb <= kByJMax && na >= 1 &&
+        na <= kByJMaxNa && S >= 1 && S <= kByJMaxNa) {
+        std::vector<uint16_t> src(static_cast<size_t>(nb) * S, kByJNone), colof(static_cast<size_t>(nb) * na, kByJNone);
         std::vector<uint32_t> wave_cols;
         for (int32_t c = 0; c < S; ++c) {
             bool regular = col_ptr[c + 1] - col_ptr[c] <= static_cast<uint32_t>(kLongTableCol);
             for (uint32_t q = col_ptr[c]; q < col_ptr[c + 1] && regular; ++q) {
-                int32_t &slot = src[static_cast<size_t>(col_ij[q] >> 16) * S + c];
-                if (slot != -1) regular = false;
-                slot = static_cast<int32_t>(col_ij[q] & 0xffffu);
+                uint16_t &slot = src[static_cast<size_t>(col_ij[q] >> 16) * S + c];
+                if (slot != kByJNone) regular = false;
+                slot = static_cast<uint16_t>(col_ij[q] & 0xffffu);
             }
             if (!regular) {
                 const bool is_long = col_ptr[c + 1] - col_ptr[c] > static_cast<uint32_t>(kLongTableCol);
-                for (int32_t j = 0; j < nb; ++j) src[static_cast<size_t>(j) * S + c] = -1;
-                src[c] = is_long ? -2 : -3;
+                for (int32_t j = 0; j < nb; ++j) src[static_cast<size_t>(j) * S + c] = kByJNone;
+                src[c] = is_long ? kByJWave : kByJList;
                 if (is_long) wave_cols.push_back(static_cast<uint32_t>(c));
             }
         }
-        for (size_t t = 0; t < tup.size(); ++t) colof[static_cast<size_t>(tup[t].j) * na + tup[t].i] = static_cast<int32_t>(col[t]);
+        for (size_t t = 0; t < tup.size(); ++t) colof[static_cast<size_t>(tup[t].j) * na + tup[t].i] = static_cast<uint16_t>(col[t]);
         if ((e = tb->byj_src.upload(src)) != hipSuccess || (e = tb->byj_col.upload(colof)) != hipSuccess ||
             (e = tb->byj_wave_cols.upload(wave_cols)) != hipSuccess)
             return hip_fail(e, "uploading the function table");
