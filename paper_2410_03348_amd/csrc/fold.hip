@@ -12,6 +12,8 @@
 // one fma per tuple; gradients are gated by [pre <= 1], re-derived only for stages in which some lane saw
 // pre > 1 during the forward sweep.
 #include "internal.h"
+
+#include <type_traits>
 #include "wave_util.h"
 
 #include <cfloat>
@@ -260,6 +262,62 @@ damp_fold4_kernel(const FoldArgs A)
         }
     };
 
+    // The same for H = 1 or 2 columns per lane (stages of at most TC or 2 * TC columns): 4- or 8-byte LDS loads of
+    // the H + NBP - 1 values a lane needs; the order of every column's sum is unchanged.
+    auto columns_few = [&](auto hc, const float *row, int c0, const float (&bj)[NBR], float *pre) {
+        constexpr int H = decltype(hc)::value;
+        constexpr int FR = H == 2 ? (NBP & ~1) + ((NBP - 1) > (NBP & ~1) ? 2 : 0) : NBP - 1;   // even and >= NBP - 1 for H = 2
+        constexpr int NV = FR + H;
+        float w[NV + (NV & 1)];
+        if (H == 2) {
+#pragma unroll
+            for (int p = 0; p < (NV + 1) / 2; ++p) {
+                const float2 x = *reinterpret_cast<const float2 *>(row + c0 - FR + 2 * p);
+                w[2 * p] = x.x, w[2 * p + 1] = x.y;
+            }
+        } else {
+#pragma unroll
+            for (int p = 0; p < NV; ++p) w[p] = row[c0 - FR + p];
+        }
+#pragma unroll
+        for (int k = 0; k < H; ++k) {
+            float acc = 0.0f;
+#pragma unroll
+            for (int j = NBP - 1; j >= 0; --j) acc = __builtin_fmaf(w[FR + k - j], bj[j], acc);
+            pre[k] = acc;
+        }
+    };
+    // Backward of a stage for rows i0 .. i0 + H - 1 of the first operand: their gradients (returned in o) and the
+    // lane's shares of the short operand's gradient (added to pj).
+    auto rows_few = [&](auto hc, const float *g_row, const float *row_a, int i0, int m, const float (&bj)[NBR],
+                        float (&pj)[NBP], float *o) {
+        constexpr int H = decltype(hc)::value;
+        constexpr int NV = H + NBP - 1;
+        float gw[NV + (NV & 1)], ak[H];
+        if (H == 2) {
+#pragma unroll
+            for (int p = 0; p < (NV + 1) / 2; ++p) {
+                const float2 x = *reinterpret_cast<const float2 *>(g_row + i0 + 2 * p);
+                gw[2 * p] = x.x, gw[2 * p + 1] = x.y;
+            }
+            const float2 av = *reinterpret_cast<const float2 *>(row_a + i0);
+            ak[0] = av.x, ak[H - 1] = av.y;
+        } else {
+#pragma unroll
+            for (int p = 0; p < NV; ++p) gw[p] = g_row[i0 + p];
+            ak[0] = row_a[i0];
+        }
+#pragma unroll
+        for (int k = 0; k < H; ++k) {
+            float acc = 0.0f;
+#pragma unroll
+            for (int j = 0; j < NBP; ++j) acc = __builtin_fmaf(gw[k + j], bj[j], acc);
+            o[k] = i0 + k < m ? acc : 0.0f;
+#pragma unroll
+            for (int j = 0; j < NBP; ++j) pj[j] = __builtin_fmaf(gw[k + j], ak[k], pj[j]);
+        }
+    };
+
     // ---- forward sweep (columns past the last one come out as exact zeros: they only meet zero padding)
     unsigned over = 0;                              // bit t: this lane saw pre > 1 in stage t
     for (int t = 1; t < A.n; ++t) {
@@ -269,12 +327,28 @@ damp_fold4_kernel(const FoldArgs A)
         load_b(t, bj);
         const int S = stage(m_l, t);
         float worst = 0.0f;
-        for (int c0 = 4 * tc; c0 < S; c0 += kStep) {
-            float pre[4];
-            columns(row, c0, bj, pre);
-            worst = fmaxf(worst, fmaxf(fmaxf(pre[0], pre[1]), fmaxf(pre[2], pre[3])));
-            *reinterpret_cast<float4 *>(dst + c0) =
-                make_float4(fminf(pre[0], 1.0f), fminf(pre[1], 1.0f), fminf(pre[2], 1.0f), fminf(pre[3], 1.0f));
+        if (S <= TC) {                              // narrow stages: one or two columns per lane keep all lanes busy
+            if (tc < S) {
+                float pre[1];
+                columns_few(std::integral_constant<int, 1>{}, row, tc, bj, pre);
+                worst = pre[0];
+                dst[tc] = fminf(pre[0], 1.0f);
+            }
+        } else if (S <= 2 * TC) {
+            if (2 * tc < S) {
+                float pre[2];
+                columns_few(std::integral_constant<int, 2>{}, row, 2 * tc, bj, pre);
+                worst = fmaxf(pre[0], pre[1]);
+                *reinterpret_cast<float2 *>(dst + 2 * tc) = make_float2(fminf(pre[0], 1.0f), fminf(pre[1], 1.0f));
+            }
+        } else {
+            for (int c0 = 4 * tc; c0 < S; c0 += kStep) {
+                float pre[4];
+                columns(row, c0, bj, pre);
+                worst = fmaxf(worst, fmaxf(fmaxf(pre[0], pre[1]), fmaxf(pre[2], pre[3])));
+                *reinterpret_cast<float4 *>(dst + c0) =
+                    make_float4(fminf(pre[0], 1.0f), fminf(pre[1], 1.0f), fminf(pre[2], 1.0f), fminf(pre[3], 1.0f));
+            }
         }
         if (worst > 1.0f) over |= 1u << t;
         wave_lds_fence();
@@ -341,6 +415,19 @@ damp_fold4_kernel(const FoldArgs A)
         float pj[NBP];
 #pragma unroll
         for (int j = 0; j < NBP; ++j) pj[j] = 0.0f;
+        if (m <= TC) {
+            if (tc < m) {
+                float o[1];
+                rows_few(std::integral_constant<int, 1>{}, g_cur, row_a, tc, m, bj, pj, o);
+                g_nxt[tc] = o[0];
+            }
+        } else if (m <= 2 * TC) {
+            if (2 * tc < m) {
+                float o[2];
+                rows_few(std::integral_constant<int, 2>{}, g_cur, row_a, 2 * tc, m, bj, pj, o);
+                *reinterpret_cast<float2 *>(g_nxt + 2 * tc) = make_float2(o[0], o[1]);
+            }
+        } else
         for (int i0 = 4 * tc; i0 < m; i0 += kStep) {
             float gw[4 * NW];
             load_window(g_cur + i0, gw);
@@ -358,6 +445,7 @@ damp_fold4_kernel(const FoldArgs A)
             }
             *reinterpret_cast<float4 *>(g_nxt + i0) = make_float4(o[0], o[1], o[2], o[3]);
         }
+        if (m <= 2 * TC && tc < 4 && m + tc < ((m + 3) & ~3)) g_nxt[m + tc] = 0.0f;   // the narrow paths stop at m
         if (tc < HB / 4) *reinterpret_cast<float4 *>(g_nxt + ((m + 3) & ~3) + 4 * tc) = zero4;
         // Sum the NBR partial rows over the sample's lanes.  Two halving exchanges inside each quad (a lane keeps
         // half of the entries and hands the other half to its partner), then the quads of a row are added by
