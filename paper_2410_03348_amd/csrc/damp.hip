@@ -100,38 +100,53 @@ damp_apply2_fwd_long_kernel(int32_t n_long, const uint32_t *__restrict__ long_co
 // loads coalesced, the gathers of neighbouring lanes adjacent wherever the function is monotone in i).  That is
 // not the order the clamp decision is defined in; the terms' magnitudes bound how far the two sums can lie apart,
 // and only a sum within that distance of 1 is taken again in the defining order.
+// (The maps have NBP >= nb rows, the extra ones empty.)
+template <int NBP>
 __global__ void __launch_bounds__(kThreads)
 damp_byj_fwd_kernel(Rows R, int32_t nb, const uint16_t *__restrict__ src, const uint32_t *__restrict__ col_ptr,
                     const uint32_t *__restrict__ col_ij, const float *__restrict__ a, int64_t lda,
                     const float *__restrict__ b, int64_t ldb, float *__restrict__ out, int64_t ldo)
 {
+    float y[NBP];                                   // the short operand's row of the sample at hand
+    int64_t s_held = -1;
     for_each_element(R, [&](int64_t s, int c) {
         const float *ar = a + s * lda, *br = b + s * ldb;
-        uint16_t i[kByJMax];
-        float x[kByJMax];
+        if (s != s_held) {
 #pragma unroll
-        for (int j = 0; j < kByJMax; ++j) i[j] = j < nb ? src[static_cast<size_t>(j) * R.n + c] : kByJNone;
+            for (int j = 0; j < NBP; ++j) y[j] = br[j < nb ? j : 0];
+            s_held = s;
+        }
+        uint16_t i[NBP];
+        float x[NBP];
+#pragma unroll
+        for (int j = 0; j < NBP; ++j) i[j] = src[static_cast<size_t>(j) * R.n + c];
         if (i[0] == kByJWave) return;                                     // left to the wavefront-per-column kernel
         if (i[0] == kByJList) {                                           // some j twice: the tuple list itself
             out[s * ldo + c] = fminf(column_sum(ar, br, col_ij, col_ptr[c], col_ptr[c + 1]), 1.0f);
             return;
         }
 #pragma unroll
-        for (int j = 0; j < kByJMax; ++j) x[j] = i[j] != kByJNone ? ar[i[j]] : 0.0f;
+        for (int j = 0; j < NBP; ++j) x[j] = i[j] != kByJNone ? ar[i[j]] : 0.0f;
         float acc = 0.0f, mag = 0.0f;
 #pragma unroll
-        for (int j = 0; j < kByJMax; ++j)
-            if (i[j] != kByJNone) {
-                const float y = br[j];
-                acc = __builtin_fmaf(x[j], y, acc);
-                mag = __builtin_fmaf(fabsf(x[j]), fabsf(y), mag);
-            }
+        for (int j = 0; j < NBP; ++j) {
+            acc = __builtin_fmaf(x[j], y[j], acc);
+            mag = __builtin_fmaf(fabsf(x[j]), fabsf(y[j]), mag);
+        }
         float pre = acc;
-        if (fabsf(acc - 1.0f) <= mag * (static_cast<float>(nb + 2) * 1.1920929e-7f))
+        if (fabsf(acc - 1.0f) <= mag * (static_cast<float>(NBP + 2) * 1.1920929e-7f))
             pre = column_sum(ar, br, col_ij, col_ptr[c], col_ptr[c + 1]);
         out[s * ldo + c] = fminf(pre, 1.0f);
     });
 }
+
+#define DOL_DISPATCH_NBP(nbp, CALL) \
+    switch (nbp) {                  \
+    case 4: CALL(4); break;         \
+    case 8: CALL(8); break;         \
+    case 10: CALL(10); break;       \
+    default: CALL(16); break;       \
+    }
 
 static dol_status launch_fwd_waves(const dol_fn_table *f, const DevArray<uint32_t> &cols, int32_t batch, const float *a,
                                    int64_t lda, const float *b, int64_t ldb, float *out, int64_t ldo, hipStream_t st)
@@ -156,8 +171,10 @@ dol_status launch_damp_apply2_fwd(const dol_fn_table *f, int32_t batch, const fl
     if (done) return DOL_OK;
     const Rows R = rows_of(batch, f->n_out);
     if (f->byj_fwd) {
-        hipLaunchKernelGGL(damp_byj_fwd_kernel, dim3(R.grid), dim3(kThreads), 0, st, R, f->nb, f->byj_src.ptr, f->col_ptr.ptr,
-                           f->col_ij.ptr, a, lda, b, ldb, out, ldo);
+#define CALL(N) hipLaunchKernelGGL(damp_byj_fwd_kernel<N>, dim3(R.grid), dim3(kThreads), 0, st, R, f->nb, f->byj_src.ptr, \
+                                   f->col_ptr.ptr, f->col_ij.ptr, a, lda, b, ldb, out, ldo)
+        DOL_DISPATCH_NBP(f->byj_nbp, CALL)
+#undef CALL
         DOL_HIP(hipGetLastError());
         return launch_fwd_waves(f, f->byj_wave_cols, batch, a, lda, b, ldb, out, ldo, st);
     }
@@ -238,32 +255,59 @@ damp_apply2_bwd_kernel(Rows R, BwdTable T, const float *__restrict__ a, int64_t 
     });
 }
 
-// The same for tables with a short second operand: a row i of a reads its columns from the dense map, one j at a
-// time (ascending j, the order of the row's tuple list); rows of b walk their lists as above.
+// Gradient of row i of a from the dense map, one j at a time (ascending j, the order of the row's tuple list), and
+// the row's shares gh * a[i] of the gradient of b (added to pb where SHARES).  `clamped`: some column of the sample may
+// sit at the clamp, so `out` has to be looked at.  Empty map entries read element 0 and count as 0.
+template <int NBP, bool SHARES>
+__device__ __forceinline__ float byj_row(const uint16_t *__restrict__ col_of, int32_t na, int i, bool clamped,
+                                         const float *__restrict__ gr, const float *__restrict__ outr,
+                                         const float *__restrict__ ar, const float *__restrict__ br,
+                                         const float (&bj)[NBP], const BwdTable &T, float (&pb)[NBP])
+{
+    uint16_t c[NBP];
+    float gv[NBP];
+#pragma unroll
+    for (int j = 0; j < NBP; ++j) c[j] = col_of[static_cast<size_t>(j) * na + i];
+#pragma unroll
+    for (int j = 0; j < NBP; ++j) gv[j] = gr[c[j] == kByJNone ? 0 : c[j]];
+    if (clamped) {
+#pragma unroll
+        for (int j = 0; j < NBP; ++j)
+            if (c[j] != kByJNone) gv[j] = gated_grad(gv[j], outr[c[j]], ar, br, T.col_ptr, T.col_ij, c[j]);
+    }
+    const float ai = SHARES ? ar[i] : 0.0f;
+    float acc = 0.0f;
+#pragma unroll
+    for (int j = 0; j < NBP; ++j) {
+        const float gh = c[j] == kByJNone ? 0.0f : gv[j];
+        acc = __builtin_fmaf(gh, bj[j], acc);
+        if (SHARES) pb[j] = __builtin_fmaf(gh, ai, pb[j]);
+    }
+    return acc;
+}
+
+// Backward for tables with a short second operand: a row i of a reads its columns from the dense map; rows of b walk
+// their lists as above.
+template <int NBP>
 __global__ void __launch_bounds__(kThreads)
 damp_byj_bwd_kernel(Rows R, BwdTable T, const uint16_t *__restrict__ col_of, const float *__restrict__ a, int64_t lda,
                     const float *__restrict__ b, int64_t ldb, const float *__restrict__ out, int64_t ldo,
                     const float *__restrict__ g, int64_t ldg, float *__restrict__ ga, float *__restrict__ gb,
                     int32_t accumulate)
 {
+    float bj[NBP];                                  // the short operand's row of the sample at hand
+    int64_t s_held = -1;
     for_each_element(R, [&](int64_t s, int x) {
         const float *ar = a + s * lda, *br = b + s * ldb, *outr = out + s * ldo, *gr = g + s * ldg;
         if (x < T.na) {
             if (!ga) return;
-            uint16_t c[kByJMax];
-            float gv[kByJMax], ov[kByJMax];
+            float none[NBP];
+            if (s != s_held) {
 #pragma unroll
-            for (int j = 0; j < kByJMax; ++j) c[j] = j < T.nb ? col_of[static_cast<size_t>(j) * T.na + x] : kByJNone;
-#pragma unroll
-            for (int j = 0; j < kByJMax; ++j) {
-                gv[j] = c[j] != kByJNone ? gr[c[j]] : 0.0f;
-                ov[j] = c[j] != kByJNone ? outr[c[j]] : 0.0f;
+                for (int j = 0; j < NBP; ++j) bj[j] = j < T.nb ? br[j] : 0.0f;
+                s_held = s;
             }
-            float acc = 0.0f;
-#pragma unroll
-            for (int j = 0; j < kByJMax; ++j)
-                if (c[j] != kByJNone)
-                    acc = __builtin_fmaf(gated_grad(gv[j], ov[j], ar, br, T.col_ptr, T.col_ij, static_cast<uint32_t>(c[j])), br[j], acc);
+            const float acc = byj_row<NBP, false>(col_of, T.na, x, true, gr, outr, ar, br, bj, T, none);
             float *dst = ga + s * lda + x;
             *dst = (accumulate & 1) ? *dst + acc : acc;
             return;
@@ -278,90 +322,53 @@ damp_byj_bwd_kernel(Rows R, BwdTable T, const uint16_t *__restrict__ col_of, con
     });
 }
 
-// The same for wide operands (na + nb > 1024): one workgroup of 1024 threads owns kByJRowSamples whole samples and
-// reads each map entry once for all of them.  A first pass over a sample's result row tells whether any column sits
-// at the clamp; if none does, the gate is open everywhere and `out` is not gathered again.  Each thread also adds
-// its rows' shares g^[col(i, j)] * a[i] of the gradient w.r.t. b[j] into registers; the workgroup sums them, so the
-// long rows of b need no launch of their own.
+// The same for wide operands (na + nb > 1024): one workgroup of 1024 threads owns a whole sample.  A first pass over
+// the sample's result row tells whether any column sits at the clamp; if none does, the gate is open everywhere and
+// `out` is not gathered again.  Each thread also adds its rows' shares g^[col(i, j)] * a[i] of the gradient w.r.t.
+// b[j] into registers; the workgroup sums them, so the long rows of b need no launch of their own.
 constexpr int kByJRowThreads = 1024;
-constexpr int kByJRowSamples = 1;    // more samples per workgroup save map reads but leave small batches with too few workgroups
 
+template <int NBP>
 __global__ void __launch_bounds__(kByJRowThreads)
-damp_byj_bwd_row_kernel(int32_t batch, BwdTable T, int32_t S, const uint16_t *__restrict__ col_of,
-                        const float *__restrict__ a, int64_t lda, const float *__restrict__ b, int64_t ldb,
-                        const float *__restrict__ out, int64_t ldo, const float *__restrict__ g, int64_t ldg,
-                        float *__restrict__ ga, float *__restrict__ gb, int32_t accumulate)
+damp_byj_bwd_row_kernel(BwdTable T, int32_t S, const uint16_t *__restrict__ col_of, const float *__restrict__ a,
+                        int64_t lda, const float *__restrict__ b, int64_t ldb, const float *__restrict__ out, int64_t ldo,
+                        const float *__restrict__ g, int64_t ldg, float *__restrict__ ga, float *__restrict__ gb,
+                        int32_t accumulate)
 {
-    __shared__ float red[kByJRowSamples][kByJMax][kByJRowThreads / kWave];
-    __shared__ float bs[kByJRowSamples][kByJMax];
-    const int64_t s0 = static_cast<int64_t>(blockIdx.x) * kByJRowSamples;
-    const int rows = static_cast<int>(min(static_cast<int64_t>(kByJRowSamples), batch - s0));
-    if (threadIdx.x < kByJRowSamples * kByJMax) {
-        const int r = threadIdx.x / kByJMax, j = threadIdx.x % kByJMax;
-        bs[r][j] = r < rows && j < T.nb ? b[(s0 + r) * ldb + j] : 0.0f;
+    __shared__ float red[NBP][kByJRowThreads / kWave];
+    const int64_t s = blockIdx.x;
+    const float *ar = a + s * lda, *br = b + s * ldb, *outr = out + s * ldo, *gr = g + s * ldg;
+    int hit = 0;
+    for (int c = threadIdx.x; c < S; c += kByJRowThreads) hit |= outr[c] >= 1.0f;
+    const bool clamped = __syncthreads_or(hit) != 0;
+    float bj[NBP], pb[NBP];
+#pragma unroll
+    for (int j = 0; j < NBP; ++j) {
+        bj[j] = j < T.nb ? br[j] : 0.0f;
+        pb[j] = 0.0f;
     }
-    bool clamped[kByJRowSamples];
-#pragma unroll
-    for (int r = 0; r < kByJRowSamples; ++r) {
-        int hit = 0;
-        if (r < rows)
-            for (int c = threadIdx.x; c < S; c += kByJRowThreads) hit |= out[(s0 + r) * ldo + c] >= 1.0f;
-        clamped[r] = __syncthreads_or(hit) != 0;
-    }
-    float pb[kByJRowSamples][kByJMax];
-#pragma unroll
-    for (int r = 0; r < kByJRowSamples; ++r)
-#pragma unroll
-        for (int j = 0; j < kByJMax; ++j) pb[r][j] = 0.0f;
     for (int i = threadIdx.x; i < T.na; i += kByJRowThreads) {
-        uint16_t c[kByJMax];
-#pragma unroll
-        for (int j = 0; j < kByJMax; ++j) c[j] = j < T.nb ? col_of[static_cast<size_t>(j) * T.na + i] : kByJNone;
-#pragma unroll
-        for (int r = 0; r < kByJRowSamples; ++r) {
-            if (r >= rows) break;
-            const float *ar = a + (s0 + r) * lda, *br = b + (s0 + r) * ldb, *outr = out + (s0 + r) * ldo, *gr = g + (s0 + r) * ldg;
-            float gv[kByJMax], ov[kByJMax];
-            const float ai = ar[i];
-#pragma unroll
-            for (int j = 0; j < kByJMax; ++j) {
-                gv[j] = c[j] != kByJNone ? gr[c[j]] : 0.0f;
-                ov[j] = clamped[r] && c[j] != kByJNone ? outr[c[j]] : 0.0f;
-            }
-            float acc = 0.0f;
-#pragma unroll
-            for (int j = 0; j < kByJMax; ++j)
-                if (c[j] != kByJNone) {
-                    const float gh = gated_grad(gv[j], ov[j], ar, br, T.col_ptr, T.col_ij, static_cast<uint32_t>(c[j]));
-                    acc = __builtin_fmaf(gh, bs[r][j], acc);
-                    pb[r][j] = __builtin_fmaf(gh, ai, pb[r][j]);
-                }
-            if (ga) {
-                float *dst = ga + (s0 + r) * lda + i;
-                *dst = (accumulate & 1) ? *dst + acc : acc;
-            }
+        const float acc = byj_row<NBP, true>(col_of, T.na, i, clamped, gr, outr, ar, br, bj, T, pb);
+        if (ga) {
+            float *dst = ga + s * lda + i;
+            *dst = (accumulate & 1) ? *dst + acc : acc;
         }
     }
     if (!gb) return;
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
 #pragma unroll
-    for (int r = 0; r < kByJRowSamples; ++r)
+    for (int j = 0; j < NBP; ++j) {
+        float v = pb[j];
 #pragma unroll
-        for (int j = 0; j < kByJMax; ++j) {
-            float v = pb[r][j];
-#pragma unroll
-            for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, kWave);
-            if (lane == 0) red[r][j][wave] = v;
-        }
+        for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, kWave);
+        if (lane == 0) red[j][wave] = v;
+    }
     __syncthreads();
-    if (threadIdx.x < kByJRowSamples * kByJMax) {
-        const int r = threadIdx.x / kByJMax, j = threadIdx.x % kByJMax;
-        if (r < rows && j < T.nb) {
-            float tot = 0.0f;
-            for (int w = 0; w < kByJRowThreads / kWave; ++w) tot = tot + red[r][j][w];
-            float *dst = gb + (s0 + r) * ldb + j;
-            *dst = (accumulate & 2) ? *dst + tot : tot;
-        }
+    if (threadIdx.x < static_cast<unsigned>(T.nb)) {
+        float tot = 0.0f;
+        for (int w = 0; w < kByJRowThreads / kWave; ++w) tot = tot + red[threadIdx.x][w];
+        float *dst = gb + s * ldb + threadIdx.x;
+        *dst = (accumulate & 2) ? *dst + tot : tot;
     }
 }
 
@@ -404,15 +411,19 @@ dol_status launch_damp_apply2_bwd(const dol_fn_table *f, int32_t batch, const fl
                      f->na, f->nb};
     const Rows R = rows_of(batch, f->na + f->nb);
     if (f->byj_ok && R.rpb == 1) {
-        const int64_t groups = (static_cast<int64_t>(batch) + kByJRowSamples - 1) / kByJRowSamples;
-        hipLaunchKernelGGL(damp_byj_bwd_row_kernel, dim3(static_cast<unsigned>(groups)), dim3(kByJRowThreads), 0, st, batch,
-                           T, f->n_out, f->byj_col.ptr, a, lda, b, ldb, out, ldo, g, ldg, ga, gb, accumulate);
+#define CALL(N) hipLaunchKernelGGL(damp_byj_bwd_row_kernel<N>, dim3(static_cast<unsigned>(batch)), dim3(kByJRowThreads), 0, \
+                                   st, T, f->n_out, f->byj_col.ptr, a, lda, b, ldb, out, ldo, g, ldg, ga, gb, accumulate)
+        DOL_DISPATCH_NBP(f->byj_nbp, CALL)
+#undef CALL
         DOL_HIP(hipGetLastError());
         return DOL_OK;
     }
-    if (f->byj_ok)
-        hipLaunchKernelGGL(damp_byj_bwd_kernel, dim3(R.grid), dim3(kThreads), 0, st, R, T, f->byj_col.ptr, a, lda, b, ldb, out,
-                           ldo, g, ldg, ga, gb, accumulate);
+    if (f->byj_ok) {
+#define CALL(N) hipLaunchKernelGGL(damp_byj_bwd_kernel<N>, dim3(R.grid), dim3(kThreads), 0, st, R, T, f->byj_col.ptr, a, lda, \
+                                   b, ldb, out, ldo, g, ldg, ga, gb, accumulate)
+        DOL_DISPATCH_NBP(f->byj_nbp, CALL)
+#undef CALL
+    }
     else
         hipLaunchKernelGGL(damp_apply2_bwd_kernel, dim3(R.grid), dim3(kThreads), 0, st, R, T, a, lda, b, ldb, out, ldo, g,
                            ldg, ga, gb, accumulate);

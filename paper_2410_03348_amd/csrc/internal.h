@@ -104,6 +104,7 @@ struct dol_fn_table {
     // short column where some j occurs twice has dol::kByJList there and is summed from its tuple list.
     // byj_col[j * na + i] = column of (i, j) or dol::kByJNone.
     bool byj_ok = false;
+    int32_t byj_nbp = 0;               // rows of the two maps: nb padded to 4, 8, 10 or 16 (the extra rows hold kByJNone)
     bool byj_fwd = false;              // forward uses the map only where it is at least half full (else the tuple lists)
     dol::DevArray<uint16_t> byj_src, byj_col;
     dol::DevArray<uint32_t> byj_wave_cols;

@@ -138,7 +138,9 @@ static dol_status build_table(int32_t na, int32_t nb, std::vector<Tuple> &tup, d
         if (dol_status s2 = lds_plan_build(tb.get(), col_ptr, col_ij, rowa_ptr, rowa_jc, rowb_ptr, rowb_ic)) return s2;
     if (!conv_path_ok(tb.get()) && !tb->lds_fwd_ok && !tb->lds_bwd_ok && nb >= 1 && nb <= kByJMax && na >= 1 &&
         na <= kByJMaxNa && S >= 1 && S <= kByJMaxNa) {
-        std::vector<uint16_t> src(static_cast<size_t>(nb) * S, kByJNone), colof(static_cast<size_t>(nb) * na, kByJNone);
+        const int32_t nbp = nb <= 4 ? 4 : nb <= 8 ? 8 : nb <= 10 ? 10 : 16;
+        tb->byj_nbp = nbp;
+        std::vector<uint16_t> src(static_cast<size_t>(nbp) * S, kByJNone), colof(static_cast<size_t>(nbp) * na, kByJNone);
         std::vector<uint32_t> wave_cols;
         for (int32_t c = 0; c < S; ++c) {
             bool regular = col_ptr[c + 1] - col_ptr[c] <= static_cast<uint32_t>(kLongTableCol);
