@@ -41,15 +41,47 @@ __device__ __forceinline__ float column_sum(const float *__restrict__ ar, const 
     return acc;
 }
 
+// One thread per (sample, column).  The column's first four tuples come with one 16-byte load of col_head; only a
+// column with more tuples goes on through its list (same order).
 __global__ void __launch_bounds__(kThreads)
 damp_apply2_fwd_kernel(Rows R, const uint32_t *__restrict__ col_ptr, const uint32_t *__restrict__ col_ij,
-                       const float *__restrict__ a, int64_t lda, const float *__restrict__ b, int64_t ldb,
-                       float *__restrict__ out, int64_t ldo)
+                       const uint4 *__restrict__ col_head, const float *__restrict__ a, int64_t lda,
+                       const float *__restrict__ b, int64_t ldb, float *__restrict__ out, int64_t ldo)
 {
     for_each_element(R, [&](int64_t s, int c) {
-        const uint32_t q0 = col_ptr[c], q1 = col_ptr[c + 1];
-        if (q1 - q0 > static_cast<uint32_t>(kLongTableCol)) return;        // left to the wavefront-per-column kernel
-        out[s * ldo + c] = fminf(column_sum(a + s * lda, b + s * ldb, col_ij, q0, q1), 1.0f);
+        const float *ar = a + s * lda, *br = b + s * ldb;
+        const uint4 h = col_head[c];
+        const uint32_t t[4] = {h.x, h.y, h.z, h.w};
+        float x[4], y[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const bool there = t[u] != 0xFFFFFFFFu;
+            x[u] = there ? ar[t[u] & 0xffffu] : 0.0f;
+            y[u] = there ? br[t[u] >> 16] : 0.0f;
+        }
+        float acc = 0.0f;
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (t[u] != 0xFFFFFFFFu) acc = __builtin_fmaf(x[u], y[u], acc);
+        if (t[3] != 0xFFFFFFFFu) {                                         // four or more tuples: the rest of the list
+            const uint32_t q0 = col_ptr[c], q1 = col_ptr[c + 1];
+            if (q1 - q0 > static_cast<uint32_t>(kLongTableCol)) return;    // left to the wavefront-per-column kernel
+            for (uint32_t q = q0 + 4; q < q1; q += kGather) {
+                uint32_t ij[kGather];
+                float xs[kGather], ys[kGather];
+#pragma unroll
+                for (int u = 0; u < kGather; ++u) ij[u] = col_ij[min(q + u, q1 - 1)];
+#pragma unroll
+                for (int u = 0; u < kGather; ++u) {
+                    xs[u] = ar[ij[u] & 0xffffu];
+                    ys[u] = br[ij[u] >> 16];
+                }
+#pragma unroll
+                for (int u = 0; u < kGather; ++u)
+                    if (q + u < q1) acc = __builtin_fmaf(xs[u], ys[u], acc);
+            }
+        }
+        out[s * ldo + c] = fminf(acc, 1.0f);
     });
 }
 
@@ -178,8 +210,8 @@ dol_status launch_damp_apply2_fwd(const dol_fn_table *f, int32_t batch, const fl
         DOL_HIP(hipGetLastError());
         return launch_fwd_waves(f, f->byj_wave_cols, batch, a, lda, b, ldb, out, ldo, st);
     }
-    hipLaunchKernelGGL(damp_apply2_fwd_kernel, dim3(R.grid), dim3(kThreads), 0, st, R, f->col_ptr.ptr, f->col_ij.ptr, a,
-                       lda, b, ldb, out, ldo);
+    hipLaunchKernelGGL(damp_apply2_fwd_kernel, dim3(R.grid), dim3(kThreads), 0, st, R, f->col_ptr.ptr, f->col_ij.ptr,
+                       reinterpret_cast<const uint4 *>(f->col_head.ptr), a, lda, b, ldb, out, ldo);
     DOL_HIP(hipGetLastError());
     return launch_fwd_waves(f, f->long_cols, batch, a, lda, b, ldb, out, ldo, st);
 }

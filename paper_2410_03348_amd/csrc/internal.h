@@ -84,6 +84,9 @@ struct dol_fn_table {
     std::vector<uint32_t> h_col_ptr, h_col_ij;
     // forward: column c owns entries col_ptr[c] .. col_ptr[c+1] of col_ij = pack16(i, j), ascending (i, j)
     dol::DevArray<uint32_t> col_ptr, col_ij;
+    // the first four tuples of every column again, 16 bytes per column (0xFFFFFFFF = no tuple): the forward kernel
+    // for irregular tables gets a short column with one load
+    dol::DevArray<uint32_t> col_head;
     // backward w.r.t. a: row i owns rowa_ptr[i] .. rowa_ptr[i+1] of rowa_jc = pack16(j, column), ascending j
     dol::DevArray<uint32_t> rowa_ptr, rowa_jc;
     // backward w.r.t. b: row j owns rowb_ptr[j] .. rowb_ptr[j+1] of rowb_ic = pack16(i, column), ascending i

@@ -130,6 +130,10 @@ static dol_status build_table(int32_t na, int32_t nb, std::vector<Tuple> &tup, d
     if ((e = tb->long_rows.upload(long_rows)) != hipSuccess) return hip_fail(e, "uploading the function table");
     if ((e = tb->long_cols.upload(long_cols)) != hipSuccess || (e = tb->dtkp_long_cols.upload(dtkp_long_cols)) != hipSuccess)
         return hip_fail(e, "uploading the function table");
+    std::vector<uint32_t> col_head(static_cast<size_t>(S) * 4, 0xFFFFFFFFu);
+    for (int32_t c = 0; c < S; ++c)
+        for (uint32_t q = col_ptr[c], u = 0; q < col_ptr[c + 1] && u < 4; ++q, ++u) col_head[static_cast<size_t>(c) * 4 + u] = col_ij[q];
+    if ((e = tb->col_head.upload(col_head)) != hipSuccess) return hip_fail(e, "uploading the function table");
     if ((e = tb->col_ptr.upload(col_ptr)) != hipSuccess || (e = tb->col_ij.upload(col_ij)) != hipSuccess ||
         (e = tb->rowa_ptr.upload(rowa_ptr)) != hipSuccess || (e = tb->rowa_jc.upload(rowa_jc)) != hipSuccess ||
         (e = tb->rowb_ptr.upload(rowb_ptr)) != hipSuccess || (e = tb->rowb_ic.upload(rowb_ic)) != hipSuccess)
