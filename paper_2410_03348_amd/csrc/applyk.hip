@@ -30,6 +30,10 @@ struct dol_fnk_table {
     dol::DevArray<uint32_t> row_tup;     // [n_tuples*K] grouped-tuple numbers of each operand row, ascending
     dol::DevArray<uint32_t> long_cols;   // columns with more than dol::kLongTableCol tuples
     dol::DevArray<uint32_t> dtkp_long_cols;   // ... more than dol::kLongDtkpCol
+    // unary functions (K = 1): the first eight symbols of every image again, 16 bytes per column (0xFFFF = none), and
+    // the column of every symbol (-1: rejected)
+    dol::DevArray<uint16_t> unary_head;
+    dol::DevArray<int32_t> unary_col;
     int device = 0;
 };
 
@@ -100,6 +104,64 @@ damp_applyk_fwd_kernel(Rows R, KOperands in, const uint32_t *__restrict__ col_pt
         const uint32_t q0 = col_ptr[c], q1 = col_ptr[c + 1];
         if (q1 - q0 > static_cast<uint32_t>(kLongTableCol)) return;        // left to the wavefront-per-column kernel
         out[s * ldo + c] = fminf(column_sum_k<K>(row, tup, q0, q1), 1.0f);
+    });
+}
+
+// Unary Apply: out[c] = clamp(sum of the tags of the symbols with image c).  The first eight symbols of a column come
+// with one 16-byte load; only a column with more goes on through its list (same order).
+__global__ void __launch_bounds__(kThreads)
+damp_apply1_fwd_kernel(Rows R, const float *__restrict__ x, int64_t ldx, const uint32_t *__restrict__ col_ptr,
+                       const uint16_t *__restrict__ tup, const uint4 *__restrict__ head, float *__restrict__ out,
+                       int64_t ldo)
+{
+    for_each_element(R, [&](int64_t s, int c) {
+        const float *xr = x + s * ldx;
+        const uint4 h = head[c];
+        const uint32_t w[4] = {h.x, h.y, h.z, h.w};
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const uint32_t pos = (w[u / 2] >> (16 * (u & 1))) & 0xffffu;
+            v[u] = pos != 0xffffu ? xr[pos] : 0.0f;
+        }
+        float acc = 0.0f;
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            if (((w[u / 2] >> (16 * (u & 1))) & 0xffffu) != 0xffffu) acc = acc + v[u];
+        if ((w[3] >> 16) != 0xffffu) {                                     // eight or more symbols: the rest of the list
+            const uint32_t q0 = col_ptr[c], q1 = col_ptr[c + 1];
+            if (q1 - q0 > static_cast<uint32_t>(kLongTableCol)) return;    // left to the wavefront-per-column kernel
+            for (uint32_t q = q0 + 8; q < q1; q += kGatherK) {
+                float t[kGatherK];
+#pragma unroll
+                for (int u = 0; u < kGatherK; ++u) t[u] = xr[tup[min(q + u, q1 - 1)]];
+#pragma unroll
+                for (int u = 0; u < kGatherK; ++u)
+                    if (q + u < q1) acc = acc + t[u];
+            }
+        }
+        out[s * ldo + c] = fminf(acc, 1.0f);
+    });
+}
+
+// Its vector-Jacobian product: gx[i] = g[col(i)] where the column is not clamped (0 for a rejected symbol).
+__global__ void __launch_bounds__(kThreads)
+damp_apply1_bwd_kernel(Rows R, const float *__restrict__ x, int64_t ldx, const int32_t *__restrict__ col_of,
+                       const uint32_t *__restrict__ col_ptr, const uint16_t *__restrict__ tup,
+                       const float *__restrict__ out, int64_t ldo, const float *__restrict__ g, int64_t ldg,
+                       float *__restrict__ gx)
+{
+    for_each_element(R, [&](int64_t s, int i) {
+        const int32_t c = col_of[i];
+        float gh = 0.0f;
+        if (c >= 0) {
+            gh = g[s * ldg + c];
+            if (out[s * ldo + c] >= 1.0f) {         // pre == 1 passes, pre > 1 blocks: only pre itself tells
+                const float *row[1] = {x + s * ldx};
+                if (!(column_sum_k<1>(row, tup, col_ptr[c], col_ptr[c + 1]) <= 1.0f)) gh = 0.0f;
+            }
+        }
+        gx[s * ldx + i] = gh;
     });
 }
 
@@ -183,8 +245,12 @@ damp_applyk_bwd_kernel(Rows R, KOperands in, KGrads gin, const uint32_t *__restr
 template <int K>
 static void launch_fwd_k(const Rows &R, const KOperands &in, const dol_fnk_table *f, float *out, int64_t ldo, hipStream_t st)
 {
-    hipLaunchKernelGGL(damp_applyk_fwd_kernel<K>, dim3(R.grid), dim3(kThreads), 0, st, R, in, f->col_ptr.ptr, f->tup.ptr,
-                       out, ldo);
+    if (K == 1)
+        hipLaunchKernelGGL(damp_apply1_fwd_kernel, dim3(R.grid), dim3(kThreads), 0, st, R, in.p[0], in.ld[0], f->col_ptr.ptr,
+                           f->tup.ptr, reinterpret_cast<const uint4 *>(f->unary_head.ptr), out, ldo);
+    else
+        hipLaunchKernelGGL(damp_applyk_fwd_kernel<K>, dim3(R.grid), dim3(kThreads), 0, st, R, in, f->col_ptr.ptr, f->tup.ptr,
+                           out, ldo);
     const int64_t n_long = static_cast<int64_t>(f->long_cols.n);
     if (n_long > 0)
         hipLaunchKernelGGL(damp_applyk_fwd_long_kernel<K>, dim3(static_cast<unsigned>(R.batch * n_long)), dim3(kWave), 0, st,
@@ -195,8 +261,12 @@ template <int K>
 static void launch_bwd_k(const Rows &R, const KOperands &in, const KGrads &gin, const dol_fnk_table *f, const float *out,
                          int64_t ldo, const float *g, int64_t ldg, hipStream_t st)
 {
-    hipLaunchKernelGGL(damp_applyk_bwd_kernel<K>, dim3(R.grid), dim3(kThreads), 0, st, R, in, gin, f->col_ptr.ptr,
-                       f->tup.ptr, f->tup_col.ptr, f->row_ptr.ptr, f->row_tup.ptr, out, ldo, g, ldg);
+    if (K == 1)
+        hipLaunchKernelGGL(damp_apply1_bwd_kernel, dim3(R.grid), dim3(kThreads), 0, st, R, in.p[0], in.ld[0], f->unary_col.ptr,
+                           f->col_ptr.ptr, f->tup.ptr, out, ldo, g, ldg, gin.p[0]);
+    else
+        hipLaunchKernelGGL(damp_applyk_bwd_kernel<K>, dim3(R.grid), dim3(kThreads), 0, st, R, in, gin, f->col_ptr.ptr,
+                           f->tup.ptr, f->tup_col.ptr, f->row_ptr.ptr, f->row_tup.ptr, out, ldo, g, ldg);
 }
 
 #define DOL_DISPATCH_ARITY(K, CALL)  \
@@ -405,6 +475,17 @@ static dol_status build_k(int32_t K, const int32_t *n_sym, int64_t n, const int3
         if (col_ptr[c + 1] - col_ptr[c] > static_cast<uint32_t>(kLongDtkpCol)) dtkp_long_cols.push_back(static_cast<uint32_t>(c));
     }
 
+    if (K == 1) {
+        std::vector<uint16_t> head(static_cast<size_t>(S) * 8, 0xFFFFu);
+        std::vector<int32_t> col_of(static_cast<size_t>(n_sym[0]), -1);
+        for (int32_t c = 0; c < S; ++c)
+            for (uint32_t q = col_ptr[c]; q < col_ptr[c + 1]; ++q) {
+                if (q - col_ptr[c] < 8) head[static_cast<size_t>(c) * 8 + (q - col_ptr[c])] = tup[q];
+                col_of[tup[q]] = c;
+            }
+        DOL_HIP(tb->unary_head.upload(head));
+        DOL_HIP(tb->unary_col.upload(col_of));
+    }
     DOL_HIP(hipGetDevice(&tb->device));
     DOL_HIP(tb->long_cols.upload(long_cols));
     DOL_HIP(tb->dtkp_long_cols.upload(dtkp_long_cols));
