@@ -266,20 +266,23 @@ dol_status launch_dtkp_filter(const FilterPlan *p, int32_t batch, int32_t k, con
 // Pr(symbol) = min(1, sum over its kept proofs of the product of their facts' probabilities) (Sec. 3.2); which
 // proofs top-k kept is a constant of the differentiation and the clamp passes gradient inside and on its bound
 // (App. A.2).  One workgroup per sample, one lane per symbol (coalesced loads of the proof lists); a lane walks the
-// facts of each of its proofs and adds gradient * (product of the proof's other facts, ascending) to the fact's
+// facts of each of its proofs and adds gradient * (product of the proof's other facts) to the fact's
 // accumulator of its wavefront in LDS; the wavefronts' accumulators are then summed in wavefront order.
 constexpr int kGradWaves = 16;
+constexpr int kGradCopies = 8;
 
 __global__ void __launch_bounds__(kGradWaves * 64)
 dtkp_prob_bwd_kernel(int32_t n_sym, int32_t k, int32_t n_facts, const uint64_t *__restrict__ mask,
                      const float *__restrict__ pprob, const float *__restrict__ fact_prob,
                      const float *__restrict__ g, int64_t ldg, float *__restrict__ gfact)
 {
-    __shared__ float part[kGradWaves][64];
-    __shared__ float fp[64];
+    __shared__ float part[kGradWaves * kGradCopies][65];   // kGradCopies accumulators per wavefront (rows skewed over the banks): lanes that meet
+    __shared__ float fp[64];                                // on one fact in one instruction are spread over them
     const int64_t s = blockIdx.x;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, n_waves = blockDim.x >> 6;
-    part[wave][lane] = 0.0f;
+#pragma unroll
+    for (int x = 0; x < kGradCopies; ++x) part[wave * kGradCopies + x][lane] = 0.0f;
+    float *mine = part[wave * kGradCopies + (lane & (kGradCopies - 1))];
     if (wave == 0) fp[lane] = lane < n_facts ? fact_prob[s * n_facts + lane] : 1.0f;
     __syncthreads();
     for (int32_t i = threadIdx.x; i < n_sym; i += blockDim.x) {
@@ -303,16 +306,24 @@ dtkp_prob_bwd_kernel(int32_t n_sym, int32_t k, int32_t n_facts, const uint64_t *
             if (mm[x] == kAbsent) continue;
             for (uint64_t r = mm[x]; r; r &= r - 1) {
                 const int j = __builtin_ctzll(r);
-                float others = 1.0f;
-                for (uint64_t q = mm[x] & ~(uint64_t(1) << j); q; q &= q - 1) others = others * fp[__builtin_ctzll(q)];
-                atomicAdd(&part[wave][j], gi * others);
+                // the product of the proof's other facts: its stored probability divided by this fact's (one rounding
+                // more than multiplying them out), multiplied out only where that fact's probability is (nearly) 0
+                const float pj = fp[j];
+                float others;
+                if (pj > 1e-30f) {
+                    others = pv[x] * __builtin_amdgcn_rcpf(pj);        // 1 ulp reciprocal: far inside the 1e-5 bar
+                } else {
+                    others = 1.0f;
+                    for (uint64_t q = mm[x] & ~(uint64_t(1) << j); q; q &= q - 1) others = others * fp[__builtin_ctzll(q)];
+                }
+                atomicAdd(&mine[j], gi * others);
             }
         }
     }
     __syncthreads();
     if (wave == 0 && lane < n_facts) {
         float tot = 0.0f;
-        for (int w = 0; w < n_waves; ++w) tot = tot + part[w][lane];
+        for (int w = 0; w < n_waves * kGradCopies; ++w) tot = tot + part[w][lane];
         gfact[s * n_facts + lane] = tot;
     }
 }
