@@ -116,6 +116,14 @@ dol_status dol_fn_table_create_if(int32_t na, int32_t nb, const int32_t *out_id,
 dol_status dol_apply2(const dol_dist *a, const dol_dist *b, const dol_fn_table *f, const dol_prov *prov,
                       dol_dist *out, void *hip_stream);
 
+/* Apply, K=2, under DTKP-AM with an input Distribution as second operand (the shape of every fold over model
+ * outputs: D_res = apply(D_res, D_i, f), Fig. 2): symbol j of the second operand is input fact fact_of_sym_b[j]
+ * (host [nb], each in 0..n_facts-1) and carries the tag natural initialisation gives it (App. A.1: the single proof
+ * {that fact}).  The result equals dol_dtkp_init on the operand followed by dol_apply2; the operand's tags are
+ * never stored.  a, f, prov, out as for dol_apply2. */
+dol_status dol_dtkp_apply2_input(const dol_dist *a, const int32_t *fact_of_sym_b, const dol_fn_table *f,
+                                 const dol_prov *prov, dol_dist *out, void *hip_stream);
+
 /* Filter (Sec. 3.1.2): symbols whose pred_mask entry is 0 are removed, the rest keep tags and order.
  * pred_mask: host [d->n_sym].  dol_filter_plan returns the kept count and (if out_syms != NULL,
  * room for d->n_sym) the kept ids, so that the caller can allocate `out`. */

@@ -78,6 +78,7 @@ _lib.dol_fn_table_kernel.restype = C.c_char_p
 _lib.dol_fn_table_destroy.argtypes = [C.c_void_p]
 _lib.dol_fn_table_destroy.restype = None
 _lib.dol_apply2.argtypes = [C.POINTER(_Dist), C.POINTER(_Dist), C.c_void_p, C.POINTER(_Prov), C.POINTER(_Dist), C.c_void_p]
+_lib.dol_dtkp_apply2_input.argtypes = [C.POINTER(_Dist), _i32p, C.c_void_p, C.POINTER(_Prov), C.POINTER(_Dist), C.c_void_p]
 _lib.dol_filter_plan.argtypes = [C.POINTER(_Dist), _u8p, _i32p, _i32p]
 _lib.dol_filter.argtypes = [C.POINTER(_Dist), _u8p, C.POINTER(_Prov), C.POINTER(_Dist), C.c_void_p]
 _lib.dol_union_plan.argtypes = [C.POINTER(_Dist), C.POINTER(_Dist), _i32p, _i32p]
@@ -289,6 +290,13 @@ def apply_k_backward(ins, f: FnkTable, out: Dist, grad_out: torch.Tensor, grad_i
     ptrs = (C.c_void_p * len(ins))(*[None if g is None else g.data_ptr() for g in grad_in])
     _check(_lib.dol_apply_k_backward(len(ins), _dist_array(ins), f._h, out.ref(), _dptr(grad_out),
                                      max(int(grad_out.stride(0)), grad_out.shape[1]), ptrs, _stream(stream)))
+
+
+def dtkp_apply2_input(a: Dist, fact_of_sym_b, f: FnTable, prov: Prov, out: Dist, stream=None):
+    """dol_apply2 whose second operand is an input Distribution: symbol j of it is fact fact_of_sym_b[j]."""
+    fb = _np_i32(fact_of_sym_b)
+    assert fb.size == f.nb
+    _check(_lib.dol_dtkp_apply2_input(a.ref(), _ptr(fb, C.c_int32), f._h, prov.ref(), out.ref(), _stream(stream)))
 
 
 def filter_plan(d: Dist, pred_mask):

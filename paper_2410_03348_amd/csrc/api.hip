@@ -72,7 +72,38 @@ dol_status dol_apply2(const dol_dist *a, const dol_dist *b, const dol_fn_table *
     GroupMasks gm;
     if (dol_status s2 = make_group_masks(prov, &gm)) return s2;
     return launch_dtkp_apply2(f, a->batch, prov->k, prov->n_facts, gm, prov->fact_prob, a->proof_mask, a->proof_prob,
-                              b->proof_mask, b->proof_prob, out->proof_mask, out->proof_prob, out->prob, out->ld, st);
+                              b->proof_mask, b->proof_prob, nullptr, out->proof_mask, out->proof_prob, out->prob, out->ld,
+                              st);
+}
+
+dol_status dol_dtkp_apply2_input(const dol_dist *a, const int32_t *fact_of_sym_b, const dol_fn_table *f,
+                                 const dol_prov *prov, dol_dist *out, void *hip_stream)
+{
+    if (!f) return fail(DOL_EINVAL, "function table is NULL");
+    if (!is_dtkp(prov)) return fail(DOL_EINVAL, "dol_dtkp_apply2_input needs a DTKP provenance");
+    if (dol_status st = check_dist(a, "a", true, false, false)) return st;
+    if (dol_status st = check_dist(out, "out", true, false, true)) return st;
+    if (dol_status st = check_prov(prov, a->batch)) return st;
+    if (a->batch != out->batch) return fail(DOL_ESHAPE, "batch sizes differ: %d, %d", a->batch, out->batch);
+    if (a->n_sym != f->na || out->n_sym != f->n_out)
+        return fail(DOL_ESHAPE, "a has %d symbols and out %d, the table is %d x %d -> %d", a->n_sym, out->n_sym, f->na, f->nb, f->n_out);
+    if (f->nb > 0 && !fact_of_sym_b) return fail(DOL_EINVAL, "fact_of_sym_b is NULL");
+    for (int32_t j = 0; j < f->nb; ++j)
+        if (fact_of_sym_b[j] < 0 || fact_of_sym_b[j] >= prov->n_facts)
+            return fail(DOL_EINVAL, "fact_of_sym_b[%d] = %d outside 0..%d", j, fact_of_sym_b[j], prov->n_facts - 1);
+    if (out->sym_ids)
+        for (int32_t c = 0; c < f->n_out; ++c)
+            if (out->sym_ids[c] != f->out_syms[c]) return fail(DOL_EINVAL, "out.sym_ids[%d] = %d, the table produces %d there", c, out->sym_ids[c], f->out_syms[c]);
+    if (dol_status st = check_work(a->batch, f->n_out)) return st;
+    if (a->batch == 0 || f->n_out == 0) return DOL_OK;
+    if (!out->proof_prob) return fail(DOL_EINVAL, "out.proof_prob is NULL");
+    GroupMasks gm;
+    if (dol_status s2 = make_group_masks(prov, &gm)) return s2;
+    const int32_t *d_fact_b = nullptr;
+    if (dol_status s2 = get_i32_array(f->nb, fact_of_sym_b, &d_fact_b)) return s2;
+    return launch_dtkp_apply2(f, a->batch, prov->k, prov->n_facts, gm, prov->fact_prob, a->proof_mask, a->proof_prob,
+                              nullptr, nullptr, d_fact_b, out->proof_mask, out->proof_prob, out->prob, out->ld,
+                              static_cast<hipStream_t>(hip_stream));
 }
 
 dol_status dol_filter(const dol_dist *d, const uint8_t *pred_mask, const dol_prov *prov, dol_dist *out,

@@ -56,11 +56,31 @@ template <int K>
 __device__ __forceinline__ void offer_tuple(TopK<K> &top, uint32_t ij, int64_t a0, int64_t b0, const GroupMasks &gm,
                                             const float *__restrict__ fp, const uint64_t *__restrict__ am,
                                             const float *__restrict__ ap, const uint64_t *__restrict__ bm,
-                                            const float *__restrict__ bp)
+                                            const float *__restrict__ bp, const int32_t *__restrict__ fact_b)
 {
     const int64_t ia = a0 + static_cast<int64_t>(ij & 0xffffu) * K, ib = b0 + static_cast<int64_t>(ij >> 16) * K;
     uint64_t ma[K], mb[K];
     float pa[K], pb[K];
+    if (fact_b) {
+        // the second operand is an input Distribution under natural initialisation: its symbol is one fact, its
+        // tag the single proof {that fact} (App. A.1); nothing of it is stored
+        const int fb = fact_b[ij >> 16];
+        const uint64_t bit = uint64_t(1) << fb;
+        const float pbit = 1.0f * fp[fb];
+#pragma unroll
+        for (int x = 0; x < K; ++x) {
+            ma[x] = am[ia + x];
+            pa[x] = ap ? ap[ia + x] : -1.0f;
+        }
+#pragma unroll
+        for (int x = 0; x < K; ++x) {
+            if (ma[x] == kAbsent) continue;
+            const uint64_t m = ma[x] | bit;
+            if (proof_conflict(m, gm)) continue;
+            top.insert(m, union_prob(ma[x], pa[x], bit, pbit, fp));
+        }
+        return;
+    }
 #pragma unroll
     for (int x = 0; x < K; ++x) {
         ma[x] = am[ia + x];
@@ -87,7 +107,8 @@ dtkp_apply2_kernel(int64_t total, int32_t S, int32_t na, int32_t nb, int32_t n_f
                    const uint32_t *__restrict__ col_ptr, const uint32_t *__restrict__ col_ij, GroupMasks gm,
                    const float *__restrict__ fact_prob, const uint64_t *__restrict__ am,
                    const float *__restrict__ ap, const uint64_t *__restrict__ bm, const float *__restrict__ bp,
-                   uint64_t *__restrict__ om, float *__restrict__ op, float *__restrict__ oprob, int64_t ldo)
+                   const int32_t *__restrict__ fact_b, uint64_t *__restrict__ om, float *__restrict__ op,
+                   float *__restrict__ oprob, int64_t ldo)
 {
     const int64_t idx = static_cast<int64_t>(blockIdx.x) * kThreadsT + threadIdx.x;
     if (idx >= total) return;
@@ -99,7 +120,7 @@ dtkp_apply2_kernel(int64_t total, int32_t S, int32_t na, int32_t nb, int32_t n_f
     if (q1 - q0 > static_cast<uint32_t>(kLongDtkpCol)) return;           // left to the wavefront-per-column kernel
     TopK<K> top;
     top.clear();
-    for (uint32_t q = q0; q < q1; ++q) offer_tuple<K>(top, col_ij[q], a0, b0, gm, fp, am, ap, bm, bp);
+    for (uint32_t q = q0; q < q1; ++q) offer_tuple<K>(top, col_ij[q], a0, b0, gm, fp, am, ap, bm, bp, fact_b);
     oprob[s * ldo + c] = top.store(om + idx * K, op + idx * K);
 }
 
@@ -113,7 +134,8 @@ dtkp_apply2_long_kernel(int32_t n_long, const uint32_t *__restrict__ long_cols, 
                         int32_t n_facts, const uint32_t *__restrict__ col_ptr, const uint32_t *__restrict__ col_ij,
                         GroupMasks gm, const float *__restrict__ fact_prob, const uint64_t *__restrict__ am,
                         const float *__restrict__ ap, const uint64_t *__restrict__ bm, const float *__restrict__ bp,
-                        uint64_t *__restrict__ om, float *__restrict__ op, float *__restrict__ oprob, int64_t ldo)
+                        const int32_t *__restrict__ fact_b, uint64_t *__restrict__ om, float *__restrict__ op,
+                        float *__restrict__ oprob, int64_t ldo)
 {
     const int64_t s = blockIdx.x / n_long;
     const uint32_t c = long_cols[blockIdx.x - s * n_long];
@@ -122,7 +144,7 @@ dtkp_apply2_long_kernel(int32_t n_long, const uint32_t *__restrict__ long_cols, 
     TopK<K> top;
     top.clear();
     for (uint32_t q = col_ptr[c] + threadIdx.x, q1 = col_ptr[c + 1]; q < q1; q += kWave)
-        offer_tuple<K>(top, col_ij[q], a0, b0, gm, fp, am, ap, bm, bp);
+        offer_tuple<K>(top, col_ij[q], a0, b0, gm, fp, am, ap, bm, bp, fact_b);
 #pragma unroll
     for (int d = 32; d >= 1; d >>= 1) {
         uint64_t pm[K];
@@ -147,15 +169,17 @@ dtkp_apply2_long_kernel(int32_t n_long, const uint32_t *__restrict__ long_cols, 
 template <int K>
 static void launch_apply2_k(int64_t total, const dol_fn_table *f, int32_t n_facts, const GroupMasks &gm,
                             const float *fact_prob, const uint64_t *am, const float *ap, const uint64_t *bm,
-                            const float *bp, uint64_t *om, float *op, float *oprob, int64_t ldo, hipStream_t st)
+                            const float *bp, const int32_t *fact_b, uint64_t *om, float *op, float *oprob, int64_t ldo,
+                            hipStream_t st)
 {
     hipLaunchKernelGGL(dtkp_apply2_kernel<K>, dim3(grid_t(total)), dim3(kThreadsT), 0, st, total, f->n_out, f->na,
-                       f->nb, n_facts, f->col_ptr.ptr, f->col_ij.ptr, gm, fact_prob, am, ap, bm, bp, om, op, oprob, ldo);
+                       f->nb, n_facts, f->col_ptr.ptr, f->col_ij.ptr, gm, fact_prob, am, ap, bm, bp, fact_b, om, op, oprob,
+                       ldo);
     const int64_t n_long = static_cast<int64_t>(f->dtkp_long_cols.n);
     if (n_long > 0)
         hipLaunchKernelGGL(dtkp_apply2_long_kernel<K>, dim3(static_cast<unsigned>(total / f->n_out * n_long)), dim3(kWave),
                            0, st, static_cast<int32_t>(n_long), f->dtkp_long_cols.ptr, f->n_out, f->na, f->nb, n_facts,
-                           f->col_ptr.ptr, f->col_ij.ptr, gm, fact_prob, am, ap, bm, bp, om, op, oprob, ldo);
+                           f->col_ptr.ptr, f->col_ij.ptr, gm, fact_prob, am, ap, bm, bp, fact_b, om, op, oprob, ldo);
 }
 
 #define DOL_DISPATCH_K(k, CALL)                                      \
@@ -173,13 +197,14 @@ static void launch_apply2_k(int64_t total, const dol_fn_table *f, int32_t n_fact
 
 dol_status launch_dtkp_apply2(const dol_fn_table *f, int32_t batch, int32_t k, int32_t n_facts, const GroupMasks &gm,
                               const float *fact_prob, const uint64_t *am, const float *ap, const uint64_t *bm,
-                              const float *bp, uint64_t *om, float *op, float *oprob, int64_t ldo, hipStream_t st)
+                              const float *bp, const int32_t *fact_b, uint64_t *om, float *op, float *oprob, int64_t ldo,
+                              hipStream_t st)
 {
     const int64_t total = static_cast<int64_t>(batch) * f->n_out;
     if (total == 0) return DOL_OK;
     if (static_cast<int64_t>(batch) * static_cast<int64_t>(f->dtkp_long_cols.n) > 0x7fffffffLL)
         return fail(DOL_EUNSUPPORTED, "batch x long table columns exceeds 2^31");
-#define CALL(KK) launch_apply2_k<KK>(total, f, n_facts, gm, fact_prob, am, ap, bm, bp, om, op, oprob, ldo, st)
+#define CALL(KK) launch_apply2_k<KK>(total, f, n_facts, gm, fact_prob, am, ap, bm, bp, fact_b, om, op, oprob, ldo, st)
     DOL_DISPATCH_K(k, CALL)
 #undef CALL
     DOL_HIP(hipGetLastError());

@@ -203,9 +203,12 @@ dol_status launch_damp_union_bwd(const UnionPlan *p, int32_t batch, const float 
 dol_status launch_dtkp_init(int32_t batch, int32_t n_sym, int32_t k, int32_t n_facts, const int32_t *d_fact_of_sym,
                             const float *fact_prob, uint64_t *mask, float *pprob, float *prob, int64_t ld,
                             hipStream_t st);
+// fact_b != nullptr: the second operand is an input Distribution under natural initialisation, symbol j = fact
+// fact_b[j] (device array); bm / bp are not read
 dol_status launch_dtkp_apply2(const dol_fn_table *f, int32_t batch, int32_t k, int32_t n_facts, const GroupMasks &gm,
                               const float *fact_prob, const uint64_t *am, const float *ap, const uint64_t *bm,
-                              const float *bp, uint64_t *om, float *op, float *oprob, int64_t ldo, hipStream_t st);
+                              const float *bp, const int32_t *fact_b, uint64_t *om, float *op, float *oprob, int64_t ldo,
+                              hipStream_t st);
 dol_status launch_dtkp_union(const UnionPlan *p, int32_t batch, int32_t k, const uint64_t *am, const float *ap,
                              const uint64_t *bm, const float *bp, uint64_t *om, float *op, float *oprob, int64_t ldo,
                              hipStream_t st);

@@ -442,7 +442,7 @@ class HwfPipeline(Program):
             grp = np.concatenate([np.full(len(x), t, np.int32) for t, x in enumerate(kept)])
             self.prov = dol.Prov(dol.DTKP, k, self.fact_prob, grp)
             self.xs = [dol.Dist(kept[t], self.fact_prob[:, off[t]:off[t + 1]]) for t in range(L)]
-            self.tags = [dol.Dist.empty(kept[t], B, device, k=k) for t in range(L)]
+            self.tags = [dol.Dist.empty(kept[0], B, device, k=k)]
         else:
             self.prov = None
             self.xs = [dol.Dist.empty(kept[t], B, device) for t in range(L)]
@@ -451,18 +451,24 @@ class HwfPipeline(Program):
         for t in range(L):
             self.launches.append(Launch("damp_gather_cols_kernel", lambda t=t: dol.filter(self.pos[t], self.keep[t], None, self.xs[t]),
                                         4 * B * (14 + self.xs[t].n_sym), 0, "fwd"))
-        if dtkp:
-            for t in range(L):
-                facts = np.arange(off[t], off[t + 1], dtype=np.int32)
-                self.launches.append(Launch("dtkp_init_kernel", lambda t=t, f=facts: dol.dtkp_init(self.tags[t], f, self.prov),
-                                            B * self.tags[t].n_sym * (4 + 12 * k + 4), 0, "fwd"))
+        facts = [np.arange(off[t], off[t + 1], dtype=np.int32) for t in range(L)]
+        if dtkp:                                     # only position 0 needs stored tags: the later positions enter
+            self.launches.append(Launch("dtkp_init_kernel", lambda: dol.dtkp_init(self.tags[0], facts[0], self.prov),
+                                        B * self.tags[0].n_sym * (4 + 12 * k + 4), 0, "fwd"))   # as input operands
         self.tables, self.accs, n_tup = [], [self.tags[0]], []
         for t in range(1, L):
             tb = dol.FnTable.create_dense(w["tables"][t - 1])
             self.tables.append(tb)
             n_tup.append(_n_tuples(w["tables"][t - 1]))
             out = dol.Dist.empty(tb.out_syms, B, device, k=k)
-            self.launches.append(_apply_fwd(self.accs[-1], self.tags[t], tb, out, n_tup[-1], self.prov, k))
+            if dtkp:
+                a = self.accs[-1]
+                self.launches.append(Launch("dtkp_apply2_kernel",
+                                            lambda a=a, t=t, tb=tb, out=out: dol.dtkp_apply2_input(a, facts[t], tb, self.prov, out),
+                                            B * (12 * k * (a.n_sym + out.n_sym) + 4 * (self.xs[t].n_sym + out.n_sym)),
+                                            B * n_tup[-1] * k, "fwd"))
+            else:
+                self.launches.append(_apply_fwd(self.accs[-1], self.tags[t], tb, out, n_tup[-1], self.prov, k))
             self.accs.append(out)
         self.final = dol.FnkTable.create_dense(w["final_map"])
         self.out = dol.Dist.empty(self.final.out_syms, B, device, k=k)
@@ -471,7 +477,7 @@ class HwfPipeline(Program):
         self.launches.append(Launch("dtkp_applyk_kernel" if dtkp else "damp_applyk_fwd_kernel",
                                     lambda: dol.apply_k([last], self.final, self.prov, self.out),
                                     B * per * (last.n_sym + self.out.n_sym), B * last.n_sym * max(k, 1), "fwd"))
-        n_ops = 2 * L + (L if dtkp else 0)
+        n_ops = 2 * L + (1 if dtkp else 0)
         if dtkp:
             self.launches.append(Launch("dtkp_prob_bwd_kernel", lambda: dol.dtkp_backward(self.out, self.prov, self.g, self.gfact),
                                         B * (self.out.n_sym * (12 * k + 4) + 8 * int(off[-1])), 0, "bwd"))

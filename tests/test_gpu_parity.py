@@ -1234,3 +1234,42 @@ def test_random_tables_differential_dtkp(dol, seed):
     gf = torch.empty((B, fp.shape[1]), device="cuda")
     dol.dtkp_backward(out, prov, dev(gsym), gf)
     assert_close(host(gf), want, "dtkp random table gradient, seed %d" % seed)
+
+
+@pytest.mark.parametrize("k", [1, 3])
+def test_dtkp_apply2_input_equals_init_then_apply2(dol, k):
+    """The second operand given by its facts: bit for bit what dol_dtkp_init + dol_apply2 give, on a table with
+    columns of every length, a first operand with several proofs per symbol, shared exclusion groups."""
+    B, nv = 50, 6
+    fp = np.concatenate([W.softmax_rows(W.normal(5600 + t, B * nv).reshape(B, nv)) for t in range(3)], axis=1)
+    grp = np.repeat(np.arange(3), nv).astype(np.int32)
+    prov = dol.Prov(dol.DTKP, k, dev(fp), grp)
+    d0, d1, d2 = (dol.Dist.empty(np.arange(nv), B, k=k) for _ in range(3))
+    for t, d in enumerate((d0, d1, d2)):
+        dol.dtkp_init(d, np.arange(nv) + nv * t, prov)
+    tab = (W.splitmix64(5700, np.arange(nv * nv)) % np.uint64(9)).astype(np.int32).reshape(nv, nv)
+    ft = dol.FnTable.create_dense(tab)
+    a = dol.Dist.empty(ft.out_syms, B, k=k)
+    dol.apply2(d0, d1, ft, prov, a)
+    # second operand: the facts of slot 2 in a permuted order, one of them used by two symbols, one fact of slot 1
+    fact_b = np.array([14, 12, 17, 12, 13, 15, 16, 7], np.int32)
+    table = (W.splitmix64(5800, np.arange(a.n_sym * fact_b.size)) % np.uint64(4)).astype(np.int32).reshape(a.n_sym, -1)
+    table.reshape(-1)[::5] = -1
+    f = dol.FnTable.create_dense(table)
+    b = dol.Dist.empty(np.arange(fact_b.size), B, k=k)
+    dol.dtkp_init(b, fact_b, prov)
+    want, got = dol.Dist.empty(f.out_syms, B, k=k), dol.Dist.empty(f.out_syms, B, k=k)
+    dol.apply2(a, b, f, prov, want)
+    dol.dtkp_apply2_input(a, fact_b, f, prov, got)
+    np.testing.assert_array_equal(host(got.proof_mask), host(want.proof_mask))
+    np.testing.assert_array_equal(host(got.proof_prob), host(want.proof_prob))
+    np.testing.assert_array_equal(host(got.prob), host(want.prob))
+    # and against the oracle's composition
+    am = oracle.dtkp_apply2(oracle.dense_to_triples(tab), nv, nv, k, grp, fp,
+                            oracle.dtkp_init(np.arange(nv), fp, k)[0], oracle.dtkp_init(np.arange(nv) + nv, fp, k)[0])[1]
+    _, om, op, opr = oracle.dtkp_apply2(oracle.dense_to_triples(table), a.n_sym, fact_b.size, k, grp, fp, am,
+                                        oracle.dtkp_init(fact_b, fp, k)[0])
+    np.testing.assert_array_equal(host(got.proof_mask).view(np.uint64), om)
+    np.testing.assert_array_equal(host(got.proof_prob), op)
+    with pytest.raises(dol.DolError):
+        dol.dtkp_apply2_input(a, np.full(fact_b.size, 18, np.int32), f, prov, got)
