@@ -85,11 +85,11 @@ damp_apply2_fwd_kernel(Rows R, const uint32_t *__restrict__ col_ptr, const uint3
     });
 }
 
-// One wavefront per (sample, long column).  The lanes stride over the column's tuples and their partial sums meet
-// by shuffles; this is not the order the clamp decision is defined in, so alongside the sum the lanes add up the
+// One workgroup of 1, 4 or 16 wavefronts (by the table's longest column) per (sample, long column).  The lanes stride
+// over the column's tuples and their partial sums meet by shuffles and, between wavefronts, through LDS; this is not the order the clamp decision is defined in, so alongside the sum the lanes add up the
 // terms' magnitudes, which bounds how far the two orders can lie apart (n roundings of relative size 2^-24 each
 // way).  Only a sum within that distance of 1 is taken again in the defining order, by every lane alike.
-__global__ void __launch_bounds__(kWave)
+__global__ void __launch_bounds__(1024)
 damp_apply2_fwd_long_kernel(int32_t n_long, const uint32_t *__restrict__ long_cols,
                             const uint32_t *__restrict__ col_ptr, const uint32_t *__restrict__ col_ij,
                             const float *__restrict__ a, int64_t lda, const float *__restrict__ b, int64_t ldb,
@@ -99,12 +99,14 @@ damp_apply2_fwd_long_kernel(int32_t n_long, const uint32_t *__restrict__ long_co
     const uint32_t c = long_cols[blockIdx.x - s * n_long];
     const float *ar = a + s * lda, *br = b + s * ldb;
     const uint32_t q0 = col_ptr[c], q1 = col_ptr[c + 1];
+    __shared__ float part[2][16];
+    const uint32_t step = blockDim.x;
     float acc = 0.0f, mag = 0.0f;
-    for (uint32_t q = q0 + threadIdx.x; q < q1; q += kGather * kWave) {
+    for (uint32_t q = q0 + threadIdx.x; q < q1; q += kGather * step) {
         uint32_t ij[kGather];
         float x[kGather], y[kGather];
 #pragma unroll
-        for (int u = 0; u < kGather; ++u) ij[u] = col_ij[min(q + u * kWave, q1 - 1)];
+        for (int u = 0; u < kGather; ++u) ij[u] = col_ij[min(q + u * step, q1 - 1)];
 #pragma unroll
         for (int u = 0; u < kGather; ++u) {
             x[u] = ar[ij[u] & 0xffffu];
@@ -112,7 +114,7 @@ damp_apply2_fwd_long_kernel(int32_t n_long, const uint32_t *__restrict__ long_co
         }
 #pragma unroll
         for (int u = 0; u < kGather; ++u)
-            if (q + u * kWave < q1) {
+            if (q + u * step < q1) {
                 acc = __builtin_fmaf(x[u], y[u], acc);
                 mag = __builtin_fmaf(fabsf(x[u]), fabsf(y[u]), mag);
             }
@@ -122,7 +124,15 @@ damp_apply2_fwd_long_kernel(int32_t n_long, const uint32_t *__restrict__ long_co
         acc += __shfl_xor(acc, d, kWave);
         mag += __shfl_xor(mag, d, kWave);
     }
-    const float slack = mag * (static_cast<float>(q1 - q0 + kWave) * 1.1920929e-7f);
+    if (step > kWave) {                             // uniform: the wavefronts' sums, added in wavefront order
+        const int wave = threadIdx.x / kWave, n_waves = step / kWave;
+        if ((threadIdx.x & (kWave - 1)) == 0) { part[0][wave] = acc; part[1][wave] = mag; }
+        __syncthreads();
+        if (wave != 0) return;
+        acc = 0.0f, mag = 0.0f;
+        for (int w = 0; w < n_waves; ++w) { acc += part[0][w]; mag += part[1][w]; }
+    }
+    const float slack = mag * (static_cast<float>(q1 - q0 + step) * 1.1920929e-7f);
     float pre = acc;
     if (fabsf(acc - 1.0f) <= slack) pre = column_sum(ar, br, col_ij, q0, q1);
     if (threadIdx.x == 0) out[s * ldo + c] = fminf(pre, 1.0f);
@@ -180,15 +190,21 @@ damp_byj_fwd_kernel(Rows R, int32_t nb, const uint16_t *__restrict__ src, const 
     default: CALL(16); break;       \
     }
 
-static dol_status launch_fwd_waves(const dol_fn_table *f, const DevArray<uint32_t> &cols, int32_t batch, const float *a,
-                                   int64_t lda, const float *b, int64_t ldb, float *out, int64_t ldo, hipStream_t st)
+static dol_status launch_fwd_waves(const dol_fn_table *f, const DevArray<uint32_t> &cols, int32_t n_huge, int32_t batch,
+                                   const float *a, int64_t lda, const float *b, int64_t ldb, float *out, int64_t ldo,
+                                   hipStream_t st)
 {
     const int64_t n_long = static_cast<int64_t>(cols.n);
     if (n_long == 0) return DOL_OK;
     if (batch * n_long > 0x7fffffffLL)
         return fail(DOL_EUNSUPPORTED, "batch x long table columns = %lld exceeds 2^31", static_cast<long long>(batch * n_long));
-    hipLaunchKernelGGL(damp_apply2_fwd_long_kernel, dim3(static_cast<unsigned>(batch * n_long)), dim3(kWave), 0, st,
-                       static_cast<int32_t>(n_long), cols.ptr, f->col_ptr.ptr, f->col_ij.ptr, a, lda, b, ldb, out, ldo);
+    if (n_huge > 0)                                  // the list's first n_huge columns: 16 wavefronts each
+        hipLaunchKernelGGL(damp_apply2_fwd_long_kernel, dim3(static_cast<unsigned>(batch) * n_huge), dim3(1024), 0, st, n_huge,
+                           cols.ptr, f->col_ptr.ptr, f->col_ij.ptr, a, lda, b, ldb, out, ldo);
+    if (n_long > n_huge)
+        hipLaunchKernelGGL(damp_apply2_fwd_long_kernel, dim3(static_cast<unsigned>(batch * (n_long - n_huge))), dim3(kWave), 0,
+                           st, static_cast<int32_t>(n_long - n_huge), cols.ptr + n_huge, f->col_ptr.ptr, f->col_ij.ptr, a, lda,
+                           b, ldb, out, ldo);
     DOL_HIP(hipGetLastError());
     return DOL_OK;
 }
@@ -208,12 +224,12 @@ dol_status launch_damp_apply2_fwd(const dol_fn_table *f, int32_t batch, const fl
         DOL_DISPATCH_NBP(f->byj_nbp, CALL)
 #undef CALL
         DOL_HIP(hipGetLastError());
-        return launch_fwd_waves(f, f->byj_wave_cols, batch, a, lda, b, ldb, out, ldo, st);
+        return launch_fwd_waves(f, f->byj_wave_cols, f->n_huge_byj_cols, batch, a, lda, b, ldb, out, ldo, st);
     }
     hipLaunchKernelGGL(damp_apply2_fwd_kernel, dim3(R.grid), dim3(kThreads), 0, st, R, f->col_ptr.ptr, f->col_ij.ptr,
                        reinterpret_cast<const uint4 *>(f->col_head.ptr), a, lda, b, ldb, out, ldo);
     DOL_HIP(hipGetLastError());
-    return launch_fwd_waves(f, f->long_cols, batch, a, lda, b, ldb, out, ldo, st);
+    return launch_fwd_waves(f, f->long_cols, f->n_huge_cols, batch, a, lda, b, ldb, out, ldo, st);
 }
 
 // ---------------------------------------------------------------- apply2 backward

@@ -124,27 +124,15 @@ dtkp_apply2_kernel(int64_t total, int32_t S, int32_t na, int32_t nb, int32_t n_f
     oprob[s * ldo + c] = top.store(om + idx * K, op + idx * K);
 }
 
-// One wavefront per (sample, long column): every lane streams a share of the column's tuples through a list of its
-// own; the lists then meet by log2(64) exchange rounds in which each lane offers its partner's entries to its own
-// list.  The list order is total on distinct proofs and repeated proofs are one proof, so the result does not depend
+// One workgroup of 1, 4 or 16 wavefronts (by the table's longest column) per (sample, long column): every lane streams
+// a share of the column's tuples through a list of its own; the lists of a wavefront then meet by log2(64) exchange
+// rounds in which each lane offers its partner's entries to its own list, the wavefronts' lists through LDS and one
+// more such merge.  The list order is total on distinct proofs and repeated proofs are one proof, so the result does not depend
 // on how the candidates were split.
+// All lanes end with the merge of the 64 lanes' lists.
 template <int K>
-__global__ void __launch_bounds__(kWave)
-dtkp_apply2_long_kernel(int32_t n_long, const uint32_t *__restrict__ long_cols, int32_t S, int32_t na, int32_t nb,
-                        int32_t n_facts, const uint32_t *__restrict__ col_ptr, const uint32_t *__restrict__ col_ij,
-                        GroupMasks gm, const float *__restrict__ fact_prob, const uint64_t *__restrict__ am,
-                        const float *__restrict__ ap, const uint64_t *__restrict__ bm, const float *__restrict__ bp,
-                        const int32_t *__restrict__ fact_b, uint64_t *__restrict__ om, float *__restrict__ op,
-                        float *__restrict__ oprob, int64_t ldo)
+__device__ __forceinline__ void merge_lists(TopK<K> &top)
 {
-    const int64_t s = blockIdx.x / n_long;
-    const uint32_t c = long_cols[blockIdx.x - s * n_long];
-    const float *fp = fact_prob + s * n_facts;
-    const int64_t a0 = s * na * K, b0 = s * nb * K;
-    TopK<K> top;
-    top.clear();
-    for (uint32_t q = col_ptr[c] + threadIdx.x, q1 = col_ptr[c + 1]; q < q1; q += kWave)
-        offer_tuple<K>(top, col_ij[q], a0, b0, gm, fp, am, ap, bm, bp, fact_b);
 #pragma unroll
     for (int d = 32; d >= 1; d >>= 1) {
         uint64_t pm[K];
@@ -159,6 +147,43 @@ dtkp_apply2_long_kernel(int32_t n_long, const uint32_t *__restrict__ long_cols, 
 #pragma unroll
         for (int x = 0; x < K; ++x)
             if (pm[x] != kAbsent) top.insert(pm[x], pp[x]);
+    }
+}
+
+template <int K>
+__global__ void __launch_bounds__(1024)
+dtkp_apply2_long_kernel(int32_t n_long, const uint32_t *__restrict__ long_cols, int32_t S, int32_t na, int32_t nb,
+                        int32_t n_facts, const uint32_t *__restrict__ col_ptr, const uint32_t *__restrict__ col_ij,
+                        GroupMasks gm, const float *__restrict__ fact_prob, const uint64_t *__restrict__ am,
+                        const float *__restrict__ ap, const uint64_t *__restrict__ bm, const float *__restrict__ bp,
+                        const int32_t *__restrict__ fact_b, uint64_t *__restrict__ om, float *__restrict__ op,
+                        float *__restrict__ oprob, int64_t ldo)
+{
+    const int64_t s = blockIdx.x / n_long;
+    const uint32_t c = long_cols[blockIdx.x - s * n_long];
+    const float *fp = fact_prob + s * n_facts;
+    const int64_t a0 = s * na * K, b0 = s * nb * K;
+    TopK<K> top;
+    top.clear();
+    for (uint32_t q = col_ptr[c] + threadIdx.x, q1 = col_ptr[c + 1]; q < q1; q += blockDim.x)
+        offer_tuple<K>(top, col_ij[q], a0, b0, gm, fp, am, ap, bm, bp, fact_b);
+    merge_lists<K>(top);
+    if (blockDim.x > kWave) {                       // uniform: the wavefronts' lists meet in the first wavefront
+        __shared__ uint64_t lm[16][K];
+        __shared__ float lp[16][K];
+        const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave, n_waves = blockDim.x / kWave;
+        if (lane == 0) {
+#pragma unroll
+            for (int x = 0; x < K; ++x) { lm[wave][x] = top.m[x]; lp[wave][x] = top.p[x]; }
+        }
+        __syncthreads();
+        if (wave != 0) return;
+        top.clear();
+        if (lane < n_waves) {
+#pragma unroll
+            for (int x = 0; x < K; ++x) { top.m[x] = lm[lane][x]; top.p[x] = lp[lane][x]; }
+        }
+        merge_lists<K>(top);
     }
     if (threadIdx.x == 0) {
         const int64_t idx = s * S + c;
@@ -176,10 +201,15 @@ static void launch_apply2_k(int64_t total, const dol_fn_table *f, int32_t n_fact
                        f->nb, n_facts, f->col_ptr.ptr, f->col_ij.ptr, gm, fact_prob, am, ap, bm, bp, fact_b, om, op, oprob,
                        ldo);
     const int64_t n_long = static_cast<int64_t>(f->dtkp_long_cols.n);
-    if (n_long > 0)
-        hipLaunchKernelGGL(dtkp_apply2_long_kernel<K>, dim3(static_cast<unsigned>(total / f->n_out * n_long)), dim3(kWave),
-                           0, st, static_cast<int32_t>(n_long), f->dtkp_long_cols.ptr, f->n_out, f->na, f->nb, n_facts,
+    const int64_t n_huge = f->n_huge_dtkp_cols, batch = total / f->n_out;
+    if (n_huge > 0)                                  // the list's first n_huge columns: 16 wavefronts each
+        hipLaunchKernelGGL(dtkp_apply2_long_kernel<K>, dim3(static_cast<unsigned>(batch * n_huge)), dim3(1024), 0, st,
+                           static_cast<int32_t>(n_huge), f->dtkp_long_cols.ptr, f->n_out, f->na, f->nb, n_facts,
                            f->col_ptr.ptr, f->col_ij.ptr, gm, fact_prob, am, ap, bm, bp, fact_b, om, op, oprob, ldo);
+    if (n_long > n_huge)
+        hipLaunchKernelGGL(dtkp_apply2_long_kernel<K>, dim3(static_cast<unsigned>(batch * (n_long - n_huge))), dim3(kWave), 0,
+                           st, static_cast<int32_t>(n_long - n_huge), f->dtkp_long_cols.ptr + n_huge, f->n_out, f->na, f->nb,
+                           n_facts, f->col_ptr.ptr, f->col_ij.ptr, gm, fact_prob, am, ap, bm, bp, fact_b, om, op, oprob, ldo);
 }
 
 #define DOL_DISPATCH_K(k, CALL)                                      \

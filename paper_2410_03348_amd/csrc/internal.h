@@ -60,6 +60,8 @@ struct DevArray {
 constexpr int kLongTableRow = 64;   // backward: table rows with more tuples are reduced by a whole wavefront
 constexpr int kLongTableCol = 64;   // forward: output columns with more tuples are summed by a whole wavefront
 constexpr int kLongDtkpCol = 16;    // the same under DTKP, where a tuple costs a few hundred instructions
+constexpr int kHugeTableCol = 4096; // columns with more tuples get a workgroup of 16 wavefronts instead of one wavefront
+constexpr int kHugeDtkpCol = 1024;  // the same under DTKP
 constexpr int kByJMax = 16;         // tables whose second operand has at most this many symbols get dense per-j maps
 constexpr int kByJMaxNa = 65000;    // ... and whose first operand leaves room for the three marks below
 constexpr uint16_t kByJNone = 0xFFFF, kByJWave = 0xFFFE, kByJList = 0xFFFD;
@@ -95,6 +97,8 @@ struct dol_fn_table {
     dol::DevArray<uint32_t> long_rows;
     // output columns with more than dol::kLongTableCol / dol::kLongDtkpCol tuples
     dol::DevArray<uint32_t> long_cols, dtkp_long_cols;
+    // each list starts with its huge columns (more than dol::kHugeTableCol / dol::kHugeDtkpCol tuples)
+    int32_t n_huge_cols = 0, n_huge_dtkp_cols = 0, n_huge_byj_cols = 0;
     // LDS gather kernels (damp_lds.hip): per output column (forward), row of a, row of b (backward) a list of
     // 16-byte packets of four tuples; *_ptr[x] .. *_ptr[x+1] are the packets of x
     bool lds_fwd_ok = false, lds_bwd_ok = false;

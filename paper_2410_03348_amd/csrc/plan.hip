@@ -119,11 +119,20 @@ static dol_status build_table(int32_t na, int32_t nb, std::vector<Tuple> &tup, d
     for (int32_t j = 0; j < nb; ++j)
         if (rowb_ptr[j + 1] - rowb_ptr[j] > static_cast<uint32_t>(kLongTableRow)) long_rows.push_back(static_cast<uint32_t>(na + j));
 
-    std::vector<uint32_t> long_cols, dtkp_long_cols;
-    for (int32_t c = 0; c < S; ++c) {
-        if (col_ptr[c + 1] - col_ptr[c] > static_cast<uint32_t>(kLongTableCol)) long_cols.push_back(static_cast<uint32_t>(c));
-        if (col_ptr[c + 1] - col_ptr[c] > static_cast<uint32_t>(kLongDtkpCol)) dtkp_long_cols.push_back(static_cast<uint32_t>(c));
-    }
+    // long columns, the huge ones first
+    auto long_list = [&](uint32_t longer_than, uint32_t huge_above, int32_t *n_huge) {
+        std::vector<uint32_t> huge, rest;
+        for (int32_t c = 0; c < S; ++c) {
+            const uint32_t len = col_ptr[c + 1] - col_ptr[c];
+            if (len > huge_above) huge.push_back(static_cast<uint32_t>(c));
+            else if (len > longer_than) rest.push_back(static_cast<uint32_t>(c));
+        }
+        *n_huge = static_cast<int32_t>(huge.size());
+        huge.insert(huge.end(), rest.begin(), rest.end());
+        return huge;
+    };
+    const std::vector<uint32_t> long_cols = long_list(kLongTableCol, kHugeTableCol, &tb->n_huge_cols);
+    const std::vector<uint32_t> dtkp_long_cols = long_list(kLongDtkpCol, kHugeDtkpCol, &tb->n_huge_dtkp_cols);
 
     if (hipGetDevice(&tb->device) != hipSuccess) tb->device = 0;
     hipError_t e;
@@ -145,7 +154,7 @@ static dol_status build_table(int32_t na, int32_t nb, std::vector<Tuple> &tup, d
         const int32_t nbp = nb <= 4 ? 4 : nb <= 8 ? 8 : nb <= 10 ? 10 : 16;
         tb->byj_nbp = nbp;
         std::vector<uint16_t> src(static_cast<size_t>(nbp) * S, kByJNone), colof(static_cast<size_t>(nbp) * na, kByJNone);
-        std::vector<uint32_t> wave_cols;
+        std::vector<uint32_t> wave_cols, huge_cols;
         for (int32_t c = 0; c < S; ++c) {
             bool regular = col_ptr[c + 1] - col_ptr[c] <= static_cast<uint32_t>(kLongTableCol);
             for (uint32_t q = col_ptr[c]; q < col_ptr[c + 1] && regular; ++q) {
@@ -157,9 +166,12 @@ static dol_status build_table(int32_t na, int32_t nb, std::vector<Tuple> &tup, d
                 const bool is_long = col_ptr[c + 1] - col_ptr[c] > static_cast<uint32_t>(kLongTableCol);
                 for (int32_t j = 0; j < nb; ++j) src[static_cast<size_t>(j) * S + c] = kByJNone;
                 src[c] = is_long ? kByJWave : kByJList;
-                if (is_long) wave_cols.push_back(static_cast<uint32_t>(c));
+                if (is_long) (col_ptr[c + 1] - col_ptr[c] > static_cast<uint32_t>(kHugeTableCol) ? huge_cols : wave_cols).push_back(static_cast<uint32_t>(c));
             }
         }
+        tb->n_huge_byj_cols = static_cast<int32_t>(huge_cols.size());
+        huge_cols.insert(huge_cols.end(), wave_cols.begin(), wave_cols.end());
+        wave_cols.swap(huge_cols);
         for (size_t t = 0; t < tup.size(); ++t) colof[static_cast<size_t>(tup[t].j) * na + tup[t].i] = static_cast<uint16_t>(col[t]);
         if ((e = tb->byj_src.upload(src)) != hipSuccess || (e = tb->byj_col.upload(colof)) != hipSuccess ||
             (e = tb->byj_wave_cols.upload(wave_cols)) != hipSuccess)
