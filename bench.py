@@ -123,17 +123,23 @@ def cpu_baseline(cfg, w, sample_ops, budget_s):
     run = {1: OP.sum2_fwd, 2: OP.sum_chain_fwd_bwd, 3: OP.hashed_pipeline_fwd_bwd, 4: OP.dtkp_sum_chain,
            5: OP.grid_reach_fwd_bwd, 6: OP.product_chain_fwd_bwd, 7: OP.hwf_pipeline_dtkp, 8: OP.hwf_pipeline_damp}[cfg]
     want = int(os.environ.get("OMP_NUM_THREADS", "0") or 0) or (os.cpu_count() or 1)
-    cores = oracle.set_threads(min(want, os.cpu_count() or 1))
-    run(w)                                   # build + page in
-    reps, t0 = 0, time.perf_counter()
-    while True:
-        run(w)
-        reps += 1
-        el = time.perf_counter() - t0
-        if el >= budget_s:
-            break
+
+    def timed(threads, seconds):
+        cores = oracle.set_threads(threads)
+        run(w)                               # build + page in
+        reps, t0 = 0, time.perf_counter()
+        while True:
+            run(w)
+            reps += 1
+            el = time.perf_counter() - t0
+            if el >= seconds:
+                return cores, reps, el
+
+    cores, reps, el = timed(min(want, os.cpu_count() or 1), 0.75 * budget_s)
+    _, reps1, el1 = timed(1, 0.25 * budget_s)
     return dict(value=round(sample_ops * reps / el, 1), unit="sample-ops/s", cores=cores, kind="oracle",
-                sample="%d full passes of the same workload (batch %d) in %.1f s" % (reps, w["batch"], el))
+                sample="%d full passes of the same workload (batch %d) in %.1f s" % (reps, w["batch"], el),
+                single_thread_value=round(sample_ops * reps1 / el1, 1))
 
 
 def main():
