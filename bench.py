@@ -53,6 +53,23 @@ def time_step(prog, torch, steps, warmup, mode):
     return (time.perf_counter() - t0) * 1e3 / steps
 
 
+def measured_copy_gbs(torch, mib=1024, reps=5):
+    """Read + write rate of a plain device-to-device copy of `mib` MiB (the runtime's copy kernel), for setting the
+    published HBM peak beside what a streaming kernel reaches on this device."""
+    n = mib * (1 << 20) // 4
+    src = torch.full((n,), 1.0, dtype=torch.float32, device="cuda")
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(reps):
+        dst.copy_(src)
+    e1.record()
+    torch.cuda.synchronize()
+    return round(2.0 * mib * (1 << 20) * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)
+
+
 def time_launches(prog, torch, repeats):
     """Average duration of every launch of a step: `repeats` back-to-back launches between two HIP events on
     the launch stream.  Returns {kernel: dict(launches, ms, bytes, macs)} summed over one step."""
@@ -211,6 +228,7 @@ def main():
         "roofline": roof,
         "kernels": kernel_table(per_kernel),
     }
+    out["roofline"]["hbm_copy_gbs_measured"] = measured_copy_gbs(torch)
     if getattr(prog, "candidate_slots", 0):     # DTKP: proof pairs offered to the top-k lists, per second
         out["config"]["candidate_slots_per_step"] = prog.candidate_slots
         out["candidate_slots_per_s"] = round(prog.candidate_slots / (ms * 1e-3), 1)
