@@ -29,7 +29,8 @@ struct dol_fnk_table {
     dol::DevArray<uint32_t> row_ptr;     // [sum n_sym + 1]
     dol::DevArray<uint32_t> row_tup;     // [n_tuples*K] grouped-tuple numbers of each operand row, ascending
     dol::DevArray<uint32_t> long_cols;   // columns with more than dol::kLongTableCol tuples
-    dol::DevArray<uint32_t> dtkp_long_cols;   // ... more than dol::kLongDtkpCol
+    dol::DevArray<uint32_t> dtkp_long_cols;   // ... more than dol::kLongDtkpCol: first those above dol::kWaveDtkpCol
+    int32_t n_wave_dtkp_cols = 0;             // (one wavefront each), then the shorter ones (four to a wavefront)
     // unary functions (K = 1): the first eight symbols of every image again, 16 bytes per column (0xFFFF = none), and
     // the column of every symbol (-1: rejected)
     dol::DevArray<uint16_t> unary_head;
@@ -366,22 +367,33 @@ dtkp_applyk_long_kernel(int32_t n_long, const uint32_t *__restrict__ long_cols, 
     top.clear();
     for (uint32_t q = col_ptr[c] + threadIdx.x, q1 = col_ptr[c + 1]; q < q1; q += kWave)
         offer_tuple_k<KP>(top, tup + static_cast<size_t>(q) * arity, s, arity, in, gm, fp);
-#pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) {
-        uint64_t pm[KP];
-        float pp[KP];
-#pragma unroll
-        for (int x = 0; x < KP; ++x) {
-            const uint32_t lo = __shfl_xor(static_cast<uint32_t>(top.m[x]), d, kWave);
-            const uint32_t hi = __shfl_xor(static_cast<uint32_t>(top.m[x] >> 32), d, kWave);
-            pm[x] = (static_cast<uint64_t>(hi) << 32) | lo;
-            pp[x] = __shfl_xor(top.p[x], d, kWave);
-        }
-#pragma unroll
-        for (int x = 0; x < KP; ++x)
-            if (pm[x] != kAbsent) top.insert(pm[x], pp[x]);
-    }
+    merge_lists<KP>(top);
     if (threadIdx.x == 0) {
+        const int64_t idx = s * S + c;
+        oprob[s * ldo + c] = top.store(om + idx * KP, op + idx * KP);
+    }
+}
+
+// Columns of a few dozen tuples: four to a wavefront, 16 lanes each.
+template <int KP>
+__global__ void __launch_bounds__(kWave)
+dtkp_applyk_mid_kernel(int32_t n_mid, const uint32_t *__restrict__ cols, int32_t S, int32_t arity, KProofs in,
+                       const uint32_t *__restrict__ col_ptr, const uint16_t *__restrict__ tup, GroupMasks gm,
+                       int32_t n_facts, const float *__restrict__ fact_prob, uint64_t *__restrict__ om,
+                       float *__restrict__ op, float *__restrict__ oprob, int64_t ldo)
+{
+    const int32_t quads = (n_mid + 3) / 4;
+    const int64_t s = blockIdx.x / quads;
+    const int32_t ci = static_cast<int32_t>(blockIdx.x - s * quads) * 4 + static_cast<int32_t>(threadIdx.x / 16);
+    if (ci >= n_mid) return;                        // a whole group of 16 lanes at once
+    const uint32_t c = cols[ci];
+    const float *fp = fact_prob + s * n_facts;
+    TopK<KP> top;
+    top.clear();
+    for (uint32_t q = col_ptr[c] + (threadIdx.x & 15), q1 = col_ptr[c + 1]; q < q1; q += 16)
+        offer_tuple_k<KP>(top, tup + static_cast<size_t>(q) * arity, s, arity, in, gm, fp);
+    merge_lists<KP, 16>(top);
+    if ((threadIdx.x & 15) == 0) {
         const int64_t idx = s * S + c;
         oprob[s * ldo + c] = top.store(om + idx * KP, op + idx * KP);
     }
@@ -394,10 +406,15 @@ static void launch_dtkp_k(int64_t total, const dol_fnk_table *f, const KProofs &
     hipLaunchKernelGGL(dtkp_applyk_kernel<KP>, dim3(static_cast<unsigned>((total + kThreadsP - 1) / kThreadsP)),
                        dim3(kThreadsP), 0, st, total, f->n_out, f->K, in, f->col_ptr.ptr, f->tup.ptr, gm, n_facts,
                        fact_prob, om, op, oprob, ldo);
-    const int64_t n_long = static_cast<int64_t>(f->dtkp_long_cols.n);
-    if (n_long > 0)
-        hipLaunchKernelGGL(dtkp_applyk_long_kernel<KP>, dim3(static_cast<unsigned>(total / f->n_out * n_long)), dim3(kWave),
-                           0, st, static_cast<int32_t>(n_long), f->dtkp_long_cols.ptr, f->n_out, f->K, in, f->col_ptr.ptr,
+    const int64_t n_wave = f->n_wave_dtkp_cols, n_mid = static_cast<int64_t>(f->dtkp_long_cols.n) - n_wave;
+    const int64_t batch = total / f->n_out;
+    if (n_wave > 0)
+        hipLaunchKernelGGL(dtkp_applyk_long_kernel<KP>, dim3(static_cast<unsigned>(batch * n_wave)), dim3(kWave), 0, st,
+                           static_cast<int32_t>(n_wave), f->dtkp_long_cols.ptr, f->n_out, f->K, in, f->col_ptr.ptr, f->tup.ptr,
+                           gm, n_facts, fact_prob, om, op, oprob, ldo);
+    if (n_mid > 0)
+        hipLaunchKernelGGL(dtkp_applyk_mid_kernel<KP>, dim3(static_cast<unsigned>(batch * ((n_mid + 3) / 4))), dim3(kWave), 0, st,
+                           static_cast<int32_t>(n_mid), f->dtkp_long_cols.ptr + n_wave, f->n_out, f->K, in, f->col_ptr.ptr,
                            f->tup.ptr, gm, n_facts, fact_prob, om, op, oprob, ldo);
 }
 
@@ -469,11 +486,15 @@ static dol_status build_k(int32_t K, const int32_t *n_sym, int64_t n, const int3
             for (int l = 0; l < K; ++l) row_tup[fill[tb->row_base[l] + tup[t * K + l]]++] = static_cast<uint32_t>(t);
     }
 
-    std::vector<uint32_t> long_cols, dtkp_long_cols;
+    std::vector<uint32_t> long_cols, dtkp_long_cols, dtkp_mid_cols;
     for (int32_t c = 0; c < S; ++c) {
-        if (col_ptr[c + 1] - col_ptr[c] > static_cast<uint32_t>(kLongTableCol)) long_cols.push_back(static_cast<uint32_t>(c));
-        if (col_ptr[c + 1] - col_ptr[c] > static_cast<uint32_t>(kLongDtkpCol)) dtkp_long_cols.push_back(static_cast<uint32_t>(c));
+        const uint32_t len = col_ptr[c + 1] - col_ptr[c];
+        if (len > static_cast<uint32_t>(kLongTableCol)) long_cols.push_back(static_cast<uint32_t>(c));
+        if (len > static_cast<uint32_t>(kWaveDtkpCol)) dtkp_long_cols.push_back(static_cast<uint32_t>(c));
+        else if (len > static_cast<uint32_t>(kLongDtkpCol)) dtkp_mid_cols.push_back(static_cast<uint32_t>(c));
     }
+    tb->n_wave_dtkp_cols = static_cast<int32_t>(dtkp_long_cols.size());
+    dtkp_long_cols.insert(dtkp_long_cols.end(), dtkp_mid_cols.begin(), dtkp_mid_cols.end());
 
     if (K == 1) {
         std::vector<uint16_t> head(static_cast<size_t>(S) * 8, 0xFFFFu);

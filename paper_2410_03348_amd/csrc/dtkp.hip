@@ -129,27 +129,6 @@ dtkp_apply2_kernel(int64_t total, int32_t S, int32_t na, int32_t nb, int32_t n_f
 // rounds in which each lane offers its partner's entries to its own list, the wavefronts' lists through LDS and one
 // more such merge.  The list order is total on distinct proofs and repeated proofs are one proof, so the result does not depend
 // on how the candidates were split.
-// All lanes end with the merge of the 64 lanes' lists.
-template <int K>
-__device__ __forceinline__ void merge_lists(TopK<K> &top)
-{
-#pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) {
-        uint64_t pm[K];
-        float pp[K];
-#pragma unroll
-        for (int x = 0; x < K; ++x) {
-            const uint32_t lo = __shfl_xor(static_cast<uint32_t>(top.m[x]), d, kWave);
-            const uint32_t hi = __shfl_xor(static_cast<uint32_t>(top.m[x] >> 32), d, kWave);
-            pm[x] = (static_cast<uint64_t>(hi) << 32) | lo;
-            pp[x] = __shfl_xor(top.p[x], d, kWave);
-        }
-#pragma unroll
-        for (int x = 0; x < K; ++x)
-            if (pm[x] != kAbsent) top.insert(pm[x], pp[x]);
-    }
-}
-
 template <int K>
 __global__ void __launch_bounds__(1024)
 dtkp_apply2_long_kernel(int32_t n_long, const uint32_t *__restrict__ long_cols, int32_t S, int32_t na, int32_t nb,
@@ -191,6 +170,33 @@ dtkp_apply2_long_kernel(int32_t n_long, const uint32_t *__restrict__ long_cols, 
     }
 }
 
+// Columns of a few dozen tuples: four to a wavefront, 16 lanes each.
+template <int K>
+__global__ void __launch_bounds__(kWave)
+dtkp_apply2_mid_kernel(int32_t n_mid, const uint32_t *__restrict__ cols, int32_t S, int32_t na, int32_t nb, int32_t n_facts,
+                       const uint32_t *__restrict__ col_ptr, const uint32_t *__restrict__ col_ij, GroupMasks gm,
+                       const float *__restrict__ fact_prob, const uint64_t *__restrict__ am, const float *__restrict__ ap,
+                       const uint64_t *__restrict__ bm, const float *__restrict__ bp, const int32_t *__restrict__ fact_b,
+                       uint64_t *__restrict__ om, float *__restrict__ op, float *__restrict__ oprob, int64_t ldo)
+{
+    const int32_t quads = (n_mid + 3) / 4;
+    const int64_t s = blockIdx.x / quads;
+    const int32_t ci = static_cast<int32_t>(blockIdx.x - s * quads) * 4 + static_cast<int32_t>(threadIdx.x / 16);
+    if (ci >= n_mid) return;                        // a whole group of 16 lanes at once
+    const uint32_t c = cols[ci];
+    const float *fp = fact_prob + s * n_facts;
+    const int64_t a0 = s * na * K, b0 = s * nb * K;
+    TopK<K> top;
+    top.clear();
+    for (uint32_t q = col_ptr[c] + (threadIdx.x & 15), q1 = col_ptr[c + 1]; q < q1; q += 16)
+        offer_tuple<K>(top, col_ij[q], a0, b0, gm, fp, am, ap, bm, bp, fact_b);
+    merge_lists<K, 16>(top);
+    if ((threadIdx.x & 15) == 0) {
+        const int64_t idx = s * S + c;
+        oprob[s * ldo + c] = top.store(om + idx * K, op + idx * K);
+    }
+}
+
 template <int K>
 static void launch_apply2_k(int64_t total, const dol_fn_table *f, int32_t n_facts, const GroupMasks &gm,
                             const float *fact_prob, const uint64_t *am, const float *ap, const uint64_t *bm,
@@ -206,9 +212,14 @@ static void launch_apply2_k(int64_t total, const dol_fn_table *f, int32_t n_fact
         hipLaunchKernelGGL(dtkp_apply2_long_kernel<K>, dim3(static_cast<unsigned>(batch * n_huge)), dim3(1024), 0, st,
                            static_cast<int32_t>(n_huge), f->dtkp_long_cols.ptr, f->n_out, f->na, f->nb, n_facts,
                            f->col_ptr.ptr, f->col_ij.ptr, gm, fact_prob, am, ap, bm, bp, fact_b, om, op, oprob, ldo);
-    if (n_long > n_huge)
-        hipLaunchKernelGGL(dtkp_apply2_long_kernel<K>, dim3(static_cast<unsigned>(batch * (n_long - n_huge))), dim3(kWave), 0,
-                           st, static_cast<int32_t>(n_long - n_huge), f->dtkp_long_cols.ptr + n_huge, f->n_out, f->na, f->nb,
+    const int64_t n_wave = f->n_wave_dtkp_cols, n_mid = n_long - n_huge - n_wave;
+    if (n_wave > 0)
+        hipLaunchKernelGGL(dtkp_apply2_long_kernel<K>, dim3(static_cast<unsigned>(batch * n_wave)), dim3(kWave), 0, st,
+                           static_cast<int32_t>(n_wave), f->dtkp_long_cols.ptr + n_huge, f->n_out, f->na, f->nb, n_facts,
+                           f->col_ptr.ptr, f->col_ij.ptr, gm, fact_prob, am, ap, bm, bp, fact_b, om, op, oprob, ldo);
+    if (n_mid > 0)
+        hipLaunchKernelGGL(dtkp_apply2_mid_kernel<K>, dim3(static_cast<unsigned>(batch * ((n_mid + 3) / 4))), dim3(kWave), 0, st,
+                           static_cast<int32_t>(n_mid), f->dtkp_long_cols.ptr + n_huge + n_wave, f->n_out, f->na, f->nb,
                            n_facts, f->col_ptr.ptr, f->col_ij.ptr, gm, fact_prob, am, ap, bm, bp, fact_b, om, op, oprob, ldo);
 }
 

@@ -96,4 +96,25 @@ __device__ __forceinline__ float union_prob(uint64_t ma, float pa, uint64_t mb, 
     return proof_prob(ma | mb, fp);
 }
 
+// All lanes of every aligned group of LANES lanes end with the merge of the group's lists.
+template <int K, int LANES = 64>
+__device__ __forceinline__ void merge_lists(TopK<K> &top)
+{
+#pragma unroll
+    for (int d = LANES / 2; d >= 1; d >>= 1) {
+        uint64_t pm[K];
+        float pp[K];
+#pragma unroll
+        for (int x = 0; x < K; ++x) {
+            const uint32_t lo = __shfl_xor(static_cast<uint32_t>(top.m[x]), d, 64);
+            const uint32_t hi = __shfl_xor(static_cast<uint32_t>(top.m[x] >> 32), d, 64);
+            pm[x] = (static_cast<uint64_t>(hi) << 32) | lo;
+            pp[x] = __shfl_xor(top.p[x], d, 64);
+        }
+#pragma unroll
+        for (int x = 0; x < K; ++x)
+            if (pm[x] != kAbsent) top.insert(pm[x], pp[x]);
+    }
+}
+
 }  // namespace dol

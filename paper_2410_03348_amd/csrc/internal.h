@@ -62,6 +62,7 @@ constexpr int kLongTableCol = 64;   // forward: output columns with more tuples 
 constexpr int kLongDtkpCol = 16;    // the same under DTKP, where a tuple costs a few hundred instructions
 constexpr int kHugeTableCol = 4096; // columns with more tuples get a workgroup of 16 wavefronts instead of one wavefront
 constexpr int kHugeDtkpCol = 1024;  // the same under DTKP
+constexpr int kWaveDtkpCol = 64;    // DTKP columns of kLongDtkpCol+1 .. this many tuples share a wavefront four at a time
 constexpr int kByJMax = 16;         // tables whose second operand has at most this many symbols get dense per-j maps
 constexpr int kByJMaxNa = 65000;    // ... and whose first operand leaves room for the three marks below
 constexpr uint16_t kByJNone = 0xFFFF, kByJWave = 0xFFFE, kByJList = 0xFFFD;
@@ -99,6 +100,7 @@ struct dol_fn_table {
     dol::DevArray<uint32_t> long_cols, dtkp_long_cols;
     // each list starts with its huge columns (more than dol::kHugeTableCol / dol::kHugeDtkpCol tuples)
     int32_t n_huge_cols = 0, n_huge_dtkp_cols = 0, n_huge_byj_cols = 0;
+    int32_t n_wave_dtkp_cols = 0;        // dtkp_long_cols: huge, then this many one-wavefront columns, then the shorter ones
     // LDS gather kernels (damp_lds.hip): per output column (forward), row of a, row of b (backward) a list of
     // 16-byte packets of four tuples; *_ptr[x] .. *_ptr[x+1] are the packets of x
     bool lds_fwd_ok = false, lds_bwd_ok = false;

@@ -119,20 +119,25 @@ static dol_status build_table(int32_t na, int32_t nb, std::vector<Tuple> &tup, d
     for (int32_t j = 0; j < nb; ++j)
         if (rowb_ptr[j + 1] - rowb_ptr[j] > static_cast<uint32_t>(kLongTableRow)) long_rows.push_back(static_cast<uint32_t>(na + j));
 
-    // long columns, the huge ones first
-    auto long_list = [&](uint32_t longer_than, uint32_t huge_above, int32_t *n_huge) {
-        std::vector<uint32_t> huge, rest;
+    // long columns: the huge ones first, then those above `wave_above`, then the rest
+    auto long_list = [&](uint32_t longer_than, uint32_t wave_above, uint32_t huge_above, int32_t *n_huge, int32_t *n_wave) {
+        std::vector<uint32_t> huge, wave, rest;
         for (int32_t c = 0; c < S; ++c) {
             const uint32_t len = col_ptr[c + 1] - col_ptr[c];
             if (len > huge_above) huge.push_back(static_cast<uint32_t>(c));
+            else if (len > wave_above) wave.push_back(static_cast<uint32_t>(c));
             else if (len > longer_than) rest.push_back(static_cast<uint32_t>(c));
         }
         *n_huge = static_cast<int32_t>(huge.size());
+        *n_wave = static_cast<int32_t>(wave.size());
+        huge.insert(huge.end(), wave.begin(), wave.end());
         huge.insert(huge.end(), rest.begin(), rest.end());
         return huge;
     };
-    const std::vector<uint32_t> long_cols = long_list(kLongTableCol, kHugeTableCol, &tb->n_huge_cols);
-    const std::vector<uint32_t> dtkp_long_cols = long_list(kLongDtkpCol, kHugeDtkpCol, &tb->n_huge_dtkp_cols);
+    int32_t unused = 0;
+    const std::vector<uint32_t> long_cols = long_list(kLongTableCol, kLongTableCol, kHugeTableCol, &tb->n_huge_cols, &unused);
+    const std::vector<uint32_t> dtkp_long_cols =
+        long_list(kLongDtkpCol, kWaveDtkpCol, kHugeDtkpCol, &tb->n_huge_dtkp_cols, &tb->n_wave_dtkp_cols);
 
     if (hipGetDevice(&tb->device) != hipSuccess) tb->device = 0;
     hipError_t e;
