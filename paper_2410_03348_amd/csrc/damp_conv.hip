@@ -45,7 +45,7 @@ std::string damp_kernel_name(const dol_fn_table *f, bool backward)
     }
     char buf[96];
     snprintf(buf, sizeof buf, "damp_conv_%s_%s_kernel<%d", backward ? "bwd" : "fwd",
-             f->na <= kTileMaxM ? "tile" : "loop", padded_nb(f->nb));   // a prefix: the tile size follows
+             !backward && f->na <= 16 ? "small" : f->na <= kTileMaxM ? "tile" : "loop", padded_nb(f->nb));   // a prefix
     return buf;
 }
 
@@ -107,6 +107,63 @@ damp_conv_fwd_tile_kernel(int32_t n_tiles, int32_t m, int32_t nb, int32_t rs, co
     }
 }
 
+// ---------------------------------------------------------------- forward, short first operand: a thread per sample
+
+// First operand of at most kSmallM symbols (the first apply of a Sum-N program: two digit Distributions), contiguous
+// tensors.  A workgroup owns 256 consecutive samples: their rows are one contiguous block of each tensor, copied flat
+// (16 bytes per lane) into LDS; each thread then takes its sample's two rows into registers, zero-padded so that
+// every column is the same chain of fma over ascending i (padding terms are exact no-ops), writes its result row back
+// to LDS, and the block leaves as flat 16-byte stores.
+constexpr int kSmallM = 16;
+constexpr int kSmallTile = 256;
+
+template <int NBP>
+__global__ void __launch_bounds__(kSmallTile)
+damp_conv_fwd_small_kernel(int32_t batch, int32_t m, int32_t nb, const float *__restrict__ a, const float *__restrict__ b,
+                           float *__restrict__ out)
+{
+    extern __shared__ __align__(16) float lds[];    // a block, b block, out block
+    const int S = m + nb - 1, tid = threadIdx.x;
+    const int64_t s0 = static_cast<int64_t>(blockIdx.x) * kSmallTile;
+    const int n = static_cast<int>(min(static_cast<int64_t>(kSmallTile), batch - s0));
+    float *la = lds, *lb = la + kSmallTile * m, *lo = lb + kSmallTile * nb;
+    auto copy_in = [&](float *dst, const float *src, int count) {
+        if (count % 4 == 0) {                       // whole tiles of 256 samples always are
+            for (int e = tid; e < count / 4; e += kSmallTile)
+                reinterpret_cast<float4 *>(dst)[e] = reinterpret_cast<const float4 *>(src)[e];
+        } else {
+            for (int e = tid; e < count; e += kSmallTile) dst[e] = src[e];
+        }
+    };
+    copy_in(la, a + s0 * m, n * m);
+    copy_in(lb, b + s0 * nb, n * nb);
+    __syncthreads();
+    if (tid < n) {
+        float ar[kSmallM + 2 * (NBP - 1)], br[NBP];  // ar[NBP - 1 + i] = a[i], zeros around
+#pragma unroll
+        for (int i = 0; i < kSmallM + 2 * (NBP - 1); ++i) {
+            const int k = i - (NBP - 1);
+            ar[i] = k >= 0 && k < m ? la[tid * m + k] : 0.0f;
+        }
+#pragma unroll
+        for (int j = 0; j < NBP; ++j) br[j] = j < nb ? lb[tid * nb + j] : 0.0f;
+#pragma unroll
+        for (int c = 0; c < kSmallM + NBP - 1; ++c) {
+            float acc = 0.0f;
+#pragma unroll
+            for (int j = NBP - 1; j >= 0; --j) acc = __builtin_fmaf(ar[NBP - 1 + c - j], br[j], acc);
+            if (c < S) lo[tid * S + c] = fminf(acc, 1.0f);
+        }
+    }
+    __syncthreads();
+    float *dst = out + s0 * S;
+    if ((n * S) % 4 == 0) {
+        for (int e = tid; e < n * S / 4; e += kSmallTile) reinterpret_cast<float4 *>(dst)[e] = reinterpret_cast<const float4 *>(lo)[e];
+    } else {
+        for (int e = tid; e < n * S; e += kSmallTile) dst[e] = lo[e];
+    }
+}
+
 // ---------------------------------------------------------------- forward, one wavefront per sample
 
 template <int NBP>
@@ -144,6 +201,14 @@ static void launch_fwd_nbp(const dol_fn_table *f, int32_t batch, const float *a,
                            int64_t ldb, float *out, int64_t ldo, hipStream_t st)
 {
     const int m = f->na, nb = f->nb, S = m + nb - 1;
+    if (m <= kSmallM && lda == m && ldb == nb && ldo == S && (reinterpret_cast<uintptr_t>(a) | reinterpret_cast<uintptr_t>(b) |
+                                                            reinterpret_cast<uintptr_t>(out)) % 16 == 0) {
+        // the offsets of the tile's blocks: multiples of 256 samples, hence of 16 bytes
+        const size_t lds = sizeof(float) * kSmallTile * static_cast<size_t>(m + nb + S);
+        const unsigned grid = static_cast<unsigned>((static_cast<int64_t>(batch) + kSmallTile - 1) / kSmallTile);
+        hipLaunchKernelGGL(damp_conv_fwd_small_kernel<NBP>, dim3(grid), dim3(kSmallTile), lds, st, batch, m, nb, a, b, out);
+        return;
+    }
     int32_t done = 0;
     const int tile_s = tile_samples(batch);
     if (m <= kTileMaxM && batch >= tile_s && lda == m && ldb == nb && ldo == S) {
