@@ -1273,3 +1273,28 @@ def test_dtkp_apply2_input_equals_init_then_apply2(dol, k):
     np.testing.assert_array_equal(host(got.proof_prob), op)
     with pytest.raises(dol.DolError):
         dol.dtkp_apply2_input(a, np.full(fact_b.size, 18, np.int32), f, prov, got)
+
+
+@pytest.mark.parametrize("m,nb,batch", [(1, 1, 5), (16, 16, 257), (7, 3, 256), (16, 1, 1000), (10, 10, 255), (3, 16, 513)])
+def test_sum_shaped_apply_with_short_first_operand(dol, m, nb, batch):
+    """The thread-per-sample forward kernel: every width up to 16, whole and partial tiles of 256 samples, tags that
+    clamp; backward (through the tile / loop kernels) on the same result."""
+    a = (W.uniform01(100 + m, batch * m) * 0.9).astype(np.float32).reshape(batch, m)
+    b = (W.uniform01(200 + nb, batch * nb) * 0.9).astype(np.float32).reshape(batch, nb)
+    table = W.sum_table(np.arange(m), np.arange(nb))
+    tri = oracle.dense_to_triples(table)
+    syms, want, pre32, _ = oracle.damp_apply2_fwd(tri, m, nb, a, b, want_pre=True)
+    f = dol.FnTable.create_dense(table)
+    assert f.kernel_fwd.startswith("damp_conv_fwd_small_kernel")
+    da, db = dol.Dist(np.arange(m), dev(a)), dol.Dist(np.arange(nb), dev(b))
+    out = dol.Dist.empty(f.out_syms, batch)
+    dol.apply2(da, db, f, None, out)
+    assert_close(host(out.prob), want, "short first operand forward")
+    if min(m, nb) >= 3:
+        assert (pre32 > 1).any()
+    g = np.abs(W.normal(300 + m, batch * syms.size)).astype(np.float32).reshape(batch, -1)
+    wa, wb = oracle.damp_apply2_bwd(tri, m, nb, a, b, g)
+    ga, gb = torch.empty((batch, m), device="cuda"), torch.empty((batch, nb), device="cuda")
+    dol.backward(dol.OpRecord(dol.OP_APPLY2, da, db, out, f=f), dev(g), ga, gb)
+    assert_close(host(ga), wa, "short first operand grad a")
+    assert_close(host(gb), wb, "short first operand grad b")
