@@ -120,7 +120,9 @@ dol_status dol_apply2(const dol_dist *a, const dol_dist *b, const dol_fn_table *
  * outputs: D_res = apply(D_res, D_i, f), Fig. 2): symbol j of the second operand is input fact fact_of_sym_b[j]
  * (host [nb], each in 0..n_facts-1) and carries the tag natural initialisation gives it (App. A.1: the single proof
  * {that fact}).  The result equals dol_dtkp_init on the operand followed by dol_apply2; the operand's tags are
- * never stored.  a, f, prov, out as for dol_apply2. */
+ * never stored.  a, f, prov, out as for dol_apply2, and each proof of a must hold at most one fact per exclusion
+ * group (every proof this library writes does): the conjunction is then inconsistent exactly when the proof holds
+ * another fact of the group of the fact it is joined with, which is all this call tests. */
 dol_status dol_dtkp_apply2_input(const dol_dist *a, const int32_t *fact_of_sym_b, const dol_fn_table *f,
                                  const dol_prov *prov, dol_dist *out, void *hip_stream);
 

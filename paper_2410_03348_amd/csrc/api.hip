@@ -99,8 +99,20 @@ dol_status dol_dtkp_apply2_input(const dol_dist *a, const int32_t *fact_of_sym_b
     if (!out->proof_prob) return fail(DOL_EINVAL, "out.proof_prob is NULL");
     GroupMasks gm;
     if (dol_status s2 = make_group_masks(prov, &gm)) return s2;
+    // four words per symbol of b: its fact, the other facts of that fact's exclusion group (low, high word), 0
+    std::vector<int32_t> words(4 * static_cast<size_t>(f->nb), 0);
+    for (int32_t j = 0; j < f->nb; ++j) {
+        const int32_t fb = fact_of_sym_b[j];
+        uint64_t rival = 0;
+        for (int32_t g = 0; g < gm.n; ++g)
+            if ((gm.m[g] >> fb) & 1) rival |= gm.m[g];
+        rival &= ~(uint64_t(1) << fb);
+        words[4 * j] = fb;
+        words[4 * j + 1] = static_cast<int32_t>(static_cast<uint32_t>(rival));
+        words[4 * j + 2] = static_cast<int32_t>(static_cast<uint32_t>(rival >> 32));
+    }
     const int32_t *d_fact_b = nullptr;
-    if (dol_status s2 = get_i32_array(f->nb, fact_of_sym_b, &d_fact_b)) return s2;
+    if (dol_status s2 = get_i32_array(static_cast<int32_t>(words.size()), words.data(), &d_fact_b)) return s2;
     return launch_dtkp_apply2(f, a->batch, prov->k, prov->n_facts, gm, prov->fact_prob, a->proof_mask, a->proof_prob,
                               nullptr, nullptr, d_fact_b, out->proof_mask, out->proof_prob, out->prob, out->ld,
                               static_cast<hipStream_t>(hip_stream));

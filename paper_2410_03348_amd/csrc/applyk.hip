@@ -31,6 +31,7 @@ struct dol_fnk_table {
     dol::DevArray<uint32_t> long_cols;   // columns with more than dol::kLongTableCol tuples
     dol::DevArray<uint32_t> dtkp_long_cols;   // ... more than dol::kLongDtkpCol: first those above dol::kWaveDtkpCol
     int32_t n_wave_dtkp_cols = 0;             // (one wavefront each), then the shorter ones (four to a wavefront)
+    dol::DevArray<uint32_t> dtkp_col_order;   // K >= 2: all columns in the order of dol::columns_by_length
     // unary functions (K = 1): the first eight symbols of every image again, 16 bytes per column (0xFFFF = none), and
     // the column of every symbol (-1: rejected)
     dol::DevArray<uint16_t> unary_head;
@@ -293,22 +294,20 @@ __device__ __forceinline__ void offer_tuple_k(TopK<KP> &top, const uint16_t *__r
     TopK<KP> cur;
     {
         const int64_t o = (s * in.n[0] + t[0]) * KP;
+        load_masks<KP>(in.m[0] + o, cur.m);
+        if (in.p[0]) load_probs<KP>(in.p[0] + o, cur.p);
 #pragma unroll
-        for (int x = 0; x < KP; ++x) {
-            const uint64_t m = in.m[0][o + x];
-            cur.m[x] = m;
-            cur.p[x] = m == kAbsent ? -1.0f : in.p[0] ? in.p[0][o + x] : proof_prob(m, fp);
-        }
+        for (int x = 0; x < KP; ++x)
+            cur.p[x] = cur.m[x] == kAbsent ? -1.0f : in.p[0] ? cur.p[x] : proof_prob(cur.m[x], fp);
     }
     for (int l = 1; l < arity; ++l) {
         const int64_t o = (s * in.n[l] + t[l]) * KP;
         uint64_t mb[KP];
         float pb[KP];
+        load_masks<KP>(in.m[l] + o, mb);
 #pragma unroll
-        for (int y = 0; y < KP; ++y) {
-            mb[y] = in.m[l][o + y];
-            pb[y] = in.p[l] ? in.p[l][o + y] : -1.0f;
-        }
+        for (int y = 0; y < KP; ++y) pb[y] = -1.0f;
+        if (in.p[l]) load_probs<KP>(in.p[l] + o, pb);
         TopK<KP> nxt;
         nxt.clear();
 #pragma unroll
@@ -332,14 +331,16 @@ __device__ __forceinline__ void offer_tuple_k(TopK<KP> &top, const uint16_t *__r
 // One thread per (sample, output symbol): the proofs of the column's tuples meet in one k-entry list.
 template <int KP>
 __global__ void __launch_bounds__(kThreadsP)
-dtkp_applyk_kernel(int64_t total, int32_t S, int32_t arity, KProofs in, const uint32_t *__restrict__ col_ptr,
+dtkp_applyk_kernel(int64_t total, int32_t S, int32_t arity, KProofs in, const uint32_t *__restrict__ order,
+                   const uint32_t *__restrict__ col_ptr,
                    const uint16_t *__restrict__ tup, GroupMasks gm, int32_t n_facts, const float *__restrict__ fact_prob,
                    uint64_t *__restrict__ om, float *__restrict__ op, float *__restrict__ oprob, int64_t ldo)
 {
     const int64_t idx = static_cast<int64_t>(blockIdx.x) * kThreadsP + threadIdx.x;
     if (idx >= total) return;
     const int64_t s = idx / S;
-    const int32_t c = static_cast<int32_t>(idx - s * S);
+    const int32_t r = static_cast<int32_t>(idx - s * S);
+    const int32_t c = order ? static_cast<int32_t>(order[r]) : r;          // lanes of a wavefront: columns of like length
     const float *fp = fact_prob + s * n_facts;
     const uint32_t q0 = col_ptr[c], q1 = col_ptr[c + 1];
     if (q1 - q0 > static_cast<uint32_t>(kLongDtkpCol)) return;             // left to the wavefront-per-column kernel
@@ -348,7 +349,8 @@ dtkp_applyk_kernel(int64_t total, int32_t S, int32_t arity, KProofs in, const ui
     for (uint32_t q = q0; q < q1; ++q) {
         offer_tuple_k<KP>(top, tup + static_cast<size_t>(q) * arity, s, arity, in, gm, fp);
     }
-    oprob[s * ldo + c] = top.store(om + idx * KP, op + idx * KP);
+    const int64_t o = s * S + c;
+    oprob[s * ldo + c] = top.store(om + o * KP, op + o * KP);
 }
 
 // One wavefront per (sample, long column): every lane streams a share of the tuples through a list of its own; the
@@ -404,8 +406,8 @@ static void launch_dtkp_k(int64_t total, const dol_fnk_table *f, const KProofs &
                           const float *fact_prob, uint64_t *om, float *op, float *oprob, int64_t ldo, hipStream_t st)
 {
     hipLaunchKernelGGL(dtkp_applyk_kernel<KP>, dim3(static_cast<unsigned>((total + kThreadsP - 1) / kThreadsP)),
-                       dim3(kThreadsP), 0, st, total, f->n_out, f->K, in, f->col_ptr.ptr, f->tup.ptr, gm, n_facts,
-                       fact_prob, om, op, oprob, ldo);
+                       dim3(kThreadsP), 0, st, total, f->n_out, f->K, in, f->dtkp_col_order.ptr, f->col_ptr.ptr, f->tup.ptr, gm,
+                       n_facts, fact_prob, om, op, oprob, ldo);
     const int64_t n_wave = f->n_wave_dtkp_cols, n_mid = static_cast<int64_t>(f->dtkp_long_cols.n) - n_wave;
     const int64_t batch = total / f->n_out;
     if (n_wave > 0)
@@ -510,6 +512,8 @@ static dol_status build_k(int32_t K, const int32_t *n_sym, int64_t n, const int3
     DOL_HIP(hipGetDevice(&tb->device));
     DOL_HIP(tb->long_cols.upload(long_cols));
     DOL_HIP(tb->dtkp_long_cols.upload(dtkp_long_cols));
+    // (a unary function's lists are one gather each: there the neighbouring columns' neighbouring symbols matter more)
+    if (K >= 2) DOL_HIP(tb->dtkp_col_order.upload(columns_by_length(col_ptr, S, kLongDtkpCol)));
     DOL_HIP(tb->col_ptr.upload(col_ptr));
     DOL_HIP(tb->tup.upload(tup));
     DOL_HIP(tb->tup_col.upload(tup_col));

@@ -63,31 +63,33 @@ __device__ __forceinline__ void offer_tuple(TopK<K> &top, uint32_t ij, int64_t a
     float pa[K], pb[K];
     if (fact_b) {
         // the second operand is an input Distribution under natural initialisation: its symbol is one fact, its
-        // tag the single proof {that fact} (App. A.1); nothing of it is stored
-        const int fb = fact_b[ij >> 16];
-        const uint64_t bit = uint64_t(1) << fb;
+        // tag the single proof {that fact} (App. A.1); nothing of it is stored.  fact_b holds four words per symbol:
+        // the fact and the mask of the other facts of its exclusion group (low, high word).  The first operand's
+        // proofs hold at most one fact per exclusion group, so the union is inconsistent exactly when such a proof
+        // holds a rival of the one fact the second operand brings.  The product over ascending facts is unchanged
+        // when the fact is already there, takes one more factor when it lies above every fact of the proof
+        // (ma < bit as integers), and is redone from scratch otherwise.
+        const uint4 fr = reinterpret_cast<const uint4 *>(fact_b)[ij >> 16];
+        const int fb = static_cast<int>(fr.x);
+        const uint64_t bit = uint64_t(1) << fb, rival = (static_cast<uint64_t>(fr.z) << 32) | fr.y;
         const float pbit = 1.0f * fp[fb];
+        load_masks<K>(am + ia, ma);
+        if (ap) load_probs<K>(ap + ia, pa);
 #pragma unroll
         for (int x = 0; x < K; ++x) {
-            ma[x] = am[ia + x];
-            pa[x] = ap ? ap[ia + x] : -1.0f;
-        }
-#pragma unroll
-        for (int x = 0; x < K; ++x) {
-            if (ma[x] == kAbsent) continue;
-            const uint64_t m = ma[x] | bit;
-            if (proof_conflict(m, gm)) continue;
-            top.insert(m, union_prob(ma[x], pa[x], bit, pbit, fp));
+            if (ma[x] == kAbsent || (ma[x] & rival)) continue;
+            const bool held = (ma[x] & bit) != 0;
+            const float pr = ap && (held || ma[x] < bit) ? (held ? pa[x] : pa[x] * pbit) : proof_prob(ma[x] | bit, fp);
+            top.insert(ma[x] | bit, pr);
         }
         return;
     }
+    load_masks<K>(am + ia, ma);
+    load_masks<K>(bm + ib, mb);
 #pragma unroll
-    for (int x = 0; x < K; ++x) {
-        ma[x] = am[ia + x];
-        mb[x] = bm[ib + x];
-        pa[x] = ap ? ap[ia + x] : -1.0f;
-        pb[x] = bp ? bp[ib + x] : -1.0f;
-    }
+    for (int x = 0; x < K; ++x) pa[x] = pb[x] = -1.0f;
+    if (ap) load_probs<K>(ap + ia, pa);
+    if (bp) load_probs<K>(bp + ib, pb);
 #pragma unroll
     for (int x = 0; x < K; ++x) {
         if (ma[x] == kAbsent) continue;
@@ -103,7 +105,7 @@ __device__ __forceinline__ void offer_tuple(TopK<K> &top, uint32_t ij, int64_t a
 
 template <int K>
 __global__ void __launch_bounds__(kThreadsT)
-dtkp_apply2_kernel(int64_t total, int32_t S, int32_t na, int32_t nb, int32_t n_facts,
+dtkp_apply2_kernel(int64_t total, int32_t S, int32_t na, int32_t nb, int32_t n_facts, const uint32_t *__restrict__ order,
                    const uint32_t *__restrict__ col_ptr, const uint32_t *__restrict__ col_ij, GroupMasks gm,
                    const float *__restrict__ fact_prob, const uint64_t *__restrict__ am,
                    const float *__restrict__ ap, const uint64_t *__restrict__ bm, const float *__restrict__ bp,
@@ -113,7 +115,7 @@ dtkp_apply2_kernel(int64_t total, int32_t S, int32_t na, int32_t nb, int32_t n_f
     const int64_t idx = static_cast<int64_t>(blockIdx.x) * kThreadsT + threadIdx.x;
     if (idx >= total) return;
     const int64_t s = idx / S;
-    const int32_t c = static_cast<int32_t>(idx - s * S);
+    const int32_t c = static_cast<int32_t>(order[idx - s * S]);          // lanes of a wavefront: columns of like length
     const float *fp = fact_prob + s * n_facts;
     const int64_t a0 = s * na * K, b0 = s * nb * K;
     const uint32_t q0 = col_ptr[c], q1 = col_ptr[c + 1];
@@ -121,7 +123,8 @@ dtkp_apply2_kernel(int64_t total, int32_t S, int32_t na, int32_t nb, int32_t n_f
     TopK<K> top;
     top.clear();
     for (uint32_t q = q0; q < q1; ++q) offer_tuple<K>(top, col_ij[q], a0, b0, gm, fp, am, ap, bm, bp, fact_b);
-    oprob[s * ldo + c] = top.store(om + idx * K, op + idx * K);
+    const int64_t o = s * S + c;
+    oprob[s * ldo + c] = top.store(om + o * K, op + o * K);
 }
 
 // One workgroup of 1, 4 or 16 wavefronts (by the table's longest column) per (sample, long column): every lane streams
@@ -204,8 +207,8 @@ static void launch_apply2_k(int64_t total, const dol_fn_table *f, int32_t n_fact
                             hipStream_t st)
 {
     hipLaunchKernelGGL(dtkp_apply2_kernel<K>, dim3(grid_t(total)), dim3(kThreadsT), 0, st, total, f->n_out, f->na,
-                       f->nb, n_facts, f->col_ptr.ptr, f->col_ij.ptr, gm, fact_prob, am, ap, bm, bp, fact_b, om, op, oprob,
-                       ldo);
+                       f->nb, n_facts, f->dtkp_col_order.ptr, f->col_ptr.ptr, f->col_ij.ptr, gm, fact_prob, am, ap, bm, bp,
+                       fact_b, om, op, oprob, ldo);
     const int64_t n_long = static_cast<int64_t>(f->dtkp_long_cols.n);
     const int64_t n_huge = f->n_huge_dtkp_cols, batch = total / f->n_out;
     if (n_huge > 0)                                  // the list's first n_huge columns: 16 wavefronts each
@@ -331,65 +334,96 @@ dol_status launch_dtkp_filter(const FilterPlan *p, int32_t batch, int32_t k, con
 
 // Pr(symbol) = min(1, sum over its kept proofs of the product of their facts' probabilities) (Sec. 3.2); which
 // proofs top-k kept is a constant of the differentiation and the clamp passes gradient inside and on its bound
-// (App. A.2).  One workgroup per sample, one lane per symbol (coalesced loads of the proof lists); a lane walks the
-// facts of each of its proofs and adds gradient * (product of the proof's other facts) to the fact's
-// accumulator of its wavefront in LDS; the wavefronts' accumulators are then summed in wavefront order.
+// (App. A.2).  One workgroup per sample; its wavefronts take 64 symbols at a time.  A lane first loads one symbol's
+// proof list (coalesced) and folds the clamp's gate and the upstream gradient into one coefficient per proof; then
+// the 64 lanes turn into the 64 facts: every proof of the 64 symbols is broadcast in turn, its mask selecting the
+// lanes that add coefficient / (own fact's probability), the product of the proof's other facts, to a register.
+// No atomics; the sum over symbols runs in ascending order within a wavefront's share, then over the wavefronts.
 constexpr int kGradWaves = 16;
-constexpr int kGradCopies = 8;
 
+template <int K>
 __global__ void __launch_bounds__(kGradWaves * 64)
-dtkp_prob_bwd_kernel(int32_t n_sym, int32_t k, int32_t n_facts, const uint64_t *__restrict__ mask,
+dtkp_prob_bwd_kernel(int32_t n_sym, int32_t n_facts, const uint64_t *__restrict__ mask,
                      const float *__restrict__ pprob, const float *__restrict__ fact_prob,
                      const float *__restrict__ g, int64_t ldg, float *__restrict__ gfact)
 {
-    __shared__ float part[kGradWaves * kGradCopies][65];   // kGradCopies accumulators per wavefront (rows skewed over the banks): lanes that meet
-    __shared__ float fp[64];                                // on one fact in one instruction are spread over them
+    __shared__ float part[kGradWaves][64];
     const int64_t s = blockIdx.x;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, n_waves = blockDim.x >> 6;
+    const int lane = threadIdx.x & 63, n_waves = blockDim.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6));   // tells the compiler it is uniform
+    const float pj = lane < n_facts ? fact_prob[s * n_facts + lane] : 1.0f;
+    // a proof's other facts: its stored probability divided by this fact's (one rounding more than multiplying
+    // them out; the 1 ulp reciprocal is far inside the 1e-5 bar); multiplied out, in ascending order, for every
+    // group of 64 symbols one of whose proofs holds a fact of probability (nearly) 0
+    const uint64_t tiny = __ballot(!(pj > 1e-30f));
+    const float inv = pj > 1e-30f ? __builtin_amdgcn_rcpf(pj) : 0.0f;
+    float acc = 0.0f;
+    for (int32_t i0 = wave * 64; i0 < n_sym; i0 += n_waves * 64) {
+        const int32_t i = i0 + lane;
+        uint64_t mm[K];                     // 0: absent, gated by the clamp, or past the last symbol
+        float cf[K], gate_g = 0.0f;
 #pragma unroll
-    for (int x = 0; x < kGradCopies; ++x) part[wave * kGradCopies + x][lane] = 0.0f;
-    float *mine = part[wave * kGradCopies + (lane & (kGradCopies - 1))];
-    if (wave == 0) fp[lane] = lane < n_facts ? fact_prob[s * n_facts + lane] : 1.0f;
-    __syncthreads();
-    for (int32_t i = threadIdx.x; i < n_sym; i += blockDim.x) {
-        const uint64_t *m = mask + (s * n_sym + i) * k;
-        const float *pp = pprob + (s * n_sym + i) * k;
-        uint64_t mm[DOL_MAX_K];
-        float pv[DOL_MAX_K];
+        for (int x = 0; x < K; ++x) { mm[x] = 0; cf[x] = 0.0f; }
+        if (i < n_sym) {
+            const uint64_t *m = mask + (s * n_sym + i) * K;
+            const float *pp = pprob + (s * n_sym + i) * K;
+            uint64_t lm[K];
+            float pv[K];
+            load_masks<K>(m, lm);
+            load_probs<K>(pp, pv);
+            const float gi = g[s * ldg + i];
+            float sum = 0.0f;               // the quantity the forward pass clamped: kept proofs in rank order
 #pragma unroll
-        for (int x = 0; x < DOL_MAX_K; ++x) {
-            mm[x] = x < k ? m[x] : kAbsent;
-            pv[x] = x < k ? pp[x] : 0.0f;
+            for (int x = 0; x < K; ++x)
+                if (lm[x] != kAbsent) sum = sum + pv[x];
+            if (sum <= 1.0f) {
+                gate_g = gi;
+#pragma unroll
+                for (int x = 0; x < K; ++x)
+                    if (lm[x] != kAbsent) { mm[x] = lm[x]; cf[x] = gi * pv[x]; }
+            }
         }
-        const float gi = g[s * ldg + i];
-        float sum = 0.0f;                   // the quantity the forward pass clamped: kept proofs in rank order
+        const int cnt = min(64, n_sym - i0);
+        auto proof_mask_of = [&](int x, int l) {
+            const uint32_t lo = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(static_cast<uint32_t>(mm[x])), l));
+            const uint32_t hi = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(static_cast<uint32_t>(mm[x] >> 32)), l));
+            return (static_cast<uint64_t>(hi) << 32) | lo;
+        };
+        uint64_t all = 0;
 #pragma unroll
-        for (int x = 0; x < DOL_MAX_K; ++x)
-            if (mm[x] != kAbsent) sum = sum + pv[x];
-        if (!(sum <= 1.0f)) continue;
+        for (int x = 0; x < K; ++x) all |= mm[x];
+        if (!__any((all & tiny) != 0)) {    // the usual case: no proof of these symbols holds a (nearly) impossible fact
+            for (int l = 0; l < cnt; ++l) {
 #pragma unroll
-        for (int x = 0; x < DOL_MAX_K; ++x) {
-            if (mm[x] == kAbsent) continue;
-            for (uint64_t r = mm[x]; r; r &= r - 1) {
-                const int j = __builtin_ctzll(r);
-                // the product of the proof's other facts: its stored probability divided by this fact's (one rounding
-                // more than multiplying them out), multiplied out only where that fact's probability is (nearly) 0
-                const float pj = fp[j];
-                float others;
-                if (pj > 1e-30f) {
-                    others = pv[x] * __builtin_amdgcn_rcpf(pj);        // 1 ulp reciprocal: far inside the 1e-5 bar
-                } else {
-                    others = 1.0f;
-                    for (uint64_t q = mm[x] & ~(uint64_t(1) << j); q; q &= q - 1) others = others * fp[__builtin_ctzll(q)];
+                for (int x = 0; x < K; ++x) {
+                    const bool has = __builtin_amdgcn_inverse_ballot_w64(proof_mask_of(x, l));   // lane j: fact j is in the proof
+                    const float c = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, cf[x]), l));
+                    acc = has ? __builtin_fmaf(c, inv, acc) : acc;
                 }
-                atomicAdd(&mine[j], gi * others);
+            }
+        } else {
+            for (int l = 0; l < cnt; ++l) {
+                const float gl = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, gate_g), l));
+#pragma unroll
+                for (int x = 0; x < K; ++x) {
+                    const uint64_t um = proof_mask_of(x, l);
+                    const bool has = __builtin_amdgcn_inverse_ballot_w64(um);
+                    float others = 1.0f;
+                    for (uint64_t r = um; r; r &= r - 1) {
+                        const int q = __builtin_ctzll(r);
+                        const float fq = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, pj), q));
+                        others = others * (q == lane ? 1.0f : fq);
+                    }
+                    acc = has ? __builtin_fmaf(gl, others, acc) : acc;
+                }
             }
         }
     }
+    part[wave][lane] = acc;
     __syncthreads();
     if (wave == 0 && lane < n_facts) {
         float tot = 0.0f;
-        for (int w = 0; w < n_waves * kGradCopies; ++w) tot = tot + part[w][lane];
+        for (int w = 0; w < n_waves; ++w) tot = tot + part[w][lane];
         gfact[s * n_facts + lane] = tot;
     }
 }
@@ -400,8 +434,11 @@ dol_status launch_dtkp_prob_bwd(int32_t batch, int32_t n_sym, int32_t k, int32_t
 {
     if (batch == 0 || n_facts == 0) return DOL_OK;
     const int waves = std::max(1, std::min(kGradWaves, (n_sym + 63) / 64));
-    hipLaunchKernelGGL(dtkp_prob_bwd_kernel, dim3(static_cast<unsigned>(batch)), dim3(64 * waves), 0, st, n_sym, k,
-                       n_facts, mask, pprob, fact_prob, g, ldg, gfact);
+#define CALL(K)                                                                                                        \
+    hipLaunchKernelGGL(dtkp_prob_bwd_kernel<K>, dim3(static_cast<unsigned>(batch)), dim3(64 * waves), 0, st, n_sym,     \
+                       n_facts, mask, pprob, fact_prob, g, ldg, gfact)
+    DOL_DISPATCH_K(k, CALL)
+#undef CALL
     DOL_HIP(hipGetLastError());
     return DOL_OK;
 }

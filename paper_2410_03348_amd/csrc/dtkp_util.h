@@ -8,6 +8,82 @@ namespace dol {
 
 constexpr uint64_t kAbsent = ~uint64_t(0);
 
+// A symbol's k proof masks and k proof probabilities are 8k and 4k contiguous bytes, aligned to 8 and 4: they move
+// with 16-byte accesses of that declared alignment (the target allows global accesses that are not naturally
+// aligned), so that a gathered list costs two or three memory instructions instead of 2k.
+typedef uint32_t __attribute__((ext_vector_type(4), aligned(8))) u32x4_a8;
+typedef float __attribute__((ext_vector_type(4), aligned(4))) f32x4_a4;
+typedef float __attribute__((ext_vector_type(3), aligned(4))) f32x3_a4;
+typedef float __attribute__((ext_vector_type(2), aligned(4))) f32x2_a4;
+
+template <int K>
+__device__ __forceinline__ void load_masks(const uint64_t *__restrict__ src, uint64_t (&m)[K])
+{
+#pragma unroll
+    for (int x = 0; x + 1 < K; x += 2) {
+        const u32x4_a8 v = *reinterpret_cast<const u32x4_a8 *>(src + x);
+        m[x] = (static_cast<uint64_t>(v.y) << 32) | v.x;
+        m[x + 1] = (static_cast<uint64_t>(v.w) << 32) | v.z;
+    }
+    if constexpr ((K & 1) != 0) m[K - 1] = src[K - 1];
+}
+
+template <int K>
+__device__ __forceinline__ void load_probs(const float *__restrict__ src, float (&p)[K])
+{
+#pragma unroll
+    for (int x = 0; x + 3 < K; x += 4) {
+        const f32x4_a4 v = *reinterpret_cast<const f32x4_a4 *>(src + x);
+        p[x] = v.x, p[x + 1] = v.y, p[x + 2] = v.z, p[x + 3] = v.w;
+    }
+    constexpr int R = K & 3, B = K - R;
+    if constexpr (R == 3) {
+        const f32x3_a4 v = *reinterpret_cast<const f32x3_a4 *>(src + B);
+        p[B] = v.x, p[B + 1] = v.y, p[B + 2] = v.z;
+    } else if constexpr (R == 2) {
+        const f32x2_a4 v = *reinterpret_cast<const f32x2_a4 *>(src + B);
+        p[B] = v.x, p[B + 1] = v.y;
+    } else if constexpr (R == 1) {
+        p[B] = src[B];
+    }
+}
+
+template <int K>
+__device__ __forceinline__ void store_masks(uint64_t *__restrict__ dst, const uint64_t (&m)[K])
+{
+#pragma unroll
+    for (int x = 0; x + 1 < K; x += 2) {
+        u32x4_a8 v;
+        v.x = static_cast<uint32_t>(m[x]), v.y = static_cast<uint32_t>(m[x] >> 32);
+        v.z = static_cast<uint32_t>(m[x + 1]), v.w = static_cast<uint32_t>(m[x + 1] >> 32);
+        *reinterpret_cast<u32x4_a8 *>(dst + x) = v;
+    }
+    if constexpr ((K & 1) != 0) dst[K - 1] = m[K - 1];
+}
+
+template <int K>
+__device__ __forceinline__ void store_probs(float *__restrict__ dst, const float (&p)[K])
+{
+#pragma unroll
+    for (int x = 0; x + 3 < K; x += 4) {
+        f32x4_a4 v;
+        v.x = p[x], v.y = p[x + 1], v.z = p[x + 2], v.w = p[x + 3];
+        *reinterpret_cast<f32x4_a4 *>(dst + x) = v;
+    }
+    constexpr int R = K & 3, B = K - R;
+    if constexpr (R == 3) {
+        f32x3_a4 v;
+        v.x = p[B], v.y = p[B + 1], v.z = p[B + 2];
+        *reinterpret_cast<f32x3_a4 *>(dst + B) = v;
+    } else if constexpr (R == 2) {
+        f32x2_a4 v;
+        v.x = p[B], v.y = p[B + 1];
+        *reinterpret_cast<f32x2_a4 *>(dst + B) = v;
+    } else if constexpr (R == 1) {
+        dst[B] = p[B];
+    }
+}
+
 template <int K>
 struct TopK {
     uint64_t m[K];
@@ -43,14 +119,15 @@ struct TopK {
     // Writes the k slots and returns the tag probability min(1, sum in rank order) (App. A.1).
     __device__ __forceinline__ float store(uint64_t *__restrict__ om, float *__restrict__ op) const
     {
-        float sum = 0.0f;
+        float sum = 0.0f, q[K];
 #pragma unroll
         for (int x = 0; x < K; ++x) {
             const bool present = m[x] != kAbsent;
-            om[x] = m[x];
-            op[x] = present ? p[x] : 0.0f;
+            q[x] = present ? p[x] : 0.0f;
             if (present) sum = sum + p[x];
         }
+        store_masks<K>(om, m);
+        store_probs<K>(op, q);
         return fminf(sum, 1.0f);
     }
 };

@@ -7,6 +7,8 @@
 #include <cstdint>
 #include <cstdio>
 #include <string>
+#include <algorithm>
+#include <numeric>
 #include <vector>
 
 #include "dolphin_hip.h"
@@ -98,6 +100,8 @@ struct dol_fn_table {
     dol::DevArray<uint32_t> long_rows;
     // output columns with more than dol::kLongTableCol / dol::kLongDtkpCol tuples
     dol::DevArray<uint32_t> long_cols, dtkp_long_cols;
+    // all columns in the order the thread-per-column DTKP kernel takes them (dol::columns_by_length)
+    dol::DevArray<uint32_t> dtkp_col_order;
     // each list starts with its huge columns (more than dol::kHugeTableCol / dol::kHugeDtkpCol tuples)
     int32_t n_huge_cols = 0, n_huge_dtkp_cols = 0, n_huge_byj_cols = 0;
     int32_t n_wave_dtkp_cols = 0;        // dtkp_long_cols: huge, then this many one-wavefront columns, then the shorter ones
@@ -121,6 +125,27 @@ struct dol_fn_table {
 };
 
 namespace dol {
+
+// The order in which a thread-per-column kernel takes the columns of a table: inside every block of kOrderBlock
+// consecutive columns, longest tuple list first (columns above `skip_above` tuples, which such a kernel leaves to
+// another one, last), equal lengths in ascending column order.  The 64 lanes of a wavefront then walk lists of (nearly)
+// one length instead of waiting for the longest of 64 arbitrary ones, while a block's results still land in one
+// contiguous stretch of the output.
+constexpr int32_t kOrderBlock = 4096;
+
+inline std::vector<uint32_t> columns_by_length(const std::vector<uint32_t> &col_ptr, int32_t n_cols, uint32_t skip_above)
+{
+    std::vector<uint32_t> order(static_cast<size_t>(n_cols));
+    std::iota(order.begin(), order.end(), 0u);
+    auto work = [&](uint32_t c) {
+        const uint32_t len = col_ptr[c + 1] - col_ptr[c];
+        return len > skip_above ? 0u : len;
+    };
+    for (int32_t b = 0; b < n_cols; b += kOrderBlock)
+        std::stable_sort(order.begin() + b, order.begin() + std::min(n_cols, b + kOrderBlock),
+                         [&](uint32_t x, uint32_t y) { return work(x) > work(y); });
+    return order;
+}
 
 struct FilterPlan {
     int32_t n_in = 0, n_out = 0;

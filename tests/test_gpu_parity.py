@@ -1275,6 +1275,49 @@ def test_dtkp_apply2_input_equals_init_then_apply2(dol, k):
         dol.dtkp_apply2_input(a, np.full(fact_b.size, 18, np.int32), f, prov, got)
 
 
+@pytest.mark.parametrize("k,nv", [(1, 6), (3, 6), (3, 20), (8, 12)])
+def test_dtkp_gradient_with_impossible_facts(dol, k, nv):
+    """Fact probabilities of exactly 0 and far below 1e-30 in some samples: there the product of a proof's other facts
+    cannot come from dividing the proof's probability, so the kernel multiplies them out.  nv = 20 gives 400 result
+    symbols (several wavefronts per sample, a ragged last group of 64); the padded gradient tensor has ld > n_sym."""
+    B = 70
+    fp = np.concatenate([W.softmax_rows(W.normal(5900 + t, B * nv).reshape(B, nv)) for t in range(3)], axis=1)
+    fp[::3, 1:nv] = 0.0                                            # kept lists there must take impossible proofs
+    fp[1::5, nv + 1] = np.float32(1e-36)
+    fp[2::7, 2 * nv + 3] = np.float32(1e-41)                       # subnormal
+    fp[5, :] = 0.0                                                 # every proof of this sample is impossible
+    fp = np.ascontiguousarray(fp, np.float32)
+    grp = np.repeat(np.arange(3), nv).astype(np.int32)
+    prov = dol.Prov(dol.DTKP, k, dev(fp), grp)
+    d = [dol.Dist.empty(np.arange(nv), B, k=k) for _ in range(3)]
+    for t in range(3):
+        dol.dtkp_init(d[t], np.arange(nv) + nv * t, prov)
+    # a: pairs of (slot 0, slot 1) facts folded onto few symbols, so that symbols keep several proofs
+    tab = (W.splitmix64(5950, np.arange(nv * nv)) % np.uint64(nv)).astype(np.int32).reshape(nv, nv)
+    ft = dol.FnTable.create_dense(tab)
+    a = dol.Dist.empty(ft.out_syms, B, k=k)
+    dol.apply2(d[0], d[1], ft, prov, a)
+    # out: one symbol per (a symbol, slot 2 fact)
+    table = np.arange(a.n_sym * nv, dtype=np.int32).reshape(a.n_sym, nv)
+    f = dol.FnTable.create_dense(table)
+    out = dol.Dist.empty(f.out_syms, B, k=k)
+    dol.apply2(a, d[2], f, prov, out)
+    inits = [oracle.dtkp_init(np.arange(nv) + nv * t, fp, k)[0] for t in range(3)]
+    _, am, _, _ = oracle.dtkp_apply2(oracle.dense_to_triples(tab), nv, nv, k, grp, fp, inits[0], inits[1])
+    _, om, op, opr = oracle.dtkp_apply2(oracle.dense_to_triples(table), a.n_sym, nv, k, grp, fp, am, inits[2])
+    np.testing.assert_array_equal(host(out.proof_mask).view(np.uint64), om)
+    np.testing.assert_array_equal(host(out.proof_prob), op)
+    S = om.shape[1]
+    gsym = W.normal(5960 + k, B * S).astype(np.float32).reshape(B, S)
+    want = oracle.dtkp_prob_bwd(om, fp, gsym)
+    assert np.abs(want[::3, 1:nv]).max() > 0                       # the zero facts do receive gradient
+    gpad = torch.zeros((B, S + 5), device="cuda")
+    gpad[:, :S] = dev(gsym)
+    gf = torch.full((B, fp.shape[1]), 3.0, device="cuda")
+    dol.dtkp_backward(out, prov, gpad, gf)
+    assert_close(host(gf), want, "dtkp gradient with impossible facts, k=%d" % k)
+
+
 @pytest.mark.parametrize("m,nb,batch", [(1, 1, 5), (16, 16, 257), (7, 3, 256), (16, 1, 1000), (10, 10, 255), (3, 16, 513)])
 def test_sum_shaped_apply_with_short_first_operand(dol, m, nb, batch):
     """The thread-per-sample forward kernel: every width up to 16, whole and partial tiles of 256 samples, tags that
