@@ -31,7 +31,7 @@ struct dol_fnk_table {
     dol::DevArray<uint32_t> long_cols;   // columns with more than dol::kLongTableCol tuples
     dol::DevArray<uint32_t> dtkp_long_cols;   // ... more than dol::kLongDtkpCol: first those above dol::kWaveDtkpCol
     int32_t n_wave_dtkp_cols = 0;             // (one wavefront each), then the shorter ones (four to a wavefront)
-    dol::DevArray<uint32_t> dtkp_col_order;   // K >= 2: all columns in the order of dol::columns_by_length
+    dol::DevArray<uint32_t> col_order;   // all columns in the order of dol::columns_by_length (limit: kLongDtkpCol)
     // unary functions (K = 1): the first eight symbols of every image again, 16 bytes per column (0xFFFF = none), and
     // the column of every symbol (-1: rejected)
     dol::DevArray<uint16_t> unary_head;
@@ -167,6 +167,75 @@ damp_apply1_bwd_kernel(Rows R, const float *__restrict__ x, int64_t ldx, const i
     });
 }
 
+// The same two for wide rows, staged in LDS (element_map.h).  Forward: the operand row is staged and the symbols of a
+// column are gathered from it, in the same order.  Backward: the gradient row, gated by the clamp, is staged and
+// every operand symbol picks its column's entry.
+__global__ void __launch_bounds__(kStageThreads)
+damp_apply1_fwd_staged_kernel(int32_t n_in, int32_t S, int32_t parts, const float *__restrict__ x, int64_t ldx,
+                              const uint32_t *__restrict__ order, const uint32_t *__restrict__ col_ptr, const uint16_t *__restrict__ tup,
+                              const uint4 *__restrict__ head, float *__restrict__ out, int64_t ldo)
+{
+    extern __shared__ __align__(16) float xr[];
+    const int64_t s = blockIdx.x / static_cast<unsigned>(parts);
+    int c0, c1;
+    stage_part(S, parts, static_cast<int>(blockIdx.x - s * parts), c0, c1);
+    stage_row(xr, x + s * ldx, n_in);
+    __syncthreads();
+    for (int r = c0 + threadIdx.x; r < c1; r += kStageThreads) {
+        const uint32_t c = order[r];                                       // lanes of a wavefront: columns of like length
+        const uint4 h = head[c];
+        const uint32_t w[4] = {h.x, h.y, h.z, h.w};
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {                                      // all eight reads at once (slot 0 for "none")
+            const uint32_t pos = (w[u / 2] >> (16 * (u & 1))) & 0xffffu;
+            v[u] = xr[pos != 0xffffu ? pos : 0u];
+        }
+        float acc = 0.0f;
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            if (((w[u / 2] >> (16 * (u & 1))) & 0xffffu) != 0xffffu) acc = acc + v[u];
+        if ((w[3] >> 16) != 0xffffu) {                                     // eight or more symbols: the rest of the list
+            const uint32_t q0 = col_ptr[c], q1 = col_ptr[c + 1];
+            if (q1 - q0 > static_cast<uint32_t>(kLongTableCol)) continue;  // left to the wavefront-per-column kernel
+            for (uint32_t q = q0 + 8; q < q1; q += kGatherK) {
+                uint32_t pos[kGatherK];
+#pragma unroll
+                for (int u = 0; u < kGatherK; ++u) pos[u] = tup[min(q + u, q1 - 1)];
+#pragma unroll
+                for (int u = 0; u < kGatherK; ++u)
+                    if (q + u < q1) acc = acc + xr[pos[u]];
+            }
+        }
+        out[s * ldo + c] = fminf(acc, 1.0f);
+    }
+}
+
+__global__ void __launch_bounds__(kStageThreads)
+damp_apply1_bwd_staged_kernel(int32_t n_in, int32_t S, int32_t parts, const float *__restrict__ x, int64_t ldx,
+                              const int32_t *__restrict__ col_of, const uint32_t *__restrict__ col_ptr,
+                              const uint16_t *__restrict__ tup, const float *__restrict__ out, int64_t ldo,
+                              const float *__restrict__ g, int64_t ldg, float *__restrict__ gx)
+{
+    extern __shared__ __align__(16) float gh[];
+    const int64_t s = blockIdx.x / static_cast<unsigned>(parts);
+    int i0, i1;
+    stage_part(n_in, parts, static_cast<int>(blockIdx.x - s * parts), i0, i1);
+    for (int c = threadIdx.x; c < S; c += kStageThreads) {
+        float v = g[s * ldg + c];
+        if (out[s * ldo + c] >= 1.0f) {             // pre == 1 passes, pre > 1 blocks: only pre itself tells
+            const float *row[1] = {x + s * ldx};
+            if (!(column_sum_k<1>(row, tup, col_ptr[c], col_ptr[c + 1]) <= 1.0f)) v = 0.0f;
+        }
+        gh[c] = v;
+    }
+    __syncthreads();
+    for (int i = i0 + threadIdx.x; i < i1; i += kStageThreads) {
+        const int32_t c = col_of[i];
+        gx[s * ldx + i] = c >= 0 ? gh[c] : 0.0f;
+    }
+}
+
 // One wavefront per (sample, long column): lanes stride over the tuples and their partial sums meet by shuffles.
 // That is not the order the clamp decision is defined in, so the lanes also add up the terms' magnitudes, which
 // bounds how far the two orders can lie apart (about n roundings of relative size 2^-24 each way); only a sum within
@@ -247,7 +316,18 @@ damp_applyk_bwd_kernel(Rows R, KOperands in, KGrads gin, const uint32_t *__restr
 template <int K>
 static void launch_fwd_k(const Rows &R, const KOperands &in, const dol_fnk_table *f, float *out, int64_t ldo, hipStream_t st)
 {
-    if (K == 1)
+    if (K == 1 && stage_fits(f->n_sym[0])) {
+        const int32_t parts = stage_parts(R.batch, f->n_out);
+        static bool attr_set = false;                // more than 64 KB of dynamic LDS has to be asked for once
+        if (!attr_set) {
+            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(damp_apply1_fwd_staged_kernel),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(kStageMaxBytes));
+            attr_set = true;
+        }
+        hipLaunchKernelGGL(damp_apply1_fwd_staged_kernel, dim3(static_cast<unsigned>(R.batch) * parts), dim3(kStageThreads),
+                           sizeof(float) * f->n_sym[0], st, f->n_sym[0], f->n_out, parts, in.p[0], in.ld[0], f->col_order.ptr,
+                           f->col_ptr.ptr, f->tup.ptr, reinterpret_cast<const uint4 *>(f->unary_head.ptr), out, ldo);
+    } else if (K == 1)
         hipLaunchKernelGGL(damp_apply1_fwd_kernel, dim3(R.grid), dim3(kThreads), 0, st, R, in.p[0], in.ld[0], f->col_ptr.ptr,
                            f->tup.ptr, reinterpret_cast<const uint4 *>(f->unary_head.ptr), out, ldo);
     else
@@ -263,7 +343,18 @@ template <int K>
 static void launch_bwd_k(const Rows &R, const KOperands &in, const KGrads &gin, const dol_fnk_table *f, const float *out,
                          int64_t ldo, const float *g, int64_t ldg, hipStream_t st)
 {
-    if (K == 1)
+    if (K == 1 && f->n_sym[0] >= kStageMinRow && sizeof(float) * f->n_out <= kStageMaxBytes) {
+        const int32_t parts = stage_parts(R.batch, f->n_sym[0]);
+        static bool attr_set = false;
+        if (!attr_set) {
+            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(damp_apply1_bwd_staged_kernel),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(kStageMaxBytes));
+            attr_set = true;
+        }
+        hipLaunchKernelGGL(damp_apply1_bwd_staged_kernel, dim3(static_cast<unsigned>(R.batch) * parts), dim3(kStageThreads),
+                           sizeof(float) * f->n_out, st, f->n_sym[0], f->n_out, parts, in.p[0], in.ld[0], f->unary_col.ptr,
+                           f->col_ptr.ptr, f->tup.ptr, out, ldo, g, ldg, gin.p[0]);
+    } else if (K == 1)
         hipLaunchKernelGGL(damp_apply1_bwd_kernel, dim3(R.grid), dim3(kThreads), 0, st, R, in.p[0], in.ld[0], f->unary_col.ptr,
                            f->col_ptr.ptr, f->tup.ptr, out, ldo, g, ldg, gin.p[0]);
     else
@@ -340,7 +431,9 @@ dtkp_applyk_kernel(int64_t total, int32_t S, int32_t arity, KProofs in, const ui
     if (idx >= total) return;
     const int64_t s = idx / S;
     const int32_t r = static_cast<int32_t>(idx - s * S);
-    const int32_t c = order ? static_cast<int32_t>(order[r]) : r;          // lanes of a wavefront: columns of like length
+    // lanes of a wavefront: columns of like length (not for a unary function under DTKP-AM, whose lists are one
+    // gather each: there the neighbouring columns' neighbouring symbols matter more)
+    const int32_t c = order ? static_cast<int32_t>(order[r]) : r;
     const float *fp = fact_prob + s * n_facts;
     const uint32_t q0 = col_ptr[c], q1 = col_ptr[c + 1];
     if (q1 - q0 > static_cast<uint32_t>(kLongDtkpCol)) return;             // left to the wavefront-per-column kernel
@@ -406,7 +499,7 @@ static void launch_dtkp_k(int64_t total, const dol_fnk_table *f, const KProofs &
                           const float *fact_prob, uint64_t *om, float *op, float *oprob, int64_t ldo, hipStream_t st)
 {
     hipLaunchKernelGGL(dtkp_applyk_kernel<KP>, dim3(static_cast<unsigned>((total + kThreadsP - 1) / kThreadsP)),
-                       dim3(kThreadsP), 0, st, total, f->n_out, f->K, in, f->dtkp_col_order.ptr, f->col_ptr.ptr, f->tup.ptr, gm,
+                       dim3(kThreadsP), 0, st, total, f->n_out, f->K, in, f->K >= 2 ? f->col_order.ptr : nullptr, f->col_ptr.ptr, f->tup.ptr, gm,
                        n_facts, fact_prob, om, op, oprob, ldo);
     const int64_t n_wave = f->n_wave_dtkp_cols, n_mid = static_cast<int64_t>(f->dtkp_long_cols.n) - n_wave;
     const int64_t batch = total / f->n_out;
@@ -512,8 +605,7 @@ static dol_status build_k(int32_t K, const int32_t *n_sym, int64_t n, const int3
     DOL_HIP(hipGetDevice(&tb->device));
     DOL_HIP(tb->long_cols.upload(long_cols));
     DOL_HIP(tb->dtkp_long_cols.upload(dtkp_long_cols));
-    // (a unary function's lists are one gather each: there the neighbouring columns' neighbouring symbols matter more)
-    if (K >= 2) DOL_HIP(tb->dtkp_col_order.upload(columns_by_length(col_ptr, S, kLongDtkpCol)));
+    DOL_HIP(tb->col_order.upload(columns_by_length(col_ptr, S, kLongDtkpCol)));
     DOL_HIP(tb->col_ptr.upload(col_ptr));
     DOL_HIP(tb->tup.upload(tup));
     DOL_HIP(tb->tup_col.upload(tup_col));

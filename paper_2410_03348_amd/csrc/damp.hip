@@ -85,6 +85,54 @@ damp_apply2_fwd_kernel(Rows R, const uint32_t *__restrict__ col_ptr, const uint3
     });
 }
 
+// The same for wide operand rows, staged in LDS (element_map.h): both rows of the sample are copied in, then every
+// thread walks columns as above with its gathers served by LDS.
+__global__ void __launch_bounds__(kStageThreads)
+damp_apply2_fwd_staged_kernel(int32_t na, int32_t nb, int32_t S, int32_t parts, const uint32_t *__restrict__ order,
+                              const uint32_t *__restrict__ col_ptr, const uint32_t *__restrict__ col_ij,
+                              const uint4 *__restrict__ col_head,
+                              const float *__restrict__ a, int64_t lda, const float *__restrict__ b, int64_t ldb,
+                              float *__restrict__ out, int64_t ldo)
+{
+    extern __shared__ __align__(16) float lds_rows[];
+    float *ar = lds_rows, *br = lds_rows + ((na + 3) & ~3);
+    const int64_t s = blockIdx.x / static_cast<unsigned>(parts);
+    int c0, c1;
+    stage_part(S, parts, static_cast<int>(blockIdx.x - s * parts), c0, c1);
+    stage_row(ar, a + s * lda, na);
+    stage_row(br, b + s * ldb, nb);
+    __syncthreads();
+    for (int r = c0 + threadIdx.x; r < c1; r += kStageThreads) {
+        const uint32_t c = order[r];                                       // lanes of a wavefront: columns of like length
+        const uint4 h = col_head[c];
+        const uint32_t t[4] = {h.x, h.y, h.z, h.w};
+        float x[4], y[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {                                      // all eight reads at once (tuple (0, 0) for "none")
+            const uint32_t ij = t[u] != 0xFFFFFFFFu ? t[u] : 0u;
+            x[u] = ar[ij & 0xffffu];
+            y[u] = br[ij >> 16];
+        }
+        float acc = 0.0f;
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (t[u] != 0xFFFFFFFFu) acc = __builtin_fmaf(x[u], y[u], acc);
+        if (t[3] != 0xFFFFFFFFu) {                                         // four or more tuples: the rest of the list
+            const uint32_t q0 = col_ptr[c], q1 = col_ptr[c + 1];
+            if (q1 - q0 > static_cast<uint32_t>(kLongTableCol)) continue;  // left to the wavefront-per-column kernel
+            for (uint32_t q = q0 + 4; q < q1; q += kGather) {
+                uint32_t ij[kGather];
+#pragma unroll
+                for (int u = 0; u < kGather; ++u) ij[u] = col_ij[min(q + u, q1 - 1)];
+#pragma unroll
+                for (int u = 0; u < kGather; ++u)
+                    if (q + u < q1) acc = __builtin_fmaf(ar[ij[u] & 0xffffu], br[ij[u] >> 16], acc);
+            }
+        }
+        out[s * ldo + c] = fminf(acc, 1.0f);
+    }
+}
+
 // One workgroup of 1, 4 or 16 wavefronts (by the table's longest column) per (sample, long column).  The lanes stride
 // over the column's tuples and their partial sums meet by shuffles and, between wavefronts, through LDS; this is not the order the clamp decision is defined in, so alongside the sum the lanes add up the
 // terms' magnitudes, which bounds how far the two orders can lie apart (n roundings of relative size 2^-24 each
@@ -226,8 +274,21 @@ dol_status launch_damp_apply2_fwd(const dol_fn_table *f, int32_t batch, const fl
         DOL_HIP(hipGetLastError());
         return launch_fwd_waves(f, f->byj_wave_cols, f->n_huge_byj_cols, batch, a, lda, b, ldb, out, ldo, st);
     }
-    hipLaunchKernelGGL(damp_apply2_fwd_kernel, dim3(R.grid), dim3(kThreads), 0, st, R, f->col_ptr.ptr, f->col_ij.ptr,
-                       reinterpret_cast<const uint4 *>(f->col_head.ptr), a, lda, b, ldb, out, ldo);
+    if (staged_fwd_ok(f)) {
+        const int32_t parts = stage_parts(batch, f->n_out);
+        static bool attr_set = false;                // more than 64 KB of dynamic LDS has to be asked for once
+        if (!attr_set) {
+            DOL_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(damp_apply2_fwd_staged_kernel),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(kStageMaxBytes)));
+            attr_set = true;
+        }
+        hipLaunchKernelGGL(damp_apply2_fwd_staged_kernel, dim3(static_cast<unsigned>(batch) * parts), dim3(kStageThreads),
+                           sizeof(float) * (((f->na + 3) & ~3) + f->nb), st, f->na, f->nb, f->n_out, parts, f->col_order.ptr,
+                           f->col_ptr.ptr, f->col_ij.ptr, reinterpret_cast<const uint4 *>(f->col_head.ptr), a, lda, b, ldb, out, ldo);
+    } else {
+        hipLaunchKernelGGL(damp_apply2_fwd_kernel, dim3(R.grid), dim3(kThreads), 0, st, R, f->col_ptr.ptr, f->col_ij.ptr,
+                           reinterpret_cast<const uint4 *>(f->col_head.ptr), a, lda, b, ldb, out, ldo);
+    }
     DOL_HIP(hipGetLastError());
     return launch_fwd_waves(f, f->long_cols, f->n_huge_cols, batch, a, lda, b, ldb, out, ldo, st);
 }

@@ -32,6 +32,13 @@ static int padded_nb(int nb) { return nb <= 4 ? 4 : nb <= 8 ? 8 : nb <= 10 ? 10 
 // Smallest row stride >= n with stride % 64 == 32: the two samples of a wavefront then use disjoint banks.
 static int pad_row(int n) { return ((n + 31) / 64) * 64 + 32; }
 
+// Tables served by the thread-per-column forward kernel whose operand rows are wide enough to be worth staging in
+// LDS and narrow enough to fit.
+bool staged_fwd_ok(const dol_fn_table *f)
+{
+    return std::max(f->na, f->nb) >= kStageMinRow && sizeof(float) * (static_cast<size_t>(f->na) + f->nb + 4) <= kStageMaxBytes;
+}
+
 bool conv_path_ok(const dol_fn_table *f)
 {
     return f->conv_like && f->nb <= kConvMaxNb && f->na + 3 * kConvMaxNb <= kConvMaxRow;
@@ -41,7 +48,8 @@ std::string damp_kernel_name(const dol_fn_table *f, bool backward)
 {
     if (!conv_path_ok(f)) {
         if (backward) return f->lds_bwd_ok ? "damp_lds_bwd_kernel" : !f->byj_ok ? "damp_apply2_bwd_kernel" : f->na + f->nb > 1024 ? "damp_byj_bwd_row_kernel" : "damp_byj_bwd_kernel";
-        return f->lds_fwd_ok ? "damp_lds_fwd_kernel" : f->byj_fwd ? "damp_byj_fwd_kernel" : "damp_apply2_fwd_kernel";
+        return f->lds_fwd_ok ? "damp_lds_fwd_kernel" : f->byj_fwd ? "damp_byj_fwd_kernel" :
+               staged_fwd_ok(f) ? "damp_apply2_fwd_staged_kernel" : "damp_apply2_fwd_kernel";
     }
     char buf[96];
     snprintf(buf, sizeof buf, "damp_conv_%s_%s_kernel<%d", backward ? "bwd" : "fwd",

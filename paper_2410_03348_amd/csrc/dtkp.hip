@@ -207,7 +207,7 @@ static void launch_apply2_k(int64_t total, const dol_fn_table *f, int32_t n_fact
                             hipStream_t st)
 {
     hipLaunchKernelGGL(dtkp_apply2_kernel<K>, dim3(grid_t(total)), dim3(kThreadsT), 0, st, total, f->n_out, f->na,
-                       f->nb, n_facts, f->dtkp_col_order.ptr, f->col_ptr.ptr, f->col_ij.ptr, gm, fact_prob, am, ap, bm, bp,
+                       f->nb, n_facts, f->col_order.ptr, f->col_ptr.ptr, f->col_ij.ptr, gm, fact_prob, am, ap, bm, bp,
                        fact_b, om, op, oprob, ldo);
     const int64_t n_long = static_cast<int64_t>(f->dtkp_long_cols.n);
     const int64_t n_huge = f->n_huge_dtkp_cols, batch = total / f->n_out;

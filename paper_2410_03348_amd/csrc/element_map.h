@@ -6,6 +6,8 @@
 
 #include "internal.h"
 
+#include <algorithm>
+
 namespace dol {
 
 constexpr int kThreads = 256;
@@ -50,6 +52,47 @@ __device__ __forceinline__ void for_each_element(const Rows &R, F f)
         if (c < 0) { c += R.n; --r; } else if (c >= R.n) { c -= R.n; ++r; }
         f(s0 + r, c);
     }
+}
+
+// ---- operand rows staged whole in LDS: one workgroup of kStageThreads per (sample, part of the output row)
+//
+// A gather from a row of thousands of tags misses the first-level cache on nearly every lane; from LDS it costs a
+// bank conflict or two.  So for wide operand rows a workgroup first copies the sample's row(s) into LDS with
+// coalesced loads and then gathers there.  Small batches are cut into several parts per sample (each stages the row
+// again) so that the chip still fills.
+constexpr int kStageThreads = 1024;
+
+static inline bool stage_fits(int64_t row_floats) { return row_floats >= kStageMinRow && row_floats * 4 <= static_cast<int64_t>(kStageMaxBytes); }
+
+// Parts per sample: enough workgroups for about two per compute unit, at most one per kStageThreads outputs.
+static inline int32_t stage_parts(int32_t batch, int32_t n_out)
+{
+    const int32_t most = (n_out + kStageThreads - 1) / kStageThreads;
+    const int32_t want = (512 + batch - 1) / batch;
+    return std::max(1, std::min(most, want));
+}
+
+// Copies n floats into LDS with every thread of the workgroup; 16-byte pieces when the source row allows.
+__device__ __forceinline__ void stage_row(float *__restrict__ dst, const float *__restrict__ src, int n)
+{
+    if ((reinterpret_cast<uintptr_t>(src) & 15u) == 0) {
+        const int n4 = n >> 2;
+#pragma unroll 4
+        for (int e = threadIdx.x; e < n4; e += kStageThreads)
+            reinterpret_cast<float4 *>(dst)[e] = reinterpret_cast<const float4 *>(src)[e];
+        for (int e = (n4 << 2) + threadIdx.x; e < n; e += kStageThreads) dst[e] = src[e];
+    } else {
+#pragma unroll 4
+        for (int e = threadIdx.x; e < n; e += kStageThreads) dst[e] = src[e];
+    }
+}
+
+// The columns [c0, c1) of part `part` of `parts` of a row of n.
+__device__ __forceinline__ void stage_part(int n, int parts, int part, int &c0, int &c1)
+{
+    const int per = (n + parts - 1) / parts;
+    c0 = part * per;
+    c1 = min(n, c0 + per);
 }
 
 }  // namespace dol

@@ -65,6 +65,8 @@ constexpr int kLongDtkpCol = 16;    // the same under DTKP, where a tuple costs 
 constexpr int kHugeTableCol = 4096; // columns with more tuples get a workgroup of 16 wavefronts instead of one wavefront
 constexpr int kHugeDtkpCol = 1024;  // the same under DTKP
 constexpr int kWaveDtkpCol = 64;    // DTKP columns of kLongDtkpCol+1 .. this many tuples share a wavefront four at a time
+constexpr int32_t kStageMinRow = 2048;       // operand rows of at least this many tags are staged in LDS before gathers;
+constexpr size_t kStageMaxBytes = 158 * 1024;   // narrower ones stay with the cached gathers; of the 160 KB of a compute unit
 constexpr int kByJMax = 16;         // tables whose second operand has at most this many symbols get dense per-j maps
 constexpr int kByJMaxNa = 65000;    // ... and whose first operand leaves room for the three marks below
 constexpr uint16_t kByJNone = 0xFFFF, kByJWave = 0xFFFE, kByJList = 0xFFFD;
@@ -100,8 +102,9 @@ struct dol_fn_table {
     dol::DevArray<uint32_t> long_rows;
     // output columns with more than dol::kLongTableCol / dol::kLongDtkpCol tuples
     dol::DevArray<uint32_t> long_cols, dtkp_long_cols;
-    // all columns in the order the thread-per-column DTKP kernel takes them (dol::columns_by_length)
-    dol::DevArray<uint32_t> dtkp_col_order;
+    // all columns in the order the thread-per-column kernels over long operand rows take them
+    // (dol::columns_by_length, with the DTKP kernel's limit on the length of a column)
+    dol::DevArray<uint32_t> col_order;
     // each list starts with its huge columns (more than dol::kHugeTableCol / dol::kHugeDtkpCol tuples)
     int32_t n_huge_cols = 0, n_huge_dtkp_cols = 0, n_huge_byj_cols = 0;
     int32_t n_wave_dtkp_cols = 0;        // dtkp_long_cols: huge, then this many one-wavefront columns, then the shorter ones
@@ -197,6 +200,7 @@ dol_status launch_nll_grad(int32_t batch, int32_t n, const float *p, int64_t ld,
                            hipStream_t st);
 // Convolution-shaped tables with a short second operand (damp_conv.hip)
 bool conv_path_ok(const dol_fn_table *f);
+bool staged_fwd_ok(const dol_fn_table *f);   // forward through the kernel that stages both operand rows in LDS
 std::string damp_kernel_name(const dol_fn_table *f, bool backward);
 dol_status launch_damp_conv_fwd(const dol_fn_table *f, int32_t batch, const float *a, int64_t lda, const float *b,
                                 int64_t ldb, float *out, int64_t ldo, hipStream_t st);

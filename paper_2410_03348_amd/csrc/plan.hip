@@ -143,7 +143,7 @@ static dol_status build_table(int32_t na, int32_t nb, std::vector<Tuple> &tup, d
     hipError_t e;
     if ((e = tb->long_rows.upload(long_rows)) != hipSuccess) return hip_fail(e, "uploading the function table");
     if ((e = tb->long_cols.upload(long_cols)) != hipSuccess || (e = tb->dtkp_long_cols.upload(dtkp_long_cols)) != hipSuccess ||
-        (e = tb->dtkp_col_order.upload(columns_by_length(col_ptr, S, kLongDtkpCol))) != hipSuccess)
+        (e = tb->col_order.upload(columns_by_length(col_ptr, S, kLongDtkpCol))) != hipSuccess)
         return hip_fail(e, "uploading the function table");
     std::vector<uint32_t> col_head(static_cast<size_t>(S) * 4, 0xFFFFFFFFu);
     for (int32_t c = 0; c < S; ++c)

@@ -883,6 +883,59 @@ def test_apply_k_damp_forward_and_backward(dol, shape, n_ids, scale, batch):
         assert np.all(got[:, n:] == 5.0)
 
 
+@pytest.mark.parametrize("batch", [3, 300])
+def test_wide_operand_rows_staged_in_lds(dol, batch):
+    """Unary and binary Apply over operand rows of thousands of tags (the kernels that copy a sample's rows into LDS
+    and gather there): a few workgroups per sample at batch 3, one at batch 300; padded rows whose starts fall off
+    16-byte boundaries; columns of every length from 1 up, one of them long enough for the wavefront kernel; tags
+    scaled so that columns clamp, with pre exactly 1 (gradient passes) and pre > 1 (blocked) in sample 0."""
+    # ---- unary
+    n_in, n_ids = 5001, 700
+    table = _rand_table(6100, (n_in,), n_ids, drop_every=9)
+    table[:200:2] = 5                                                  # 100 symbols on one column
+    x = (W.softmax_rows(W.normal(6101, batch * n_in).reshape(batch, n_in)) * 700.0).astype(np.float32)
+    x[0, :] = 0.125                                                    # columns of 8 symbols sum to exactly 1
+    idx, to = oracle.dense_to_tuples(table)
+    syms, want, pre32, _ = oracle.damp_applyk_fwd(idx, to, [x], want_pre=True)
+    assert (pre32[0] == 1).any() and (pre32 > 1).any() and (pre32 < 1).any()
+    f = dol.FnkTable.create_dense(table)
+    buf = torch.zeros((batch, n_in + 3), device="cuda")
+    buf[:, :n_in] = dev(x)
+    d_in = [dol.Dist(np.arange(n_in), buf[:, :n_in])]
+    out = dol.Dist.empty(f.out_syms, batch)
+    dol.apply_k(d_in, f, None, out)
+    assert_close(host(out.prob), want, "wide unary forward")
+    g = np.abs(W.normal(6102, batch * syms.size).astype(np.float32).reshape(batch, -1)) + np.float32(0.5)
+    (wx,) = oracle.damp_applyk_bwd(idx, to, [x], g)
+    gx = torch.full((batch, n_in + 3), 5.0, device="cuda")
+    dol.apply_k_backward(d_in, f, out, dev(g), [gx])
+    got = host(gx)
+    np.testing.assert_array_equal(got[:, :n_in], wx)                   # each entry is a gradient entry or 0
+    assert np.all(got[:, n_in:] == 5.0)
+    assert (wx[0] == 0).any() and (wx[0] != 0).any()
+    # ---- binary
+    na, nb = 3000, 20
+    table2 = _rand_table(6110, (na, nb), 9000, drop_every=7)
+    table2[:90, 0] = 17                                                # a long column
+    a = (W.softmax_rows(W.normal(6111, batch * na).reshape(batch, na)) * (na * 1.2)).astype(np.float32)
+    b = (W.softmax_rows(W.normal(6112, batch * nb).reshape(batch, nb)) * 3.0).astype(np.float32)
+    tri = oracle.dense_to_triples(table2)
+    syms2, want2, pre2, _ = oracle.damp_apply2_fwd(tri, na, nb, a, b, want_pre=True)
+    assert (pre2 > 1).any() and (pre2 < 1).any()
+    f2 = dol.FnTable.create_dense(table2)
+    assert f2.kernel_fwd == "damp_apply2_fwd_staged_kernel"
+    abuf = torch.zeros((batch, na + 1), device="cuda")
+    abuf[:, :na] = dev(a)
+    bbuf = torch.zeros((batch, nb + 2), device="cuda")
+    bbuf[:, :nb] = dev(b)
+    da, db = dol.Dist(np.arange(na), abuf[:, :na]), dol.Dist(np.arange(nb), bbuf[:, :nb])
+    out2 = dol.Dist.empty(f2.out_syms, batch)
+    dol.apply2(da, db, f2, None, out2)
+    np.testing.assert_array_equal(out2.sym_ids, syms2)
+    assert_close(host(out2.prob), want2, "wide binary forward")
+    np.testing.assert_array_equal(host(out2.prob) == 1.0, pre2 >= 1.0)
+
+
 def test_apply_k_two_operands_equal_apply2_bit_for_bit(dol):
     B = 150
     table = W.hashed_table(41, 30, 20, 64)
