@@ -427,7 +427,8 @@ dtkp_applyk_kernel(int64_t total, int32_t S, int32_t arity, KProofs in, const ui
                    const uint16_t *__restrict__ tup, GroupMasks gm, int32_t n_facts, const float *__restrict__ fact_prob,
                    uint64_t *__restrict__ om, float *__restrict__ op, float *__restrict__ oprob, int64_t ldo)
 {
-    const int64_t idx = static_cast<int64_t>(blockIdx.x) * kThreadsP + threadIdx.x;
+    // (each XCD takes a contiguous range of samples: a sample's operand lists then fill one L2 and not all eight)
+    const int64_t idx = static_cast<int64_t>(xcd_contiguous(blockIdx.x, gridDim.x)) * kThreadsP + threadIdx.x;
     if (idx >= total) return;
     const int64_t s = idx / S;
     const int32_t r = static_cast<int32_t>(idx - s * S);

@@ -112,7 +112,8 @@ dtkp_apply2_kernel(int64_t total, int32_t S, int32_t na, int32_t nb, int32_t n_f
                    const int32_t *__restrict__ fact_b, uint64_t *__restrict__ om, float *__restrict__ op,
                    float *__restrict__ oprob, int64_t ldo)
 {
-    const int64_t idx = static_cast<int64_t>(blockIdx.x) * kThreadsT + threadIdx.x;
+    // (each XCD takes a contiguous range of samples: a sample's operand lists then fill one L2 and not all eight)
+    const int64_t idx = static_cast<int64_t>(xcd_contiguous(blockIdx.x, gridDim.x)) * kThreadsT + threadIdx.x;
     if (idx >= total) return;
     const int64_t s = idx / S;
     const int32_t c = static_cast<int32_t>(order[idx - s * S]);          // lanes of a wavefront: columns of like length
