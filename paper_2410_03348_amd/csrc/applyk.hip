@@ -456,8 +456,9 @@ dtkp_applyk_long_kernel(int32_t n_long, const uint32_t *__restrict__ long_cols, 
                         int32_t n_facts, const float *__restrict__ fact_prob, uint64_t *__restrict__ om,
                         float *__restrict__ op, float *__restrict__ oprob, int64_t ldo)
 {
-    const int64_t s = blockIdx.x / n_long;
-    const uint32_t c = long_cols[blockIdx.x - s * n_long];
+    const int64_t wg = xcd_contiguous(blockIdx.x, gridDim.x);       // a sample's columns on one XCD: its lists fill one L2
+    const int64_t s = wg / n_long;
+    const uint32_t c = long_cols[wg - s * n_long];
     const float *fp = fact_prob + s * n_facts;
     TopK<KP> top;
     top.clear();
@@ -479,8 +480,9 @@ dtkp_applyk_mid_kernel(int32_t n_mid, const uint32_t *__restrict__ cols, int32_t
                        float *__restrict__ op, float *__restrict__ oprob, int64_t ldo)
 {
     const int32_t quads = (n_mid + 3) / 4;
-    const int64_t s = blockIdx.x / quads;
-    const int32_t ci = static_cast<int32_t>(blockIdx.x - s * quads) * 4 + static_cast<int32_t>(threadIdx.x / 16);
+    const int64_t wg = xcd_contiguous(blockIdx.x, gridDim.x);       // a sample's columns on one XCD: its lists fill one L2
+    const int64_t s = wg / quads;
+    const int32_t ci = static_cast<int32_t>(wg - s * quads) * 4 + static_cast<int32_t>(threadIdx.x / 16);
     if (ci >= n_mid) return;                        // a whole group of 16 lanes at once
     const uint32_t c = cols[ci];
     const float *fp = fact_prob + s * n_facts;

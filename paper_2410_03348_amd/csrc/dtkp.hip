@@ -142,8 +142,9 @@ dtkp_apply2_long_kernel(int32_t n_long, const uint32_t *__restrict__ long_cols, 
                         const int32_t *__restrict__ fact_b, uint64_t *__restrict__ om, float *__restrict__ op,
                         float *__restrict__ oprob, int64_t ldo)
 {
-    const int64_t s = blockIdx.x / n_long;
-    const uint32_t c = long_cols[blockIdx.x - s * n_long];
+    const int64_t wg = xcd_contiguous(blockIdx.x, gridDim.x);       // a sample's columns on one XCD: its lists fill one L2
+    const int64_t s = wg / n_long;
+    const uint32_t c = long_cols[wg - s * n_long];
     const float *fp = fact_prob + s * n_facts;
     const int64_t a0 = s * na * K, b0 = s * nb * K;
     TopK<K> top;
@@ -184,8 +185,9 @@ dtkp_apply2_mid_kernel(int32_t n_mid, const uint32_t *__restrict__ cols, int32_t
                        uint64_t *__restrict__ om, float *__restrict__ op, float *__restrict__ oprob, int64_t ldo)
 {
     const int32_t quads = (n_mid + 3) / 4;
-    const int64_t s = blockIdx.x / quads;
-    const int32_t ci = static_cast<int32_t>(blockIdx.x - s * quads) * 4 + static_cast<int32_t>(threadIdx.x / 16);
+    const int64_t wg = xcd_contiguous(blockIdx.x, gridDim.x);       // a sample's columns on one XCD: its lists fill one L2
+    const int64_t s = wg / quads;
+    const int32_t ci = static_cast<int32_t>(wg - s * quads) * 4 + static_cast<int32_t>(threadIdx.x / 16);
     if (ci >= n_mid) return;                        // a whole group of 16 lanes at once
     const uint32_t c = cols[ci];
     const float *fp = fact_prob + s * n_facts;
