@@ -205,6 +205,10 @@ dol_status dol_fnk_table_create(int32_t K, const int32_t *n_sym, int64_t n, cons
 /* Distinct produced symbols S and their ids ascending (host [S], valid until destroy): column c of the result. */
 int32_t dol_fnk_table_n_out(const dol_fnk_table *table);
 const int32_t *dol_fnk_table_out_syms(const dol_fnk_table *table);
+/* Name of the HIP kernel that dol_apply_k (which = 0) or dol_apply_k_backward (which = 1) launches for this table
+ * under DAMP, as a profiler prints it without namespace (valid until the next call on this thread); the library
+ * picks it from the table's structure, as dol_fn_table_kernel does. */
+const char *dol_fnk_table_kernel(const dol_fnk_table *table, int32_t which);
 /* Synchronises the device before releasing the device copies.  NULL is ignored. */
 void dol_fnk_table_destroy(dol_fnk_table *table);
 

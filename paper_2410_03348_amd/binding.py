@@ -64,6 +64,8 @@ _lib.dol_fnk_table_n_out.argtypes = [C.c_void_p]
 _lib.dol_fnk_table_n_out.restype = C.c_int32
 _lib.dol_fnk_table_out_syms.argtypes = [C.c_void_p]
 _lib.dol_fnk_table_out_syms.restype = _i32p
+_lib.dol_fnk_table_kernel.argtypes = [C.c_void_p, C.c_int32]
+_lib.dol_fnk_table_kernel.restype = C.c_char_p
 _lib.dol_fnk_table_destroy.argtypes = [C.c_void_p]
 _lib.dol_fnk_table_destroy.restype = None
 _lib.dol_apply_k.argtypes = [C.c_int32, C.POINTER(C.POINTER(_Dist)), C.c_void_p, C.POINTER(_Prov), C.POINTER(_Dist), C.c_void_p]
@@ -252,6 +254,8 @@ class FnkTable:
                                          _ptr(o, C.c_int32), C.byref(h)))
         self._h, self.n_sym = h, n_sym
         self.n_out = int(_lib.dol_fnk_table_n_out(h))
+        self.kernel_fwd = _lib.dol_fnk_table_kernel(h, 0).decode()
+        self.kernel_bwd = _lib.dol_fnk_table_kernel(h, 1).decode()
         p = _lib.dol_fnk_table_out_syms(h)
         self.out_syms = np.ctypeslib.as_array(p, shape=(self.n_out,)).copy() if self.n_out else np.empty(0, np.int32)
 

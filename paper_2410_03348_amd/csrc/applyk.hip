@@ -12,6 +12,7 @@
 #include "wave_util.h"
 
 #include <algorithm>
+#include <cstdio>
 #include <memory>
 #include <new>
 #include <numeric>
@@ -313,10 +314,17 @@ damp_applyk_bwd_kernel(Rows R, KOperands in, KGrads gin, const uint32_t *__restr
     });
 }
 
+// Unary functions over wide rows go through the kernels that stage a row in LDS.
+static bool staged_unary_fwd(const dol_fnk_table *f) { return f->K == 1 && stage_fits(f->n_sym[0]); }
+static bool staged_unary_bwd(const dol_fnk_table *f)
+{
+    return f->K == 1 && f->n_sym[0] >= kStageMinRow && sizeof(float) * f->n_out <= kStageMaxBytes;
+}
+
 template <int K>
 static void launch_fwd_k(const Rows &R, const KOperands &in, const dol_fnk_table *f, float *out, int64_t ldo, hipStream_t st)
 {
-    if (K == 1 && stage_fits(f->n_sym[0])) {
+    if (K == 1 && staged_unary_fwd(f)) {
         const int32_t parts = stage_parts(R.batch, f->n_out);
         static bool attr_set = false;                // more than 64 KB of dynamic LDS has to be asked for once
         if (!attr_set) {
@@ -343,7 +351,7 @@ template <int K>
 static void launch_bwd_k(const Rows &R, const KOperands &in, const KGrads &gin, const dol_fnk_table *f, const float *out,
                          int64_t ldo, const float *g, int64_t ldg, hipStream_t st)
 {
-    if (K == 1 && f->n_sym[0] >= kStageMinRow && sizeof(float) * f->n_out <= kStageMaxBytes) {
+    if (K == 1 && staged_unary_bwd(f)) {
         const int32_t parts = stage_parts(R.batch, f->n_sym[0]);
         static bool attr_set = false;
         if (!attr_set) {
@@ -656,6 +664,18 @@ dol_status dol_fnk_table_create(int32_t K, const int32_t *n_sym, int64_t n, cons
 int32_t dol_fnk_table_n_out(const dol_fnk_table *table) { return table ? table->n_out : 0; }
 
 const int32_t *dol_fnk_table_out_syms(const dol_fnk_table *table) { return table ? table->out_syms.data() : nullptr; }
+
+const char *dol_fnk_table_kernel(const dol_fnk_table *table, int32_t which)
+{
+    static thread_local char name[64];
+    if (!table) return "";
+    if (table->K == 1)
+        snprintf(name, sizeof name, "damp_apply1_%s%s_kernel", which ? "bwd" : "fwd",
+                 (which ? staged_unary_bwd(table) : staged_unary_fwd(table)) ? "_staged" : "");
+    else
+        snprintf(name, sizeof name, "damp_applyk_%s_kernel<%d>", which ? "bwd" : "fwd", table->K);
+    return name;
+}
 
 void dol_fnk_table_destroy(dol_fnk_table *table) { delete table; }
 

@@ -474,7 +474,7 @@ class HwfPipeline(Program):
         self.out = dol.Dist.empty(self.final.out_syms, B, device, k=k)
         last = self.accs[-1]
         per = 12 * k + 4 if dtkp else 4
-        self.launches.append(Launch("dtkp_applyk_kernel" if dtkp else "damp_applyk_fwd_kernel",
+        self.launches.append(Launch("dtkp_applyk_kernel" if dtkp else self.final.kernel_fwd,
                                     lambda: dol.apply_k([last], self.final, self.prov, self.out),
                                     B * per * (last.n_sym + self.out.n_sym), B * last.n_sym * max(k, 1), "fwd"))
         n_ops = 2 * L + (1 if dtkp else 0)
@@ -490,9 +490,9 @@ class HwfPipeline(Program):
             self.g_acc = [torch.empty((B, d.n_sym), dtype=torch.float32, device=device) for d in self.accs]
             self.g_x = [torch.empty((B, d.n_sym), dtype=torch.float32, device=device) for d in self.xs]
             self.g_acc[0] = self.g_x[0]                                # the first accumulator is position 0 itself
-            self.launches.append(Launch("damp_applyk_bwd_kernel",
+            self.launches.append(Launch(self.final.kernel_bwd,
                                         lambda: dol.apply_k_backward([last], self.final, self.out, self.g, [self.g_acc[-1]]),
-                                        4 * B * (2 * last.n_sym + 2 * self.out.n_sym), B * last.n_sym, "bwd"))
+                                        4 * B * (last.n_sym + 2 * self.out.n_sym), B * last.n_sym, "bwd"))   # out, g in; gx out
             self.records = [dol.OpRecord(dol.OP_APPLY2, self.accs[t - 1], self.xs[t], self.accs[t], f=self.tables[t - 1])
                             for t in range(1, L)]
             for t in range(L - 1, 0, -1):

@@ -899,6 +899,7 @@ def test_wide_operand_rows_staged_in_lds(dol, batch):
     syms, want, pre32, _ = oracle.damp_applyk_fwd(idx, to, [x], want_pre=True)
     assert (pre32[0] == 1).any() and (pre32 > 1).any() and (pre32 < 1).any()
     f = dol.FnkTable.create_dense(table)
+    assert (f.kernel_fwd, f.kernel_bwd) == ("damp_apply1_fwd_staged_kernel", "damp_apply1_bwd_staged_kernel")
     buf = torch.zeros((batch, n_in + 3), device="cuda")
     buf[:, :n_in] = dev(x)
     d_in = [dol.Dist(np.arange(n_in), buf[:, :n_in])]
