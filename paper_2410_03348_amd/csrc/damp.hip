@@ -431,25 +431,39 @@ damp_byj_bwd_kernel(Rows R, BwdTable T, const uint16_t *__restrict__ col_of, con
     });
 }
 
-// The same for wide operands (na + nb > 1024): one workgroup of 1024 threads owns a whole sample.  A first pass over
-// the sample's result row tells whether any column sits at the clamp; if none does, the gate is open everywhere and
-// `out` is not gathered again.  Each thread also adds its rows' shares g^[col(i, j)] * a[i] of the gradient w.r.t.
-// b[j] into registers; the workgroup sums them, so the long rows of b need no launch of their own.
+// The same for wide operands (na + nb > 1024): one workgroup of 1024 threads owns a whole sample.  STAGED (the result
+// row fits LDS): a first pass copies the sample's gradient row into LDS, gated by the clamp (a column with out == 1 has
+// its sum taken again), and the rows then gather from LDS alone.  Otherwise a first pass over the sample's result row
+// tells whether any column sits at the clamp; if none does, the gate is open everywhere and `out` is not gathered
+// again.  Each thread also adds its rows' shares g^[col(i, j)] * a[i] of the gradient w.r.t. b[j] into registers; the
+// workgroup sums them, so the long rows of b need no launch of their own.
 constexpr int kByJRowThreads = 1024;
 
-template <int NBP>
+template <int NBP, bool STAGED>
 __global__ void __launch_bounds__(kByJRowThreads)
 damp_byj_bwd_row_kernel(BwdTable T, int32_t S, const uint16_t *__restrict__ col_of, const float *__restrict__ a,
                         int64_t lda, const float *__restrict__ b, int64_t ldb, const float *__restrict__ out, int64_t ldo,
                         const float *__restrict__ g, int64_t ldg, float *__restrict__ ga, float *__restrict__ gb,
                         int32_t accumulate)
 {
+    extern __shared__ __align__(16) float gh_row[];                 // STAGED: [S] gated gradient
     __shared__ float red[NBP][kByJRowThreads / kWave];
     const int64_t s = blockIdx.x;
     const float *ar = a + s * lda, *br = b + s * ldb, *outr = out + s * ldo, *gr = g + s * ldg;
-    int hit = 0;
-    for (int c = threadIdx.x; c < S; c += kByJRowThreads) hit |= outr[c] >= 1.0f;
-    const bool clamped = __syncthreads_or(hit) != 0;
+    bool clamped = false;
+    if (STAGED) {
+        for (int c = threadIdx.x; c < S; c += kByJRowThreads) {
+            const float o = outr[c];
+            float v = gr[c];
+            if (o >= 1.0f) v = gated_grad(v, o, ar, br, T.col_ptr, T.col_ij, c);
+            gh_row[c] = v;
+        }
+        __syncthreads();
+    } else {
+        int hit = 0;
+        for (int c = threadIdx.x; c < S; c += kByJRowThreads) hit |= outr[c] >= 1.0f;
+        clamped = __syncthreads_or(hit) != 0;
+    }
     float bj[NBP], pb[NBP];
 #pragma unroll
     for (int j = 0; j < NBP; ++j) {
@@ -457,7 +471,8 @@ damp_byj_bwd_row_kernel(BwdTable T, int32_t S, const uint16_t *__restrict__ col_
         pb[j] = 0.0f;
     }
     for (int i = threadIdx.x; i < T.na; i += kByJRowThreads) {
-        const float acc = byj_row<NBP, true>(col_of, T.na, i, clamped, gr, outr, ar, br, bj, T, pb);
+        const float acc = STAGED ? byj_row<NBP, true>(col_of, T.na, i, false, gh_row, outr, ar, br, bj, T, pb)
+                                 : byj_row<NBP, true>(col_of, T.na, i, clamped, gr, outr, ar, br, bj, T, pb);
         if (ga) {
             float *dst = ga + s * lda + i;
             *dst = (accumulate & 1) ? *dst + acc : acc;
@@ -507,6 +522,9 @@ damp_apply2_bwd_long_kernel(int32_t n_long, const uint32_t *__restrict__ long_ro
     }
 }
 
+// The workgroup-per-sample backward stages the gated gradient row in LDS when it fits beside the reduction scratch.
+static bool byj_bwd_staged(const dol_fn_table *f) { return sizeof(float) * f->n_out + 2048 <= kStageMaxBytes; }
+
 dol_status launch_damp_apply2_bwd(const dol_fn_table *f, int32_t batch, const float *a, int64_t lda, const float *b,
                                   int64_t ldb, const float *out, int64_t ldo, const float *g, int64_t ldg, float *ga,
                                   float *gb, int32_t accumulate, hipStream_t st)
@@ -520,10 +538,27 @@ dol_status launch_damp_apply2_bwd(const dol_fn_table *f, int32_t batch, const fl
                      f->na, f->nb};
     const Rows R = rows_of(batch, f->na + f->nb);
     if (f->byj_ok && R.rpb == 1) {
-#define CALL(N) hipLaunchKernelGGL(damp_byj_bwd_row_kernel<N>, dim3(static_cast<unsigned>(batch)), dim3(kByJRowThreads), 0, \
-                                   st, T, f->n_out, f->byj_col.ptr, a, lda, b, ldb, out, ldo, g, ldg, ga, gb, accumulate)
-        DOL_DISPATCH_NBP(f->byj_nbp, CALL)
+        if (byj_bwd_staged(f)) {
+#define CALL(N)                                                                                                           \
+    {                                                                                                                     \
+        static bool attr_set = false; /* more than 64 KB of dynamic LDS has to be asked for once */                       \
+        if (!attr_set) {                                                                                                  \
+            DOL_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(damp_byj_bwd_row_kernel<N, true>),                 \
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(kStageMaxBytes)));   \
+            attr_set = true;                                                                                              \
+        }                                                                                                                 \
+        hipLaunchKernelGGL((damp_byj_bwd_row_kernel<N, true>), dim3(static_cast<unsigned>(batch)), dim3(kByJRowThreads),  \
+                           sizeof(float) * f->n_out, st, T, f->n_out, f->byj_col.ptr, a, lda, b, ldb, out, ldo, g, ldg,   \
+                           ga, gb, accumulate);                                                                           \
+    }
+            DOL_DISPATCH_NBP(f->byj_nbp, CALL)
 #undef CALL
+        } else {
+#define CALL(N) hipLaunchKernelGGL((damp_byj_bwd_row_kernel<N, false>), dim3(static_cast<unsigned>(batch)), dim3(kByJRowThreads), 0, \
+                                   st, T, f->n_out, f->byj_col.ptr, a, lda, b, ldb, out, ldo, g, ldg, ga, gb, accumulate)
+            DOL_DISPATCH_NBP(f->byj_nbp, CALL)
+#undef CALL
+        }
         DOL_HIP(hipGetLastError());
         return DOL_OK;
     }
