@@ -230,6 +230,54 @@ damp_byj_fwd_kernel(Rows R, int32_t nb, const uint16_t *__restrict__ src, const 
     });
 }
 
+// The same with the first operand's row staged in LDS (element_map.h), for rows of thousands of tags: one workgroup
+// per (sample, part of the output row); the map is still read coalesced and the gathers become LDS reads (an empty
+// entry reads element 0 and counts as 0).
+template <int NBP>
+__global__ void __launch_bounds__(kStageThreads)
+damp_byj_fwd_staged_kernel(int32_t na, int32_t nb, int32_t S, int32_t parts, const uint16_t *__restrict__ src,
+                           const uint32_t *__restrict__ col_ptr, const uint32_t *__restrict__ col_ij,
+                           const float *__restrict__ a, int64_t lda, const float *__restrict__ b, int64_t ldb,
+                           float *__restrict__ out, int64_t ldo)
+{
+    extern __shared__ __align__(16) float a_row[];
+    const int64_t s = blockIdx.x / static_cast<unsigned>(parts);
+    int c0, c1;
+    stage_part(S, parts, static_cast<int>(blockIdx.x - s * parts), c0, c1);
+    const float *ar = a + s * lda, *br = b + s * ldb;
+    stage_row(a_row, ar, na);
+    float y[NBP];
+#pragma unroll
+    for (int j = 0; j < NBP; ++j) y[j] = br[j < nb ? j : 0];
+    __syncthreads();
+    for (int c = c0 + threadIdx.x; c < c1; c += kStageThreads) {
+        uint16_t i[NBP];
+        float x[NBP];
+#pragma unroll
+        for (int j = 0; j < NBP; ++j) i[j] = src[static_cast<size_t>(j) * S + c];
+        if (i[0] == kByJWave) continue;                                   // left to the wavefront-per-column kernel
+        if (i[0] == kByJList) {                                           // some j twice: the tuple list itself
+            out[s * ldo + c] = fminf(column_sum(ar, br, col_ij, col_ptr[c], col_ptr[c + 1]), 1.0f);
+            continue;
+        }
+#pragma unroll
+        for (int j = 0; j < NBP; ++j) {
+            const float v = a_row[i[j] != kByJNone ? i[j] : 0];
+            x[j] = i[j] != kByJNone ? v : 0.0f;
+        }
+        float acc = 0.0f, mag = 0.0f;
+#pragma unroll
+        for (int j = 0; j < NBP; ++j) {
+            acc = __builtin_fmaf(x[j], y[j], acc);
+            mag = __builtin_fmaf(fabsf(x[j]), fabsf(y[j]), mag);
+        }
+        float pre = acc;
+        if (fabsf(acc - 1.0f) <= mag * (static_cast<float>(NBP + 2) * 1.1920929e-7f))
+            pre = column_sum(ar, br, col_ij, col_ptr[c], col_ptr[c + 1]);
+        out[s * ldo + c] = fminf(pre, 1.0f);
+    }
+}
+
 #define DOL_DISPATCH_NBP(nbp, CALL) \
     switch (nbp) {                  \
     case 4: CALL(4); break;         \
@@ -266,6 +314,25 @@ dol_status launch_damp_apply2_fwd(const dol_fn_table *f, int32_t batch, const fl
     if (dol_status s2 = launch_damp_lds_fwd(f, batch, a, lda, b, ldb, out, ldo, st, &done)) return s2;
     if (done) return DOL_OK;
     const Rows R = rows_of(batch, f->n_out);
+    if (f->byj_fwd && byj_fwd_staged_ok(f)) {
+        const int32_t parts = stage_parts(batch, f->n_out);
+#define CALL(N)                                                                                                           \
+    {                                                                                                                     \
+        static bool attr_set = false; /* more than 64 KB of dynamic LDS has to be asked for once */                       \
+        if (!attr_set) {                                                                                                  \
+            DOL_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(damp_byj_fwd_staged_kernel<N>),                    \
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(kStageMaxBytes)));   \
+            attr_set = true;                                                                                              \
+        }                                                                                                                 \
+        hipLaunchKernelGGL(damp_byj_fwd_staged_kernel<N>, dim3(static_cast<unsigned>(batch) * parts), dim3(kStageThreads), \
+                           sizeof(float) * f->na, st, f->na, f->nb, f->n_out, parts, f->byj_src.ptr, f->col_ptr.ptr,      \
+                           f->col_ij.ptr, a, lda, b, ldb, out, ldo);                                                      \
+    }
+        DOL_DISPATCH_NBP(f->byj_nbp, CALL)
+#undef CALL
+        DOL_HIP(hipGetLastError());
+        return launch_fwd_waves(f, f->byj_wave_cols, f->n_huge_byj_cols, batch, a, lda, b, ldb, out, ldo, st);
+    }
     if (f->byj_fwd) {
 #define CALL(N) hipLaunchKernelGGL(damp_byj_fwd_kernel<N>, dim3(R.grid), dim3(kThreads), 0, st, R, f->nb, f->byj_src.ptr, \
                                    f->col_ptr.ptr, f->col_ij.ptr, a, lda, b, ldb, out, ldo)

@@ -39,6 +39,12 @@ bool staged_fwd_ok(const dol_fn_table *f)
     return std::max(f->na, f->nb) >= kStageMinRow && sizeof(float) * (static_cast<size_t>(f->na) + f->nb + 4) <= kStageMaxBytes;
 }
 
+// Tables walked through their per-j map whose first operand's row is worth staging in LDS, and fits.
+bool byj_fwd_staged_ok(const dol_fn_table *f)
+{
+    return f->na >= kStageMinRow && sizeof(float) * static_cast<size_t>(f->na) <= kStageMaxBytes;
+}
+
 bool conv_path_ok(const dol_fn_table *f)
 {
     return f->conv_like && f->nb <= kConvMaxNb && f->na + 3 * kConvMaxNb <= kConvMaxRow;
@@ -48,7 +54,7 @@ std::string damp_kernel_name(const dol_fn_table *f, bool backward)
 {
     if (!conv_path_ok(f)) {
         if (backward) return f->lds_bwd_ok ? "damp_lds_bwd_kernel" : !f->byj_ok ? "damp_apply2_bwd_kernel" : f->na + f->nb > 1024 ? "damp_byj_bwd_row_kernel" : "damp_byj_bwd_kernel";
-        return f->lds_fwd_ok ? "damp_lds_fwd_kernel" : f->byj_fwd ? "damp_byj_fwd_kernel" :
+        return f->lds_fwd_ok ? "damp_lds_fwd_kernel" : f->byj_fwd ? (byj_fwd_staged_ok(f) ? "damp_byj_fwd_staged_kernel" : "damp_byj_fwd_kernel") :
                staged_fwd_ok(f) ? "damp_apply2_fwd_staged_kernel" : "damp_apply2_fwd_kernel";
     }
     char buf[96];

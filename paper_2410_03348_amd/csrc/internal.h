@@ -200,6 +200,7 @@ dol_status launch_nll_grad(int32_t batch, int32_t n, const float *p, int64_t ld,
                            hipStream_t st);
 // Convolution-shaped tables with a short second operand (damp_conv.hip)
 bool conv_path_ok(const dol_fn_table *f);
+bool byj_fwd_staged_ok(const dol_fn_table *f);   // forward through the per-j map with the first operand's row in LDS
 bool staged_fwd_ok(const dol_fn_table *f);   // forward through the kernel that stages both operand rows in LDS
 std::string damp_kernel_name(const dol_fn_table *f, bool backward);
 dol_status launch_damp_conv_fwd(const dol_fn_table *f, int32_t batch, const float *a, int64_t lda, const float *b,

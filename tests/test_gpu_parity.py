@@ -935,6 +935,29 @@ def test_wide_operand_rows_staged_in_lds(dol, batch):
     np.testing.assert_array_equal(out2.sym_ids, syms2)
     assert_close(host(out2.prob), want2, "wide binary forward")
     np.testing.assert_array_equal(host(out2.prob) == 1.0, pre2 >= 1.0)
+    # ---- binary with a short second operand: the per-j map kernels with the long row (forward) and the gated
+    # gradient row (backward) in LDS; columns where some j occurs twice go through their tuple lists
+    nb3 = 7
+    table3 = _rand_table(6120, (na, nb3), 2500, drop_every=7)
+    b3 = (W.softmax_rows(W.normal(6122, batch * nb3).reshape(batch, nb3)) * 1.1).astype(np.float32)
+    tri3 = oracle.dense_to_triples(table3)
+    syms3, want3, pre3, _ = oracle.damp_apply2_fwd(tri3, na, nb3, a, b3, want_pre=True)
+    assert (pre3 > 1).any() and (pre3 < 1).any()
+    f3 = dol.FnTable.create_dense(table3)
+    assert (f3.kernel_fwd, f3.kernel_bwd) == ("damp_byj_fwd_staged_kernel", "damp_byj_bwd_row_kernel")
+    db3 = dol.Dist(np.arange(nb3), dev(b3))
+    out3 = dol.Dist.empty(f3.out_syms, batch)
+    dol.apply2(da, db3, f3, None, out3)
+    assert_close(host(out3.prob), want3, "wide per-j forward")
+    np.testing.assert_array_equal(host(out3.prob) == 1.0, pre3 >= 1.0)
+    g3 = np.abs(W.normal(6123, batch * syms3.size).astype(np.float32).reshape(batch, -1)) + np.float32(0.5)
+    wa3, wb3 = oracle.damp_apply2_bwd(tri3, na, nb3, a, b3, g3)
+    ga3 = torch.full((batch, na + 1), 5.0, device="cuda")
+    gb3 = torch.empty((batch, nb3), device="cuda")
+    dol.backward(dol.OpRecord(dol.OP_APPLY2, da, db3, out3, f=f3), dev(g3), ga3, gb3)
+    assert_close(host(ga3)[:, :na], wa3, "wide per-j grad a")
+    assert_close(host(gb3), wb3, "wide per-j grad b")
+    assert np.all(host(ga3)[:, na:] == 5.0)
 
 
 def test_apply_k_two_operands_equal_apply2_bit_for_bit(dol):
