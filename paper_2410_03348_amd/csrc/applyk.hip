@@ -36,6 +36,7 @@ struct dol_fnk_table {
     // unary functions (K = 1): the first eight symbols of every image again, 16 bytes per column (0xFFFF = none), and
     // the column of every symbol (-1: rejected)
     dol::DevArray<uint16_t> unary_head;
+    dol::DevArray<uint16_t> unary_head_ord;   // the same, entry r being that of column col_order[r]
     dol::DevArray<int32_t> unary_col;
     int device = 0;
 };
@@ -184,7 +185,7 @@ damp_apply1_fwd_staged_kernel(int32_t n_in, int32_t S, int32_t parts, const floa
     __syncthreads();
     for (int r = c0 + threadIdx.x; r < c1; r += kStageThreads) {
         const uint32_t c = order[r];                                       // lanes of a wavefront: columns of like length
-        const uint4 h = head[c];
+        const uint4 h = head[r];                                           // (the head table in that order: a coalesced load)
         const uint32_t w[4] = {h.x, h.y, h.z, h.w};
         float v[8];
 #pragma unroll
@@ -334,7 +335,7 @@ static void launch_fwd_k(const Rows &R, const KOperands &in, const dol_fnk_table
         }
         hipLaunchKernelGGL(damp_apply1_fwd_staged_kernel, dim3(static_cast<unsigned>(R.batch) * parts), dim3(kStageThreads),
                            sizeof(float) * f->n_sym[0], st, f->n_sym[0], f->n_out, parts, in.p[0], in.ld[0], f->col_order.ptr,
-                           f->col_ptr.ptr, f->tup.ptr, reinterpret_cast<const uint4 *>(f->unary_head.ptr), out, ldo);
+                           f->col_ptr.ptr, f->tup.ptr, reinterpret_cast<const uint4 *>(f->unary_head_ord.ptr), out, ldo);
     } else if (K == 1)
         hipLaunchKernelGGL(damp_apply1_fwd_kernel, dim3(R.grid), dim3(kThreads), 0, st, R, in.p[0], in.ld[0], f->col_ptr.ptr,
                            f->tup.ptr, reinterpret_cast<const uint4 *>(f->unary_head.ptr), out, ldo);
@@ -602,6 +603,7 @@ static dol_status build_k(int32_t K, const int32_t *n_sym, int64_t n, const int3
     tb->n_wave_dtkp_cols = static_cast<int32_t>(dtkp_long_cols.size());
     dtkp_long_cols.insert(dtkp_long_cols.end(), dtkp_mid_cols.begin(), dtkp_mid_cols.end());
 
+    const std::vector<uint32_t> col_order = columns_by_length(col_ptr, S, kLongDtkpCol);
     if (K == 1) {
         std::vector<uint16_t> head(static_cast<size_t>(S) * 8, 0xFFFFu);
         std::vector<int32_t> col_of(static_cast<size_t>(n_sym[0]), -1);
@@ -612,11 +614,15 @@ static dol_status build_k(int32_t K, const int32_t *n_sym, int64_t n, const int3
             }
         DOL_HIP(tb->unary_head.upload(head));
         DOL_HIP(tb->unary_col.upload(col_of));
+        std::vector<uint16_t> ord(head.size());
+        for (int32_t r = 0; r < S; ++r)
+            for (int u = 0; u < 8; ++u) ord[static_cast<size_t>(r) * 8 + u] = head[static_cast<size_t>(col_order[r]) * 8 + u];
+        DOL_HIP(tb->unary_head_ord.upload(ord));
     }
     DOL_HIP(hipGetDevice(&tb->device));
     DOL_HIP(tb->long_cols.upload(long_cols));
     DOL_HIP(tb->dtkp_long_cols.upload(dtkp_long_cols));
-    DOL_HIP(tb->col_order.upload(columns_by_length(col_ptr, S, kLongDtkpCol)));
+    DOL_HIP(tb->col_order.upload(col_order));
     DOL_HIP(tb->col_ptr.upload(col_ptr));
     DOL_HIP(tb->tup.upload(tup));
     DOL_HIP(tb->tup_col.upload(tup_col));

@@ -104,7 +104,7 @@ damp_apply2_fwd_staged_kernel(int32_t na, int32_t nb, int32_t S, int32_t parts, 
     __syncthreads();
     for (int r = c0 + threadIdx.x; r < c1; r += kStageThreads) {
         const uint32_t c = order[r];                                       // lanes of a wavefront: columns of like length
-        const uint4 h = col_head[c];
+        const uint4 h = col_head[r];                                       // (the head table in that order: a coalesced load)
         const uint32_t t[4] = {h.x, h.y, h.z, h.w};
         float x[4], y[4];
 #pragma unroll
@@ -351,7 +351,7 @@ dol_status launch_damp_apply2_fwd(const dol_fn_table *f, int32_t batch, const fl
         }
         hipLaunchKernelGGL(damp_apply2_fwd_staged_kernel, dim3(static_cast<unsigned>(batch) * parts), dim3(kStageThreads),
                            sizeof(float) * (((f->na + 3) & ~3) + f->nb), st, f->na, f->nb, f->n_out, parts, f->col_order.ptr,
-                           f->col_ptr.ptr, f->col_ij.ptr, reinterpret_cast<const uint4 *>(f->col_head.ptr), a, lda, b, ldb, out, ldo);
+                           f->col_ptr.ptr, f->col_ij.ptr, reinterpret_cast<const uint4 *>(f->col_head_ord.ptr), a, lda, b, ldb, out, ldo);
     } else {
         hipLaunchKernelGGL(damp_apply2_fwd_kernel, dim3(R.grid), dim3(kThreads), 0, st, R, f->col_ptr.ptr, f->col_ij.ptr,
                            reinterpret_cast<const uint4 *>(f->col_head.ptr), a, lda, b, ldb, out, ldo);

@@ -94,6 +94,7 @@ struct dol_fn_table {
     // the first four tuples of every column again, 16 bytes per column (0xFFFFFFFF = no tuple): the forward kernel
     // for irregular tables gets a short column with one load
     dol::DevArray<uint32_t> col_head;
+    dol::DevArray<uint32_t> col_head_ord;   // the same, entry r being that of column col_order[r] (read coalesced there)
     // backward w.r.t. a: row i owns rowa_ptr[i] .. rowa_ptr[i+1] of rowa_jc = pack16(j, column), ascending j
     dol::DevArray<uint32_t> rowa_ptr, rowa_jc;
     // backward w.r.t. b: row j owns rowb_ptr[j] .. rowb_ptr[j+1] of rowb_ic = pack16(i, column), ascending i

@@ -142,13 +142,20 @@ static dol_status build_table(int32_t na, int32_t nb, std::vector<Tuple> &tup, d
     if (hipGetDevice(&tb->device) != hipSuccess) tb->device = 0;
     hipError_t e;
     if ((e = tb->long_rows.upload(long_rows)) != hipSuccess) return hip_fail(e, "uploading the function table");
+    const std::vector<uint32_t> col_order = columns_by_length(col_ptr, S, kLongDtkpCol);
     if ((e = tb->long_cols.upload(long_cols)) != hipSuccess || (e = tb->dtkp_long_cols.upload(dtkp_long_cols)) != hipSuccess ||
-        (e = tb->col_order.upload(columns_by_length(col_ptr, S, kLongDtkpCol))) != hipSuccess)
+        (e = tb->col_order.upload(col_order)) != hipSuccess)
         return hip_fail(e, "uploading the function table");
     std::vector<uint32_t> col_head(static_cast<size_t>(S) * 4, 0xFFFFFFFFu);
     for (int32_t c = 0; c < S; ++c)
         for (uint32_t q = col_ptr[c], u = 0; q < col_ptr[c + 1] && u < 4; ++q, ++u) col_head[static_cast<size_t>(c) * 4 + u] = col_ij[q];
     if ((e = tb->col_head.upload(col_head)) != hipSuccess) return hip_fail(e, "uploading the function table");
+    {
+        std::vector<uint32_t> ord(col_head.size());
+        for (int32_t r = 0; r < S; ++r)
+            for (int u = 0; u < 4; ++u) ord[static_cast<size_t>(r) * 4 + u] = col_head[static_cast<size_t>(col_order[r]) * 4 + u];
+        if ((e = tb->col_head_ord.upload(ord)) != hipSuccess) return hip_fail(e, "uploading the function table");
+    }
     if ((e = tb->col_ptr.upload(col_ptr)) != hipSuccess || (e = tb->col_ij.upload(col_ij)) != hipSuccess ||
         (e = tb->rowa_ptr.upload(rowa_ptr)) != hipSuccess || (e = tb->rowa_jc.upload(rowa_jc)) != hipSuccess ||
         (e = tb->rowb_ptr.upload(rowb_ptr)) != hipSuccess || (e = tb->rowb_ic.upload(rowb_ic)) != hipSuccess)
