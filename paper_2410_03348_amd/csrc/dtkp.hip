@@ -106,7 +106,7 @@ __device__ __forceinline__ void offer_tuple(TopK<K> &top, uint32_t ij, int64_t a
 template <int K>
 __global__ void __launch_bounds__(kThreadsT)
 dtkp_apply2_kernel(int64_t total, int32_t S, int32_t na, int32_t nb, int32_t n_facts, const uint32_t *__restrict__ order,
-                   const uint32_t *__restrict__ col_ptr, const uint32_t *__restrict__ col_ij, GroupMasks gm,
+                   const uint32_t *__restrict__ ord_len, const uint32_t *__restrict__ ord_tuples, GroupMasks gm,
                    const float *__restrict__ fact_prob, const uint64_t *__restrict__ am,
                    const float *__restrict__ ap, const uint64_t *__restrict__ bm, const float *__restrict__ bp,
                    const int32_t *__restrict__ fact_b, uint64_t *__restrict__ om, float *__restrict__ op,
@@ -116,14 +116,16 @@ dtkp_apply2_kernel(int64_t total, int32_t S, int32_t na, int32_t nb, int32_t n_f
     const int64_t idx = static_cast<int64_t>(xcd_contiguous(blockIdx.x, gridDim.x)) * kThreadsT + threadIdx.x;
     if (idx >= total) return;
     const int64_t s = idx / S;
-    const int32_t c = static_cast<int32_t>(order[idx - s * S]);          // lanes of a wavefront: columns of like length
+    const int64_t r = idx - s * S;
+    const uint32_t len = ord_len[r];                                     // lanes of a wavefront: columns of like length,
+    if (len == 0) return;                                                // the long ones left to the wavefront-per-column kernels
+    const int32_t c = static_cast<int32_t>(order[r]);
     const float *fp = fact_prob + s * n_facts;
     const int64_t a0 = s * na * K, b0 = s * nb * K;
-    const uint32_t q0 = col_ptr[c], q1 = col_ptr[c + 1];
-    if (q1 - q0 > static_cast<uint32_t>(kLongDtkpCol)) return;           // left to the wavefront-per-column kernel
     TopK<K> top;
     top.clear();
-    for (uint32_t q = q0; q < q1; ++q) offer_tuple<K>(top, col_ij[q], a0, b0, gm, fp, am, ap, bm, bp, fact_b);
+    for (uint32_t k = 0; k < len; ++k)                                   // (the lists interleaved in that order: coalesced loads)
+        offer_tuple<K>(top, ord_tuples[static_cast<size_t>(k) * S + r], a0, b0, gm, fp, am, ap, bm, bp, fact_b);
     const int64_t o = s * S + c;
     oprob[s * ldo + c] = top.store(om + o * K, op + o * K);
 }
@@ -210,7 +212,7 @@ static void launch_apply2_k(int64_t total, const dol_fn_table *f, int32_t n_fact
                             hipStream_t st)
 {
     hipLaunchKernelGGL(dtkp_apply2_kernel<K>, dim3(grid_t(total)), dim3(kThreadsT), 0, st, total, f->n_out, f->na,
-                       f->nb, n_facts, f->col_order.ptr, f->col_ptr.ptr, f->col_ij.ptr, gm, fact_prob, am, ap, bm, bp,
+                       f->nb, n_facts, f->col_order.ptr, f->ord_len.ptr, f->ord_tuples.ptr, gm, fact_prob, am, ap, bm, bp,
                        fact_b, om, op, oprob, ldo);
     const int64_t n_long = static_cast<int64_t>(f->dtkp_long_cols.n);
     const int64_t n_huge = f->n_huge_dtkp_cols, batch = total / f->n_out;

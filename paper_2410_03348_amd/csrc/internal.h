@@ -106,6 +106,10 @@ struct dol_fn_table {
     // all columns in the order the thread-per-column kernels over long operand rows take them
     // (dol::columns_by_length, with the DTKP kernel's limit on the length of a column)
     dol::DevArray<uint32_t> col_order;
+    // the tuple lists of the columns of at most dol::kLongDtkpCol tuples, interleaved in that order: tuple k of column
+    // col_order[r] is ord_tuples[k * n_out + r] and its list has ord_len[r] entries (0: a longer column), so that lanes on
+    // neighbouring r read neighbouring words
+    dol::DevArray<uint32_t> ord_tuples, ord_len;
     // each list starts with its huge columns (more than dol::kHugeTableCol / dol::kHugeDtkpCol tuples)
     int32_t n_huge_cols = 0, n_huge_dtkp_cols = 0, n_huge_byj_cols = 0;
     int32_t n_wave_dtkp_cols = 0;        // dtkp_long_cols: huge, then this many one-wavefront columns, then the shorter ones

@@ -151,6 +151,19 @@ static dol_status build_table(int32_t na, int32_t nb, std::vector<Tuple> &tup, d
         for (uint32_t q = col_ptr[c], u = 0; q < col_ptr[c + 1] && u < 4; ++q, ++u) col_head[static_cast<size_t>(c) * 4 + u] = col_ij[q];
     if ((e = tb->col_head.upload(col_head)) != hipSuccess) return hip_fail(e, "uploading the function table");
     {
+        uint32_t longest = 0;
+        std::vector<uint32_t> ord_len(static_cast<size_t>(S), 0);
+        for (int32_t r = 0; r < S; ++r) {
+            const uint32_t len = col_ptr[col_order[r] + 1] - col_ptr[col_order[r]];
+            if (len <= static_cast<uint32_t>(kLongDtkpCol)) { ord_len[r] = len; longest = std::max(longest, len); }
+        }
+        std::vector<uint32_t> ord_tuples(static_cast<size_t>(longest) * S, 0);
+        for (int32_t r = 0; r < S; ++r)
+            for (uint32_t k = 0; k < ord_len[r]; ++k) ord_tuples[static_cast<size_t>(k) * S + r] = col_ij[col_ptr[col_order[r]] + k];
+        if ((e = tb->ord_len.upload(ord_len)) != hipSuccess || (e = tb->ord_tuples.upload(ord_tuples)) != hipSuccess)
+            return hip_fail(e, "uploading the function table");
+    }
+    {
         std::vector<uint32_t> ord(col_head.size());
         for (int32_t r = 0; r < S; ++r)
             for (int u = 0; u < 4; ++u) ord[static_cast<size_t>(r) * 4 + u] = col_head[static_cast<size_t>(col_order[r]) * 4 + u];
