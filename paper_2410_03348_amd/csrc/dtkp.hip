@@ -339,11 +339,15 @@ dol_status launch_dtkp_filter(const FilterPlan *p, int32_t batch, int32_t k, con
 
 // Pr(symbol) = min(1, sum over its kept proofs of the product of their facts' probabilities) (Sec. 3.2); which
 // proofs top-k kept is a constant of the differentiation and the clamp passes gradient inside and on its bound
-// (App. A.2).  One workgroup per sample; its wavefronts take 64 symbols at a time.  A lane first loads one symbol's
-// proof list (coalesced) and folds the clamp's gate and the upstream gradient into one coefficient per proof; then
-// the 64 lanes turn into the 64 facts: every proof of the 64 symbols is broadcast in turn, its mask selecting the
-// lanes that add coefficient / (own fact's probability), the product of the proof's other facts, to a register.
-// No atomics; the sum over symbols runs in ascending order within a wavefront's share, then over the wavefronts.
+// (App. A.2).  One workgroup per sample; its wavefronts take 64 symbols at a time, a lane per symbol (coalesced loads
+// of the proof lists).  A lane folds the clamp's gate and the upstream gradient into one coefficient per proof,
+// gradient * proof probability, and adds it to a register accumulator of every fact the proof holds (the loop over
+// the facts is unrolled, so the accumulators are plain registers and a fact's test is a bit-field extract).  The
+// product of a proof's other facts is its probability divided by the fact's: that division happens once, on the
+// accumulator's total (one rounding more than multiplying the facts out, far inside the 1e-5 bar).  A fact of
+// probability (nearly) 0 cannot be divided by: its accumulator takes gradient * (the other facts multiplied out, in
+// ascending order) instead.  No atomics; the sums run over a lane's symbols in ascending order, then over the lanes
+// (exchange tree), then over the wavefronts in order.
 constexpr int kGradWaves = 16;
 
 template <int K>
@@ -353,16 +357,17 @@ dtkp_prob_bwd_kernel(int32_t n_sym, int32_t n_facts, const uint64_t *__restrict_
                      const float *__restrict__ g, int64_t ldg, float *__restrict__ gfact)
 {
     __shared__ float part[kGradWaves][64];
+    __shared__ float fp[64];
     const int64_t s = blockIdx.x;
     const int lane = threadIdx.x & 63, n_waves = blockDim.x >> 6;
     const int wave = __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6));   // tells the compiler it is uniform
-    const float pj = lane < n_facts ? fact_prob[s * n_facts + lane] : 1.0f;
-    // a proof's other facts: its stored probability divided by this fact's (one rounding more than multiplying
-    // them out; the 1 ulp reciprocal is far inside the 1e-5 bar); multiplied out, in ascending order, for every
-    // group of 64 symbols one of whose proofs holds a fact of probability (nearly) 0
+    if (wave == 0) fp[lane] = lane < n_facts ? fact_prob[s * n_facts + lane] : 1.0f;
+    __syncthreads();
+    const float pj = fp[lane];
     const uint64_t tiny = __ballot(!(pj > 1e-30f));
-    const float inv = pj > 1e-30f ? __builtin_amdgcn_rcpf(pj) : 0.0f;
-    float acc = 0.0f;
+    float acc[64], mine_tiny = 0.0f;
+#pragma unroll
+    for (int j = 0; j < 64; ++j) acc[j] = 0.0f;
     for (int32_t i0 = wave * 64; i0 < n_sym; i0 += n_waves * 64) {
         const int32_t i = i0 + lane;
         uint64_t mm[K];                     // 0: absent, gated by the clamp, or past the last symbol
@@ -388,43 +393,48 @@ dtkp_prob_bwd_kernel(int32_t n_sym, int32_t n_facts, const uint64_t *__restrict_
                     if (lm[x] != kAbsent) { mm[x] = lm[x]; cf[x] = gi * pv[x]; }
             }
         }
-        const int cnt = min(64, n_sym - i0);
-        auto proof_mask_of = [&](int x, int l) {
-            const uint32_t lo = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(static_cast<uint32_t>(mm[x])), l));
-            const uint32_t hi = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(static_cast<uint32_t>(mm[x] >> 32)), l));
-            return (static_cast<uint64_t>(hi) << 32) | lo;
-        };
-        uint64_t all = 0;
 #pragma unroll
-        for (int x = 0; x < K; ++x) all |= mm[x];
-        if (!__any((all & tiny) != 0)) {    // the usual case: no proof of these symbols holds a (nearly) impossible fact
-            for (int l = 0; l < cnt; ++l) {
+        for (int j0 = 0; j0 < 64; j0 += 8) {
+            if (j0 >= n_facts) continue;    // (uniform; facts past n_facts are in no proof)
+#pragma unroll
+            for (int j = j0; j < j0 + 8; ++j) {
 #pragma unroll
                 for (int x = 0; x < K; ++x) {
-                    const bool has = __builtin_amdgcn_inverse_ballot_w64(proof_mask_of(x, l));   // lane j: fact j is in the proof
-                    const float c = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, cf[x]), l));
-                    acc = has ? __builtin_fmaf(c, inv, acc) : acc;
-                }
-            }
-        } else {
-            for (int l = 0; l < cnt; ++l) {
-                const float gl = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, gate_g), l));
-#pragma unroll
-                for (int x = 0; x < K; ++x) {
-                    const uint64_t um = proof_mask_of(x, l);
-                    const bool has = __builtin_amdgcn_inverse_ballot_w64(um);
-                    float others = 1.0f;
-                    for (uint64_t r = um; r; r &= r - 1) {
-                        const int q = __builtin_ctzll(r);
-                        const float fq = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, pj), q));
-                        others = others * (q == lane ? 1.0f : fq);
-                    }
-                    acc = has ? __builtin_fmaf(gl, others, acc) : acc;
+                    const int word = static_cast<int>(static_cast<uint32_t>(j < 32 ? mm[x] : mm[x] >> 32));
+                    const int held = __builtin_amdgcn_sbfe(word, j & 31, 1);                    // all ones: the proof holds fact j
+                    acc[j] = acc[j] + __builtin_bit_cast(float, held & __builtin_bit_cast(int, cf[x]));
                 }
             }
         }
+        for (uint64_t tm = tiny; tm; tm &= tm - 1) {                     // (uniform) facts that cannot be divided by
+            const int j = __builtin_ctzll(tm);
+            float t = 0.0f;
+#pragma unroll
+            for (int x = 0; x < K; ++x) {
+                if (!((mm[x] >> j) & 1)) continue;
+                float others = 1.0f;
+                for (uint64_t r = mm[x] & ~(uint64_t(1) << j); r; r &= r - 1) others = others * fp[__builtin_ctzll(r)];
+                t = __builtin_fmaf(gate_g, others, t);
+            }
+#pragma unroll
+            for (int d = 32; d >= 1; d >>= 1) t += __shfl_xor(t, d, 64);
+            if (lane == j) mine_tiny = mine_tiny + t;
+        }
     }
-    part[wave][lane] = acc;
+    float mine = 0.0f;                      // lane j ends with this wavefront's total of fact j
+#pragma unroll
+    for (int j0 = 0; j0 < 64; j0 += 8) {
+        if (j0 >= n_facts) continue;
+#pragma unroll
+        for (int j = j0; j < j0 + 8; ++j) {
+            float v = acc[j];
+#pragma unroll
+            for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);
+            if (lane == j) mine = v;
+        }
+    }
+    mine = pj > 1e-30f ? mine * __builtin_amdgcn_rcpf(pj) : mine_tiny;
+    part[wave][lane] = mine;
     __syncthreads();
     if (wave == 0 && lane < n_facts) {
         float tot = 0.0f;
