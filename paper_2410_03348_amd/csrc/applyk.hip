@@ -183,33 +183,44 @@ damp_apply1_fwd_staged_kernel(int32_t n_in, int32_t S, int32_t parts, const floa
     stage_part(S, parts, static_cast<int>(blockIdx.x - s * parts), c0, c1);
     stage_row(xr, x + s * ldx, n_in);
     __syncthreads();
-    for (int r = c0 + threadIdx.x; r < c1; r += kStageThreads) {
-        const uint32_t c = order[r];                                       // lanes of a wavefront: columns of like length
-        const uint4 h = head[r];                                           // (the head table in that order: a coalesced load)
-        const uint32_t w[4] = {h.x, h.y, h.z, h.w};
-        float v[8];
+    // kStageUnroll columns per thread and pass, so that their index and head loads are in flight together
+    for (int r0 = c0 + threadIdx.x; r0 < c1; r0 += kStageUnroll * kStageThreads) {
+        uint32_t c[kStageUnroll];
+        uint4 h[kStageUnroll];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {                                      // all eight reads at once (slot 0 for "none")
-            const uint32_t pos = (w[u / 2] >> (16 * (u & 1))) & 0xffffu;
-            v[u] = xr[pos != 0xffffu ? pos : 0u];
+        for (int v = 0; v < kStageUnroll; ++v) {
+            const int r = min(r0 + v * kStageThreads, c1 - 1);
+            c[v] = order[r];                                               // lanes of a wavefront: columns of like length
+            h[v] = head[r];                                                // (the head table in that order: a coalesced load)
         }
-        float acc = 0.0f;
 #pragma unroll
-        for (int u = 0; u < 8; ++u)
-            if (((w[u / 2] >> (16 * (u & 1))) & 0xffffu) != 0xffffu) acc = acc + v[u];
-        if ((w[3] >> 16) != 0xffffu) {                                     // eight or more symbols: the rest of the list
-            const uint32_t q0 = col_ptr[c], q1 = col_ptr[c + 1];
-            if (q1 - q0 > static_cast<uint32_t>(kLongTableCol)) continue;  // left to the wavefront-per-column kernel
-            for (uint32_t q = q0 + 8; q < q1; q += kGatherK) {
-                uint32_t pos[kGatherK];
+        for (int v = 0; v < kStageUnroll; ++v) {
+            if (r0 + v * kStageThreads >= c1) continue;
+            const uint32_t w[4] = {h[v].x, h[v].y, h[v].z, h[v].w};
+            float val[8];
 #pragma unroll
-                for (int u = 0; u < kGatherK; ++u) pos[u] = tup[min(q + u, q1 - 1)];
-#pragma unroll
-                for (int u = 0; u < kGatherK; ++u)
-                    if (q + u < q1) acc = acc + xr[pos[u]];
+            for (int u = 0; u < 8; ++u) {                                  // all eight reads at once (slot 0 for "none")
+                const uint32_t pos = (w[u / 2] >> (16 * (u & 1))) & 0xffffu;
+                val[u] = xr[pos != 0xffffu ? pos : 0u];
             }
+            float acc = 0.0f;
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (((w[u / 2] >> (16 * (u & 1))) & 0xffffu) != 0xffffu) acc = acc + val[u];
+            if ((w[3] >> 16) != 0xffffu) {                                 // eight or more symbols: the rest of the list
+                const uint32_t q0 = col_ptr[c[v]], q1 = col_ptr[c[v] + 1];
+                if (q1 - q0 > static_cast<uint32_t>(kLongTableCol)) continue;   // left to the wavefront-per-column kernel
+                for (uint32_t q = q0 + 8; q < q1; q += kGatherK) {
+                    uint32_t pos[kGatherK];
+#pragma unroll
+                    for (int u = 0; u < kGatherK; ++u) pos[u] = tup[min(q + u, q1 - 1)];
+#pragma unroll
+                    for (int u = 0; u < kGatherK; ++u)
+                        if (q + u < q1) acc = acc + xr[pos[u]];
+                }
+            }
+            out[s * ldo + c[v]] = fminf(acc, 1.0f);
         }
-        out[s * ldo + c] = fminf(acc, 1.0f);
     }
 }
 

@@ -102,34 +102,45 @@ damp_apply2_fwd_staged_kernel(int32_t na, int32_t nb, int32_t S, int32_t parts, 
     stage_row(ar, a + s * lda, na);
     stage_row(br, b + s * ldb, nb);
     __syncthreads();
-    for (int r = c0 + threadIdx.x; r < c1; r += kStageThreads) {
-        const uint32_t c = order[r];                                       // lanes of a wavefront: columns of like length
-        const uint4 h = col_head[r];                                       // (the head table in that order: a coalesced load)
-        const uint32_t t[4] = {h.x, h.y, h.z, h.w};
-        float x[4], y[4];
+    // kStageUnroll columns per thread and pass, so that their index and head loads are in flight together
+    for (int r0 = c0 + threadIdx.x; r0 < c1; r0 += kStageUnroll * kStageThreads) {
+        uint32_t c[kStageUnroll];
+        uint4 h[kStageUnroll];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {                                      // all eight reads at once (tuple (0, 0) for "none")
-            const uint32_t ij = t[u] != 0xFFFFFFFFu ? t[u] : 0u;
-            x[u] = ar[ij & 0xffffu];
-            y[u] = br[ij >> 16];
+        for (int v = 0; v < kStageUnroll; ++v) {
+            const int r = min(r0 + v * kStageThreads, c1 - 1);
+            c[v] = order[r];                                               // lanes of a wavefront: columns of like length
+            h[v] = col_head[r];                                            // (the head table in that order: a coalesced load)
         }
-        float acc = 0.0f;
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
-            if (t[u] != 0xFFFFFFFFu) acc = __builtin_fmaf(x[u], y[u], acc);
-        if (t[3] != 0xFFFFFFFFu) {                                         // four or more tuples: the rest of the list
-            const uint32_t q0 = col_ptr[c], q1 = col_ptr[c + 1];
-            if (q1 - q0 > static_cast<uint32_t>(kLongTableCol)) continue;  // left to the wavefront-per-column kernel
-            for (uint32_t q = q0 + 4; q < q1; q += kGather) {
-                uint32_t ij[kGather];
+        for (int v = 0; v < kStageUnroll; ++v) {
+            if (r0 + v * kStageThreads >= c1) continue;
+            const uint32_t t[4] = {h[v].x, h[v].y, h[v].z, h[v].w};
+            float x[4], y[4];
 #pragma unroll
-                for (int u = 0; u < kGather; ++u) ij[u] = col_ij[min(q + u, q1 - 1)];
-#pragma unroll
-                for (int u = 0; u < kGather; ++u)
-                    if (q + u < q1) acc = __builtin_fmaf(ar[ij[u] & 0xffffu], br[ij[u] >> 16], acc);
+            for (int u = 0; u < 4; ++u) {                                  // all eight reads at once (tuple (0, 0) for "none")
+                const uint32_t ij = t[u] != 0xFFFFFFFFu ? t[u] : 0u;
+                x[u] = ar[ij & 0xffffu];
+                y[u] = br[ij >> 16];
             }
+            float acc = 0.0f;
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (t[u] != 0xFFFFFFFFu) acc = __builtin_fmaf(x[u], y[u], acc);
+            if (t[3] != 0xFFFFFFFFu) {                                     // four or more tuples: the rest of the list
+                const uint32_t q0 = col_ptr[c[v]], q1 = col_ptr[c[v] + 1];
+                if (q1 - q0 > static_cast<uint32_t>(kLongTableCol)) continue;   // left to the wavefront-per-column kernel
+                for (uint32_t q = q0 + 4; q < q1; q += kGather) {
+                    uint32_t ij[kGather];
+#pragma unroll
+                    for (int u = 0; u < kGather; ++u) ij[u] = col_ij[min(q + u, q1 - 1)];
+#pragma unroll
+                    for (int u = 0; u < kGather; ++u)
+                        if (q + u < q1) acc = __builtin_fmaf(ar[ij[u] & 0xffffu], br[ij[u] >> 16], acc);
+                }
+            }
+            out[s * ldo + c[v]] = fminf(acc, 1.0f);
         }
-        out[s * ldo + c] = fminf(acc, 1.0f);
     }
 }
 

@@ -61,6 +61,7 @@ __device__ __forceinline__ void for_each_element(const Rows &R, F f)
 // coalesced loads and then gathers there.  Small batches are cut into several parts per sample (each stages the row
 // again) so that the chip still fills.
 constexpr int kStageThreads = 1024;
+constexpr int kStageUnroll = 4;                       // outputs a thread works on at a time (their loads in flight together)
 
 static inline bool stage_fits(int64_t row_floats) { return row_floats >= kStageMinRow && row_floats * 4 <= static_cast<int64_t>(kStageMaxBytes); }
 
