@@ -855,6 +855,12 @@ def test_apply_k_damp_forward_and_backward(dol, shape, n_ids, scale, batch):
     syms, want, pre32, _ = oracle.damp_applyk_fwd(idx, to, ins, want_pre=True)
     f = dol.FnkTable.create_dense(table)
     np.testing.assert_array_equal(f.out_syms, syms)
+    if K == 1:      # rows of fewer than 2 048 tags stay with the cached gathers
+        want_names = ("damp_apply1_fwd_kernel", "damp_apply1_bwd_kernel") if shape[0] < 2048 else \
+                     ("damp_apply1_fwd_staged_kernel", "damp_apply1_bwd_staged_kernel")
+    else:
+        want_names = ("damp_applyk_fwd_kernel<%d>" % K, "damp_applyk_bwd_kernel<%d>" % K)
+    assert (f.kernel_fwd, f.kernel_bwd) == want_names
     lds = [n + (3 if l % 2 else 0) for l, n in enumerate(shape)]       # some operands with padded rows
     d_in = []
     for x, n, ld in zip(ins, shape, lds):
