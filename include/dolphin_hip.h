@@ -291,17 +291,36 @@ dol_status dol_dtkp_fold_apply2(const dol_dtkp_fold *fold, const dol_prov *prov,
  * all rounds in ONE launch, one workgroup per sample with r_t in LDS.  The table must be square: it produces
  * exactly the symbols of its first operand (n_out == na and out_syms == r0->sym_ids), so that a round's result
  * can be the next round's first operand.  Results equal `rounds` dol_apply2 calls (same order, same clamps).
+ * The reverse sweep needs the rounds in between; the caller chooses what it keeps of them:
+ *
+ * Full history (rounds + 1 tensors through HBM):
  *   hist  device [rounds+1, batch, na], contiguous: receives r_0 .. r_rounds; r_rounds is the result and the
  *         whole history is what dol_iterate_backward reads.
- * dol_iterate_backward: grad_out device [batch, grad_out_ld] w.r.t. r_rounds;
- *   grad_r0 device [batch, na] contiguous or NULL; grad_e device [batch, e->ld] or NULL: the gradient w.r.t. e
- *   summed over the rounds.  Both overwritten.
- * DOL_EUNSUPPORTED when the table is not square or the rows do not fit in LDS (na, nb up to a few thousand). */
+ *   dol_iterate_backward: grad_out device [batch, grad_out_ld] w.r.t. r_rounds;
+ *     grad_r0 device [batch, na] contiguous or NULL; grad_e device [batch, e->ld] or NULL: the gradient w.r.t. e
+ *     summed over the rounds.  Both overwritten.
+ *
+ * Checkpoints (only r_rounds and every ckpt_every-th round leave the chip; the reverse sweep replays each stretch
+ * of ckpt_every rounds forward in LDS before walking it backwards, same arithmetic, same results bit for bit):
+ *   dol_iterate_apply2_ckpt: out->prob receives r_rounds; ckpt, device [n_ckpt, batch, na] contiguous with
+ *     n_ckpt = dol_iterate_ckpt_count(rounds, ckpt_every) = ceil(rounds / ckpt_every) - 1, receives r_{ckpt_every},
+ *     r_{2 ckpt_every}, ... (those before r_rounds); may be NULL when n_ckpt == 0.
+ *   dol_iterate_backward_ckpt: r0, e, f, rounds, ckpt_every, ckpt as in the forward call; gradients as above.
+ *
+ * The gradient w.r.t. e is summed in a fixed order (no atomics): two runs give the same bits.
+ * DOL_EUNSUPPORTED when the table is not square, an operand has more than 4096 symbols, or the rows (for the
+ * reverse sweep: ckpt_every + 3 rows of na tags, e, and one word per tuple) do not fit in 160 KB of LDS. */
 dol_status dol_iterate_apply2(const dol_dist *r0, const dol_dist *e, const dol_fn_table *f, int32_t rounds, float *hist,
                               void *hip_stream);
 dol_status dol_iterate_backward(const dol_dist *e, const dol_fn_table *f, int32_t rounds, const float *hist,
                                 const float *grad_out, int64_t grad_out_ld, float *grad_r0, float *grad_e,
                                 void *hip_stream);
+int32_t dol_iterate_ckpt_count(int32_t rounds, int32_t ckpt_every);
+dol_status dol_iterate_apply2_ckpt(const dol_dist *r0, const dol_dist *e, const dol_fn_table *f, int32_t rounds,
+                                   int32_t ckpt_every, dol_dist *out, float *ckpt, void *hip_stream);
+dol_status dol_iterate_backward_ckpt(const dol_dist *r0, const dol_dist *e, const dol_fn_table *f, int32_t rounds,
+                                     int32_t ckpt_every, const float *ckpt, const float *grad_out, int64_t grad_out_ld,
+                                     float *grad_r0, float *grad_e, void *hip_stream);
 
 /* Harness helper for loss = -log p[target] (Sec. 3.3 leaves the loss to the user): for every sample s,
  * grad[s, c] = -1 / max(d->prob[s, c], FLT_MIN) at c = target_col[s] and 0 elsewhere (all n_sym columns written).

@@ -479,6 +479,37 @@ def iterate_backward(e: Dist, f: FnTable, rounds: int, hist: torch.Tensor, grad_
                                      _stream(stream)))
 
 
+_lib.dol_iterate_ckpt_count.argtypes = [C.c_int32, C.c_int32]
+_lib.dol_iterate_ckpt_count.restype = C.c_int32
+_lib.dol_iterate_apply2_ckpt.argtypes = [C.POINTER(_Dist), C.POINTER(_Dist), C.c_void_p, C.c_int32, C.c_int32,
+                                         C.POINTER(_Dist), C.c_void_p, C.c_void_p]
+_lib.dol_iterate_backward_ckpt.argtypes = [C.POINTER(_Dist), C.POINTER(_Dist), C.c_void_p, C.c_int32, C.c_int32,
+                                           C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p]
+
+
+def iterate_ckpt_count(rounds: int, ckpt_every: int) -> int:
+    return int(_lib.dol_iterate_ckpt_count(rounds, ckpt_every))
+
+
+def iterate_apply2_ckpt(r0: Dist, e: Dist, f: FnTable, rounds: int, ckpt_every: int, out: Dist,
+                        ckpt: Optional[torch.Tensor], stream=None):
+    """ckpt: float32 [iterate_ckpt_count(rounds, ckpt_every), batch, na] contiguous (None when that count is 0)."""
+    n = iterate_ckpt_count(rounds, ckpt_every)
+    assert n == 0 or (ckpt.dtype == torch.float32 and ckpt.is_contiguous() and ckpt.shape == (n, r0.batch, f.na))
+    _check(_lib.dol_iterate_apply2_ckpt(r0.ref(), e.ref(), f._h, rounds, ckpt_every, out.ref(), _dptr(ckpt),
+                                        _stream(stream)))
+
+
+def iterate_backward_ckpt(r0: Dist, e: Dist, f: FnTable, rounds: int, ckpt_every: int, ckpt: Optional[torch.Tensor],
+                          grad_out: torch.Tensor, grad_r0: Optional[torch.Tensor], grad_e: Optional[torch.Tensor],
+                          stream=None):
+    assert grad_out.dtype == torch.float32 and grad_out.stride(1) == 1
+    assert grad_r0 is None or grad_r0.is_contiguous()
+    _check(_lib.dol_iterate_backward_ckpt(r0.ref(), e.ref(), f._h, rounds, ckpt_every, _dptr(ckpt), _dptr(grad_out),
+                                          max(int(grad_out.stride(0)), grad_out.shape[1]), _dptr(grad_r0), _dptr(grad_e),
+                                          _stream(stream)))
+
+
 def nll_grad(d: Dist, target_col: torch.Tensor, grad: torch.Tensor, stream=None):
     """target_col: int32 device tensor [batch]; grad rows have stride d.ld."""
     assert target_col.dtype == torch.int32 and target_col.is_contiguous()

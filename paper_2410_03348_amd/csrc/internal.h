@@ -99,6 +99,8 @@ struct dol_fn_table {
     dol::DevArray<uint32_t> rowa_ptr, rowa_jc;
     // backward w.r.t. b: row j owns rowb_ptr[j] .. rowb_ptr[j+1] of rowb_ic = pack16(i, column), ascending i
     dol::DevArray<uint32_t> rowb_ptr, rowb_ic;
+    // square tables (n_out == na) only: rowb_pos[q] = position in rowa_jc of the tuple at position q of rowb_ic
+    dol::DevArray<uint32_t> rowb_pos;
     // rows with more than dol::kLongTableRow tuples (x < na: row x of a, else row x - na of b)
     dol::DevArray<uint32_t> long_rows;
     // output columns with more than dol::kLongTableCol / dol::kLongDtkpCol tuples
@@ -240,6 +242,16 @@ dol_status launch_damp_union_fwd(const UnionPlan *p, int32_t batch, const float 
 dol_status launch_damp_union_bwd(const UnionPlan *p, int32_t batch, const float *a, int64_t lda, const float *b,
                                  int64_t ldb, const float *g, int64_t ldg, float *ga, float *gb, int32_t accumulate,
                                  hipStream_t st);
+
+// Repeated Apply with feedback (iterate.hip).  Forward: any of hist / ckpt / out may be nullptr.  Backward: reads either
+// the full history (hist) or r0 and the checkpoints written every `every` rounds.
+dol_status check_iterate(const dol_dist *e, const dol_fn_table *f, int32_t rounds);
+dol_status check_r0(const dol_dist *r0, const dol_dist *e, const dol_fn_table *f);
+dol_status launch_iterate_fwd(const dol_dist *r0, const dol_dist *e, const dol_fn_table *f, int32_t rounds,
+                              float *hist, float *ckpt, int32_t every, float *out, int64_t ldo, hipStream_t st);
+dol_status launch_iterate_bwd(const dol_dist *e, const dol_fn_table *f, int32_t rounds, const float *hist,
+                              const float *r0, int64_t ldr, const float *ckpt, int32_t every, const float *grad_out,
+                              int64_t ldg, float *grad_r0, float *grad_e, hipStream_t st);
 
 dol_status launch_dtkp_init(int32_t batch, int32_t n_sym, int32_t k, int32_t n_facts, const int32_t *d_fact_of_sym,
                             const float *fact_prob, uint64_t *mask, float *pprob, float *prob, int64_t ld,

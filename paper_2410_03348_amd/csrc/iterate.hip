@@ -1,106 +1,160 @@
 // Repeated DAMP Apply with feedback (the fixed-round form of the recursion of App. B, Fig. 9):
 //     r_{t+1}[c] = min(1, sum over the tuples (i, j) of column c of r_t[i] * e[j]),
-// every round in one launch.  One workgroup of 1024 threads owns a sample: r_t, r_{t+1} and the second
-// operand sit in LDS; the function table never changes between rounds, so every thread keeps the tuples of
-// its own columns (rows, for the reverse sweep) in registers and a round is one burst of LDS reads, a short
-// fma chain and a barrier.  Tuples beyond the first few of a column are read through the caches; rows with
-// more than 64 tuples are summed by the whole workgroup.  Summation order and clamp decisions are those of
-// dol_apply2 / dol_backward.
+// every round in one launch.  One workgroup owns a sample: r_t, r_{t+1} and the second operand sit in LDS; the
+// function table never changes between rounds, so every thread keeps the first tuples of its own columns (rows, for
+// the reverse sweep) in registers together with the tags of e they name, and a round is one burst of LDS reads,
+// a short fma chain and a barrier.  Tuples beyond the first few of a column are read through the caches.
+// Summation order and clamp decisions are those of dol_apply2 / dol_backward.
+//
+// What the reverse sweep needs of the rounds in between comes from one of two places: the full history r_0 ..
+// r_rounds that the forward launch wrote when asked to (dol_iterate_apply2), or checkpoints r_R, r_2R, ... written
+// every R rounds (dol_iterate_apply2_ckpt), from which the sweep replays a segment of R rounds forward in LDS before
+// walking it backwards.  Inside LDS a round's result is kept as x = pre where pre <= 1 and -1 where the clamp acted:
+// |x| is the clamped tag and the sign is the clamp's decision, so the reverse sweep never re-derives a sum.
+//
+// The gradient w.r.t. e has one share per tuple and round.  A share belongs to the thread that owns the tuple's row
+// and is summed over the rounds in a register (or in the tuple's own LDS word); at the end the shares of every symbol
+// of e are added in ascending order of the first operand's symbol by one thread (rows of more than 64 tuples: by one
+// wavefront, strided, then a fixed exchange tree).  No atomics: the result is the same bit for bit on every run.
 #include "internal.h"
 #include "wave_util.h"
 
+#include <mutex>
+
 namespace dol {
 
-constexpr int kItThreads = 1024;
-constexpr int kItWaves = kItThreads / kWave;
-constexpr int kItMaxK = 4;              // columns per thread: na, nb up to 2048
-constexpr int kItMaxRow = kItThreads * kItMaxK;
-constexpr int kItCacheA = 6;            // tuples of a column / of a row of the first operand kept in registers
+constexpr int kItMaxRow = 4096;         // most symbols of either operand
+constexpr size_t kItLdsMax = 160 * 1024;
 
-// The tuples [q0, q1) of one column or row: the first N in registers, the rest behind `list`.
+// The tuples [q0, q1) of one column or row: the first N in registers (with the tag of e each names), the rest
+// behind `list`.  Register slots past the end of a short list point at the zero entry kept behind the operand
+// row and carry the tag 0: their product is an exact +0 added after the real tuples, so no slot needs a branch.
 template <int N>
 struct Cached {
     uint32_t t[N];
+    float e[N];
     uint32_t q0, q1;
 };
 
-// Register slots past the end of a short list hold `dummy`, a tuple that points at the zero entries kept
-// behind both operand rows: its product is an exact +0 added after the real tuples, so no slot needs a branch.
-template <int N>
+// lo16 of a column tuple = symbol of r, hi16 = symbol of e; of a row tuple: lo16 = symbol of e, hi16 = column.
+template <int N, bool E_IN_LO>
 __device__ __forceinline__ void load_cached(Cached<N> &c, const uint32_t *__restrict__ ptr,
-                                            const uint32_t *__restrict__ list, int r, int n, uint32_t dummy)
+                                            const uint32_t *__restrict__ list, int r, int n, uint32_t dummy,
+                                            const float *__restrict__ e_row)
 {
     c.q0 = c.q1 = 0;
     if (r < n) { c.q0 = ptr[r]; c.q1 = ptr[r + 1]; }
 #pragma unroll
-    for (int x = 0; x < N; ++x) c.t[x] = c.q0 + x < c.q1 ? list[c.q0 + x] : dummy;
+    for (int x = 0; x < N; ++x) {
+        const bool on = c.q0 + x < c.q1;
+        c.t[x] = on ? list[c.q0 + x] : dummy;
+        c.e[x] = on ? e_row[E_IN_LO ? c.t[x] & 0xffffu : c.t[x] >> 16] : 0.0f;
+    }
 }
 
-// sum over the tuples of x[lo16] * y[hi16], in list order, one fma each, starting from 0
+// pre of one column: sum over its tuples of |x[i]| * e[j], in list order, one fma each, starting from 0
 template <int N>
-__device__ __forceinline__ float dot_lo_hi(const Cached<N> &c, const uint32_t *__restrict__ list, const float *x,
-                                           const float *y)
+__device__ __forceinline__ float col_pre(const Cached<N> &c, const uint32_t *__restrict__ list, const float *x,
+                                         const float *le)
 {
     float acc = 0.0f;
 #pragma unroll
-    for (int k = 0; k < N; ++k) acc = __builtin_fmaf(x[c.t[k] & 0xffffu], y[c.t[k] >> 16], acc);
+    for (int k = 0; k < N; ++k) acc = __builtin_fmaf(fabsf(x[c.t[k] & 0xffffu]), c.e[k], acc);
     for (uint32_t q = c.q0 + N; q < c.q1; ++q) {
         const uint32_t t = list[q];
-        acc = __builtin_fmaf(x[t & 0xffffu], y[t >> 16], acc);
+        acc = __builtin_fmaf(fabsf(x[t & 0xffffu]), le[t >> 16], acc);
     }
     return acc;
 }
 
+__device__ __forceinline__ float signed_tag(float pre) { return pre <= 1.0f ? pre : -1.0f; }
+
+struct ItFwdArgs {
+    int32_t batch, na, nb, rounds;
+    const uint32_t *col_ptr, *col_ij;
+    const float *r0;
+    int64_t ldr;
+    const float *e;
+    int64_t lde;
+    float *hist;                        // [rounds + 1, batch, na] or nullptr
+    float *ckpt;                        // [n_ckpt, batch, na] or nullptr: r_every, r_2*every, ... (those before r_rounds)
+    int32_t every;
+    float *out;                         // [batch, ldo] or nullptr: r_rounds
+    int64_t ldo;
+};
+
 // ---------------------------------------------------------------- forward
 
-template <int K>
-__global__ void __launch_bounds__(kItThreads)
-damp_iterate_fwd_kernel(int32_t batch, int32_t na, int32_t nb, int32_t rounds, const uint32_t *__restrict__ col_ptr,
-                        const uint32_t *__restrict__ col_ij, const float *__restrict__ r0, int64_t ldr,
-                        const float *__restrict__ e, int64_t lde, float *__restrict__ hist)
+template <int T, int K, int CA>
+__global__ void __launch_bounds__(T)
+damp_iterate_fwd_kernel(const ItFwdArgs A)
 {
-    extern __shared__ float lds[];          // r (two rows of na + 1), e (nb + 1): each row ends with a zero
-    float *r_cur = lds, *r_nxt = lds + na + 1;
+    extern __shared__ float lds[];          // x (two rows of na + 1), e (nb + 1): each row ends with a zero
+    const int na = A.na, nb = A.nb;
+    float *x_cur = lds, *x_nxt = lds + na + 1;
     float *le = lds + 2 * (na + 1);
     const int tid = threadIdx.x;
     const int64_t s = blockIdx.x;
-    const int64_t plane = static_cast<int64_t>(batch) * na;
-    float *hs = hist + s * na;
-    for (int c = tid; c < na; c += kItThreads) { const float v = r0[s * ldr + c]; r_cur[c] = v; hs[c] = v; }
-    for (int j = tid; j < nb; j += kItThreads) le[j] = e[s * lde + j];
-    if (tid == 0) { r_cur[na] = 0.0f; r_nxt[na] = 0.0f; le[nb] = 0.0f; }
-    Cached<kItCacheA> col[K];
+    const int64_t plane = static_cast<int64_t>(A.batch) * na;
+    const float *e_row = A.e + s * A.lde;
+    for (int c = tid; c < na; c += T) {
+        const float v = A.r0[s * A.ldr + c];
+        x_cur[c] = v;
+        if (A.hist) A.hist[s * na + c] = v;
+        if (A.rounds == 0 && A.out) A.out[s * A.ldo + c] = v;
+    }
+    for (int j = tid; j < nb; j += T) le[j] = e_row[j];
+    if (tid == 0) { x_cur[na] = 0.0f; x_nxt[na] = 0.0f; le[nb] = 0.0f; }
+    Cached<CA> col[K];
 #pragma unroll
-    for (int k = 0; k < K; ++k) load_cached(col[k], col_ptr, col_ij, tid + kItThreads * k, na, pack16(na, nb));
+    for (int k = 0; k < K; ++k) load_cached<CA, false>(col[k], A.col_ptr, A.col_ij, tid + T * k, na, pack16(na, nb), e_row);
     lds_barrier();
-    for (int t = 0; t < rounds; ++t) {
-        float *ht = hs + (t + 1) * plane;
+    int next_ckpt = A.every, n_ckpt = 0;
+    for (int t = 1; t <= A.rounds; ++t) {
+        const bool keep = A.ckpt && t == next_ckpt && t < A.rounds;
+        float *kp = keep ? A.ckpt + n_ckpt * plane + s * na : nullptr;
+        float *hp = A.hist ? A.hist + t * plane + s * na : nullptr;
+        float *op = t == A.rounds && A.out ? A.out + s * A.ldo : nullptr;
 #pragma unroll
         for (int k = 0; k < K; ++k) {
-            const int c = tid + kItThreads * k;
+            const int c = tid + T * k;
             if (c < na) {
-                const float v = fminf(dot_lo_hi(col[k], col_ij, r_cur, le), 1.0f);
-                r_nxt[c] = v;
-                ht[c] = v;
+                const float pre = col_pre(col[k], A.col_ij, x_cur, le);
+                x_nxt[c] = signed_tag(pre);
+                const float v = fminf(pre, 1.0f);
+                if (hp) hp[c] = v;
+                if (kp) kp[c] = v;
+                if (op) op[c] = v;
             }
         }
+        if (keep) { next_ckpt += A.every; ++n_ckpt; }
         lds_barrier();
-        float *sw = r_cur; r_cur = r_nxt; r_nxt = sw;
+        float *sw = x_cur; x_cur = x_nxt; x_nxt = sw;
     }
 }
 
 // ---------------------------------------------------------------- backward
 
-struct ItTable {
-    const uint32_t *col_ptr, *col_ij, *rowa_ptr, *rowa_jc, *rowb_ptr, *rowb_ic, *long_rows;
-    int32_t n_long;
+struct ItBwdArgs {
+    int32_t batch, na, nb, rounds, every;   // every: rounds per segment (the checkpoint interval)
+    int32_t n_tuples, n_long;
+    const uint32_t *col_ptr, *col_ij, *rowa_ptr, *rowa_jc, *rowb_ptr, *rowb_pos, *long_rows;
+    const float *e;
+    int64_t lde;
+    const float *hist;                      // full history, or nullptr: then r0 and ckpt
+    const float *r0;
+    int64_t ldr;
+    const float *ckpt;
+    const float *gout;
+    int64_t ldg;
+    float *grad_r0;                         // [batch, na] or nullptr
+    float *grad_e;                          // [batch, ldge] or nullptr
+    int64_t ldge;
 };
 
-constexpr int kItLongCache = 2;         // long rows whose tuples the threads keep in registers
-constexpr int kItAhead = 4;             // reverse sweep: rounds between requesting a row of the history and using it
-
-// Sum of x over the workgroup (every thread gets the total); `red` holds one float per wavefront and must not
-// be in use by an earlier call that other threads may still be reading.
+// Sum of x over the workgroup (every thread gets the total); `red` holds one float per wavefront.  Successive
+// calls must alternate between two such arrays: a wavefront may still be reading the last call's partial sums.
+template <int T>
 __device__ __forceinline__ float block_sum(float x, float *red)
 {
 #pragma unroll
@@ -109,241 +163,291 @@ __device__ __forceinline__ float block_sum(float x, float *red)
     lds_barrier();
     float tot = 0.0f;
 #pragma unroll
-    for (int w = 0; w < kItWaves; ++w) tot += red[w];
+    for (int w = 0; w < T / kWave; ++w) tot += red[w];
     return tot;
 }
 
-// Reverse sweep, one barrier per round.  At the start of round t (t = rounds - 1 .. 0) LDS holds gh = the gradient
-// reaching the unclamped sums of round t + 1, r_t and r_{t-1}.  A thread owns the same symbols i of the first
-// operand in every round.  For each tuple (i, j, c) of its rows it reads e[j] and gh[c] once: e[j] * gh[c] goes
-// into g[i] = d loss / d r_t[i], and r_t[i] * gh[c], the tuple's share of d loss / d e[j], into a register that
-// belongs to the tuple and runs over all rounds; the shares meet in LDS after the last round.  g[i] is gated
-// with the clamp decision of round t (re-derived from r_{t-1} only where r_t[i] sits on the clamp) and becomes
-// the next round's gh.  r_{t-2} arrives from HBM through a ring of registers requested kItAhead rounds earlier.
-template <int K>                        // symbols of the first operand per thread
-__global__ void __launch_bounds__(kItThreads)
-damp_iterate_bwd_kernel(int32_t batch, int32_t na, int32_t nb, int32_t rounds, ItTable T,
-                        const float *__restrict__ e, int64_t lde, const float *__restrict__ hist,
-                        const float *__restrict__ gout, int64_t ldg, float *__restrict__ grad_r0,
-                        float *__restrict__ grad_e, int64_t ldge)
+// Reverse sweep.  LDS: seg[0 .. every] = the rounds of the segment being walked (seg[x] = signed r_{t0 + x}), two
+// gradient rows, e, one word per tuple for its share of d loss / d e, partial sums.  A thread owns the same
+// symbols i of the first operand in every round.  For a round t of the segment, gA holds gh = the gradient
+// reaching the unclamped sums of round t; for each tuple (i, j, c) of its rows the thread reads gh[c] once:
+// e[j] * gh[c] goes into g[i] = d loss / d r_t[i], and r_t[i] * gh[c] into the tuple's share.  g[i] gated with the
+// sign of seg[x][i] (the decision of the round that produced r_t) is the next gh; the first row of a segment comes
+// from a checkpoint and carries no decision, so its gradient is handed over ungated and gated after the next
+// segment has been replayed.
+template <int T, int K, int CA>
+__global__ void __launch_bounds__(T)
+damp_iterate_bwd_kernel(const ItBwdArgs A)
 {
-    extern __shared__ float lds[];          // gh[2], r[3]: rows of na + 1; e, ge: nb + 1; red[kItLongCache][kItWaves]
-    const int na1 = na + 1;                 // operand rows end with a zero entry (see load_cached)
-    float *gh_cur = lds, *gh_nxt = lds + na1, *h_cur = lds + 2 * na1, *h_pre = lds + 3 * na1, *h_in = lds + 4 * na1;
-    float *le = lds + 5 * na1, *ge = le + nb + 1, *red = ge + nb + 1;
+    extern __shared__ float lds[];
+    const int na = A.na, nb = A.nb, na1 = na + 1;
+    float *seg = lds;
+    float *gA = seg + static_cast<size_t>(A.every + 1) * na1, *gB = gA + na1;
+    float *le = gB + na1;
+    float *share_buf = le + nb + 1;
+    float *red = share_buf + A.n_tuples;            // two arrays of T / 64
     const int tid = threadIdx.x;
     const int64_t s = blockIdx.x;
-    const int64_t plane = static_cast<int64_t>(batch) * na;
-    const float *hs = hist + s * na;
-    if (rounds == 0) {
-        if (grad_r0)
-            for (int c = tid; c < na; c += kItThreads) grad_r0[s * na + c] = gout[s * ldg + c];
-        if (grad_e)
-            for (int j = tid; j < nb; j += kItThreads) grad_e[s * ldge + j] = 0.0f;
+    const int64_t plane = static_cast<int64_t>(A.batch) * na;
+    const float *e_row = A.e + s * A.lde;
+    const float *gs = A.gout + s * A.ldg;
+    if (A.rounds == 0) {
+        if (A.grad_r0)
+            for (int c = tid; c < na; c += T) A.grad_r0[s * na + c] = gs[c];
+        if (A.grad_e)
+            for (int j = tid; j < nb; j += T) A.grad_e[s * A.ldge + j] = 0.0f;
         return;
     }
-    for (int c = tid; c < na; c += kItThreads) {
-        h_cur[c] = hs[(rounds - 1) * plane + c];
-        h_pre[c] = hs[max(rounds - 2, 0) * plane + c];
+    for (int j = tid; j <= nb; j += T) le[j] = j < nb ? e_row[j] : 0.0f;
+    for (int q = tid; q < A.n_tuples; q += T) share_buf[q] = 0.0f;
+    for (int c = tid; c < na; c += T) gA[c] = gs[c];
+    if (tid == 0) {
+        gA[na] = 0.0f; gB[na] = 0.0f;
+        for (int x = 0; x <= A.every; ++x) seg[x * na1 + na] = 0.0f;
     }
-    for (int j = tid; j <= nb; j += kItThreads) { le[j] = j < nb ? e[s * lde + j] : 0.0f; ge[j] = 0.0f; }
-    if (tid == 0) { gh_cur[na] = 0.0f; gh_nxt[na] = 0.0f; h_cur[na] = 0.0f; h_pre[na] = 0.0f; h_in[na] = 0.0f; }
-    Cached<kItCacheA> col[K], rowa[K];
+    Cached<CA> col[K], rowa[K];
+    bool wide[K];                           // this row is summed by the whole workgroup
+    float share[K][CA];
 #pragma unroll
     for (int k = 0; k < K; ++k) {
-        load_cached(col[k], T.col_ptr, T.col_ij, tid + kItThreads * k, na, pack16(na, nb));
-        load_cached(rowa[k], T.rowa_ptr, T.rowa_jc, tid + kItThreads * k, na, pack16(nb, na));
+        load_cached<CA, false>(col[k], A.col_ptr, A.col_ij, tid + T * k, na, pack16(na, nb), e_row);
+        load_cached<CA, true>(rowa[k], A.rowa_ptr, A.rowa_jc, tid + T * k, na, pack16(nb, na), e_row);
+        wide[k] = rowa[k].q1 - rowa[k].q0 > static_cast<uint32_t>(kLongTableRow);
+#pragma unroll
+        for (int x = 0; x < CA; ++x) share[k][x] = 0.0f;
     }
-    // The first kItLongCache rows of the first operand with many tuples are summed by the whole workgroup: which
-    // rows they are and this thread's share of their tuples are the same in every round.
-    int lx[kItLongCache];
-    bool l_on[kItLongCache];
-    uint32_t ent_l[kItLongCache][kItMaxK];
-    int n_long_a = 0;
-    for (int l = 0; l < T.n_long; ++l) n_long_a += static_cast<int>(T.long_rows[l]) < na;   // rows of a come first
+    int n_long_a = 0;                       // the long rows of the first operand come first in the list
+    for (int l = 0; l < A.n_long; ++l) n_long_a += static_cast<int>(A.long_rows[l]) < na;
+    int red_sel = 0;
+
+    const int n_seg = (A.rounds + A.every - 1) / A.every;
+    for (int sg = n_seg - 1; sg >= 0; --sg) {
+        const int t0 = sg * A.every, len = min(A.every, A.rounds - t0);
+        // ---- the rounds of this segment into seg[0 .. len]
+        if (A.hist) {
+            for (int x = 0; x <= len; ++x) {
+                const float *h = A.hist + (t0 + x) * plane + s * na;
+                for (int c = tid; c < na; c += T) seg[x * na1 + c] = h[c];
+            }
+            lds_barrier();
+            // a stored 1 may be a clamped sum: give it the sign of the decision (the magnitudes others read stay 1)
+            for (int x = 1; x <= len; ++x) {
 #pragma unroll
-    for (int l = 0; l < kItLongCache; ++l) {
-        l_on[l] = l < n_long_a;
-        lx[l] = l_on[l] ? static_cast<int>(T.long_rows[l]) : -1;
-        const uint32_t q0 = l_on[l] ? T.rowa_ptr[lx[l]] : 0u;
-        const uint32_t len = l_on[l] ? T.rowa_ptr[lx[l] + 1] - q0 : 0u;
+                for (int k = 0; k < K; ++k) {
+                    const int c = tid + T * k;
+                    if (c < na && seg[x * na1 + c] >= 1.0f)
+                        seg[x * na1 + c] = signed_tag(col_pre(col[k], A.col_ij, seg + (x - 1) * na1, le)) < 0.0f ? -1.0f : 1.0f;
+                }
+            }
+            lds_barrier();
+        } else {
+            const float *first = sg == 0 ? A.r0 + s * A.ldr : A.ckpt + (sg - 1) * plane + s * na;
+            for (int c = tid; c < na; c += T) seg[c] = first[c];
+            lds_barrier();
+            for (int x = 0; x < len; ++x) {
+                const float *x_cur = seg + x * na1;
+                float *x_nxt = seg + (x + 1) * na1;
 #pragma unroll
-        for (int k = 0; k < kItMaxK; ++k)          // a row has at most nb <= kItMaxRow tuples
-            ent_l[l][k] = static_cast<uint32_t>(tid + kItThreads * k) < len ? T.rowa_jc[q0 + tid + kItThreads * k] : pack16(nb, na);
-    }
-    int wide_a[K];                          // index of the workgroup-summed row that is this thread's, or -1
-#pragma unroll
-    for (int k = 0; k < K; ++k) {
-        wide_a[k] = -1;
-#pragma unroll
-        for (int l = 0; l < kItLongCache; ++l)
-            if (l_on[l] && lx[l] == tid + kItThreads * k) wide_a[k] = l;
-    }
-    float share[K][kItCacheA], share_l[kItLongCache][kItMaxK];
-#pragma unroll
-    for (int k = 0; k < K; ++k)
-#pragma unroll
-        for (int x = 0; x < kItCacheA; ++x) share[k][x] = 0.0f;
-#pragma unroll
-    for (int l = 0; l < kItLongCache; ++l)
-#pragma unroll
-        for (int k = 0; k < kItMaxK; ++k) share_l[l][k] = 0.0f;
-    lds_barrier();
-    // gradient reaching the unclamped sums of the last round: r_rounds < 1 means the clamp did not act
-#pragma unroll
-    for (int k = 0; k < K; ++k) {
-        const int c = tid + kItThreads * k;
-        if (c < na) {
-            float gv = gout[s * ldg + c];
-            if (hs[rounds * plane + c] >= 1.0f && !(dot_lo_hi(col[k], T.col_ij, h_cur, le) <= 1.0f)) gv = 0.0f;
-            gh_cur[c] = gv;
+                for (int k = 0; k < K; ++k) {
+                    const int c = tid + T * k;
+                    if (c < na) x_nxt[c] = signed_tag(col_pre(col[k], A.col_ij, x_cur, le));
+                }
+                lds_barrier();
+            }
         }
-    }
-    lds_barrier();
-    // One round.  `slot` carries this thread's piece of r_{t-2} from memory: with `primed` it was requested
-    // kItAhead rounds ago and is re-armed here for round t - kItAhead; otherwise it is requested at the start of
-    // the round.  The requests are unconditional (indices clamped) so that the wait in front of their use counts
-    // exactly the younger requests in flight.
-    auto round_body = [&](int t, float (&slot)[K], bool primed) {
-        if (!primed) {
+        // ---- the gradient handed over by the later segment (or the upstream gradient) meets the decision of this
+        // segment's last round
+        for (int c = tid; c < na; c += T)
+            if (seg[len * na1 + c] < 0.0f) gA[c] = 0.0f;
+        lds_barrier();
+        // ---- walk the segment backwards
+        for (int x = len - 1; x >= 0; --x) {
+            const float *xr = seg + x * na1;
+            // rows with many tuples: the whole workgroup takes strided shares of the row
+            float g_wide[K];
 #pragma unroll
-            for (int k = 0; k < K; ++k)
-                slot[k] = hs[max(t - 2, 0) * plane + min(tid + kItThreads * k, na - 1)];
-        }
-        float wide_tot[kItLongCache];
-#pragma unroll
-        for (int l = 0; l < kItLongCache; ++l) {
-            wide_tot[l] = 0.0f;
-            if (l_on[l]) {
-                const float ri = h_cur[lx[l]];
+            for (int k = 0; k < K; ++k) g_wide[k] = 0.0f;
+            for (int l = 0; l < n_long_a; ++l) {
+                const int i = static_cast<int>(A.long_rows[l]);
+                const float ri = fabsf(xr[i]);
                 float acc = 0.0f;
-#pragma unroll
-                for (int k = 0; k < kItMaxK; ++k) {
-                    const float ghc = gh_cur[ent_l[l][k] >> 16];
-                    acc = __builtin_fmaf(le[ent_l[l][k] & 0xffffu], ghc, acc);
-                    share_l[l][k] = __builtin_fmaf(ri, ghc, share_l[l][k]);
-                }
-                wide_tot[l] = block_sum(acc, red + l * kItWaves);
-            }
-        }
-        float g[K], ri[K];
-#pragma unroll
-        for (int k = 0; k < K; ++k) {           // rowa tuples are (j | column << 16)
-            const int i = tid + kItThreads * k;
-            ri[k] = h_cur[min(i, na)];
-            float acc = 0.0f;
-            if (wide_a[k] < 0) {
-#pragma unroll
-                for (int x = 0; x < kItCacheA; ++x) {
-                    const float ghc = gh_cur[rowa[k].t[x] >> 16];
-                    acc = __builtin_fmaf(le[rowa[k].t[x] & 0xffffu], ghc, acc);
-                    share[k][x] = __builtin_fmaf(ri[k], ghc, share[k][x]);
-                }
-                for (uint32_t q = rowa[k].q0 + kItCacheA; q < rowa[k].q1; ++q) {   // tuples past the registers
-                    const uint32_t tu = T.rowa_jc[q];
-                    const float ghc = gh_cur[tu >> 16];
+                for (uint32_t q = A.rowa_ptr[i] + tid, q1 = A.rowa_ptr[i + 1]; q < q1; q += T) {
+                    const uint32_t tu = A.rowa_jc[q];
+                    const float ghc = gA[tu >> 16];
                     acc = __builtin_fmaf(le[tu & 0xffffu], ghc, acc);
-                    atomicAdd(&ge[tu & 0xffffu], ri[k] * ghc);
+                    share_buf[q] = __builtin_fmaf(ri, ghc, share_buf[q]);
                 }
-            } else {
-                acc = wide_a[k] == 0 ? wide_tot[0] : wide_tot[kItLongCache - 1];
+                const float tot = block_sum<T>(acc, red + red_sel * (T / kWave));
+                red_sel ^= 1;
+#pragma unroll
+                for (int k = 0; k < K; ++k)
+                    if (i == tid + T * k) g_wide[k] = tot;
             }
-            g[k] = acc;
-        }
-        if (t > 0) {
 #pragma unroll
             for (int k = 0; k < K; ++k) {
-                const int c = tid + kItThreads * k;
-                if (c < na) {
-                    float gv = g[k];
-                    if (ri[k] >= 1.0f && !(dot_lo_hi(col[k], T.col_ij, h_pre, le) <= 1.0f)) gv = 0.0f;
-                    gh_nxt[c] = gv;
-                    h_in[c] = slot[k];          // r_{t-2} goes to the row no thread reads in this round
+                const int i = tid + T * k;
+                const float xi = xr[min(i, na)];
+                const float ri = fabsf(xi);
+                float g = g_wide[k];
+                if (!wide[k]) {
+#pragma unroll
+                    for (int y = 0; y < CA; ++y) {  // row tuples are (j | column << 16)
+                        const float ghc = gA[rowa[k].t[y] >> 16];
+                        g = __builtin_fmaf(rowa[k].e[y], ghc, g);
+                        share[k][y] = __builtin_fmaf(ri, ghc, share[k][y]);
+                    }
+                    for (uint32_t q = rowa[k].q0 + CA; q < rowa[k].q1; ++q) {   // tuples past the registers
+                        const uint32_t tu = A.rowa_jc[q];
+                        const float ghc = gA[tu >> 16];
+                        g = __builtin_fmaf(le[tu & 0xffffu], ghc, g);
+                        share_buf[q] = __builtin_fmaf(ri, ghc, share_buf[q]);
+                    }
                 }
+                if (i < na) gB[i] = (x > 0 && xi < 0.0f) ? 0.0f : g;
             }
-        } else if (grad_r0) {
-#pragma unroll
-            for (int k = 0; k < K; ++k)
-                if (tid + kItThreads * k < na) grad_r0[s * na + tid + kItThreads * k] = g[k];
+            lds_barrier();
+            float *sw = gA; gA = gB; gB = sw;
         }
-        if (primed) {
-#pragma unroll
-            for (int k = 0; k < K; ++k)
-                slot[k] = hs[max(t - 2 - kItAhead, 0) * plane + min(tid + kItThreads * k, na - 1)];
-        }
-        lds_barrier();
-        float *sw = gh_cur; gh_cur = gh_nxt; gh_nxt = sw;
-        sw = h_cur; h_cur = h_pre; h_pre = h_in; h_in = sw;
-    };
-    float ring[kItAhead][K];
-    int t = rounds - 1;
-    for (; (t + 1) % kItAhead != 0; --t) round_body(t, ring[0], false);
-    if (t >= 0) {
-#pragma unroll
-        for (int x = 0; x < kItAhead; ++x)
-#pragma unroll
-            for (int k = 0; k < K; ++k)
-                ring[x][k] = hs[max(t - 2 - x, 0) * plane + min(tid + kItThreads * k, na - 1)];
     }
-    for (; t >= 0; t -= kItAhead) {
-        round_body(t, ring[0], true);
-        round_body(t - 1, ring[1], true);
-        round_body(t - 2, ring[2], true);
-        round_body(t - 3, ring[3], true);
-    }
-    if (!grad_e) return;
-    // The tuples' shares meet per symbol of e.  Symbols whose row is long (met by most threads) are summed over
-    // the workgroup first, two of them; every other share is added to its symbol's entry in LDS.
-    int jw[kItLongCache];
-#pragma unroll
-    for (int l = 0; l < kItLongCache; ++l) {
-        const int x = n_long_a + l;
-        jw[l] = x < T.n_long ? static_cast<int>(T.long_rows[x]) - na : -1;
-    }
-    float wide_e[kItLongCache];
-#pragma unroll
-    for (int l = 0; l < kItLongCache; ++l) wide_e[l] = 0.0f;
-    auto deposit = [&](uint32_t tu, float v) {
-        const int j = static_cast<int>(tu & 0xffffu);
-        if (j >= nb) return;                    // an empty register slot
-        if (j == jw[0]) wide_e[0] += v;
-        else if (j == jw[kItLongCache - 1]) wide_e[kItLongCache - 1] += v;
-        else atomicAdd(&ge[j], v);
-    };
+    if (A.grad_r0)
+        for (int c = tid; c < na; c += T) A.grad_r0[s * na + c] = gA[c];
+    if (!A.grad_e) return;
+    // ---- the tuples' shares meet per symbol of e, in the order of the symbol's row (ascending first operand)
 #pragma unroll
     for (int k = 0; k < K; ++k)
-        if (wide_a[k] < 0)
+        if (!wide[k])
 #pragma unroll
-            for (int x = 0; x < kItCacheA; ++x) deposit(rowa[k].t[x], share[k][x]);
-#pragma unroll
-    for (int l = 0; l < kItLongCache; ++l)
-        if (l_on[l])
-#pragma unroll
-            for (int k = 0; k < kItMaxK; ++k) deposit(ent_l[l][k], share_l[l][k]);
-#pragma unroll
-    for (int l = 0; l < kItLongCache; ++l) {
-        if (jw[l] >= 0) {
-            const float tot = block_sum(wide_e[l], red + l * kItWaves);
-            if (tid == 0) atomicAdd(&ge[jw[l]], tot);
-        }
-    }
+            for (int y = 0; y < CA; ++y)
+                if (rowa[k].q0 + y < rowa[k].q1) share_buf[rowa[k].q0 + y] = share[k][y];
     lds_barrier();
-    for (int j = tid; j < nb; j += kItThreads) grad_e[s * ldge + j] = ge[j];
+    for (int j = tid; j < nb; j += T) {
+        const uint32_t q0 = A.rowb_ptr[j], q1 = A.rowb_ptr[j + 1];
+        if (q1 - q0 > static_cast<uint32_t>(kLongTableRow)) continue;
+        float tot = 0.0f;
+        for (uint32_t q = q0; q < q1; ++q) tot += share_buf[A.rowb_pos[q]];
+        A.grad_e[s * A.ldge + j] = tot;
+    }
+    const int wave = tid / kWave, lane = tid & (kWave - 1);
+    for (int l = n_long_a + wave; l < A.n_long; l += T / kWave) {
+        const int j = static_cast<int>(A.long_rows[l]) - na;
+        float tot = 0.0f;
+        for (uint32_t q = A.rowb_ptr[j] + lane, q1 = A.rowb_ptr[j + 1]; q < q1; q += kWave) tot += share_buf[A.rowb_pos[q]];
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) tot += __shfl_xor(tot, d, kWave);
+        if (lane == 0) A.grad_e[s * A.ldge + j] = tot;
+    }
 }
 
-static dol_status check_iterate(const dol_dist *e, const dol_fn_table *f, int32_t rounds, size_t lds_bytes)
+// ---------------------------------------------------------------- host side
+
+dol_status check_iterate(const dol_dist *e, const dol_fn_table *f, int32_t rounds)
 {
     if (!e || !f) return fail(DOL_EINVAL, "NULL argument");
     if (rounds < 0) return fail(DOL_EINVAL, "rounds is negative");
     if (e->batch < 0 || e->n_sym != f->nb || e->ld < e->n_sym) return fail(DOL_ESHAPE, "e has %d symbols, the table needs %d", e->n_sym, f->nb);
     if (f->n_out != f->na) return fail(DOL_EUNSUPPORTED, "the table maps %d symbols to %d: not square", f->na, f->n_out);
     if (f->na > kItMaxRow || f->nb > kItMaxRow) return fail(DOL_EUNSUPPORTED, "operands of more than %d symbols", kItMaxRow);
-    if (lds_bytes > 64 * 1024) return fail(DOL_EUNSUPPORTED, "the rows need %zu bytes of LDS, more than 65536", lds_bytes);
     if (e->batch > 0 && e->n_sym > 0 && !e->prob) return fail(DOL_EINVAL, "e.prob is NULL");
     return DOL_OK;
 }
 
-static int iterate_k(int n) { return n <= kItThreads ? 1 : n <= 2 * kItThreads ? 2 : 4; }
+dol_status check_r0(const dol_dist *r0, const dol_dist *e, const dol_fn_table *f)
+{
+    if (!r0) return fail(DOL_EINVAL, "r0 is NULL");
+    if (r0->batch != e->batch || r0->n_sym != f->na || r0->ld < r0->n_sym)
+        return fail(DOL_ESHAPE, "r0 has %d x %d, the table needs %d x %d", r0->batch, r0->n_sym, e->batch, f->na);
+    if (r0->sym_ids)
+        for (int32_t c = 0; c < f->na; ++c)
+            if (r0->sym_ids[c] != f->out_syms[c])
+                return fail(DOL_EUNSUPPORTED, "the table produces symbol %d where r0 has %d: a round's result cannot feed the next", f->out_syms[c], r0->sym_ids[c]);
+    if (r0->batch > 0 && f->na > 0 && !r0->prob) return fail(DOL_EINVAL, "r0.prob is NULL");
+    return DOL_OK;
+}
+
+static size_t fwd_lds(const dol_fn_table *f) { return sizeof(float) * (2 * static_cast<size_t>(f->na) + f->nb + 3); }
+
+static size_t bwd_lds(const dol_fn_table *f, int32_t every)
+{
+    return sizeof(float) * ((static_cast<size_t>(every) + 3) * (f->na + 1) + f->nb + 1 + static_cast<size_t>(f->n_tuples) + 2 * 16);
+}
+
+// Launch shape by the width of the first operand: threads per workgroup, columns per thread, tuples in registers.
+#define DOL_IT_DISPATCH(KERNEL, na, lds, st, ...)                                                                      \
+    do {                                                                                                               \
+        if ((na) <= 512) hipLaunchKernelGGL((KERNEL<512, 1, 6>), grid, dim3(512), lds, st, __VA_ARGS__);               \
+        else if ((na) <= 1024) hipLaunchKernelGGL((KERNEL<512, 2, 6>), grid, dim3(512), lds, st, __VA_ARGS__);         \
+        else if ((na) <= 2048) hipLaunchKernelGGL((KERNEL<512, 4, 3>), grid, dim3(512), lds, st, __VA_ARGS__);         \
+        else hipLaunchKernelGGL((KERNEL<1024, 4, 3>), grid, dim3(1024), lds, st, __VA_ARGS__);                         \
+    } while (0)
+
+template <typename Kern>
+static hipError_t allow_lds(Kern kern) {
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                               static_cast<int>(kItLdsMax));
+}
+
+// Kernels that ask for more than 64 KB of LDS must be told so once per device.
+static dol_status allow_big_lds()
+{
+    static std::mutex mu;
+    static bool done[64] = {};
+    int dev = 0;
+    DOL_HIP(hipGetDevice(&dev));
+    std::lock_guard<std::mutex> lock(mu);
+    if (dev < 0 || dev >= 64 || done[dev]) return DOL_OK;
+    DOL_HIP(allow_lds(damp_iterate_bwd_kernel<512, 1, 6>));
+    DOL_HIP(allow_lds(damp_iterate_bwd_kernel<512, 2, 6>));
+    DOL_HIP(allow_lds(damp_iterate_bwd_kernel<512, 4, 3>));
+    DOL_HIP(allow_lds(damp_iterate_bwd_kernel<1024, 4, 3>));
+    done[dev] = true;
+    return DOL_OK;
+}
+
+dol_status launch_iterate_fwd(const dol_dist *r0, const dol_dist *e, const dol_fn_table *f, int32_t rounds,
+                                     float *hist, float *ckpt, int32_t every, float *out, int64_t ldo, hipStream_t st)
+{
+    const size_t lds = fwd_lds(f);
+    if (lds > 64 * 1024) return fail(DOL_EUNSUPPORTED, "the rows need %zu bytes of LDS, more than 65536", lds);
+    ItFwdArgs A{};
+    A.batch = r0->batch, A.na = f->na, A.nb = f->nb, A.rounds = rounds;
+    A.col_ptr = f->col_ptr.ptr, A.col_ij = f->col_ij.ptr;
+    A.r0 = r0->prob, A.ldr = r0->ld, A.e = e->prob, A.lde = e->ld;
+    A.hist = hist, A.ckpt = ckpt, A.every = every > 0 ? every : rounds + 1, A.out = out, A.ldo = ldo;
+    const dim3 grid(static_cast<unsigned>(r0->batch));
+    DOL_IT_DISPATCH(damp_iterate_fwd_kernel, f->na, lds, st, A);
+    DOL_HIP(hipGetLastError());
+    return DOL_OK;
+}
+
+dol_status launch_iterate_bwd(const dol_dist *e, const dol_fn_table *f, int32_t rounds, const float *hist,
+                                     const float *r0, int64_t ldr, const float *ckpt, int32_t every,
+                                     const float *grad_out, int64_t ldg, float *grad_r0, float *grad_e, hipStream_t st)
+{
+    if (!f->rowb_pos.ptr && f->n_tuples > 0) return fail(DOL_EINVAL, "the table lacks the row cross-index of square tables");
+    const size_t lds = bwd_lds(f, every);
+    if (lds > kItLdsMax)
+        return fail(DOL_EUNSUPPORTED, "segments of %d rounds need %zu bytes of LDS, more than %zu", every, lds, kItLdsMax);
+    if (dol_status s = allow_big_lds()) return s;
+    ItBwdArgs A{};
+    A.batch = e->batch, A.na = f->na, A.nb = f->nb, A.rounds = rounds, A.every = every;
+    A.n_tuples = static_cast<int32_t>(f->n_tuples), A.n_long = static_cast<int32_t>(f->long_rows.n);
+    A.col_ptr = f->col_ptr.ptr, A.col_ij = f->col_ij.ptr, A.rowa_ptr = f->rowa_ptr.ptr, A.rowa_jc = f->rowa_jc.ptr;
+    A.rowb_ptr = f->rowb_ptr.ptr, A.rowb_pos = f->rowb_pos.ptr, A.long_rows = f->long_rows.ptr;
+    A.e = e->prob, A.lde = e->ld, A.hist = hist, A.r0 = r0, A.ldr = ldr, A.ckpt = ckpt;
+    A.gout = grad_out, A.ldg = ldg, A.grad_r0 = grad_r0, A.grad_e = grad_e, A.ldge = e->ld;
+    const dim3 grid(static_cast<unsigned>(e->batch));
+    DOL_IT_DISPATCH(damp_iterate_bwd_kernel, f->na, lds, st, A);
+    DOL_HIP(hipGetLastError());
+    return DOL_OK;
+}
+
+// Rounds per segment when the sweep reads a full history: as many as fit beside one more workgroup on the unit.
+static int32_t hist_segment(const dol_fn_table *f, int32_t rounds)
+{
+    int32_t every = 8;
+    while (every > 1 && bwd_lds(f, every) > kItLdsMax / 2) every >>= 1;
+    return std::max(1, std::min(every, std::max(rounds, 1)));
+}
 
 }  // namespace dol
 
@@ -354,56 +458,60 @@ extern "C" {
 dol_status dol_iterate_apply2(const dol_dist *r0, const dol_dist *e, const dol_fn_table *f, int32_t rounds, float *hist,
                               void *hip_stream)
 {
-    if (!r0) return fail(DOL_EINVAL, "r0 is NULL");
-    const size_t lds = f ? sizeof(float) * (2 * static_cast<size_t>(f->na) + f->nb + 3) : 0;
-    if (dol_status st = check_iterate(e, f, rounds, lds)) return st;
-    if (r0->batch != e->batch || r0->n_sym != f->na || r0->ld < r0->n_sym)
-        return fail(DOL_ESHAPE, "r0 has %d x %d, the table needs %d x %d", r0->batch, r0->n_sym, e->batch, f->na);
-    if (r0->sym_ids)
-        for (int32_t c = 0; c < f->na; ++c)
-            if (r0->sym_ids[c] != f->out_syms[c])
-                return fail(DOL_EUNSUPPORTED, "the table produces symbol %d where r0 has %d: a round's result cannot feed the next", f->out_syms[c], r0->sym_ids[c]);
+    if (dol_status st = check_iterate(e, f, rounds)) return st;
+    if (dol_status st = check_r0(r0, e, f)) return st;
     if (r0->batch == 0 || f->na == 0) return DOL_OK;
-    if (!r0->prob || !hist) return fail(DOL_EINVAL, "r0.prob or hist is NULL");
-    const dim3 grid(static_cast<unsigned>(r0->batch)), block(kItThreads);
-    hipStream_t st = static_cast<hipStream_t>(hip_stream);
-#define DOL_IT_FWD(KK)                                                                                              \
-    hipLaunchKernelGGL(damp_iterate_fwd_kernel<KK>, grid, block, lds, st, r0->batch, f->na, f->nb, rounds, f->col_ptr.ptr, \
-                       f->col_ij.ptr, r0->prob, r0->ld, e->prob, e->ld, hist)
-    switch (iterate_k(f->na)) {
-    case 1: DOL_IT_FWD(1); break;
-    case 2: DOL_IT_FWD(2); break;
-    default: DOL_IT_FWD(4); break;
-    }
-#undef DOL_IT_FWD
-    DOL_HIP(hipGetLastError());
-    return DOL_OK;
+    if (!hist) return fail(DOL_EINVAL, "hist is NULL");
+    return launch_iterate_fwd(r0, e, f, rounds, hist, nullptr, 0, nullptr, 0, static_cast<hipStream_t>(hip_stream));
 }
 
 dol_status dol_iterate_backward(const dol_dist *e, const dol_fn_table *f, int32_t rounds, const float *hist,
                                 const float *grad_out, int64_t grad_out_ld, float *grad_r0, float *grad_e,
                                 void *hip_stream)
 {
-    const size_t lds = f ? sizeof(float) * (5 * static_cast<size_t>(f->na) + 2 * static_cast<size_t>(f->nb) + 7 + kItLongCache * kItWaves) : 0;
-    if (dol_status st = check_iterate(e, f, rounds, lds)) return st;
+    if (dol_status st = check_iterate(e, f, rounds)) return st;
     if (e->batch == 0 || f->na == 0 || (!grad_r0 && !grad_e)) return DOL_OK;
     if (!hist || !grad_out) return fail(DOL_EINVAL, "hist or grad_out is NULL");
     if (grad_out_ld < f->na) return fail(DOL_ESHAPE, "grad_out_ld = %lld is smaller than %d", static_cast<long long>(grad_out_ld), f->na);
-    const ItTable T{f->col_ptr.ptr, f->col_ij.ptr, f->rowa_ptr.ptr, f->rowa_jc.ptr, f->rowb_ptr.ptr, f->rowb_ic.ptr,
-                    f->long_rows.ptr, static_cast<int32_t>(f->long_rows.n)};
-    const dim3 grid(static_cast<unsigned>(e->batch)), block(kItThreads);
-    hipStream_t st = static_cast<hipStream_t>(hip_stream);
-#define DOL_IT_BWD(KA)                                                                                              \
-    hipLaunchKernelGGL((damp_iterate_bwd_kernel<KA>), grid, block, lds, st, e->batch, f->na, f->nb, rounds, T,            \
-                       e->prob, e->ld, hist, grad_out, grad_out_ld, grad_r0, grad_e, e->ld)
-    switch (iterate_k(f->na)) {
-    case 1: DOL_IT_BWD(1); break;
-    case 2: DOL_IT_BWD(2); break;
-    default: DOL_IT_BWD(4); break;
-    }
-#undef DOL_IT_BWD
-    DOL_HIP(hipGetLastError());
-    return DOL_OK;
+    return launch_iterate_bwd(e, f, rounds, hist, nullptr, 0, nullptr, hist_segment(f, rounds), grad_out, grad_out_ld,
+                              grad_r0, grad_e, static_cast<hipStream_t>(hip_stream));
+}
+
+int32_t dol_iterate_ckpt_count(int32_t rounds, int32_t ckpt_every)
+{
+    if (rounds <= 0 || ckpt_every <= 0) return 0;
+    return (rounds + ckpt_every - 1) / ckpt_every - 1;
+}
+
+dol_status dol_iterate_apply2_ckpt(const dol_dist *r0, const dol_dist *e, const dol_fn_table *f, int32_t rounds,
+                                   int32_t ckpt_every, dol_dist *out, float *ckpt, void *hip_stream)
+{
+    if (dol_status st = check_iterate(e, f, rounds)) return st;
+    if (dol_status st = check_r0(r0, e, f)) return st;
+    if (ckpt_every < 1) return fail(DOL_EINVAL, "ckpt_every = %d, must be at least 1", ckpt_every);
+    if (!out) return fail(DOL_EINVAL, "out is NULL");
+    if (out->batch != r0->batch || out->n_sym != f->na || out->ld < out->n_sym)
+        return fail(DOL_ESHAPE, "out has %d x %d, the rounds produce %d x %d", out->batch, out->n_sym, r0->batch, f->na);
+    if (r0->batch == 0 || f->na == 0) return DOL_OK;
+    if (!out->prob) return fail(DOL_EINVAL, "out.prob is NULL");
+    if (dol_iterate_ckpt_count(rounds, ckpt_every) > 0 && !ckpt) return fail(DOL_EINVAL, "ckpt is NULL");
+    return launch_iterate_fwd(r0, e, f, rounds, nullptr, ckpt, ckpt_every, out->prob, out->ld, static_cast<hipStream_t>(hip_stream));
+}
+
+dol_status dol_iterate_backward_ckpt(const dol_dist *r0, const dol_dist *e, const dol_fn_table *f, int32_t rounds,
+                                     int32_t ckpt_every, const float *ckpt, const float *grad_out, int64_t grad_out_ld,
+                                     float *grad_r0, float *grad_e, void *hip_stream)
+{
+    if (dol_status st = check_iterate(e, f, rounds)) return st;
+    if (dol_status st = check_r0(r0, e, f)) return st;
+    if (ckpt_every < 1) return fail(DOL_EINVAL, "ckpt_every = %d, must be at least 1", ckpt_every);
+    if (e->batch == 0 || f->na == 0 || (!grad_r0 && !grad_e)) return DOL_OK;
+    if (!grad_out) return fail(DOL_EINVAL, "grad_out is NULL");
+    if (grad_out_ld < f->na) return fail(DOL_ESHAPE, "grad_out_ld = %lld is smaller than %d", static_cast<long long>(grad_out_ld), f->na);
+    if (dol_iterate_ckpt_count(rounds, ckpt_every) > 0 && !ckpt) return fail(DOL_EINVAL, "ckpt is NULL");
+    const int32_t every = std::max(1, std::min(ckpt_every, std::max(rounds, 1)));
+    return launch_iterate_bwd(e, f, rounds, nullptr, r0->prob, r0->ld, ckpt, every, grad_out, grad_out_ld, grad_r0,
+                              grad_e, static_cast<hipStream_t>(hip_stream));
 }
 
 }  // extern "C"

@@ -91,14 +91,17 @@ static dol_status build_table(int32_t na, int32_t nb, std::vector<Tuple> &tup, d
     for (int32_t i = 0; i < na; ++i) rowa_ptr[i + 1] += rowa_ptr[i];
     for (int32_t j = 0; j < nb; ++j) rowb_ptr[j + 1] += rowb_ptr[j];
     std::vector<uint32_t> col_ij(tup.size()), rowa_jc(tup.size()), rowb_ic(tup.size());
+    std::vector<uint32_t> rowb_pos(S == na ? tup.size() : 0);
     {
         std::vector<uint32_t> fc(col_ptr.begin(), col_ptr.end() - 1), fa(rowa_ptr.begin(), rowa_ptr.end() - 1),
             fb(rowb_ptr.begin(), rowb_ptr.end() - 1);
         for (size_t t = 0; t < tup.size(); ++t) {
             const uint32_t i = static_cast<uint32_t>(tup[t].i), j = static_cast<uint32_t>(tup[t].j);
             col_ij[fc[col[t]]++] = pack16(i, j);
-            rowa_jc[fa[i]++] = pack16(j, col[t]);
-            rowb_ic[fb[j]++] = pack16(i, col[t]);
+            const uint32_t qa = fa[i]++, qb = fb[j]++;
+            rowa_jc[qa] = pack16(j, col[t]);
+            rowb_ic[qb] = pack16(i, col[t]);
+            if (!rowb_pos.empty()) rowb_pos[qb] = qa;
         }
     }
     // sum-like: inside every column i rises by one and j falls by one (f(i,j) depends on i+j only and is injective in it)
@@ -171,7 +174,8 @@ static dol_status build_table(int32_t na, int32_t nb, std::vector<Tuple> &tup, d
     }
     if ((e = tb->col_ptr.upload(col_ptr)) != hipSuccess || (e = tb->col_ij.upload(col_ij)) != hipSuccess ||
         (e = tb->rowa_ptr.upload(rowa_ptr)) != hipSuccess || (e = tb->rowa_jc.upload(rowa_jc)) != hipSuccess ||
-        (e = tb->rowb_ptr.upload(rowb_ptr)) != hipSuccess || (e = tb->rowb_ic.upload(rowb_ic)) != hipSuccess)
+        (e = tb->rowb_ptr.upload(rowb_ptr)) != hipSuccess || (e = tb->rowb_ic.upload(rowb_ic)) != hipSuccess ||
+        (e = tb->rowb_pos.upload(rowb_pos)) != hipSuccess)
         return hip_fail(e, "uploading the function table");
     if (!conv_path_ok(tb.get()))
         if (dol_status s2 = lds_plan_build(tb.get(), col_ptr, col_ij, rowa_ptr, rowa_jc, rowb_ptr, rowb_ic)) return s2;

@@ -65,7 +65,13 @@ class Program:
             l.call()
 
     def algorithmic_bytes(self) -> int:
+        """Sum over the launches of what each must move by itself (operands in, results out)."""
         return sum(l.bytes for l in self.launches)
+
+    # Bytes the whole step must move if nothing but the program's inputs and results touched HBM (every
+    # intermediate Distribution and gradient kept on chip): set by each program from its shapes.
+    min_bytes: int = 0
+    flops: int = 0                      # 2 per multiply-add of the step (DAMP); 0 for DTKP (compare / select work)
 
 
 def _apply_fwd(a, b, f, out, n_tup, prov=None, dtkp_k=0):
@@ -95,6 +101,8 @@ class Sum2Forward(Program):
         self.out = dol.Dist.empty(self.table.out_syms, self.batch, device)
         self.launches = [_apply_fwd(self.a, self.b, self.table, self.out, _n_tuples(w["table"]))]
         self.sample_ops = self.batch
+        self.min_bytes = self.launches[0].bytes
+        self.flops = 2 * self.launches[0].macs
 
 
 class SumChain(Program):
@@ -136,6 +144,9 @@ class SumChain(Program):
             ga = self.g_acc[t - 1] if t > 1 else self.grad_p[0]
             self.launches.append(_apply_bwd(self.records[t - 1], self.g_acc[t], ga, self.grad_p[t], n_tup[t - 1]))
         self.sample_ops = 2 * (self.n - 1) * self.batch
+        n_in = sum(d.n_sym for d in self.digits)         # inputs in, their gradients and the result out, the target
+        self.min_bytes = 4 * self.batch * (2 * n_in + last.n_sym + 1)
+        self.flops = 2 * sum(l.macs for l in self.launches)
 
 
 class ProductChain(SumChain):
@@ -173,6 +184,8 @@ class SumChainFused(Program):
         self.launches = [Launch(dol.fold_kernel(self.fold), lambda: dol.fold_apply2(self.fold),
                                 4 * self.batch * (2 * n_in + self.out.n_sym + 1), self.batch * macs, "fwd")]
         self.sample_ops = 2 * (self.n - 1) * self.batch
+        self.min_bytes = self.launches[0].bytes
+        self.flops = 2 * self.launches[0].macs
 
 
 class HashedPipeline(Program):
@@ -214,6 +227,9 @@ class HashedPipeline(Program):
             _apply_bwd(self.rec1, self.g1, self.ga, self.gb, n_tup),
         ]
         self.sample_ops = 6 * B
+        # pa, pb, p2 and the upstream gradient in; the result and the three input gradients out
+        self.min_bytes = 4 * B * (2 * (self.a.n_sym + self.b.n_sym + np2) + 2 * n3)
+        self.flops = 2 * 3 * B * n_tup
 
 
 class HashedPipelineFused(HashedPipeline):
@@ -262,6 +278,8 @@ class DtkpSumChain(Program):
             self.launches.append(_apply_fwd(self.accs[-1], self.digits[t], tb, out, _n_tuples(tab), self.prov, k))
             self.accs.append(out)
         self.sample_ops = (self.n - 1) * B
+        # the fact probabilities in; the last Distribution's proofs and tag probabilities out
+        self.min_bytes = B * (4 * int(self.fact_prob.shape[1]) + self.accs[-1].n_sym * (12 * k + 4))
 
 
 class DtkpSumChainFused(Program):
@@ -295,6 +313,7 @@ class DtkpSumChainFused(Program):
         self.launches = [Launch("dtkp_fold_kernel<%d>" % k, lambda: dol.dtkp_fold_apply2(self.fold, self.prov),
                                 B * (4 * n_facts + syms.size * (12 * k + 4)), 0, "fwd")]
         self.sample_ops = (self.n - 1) * B
+        self.min_bytes = self.launches[0].bytes
 
 
 class GridReach(Program):
@@ -333,12 +352,17 @@ class GridReach(Program):
             self.launches.append(_apply_bwd(self.records[t], g, gn, self.g_e, n_tup))
             g = gn
         self.sample_ops = 2 * self.rounds * B
+        # edge probabilities and the upstream gradient in; the last round's result and the edge gradient out
+        self.min_bytes = 4 * B * (2 * E + 2 * n)
+        self.flops = 2 * 3 * B * self.rounds * n_tup
 
 
 class GridReachFused(Program):
-    """Config 5 through dol_iterate_apply2 / dol_iterate_backward: all rounds of a sweep in one launch."""
+    """Config 5 through dol_iterate_apply2_ckpt / dol_iterate_backward_ckpt: all rounds of a sweep in one launch; only
+    the last round and a checkpoint every `ckpt_every` rounds leave the chip, the reverse sweep replays the rounds in
+    between in LDS.  ckpt_every = 0: the full history goes through HBM instead (dol_iterate_apply2 / _backward)."""
 
-    def __init__(self, w, device="cuda"):
+    def __init__(self, w, device="cuda", ckpt_every=8):
         B, side = w["p"].shape[0], w["side"]
         self.batch, self.rounds, n = B, w["rounds"], side * side
         E = w["edge_u"].size
@@ -351,20 +375,30 @@ class GridReachFused(Program):
         r0 = torch.zeros((B, n), dtype=torch.float32, device=device)
         r0[:, w["src"]] = 1.0
         self.r0 = dol.Dist(np.arange(n), r0)
-        self.hist = torch.empty((self.rounds + 1, B, n), dtype=torch.float32, device=device)
         self.g_out = _dev(w["g"], device)
         self.g_e = torch.empty((B, E + 1), dtype=torch.float32, device=device)
         self.grad_p = self.g_e[:, :E]
         R = self.rounds
+        self.ckpt_every = ckpt_every
+        if ckpt_every:
+            self.out = dol.Dist.empty(np.arange(n), B, device)
+            n_ck = dol.iterate_ckpt_count(R, ckpt_every)
+            self.ckpt = torch.empty((n_ck, B, n), dtype=torch.float32, device=device) if n_ck else None
+            fwd = lambda: dol.iterate_apply2_ckpt(self.r0, self.edges, self.table, R, ckpt_every, self.out, self.ckpt)
+            bwd = lambda: dol.iterate_backward_ckpt(self.r0, self.edges, self.table, R, ckpt_every, self.ckpt,
+                                                    self.g_out, None, self.g_e)
+        else:
+            self.hist = torch.empty((R + 1, B, n), dtype=torch.float32, device=device)
+            self.out = dol.Dist(np.arange(n), self.hist[R])
+            fwd = lambda: dol.iterate_apply2(self.r0, self.edges, self.table, R, self.hist)
+            bwd = lambda: dol.iterate_backward(self.edges, self.table, R, self.hist, self.g_out, None, self.g_e)
         self.launches = [
-            Launch("damp_iterate_fwd_kernel",
-                   lambda: dol.iterate_apply2(self.r0, self.edges, self.table, R, self.hist),
-                   4 * B * (n + E + 1 + (R + 1) * n), B * R * n_tup, "fwd"),
-            Launch("damp_iterate_bwd_kernel",
-                   lambda: dol.iterate_backward(self.edges, self.table, R, self.hist, self.g_out, None, self.g_e),
-                   4 * B * ((R + 1) * n + n + 2 * (E + 1)), 2 * B * R * n_tup, "bwd"),
-        ]
+            Launch("damp_iterate_fwd_kernel", fwd, 4 * B * (n + E + 1 + n), B * R * n_tup, "fwd"),     # r_0 and e in, r_R out
+            Launch("damp_iterate_bwd_kernel", bwd, 4 * B * (n + 2 * (E + 1)), 2 * B * R * n_tup, "bwd"),  # gradient and e in, gradient of e out
+        ]                                    # (what the sweeps keep of the rounds in between is not algorithmic)
         self.sample_ops = 2 * R * B
+        self.min_bytes = 4 * B * (2 * E + 2 * n)
+        self.flops = 2 * 3 * B * R * n_tup
 
 
 class TransitiveClosure(Program):

@@ -307,7 +307,7 @@ def test_config5_fused_iteration(gp, dol, batch, side, rounds):
     """dol_iterate_apply2 / dol_iterate_backward: all rounds in one launch, same results as round-by-round calls."""
     w = W.config5(batch=batch, side=side, rounds=rounds, seed=side + 1)
     ref = OP.grid_reach_fwd_bwd(w)
-    prog = gp.GridReachFused(w)
+    prog = gp.GridReachFused(w, ckpt_every=0)
     prog.step()
     hist = host(prog.hist)
     assert_close(hist, ref["hist"], "fused reach history")
@@ -327,6 +327,37 @@ def test_config5_fused_iteration(gp, dol, batch, side, rounds):
                            dol.Dist(np.arange(3), torch.ones((2, 3), device="cuda")), f, 2,
                            torch.empty((3, 2, 4), device="cuda"))
     assert ei.value.status == 5
+
+
+@pytest.mark.parametrize("batch,side,rounds,every", [(256, 32, 64, 8), (256, 32, 64, 16), (33, 7, 20, 6), (33, 7, 20, 1),
+                                                      (2, 3, 5, 5), (2, 3, 5, 9), (5, 4, 1, 3), (3, 3, 0, 2), (7, 32, 64, 30)])
+def test_config5_checkpointed_iteration(gp, dol, batch, side, rounds, every):
+    """dol_iterate_apply2_ckpt / dol_iterate_backward_ckpt: only the last round and a checkpoint every `every` rounds
+    leave the chip; the reverse sweep replays the rounds in between.  Same results as the oracle, and bit for bit
+    those of the sweeps that keep the whole history."""
+    w = W.config5(batch=batch, side=side, rounds=rounds, seed=side + 2)
+    ref = OP.grid_reach_fwd_bwd(w)
+    prog = gp.GridReachFused(w, ckpt_every=every)
+    prog.step()
+    out = host(prog.out.prob)
+    assert_close(out, ref["hist"][-1], "checkpointed reach result")
+    np.testing.assert_array_equal(out == 1.0, ref["hist"][-1] == 1.0)
+    assert_close(host(prog.grad_p), ref["grad_p"], "checkpointed reach grad")
+    n_ck = dol.iterate_ckpt_count(rounds, every)
+    assert n_ck == max(0, -(-rounds // every) - 1)
+    for x in range(n_ck):                                                   # the checkpoints are rounds of the history
+        assert_close(host(prog.ckpt[x]), ref["hist"][(x + 1) * every], "checkpoint %d" % x)
+    full = gp.GridReachFused(w, ckpt_every=0)
+    full.step()
+    np.testing.assert_array_equal(out, host(full.hist[rounds]))
+    np.testing.assert_array_equal(host(prog.g_e), host(full.g_e))
+    g0a, g0b = torch.empty((batch, side * side), device="cuda"), torch.empty((batch, side * side), device="cuda")
+    dol.iterate_backward_ckpt(prog.r0, prog.edges, prog.table, rounds, every, prog.ckpt, prog.g_out, g0a, None)
+    dol.iterate_backward(full.edges, full.table, rounds, full.hist, full.g_out, g0b, None)
+    np.testing.assert_array_equal(host(g0a), host(g0b))
+    with pytest.raises(dol.DolError) as ei:
+        dol.iterate_apply2_ckpt(prog.r0, prog.edges, prog.table, rounds, 0, prog.out, prog.ckpt)
+    assert ei.value.status == 1
 
 
 @pytest.mark.parametrize("batch,n_nodes,n_edges,scale", [(64, 10, 16, 0.5), (130, 12, 30, 1.0), (3, 5, 4, 0.9), (70, 16, 40, 0.3)])
@@ -386,6 +417,21 @@ def test_fused_iteration_with_long_rows(dol, long_a, long_b):
     dol.iterate_backward(de, f, rounds, dh, dev(g), g0, ge)
     assert_close(host(g0), gr, "iterated apply: gradient of r0")
     assert_close(host(ge), want_ge, "iterated apply: gradient of e")
+    # the shares of d loss / d e meet in a fixed order: a second run and the checkpointed sweeps give the same bits
+    g0b, geb = torch.empty_like(g0), torch.empty_like(ge)
+    dol.iterate_backward(de, f, rounds, dh, dev(g), g0b, geb)
+    np.testing.assert_array_equal(host(ge), host(geb))
+    np.testing.assert_array_equal(host(g0), host(g0b))
+    for every in (2, 3, 7):
+        out = dol.Dist.empty(np.arange(na), B)
+        n_ck = dol.iterate_ckpt_count(rounds, every)
+        ck = torch.empty((n_ck, B, na), device="cuda") if n_ck else None
+        dol.iterate_apply2_ckpt(d0, de, f, rounds, every, out, ck)
+        np.testing.assert_array_equal(host(out.prob), got[-1])
+        g0c, gec = torch.empty_like(g0), torch.empty_like(ge)
+        dol.iterate_backward_ckpt(d0, de, f, rounds, every, ck, dev(g), g0c, gec)
+        np.testing.assert_array_equal(host(gec), host(ge))
+        np.testing.assert_array_equal(host(g0c), host(g0))
 
 
 def test_fused_iteration_with_more_than_1024_symbols(dol):
@@ -419,6 +465,14 @@ def test_fused_iteration_with_more_than_1024_symbols(dol):
     dol.iterate_backward(de, f, rounds, dh, dev(g), g0, ge)
     assert_close(host(g0), gr, "iterated apply, 1100 symbols: gradient of r0")
     assert_close(host(ge), want_ge, "iterated apply, 1100 symbols: gradient of e")
+    out = dol.Dist.empty(np.arange(na), B)
+    ck = torch.empty((1, B, na), device="cuda")
+    dol.iterate_apply2_ckpt(d0, de, f, rounds, 2, out, ck)
+    np.testing.assert_array_equal(host(out.prob), got[-1])
+    g0c, gec = torch.empty_like(g0), torch.empty_like(ge)
+    dol.iterate_backward_ckpt(d0, de, f, rounds, 2, ck, dev(g), g0c, gec)
+    np.testing.assert_array_equal(host(gec), host(ge))
+    np.testing.assert_array_equal(host(g0c), host(g0))
 
 
 def test_backward_of_tables_with_long_rows(dol):
@@ -822,7 +876,7 @@ def test_large_batches_sampled_rows(gp, cfg, batch):
         prog = gp.GridReachFused(w)
         prog.step()
         ref = OP.grid_reach_fwd_bwd(_rows_of(w, idx, dict(p=0, g=0)))
-        assert_close(host(prog.hist)[-1][idx], ref["r"], "reachability, sampled rows")
+        assert_close(host(prog.out.prob)[idx], ref["r"], "reachability, sampled rows")
         assert_close(host(prog.grad_p)[idx], ref["grad_p"], "reachability gradient, sampled rows")
 
 
