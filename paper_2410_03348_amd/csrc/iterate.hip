@@ -37,19 +37,22 @@ struct Cached {
 };
 
 // lo16 of a column tuple = symbol of r, hi16 = symbol of e; of a row tuple: lo16 = symbol of e, hi16 = column.
-template <int N, bool E_IN_LO>
+template <int N>
 __device__ __forceinline__ void load_cached(Cached<N> &c, const uint32_t *__restrict__ ptr,
-                                            const uint32_t *__restrict__ list, int r, int n, uint32_t dummy,
-                                            const float *__restrict__ e_row)
+                                            const uint32_t *__restrict__ list, int r, int n, uint32_t dummy)
 {
     c.q0 = c.q1 = 0;
     if (r < n) { c.q0 = ptr[r]; c.q1 = ptr[r + 1]; }
 #pragma unroll
-    for (int x = 0; x < N; ++x) {
-        const bool on = c.q0 + x < c.q1;
-        c.t[x] = on ? list[c.q0 + x] : dummy;
-        c.e[x] = on ? e_row[E_IN_LO ? c.t[x] & 0xffffu : c.t[x] >> 16] : 0.0f;
-    }
+    for (int x = 0; x < N; ++x) c.t[x] = c.q0 + x < c.q1 ? list[c.q0 + x] : dummy;
+}
+
+// The tags of e the cached tuples name, from the staged row (whose entry nb is 0: the dummy tuples point there).
+template <int N, bool E_IN_LO>
+__device__ __forceinline__ void load_cached_tags(Cached<N> &c, const float *le)
+{
+#pragma unroll
+    for (int x = 0; x < N; ++x) c.e[x] = le[E_IN_LO ? c.t[x] & 0xffffu : c.t[x] >> 16];
 }
 
 // pre of one column: sum over its tuples of |x[i]| * e[j], in list order, one fma each, starting from 0
@@ -85,13 +88,29 @@ struct ItFwdArgs {
 
 // ---------------------------------------------------------------- forward
 
+// One round from the row at `xc` into the row at `xn` (this thread's columns), then the workgroup's barrier.
+// ai[k][y] = element of the row that tuple y of column k reads; pre[k] = the column's unclamped sum.
+template <int T, int K, int CA>
+__device__ __forceinline__ void iterate_round(const Cached<CA> (&col)[K], const uint32_t *__restrict__ list, const float *xc,
+                                              float *xn, const float *le, int na, float (&pre)[K])
+{
+    const int tid = threadIdx.x;
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        const int c = tid + T * k;
+        pre[k] = col_pre(col[k], list, xc, le);
+        if (c < na) xn[c] = signed_tag(pre[k]);
+    }
+    lds_barrier();
+}
+
 template <int T, int K, int CA>
 __global__ void __launch_bounds__(T)
 damp_iterate_fwd_kernel(const ItFwdArgs A)
 {
     extern __shared__ float lds[];          // x (two rows of na + 1), e (nb + 1): each row ends with a zero
     const int na = A.na, nb = A.nb;
-    float *x_cur = lds, *x_nxt = lds + na + 1;
+    float *x0 = lds, *x1 = lds + na + 1;
     float *le = lds + 2 * (na + 1);
     const int tid = threadIdx.x;
     const int64_t s = blockIdx.x;
@@ -99,37 +118,47 @@ damp_iterate_fwd_kernel(const ItFwdArgs A)
     const float *e_row = A.e + s * A.lde;
     for (int c = tid; c < na; c += T) {
         const float v = A.r0[s * A.ldr + c];
-        x_cur[c] = v;
+        x0[c] = v;
         if (A.hist) A.hist[s * na + c] = v;
         if (A.rounds == 0 && A.out) A.out[s * A.ldo + c] = v;
     }
     for (int j = tid; j < nb; j += T) le[j] = e_row[j];
-    if (tid == 0) { x_cur[na] = 0.0f; x_nxt[na] = 0.0f; le[nb] = 0.0f; }
+    if (tid == 0) { x0[na] = 0.0f; x1[na] = 0.0f; le[nb] = 0.0f; }
     Cached<CA> col[K];
 #pragma unroll
-    for (int k = 0; k < K; ++k) load_cached<CA, false>(col[k], A.col_ptr, A.col_ij, tid + T * k, na, pack16(na, nb), e_row);
+    for (int k = 0; k < K; ++k) load_cached(col[k], A.col_ptr, A.col_ij, tid + T * k, na, pack16(na, nb));
     lds_barrier();
-    int next_ckpt = A.every, n_ckpt = 0;
-    for (int t = 1; t <= A.rounds; ++t) {
-        const bool keep = A.ckpt && t == next_ckpt && t < A.rounds;
-        float *kp = keep ? A.ckpt + n_ckpt * plane + s * na : nullptr;
-        float *hp = A.hist ? A.hist + t * plane + s * na : nullptr;
-        float *op = t == A.rounds && A.out ? A.out + s * A.ldo : nullptr;
+#pragma unroll
+    for (int k = 0; k < K; ++k) load_cached_tags<CA, false>(col[k], le);
+    // Rounds run in stretches that end where something leaves the chip: every round with a history, every
+    // `every`-th with checkpoints, the last one always.  Inside a stretch a round is LDS reads, the fma chain, one
+    // LDS write and the barrier; the two rows swap roles from round to round.
+    const int stride = A.hist ? 1 : A.every;
+    float pre[K];
+    int t = 0, n_ckpt = 0;
+    while (t < A.rounds) {
+        const int stop = min(A.rounds, (t / stride + 1) * stride);
+        for (; t + 1 < stop; t += 2) {
+            iterate_round<T, K, CA>(col, A.col_ij, x0, x1, le, na, pre);
+            iterate_round<T, K, CA>(col, A.col_ij, x1, x0, le, na, pre);
+        }
+        if (t < stop) {                     // an odd stretch: one more round, and the rows change names
+            iterate_round<T, K, CA>(col, A.col_ij, x0, x1, le, na, pre);
+            float *sw = x0; x0 = x1; x1 = sw;
+            ++t;
+        }
+        float *dst = nullptr;
+        if (A.hist) dst = A.hist + t * plane + s * na;
+        else if (t < A.rounds && A.ckpt) dst = A.ckpt + (n_ckpt++) * plane + s * na;
 #pragma unroll
         for (int k = 0; k < K; ++k) {
             const int c = tid + T * k;
+            const float v = fminf(pre[k], 1.0f);
             if (c < na) {
-                const float pre = col_pre(col[k], A.col_ij, x_cur, le);
-                x_nxt[c] = signed_tag(pre);
-                const float v = fminf(pre, 1.0f);
-                if (hp) hp[c] = v;
-                if (kp) kp[c] = v;
-                if (op) op[c] = v;
+                if (dst) dst[c] = v;
+                if (t == A.rounds && A.out) A.out[s * A.ldo + c] = v;
             }
         }
-        if (keep) { next_ckpt += A.every; ++n_ckpt; }
-        lds_barrier();
-        float *sw = x_cur; x_cur = x_nxt; x_nxt = sw;
     }
 }
 
@@ -210,8 +239,8 @@ damp_iterate_bwd_kernel(const ItBwdArgs A)
     float share[K][CA];
 #pragma unroll
     for (int k = 0; k < K; ++k) {
-        load_cached<CA, false>(col[k], A.col_ptr, A.col_ij, tid + T * k, na, pack16(na, nb), e_row);
-        load_cached<CA, true>(rowa[k], A.rowa_ptr, A.rowa_jc, tid + T * k, na, pack16(nb, na), e_row);
+        load_cached(col[k], A.col_ptr, A.col_ij, tid + T * k, na, pack16(na, nb));
+        load_cached(rowa[k], A.rowa_ptr, A.rowa_jc, tid + T * k, na, pack16(nb, na));
         wide[k] = rowa[k].q1 - rowa[k].q0 > static_cast<uint32_t>(kLongTableRow);
 #pragma unroll
         for (int x = 0; x < CA; ++x) share[k][x] = 0.0f;
@@ -219,6 +248,12 @@ damp_iterate_bwd_kernel(const ItBwdArgs A)
     int n_long_a = 0;                       // the long rows of the first operand come first in the list
     for (int l = 0; l < A.n_long; ++l) n_long_a += static_cast<int>(A.long_rows[l]) < na;
     int red_sel = 0;
+    lds_barrier();                          // e is staged
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        load_cached_tags<CA, false>(col[k], le);
+        load_cached_tags<CA, true>(rowa[k], le);
+    }
 
     const int n_seg = (A.rounds + A.every - 1) / A.every;
     for (int sg = n_seg - 1; sg >= 0; --sg) {
@@ -290,12 +325,15 @@ damp_iterate_bwd_kernel(const ItBwdArgs A)
                 const float ri = fabsf(xi);
                 float g = g_wide[k];
                 if (!wide[k]) {
+                    float g_odd = 0.0f;             // two chains of half the length
 #pragma unroll
                     for (int y = 0; y < CA; ++y) {  // row tuples are (j | column << 16)
                         const float ghc = gA[rowa[k].t[y] >> 16];
-                        g = __builtin_fmaf(rowa[k].e[y], ghc, g);
+                        if (y & 1) g_odd = __builtin_fmaf(rowa[k].e[y], ghc, g_odd);
+                        else g = __builtin_fmaf(rowa[k].e[y], ghc, g);
                         share[k][y] = __builtin_fmaf(ri, ghc, share[k][y]);
                     }
+                    g += g_odd;
                     for (uint32_t q = rowa[k].q0 + CA; q < rowa[k].q1; ++q) {   // tuples past the registers
                         const uint32_t tu = A.rowa_jc[q];
                         const float ghc = gA[tu >> 16];
@@ -371,10 +409,14 @@ static size_t bwd_lds(const dol_fn_table *f, int32_t every)
     return sizeof(float) * ((static_cast<size_t>(every) + 3) * (f->na + 1) + f->nb + 1 + static_cast<size_t>(f->n_tuples) + 2 * 16);
 }
 
-// Launch shape by the width of the first operand: threads per workgroup, columns per thread, tuples in registers.
-#define DOL_IT_DISPATCH(KERNEL, na, lds, st, ...)                                                                      \
+// Launch shape by the width of the first operand and the batch: threads per workgroup, columns per thread, tuples in
+// registers.
+// (a batch that leaves units idle gets the widest workgroup: a round is then bound by the latency of its LDS reads
+// and barrier, which more wavefronts hide; a batch of several workgroups per unit gets two columns per thread)
+#define DOL_IT_DISPATCH(KERNEL, batch, na, lds, st, ...)                                                               \
     do {                                                                                                               \
         if ((na) <= 512) hipLaunchKernelGGL((KERNEL<512, 1, 6>), grid, dim3(512), lds, st, __VA_ARGS__);               \
+        else if ((na) <= 1024 && (batch) <= 512) hipLaunchKernelGGL((KERNEL<1024, 1, 6>), grid, dim3(1024), lds, st, __VA_ARGS__); \
         else if ((na) <= 1024) hipLaunchKernelGGL((KERNEL<512, 2, 6>), grid, dim3(512), lds, st, __VA_ARGS__);         \
         else if ((na) <= 2048) hipLaunchKernelGGL((KERNEL<512, 4, 3>), grid, dim3(512), lds, st, __VA_ARGS__);         \
         else hipLaunchKernelGGL((KERNEL<1024, 4, 3>), grid, dim3(1024), lds, st, __VA_ARGS__);                         \
@@ -399,6 +441,7 @@ static dol_status allow_big_lds()
     DOL_HIP(allow_lds(damp_iterate_bwd_kernel<512, 2, 6>));
     DOL_HIP(allow_lds(damp_iterate_bwd_kernel<512, 4, 3>));
     DOL_HIP(allow_lds(damp_iterate_bwd_kernel<1024, 4, 3>));
+    DOL_HIP(allow_lds(damp_iterate_bwd_kernel<1024, 1, 6>));
     done[dev] = true;
     return DOL_OK;
 }
@@ -414,7 +457,7 @@ dol_status launch_iterate_fwd(const dol_dist *r0, const dol_dist *e, const dol_f
     A.r0 = r0->prob, A.ldr = r0->ld, A.e = e->prob, A.lde = e->ld;
     A.hist = hist, A.ckpt = ckpt, A.every = every > 0 ? every : rounds + 1, A.out = out, A.ldo = ldo;
     const dim3 grid(static_cast<unsigned>(r0->batch));
-    DOL_IT_DISPATCH(damp_iterate_fwd_kernel, f->na, lds, st, A);
+    DOL_IT_DISPATCH(damp_iterate_fwd_kernel, r0->batch, f->na, lds, st, A);
     DOL_HIP(hipGetLastError());
     return DOL_OK;
 }
@@ -436,7 +479,7 @@ dol_status launch_iterate_bwd(const dol_dist *e, const dol_fn_table *f, int32_t 
     A.e = e->prob, A.lde = e->ld, A.hist = hist, A.r0 = r0, A.ldr = ldr, A.ckpt = ckpt;
     A.gout = grad_out, A.ldg = ldg, A.grad_r0 = grad_r0, A.grad_e = grad_e, A.ldge = e->ld;
     const dim3 grid(static_cast<unsigned>(e->batch));
-    DOL_IT_DISPATCH(damp_iterate_bwd_kernel, f->na, lds, st, A);
+    DOL_IT_DISPATCH(damp_iterate_bwd_kernel, e->batch, f->na, lds, st, A);
     DOL_HIP(hipGetLastError());
     return DOL_OK;
 }

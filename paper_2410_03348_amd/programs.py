@@ -362,8 +362,10 @@ class GridReachFused(Program):
     the last round and a checkpoint every `ckpt_every` rounds leave the chip, the reverse sweep replays the rounds in
     between in LDS.  ckpt_every = 0: the full history goes through HBM instead (dol_iterate_apply2 / _backward)."""
 
-    def __init__(self, w, device="cuda", ckpt_every=8):
+    def __init__(self, w, device="cuda", ckpt_every=None):
         B, side = w["p"].shape[0], w["side"]
+        if ckpt_every is None:               # few samples: one workgroup per unit, longer stretches cost nothing;
+            ckpt_every = 16 if B <= 512 else 8   # many: 8 rounds of LDS leave room for two workgroups per unit
         self.batch, self.rounds, n = B, w["rounds"], side * side
         E = w["edge_u"].size
         self.E = E
