@@ -322,6 +322,18 @@ dol_status dol_iterate_backward_ckpt(const dol_dist *r0, const dol_dist *e, cons
                                      int32_t ckpt_every, const float *ckpt, const float *grad_out, int64_t grad_out_ld,
                                      float *grad_r0, float *grad_e, void *hip_stream);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops, harnesses that
+ * forbid it): the reverse sweep of dol_iterate_backward_ckpt without a workspace argument.  The call first replays the
+ * forward sweep from r0, keeping a checkpoint every 8 rounds in a 16 MiB device array built into the library (one copy
+ * per device, held until the process ends), then walks the rounds backwards from it; same kernels and same results,
+ * bit for bit, as dol_iterate_apply2_ckpt followed by dol_iterate_backward_ckpt with ckpt_every = 8.  It calls no
+ * allocating routine.  DOL_EUNSUPPORTED (outputs untouched) when (ceil(rounds / 8) - 1) * batch * na exceeds
+ * 4 194 304 floats.  Every call on a device uses that device's one array: calls that overlap on one device (two
+ * streams, two threads) race; calls on one stream are safe, each rewrites the checkpoints it reads. */
+dol_status dol_iterate_backward_noalloc(const dol_dist *r0, const dol_dist *e, const dol_fn_table *f, int32_t rounds,
+                                        const float *grad_out, int64_t grad_out_ld, float *grad_r0, float *grad_e,
+                                        void *hip_stream);
+
 /* Harness helper for loss = -log p[target] (Sec. 3.3 leaves the loss to the user): for every sample s,
  * grad[s, c] = -1 / max(d->prob[s, c], FLT_MIN) at c = target_col[s] and 0 elsewhere (all n_sym columns written).
  * target_col: device [batch] int32 column indices in 0..n_sym-1 (rows with an index outside get all zeros).

@@ -510,6 +510,20 @@ def iterate_backward_ckpt(r0: Dist, e: Dist, f: FnTable, rounds: int, ckpt_every
                                           _stream(stream)))
 
 
+_lib.dol_iterate_backward_noalloc.argtypes = [C.POINTER(_Dist), C.POINTER(_Dist), C.c_void_p, C.c_int32, C.c_void_p,
+                                              C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p]
+
+
+def iterate_backward_noalloc(r0: Dist, e: Dist, f: FnTable, rounds: int, grad_out: torch.Tensor,
+                             grad_r0: Optional[torch.Tensor], grad_e: Optional[torch.Tensor], stream=None):
+    """The reverse sweep with the library's built-in workspace: no allocation, forward sweep replayed inside."""
+    assert grad_out.dtype == torch.float32 and grad_out.stride(1) == 1
+    assert grad_r0 is None or grad_r0.is_contiguous()
+    _check(_lib.dol_iterate_backward_noalloc(r0.ref(), e.ref(), f._h, rounds, _dptr(grad_out),
+                                             max(int(grad_out.stride(0)), grad_out.shape[1]), _dptr(grad_r0),
+                                             _dptr(grad_e), _stream(stream)))
+
+
 def nll_grad(d: Dist, target_col: torch.Tensor, grad: torch.Tensor, stream=None):
     """target_col: int32 device tensor [batch]; grad rows have stride d.ld."""
     assert target_col.dtype == torch.int32 and target_col.is_contiguous()
