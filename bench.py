@@ -302,7 +302,7 @@ def near_ties(cfg, w):
 
 def build_program(GP, cfg, wl, chain):
     if chain == "fused":
-        fused = {2: GP.SumChainFused, 3: GP.HashedPipelineFused, 4: GP.DtkpSumChainFused, 5: GP.GridReachFused}
+        fused = {2: GP.SumChainFused, 3: GP.HashedPipelineMerged, 4: GP.DtkpSumChainFused, 5: GP.GridReachFused}
         if cfg in fused:
             return fused[cfg](wl)
     return GP.make_program(cfg, wl)
@@ -376,8 +376,8 @@ def main():
                          "auto = graph for steps of several launches, plain launches for a single-launch step (a graph "
                          "replay of one kernel only adds its own submission gap)")
     ap.add_argument("--chain", default="fused", choices=["fused", "per-op"],
-                    help="configs 2-5: the fused entry points (dol_fold_apply2, dol_filter_union, dol_dtkp_fold_apply2, dol_iterate_*), or one dol_apply2 / "
-                         "dol_backward call per operator")
+                    help="configs 2-5: the fused entry points (dol_fold_apply2, dol_apply2_filter_union, dol_dtkp_fold_apply2, "
+                         "dol_iterate_*_ckpt), or one dol_apply2 / dol_backward call per operator")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--regions", type=int, default=5, help="timed regions; the step time is their median")
     ap.add_argument("--min-region-ms", type=float, default=20.0, help="a region repeats its steps until it lasts this long")

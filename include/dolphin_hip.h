@@ -149,6 +149,37 @@ dol_status dol_filter_union_plan(const dol_dist *d, const uint8_t *pred_mask, co
 dol_status dol_filter_union(const dol_dist *d, const uint8_t *pred_mask, const dol_dist *c, const dol_prov *prov,
                             dol_dist *out, void *hip_stream);
 
+/* union(filter(apply2(a, b, f), pred_mask), c) in ONE launch under DAMP (one step of the recursion of App. B, Fig. 9:
+ * merged = union(paths, apply_if(...)), with a Filter in between as in Ex. 3.3): neither the Apply's result nor the
+ * filtered Distribution ever leaves the chip.  Same values, same clamp decisions as dol_apply2 followed by
+ * dol_filter_union (Eq. 1-3 with the fused multiply-add order of dol_apply2; the union's min(1, x + y) on one float add).
+ *   a, b, f     as for dol_apply2
+ *   pred_mask   host [dol_fn_table_n_out(f)], 1 = the produced symbol is kept
+ *   c           the Distribution the kept symbols are merged with
+ *   out         n_sym and sym_ids as dol_filter_union_plan gives for (a Distribution over f's symbols, pred_mask, c)
+ *   saved       device [batch] int32 or NULL: the forward call leaves 1 for a sample in which some clamp acted (a sum
+ *               of the Apply or of the union above 1) and 0 otherwise; the reverse call reads it and re-derives the
+ *               clamp decisions only for tiles of 64 samples that hold such a sample (with NULL: for every tile)
+ * dol_apply2_filter_union_backward: grad_out device [batch, grad_out_ld] w.r.t. out; grad_a, grad_b, grad_c device
+ * [batch, n_sym] of a, b, c, each overwritten, or added to where `accumulate` has bit 0, 1, 2 set; any may be NULL.
+ *   gh = grad_out gated by the union's clamp (symbols of both sides) -> grad_c, and, for the kept symbols of the
+ *   Apply, further by [pre <= 1] -> grad_a, grad_b as dol_backward defines them.
+ * Supported when the table has at most 64 x 64 symbols and produces at most 512, all symbol counts (a, b, f's result,
+ * c, out) are multiples of 4 and every tensor is contiguous (ld == n_sym) and 16-byte aligned; otherwise
+ * DOL_EUNSUPPORTED and the caller composes dol_apply2, dol_filter_union and dol_backward.  The first call with a table
+ * builds its code (synchronously, about a second); later calls are pure asynchronous launches. */
+typedef struct {
+    const dol_dist *a, *b;
+    const dol_fn_table *f;
+    const uint8_t *pred_mask;
+    const dol_dist *c;
+    dol_dist *out;
+    int32_t *saved;
+} dol_apply_merge;
+dol_status dol_apply2_filter_union(const dol_apply_merge *m, void *hip_stream);
+dol_status dol_apply2_filter_union_backward(const dol_apply_merge *m, const float *grad_out, int64_t grad_out_ld, float *grad_a,
+                                            float *grad_b, float *grad_c, int32_t accumulate, void *hip_stream);
+
 /* DTKP natural initialisation (App. A.1): symbol i of `d` gets the single proof {fact_of_sym[i]}.
  * fact_of_sym: host [d->n_sym].  Writes proof_mask, proof_prob and prob. */
 dol_status dol_dtkp_init(dol_dist *d, const int32_t *fact_of_sym, const dol_prov *prov, void *hip_stream);

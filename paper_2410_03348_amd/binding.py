@@ -231,10 +231,23 @@ class FnTable:
             self._h = None
 
     def __del__(self):
+        # The collector may run this at any moment, also while a stream is being captured into a HIP graph, where
+        # releasing device memory and code is not allowed: such handles wait for the next release outside a capture.
         try:
+            if self._h is None:
+                return
+            if torch.cuda.is_available() and torch.cuda.is_current_stream_capturing():
+                _deferred_tables.append(self._h)
+                self._h = None
+                return
             self.destroy()
+            while _deferred_tables:
+                _lib.dol_fn_table_destroy(_deferred_tables.pop())
         except Exception:
             pass
+
+
+_deferred_tables = []
 
 
 def apply2(a: Dist, b: Dist, f: FnTable, prov: Optional[Prov], out: Dist, stream=None):
@@ -339,6 +352,40 @@ def filter_union(d: Dist, pred_mask, c: Dist, prov: Optional[Prov], out: Dist, s
     pm = np.ascontiguousarray(pred_mask, dtype=np.uint8)
     _check(_lib.dol_filter_union(d.ref(), _ptr(pm, C.c_uint8), c.ref(), prov.ref() if prov else None, out.ref(),
                                  _stream(stream)))
+
+
+class _ApplyMerge(C.Structure):
+    _fields_ = [("a", C.POINTER(_Dist)), ("b", C.POINTER(_Dist)), ("f", C.c_void_p), ("pred_mask", _u8p),
+                ("c", C.POINTER(_Dist)), ("out", C.POINTER(_Dist)), ("saved", C.c_void_p)]
+
+
+_lib.dol_apply2_filter_union.argtypes = [C.POINTER(_ApplyMerge), C.c_void_p]
+_lib.dol_apply2_filter_union_backward.argtypes = [C.POINTER(_ApplyMerge), C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p,
+                                                  C.c_void_p, C.c_int32, C.c_void_p]
+
+
+class ApplyMerge:
+    """dol_apply_merge: union(filter(apply2(a, b, f), pred_mask), c) described once, for the forward and reverse calls."""
+
+    def __init__(self, a: Dist, b: Dist, f: FnTable, pred_mask, c: Dist, out: Dist, saved: Optional[torch.Tensor] = None):
+        self._keep = (a, b, f, c, out, saved)
+        self._pred = np.ascontiguousarray(pred_mask, dtype=np.uint8)
+        assert self._pred.shape == (f.n_out,)
+        assert saved is None or (saved.dtype == torch.int32 and saved.is_contiguous() and saved.shape == (a.batch,))
+        self.c = _ApplyMerge(C.pointer(a.c), C.pointer(b.c), f._h, _ptr(self._pred, C.c_uint8), C.pointer(c.c), C.pointer(out.c),
+                             C.c_void_p(saved.data_ptr()) if saved is not None else None)
+
+
+def apply2_filter_union(m: ApplyMerge, stream=None):
+    _check(_lib.dol_apply2_filter_union(C.byref(m.c), _stream(stream)))
+
+
+def apply2_filter_union_backward(m: ApplyMerge, grad_out: torch.Tensor, grad_a: Optional[torch.Tensor],
+                                 grad_b: Optional[torch.Tensor], grad_c: Optional[torch.Tensor], accumulate: int = 0,
+                                 stream=None):
+    assert grad_out.dtype == torch.float32 and grad_out.stride(1) == 1
+    _check(_lib.dol_apply2_filter_union_backward(C.byref(m.c), _dptr(grad_out), int(grad_out.stride(0)), _dptr(grad_a),
+                                                 _dptr(grad_b), _dptr(grad_c), accumulate, _stream(stream)))
 
 
 def dtkp_init(d: Dist, fact_of_sym, prov: Prov, stream=None):

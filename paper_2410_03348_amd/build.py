@@ -58,7 +58,7 @@ def build(verbose: bool = False, incremental: bool = False) -> str:
             if verbose and err.strip():
                 print(err, file=sys.stderr)
     objs = [os.path.join(OBJ, os.path.basename(s)[:-4] + ".o") for s in sources()]
-    rc, err = _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs)
+    rc, err = _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs + ["-L/opt/rocm/lib", "-lhiprtc"])
     if rc != 0:
         raise RuntimeError("linking libdolphin_hip.so failed:\n" + err)
     return LIB

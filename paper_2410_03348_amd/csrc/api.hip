@@ -188,6 +188,60 @@ dol_status dol_filter_union(const dol_dist *d, const uint8_t *pred_mask, const d
                                  static_cast<hipStream_t>(hip_stream));
 }
 
+// Checks of dol_apply2_filter_union and its reverse; leaves the merge plan in *plan.
+static dol_status check_apply_merge(const dol_apply_merge *m, const UnionPlan **plan)
+{
+    if (!m) return fail(DOL_EINVAL, "the description is NULL");
+    if (!m->f || !m->pred_mask) return fail(DOL_EINVAL, "f or pred_mask is NULL");
+    if (dol_status st = check_dist(m->a, "a", false, false, true)) return st;
+    if (dol_status st = check_dist(m->b, "b", false, false, true)) return st;
+    if (dol_status st = check_dist(m->c, "c", false, true, true)) return st;
+    if (dol_status st = check_dist(m->out, "out", false, false, true)) return st;
+    const dol_fn_table *f = m->f;
+    if (m->a->n_sym != f->na || m->b->n_sym != f->nb)
+        return fail(DOL_ESHAPE, "the table is %d x %d, its operands have %d and %d symbols", f->na, f->nb, m->a->n_sym, m->b->n_sym);
+    const int32_t batch = m->a->batch;
+    if (m->b->batch != batch || m->c->batch != batch || m->out->batch != batch) return fail(DOL_ESHAPE, "batch sizes differ");
+    if (dol_status st = get_filter_union_plan(f->n_out, f->out_syms.data(), m->pred_mask, m->c->n_sym, m->c->sym_ids, plan)) return st;
+    const UnionPlan *p = *plan;
+    if (p->n_out > DOL_MAX_SYMBOLS) return fail(DOL_EUNSUPPORTED, "the union has %d symbols, more than %d", p->n_out, DOL_MAX_SYMBOLS);
+    if (m->out->n_sym != p->n_out) return fail(DOL_ESHAPE, "out.n_sym = %d, the result has %d symbols", m->out->n_sym, p->n_out);
+    if (m->out->sym_ids)
+        for (int32_t u = 0; u < p->n_out; ++u)
+            if (m->out->sym_ids[u] != p->out_syms[u])
+                return fail(DOL_EINVAL, "out.sym_ids[%d] = %d, the result has %d there", u, m->out->sym_ids[u], p->out_syms[u]);
+    if (!table_merge_ok(f))
+        return fail(DOL_EUNSUPPORTED, "the one-launch form needs a table of at most 64 x 64 symbols producing at most 512, all counts multiples of 4");
+    auto flat = [](const dol_dist *d) { return d->ld == d->n_sym && !(d->n_sym & 3) && !(reinterpret_cast<uintptr_t>(d->prob) & 15u); };
+    if (!flat(m->a) || !flat(m->b) || !flat(m->c) || !flat(m->out) || m->c->n_sym < 4)
+        return fail(DOL_EUNSUPPORTED, "the one-launch form needs contiguous 16-byte aligned tensors with symbol counts that are multiples of 4");
+    return DOL_OK;
+}
+
+dol_status dol_apply2_filter_union(const dol_apply_merge *m, void *hip_stream)
+{
+    const UnionPlan *plan = nullptr;
+    if (dol_status st = check_apply_merge(m, &plan)) return st;
+    if (m->a->batch == 0) return DOL_OK;
+    return launch_damp_table_merge_fwd(m->f, plan, m->a->batch, m->a->prob, m->b->prob, m->c->prob, m->out->prob, m->saved,
+                                       static_cast<hipStream_t>(hip_stream));
+}
+
+dol_status dol_apply2_filter_union_backward(const dol_apply_merge *m, const float *grad_out, int64_t grad_out_ld, float *grad_a,
+                                            float *grad_b, float *grad_c, int32_t accumulate, void *hip_stream)
+{
+    const UnionPlan *plan = nullptr;
+    if (dol_status st = check_apply_merge(m, &plan)) return st;
+    if (m->a->batch == 0 || (!grad_a && !grad_b && !grad_c)) return DOL_OK;
+    if (!grad_out) return fail(DOL_EINVAL, "grad_out is NULL");
+    auto off16 = [](const void *ptr) { return (reinterpret_cast<uintptr_t>(ptr) & 15u) != 0; };
+    if (grad_out_ld != plan->n_out || off16(grad_out) || off16(grad_a) || off16(grad_b) || off16(grad_c))
+        return fail(DOL_EUNSUPPORTED, "the one-launch form needs contiguous 16-byte aligned gradient tensors");
+    if (grad_a && grad_a == grad_b) return fail(DOL_EINVAL, "grad_a and grad_b are the same tensor");
+    return launch_damp_table_merge_bwd(m->f, plan, m->a->batch, m->a->prob, m->b->prob, m->c->prob, grad_out, grad_a, grad_b, grad_c,
+                                       m->saved, accumulate, static_cast<hipStream_t>(hip_stream));
+}
+
 dol_status dol_dtkp_init(dol_dist *d, const int32_t *fact_of_sym, const dol_prov *prov, void *hip_stream)
 {
     if (!is_dtkp(prov)) return fail(DOL_EINVAL, "dol_dtkp_init needs a DTKP provenance");

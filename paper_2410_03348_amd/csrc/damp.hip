@@ -322,6 +322,8 @@ dol_status launch_damp_apply2_fwd(const dol_fn_table *f, int32_t batch, const fl
     if (batch == 0 || f->n_out == 0) return DOL_OK;
     if (conv_path_ok(f)) return launch_damp_conv_fwd(f, batch, a, lda, b, ldb, out, ldo, st);
     bool done = false;
+    if (dol_status s2 = launch_damp_table_fwd(f, batch, a, lda, b, ldb, out, ldo, st, &done)) return s2;
+    if (done) return DOL_OK;
     if (dol_status s2 = launch_damp_lds_fwd(f, batch, a, lda, b, ldb, out, ldo, st, &done)) return s2;
     if (done) return DOL_OK;
     const Rows R = rows_of(batch, f->n_out);
@@ -610,6 +612,8 @@ dol_status launch_damp_apply2_bwd(const dol_fn_table *f, int32_t batch, const fl
     if (batch == 0 || f->na + f->nb == 0 || (!ga && !gb)) return DOL_OK;
     if (conv_path_ok(f)) return launch_damp_conv_bwd(f, batch, a, lda, b, ldb, g, ldg, ga, gb, accumulate, st);
     bool done = false;
+    if (dol_status s2 = launch_damp_table_bwd(f, batch, a, lda, b, ldb, g, ldg, ga, gb, accumulate, st, &done)) return s2;
+    if (done) return DOL_OK;
     if (dol_status s2 = launch_damp_lds_bwd(f, batch, a, lda, b, ldb, out, ldo, g, ldg, ga, gb, accumulate, st, &done)) return s2;
     if (done) return DOL_OK;
     const BwdTable T{f->col_ptr.ptr, f->col_ij.ptr, f->rowa_ptr.ptr, f->rowa_jc.ptr, f->rowb_ptr.ptr, f->rowb_ic.ptr,

@@ -53,6 +53,7 @@ bool conv_path_ok(const dol_fn_table *f)
 std::string damp_kernel_name(const dol_fn_table *f, bool backward)
 {
     if (!conv_path_ok(f)) {
+        if (table_code_ok(f)) return backward ? "damp_table_bwd_kernel" : "damp_table_fwd_kernel";
         if (backward) return f->lds_bwd_ok ? "damp_lds_bwd_kernel" : !f->byj_ok ? "damp_apply2_bwd_kernel" : f->na + f->nb > 1024 ? "damp_byj_bwd_row_kernel" : "damp_byj_bwd_kernel";
         return f->lds_fwd_ok ? "damp_lds_fwd_kernel" : f->byj_fwd ? (byj_fwd_staged_ok(f) ? "damp_byj_fwd_staged_kernel" : "damp_byj_fwd_kernel") :
                staged_fwd_ok(f) ? "damp_apply2_fwd_staged_kernel" : "damp_apply2_fwd_kernel";

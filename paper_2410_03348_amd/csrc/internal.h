@@ -6,6 +6,7 @@
 #include <cstdarg>
 #include <cstdint>
 #include <cstdio>
+#include <memory>
 #include <string>
 #include <algorithm>
 #include <numeric>
@@ -71,6 +72,12 @@ constexpr int kByJMax = 16;         // tables whose second operand has at most t
 constexpr int kByJMaxNa = 65000;    // ... and whose first operand leaves room for the three marks below
 constexpr uint16_t kByJNone = 0xFFFF, kByJWave = 0xFFFE, kByJList = 0xFFFD;
 
+// Code compiled for one function table on its first use (damp_table.hip)
+struct JitState;
+struct JitDeleter {
+    void operator()(JitState *p) const;
+};
+
 // A tuple of the function table packed for the kernels: low 16 bits = first index, high 16 = second.
 __host__ __device__ static inline uint32_t pack16(uint32_t lo, uint32_t hi) { return lo | (hi << 16); }
 
@@ -131,6 +138,8 @@ struct dol_fn_table {
     bool byj_fwd = false;              // forward uses the map only where it is at least half full (else the tuple lists)
     dol::DevArray<uint16_t> byj_src, byj_col;
     dol::DevArray<uint32_t> byj_wave_cols;
+    // tables whose operand rows fit in registers: straight-line kernels written for the table (built on first use)
+    mutable std::unique_ptr<dol::JitState, dol::JitDeleter> jit;
     int device = 0;
 };
 
@@ -224,6 +233,21 @@ dol_status launch_damp_lds_fwd(const dol_fn_table *f, int32_t batch, const float
 dol_status launch_damp_lds_bwd(const dol_fn_table *f, int32_t batch, const float *a, int64_t lda, const float *b,
                                int64_t ldb, const float *out, int64_t ldo, const float *g, int64_t ldg, float *ga,
                                float *gb, int32_t accumulate, hipStream_t st, bool *done);
+// Small arbitrary tables as code written for the table (damp_table.hip); *done = false: the call was not taken
+bool table_code_ok(const dol_fn_table *f);
+dol_status launch_damp_table_fwd(const dol_fn_table *f, int32_t batch, const float *a, int64_t lda, const float *b,
+                                 int64_t ldb, float *out, int64_t ldo, hipStream_t st, bool *done);
+dol_status launch_damp_table_bwd(const dol_fn_table *f, int32_t batch, const float *a, int64_t lda, const float *b,
+                                 int64_t ldb, const float *g, int64_t ldg, float *ga, float *gb, int32_t accumulate,
+                                 hipStream_t st, bool *done);
+// out = union(filter(apply2(a, b, f)), c) and its reverse in one launch each; p = the filter-union plan over f's symbols
+// and c's.  Contiguous 16-byte aligned tensors only (the callers check).
+bool table_merge_ok(const dol_fn_table *f);
+dol_status launch_damp_table_merge_fwd(const dol_fn_table *f, const UnionPlan *p, int32_t batch, const float *a, const float *b,
+                                       const float *c, float *out, int32_t *saved, hipStream_t st);
+dol_status launch_damp_table_merge_bwd(const dol_fn_table *f, const UnionPlan *p, int32_t batch, const float *a, const float *b,
+                                       const float *c, const float *g, float *ga, float *gb, float *gc, const int32_t *saved,
+                                       int32_t accumulate, hipStream_t st);
 // Filter / Union on contiguous 16-byte aligned tensors (damp_rows.hip); *done = false: not taken
 dol_status launch_rows_gather(int32_t batch, int32_t n_in, int32_t n_out, const int32_t *src_col, const float *in,
                               int64_t ldi, float *out, int64_t ldo, int32_t accumulate, hipStream_t st, bool *done);

@@ -209,10 +209,10 @@ static dol_status build_table(int32_t na, int32_t nb, std::vector<Tuple> &tup, d
         tb->byj_ok = true;
         tb->byj_fwd = 2 * tup.size() >= static_cast<size_t>(nb) * static_cast<size_t>(S);
     }
-    tb->kernel_fwd = damp_kernel_name(tb.get(), false);
-    tb->kernel_bwd = damp_kernel_name(tb.get(), true);
     tb->h_col_ptr.swap(col_ptr);
     tb->h_col_ij.swap(col_ij);
+    tb->kernel_fwd = damp_kernel_name(tb.get(), false);
+    tb->kernel_bwd = damp_kernel_name(tb.get(), true);
     *out = tb.release();
     return DOL_OK;
 }

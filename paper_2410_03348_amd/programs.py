@@ -252,6 +252,40 @@ class HashedPipelineFused(HashedPipeline):
         ]
 
 
+class HashedPipelineMerged(Program):
+    """Config 3 through dol_apply2_filter_union: Apply, Filter and Union in one launch, their reverse in another;
+    only the program's inputs and results touch HBM (plus one word per sample that says whether a clamp acted)."""
+
+    def __init__(self, w, device="cuda"):
+        B = w["pa"].shape[0]
+        self.batch = B
+        self.table = dol.FnTable.create_dense(w["table"])
+        n_tup = _n_tuples(w["table"])
+        self.a = dol.Dist(np.arange(w["na"]), _dev(w["pa"], device))
+        self.b = dol.Dist(np.arange(w["nb"]), _dev(w["pb"], device))
+        self.pred = np.ascontiguousarray(w["keep"][self.table.out_syms], np.uint8)   # predicate on the symbols present
+        self.p2 = dol.Dist(np.arange(w["n_out"]), _dev(w["p2"], device))
+        o1 = dol.Dist(self.table.out_syms, None, batch=B)                             # symbols only: never materialised
+        self.o3 = dol.Dist.empty(dol.filter_union_plan(o1, self.pred, self.p2), B, device)
+        self.g3 = _dev(w["g"][:, :self.o3.n_sym], device)
+        self.gp2 = torch.empty((B, self.p2.n_sym), dtype=torch.float32, device=device)
+        self.ga = torch.empty((B, self.a.n_sym), dtype=torch.float32, device=device)
+        self.gb = torch.empty((B, self.b.n_sym), dtype=torch.float32, device=device)
+        self.saved = torch.empty((B,), dtype=torch.int32, device=device)
+        self.merge = dol.ApplyMerge(self.a, self.b, self.table, self.pred, self.p2, self.o3, self.saved)
+        na, nb, np2, n3 = self.a.n_sym, self.b.n_sym, self.p2.n_sym, self.o3.n_sym
+        self.launches = [
+            Launch("damp_table_merge_fwd_kernel", lambda: dol.apply2_filter_union(self.merge),
+                   4 * B * (na + nb + np2 + n3), B * n_tup, "fwd"),
+            Launch("damp_table_merge_bwd_kernel",
+                   lambda: dol.apply2_filter_union_backward(self.merge, self.g3, self.ga, self.gb, self.gp2),
+                   4 * B * (n3 + 2 * (na + nb) + np2), 2 * B * n_tup, "bwd"),
+        ]
+        self.sample_ops = 6 * B
+        self.min_bytes = 4 * B * (2 * (na + nb + np2) + 2 * n3)
+        self.flops = 2 * 3 * B * n_tup
+
+
 class DtkpSumChain(Program):
     """Config 4: the sum fold under DTKP-AM with k proofs per tag; fact 10*n+d says "digit n is d"."""
 

@@ -184,6 +184,63 @@ def test_config3_fused_filter_union(gp, batch, na, nb, n_out):
     np.testing.assert_array_equal(host(prog.gp2), host(per_op.gp2))
 
 
+@pytest.mark.parametrize("batch,na,nb,n_out,scale", [(16384, 64, 64, 256, 1.0), (1000, 64, 64, 256, 1.0), (333, 64, 64, 256, 12.0),
+                                                      (65, 32, 16, 64, 9.0), (1, 16, 16, 8, 1.0), (200, 64, 64, 128, 30.0),
+                                                      (130, 4, 64, 8, 3.0)])
+def test_config3_apply_filter_union_in_one_launch(gp, dol, batch, na, nb, n_out, scale):
+    """dol_apply2_filter_union and its reverse: the results of dol_apply2 + dol_filter_union + two dol_backward calls
+    (bit for bit) and of the oracle.  scale > 1 multiplies the tags (capped at 1) so that sums of the Apply and of the
+    union land on both sides of the clamp: those tiles re-derive every decision."""
+    w = W.config3(batch=batch, na=na, nb=nb, n_out=n_out, seed=11)
+    if scale != 1.0:
+        for key in ("pa", "pb", "p2"):
+            w.arrays[key] = np.minimum(w[key] * np.float32(scale), np.float32(1.0))
+        w.arrays["g"] = np.abs(w["g"])         # one-signed upstream gradient: see the tolerance note in the module docstring
+    ref = OP.hashed_pipeline_fwd_bwd(w)
+    prog = gp.HashedPipelineMerged(w)
+    prog.step()
+    np.testing.assert_array_equal(prog.o3.sym_ids, ref["s3"])
+    assert_close(host(prog.o3.prob), ref["o3"], "apply-filter-union")
+    np.testing.assert_array_equal(host(prog.o3.prob) == 1.0, ref["o3"] == 1.0)
+    assert_close(host(prog.gp2), ref["gp2"], "apply-filter-union grad c")
+    assert_close(host(prog.ga), ref["ga"], "apply-filter-union grad a")
+    assert_close(host(prog.gb), ref["gb"], "apply-filter-union grad b")
+    # some clamp acted in a sample <=> the saved word says so
+    both = np.isin(ref["s3"], ref["s2"])
+    o2_in_3 = np.zeros_like(ref["o3"], dtype=np.float32)
+    o2_in_3[:, both] = ref["o2"]
+    pre32 = oracle.damp_apply2_fwd(oracle.dense_to_triples(w["table"]), na, nb, w["pa"], w["pb"], want_pre=True)[2]
+    acted = (pre32 > 1.0).any(axis=1) | (((o2_in_3 + w["p2"].astype(np.float32)) > np.float32(1.0)) & both[None, :]).any(axis=1)
+    np.testing.assert_array_equal(host(prog.saved) != 0, acted)
+    per_op = gp.HashedPipelineFused(w)
+    per_op.step()
+    np.testing.assert_array_equal(host(prog.o3.prob), host(per_op.o3.prob))
+    np.testing.assert_array_equal(host(prog.gp2), host(per_op.gp2))
+    assert_close(host(prog.ga), host(per_op.ga).astype(np.float64), "one launch against three: grad a")
+    assert_close(host(prog.gb), host(per_op.gb).astype(np.float64), "one launch against three: grad b")
+    # without the saved words every tile re-derives its decisions: same results; accumulate adds
+    m2 = dol.ApplyMerge(prog.a, prog.b, prog.table, prog.pred, prog.p2, prog.o3, None)
+    ga, gb, gc = prog.ga.clone(), prog.gb.clone(), prog.gp2.clone()
+    dol.apply2_filter_union_backward(m2, prog.g3, ga, gb, gc, accumulate=7)
+    assert_close(host(ga), 2.0 * host(prog.ga).astype(np.float64), "accumulated grad a")
+    assert_close(host(gb), 2.0 * host(prog.gb).astype(np.float64), "accumulated grad b")
+    assert_close(host(gc), 2.0 * host(prog.gp2).astype(np.float64), "accumulated grad c")
+    dol.apply2_filter_union_backward(m2, prog.g3, None, gb, None)
+    np.testing.assert_array_equal(host(gb), host(prog.gb))
+
+
+def test_apply_filter_union_rejects_what_it_cannot_take(dol):
+    w = W.config3(batch=8, na=17, nb=33, n_out=40, seed=3)                     # symbol counts that are not multiples of 4
+    f = dol.FnTable.create_dense(w["table"])
+    a, b = dol.Dist(np.arange(17), dev(w["pa"])), dol.Dist(np.arange(33), dev(w["pb"]))
+    c = dol.Dist(np.arange(40), dev(w["p2"]))
+    pred = np.ones(f.n_out, np.uint8)
+    out = dol.Dist.empty(dol.filter_union_plan(dol.Dist(f.out_syms, None, batch=8), pred, c), 8)
+    with pytest.raises(dol.DolError) as ei:
+        dol.apply2_filter_union(dol.ApplyMerge(a, b, f, pred, c, out))
+    assert ei.value.status == 5
+
+
 def test_filter_union_edge_cases(dol):
     """Everything dropped, nothing dropped, disjoint and empty second operand, padded rows, clamped sums, accumulate."""
     B = 37
@@ -583,8 +640,9 @@ def test_hashed_tables_in_lds_with_clamping(dol, na, nb, n_out, B, scale):
     tri = oracle.dense_to_triples(tab)
     syms, want, pre32, _ = oracle.damp_apply2_fwd(tri, na, nb, a, b, want_pre=True)
     f = dol.FnTable.create_dense(tab)
-    if syms.size % 4 == 0:
-        assert f.kernel_fwd == "damp_lds_fwd_kernel" and f.kernel_bwd == "damp_lds_bwd_kernel"
+    if syms.size % 4 == 0:                 # operand rows that fit in registers: code written for the table; else LDS gathers
+        kind = "table" if max(na, nb) <= 64 else "lds"
+        assert f.kernel_fwd == "damp_%s_fwd_kernel" % kind and f.kernel_bwd == "damp_%s_bwd_kernel" % kind
     da, db = dol.Dist(np.arange(na), dev(a)), dol.Dist(np.arange(nb), dev(b))
     do = dol.Dist.empty(syms, B)
     dol.apply2(da, db, f, None, do)
