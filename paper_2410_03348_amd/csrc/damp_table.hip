@@ -449,8 +449,14 @@ std::string backward_source(const dol_fn_table *f, bool merged)
     return o.s;
 }
 
-dol_status compile(const std::string &src, const char *name, hipModule_t *mod, hipFunction_t *fn)
+}  // namespace
+
+dol_status jit_compile(const std::string &src, const char *name, hipModule_t *mod, hipFunction_t *fn)
 {
+    if (const char *dump = getenv("DOL_DUMP_TABLE_SRC")) {
+        const std::string path = std::string(dump) + "/" + name + ".hip";
+        if (FILE *fh = fopen(path.c_str(), "w")) { fputs(src.c_str(), fh); fclose(fh); }
+    }
     hiprtcProgram prog = nullptr;
     if (hiprtcCreateProgram(&prog, src.c_str(), "dol_table.hip", 0, nullptr, nullptr) != HIPRTC_SUCCESS)
         return fail(DOL_EHIP, "hiprtcCreateProgram failed");
@@ -481,6 +487,8 @@ dol_status compile(const std::string &src, const char *name, hipModule_t *mod, h
     return DOL_OK;
 }
 
+namespace {
+
 unsigned tile_grid(int n_tiles) { return static_cast<unsigned>(n_tiles); }
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -506,7 +514,7 @@ static dol_status kernel_of(const dol_fn_table *f, int slot, hipFunction_t *fn)
         js->tried[slot] = true;
         const std::string src = slot == kSlotFwd ? forward_source(f, false) : slot == kSlotBwd ? backward_source(f, false) :
                                 slot == kSlotMergeFwd ? forward_source(f, true) : backward_source(f, true);
-        js->status[slot] = compile(src, names[slot], &js->mod[slot], &js->fn[slot]);
+        js->status[slot] = jit_compile(src, names[slot], &js->mod[slot], &js->fn[slot]);
         if (js->status[slot] != DOL_OK) return js->status[slot];      // with the compiler's message
     } else if (js->status[slot] != DOL_OK) {
         return fail(js->status[slot], "the code of this function table did not build (see the first call's message)");

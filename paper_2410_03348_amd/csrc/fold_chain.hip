@@ -1,0 +1,301 @@
+// The fused left fold of convolution-shaped DAMP applies (the loop of Fig. 2, forward + loss gradient + reverse sweep
+// in one launch) as code written for the chain's shape.
+//
+// The symbol side of a fold is known before any tag is touched (Sec. 3.1.2): the number of inputs and the symbol
+// counts of every stage.  With those as compile-time constants the whole sweep unrolls: 16 lanes own a sample, a
+// wavefront four, and in every stage a lane owns a CONTIGUOUS block of output columns (rows, in the reverse sweep)
+// sized to the stage, so that
+//   - the operand window of a block slides through registers: w + nb - 1 LDS reads feed w * nb multiply-adds;
+//   - no lane idles in a narrow stage and no stage pays for a fixed four-column granularity;
+//   - every LDS offset is an immediate, every loop is gone.
+// Everything a sample needs lives in its LDS region: the running Distributions acc_0 .. acc_{n-1} (operands of the
+// reverse sweep), the short inputs and two gradient rows.  A stage's result is kept as x = pre where pre <= 1 and -1
+// where the clamp acted: |x| is the tag (the absolute value is free in a multiply-add) and the sign is the clamp's
+// decision, read by the reverse sweep with the operand it needs anyway - no stage is ever summed twice.
+//
+// Arithmetic is that of dol_apply2 / dol_backward: out[c] = min(1, sum over ascending i of a[i] * b[c - i]), one
+// fused multiply-add per tuple from 0; gradients gated by [pre <= 1].
+#include "internal.h"
+
+#include <cstdarg>
+#include <map>
+#include <mutex>
+
+namespace dol {
+
+namespace {
+
+constexpr int kL = 16;                  // lanes per sample
+constexpr int kSP = 64 / kL;            // samples per wavefront
+constexpr int kNBR = 16;                // floats reserved per short input row
+constexpr size_t kChainLdsMax = 40 * 1024;   // per wavefront: at least four wavefronts per compute unit
+
+struct Src {
+    std::string s;
+    void operator()(const char *fmt, ...) __attribute__((format(printf, 2, 3)))
+    {
+        char buf[1024];
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(buf, sizeof buf, fmt, ap);
+        va_end(ap);
+        s += buf;
+    }
+};
+
+struct Layout {
+    int n = 0;
+    int m[kFoldChainMax] = {}, nb[kFoldChainMax] = {};
+    int w[kFoldChainMax] = {};          // columns of acc_t per lane (t >= 1)
+    int off[kFoldChainMax] = {};        // first value of acc_t inside a sample's region
+    int ext[kFoldChainMax] = {};        // entries of acc_t's row that are read (values, then zeros)
+    int off_d = 0, off_g0 = 0, off_g1 = 0, g_len = 0, stride = 0;
+};
+
+int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+Layout lay_out(const std::vector<int> &shape)
+{
+    Layout Y;
+    Y.n = shape[0];
+    Y.m[0] = shape[1];
+    for (int t = 1; t < Y.n; ++t) {
+        Y.nb[t] = shape[1 + t];
+        Y.m[t] = Y.m[t - 1] + Y.nb[t] - 1;
+        Y.w[t] = ceil_div(Y.m[t], kL);
+    }
+    int pos = 0;
+    for (int t = 0; t < Y.n; ++t) {
+        const int halo = t + 1 < Y.n ? Y.nb[t + 1] - 1 : 0;       // the next stage reads nb - 1 entries before the row
+        int ext = std::max(Y.m[t], t >= 1 ? kL * Y.w[t] : 0);    // a stage writes whole blocks
+        if (t + 1 < Y.n) ext = std::max(ext, kL * Y.w[t + 1]);   // and the next one reads whole blocks
+        Y.off[t] = pos + halo;
+        Y.ext[t] = ext;
+        pos = Y.off[t] + ext;
+    }
+    Y.off_d = pos;
+    pos += Y.n * kNBR;
+    int g_len = Y.m[Y.n - 1];
+    for (int t = 1; t < Y.n; ++t) g_len = std::max(g_len, kL * ceil_div(Y.m[t - 1], kL) + Y.nb[t] - 1);
+    Y.g_len = g_len;
+    Y.off_g0 = pos;
+    Y.off_g1 = pos + g_len;
+    pos += 2 * g_len;
+    Y.stride = pos | 1;                 // odd: the samples of a wavefront start in different banks
+    return Y;
+}
+
+// lanes 0 .. len-1 of every sample (in turns of 16) write zero to region[start ..]
+void emit_zero(Src &o, int start, int len)
+{
+    for (int x = 0; x < len; x += kL) {
+        if (len - x >= kL) o("  base[%d + l] = 0.0f;\n", start + x);
+        else o("  if (l < %d) base[%d + l] = 0.0f;\n", len - x, start + x);
+    }
+}
+
+std::string chain_source(const std::vector<int> &shape)
+{
+    const Layout Y = lay_out(shape);
+    const int n = Y.n, n1 = n - 1;
+    Src o;
+    o("typedef unsigned long long u64;\n");
+    o("struct Args { int batch; int backward; const float *in[%d]; long long ld[%d]; float *gin[%d]; float *out; long long ldo; "
+      "const int *target; const float *gout; long long ldg; };\n", kFoldChainMax, kFoldChainMax, kFoldChainMax);
+    o("__device__ __forceinline__ void fence() { __builtin_amdgcn_fence(__ATOMIC_RELEASE, \"wavefront\"); __builtin_amdgcn_wave_barrier(); "
+      "__builtin_amdgcn_fence(__ATOMIC_ACQUIRE, \"wavefront\"); }\n");
+    o("__device__ __forceinline__ float dppx(float x, int which) {\n"
+      "  switch (which) {\n"
+      "  case 0: return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0xB1, 0xF, 0xF, false));\n"
+      "  case 1: return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x4E, 0xF, 0xF, false));\n"
+      "  case 2: return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x141, 0xF, 0xF, false));\n"
+      "  default: return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x140, 0xF, 0xF, false)); } }\n");
+    o("__device__ __forceinline__ float sum16(float x) { x += dppx(x, 0); x += dppx(x, 1); x += dppx(x, 2); x += dppx(x, 3); return x; }\n");
+    o("extern \"C\" __global__ void __launch_bounds__(64) damp_fold_chain_kernel(const Args A)\n{\n");
+    o("  __shared__ float lds[%d];\n", kSP * Y.stride);
+    o("  const int lane = threadIdx.x, l = lane & %d, q = lane >> %d;\n", kL - 1, kL == 16 ? 4 : 3);
+    // workgroups are dealt round-robin to the 8 XCDs: give every XCD a contiguous range of samples
+    o("  const unsigned id = blockIdx.x, nwg = gridDim.x, xcd = id & 7u, per = nwg >> 3, rem = nwg & 7u;\n");
+    o("  const long long wg = (long long)(xcd * per + (xcd < rem ? xcd : rem) + (id >> 3));\n");
+    o("  const long long s_raw = wg * %d + q;\n  const bool live = s_raw < A.batch;\n  const long long s = live ? s_raw : A.batch - 1;\n", kSP);
+    o("  float *base = lds + q * %d;\n", Y.stride);
+    // ---- zeros where a window may reach beyond what is written
+    {
+        int pos = 0;
+        for (int t = 0; t < n; ++t) {
+            emit_zero(o, pos, Y.off[t] - pos);                       // the halo in front of the row
+            if (t == 0) emit_zero(o, Y.off[0] + Y.m[0], Y.ext[0] - Y.m[0]);
+            else if (Y.ext[t] > kL * Y.w[t]) emit_zero(o, Y.off[t] + kL * Y.w[t], Y.ext[t] - kL * Y.w[t]);
+            pos = Y.off[t] + Y.ext[t];
+        }
+    }
+    // ---- inputs: all loads first, then the LDS writes
+    {
+        int slot = 0;
+        for (int t = 0; t < n; ++t) {
+            const int cnt = t == 0 ? Y.m[0] : Y.nb[t];
+            for (int x = 0; x < kSP * cnt; x += 64, ++slot) {
+                o("  float in%d = 0.0f; { const int e = lane + %d; if (e < %d) { const int qq = e / %d, i = e - qq * %d; long long ss = wg * %d + qq; "
+                  "ss = ss < A.batch ? ss : A.batch - 1; in%d = A.in[%d][ss * A.ld[%d] + i]; } }\n", slot, x, kSP * cnt, cnt, cnt, kSP, slot, t, t);
+            }
+        }
+        slot = 0;
+        for (int t = 0; t < n; ++t) {
+            const int cnt = t == 0 ? Y.m[0] : Y.nb[t];
+            const int dst = t == 0 ? Y.off[0] : Y.off_d + t * kNBR;
+            for (int x = 0; x < kSP * cnt; x += 64, ++slot)
+                o("  { const int e = lane + %d; if (e < %d) { const int qq = e / %d, i = e - qq * %d; lds[qq * %d + %d + i] = in%d; } }\n", x, kSP * cnt,
+                  cnt, cnt, Y.stride, dst, slot);
+        }
+    }
+    o("  fence();\n");
+    // ---- forward sweep
+    for (int t = 1; t < n; ++t) {
+        const int nb = Y.nb[t], w = Y.w[t], win = w + nb - 1;
+        o("  {\n    const float *rp = base + %d + l * %d;\n", Y.off[t - 1] - (nb - 1), w);
+        for (int j = 0; j < nb; ++j) o("    const float d%d = base[%d];\n", j, Y.off_d + t * kNBR + j);
+        for (int k = 0; k < win; ++k) o("    const float r%d = __builtin_fabsf(rp[%d]);\n", k, k);
+        for (int k = 0; k < w; ++k) {
+            // column c = l * w + k: ascending i = c - j, one fma per tuple
+            o("    float p%d = 0.0f;\n", k);
+            for (int j = nb - 1; j >= 0; --j) o("    p%d = __builtin_fmaf(r%d, d%d, p%d);\n", k, k + (nb - 1) - j, j, k);
+        }
+        o("    float *wp = base + %d + l * %d;\n", Y.off[t], w);
+        for (int k = 0; k < w; ++k) o("    wp[%d] = p%d <= 1.0f ? p%d : -1.0f;\n", k, k, k);
+        o("  }\n  fence();\n");
+    }
+    // ---- the result
+    o("  if (A.out && live) { float *os = A.out + s * A.ldo;\n");
+    for (int x = 0; x < Y.m[n1]; x += kL)
+        o("    %s os[%d + l] = __builtin_fabsf(base[%d + l]);\n", Y.m[n1] - x >= kL ? "" : (std::string("if (l < ") + std::to_string(Y.m[n1] - x) + ")").c_str(),
+          x, Y.off[n1] + x);
+    o("  }\n  if (!A.backward) return;\n");
+    // ---- upstream gradient into the first gradient row, gated by the last stage's clamp
+    o("  { const int tgt = A.target ? A.target[s] : -1; const float *gs = A.gout + s * A.ldg;\n");
+    for (int x = 0; x < Y.g_len; x += kL) {
+        const bool whole = Y.g_len - x >= kL;
+        o("    %s{ const int c = %d + l; float gv = 0.0f;\n", whole ? "" : (std::string("if (l < ") + std::to_string(Y.g_len - x) + ") ").c_str(), x);
+        if (x < Y.m[n1]) {
+            o("      if (c < %d) { const float xv = base[%d + c];\n", Y.m[n1], Y.off[n1]);
+            o("        if (A.target) gv = c == tgt ? -1.0f / fmaxf(__builtin_fabsf(xv), 1.17549435e-38f) : 0.0f; else gv = gs[c];\n");
+            o("        if (xv < 0.0f) gv = 0.0f; }\n");
+        }
+        o("      base[%d + c] = gv; }\n", Y.off_g0);
+    }
+    o("  }\n  fence();\n");
+    // ---- reverse sweep
+    for (int t = n1; t >= 1; --t) {
+        const int nb = Y.nb[t], m = Y.m[t - 1], v = ceil_div(m, kL), win = v + nb - 1;
+        const int g_cur = (n1 - t) & 1 ? Y.off_g1 : Y.off_g0, g_nxt = (n1 - t) & 1 ? Y.off_g0 : Y.off_g1;
+        o("  {\n    const float *gp = base + %d + l * %d, *ap = base + %d + l * %d;\n", g_cur, v, Y.off[t - 1], v);
+        for (int j = 0; j < nb; ++j) o("    const float d%d = base[%d];\n", j, Y.off_d + t * kNBR + j);
+        for (int k = 0; k < win; ++k) o("    const float g%d = gp[%d];\n", k, k);
+        for (int k = 0; k < v; ++k) o("    const float x%d = ap[%d];\n", k, k);
+        for (int j = 0; j < nb; ++j) o("    float s%d = 0.0f;\n", j);
+        o("    float *wp = base + %d + l * %d;\n", g_nxt, v);
+        for (int k = 0; k < v; ++k) {
+            o("    { float acc = 0.0f;\n");
+            for (int j = 0; j < nb; ++j) o("      acc = __builtin_fmaf(g%d, d%d, acc);\n", k + j, j);
+            // rows past the operand's last symbol hold 0; a row whose own sum was clamped (sign) passes no gradient on
+            if (t > 1) o("      wp[%d] = (l * %d + %d < %d && !(x%d < 0.0f)) ? acc : 0.0f;\n", k, v, k, m, k);
+            else o("      wp[%d] = l * %d + %d < %d ? acc : 0.0f;\n", k, v, k, m);
+            for (int j = 0; j < nb; ++j) o("      s%d = __builtin_fmaf(g%d, __builtin_fabsf(x%d), s%d);\n", j, k + j, k, j);
+            o("    }\n");
+        }
+        // the next stage's windows reach past the rows just written: zeros there
+        if (t > 1) {
+            const int need = kL * ceil_div(Y.m[t - 2], kL) + Y.nb[t - 1] - 1, have = kL * v;
+            for (int x = have; x < need; x += kL)
+                o("    %s base[%d + l] = 0.0f;\n", need - x >= kL ? "" : (std::string("if (l < ") + std::to_string(need - x) + ")").c_str(), g_nxt + x);
+        }
+        // the short operand's gradient: sum of the lanes' shares; it takes the place of the operand's row, which is spent
+        for (int j = 0; j < nb; ++j) o("    s%d = sum16(s%d);\n", j, j);
+        o("    if (l == 0) {\n");
+        for (int j = 0; j < nb; ++j) o("      base[%d] = s%d;\n", Y.off_d + t * kNBR + j, j);
+        o("    }\n  }\n  fence();\n");
+    }
+    // ---- gradients out
+    o("  if (!live) return;\n");
+    {
+        const int g_fin = (n1 & 1) ? Y.off_g1 : Y.off_g0;        // after n - 1 swaps
+        o("  if (A.gin[0]) { float *dst = A.gin[0] + s * A.ld[0];\n");
+        for (int x = 0; x < Y.m[0]; x += kL)
+            o("    %s dst[%d + l] = base[%d + l];\n", Y.m[0] - x >= kL ? "" : (std::string("if (l < ") + std::to_string(Y.m[0] - x) + ")").c_str(), x,
+              g_fin + x);
+        o("  }\n");
+        for (int t = 1; t < n; ++t)
+            o("  if (A.gin[%d] && l < %d) A.gin[%d][s * A.ld[%d] + l] = base[%d + l];\n", t, Y.nb[t], t, t, Y.off_d + t * kNBR);
+    }
+    o("}\n");
+    return o.s;
+}
+
+struct ChainKernel {
+    hipModule_t mod = nullptr;
+    hipFunction_t fn = nullptr;
+    dol_status status = DOL_OK;
+};
+
+struct ChainArgs {
+    int32_t batch, backward;
+    const float *in[kFoldChainMax];
+    int64_t ld[kFoldChainMax];
+    float *gin[kFoldChainMax];
+    float *out;
+    int64_t ldo;
+    const int32_t *target;
+    const float *gout;
+    int64_t ldg;
+};
+
+}  // namespace
+
+bool fold_chain_ok(int n, const int32_t *m, const int32_t *nb)
+{
+    if (n < 2 || n > kFoldChainMax) return false;
+    std::vector<int> shape{n, m[0]};
+    for (int t = 1; t < n; ++t) {
+        if (nb[t] < 1 || nb[t] > kNBR) return false;
+        shape.push_back(nb[t]);
+    }
+    if (m[0] < 1 || m[0] > 256) return false;
+    const Layout Y = lay_out(shape);
+    return sizeof(float) * kSP * static_cast<size_t>(Y.stride) <= kChainLdsMax;
+}
+
+dol_status launch_fold_chain(int n, const int32_t *m, const int32_t *nb, int32_t batch, const float *const *in, const int64_t *ld,
+                             float *const *gin, float *out, int64_t ldo, const int32_t *target, const float *gout, int64_t ldg,
+                             int32_t backward, hipStream_t st)
+{
+    static std::mutex mu;
+    static std::map<std::pair<int, std::vector<int>>, ChainKernel> cache;    // per device and shape; lives until the process ends
+    std::vector<int> shape{n, m[0]};
+    for (int t = 1; t < n; ++t) shape.push_back(nb[t]);
+    int dev = 0;
+    DOL_HIP(hipGetDevice(&dev));
+    hipFunction_t fn = nullptr;
+    {
+        std::lock_guard<std::mutex> lock(mu);
+        auto key = std::make_pair(dev, shape);
+        auto it = cache.find(key);
+        if (it == cache.end()) {
+            ChainKernel k;
+            k.status = jit_compile(chain_source(shape), "damp_fold_chain_kernel", &k.mod, &k.fn);
+            it = cache.emplace(key, k).first;
+            if (k.status != DOL_OK) return k.status;                        // with the compiler's message
+        } else if (it->second.status != DOL_OK) {
+            return fail(it->second.status, "the code of this fold did not build (see the first call's message)");
+        }
+        fn = it->second.fn;
+    }
+    ChainArgs A{};
+    A.batch = batch, A.backward = backward;
+    for (int t = 0; t < n; ++t) { A.in[t] = in[t]; A.ld[t] = ld[t]; A.gin[t] = gin ? gin[t] : nullptr; }
+    A.out = out, A.ldo = ldo, A.target = target, A.gout = gout, A.ldg = ldg;
+    void *args[] = {&A};
+    const unsigned grid = static_cast<unsigned>((static_cast<int64_t>(batch) + kSP - 1) / kSP);
+    DOL_HIP(hipModuleLaunchKernel(fn, grid, 1, 1, 64, 1, 1, 0, st, args, nullptr));
+    return DOL_OK;
+}
+
+}  // namespace dol

@@ -233,6 +233,15 @@ dol_status launch_damp_lds_fwd(const dol_fn_table *f, int32_t batch, const float
 dol_status launch_damp_lds_bwd(const dol_fn_table *f, int32_t batch, const float *a, int64_t lda, const float *b,
                                int64_t ldb, const float *out, int64_t ldo, const float *g, int64_t ldg, float *ga,
                                float *gb, int32_t accumulate, hipStream_t st, bool *done);
+// Compiles `src` (HIP C++) for gfx950 at run time and returns the kernel `name` of it (damp_table.hip).
+dol_status jit_compile(const std::string &src, const char *name, hipModule_t *mod, hipFunction_t *fn);
+// A fold of convolution-shaped applies as code written for the chain's shape (fold_chain.hip): m[t] = symbols of the t-th
+// running Distribution, nb[t] = symbols of input t >= 1.
+constexpr int kFoldChainMax = 32;
+bool fold_chain_ok(int n, const int32_t *m, const int32_t *nb);
+dol_status launch_fold_chain(int n, const int32_t *m, const int32_t *nb, int32_t batch, const float *const *in, const int64_t *ld,
+                             float *const *gin, float *out, int64_t ldo, const int32_t *target, const float *gout, int64_t ldg,
+                             int32_t backward, hipStream_t st);
 // Small arbitrary tables as code written for the table (damp_table.hip); *done = false: the call was not taken
 bool table_code_ok(const dol_fn_table *f);
 dol_status launch_damp_table_fwd(const dol_fn_table *f, int32_t batch, const float *a, int64_t lda, const float *b,
