@@ -20,7 +20,7 @@ def _short(name):
 
 
 def _ours(name):
-    return "dol::" in name or "copyBuffer" in name
+    return "dol::" in name or "copyBuffer" in name or name.startswith(("damp_", "dtkp_", "void damp_", "void dtkp_"))
 
 
 def stats(folder, everything=False):

@@ -16,8 +16,10 @@ import subprocess
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_SRC = os.path.join(_HERE, "dol_oracle.c")
-_LIB = os.path.join(_HERE, "libdol_oracle.so")
+# DOL_ORACLE_SRC: build and load another copy of the C source instead (the planted-mistake test points it at a
+# patched copy in a temporary folder; the library is then built next to that copy)
+_SRC = os.environ.get("DOL_ORACLE_SRC") or os.path.join(_HERE, "dol_oracle.c")
+_LIB = os.path.join(os.path.dirname(_SRC), "libdol_oracle.so")
 _lib = None
 
 ABSENT = np.uint64(0xFFFFFFFFFFFFFFFF)
@@ -28,7 +30,7 @@ def build(force: bool = False) -> str:
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off",
                "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
-        subprocess.run(cmd, check=True, cwd=_HERE)
+        subprocess.run(cmd, check=True, cwd=os.path.dirname(_SRC))
     return _LIB
 
 

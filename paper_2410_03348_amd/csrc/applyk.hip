@@ -338,12 +338,7 @@ static void launch_fwd_k(const Rows &R, const KOperands &in, const dol_fnk_table
 {
     if (K == 1 && staged_unary_fwd(f)) {
         const int32_t parts = stage_parts(R.batch, f->n_out);
-        static bool attr_set = false;                // more than 64 KB of dynamic LDS has to be asked for once
-        if (!attr_set) {
-            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(damp_apply1_fwd_staged_kernel),
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(kStageMaxBytes));
-            attr_set = true;
-        }
+        (void)allow_dynamic_lds(reinterpret_cast<const void *>(damp_apply1_fwd_staged_kernel), kStageMaxBytes);
         hipLaunchKernelGGL(damp_apply1_fwd_staged_kernel, dim3(static_cast<unsigned>(R.batch) * parts), dim3(kStageThreads),
                            sizeof(float) * f->n_sym[0], st, f->n_sym[0], f->n_out, parts, in.p[0], in.ld[0], f->col_order.ptr,
                            f->col_ptr.ptr, f->tup.ptr, reinterpret_cast<const uint4 *>(f->unary_head_ord.ptr), out, ldo);
@@ -365,12 +360,7 @@ static void launch_bwd_k(const Rows &R, const KOperands &in, const KGrads &gin, 
 {
     if (K == 1 && staged_unary_bwd(f)) {
         const int32_t parts = stage_parts(R.batch, f->n_sym[0]);
-        static bool attr_set = false;
-        if (!attr_set) {
-            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(damp_apply1_bwd_staged_kernel),
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(kStageMaxBytes));
-            attr_set = true;
-        }
+        (void)allow_dynamic_lds(reinterpret_cast<const void *>(damp_apply1_bwd_staged_kernel), kStageMaxBytes);
         hipLaunchKernelGGL(damp_apply1_bwd_staged_kernel, dim3(static_cast<unsigned>(R.batch) * parts), dim3(kStageThreads),
                            sizeof(float) * f->n_out, st, f->n_sym[0], f->n_out, parts, in.p[0], in.ld[0], f->unary_col.ptr,
                            f->col_ptr.ptr, f->tup.ptr, out, ldo, g, ldg, gin.p[0]);

@@ -320,6 +320,11 @@ dol_status launch_damp_apply2_fwd(const dol_fn_table *f, int32_t batch, const fl
                                   int64_t ldb, float *out, int64_t ldo, hipStream_t st)
 {
     if (batch == 0 || f->n_out == 0) return DOL_OK;
+    {   // shape limits before anything is launched (a failing call leaves the outputs untouched)
+        const int64_t most = static_cast<int64_t>(std::max(f->long_cols.n, f->byj_wave_cols.n));
+        if (batch * most > 0x7fffffffLL)
+            return fail(DOL_EUNSUPPORTED, "batch x long table columns = %lld exceeds 2^31", static_cast<long long>(batch * most));
+    }
     if (conv_path_ok(f)) return launch_damp_conv_fwd(f, batch, a, lda, b, ldb, out, ldo, st);
     bool done = false;
     if (dol_status s2 = launch_damp_table_fwd(f, batch, a, lda, b, ldb, out, ldo, st, &done)) return s2;
@@ -331,12 +336,7 @@ dol_status launch_damp_apply2_fwd(const dol_fn_table *f, int32_t batch, const fl
         const int32_t parts = stage_parts(batch, f->n_out);
 #define CALL(N)                                                                                                           \
     {                                                                                                                     \
-        static bool attr_set = false; /* more than 64 KB of dynamic LDS has to be asked for once */                       \
-        if (!attr_set) {                                                                                                  \
-            DOL_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(damp_byj_fwd_staged_kernel<N>),                    \
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(kStageMaxBytes)));   \
-            attr_set = true;                                                                                              \
-        }                                                                                                                 \
+        DOL_HIP(allow_dynamic_lds(reinterpret_cast<const void *>(damp_byj_fwd_staged_kernel<N>), kStageMaxBytes));                    \
         hipLaunchKernelGGL(damp_byj_fwd_staged_kernel<N>, dim3(static_cast<unsigned>(batch) * parts), dim3(kStageThreads), \
                            sizeof(float) * f->na, st, f->na, f->nb, f->n_out, parts, f->byj_src.ptr, f->col_ptr.ptr,      \
                            f->col_ij.ptr, a, lda, b, ldb, out, ldo);                                                      \
@@ -356,12 +356,7 @@ dol_status launch_damp_apply2_fwd(const dol_fn_table *f, int32_t batch, const fl
     }
     if (staged_fwd_ok(f)) {
         const int32_t parts = stage_parts(batch, f->n_out);
-        static bool attr_set = false;                // more than 64 KB of dynamic LDS has to be asked for once
-        if (!attr_set) {
-            DOL_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(damp_apply2_fwd_staged_kernel),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(kStageMaxBytes)));
-            attr_set = true;
-        }
+        DOL_HIP(allow_dynamic_lds(reinterpret_cast<const void *>(damp_apply2_fwd_staged_kernel), kStageMaxBytes));
         hipLaunchKernelGGL(damp_apply2_fwd_staged_kernel, dim3(static_cast<unsigned>(batch) * parts), dim3(kStageThreads),
                            sizeof(float) * (((f->na + 3) & ~3) + f->nb), st, f->na, f->nb, f->n_out, parts, f->col_order.ptr,
                            f->col_ptr.ptr, f->col_ij.ptr, reinterpret_cast<const uint4 *>(f->col_head_ord.ptr), a, lda, b, ldb, out, ldo);
@@ -610,6 +605,9 @@ dol_status launch_damp_apply2_bwd(const dol_fn_table *f, int32_t batch, const fl
                                   float *gb, int32_t accumulate, hipStream_t st)
 {
     if (batch == 0 || f->na + f->nb == 0 || (!ga && !gb)) return DOL_OK;
+    if (batch * static_cast<int64_t>(f->long_rows.n) > 0x7fffffffLL)      // before anything is launched
+        return fail(DOL_EUNSUPPORTED, "batch x long table rows = %lld exceeds 2^31",
+                    static_cast<long long>(batch * static_cast<int64_t>(f->long_rows.n)));
     if (conv_path_ok(f)) return launch_damp_conv_bwd(f, batch, a, lda, b, ldb, g, ldg, ga, gb, accumulate, st);
     bool done = false;
     if (dol_status s2 = launch_damp_table_bwd(f, batch, a, lda, b, ldb, g, ldg, ga, gb, accumulate, st, &done)) return s2;
@@ -623,12 +621,7 @@ dol_status launch_damp_apply2_bwd(const dol_fn_table *f, int32_t batch, const fl
         if (byj_bwd_staged(f)) {
 #define CALL(N)                                                                                                           \
     {                                                                                                                     \
-        static bool attr_set = false; /* more than 64 KB of dynamic LDS has to be asked for once */                       \
-        if (!attr_set) {                                                                                                  \
-            DOL_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(damp_byj_bwd_row_kernel<N, true>),                 \
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(kStageMaxBytes)));   \
-            attr_set = true;                                                                                              \
-        }                                                                                                                 \
+        DOL_HIP(allow_dynamic_lds(reinterpret_cast<const void *>(damp_byj_bwd_row_kernel<N, true>), kStageMaxBytes));                    \
         hipLaunchKernelGGL((damp_byj_bwd_row_kernel<N, true>), dim3(static_cast<unsigned>(batch)), dim3(kByJRowThreads),  \
                            sizeof(float) * f->n_out, st, T, f->n_out, f->byj_col.ptr, a, lda, b, ldb, out, ldo, g, ldg,   \
                            ga, gb, accumulate);                                                                           \

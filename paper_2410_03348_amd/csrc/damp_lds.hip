@@ -406,14 +406,8 @@ dol_status launch_damp_lds_fwd(const dol_fn_table *f, int32_t batch, const float
     *done = false;
     if (!f->lds_fwd_ok || batch < 1) return DOL_OK;
     const int n_tiles = (batch + kLdsTile - 1) / kLdsTile;
-    static bool attr_set = false;
-    if (!attr_set) {
-        DOL_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(damp_lds_fwd_kernel<true>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(kLdsBytesMax)));
-        DOL_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(damp_lds_fwd_kernel<false>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(kLdsBytesMax)));
-        attr_set = true;
-    }
+    DOL_HIP(allow_dynamic_lds(reinterpret_cast<const void *>(damp_lds_fwd_kernel<true>), kLdsBytesMax));
+    DOL_HIP(allow_dynamic_lds(reinterpret_cast<const void *>(damp_lds_fwd_kernel<false>), kLdsBytesMax));
     const int32_t n_pk = static_cast<int32_t>(f->lds_pk.n / 4);
     const int32_t vec_out = (ldo % 4 == 0) && aligned16(out);
     const Rows2D A = rows2d(a, lda, f->na), B = rows2d(b, ldb, f->nb);
@@ -437,14 +431,8 @@ dol_status launch_damp_lds_bwd(const dol_fn_table *f, int32_t batch, const float
     *done = false;
     if (!f->lds_bwd_ok || batch < 1 || (ga && ga == gb)) return DOL_OK;
     const int n_tiles = (batch + kLdsTile - 1) / kLdsTile;
-    static bool attr_set = false;
-    if (!attr_set) {
-        DOL_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(damp_lds_bwd_kernel<true>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(kLdsBytesMax)));
-        DOL_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(damp_lds_bwd_kernel<false>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(kLdsBytesMax)));
-        attr_set = true;
-    }
+    DOL_HIP(allow_dynamic_lds(reinterpret_cast<const void *>(damp_lds_bwd_kernel<true>), kLdsBytesMax));
+    DOL_HIP(allow_dynamic_lds(reinterpret_cast<const void *>(damp_lds_bwd_kernel<false>), kLdsBytesMax));
     const int32_t vec_ga = (lda % 4 == 0) && aligned16(ga), vec_gb = (ldb % 4 == 0) && aligned16(gb);
     const Rows2D A = rows2d(a, lda, f->na), B = rows2d(b, ldb, f->nb), G = rows2d(g, ldg, f->n_out), O = rows2d(out, ldo, f->n_out);
     const dim3 grid(lds_grid(n_tiles, f->lds_bwd_bytes)), block(kLdsBwdWG);

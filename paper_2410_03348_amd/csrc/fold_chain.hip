@@ -25,8 +25,9 @@ namespace dol {
 
 namespace {
 
-constexpr int kL = 16;                  // lanes per sample
-constexpr int kSP = 64 / kL;            // samples per wavefront
+// Lanes per sample: 16, four samples per wavefront.  (32 lanes per sample - two wavefronts per SIMD at B=4096 instead
+// of one - was measured: 18.8 us against 16.4; the generator still takes the width as a parameter.)
+constexpr int kLanes = 16;
 constexpr int kNBR = 16;                // floats reserved per short input row
 constexpr size_t kChainLdsMax = 40 * 1024;   // per wavefront: at least four wavefronts per compute unit
 
@@ -54,7 +55,7 @@ struct Layout {
 
 int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
-Layout lay_out(const std::vector<int> &shape)
+Layout lay_out(const std::vector<int> &shape, int kL)
 {
     Layout Y;
     Y.n = shape[0];
@@ -85,8 +86,8 @@ Layout lay_out(const std::vector<int> &shape)
     return Y;
 }
 
-// lanes 0 .. len-1 of every sample (in turns of 16) write zero to region[start ..]
-void emit_zero(Src &o, int start, int len)
+// lanes 0 .. len-1 of every sample (in turns of kL) write zero to region[start ..]
+void emit_zero(Src &o, int start, int len, int kL)
 {
     for (int x = 0; x < len; x += kL) {
         if (len - x >= kL) o("  base[%d + l] = 0.0f;\n", start + x);
@@ -94,9 +95,10 @@ void emit_zero(Src &o, int start, int len)
     }
 }
 
-std::string chain_source(const std::vector<int> &shape)
+std::string chain_source(const std::vector<int> &shape, int kL)
 {
-    const Layout Y = lay_out(shape);
+    const int kSP = 64 / kL;
+    const Layout Y = lay_out(shape, kL);
     const int n = Y.n, n1 = n - 1;
     Src o;
     o("typedef unsigned long long u64;\n");
@@ -110,10 +112,14 @@ std::string chain_source(const std::vector<int> &shape)
       "  case 1: return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x4E, 0xF, 0xF, false));\n"
       "  case 2: return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x141, 0xF, 0xF, false));\n"
       "  default: return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x140, 0xF, 0xF, false)); } }\n");
-    o("__device__ __forceinline__ float sum16(float x) { x += dppx(x, 0); x += dppx(x, 1); x += dppx(x, 2); x += dppx(x, 3); return x; }\n");
+    // sum over the lanes of a sample: butterflies inside a row of 16 lanes; for 32 lanes the first row's total then joins
+    // the second row's (row_bcast:15 into rows 1 and 3), whose lanes hold the sample's total
+    o("__device__ __forceinline__ float sum_lanes(float x) { x += dppx(x, 0); x += dppx(x, 1); x += dppx(x, 2); x += dppx(x, 3);\n");
+    if (kL == 32) o("  x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x142, 0xA, 0xF, false));\n");
+    o("  return x; }\n");
     o("extern \"C\" __global__ void __launch_bounds__(64) damp_fold_chain_kernel(const Args A)\n{\n");
     o("  __shared__ float lds[%d];\n", kSP * Y.stride);
-    o("  const int lane = threadIdx.x, l = lane & %d, q = lane >> %d;\n", kL - 1, kL == 16 ? 4 : 3);
+    o("  const int lane = threadIdx.x, l = lane & %d, q = lane >> %d;\n", kL - 1, kL == 16 ? 4 : 5);
     // workgroups are dealt round-robin to the 8 XCDs: give every XCD a contiguous range of samples
     o("  const unsigned id = blockIdx.x, nwg = gridDim.x, xcd = id & 7u, per = nwg >> 3, rem = nwg & 7u;\n");
     o("  const long long wg = (long long)(xcd * per + (xcd < rem ? xcd : rem) + (id >> 3));\n");
@@ -123,9 +129,9 @@ std::string chain_source(const std::vector<int> &shape)
     {
         int pos = 0;
         for (int t = 0; t < n; ++t) {
-            emit_zero(o, pos, Y.off[t] - pos);                       // the halo in front of the row
-            if (t == 0) emit_zero(o, Y.off[0] + Y.m[0], Y.ext[0] - Y.m[0]);
-            else if (Y.ext[t] > kL * Y.w[t]) emit_zero(o, Y.off[t] + kL * Y.w[t], Y.ext[t] - kL * Y.w[t]);
+            emit_zero(o, pos, Y.off[t] - pos, kL);                       // the halo in front of the row
+            if (t == 0) emit_zero(o, Y.off[0] + Y.m[0], Y.ext[0] - Y.m[0], kL);
+            else if (Y.ext[t] > kL * Y.w[t]) emit_zero(o, Y.off[t] + kL * Y.w[t], Y.ext[t] - kL * Y.w[t], kL);
             pos = Y.off[t] + Y.ext[t];
         }
     }
@@ -209,8 +215,8 @@ std::string chain_source(const std::vector<int> &shape)
                 o("    %s base[%d + l] = 0.0f;\n", need - x >= kL ? "" : (std::string("if (l < ") + std::to_string(need - x) + ")").c_str(), g_nxt + x);
         }
         // the short operand's gradient: sum of the lanes' shares; it takes the place of the operand's row, which is spent
-        for (int j = 0; j < nb; ++j) o("    s%d = sum16(s%d);\n", j, j);
-        o("    if (l == 0) {\n");
+        for (int j = 0; j < nb; ++j) o("    s%d = sum_lanes(s%d);\n", j, j);
+        o("    if (l == %d) {\n", kL == 32 ? 16 : 0);
         for (int j = 0; j < nb; ++j) o("      base[%d] = s%d;\n", Y.off_d + t * kNBR + j, j);
         o("    }\n  }\n  fence();\n");
     }
@@ -259,8 +265,8 @@ bool fold_chain_ok(int n, const int32_t *m, const int32_t *nb)
         shape.push_back(nb[t]);
     }
     if (m[0] < 1 || m[0] > 256) return false;
-    const Layout Y = lay_out(shape);
-    return sizeof(float) * kSP * static_cast<size_t>(Y.stride) <= kChainLdsMax;
+    const Layout Y = lay_out(shape, kLanes);
+    return sizeof(float) * (64 / kLanes) * static_cast<size_t>(Y.stride) <= kChainLdsMax;
 }
 
 dol_status launch_fold_chain(int n, const int32_t *m, const int32_t *nb, int32_t batch, const float *const *in, const int64_t *ld,
@@ -268,19 +274,22 @@ dol_status launch_fold_chain(int n, const int32_t *m, const int32_t *nb, int32_t
                              int32_t backward, hipStream_t st)
 {
     static std::mutex mu;
-    static std::map<std::pair<int, std::vector<int>>, ChainKernel> cache;    // per device and shape; lives until the process ends
+    static std::map<std::pair<int, std::vector<int>>, ChainKernel> cache;    // per device, shape and lanes per sample; lives until the process ends
     std::vector<int> shape{n, m[0]};
     for (int t = 1; t < n; ++t) shape.push_back(nb[t]);
+    const int kL = kLanes, kSP = 64 / kL;
     int dev = 0;
     DOL_HIP(hipGetDevice(&dev));
     hipFunction_t fn = nullptr;
     {
         std::lock_guard<std::mutex> lock(mu);
-        auto key = std::make_pair(dev, shape);
+        std::vector<int> keyed(shape);
+        keyed.push_back(kL);
+        auto key = std::make_pair(dev, keyed);
         auto it = cache.find(key);
         if (it == cache.end()) {
             ChainKernel k;
-            k.status = jit_compile(chain_source(shape), "damp_fold_chain_kernel", &k.mod, &k.fn);
+            k.status = jit_compile(chain_source(shape, kL), "damp_fold_chain_kernel", &k.mod, &k.fn);
             it = cache.emplace(key, k).first;
             if (k.status != DOL_OK) return k.status;                        // with the compiler's message
         } else if (it->second.status != DOL_OK) {

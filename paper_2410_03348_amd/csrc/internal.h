@@ -28,6 +28,10 @@ dol_status hip_fail(hipError_t e, const char *what);
         if (e_ != hipSuccess) return ::dol::hip_fail(e_, #call); \
     } while (0)
 
+// A kernel that asks for more than 64 KB of dynamic LDS has to be told so, once per device: this does it the first time
+// a (device, kernel) pair is seen (thread-safe) and is a table lookup afterwards.
+hipError_t allow_dynamic_lds(const void *kernel, size_t bytes);
+
 // ---------------------------------------------------------------- device arrays owned by plans
 
 template <typename T>
@@ -180,8 +184,8 @@ struct UnionPlan {
     DevArray<int32_t> d_ca, d_cb;         // [na] / [nb] output column of each input position (-1: none, filter-union only)
 };
 
-// Content-addressed caches: the same predicate / symbol lists give the same plan object.
-// Returned pointers stay valid until the library is unloaded.
+// Content-addressed caches: the same predicate / symbol lists give the same plan object.  A cache holds at most 4096
+// plans and then releases the one unused longest, so a returned pointer is for the call that asked for it.
 dol_status get_filter_plan(int32_t n, const uint8_t *pred, const FilterPlan **plan);
 dol_status get_union_plan(int32_t na, const int32_t *sa, int32_t nb, const int32_t *sb, const UnionPlan **plan);
 // union(filter(d, pred), c) as one merge plan: na = symbols of d, ia points into d, ca is -1 for dropped symbols.

@@ -422,27 +422,17 @@ static size_t bwd_lds(const dol_fn_table *f, int32_t every)
         else hipLaunchKernelGGL((KERNEL<1024, 4, 3>), grid, dim3(1024), lds, st, __VA_ARGS__);                         \
     } while (0)
 
+// (the reverse sweep may ask for more than 64 KB of LDS)
 template <typename Kern>
-static hipError_t allow_lds(Kern kern) {
-    return hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                               static_cast<int>(kItLdsMax));
-}
+static hipError_t allow_lds(Kern kern) { return allow_dynamic_lds(reinterpret_cast<const void *>(kern), kItLdsMax); }
 
-// Kernels that ask for more than 64 KB of LDS must be told so once per device.
 static dol_status allow_big_lds()
 {
-    static std::mutex mu;
-    static bool done[64] = {};
-    int dev = 0;
-    DOL_HIP(hipGetDevice(&dev));
-    std::lock_guard<std::mutex> lock(mu);
-    if (dev < 0 || dev >= 64 || done[dev]) return DOL_OK;
     DOL_HIP(allow_lds(damp_iterate_bwd_kernel<512, 1, 6>));
     DOL_HIP(allow_lds(damp_iterate_bwd_kernel<512, 2, 6>));
     DOL_HIP(allow_lds(damp_iterate_bwd_kernel<512, 4, 3>));
     DOL_HIP(allow_lds(damp_iterate_bwd_kernel<1024, 4, 3>));
     DOL_HIP(allow_lds(damp_iterate_bwd_kernel<1024, 1, 6>));
-    done[dev] = true;
     return DOL_OK;
 }
 

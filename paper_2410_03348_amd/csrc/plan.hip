@@ -7,6 +7,7 @@
 #include <memory>
 #include <mutex>
 #include <new>
+#include <set>
 #include <unordered_map>
 
 namespace dol {
@@ -40,6 +41,20 @@ dol_status hip_fail(hipError_t e, const char *what)
 {
     set_error("%s: %s", what, hipGetErrorString(e));
     return e == hipErrorOutOfMemory ? DOL_ENOMEM : DOL_EHIP;
+}
+
+hipError_t allow_dynamic_lds(const void *kernel, size_t bytes)
+{
+    static std::mutex mu;
+    static std::set<std::pair<int, const void *>> *seen = new std::set<std::pair<int, const void *>>;   // never destroyed
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    std::lock_guard<std::mutex> lock(mu);
+    if (seen->count({dev, kernel})) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(bytes));
+    if (e == hipSuccess) seen->insert({dev, kernel});
+    return e;
 }
 
 // ---------------------------------------------------------------- function tables
@@ -235,25 +250,38 @@ static uint64_t fnv1a(const void *data, size_t n, uint64_t h = 14695981039346656
     return h;
 }
 
+// At most kCacheMax plans per cache: a program whose predicates or symbol lists keep changing would otherwise grow the
+// caches without bound.  Beyond that the plan that has gone unused longest is released (hipFree waits for launches
+// that may still read its arrays; plans handed out earlier must not be used after kCacheMax newer ones were made).
+constexpr size_t kCacheMax = 4096;
+
 template <typename Plan>
 struct Cache {
     struct Entry {
         std::vector<unsigned char> key;
         std::unique_ptr<Plan> plan;
+        uint64_t used = 0;
     };
     std::mutex mu;
     std::unordered_multimap<uint64_t, Entry> map;
+    uint64_t clock = 0;
 
     const Plan *find(uint64_t h, const std::vector<unsigned char> &key)
     {
         auto range = map.equal_range(h);
         for (auto it = range.first; it != range.second; ++it)
-            if (it->second.key == key) return it->second.plan.get();
+            if (it->second.key == key) { it->second.used = ++clock; return it->second.plan.get(); }
         return nullptr;
     }
     const Plan *insert(uint64_t h, std::vector<unsigned char> &&key, std::unique_ptr<Plan> &&plan)
     {
-        auto it = map.emplace(h, Entry{std::move(key), std::move(plan)});
+        if (map.size() >= kCacheMax) {
+            auto oldest = map.begin();
+            for (auto it = map.begin(); it != map.end(); ++it)
+                if (it->second.used < oldest->second.used) oldest = it;
+            map.erase(oldest);
+        }
+        auto it = map.emplace(h, Entry{std::move(key), std::move(plan), ++clock});
         return it->second.plan.get();
     }
 };
@@ -272,8 +300,9 @@ static std::vector<unsigned char> make_key(int device, std::initializer_list<std
     return key;
 }
 
-static Cache<FilterPlan> g_filter_cache;
-static Cache<UnionPlan> g_union_cache;
+// (on the heap and never destroyed: no hipFree during static destruction, when the HIP runtime may already be down)
+static Cache<FilterPlan> &g_filter_cache = *new Cache<FilterPlan>;
+static Cache<UnionPlan> &g_union_cache = *new Cache<UnionPlan>;
 
 dol_status get_filter_plan(int32_t n, const uint8_t *pred, const FilterPlan **plan)
 {
@@ -338,7 +367,7 @@ dol_status get_union_plan(int32_t na, const int32_t *sa, int32_t nb, const int32
     return DOL_OK;
 }
 
-static Cache<UnionPlan> g_filter_union_cache;
+static Cache<UnionPlan> &g_filter_union_cache = *new Cache<UnionPlan>;
 
 // union(filter(d, pred), c) as ONE merge plan over the unfiltered operand: ia[u] is a position in d (of a kept
 // symbol) or -1, ca[x] is the output column of d's symbol x or -1 when the predicate drops it.
@@ -386,7 +415,7 @@ dol_status get_filter_union_plan(int32_t n, const int32_t *sd, const uint8_t *pr
 struct I32Array {
     DevArray<int32_t> d;
 };
-static Cache<I32Array> g_i32_cache;
+static Cache<I32Array> &g_i32_cache = *new Cache<I32Array>;
 
 // Device copy of a small host int32 array, cached by content.
 dol_status get_i32_array(int32_t n, const int32_t *data, const int32_t **dptr)

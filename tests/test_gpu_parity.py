@@ -417,6 +417,29 @@ def test_config5_checkpointed_iteration(gp, dol, batch, side, rounds, every):
     assert ei.value.status == 1
 
 
+def test_iterated_apply_passes_gradient_on_the_clamp_bound(dol):
+    """Two nodes, one edge, a "stay" symbol of tag 1: with p = 0.5 the second round's sum at node 1 is exactly 1 and the
+    clamp passes gradient (App. A.2), d r_2[1] / d p = 2; with p = 0.75 the clamp acts (0); with 0.25 nothing clamps (2).
+    The same case pins the oracle (tests/test_oracle_reach.py)."""
+    tri = (np.array([0, 0, 1, 1], np.int32), np.array([0, 1, 0, 1], np.int32), np.array([1, 0, 0, 1], np.int32))
+    f = dol.FnTable.create_sparse(2, 2, *tri)
+    ps = np.array([0.5, 0.75, 0.25], np.float32)
+    r0 = dol.Dist(np.arange(2), dev(np.tile(np.array([[1.0, 0.0]], np.float32), (3, 1))))
+    e = dol.Dist(np.arange(2), dev(np.stack([ps, np.ones(3, np.float32)], axis=1)))
+    g = dev(np.tile(np.array([[0.0, 1.0]], np.float32), (3, 1)))
+    hist = torch.empty((3, 3, 2), device="cuda")
+    dol.iterate_apply2(r0, e, f, 2, hist)
+    np.testing.assert_array_equal(host(hist[2])[:, 1], np.array([1.0, 1.0, 0.5], np.float32))
+    ge = torch.empty((3, 2), device="cuda")
+    dol.iterate_backward(e, f, 2, hist, g, None, ge)
+    np.testing.assert_array_equal(host(ge)[:, 0], np.array([2.0, 0.0, 2.0], np.float32))
+    out, ge2 = dol.Dist.empty(np.arange(2), 3), torch.empty((3, 2), device="cuda")
+    ck = torch.empty((1, 3, 2), device="cuda")
+    dol.iterate_apply2_ckpt(r0, e, f, 2, 1, out, ck)
+    dol.iterate_backward_ckpt(r0, e, f, 2, 1, ck, g, None, ge2)
+    np.testing.assert_array_equal(host(ge2), host(ge))
+
+
 @pytest.mark.parametrize("batch,n_nodes,n_edges,scale", [(64, 10, 16, 0.5), (130, 12, 30, 1.0), (3, 5, 4, 0.9), (70, 16, 40, 0.3)])
 def test_transitive_closure_program(gp, batch, n_nodes, n_edges, scale):
     """The recursion of App. B, Fig. 9 over a random directed graph: symbol sets grow step by step, tags pile up

@@ -194,3 +194,17 @@ def test_closure_with_clamping_stays_in_range():
     res = P.transitive_closure_fwd_bwd(w, W.join_triples)
     assert res["out"].min() >= 0.0 and res["out"].max() == 1.0       # dense graph: re-derivations pile up to the clamp
     assert np.isfinite(res["grad_p"]).all()
+
+
+def test_clamp_boundary_passes_gradient_in_the_rounds():
+    """Two nodes, one edge.  With p = 0.5 the second round's sum at node 1 is 0.5 + 1 * 0.5 = 1 exactly: the clamp passes
+    gradient on its bound (App. A.2), so d r_2[1] / d p = r_1[0] + d r_1[1] / d p = 1 + 1 = 2.  With p = 0.75 the sum is
+    1.3125, the clamp acts and the gradient is 0; with p = 0.25 nothing clamps and the gradient is again 2."""
+    eu, ev = np.array([0], np.int32), np.array([1], np.int32)
+    g = np.array([[0.0, 1.0]], np.float32)
+    for p, want_r, want_g in ((0.5, 1.0, 2.0), (0.75, 1.0, 0.0), (0.25, 0.5, 2.0)):
+        pe = np.array([[p]], np.float32)
+        hist = oracle.reach_fwd(2, eu, ev, 0, 2, pe)
+        assert hist[2, 0, 1] == np.float32(want_r) and hist[1, 0, 1] == np.float32(p)
+        gp = oracle.reach_bwd(2, eu, ev, 2, pe, hist, g)
+        assert gp[0, 0] == np.float32(want_g), (p, gp)
