@@ -39,7 +39,8 @@ constexpr int kJitMaxOut = 1024;
 constexpr int kJitMaxMergeOut = 512;   // merged launches keep the Apply's whole result tile in LDS
 constexpr int64_t kJitMaxTuples = 16384;
 
-enum { kSlotFwd = 0, kSlotBwd = 1, kSlotMergeFwd = 2, kSlotMergeBwd = 3, kSlots = 4 };
+// (the last two: merged launches whose filter-union plan is `aligned`, see UnionPlan)
+enum { kSlotFwd = 0, kSlotBwd = 1, kSlotMergeFwd = 2, kSlotMergeBwd = 3, kSlotMergeFwdAligned = 4, kSlotMergeBwdAligned = 5, kSlots = 6 };
 
 struct JitState {
     std::mutex mu;
@@ -133,7 +134,7 @@ void emit_tile_head(Src &o)
 
 // Forward.  merged: the kept symbols of the result are merged with a third Distribution c in the same launch
 // (out = union(filter(apply2(a, b)), c)); the Apply's own result then lives in LDS only.
-std::string forward_source(const dol_fn_table *f, bool merged)
+std::string forward_source(const dol_fn_table *f, bool merged, bool aligned = false)
 {
     const int na = f->na, nb = f->nb, S = f->n_out;
     const int pa = na + 4, pb = nb + 4;
@@ -200,6 +201,10 @@ std::string forward_source(const dol_fn_table *f, bool merged)
         }
         for (int u = 0; u < 4; ++u) {
             o("      float4 y%d; { const float *cr = c + (s0 + ps%d) * nc;\n", u, u);
+            if (aligned) {          // the result has c's symbols in c's order: one 16-byte load
+                o("        y%d = *reinterpret_cast<const float4 *>(cr + 4 * pk%d); }\n", u, u);
+                continue;
+            }
             o("        if (jb%d.x >= 0 && !(jb%d.x & 3) && jb%d.y == jb%d.x + 1 && jb%d.z == jb%d.x + 2 && jb%d.w == jb%d.x + 3) y%d = *reinterpret_cast<const float4 *>(cr + jb%d.x);\n",
               u, u, u, u, u, u, u, u, u, u);
             o("        else y%d = make_float4(cr[jb%d.x > 0 ? jb%d.x : 0], cr[jb%d.y > 0 ? jb%d.y : 0], cr[jb%d.z > 0 ? jb%d.z : 0], cr[jb%d.w > 0 ? jb%d.w : 0]); }\n",
@@ -209,7 +214,13 @@ std::string forward_source(const dol_fn_table *f, bool merged)
             o("      { const float *xr = so + ps%d * %d; bool over = false; float v[4];\n", u, po);
             o("        const int ja[4] = {ja%d.x, ja%d.y, ja%d.z, ja%d.w}, jb[4] = {jb%d.x, jb%d.y, jb%d.z, jb%d.w}; const float yy[4] = {y%d.x, y%d.y, y%d.z, y%d.w};\n",
               u, u, u, u, u, u, u, u, u, u, u, u);
-            o("        for (int e = 0; e < 4; ++e) { const float x = xr[ja[e] > 0 ? ja[e] : 0], t = x + yy[e];\n");
+            if (aligned) {          // a kept column of the Apply sits at its own position in the result
+                o("        const float4 x4 = 4 * pk%d < %d ? *reinterpret_cast<const float4 *>(xr + 4 * pk%d) : make_float4(0.0f, 0.0f, 0.0f, 0.0f);\n", u, S, u);
+                o("        const float xx[4] = {x4.x, x4.y, x4.z, x4.w};\n");
+                o("        for (int e = 0; e < 4; ++e) { const float x = xx[e], t = x + yy[e];\n");
+            } else {
+                o("        for (int e = 0; e < 4; ++e) { const float x = xr[ja[e] > 0 ? ja[e] : 0], t = x + yy[e];\n");
+            }
             o("          if (ja[e] >= 0 && jb[e] >= 0) { over |= !(t <= 1.0f); v[e] = fminf(t, 1.0f); } else v[e] = ja[e] >= 0 ? x : yy[e]; }\n");
             o("        if (qb + %d < total) { *reinterpret_cast<float4 *>(out + (s0 + ps%d) * n3 + 4 * pk%d) = make_float4(v[0], v[1], v[2], v[3]);\n", kThreads * u, u, u);
             o("          if (over) atomicOr(&sflag[ps%d], 1); } }\n", u);
@@ -238,7 +249,7 @@ int max_multiplicity(const dol_fn_table *f, bool by_b)
 
 // Loads of one group of the gradient reaching the Apply's columns [c0, c1) into registers (th[]), and their way
 // into the LDS stage.  merged: column c of the Apply is column ca[c] of the upstream gradient (or dropped).
-void emit_gh_load(Src &o, int S, int c0, int c1, bool merged, const char *ind)
+void emit_gh_load(Src &o, int S, int c0, int c1, bool merged, bool aligned, const char *ind)
 {
     const int chunks = (c1 - c0) / 4, per_thread = (kJitTile * chunks + kThreads - 1) / kThreads;
     for (int x = 0; x < per_thread; ++x) {
@@ -247,7 +258,10 @@ void emit_gh_load(Src &o, int S, int c0, int c1, bool merged, const char *ind)
           chunks, chunks);
         if (merged) {
             o("%s  const int4 oc = reinterpret_cast<const int4 *>(ca)[%d + k]; const float *gr = g + (s0 + s) * n3;\n", ind, c0 / 4);
-            o("%s  const float4 t = make_float4(gr[oc.x > 0 ? oc.x : 0], gr[oc.y > 0 ? oc.y : 0], gr[oc.z > 0 ? oc.z : 0], gr[oc.w > 0 ? oc.w : 0]);\n", ind);
+            if (aligned)    // a kept column of the Apply is the same column of the result: one 16-byte load
+                o("%s  const float4 t = *reinterpret_cast<const float4 *>(gr + %d + 4 * k);\n", ind, c0);
+            else
+                o("%s  const float4 t = make_float4(gr[oc.x > 0 ? oc.x : 0], gr[oc.y > 0 ? oc.y : 0], gr[oc.z > 0 ? oc.z : 0], gr[oc.w > 0 ? oc.w : 0]);\n", ind);
             o("%s  th%d = make_float4(oc.x >= 0 ? t.x : 0.0f, oc.y >= 0 ? t.y : 0.0f, oc.z >= 0 ? t.z : 0.0f, oc.w >= 0 ? t.w : 0.0f); }\n", ind, x);
         } else {
             o("%s  th%d = reinterpret_cast<const float4 *>(g)[((s0 + s) * %d + %d) / 4 + k]; }\n", ind, x, S, c0);
@@ -271,7 +285,7 @@ void emit_gh_store(Src &o, int c0, int c1, int g, int n_groups, const char *dst,
     }
 }
 
-std::string backward_source(const dol_fn_table *f, bool merged)
+std::string backward_source(const dol_fn_table *f, bool merged, bool aligned = false)
 {
     const int na = f->na, nb = f->nb, S = f->n_out;
     const int pa = na + 4, pb = nb + 4, pg = kJitGroup + 4;
@@ -308,7 +322,7 @@ std::string backward_source(const dol_fn_table *f, bool merged)
     for (int x = 0; x < gh_per_thread; ++x) o("  float4 th%d;\n", x);
     emit_stage_load(o, "a", "a", na);
     emit_stage_load(o, "b", "b", nb);
-    emit_gh_load(o, S, 0, std::min(S, kJitGroup), merged, "  ");
+    emit_gh_load(o, S, 0, std::min(S, kJitGroup), merged, aligned, "  ");
     if (merged) o("  int was_clamped = 1; if (saved) was_clamped = lane < valid ? saved[s0 + lane] : 0;\n");
     emit_stage_store(o, "a", "sa", na);
     emit_stage_store(o, "b", "sb", nb);
@@ -375,7 +389,7 @@ std::string backward_source(const dol_fn_table *f, bool merged)
         for (int g = 0; g < n_groups; ++g) {
             const int c0 = g * kJitGroup, c1 = std::min(S, c0 + kJitGroup);
             const char *cur = g & 1 ? "sg1" : "sg0", *nxt = g & 1 ? "sg0" : "sg1";
-            if (g + 1 < n_groups) emit_gh_load(o, S, c1, std::min(S, c1 + kJitGroup), merged, "    ");
+            if (g + 1 < n_groups) emit_gh_load(o, S, c1, std::min(S, c1 + kJitGroup), merged, aligned, "    ");
             // 16 columns at a time, fenced for the instruction scheduler: it would otherwise fetch the whole group first and
             // run out of registers
             o("    {\n");
@@ -507,13 +521,14 @@ JitState *state_of(const dol_fn_table *f)
 static dol_status kernel_of(const dol_fn_table *f, int slot, hipFunction_t *fn)
 {
     static const char *const names[kSlots] = {"damp_table_fwd_kernel", "damp_table_bwd_kernel", "damp_table_merge_fwd_kernel",
-                                              "damp_table_merge_bwd_kernel"};
+                                              "damp_table_merge_bwd_kernel", "damp_table_merge_fwd_kernel", "damp_table_merge_bwd_kernel"};
     JitState *js = state_of(f);
     std::lock_guard<std::mutex> lock(js->mu);
     if (!js->tried[slot]) {
         js->tried[slot] = true;
         const std::string src = slot == kSlotFwd ? forward_source(f, false) : slot == kSlotBwd ? backward_source(f, false) :
-                                slot == kSlotMergeFwd ? forward_source(f, true) : backward_source(f, true);
+                                slot == kSlotMergeFwd ? forward_source(f, true) : slot == kSlotMergeBwd ? backward_source(f, true) :
+                                slot == kSlotMergeFwdAligned ? forward_source(f, true, true) : backward_source(f, true, true);
         js->status[slot] = jit_compile(src, names[slot], &js->mod[slot], &js->fn[slot]);
         if (js->status[slot] != DOL_OK) return js->status[slot];      // with the compiler's message
     } else if (js->status[slot] != DOL_OK) {
@@ -563,7 +578,7 @@ dol_status launch_damp_table_merge_fwd(const dol_fn_table *f, const UnionPlan *p
                                        const float *c, float *out, int32_t *saved, hipStream_t st)
 {
     hipFunction_t fn = nullptr;
-    if (dol_status s = kernel_of(f, kSlotMergeFwd, &fn)) return s;
+    if (dol_status s = kernel_of(f, p->aligned ? kSlotMergeFwdAligned : kSlotMergeFwd, &fn)) return s;
     int n_tiles = (batch + kJitTile - 1) / kJitTile, nc = p->nb, n3 = p->n_out;
     const int32_t *ia = p->d_ia.ptr, *ib = p->d_ib.ptr;
     void *args[] = {&a, &b, &c, &out, &ia, &ib, &saved, &batch, &n_tiles, &nc, &n3};
@@ -576,7 +591,7 @@ dol_status launch_damp_table_merge_bwd(const dol_fn_table *f, const UnionPlan *p
                                        int32_t accumulate, hipStream_t st)
 {
     hipFunction_t fn = nullptr;
-    if (dol_status s = kernel_of(f, kSlotMergeBwd, &fn)) return s;
+    if (dol_status s = kernel_of(f, p->aligned ? kSlotMergeBwdAligned : kSlotMergeBwd, &fn)) return s;
     int n_tiles = (batch + kJitTile - 1) / kJitTile, nc = p->nb, n3 = p->n_out;
     const int32_t *ia = p->d_ia.ptr, *ib = p->d_ib.ptr, *ca = p->d_ca.ptr, *cb = p->d_cb.ptr;
     void *args[] = {&a, &b, &c, &g, &ga, &gb, &gc, &ia, &ib, &ca, &cb, &saved, &batch, &n_tiles, &nc, &n3, &accumulate};

@@ -182,6 +182,10 @@ struct UnionPlan {
     std::vector<int32_t> out_syms;
     DevArray<int32_t> d_ia, d_ib;         // [n_out] position in a / b or -1
     DevArray<int32_t> d_ca, d_cb;         // [na] / [nb] output column of each input position (-1: none, filter-union only)
+    // filter-union plans: the result has exactly b's symbols in b's order and every kept symbol of a sits at its own
+    // position (ia[c] is c or -1, ib[c] = c): true when a's symbols are 0 .. na-1 of b's id list, as in a program
+    // that merges an Apply's result into a Distribution over all its possible symbols
+    bool aligned = false;
 };
 
 // Content-addressed caches: the same predicate / symbol lists give the same plan object.  A cache holds at most 4096

@@ -404,6 +404,8 @@ dol_status get_filter_union_plan(int32_t n, const int32_t *sd, const uint8_t *pr
         }
     }
     p->n_out = static_cast<int32_t>(ia.size());
+    p->aligned = p->n_out == nc && n <= nc;
+    for (int32_t c = 0; c < p->n_out && p->aligned; ++c) p->aligned = ib[c] == c && (ia[c] == c || ia[c] < 0);
     hipError_t e;
     if ((e = p->d_ia.upload(ia)) != hipSuccess || (e = p->d_ib.upload(ib)) != hipSuccess ||
         (e = p->d_ca.upload(ca)) != hipSuccess || (e = p->d_cb.upload(cb)) != hipSuccess)
