@@ -97,6 +97,9 @@ const int32_t *dol_fn_table_out_syms(const dol_fn_table *table);
  * DAMP, as a profiler prints it without namespace and arguments (valid until destroy).  The library picks the
  * kernel from the table's structure (Sec. 3.1.2: the symbol side is known before any tag is touched). */
 const char *dol_fn_table_kernel(const dol_fn_table *table, int32_t which);
+/* The same for a batch of the given size with contiguous, 16-byte aligned tensors: some tables get another kernel
+ * once the batch fills the chip (valid until the next call on this thread). */
+const char *dol_fn_table_kernel_at(const dol_fn_table *table, int32_t which, int64_t batch);
 /* Synchronises the device before releasing the device copies.  NULL is ignored. */
 void dol_fn_table_destroy(dol_fn_table *table);
 

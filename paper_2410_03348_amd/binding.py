@@ -77,6 +77,8 @@ _lib.dol_fn_table_out_syms.argtypes = [C.c_void_p]
 _lib.dol_fn_table_out_syms.restype = _i32p
 _lib.dol_fn_table_kernel.argtypes = [C.c_void_p, C.c_int32]
 _lib.dol_fn_table_kernel.restype = C.c_char_p
+_lib.dol_fn_table_kernel_at.argtypes = [C.c_void_p, C.c_int32, C.c_int64]
+_lib.dol_fn_table_kernel_at.restype = C.c_char_p
 _lib.dol_fn_table_destroy.argtypes = [C.c_void_p]
 _lib.dol_fn_table_destroy.restype = None
 _lib.dol_apply2.argtypes = [C.POINTER(_Dist), C.POINTER(_Dist), C.c_void_p, C.POINTER(_Prov), C.POINTER(_Dist), C.c_void_p]
@@ -197,6 +199,10 @@ class FnTable:
         self.out_syms = np.ctypeslib.as_array(p, shape=(self.n_out,)).copy() if self.n_out else np.empty(0, np.int32)
         self.kernel_fwd = _lib.dol_fn_table_kernel(handle, 0).decode()
         self.kernel_bwd = _lib.dol_fn_table_kernel(handle, 1).decode()
+
+    def kernel_at(self, backward: bool, batch: int) -> str:
+        """Name of the DAMP kernel launched for a batch of this size with contiguous, aligned tensors."""
+        return _lib.dol_fn_table_kernel_at(self._h, 1 if backward else 0, batch).decode()
 
     @staticmethod
     def create_dense(out_id) -> "FnTable":

@@ -50,7 +50,7 @@ bool conv_path_ok(const dol_fn_table *f)
     return f->conv_like && f->nb <= kConvMaxNb && f->na + 3 * kConvMaxNb <= kConvMaxRow;
 }
 
-std::string damp_kernel_name(const dol_fn_table *f, bool backward)
+std::string damp_kernel_name(const dol_fn_table *f, bool backward, int64_t batch)
 {
     if (!conv_path_ok(f)) {
         if (table_code_ok(f)) return backward ? "damp_table_bwd_kernel" : "damp_table_fwd_kernel";
@@ -60,7 +60,8 @@ std::string damp_kernel_name(const dol_fn_table *f, bool backward)
     }
     char buf[96];
     snprintf(buf, sizeof buf, "damp_conv_%s_%s_kernel<%d", backward ? "bwd" : "fwd",
-             !backward && f->na <= 16 ? "small" : f->na <= kTileMaxM ? "tile" : "loop", padded_nb(f->nb));   // a prefix
+             !backward && f->na <= 16 ? "small" : conv_rows_ok(f, batch, backward) ? "rows" : f->na <= kTileMaxM ? "tile" : "loop",
+             padded_nb(f->nb));   // a prefix
     return buf;
 }
 
@@ -250,6 +251,8 @@ dol_status launch_damp_conv_fwd(const dol_fn_table *f, int32_t batch, const floa
                                 int64_t ldb, float *out, int64_t ldo, hipStream_t st)
 {
     if (batch == 0) return DOL_OK;
+    dol_status taken = DOL_OK;
+    if (launch_damp_conv_rows_fwd(f, batch, a, lda, b, ldb, out, ldo, st, &taken)) return taken;
     switch (padded_nb(f->nb)) {
     case 4: launch_fwd_nbp<4>(f, batch, a, lda, b, ldb, out, ldo, st); break;
     case 8: launch_fwd_nbp<8>(f, batch, a, lda, b, ldb, out, ldo, st); break;
@@ -468,6 +471,8 @@ dol_status launch_damp_conv_bwd(const dol_fn_table *f, int32_t batch, const floa
                                 hipStream_t st)
 {
     if (batch == 0 || (!ga && !gb)) return DOL_OK;
+    dol_status taken = DOL_OK;
+    if (launch_damp_conv_rows_bwd(f, batch, a, lda, b, ldb, g, ldg, ga, gb, accumulate, st, &taken)) return taken;
     switch (padded_nb(f->nb)) {
     case 4: launch_bwd_nbp<4>(f, batch, a, lda, b, ldb, g, ldg, ga, gb, accumulate, st); break;
     case 8: launch_bwd_nbp<8>(f, batch, a, lda, b, ldb, g, ldg, ga, gb, accumulate, st); break;

@@ -467,7 +467,9 @@ std::string backward_source(const dol_fn_table *f, bool merged, bool aligned = f
 
 dol_status jit_compile(const std::string &src, const char *name, hipModule_t *mod, hipFunction_t *fn)
 {
-    if (const char *dump = getenv("DOL_DUMP_TABLE_SRC")) {
+    // DOL_JIT_DUMP_DIR names a folder that receives the source of every kernel generated in this process, so that
+    // the code written for a table or a chain can be read and compiled by hand.
+    if (const char *dump = getenv("DOL_JIT_DUMP_DIR")) {
         const std::string path = std::string(dump) + "/" + name + ".hip";
         if (FILE *fh = fopen(path.c_str(), "w")) { fputs(src.c_str(), fh); fclose(fh); }
     }

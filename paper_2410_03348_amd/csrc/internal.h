@@ -226,7 +226,14 @@ dol_status launch_nll_grad(int32_t batch, int32_t n, const float *p, int64_t ld,
 bool conv_path_ok(const dol_fn_table *f);
 bool byj_fwd_staged_ok(const dol_fn_table *f);   // forward through the per-j map with the first operand's row in LDS
 bool staged_fwd_ok(const dol_fn_table *f);   // forward through the kernel that stages both operand rows in LDS
-std::string damp_kernel_name(const dol_fn_table *f, bool backward);
+std::string damp_kernel_name(const dol_fn_table *f, bool backward, int64_t batch = 0);
+// Large batches of contiguous, 16-byte aligned tensors (damp_conv_rows.hip); false: the call was not taken.
+bool conv_rows_ok(const dol_fn_table *f, int64_t batch, bool backward);
+bool launch_damp_conv_rows_fwd(const dol_fn_table *f, int32_t batch, const float *a, int64_t lda, const float *b, int64_t ldb,
+                               float *out, int64_t ldo, hipStream_t st, dol_status *status);
+bool launch_damp_conv_rows_bwd(const dol_fn_table *f, int32_t batch, const float *a, int64_t lda, const float *b, int64_t ldb,
+                               const float *g, int64_t ldg, float *ga, float *gb, int32_t accumulate, hipStream_t st,
+                               dol_status *status);
 dol_status launch_damp_conv_fwd(const dol_fn_table *f, int32_t batch, const float *a, int64_t lda, const float *b,
                                 int64_t ldb, float *out, int64_t ldo, hipStream_t st);
 dol_status launch_damp_conv_bwd(const dol_fn_table *f, int32_t batch, const float *a, int64_t lda, const float *b,

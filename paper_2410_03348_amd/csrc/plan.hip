@@ -524,6 +524,14 @@ const char *dol_fn_table_kernel(const dol_fn_table *table, int32_t which)
     return which ? table->kernel_bwd.c_str() : table->kernel_fwd.c_str();
 }
 
+const char *dol_fn_table_kernel_at(const dol_fn_table *table, int32_t which, int64_t batch)
+{
+    static thread_local std::string name;
+    if (!table) return "";
+    name = dol::damp_kernel_name(table, which != 0, batch);
+    return name.c_str();
+}
+
 dol_status dol_filter_plan(const dol_dist *d, const uint8_t *pred_mask, int32_t *n_out, int32_t *out_syms)
 {
     if (!d || !n_out) return dol::fail(DOL_EINVAL, "NULL argument");

@@ -79,14 +79,14 @@ def _apply_fwd(a, b, f, out, n_tup, prov=None, dtkp_k=0):
     if dtkp_k:
         return Launch("dtkp_apply2_kernel", lambda: dol.apply2(a, b, f, prov, out),
                       B * (12 * dtkp_k * (a.n_sym + b.n_sym + out.n_sym) + 4 * out.n_sym), B * n_tup * dtkp_k, "fwd")
-    return Launch(f.kernel_fwd, lambda: dol.apply2(a, b, f, None, out),
+    return Launch(f.kernel_at(False, B), lambda: dol.apply2(a, b, f, None, out),
                   4 * B * (a.n_sym + b.n_sym + out.n_sym), B * n_tup, "fwd")
 
 
 def _apply_bwd(rec, g, ga, gb, n_tup):
     a, b, out = rec.a, rec.b, rec.out
     n_w = (a.n_sym if ga is not None else 0) + (b.n_sym if gb is not None else 0)
-    return Launch(rec.f.kernel_bwd, lambda: dol.backward(rec, g, ga, gb),
+    return Launch(rec.f.kernel_at(True, a.batch), lambda: dol.backward(rec, g, ga, gb),
                   4 * a.batch * (a.n_sym + b.n_sym + out.n_sym + n_w), 2 * a.batch * n_tup, "bwd")
 
 

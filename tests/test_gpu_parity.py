@@ -690,6 +690,19 @@ def test_hashed_tables_in_lds_with_clamping(dol, na, nb, n_out, B, scale):
 def test_sum_tables_with_clamping(dol, na, nb, B):
     """Sum-shaped tables of every supported width, with unnormalised tags so that many columns exceed 1 and the
     backward pass has to re-derive the clamp decisions; rows 0..2 hit 0.875 / 1.0 / 1.125 exactly."""
+    check_sum_table(dol, na, nb, B)
+
+
+@pytest.mark.parametrize("na,nb,B", [(127, 10, 16384 + 37), (19, 10, 16384), (17, 16, 20001), (192, 16, 16385), (64, 4, 16401),
+                                      (70, 1, 16390), (100, 8, 16384 + 63), (37, 3, 16387), (118, 10, 32768), (10, 10, 16389),
+                                      (3, 16, 16400), (1, 1, 16385), (16, 2, 16384)])
+def test_sum_tables_at_batches_that_fill_the_chip(dol, na, nb, B):
+    """The same at batches where a lane owns a sample and a workgroup a tile of 64: whole tiles and a ragged last
+    one, tiles that must re-derive the clamp decisions and (the second half of the batch) tiles that need not."""
+    check_sum_table(dol, na, nb, B, calm_from=B // 2, kernel="rows")
+
+
+def check_sum_table(dol, na, nb, B, calm_from=None, kernel=None):
     tab = W.sum_table(range(na), range(nb))
     x = min(1.0, 2.2 / np.sqrt(min(na, nb)))        # column sums of min(na, nb) terms scatter around 1
     a = (W.uniform01(na, B * na) * x).astype(np.float32).reshape(B, na)
@@ -698,9 +711,14 @@ def test_sum_tables_with_clamping(dol, na, nb, B):
         a[r] = 0; b[r] = 0
         a[r, na - 1] = 1.0; b[r, 0] = tot
     a[3] *= 0.01                       # a sample far below the clamp takes the shortcut
+    if calm_from is not None:
+        a[calm_from:] *= 0.01
     tri = oracle.dense_to_triples(tab)
     syms, want, pre32, _ = oracle.damp_apply2_fwd(tri, na, nb, a, b, want_pre=True)
     f = dol.FnTable.create_dense(tab)
+    if kernel:
+        assert f.kernel_at(False, B).startswith("damp_conv_fwd_%s_kernel" % (kernel if na > 16 else "small")), f.kernel_at(False, B)
+        assert f.kernel_at(True, B).startswith("damp_conv_bwd_%s_kernel" % kernel), f.kernel_at(True, B)
     da, db = dol.Dist(np.arange(na), dev(a)), dol.Dist(np.arange(nb), dev(b))
     do = dol.Dist.empty(syms, B)
     dol.apply2(da, db, f, None, do)
