@@ -48,15 +48,29 @@ dtkp_fold_kernel(const DtkpFoldArgs A)
     float *bufp = reinterpret_cast<float *>(rival + 64);
     float *fp = bufp + 2 * A.max_s * K;
     float *gh = fp + 64;
-    const uint32_t *w = reinterpret_cast<const uint32_t *>(gh + A.max_s);
+    // the symbol side starts at the next multiple of 16 bytes
+    const uint32_t w_off = (static_cast<uint32_t>(reinterpret_cast<unsigned char *>(gh + A.max_s) - lds_raw) + 15u) & ~15u;
+    const uint32_t *w = reinterpret_cast<const uint32_t *>(lds_raw + w_off);
     const int lane = threadIdx.x;
     const int64_t s = blockIdx.x;
-    fp[lane] = lane < A.n_facts ? A.fact_prob[s * A.n_facts + lane] : 1.0f;
-    rival[lane] = lane < A.n_facts ? A.rival[lane] : 0;
-    {
-        uint32_t *wl = reinterpret_cast<uint32_t *>(gh + A.max_s);
-        for (int e = lane; e < A.n_words; e += kWave) wl[e] = static_cast<uint32_t>(A.words[e]);
+    const float my_fp = lane < A.n_facts ? A.fact_prob[s * A.n_facts + lane] : 1.0f;
+    const uint64_t my_rival = lane < A.n_facts ? A.rival[lane] : 0;
+    {   // 16 bytes per lane and four loads in flight: the words are the same for every sample and sit in L2, so what
+        // this costs is round trips
+        uint4 *wl = reinterpret_cast<uint4 *>(lds_raw + w_off);
+        const uint4 *src = reinterpret_cast<const uint4 *>(A.words);
+        const int n4 = A.n_words / 4;           // the host pads the array to whole 16-byte pieces
+        for (int base = 0; base < n4; base += 4 * kWave) {
+            uint4 v[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) v[k] = src[min(base + k * kWave + lane, n4 - 1)];
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                if (base + k * kWave + lane < n4) wl[base + k * kWave + lane] = v[k];
+        }
     }
+    fp[lane] = my_fp;
+    rival[lane] = my_rival;
     wave_lds_fence();
     {   // natural initialisation (App. A.1)
         const int S0 = static_cast<int>(w[1]);
@@ -80,12 +94,22 @@ dtkp_fold_kernel(const DtkpFoldArgs A)
         const uint32_t *l_ptr = w + w[2 + 3 * t], *l_rec = w + w[3 + 3 * t];
         const bool last = t == A.n - 1;
         for (int c = lane; c < S; c += kWave) {
-            TopK<K> top;
-            top.clear();
-            uint32_t q = l_ptr[c];
-            const uint32_t q1 = l_ptr[c + 1];
-            uint32_t rec = l_rec[q];
-            for (; q < q1; ++q) {
+            // The list keeps, per rank, the probability and where the proof came from (record, slot of the first
+            // operand's list); the masks are put together again for the k winners only.  A candidate whose
+            // probability differs from every kept one finds its rank by comparing probabilities alone; one that ties
+            // (duplicates of a kept proof always do) takes the full comparison of the list's contract.
+            float tp[K];
+            int tid_[K];
+#pragma unroll
+            for (int x = 0; x < K; ++x) { tp[x] = -1.0f; tid_[x] = -1; }
+            auto mask_of = [&](int id) -> uint64_t {
+                const int q = id / K, x = id - q * K;
+                const uint32_t r = l_rec[q];
+                return cm[static_cast<int>(r & 0xffffu) * K + x] | (uint64_t(1) << (r >> 16));
+            };
+            const uint32_t q0 = l_ptr[c], q1 = l_ptr[c + 1];
+            uint32_t rec = l_rec[q0];
+            for (uint32_t q = q0; q < q1; ++q) {
                 const int i = static_cast<int>(rec & 0xffffu), fb = static_cast<int>(rec >> 16);
                 rec = l_rec[q + 1];             // the next tuple's record is on its way while this one is worked on
                 uint64_t ma[K];
@@ -98,28 +122,55 @@ dtkp_fold_kernel(const DtkpFoldArgs A)
                 // the first operand's proof holds a rival of the one fact the second brings.  The product over
                 // ascending facts is unchanged when the fact is already there, takes one more factor when it lies
                 // above every fact of the proof (ma < mb as integers), and is redone from scratch otherwise.
-                float pr[K];
-                bool ok[K], plain[K];
 #pragma unroll
                 for (int x = 0; x < K; ++x) {
-                    ok[x] = ma[x] != kAbsent && !(ma[x] & bad);
-                    plain[x] = (ma[x] & mb) || ma[x] < mb;
-                    pr[x] = (ma[x] & mb) ? pa[x] : pa[x] * pb;
-                }
+                    const bool ok = ma[x] != kAbsent && !(ma[x] & bad);
+                    const bool plain = (ma[x] & mb) || ma[x] < mb;
+                    float pr = (ma[x] & mb) ? pa[x] : pa[x] * pb;
+                    if (ok && !plain) pr = proof_prob(ma[x] | mb, fp);
+                    const int id = static_cast<int>(q) * K + x;
+                    bool tie = false;
 #pragma unroll
-                for (int x = 0; x < K; ++x) {
-                    if (!ok[x]) continue;
-                    if (!plain[x]) pr[x] = proof_prob(ma[x] | mb, fp);
-                    top.insert(ma[x] | mb, pr[x]);
+                    for (int y = 0; y < K; ++y) tie |= pr == tp[y];
+                    if (ok && tie) {
+                        const uint64_t mask = ma[x] | mb;
+                        uint64_t tm[K];
+                        bool dup = false;
+#pragma unroll
+                        for (int y = 0; y < K; ++y) {
+                            tm[y] = tid_[y] >= 0 ? mask_of(tid_[y]) : kAbsent;
+                            dup |= tm[y] == mask;
+                        }
+                        if (!dup && TopK<K>::before(mask, pr, tm[K - 1], tp[K - 1])) {
+#pragma unroll
+                            for (int y = K - 1; y >= 0; --y) {
+                                const bool here = TopK<K>::before(mask, pr, tm[y], tp[y]);
+                                const bool above = y > 0 ? TopK<K>::before(mask, pr, tm[y - 1], tp[y - 1]) : false;
+                                if (above) { tp[y] = tp[y - 1]; tid_[y] = tid_[y - 1]; }
+                                else if (here) { tp[y] = pr; tid_[y] = id; }
+                            }
+                        }
+                    } else {
+                        const float offer = ok ? pr : -2.0f;        // below every slot, absent ones (-1) included
+                        bool gt[K];
+#pragma unroll
+                        for (int y = 0; y < K; ++y) gt[y] = offer > tp[y];
+#pragma unroll
+                        for (int y = K - 1; y >= 0; --y) {
+                            const bool above = y > 0 ? gt[y - 1] : false;
+                            tp[y] = above ? tp[y - 1] : gt[y] ? offer : tp[y];
+                            tid_[y] = above ? tid_[y - 1] : gt[y] ? id : tid_[y];
+                        }
+                    }
                 }
             }
             float sum = 0.0f;
 #pragma unroll
             for (int x = 0; x < K; ++x) {
-                const bool present = top.m[x] != kAbsent;
-                nm[c * K + x] = top.m[x];
-                np[c * K + x] = present ? top.p[x] : 0.0f;
-                if (present) sum = sum + top.p[x];
+                const bool present = tid_[x] >= 0;
+                nm[c * K + x] = present ? mask_of(tid_[x]) : kAbsent;
+                np[c * K + x] = present ? tp[x] : 0.0f;
+                if (present) sum = sum + tp[x];
             }
             if (last) {
                 const int64_t o = (s * S + c) * K;
@@ -216,12 +267,13 @@ extern "C" dol_status dol_dtkp_fold_apply2(const dol_dtkp_fold *fold, const dol_
         s_prev = s_last = f->n_out;
         A.max_s = f->n_out > A.max_s ? f->n_out : A.max_s;
     }
+    while (words.size() % 4) words.push_back(0);
     A.n_words = static_cast<int32_t>(words.size());
     const dol_dist *o = fold->out;
     if (o->batch != A.batch || o->n_sym != s_last || o->ld < o->n_sym)
         return fail(DOL_ESHAPE, "out has %d x %d, the fold produces %d x %d", o->batch, o->n_sym, A.batch, s_last);
     const size_t lds = static_cast<size_t>(2) * A.max_s * K * (sizeof(uint64_t) + sizeof(float)) + 64 * sizeof(uint64_t) +
-                       sizeof(float) * (64 + A.max_s) + sizeof(uint32_t) * words.size();
+                       sizeof(float) * (64 + A.max_s) + 16 + sizeof(uint32_t) * words.size();
     if (lds > 64 * 1024) return fail(DOL_EUNSUPPORTED, "the fold needs %zu bytes of LDS per sample, more than 65536", lds);
     if (A.batch == 0) return DOL_OK;
     if (!o->proof_mask || !o->proof_prob || !o->prob) return fail(DOL_EINVAL, "out.proof_mask, out.proof_prob or out.prob is NULL");
