@@ -140,7 +140,7 @@ def _source_of(kernel):
     for fn in sorted(os.listdir(csrc)):
         if fn.endswith(".hip"):
             text = open(os.path.join(csrc, fn)).read()
-            if "\n" + base + "(" in text:
+            if base + "(" in text:      # the definition, or the line that writes it for kernels generated at run time
                 return fn, hashlib.sha256(text.encode()).hexdigest()[:16]
     return None, None
 

@@ -18,11 +18,15 @@ namespace dol {
 constexpr int kDfMax = 32;              // most inputs of one fold
 
 // The symbol side of the whole fold as one array of words, copied into LDS at the start of the kernel:
-//   [0] number of inputs n, then for t = 0 .. n-1 three words: S_t, p_t, r_t
+//   [0] number of inputs n, then for t = 0 .. n-1 four words: S_t, p_t, r_t, fresh_t
 //   t = 0:  S_0 words at p_0: the facts of the first input's symbols
 //   t >= 1: S_t + 1 words at p_t: where each output column's tuples start and end inside the stage's records;
 //           the records at r_t, one per tuple in column order: first operand's symbol | second operand's FACT << 16
 //           (one spare record at the end so that the read-ahead stays inside)
+//   fresh_t = 1: every fact of input t lies above every fact of the inputs before it and shares no exclusion group
+//           with any of them.  A proof of the running Distribution then never holds the new fact or a rival of it, and
+//           the product over ascending facts is the proof's stored probability times the new fact's: the stage needs
+//           no mask at all until its k winners are known.
 struct DtkpFoldArgs {
     int32_t n, batch, n_facts, max_s, n_words;
     const int32_t *words;
@@ -36,6 +40,132 @@ struct DtkpFoldArgs {
     int64_t ldg;
     float *gfact;
 };
+
+// One stage of the fold for this wavefront's sample: the columns of the stage's table, a lane each.  KA: slots of the
+// first operand's lists that can hold a proof (1 right after the natural initialisation); FRESH: see fresh_t above.
+// Absent slots carry the probability -1 in LDS (0 in the result tensors).
+// The list keeps, per rank, the probability and where the proof came from (record, slot of the first operand's list);
+// the masks are put together for the k winners only.  A candidate whose probability differs from every kept one
+// finds its rank by comparing probabilities alone; one that ties (duplicates of a kept proof always do) takes the
+// full comparison of the list's contract.
+template <int K, int KA, bool FRESH>
+__device__ __forceinline__ void dtkp_fold_stage(const DtkpFoldArgs &A, int64_t s, int S, bool last, const uint32_t *l_ptr,
+                                                const uint32_t *l_rec, const uint64_t *cm, const float *cp, uint64_t *nm,
+                                                float *np, const uint64_t *rival, const float *fp, float *gh)
+{
+    const int lane = threadIdx.x;
+    for (int c = lane; c < S; c += kWave) {
+        float tp[K];
+        int tid_[K];
+#pragma unroll
+        for (int x = 0; x < K; ++x) { tp[x] = -1.0f; tid_[x] = -1; }
+        auto mask_of = [&](int id) -> uint64_t {
+            const int q = id / K, x = id - q * K;
+            const uint32_t r = l_rec[q];
+            return cm[static_cast<int>(r & 0xffffu) * K + x] | (uint64_t(1) << (r >> 16));
+        };
+        // the full comparison: equal masks are one proof, order by probability, then by mask
+        auto insert_tied = [&](uint64_t mask, float pr, int id) {
+            uint64_t tm[K];
+            bool dup = false;
+#pragma unroll
+            for (int y = 0; y < K; ++y) {
+                tm[y] = tid_[y] >= 0 ? mask_of(tid_[y]) : kAbsent;
+                dup |= tm[y] == mask;
+            }
+            if (dup || !TopK<K>::before(mask, pr, tm[K - 1], tp[K - 1])) return;
+#pragma unroll
+            for (int y = K - 1; y >= 0; --y) {
+                const bool here = TopK<K>::before(mask, pr, tm[y], tp[y]);
+                const bool above = y > 0 ? TopK<K>::before(mask, pr, tm[y - 1], tp[y - 1]) : false;
+                if (above) { tp[y] = tp[y - 1]; tid_[y] = tid_[y - 1]; }
+                else if (here) { tp[y] = pr; tid_[y] = id; }
+            }
+        };
+        // offer < 0: nothing to offer (below every slot, absent ones included)
+        auto insert_untied = [&](float offer, int id) {
+            bool gt[K];
+#pragma unroll
+            for (int y = 0; y < K; ++y) gt[y] = offer > tp[y];
+#pragma unroll
+            for (int y = K - 1; y >= 0; --y) {
+                const bool above = y > 0 ? gt[y - 1] : false;
+                tp[y] = above ? tp[y - 1] : gt[y] ? offer : tp[y];
+                tid_[y] = above ? tid_[y - 1] : gt[y] ? id : tid_[y];
+            }
+        };
+        const uint32_t q0 = l_ptr[c], q1 = l_ptr[c + 1];
+        uint32_t rec = l_rec[q0];
+        for (uint32_t q = q0; q < q1; ++q) {
+            const int i = static_cast<int>(rec & 0xffffu), fb = static_cast<int>(rec >> 16);
+            rec = l_rec[q + 1];                 // the next tuple's record is on its way while this one is worked on
+            const float pb = 1.0f * fp[fb];
+            if constexpr (FRESH) {
+                float pa[KA];
+#pragma unroll
+                for (int x = 0; x < KA; ++x) pa[x] = cp[i * K + x];
+#pragma unroll
+                for (int x = 0; x < KA; ++x) {
+                    const float offer = pa[x] >= 0.0f ? pa[x] * pb : -2.0f;
+                    const int id = static_cast<int>(q) * K + x;
+                    bool tie = false;
+#pragma unroll
+                    for (int y = 0; y < K; ++y) tie |= offer == tp[y];
+                    if (tie) insert_tied(cm[i * K + x] | (uint64_t(1) << fb), offer, id);
+                    else insert_untied(offer, id);
+                }
+            } else {
+                uint64_t ma[KA];
+                float pa[KA];
+#pragma unroll
+                for (int x = 0; x < KA; ++x) { ma[x] = cm[i * K + x]; pa[x] = cp[i * K + x]; }
+                const uint64_t mb = uint64_t(1) << fb, bad = rival[fb];
+                // kept proofs hold at most one fact per exclusion group, so the union is inconsistent exactly when
+                // the first operand's proof holds a rival of the one fact the second brings.  The product over
+                // ascending facts is unchanged when the fact is already there, takes one more factor when it lies
+                // above every fact of the proof (ma < mb as integers), and is redone from scratch otherwise.
+#pragma unroll
+                for (int x = 0; x < KA; ++x) {
+                    const bool ok = ma[x] != kAbsent && !(ma[x] & bad);
+                    const bool plain = (ma[x] & mb) || ma[x] < mb;
+                    float pr = (ma[x] & mb) ? pa[x] : pa[x] * pb;
+                    if (ok && !plain) pr = proof_prob(ma[x] | mb, fp);
+                    const int id = static_cast<int>(q) * K + x;
+                    bool tie = false;
+#pragma unroll
+                    for (int y = 0; y < K; ++y) tie |= pr == tp[y];
+                    if (ok && tie) insert_tied(ma[x] | mb, pr, id);
+                    else insert_untied(ok ? pr : -2.0f, id);
+                }
+            }
+        }
+        float sum = 0.0f;
+        uint64_t wm[K];
+        float wp[K];
+#pragma unroll
+        for (int x = 0; x < K; ++x) {
+            const bool present = tid_[x] >= 0;
+            wm[x] = present ? mask_of(tid_[x]) : kAbsent;
+            wp[x] = present ? tp[x] : 0.0f;
+            nm[c * K + x] = wm[x];
+            np[c * K + x] = present ? tp[x] : -1.0f;
+            if (present) sum = sum + tp[x];
+        }
+        if (last) {
+            const int64_t o = (s * S + c) * K;
+#pragma unroll
+            for (int x = 0; x < K; ++x) { A.om[o + x] = wm[x]; A.op[o + x] = wp[x]; }
+            const float pr = fminf(sum, 1.0f);
+            A.oprob[s * A.ldo + c] = pr;
+            if (A.gfact) {                      // upstream gradient, gated by the clamp (passes on sum <= 1)
+                float g;
+                if (A.target) g = c == A.target[s] ? -1.0f / fmaxf(pr, FLT_MIN) : 0.0f;
+                else g = A.gout[s * A.ldg + c];
+                gh[c] = sum <= 1.0f ? g : 0.0f;
+            }
+        }
+    }
+}
 
 template <int K>
 __global__ void __launch_bounds__(kWave)
@@ -80,7 +210,7 @@ dtkp_fold_kernel(const DtkpFoldArgs A)
             bufm[i * K] = uint64_t(1) << f;
             bufp[i * K] = 1.0f * fp[f];
 #pragma unroll
-            for (int x = 1; x < K; ++x) { bufm[i * K + x] = kAbsent; bufp[i * K + x] = 0.0f; }
+            for (int x = 1; x < K; ++x) { bufm[i * K + x] = kAbsent; bufp[i * K + x] = -1.0f; }
         }
     }
     wave_lds_fence();
@@ -90,101 +220,15 @@ dtkp_fold_kernel(const DtkpFoldArgs A)
         const float *cp = bufp + ((t - 1) & 1) * A.max_s * K;
         uint64_t *nm = bufm + (t & 1) * A.max_s * K;
         float *np = bufp + (t & 1) * A.max_s * K;
-        S = static_cast<int>(w[1 + 3 * t]);
-        const uint32_t *l_ptr = w + w[2 + 3 * t], *l_rec = w + w[3 + 3 * t];
-        const bool last = t == A.n - 1;
-        for (int c = lane; c < S; c += kWave) {
-            // The list keeps, per rank, the probability and where the proof came from (record, slot of the first
-            // operand's list); the masks are put together again for the k winners only.  A candidate whose
-            // probability differs from every kept one finds its rank by comparing probabilities alone; one that ties
-            // (duplicates of a kept proof always do) takes the full comparison of the list's contract.
-            float tp[K];
-            int tid_[K];
-#pragma unroll
-            for (int x = 0; x < K; ++x) { tp[x] = -1.0f; tid_[x] = -1; }
-            auto mask_of = [&](int id) -> uint64_t {
-                const int q = id / K, x = id - q * K;
-                const uint32_t r = l_rec[q];
-                return cm[static_cast<int>(r & 0xffffu) * K + x] | (uint64_t(1) << (r >> 16));
-            };
-            const uint32_t q0 = l_ptr[c], q1 = l_ptr[c + 1];
-            uint32_t rec = l_rec[q0];
-            for (uint32_t q = q0; q < q1; ++q) {
-                const int i = static_cast<int>(rec & 0xffffu), fb = static_cast<int>(rec >> 16);
-                rec = l_rec[q + 1];             // the next tuple's record is on its way while this one is worked on
-                uint64_t ma[K];
-                float pa[K];
-#pragma unroll
-                for (int x = 0; x < K; ++x) { ma[x] = cm[i * K + x]; pa[x] = cp[i * K + x]; }
-                const uint64_t mb = uint64_t(1) << fb, bad = rival[fb];
-                const float pb = 1.0f * fp[fb];
-                // kept proofs hold at most one fact per exclusion group, so the union is inconsistent exactly when
-                // the first operand's proof holds a rival of the one fact the second brings.  The product over
-                // ascending facts is unchanged when the fact is already there, takes one more factor when it lies
-                // above every fact of the proof (ma < mb as integers), and is redone from scratch otherwise.
-#pragma unroll
-                for (int x = 0; x < K; ++x) {
-                    const bool ok = ma[x] != kAbsent && !(ma[x] & bad);
-                    const bool plain = (ma[x] & mb) || ma[x] < mb;
-                    float pr = (ma[x] & mb) ? pa[x] : pa[x] * pb;
-                    if (ok && !plain) pr = proof_prob(ma[x] | mb, fp);
-                    const int id = static_cast<int>(q) * K + x;
-                    bool tie = false;
-#pragma unroll
-                    for (int y = 0; y < K; ++y) tie |= pr == tp[y];
-                    if (ok && tie) {
-                        const uint64_t mask = ma[x] | mb;
-                        uint64_t tm[K];
-                        bool dup = false;
-#pragma unroll
-                        for (int y = 0; y < K; ++y) {
-                            tm[y] = tid_[y] >= 0 ? mask_of(tid_[y]) : kAbsent;
-                            dup |= tm[y] == mask;
-                        }
-                        if (!dup && TopK<K>::before(mask, pr, tm[K - 1], tp[K - 1])) {
-#pragma unroll
-                            for (int y = K - 1; y >= 0; --y) {
-                                const bool here = TopK<K>::before(mask, pr, tm[y], tp[y]);
-                                const bool above = y > 0 ? TopK<K>::before(mask, pr, tm[y - 1], tp[y - 1]) : false;
-                                if (above) { tp[y] = tp[y - 1]; tid_[y] = tid_[y - 1]; }
-                                else if (here) { tp[y] = pr; tid_[y] = id; }
-                            }
-                        }
-                    } else {
-                        const float offer = ok ? pr : -2.0f;        // below every slot, absent ones (-1) included
-                        bool gt[K];
-#pragma unroll
-                        for (int y = 0; y < K; ++y) gt[y] = offer > tp[y];
-#pragma unroll
-                        for (int y = K - 1; y >= 0; --y) {
-                            const bool above = y > 0 ? gt[y - 1] : false;
-                            tp[y] = above ? tp[y - 1] : gt[y] ? offer : tp[y];
-                            tid_[y] = above ? tid_[y - 1] : gt[y] ? id : tid_[y];
-                        }
-                    }
-                }
-            }
-            float sum = 0.0f;
-#pragma unroll
-            for (int x = 0; x < K; ++x) {
-                const bool present = tid_[x] >= 0;
-                nm[c * K + x] = present ? mask_of(tid_[x]) : kAbsent;
-                np[c * K + x] = present ? tp[x] : 0.0f;
-                if (present) sum = sum + tp[x];
-            }
-            if (last) {
-                const int64_t o = (s * S + c) * K;
-#pragma unroll
-                for (int x = 0; x < K; ++x) { A.om[o + x] = nm[c * K + x]; A.op[o + x] = np[c * K + x]; }
-                const float pr = fminf(sum, 1.0f);
-                A.oprob[s * A.ldo + c] = pr;
-                if (A.gfact) {                  // upstream gradient, gated by the clamp (passes on sum <= 1)
-                    float g;
-                    if (A.target) g = c == A.target[s] ? -1.0f / fmaxf(pr, FLT_MIN) : 0.0f;
-                    else g = A.gout[s * A.ldg + c];
-                    gh[c] = sum <= 1.0f ? g : 0.0f;
-                }
-            }
+        S = static_cast<int>(w[1 + 4 * t]);
+        const uint32_t *l_ptr = w + w[2 + 4 * t], *l_rec = w + w[3 + 4 * t];
+        const bool last = t == A.n - 1, fresh = w[4 + 4 * t] != 0;
+        if (t == 1) {                       // the first operand is naturally initialised: one proof per symbol
+            if (fresh) dtkp_fold_stage<K, 1, true>(A, s, S, last, l_ptr, l_rec, cm, cp, nm, np, rival, fp, gh);
+            else dtkp_fold_stage<K, 1, false>(A, s, S, last, l_ptr, l_rec, cm, cp, nm, np, rival, fp, gh);
+        } else {
+            if (fresh) dtkp_fold_stage<K, K, true>(A, s, S, last, l_ptr, l_rec, cm, cp, nm, np, rival, fp, gh);
+            else dtkp_fold_stage<K, K, false>(A, s, S, last, l_ptr, l_rec, cm, cp, nm, np, rival, fp, gh);
         }
         wave_lds_fence();
     }
@@ -227,9 +271,11 @@ extern "C" dol_status dol_dtkp_fold_apply2(const dol_dtkp_fold *fold, const dol_
     DtkpFoldArgs A{};
     A.n = n;
     A.n_facts = prov->n_facts;
-    std::vector<int32_t> words(1 + 3 * static_cast<size_t>(n), 0);
+    std::vector<int32_t> words(1 + 4 * static_cast<size_t>(n), 0);
     words[0] = n;
     int32_t s_prev = 0, s_last = 0;
+    int32_t fact_hi = -1;                   // highest fact of the inputs so far
+    uint64_t facts_seen = 0;
     for (int t = 0; t < n; ++t) {
         const dol_dist *d = fold->inputs[t];
         if (!d) return fail(DOL_EINVAL, "inputs[%d] is NULL", t);
@@ -241,6 +287,20 @@ extern "C" dol_status dol_dtkp_fold_apply2(const dol_dtkp_fold *fold, const dol_
         for (int32_t i = 0; i < d->n_sym; ++i)
             if (fos[i] < 0 || fos[i] >= prov->n_facts)
                 return fail(DOL_EINVAL, "fact_of_sym[%d][%d] = %d outside 0..%d", t, i, fos[i], prov->n_facts - 1);
+        {   // fresh_t: this input's facts lie above every earlier fact and share no exclusion group with one
+            bool fresh = true;
+            uint64_t mine = 0;
+            for (int32_t i = 0; i < d->n_sym; ++i) {
+                fresh = fresh && fos[i] > fact_hi;
+                mine |= uint64_t(1) << fos[i];
+            }
+            for (int f = 0; f < prov->n_facts && prov->fact_group && fresh; ++f)
+                for (int h = 0; h < prov->n_facts && ((mine >> f) & 1); ++h)
+                    if (((facts_seen >> h) & 1) && prov->fact_group[h] == prov->fact_group[f]) fresh = false;
+            words[4 + 4 * t] = fresh ? 1 : 0;
+            for (int32_t i = 0; i < d->n_sym; ++i) fact_hi = std::max(fact_hi, fos[i]);
+            facts_seen |= mine;
+        }
         if (t == 0) {
             words[1] = d->n_sym;
             words[2] = static_cast<int32_t>(words.size());
@@ -255,10 +315,10 @@ extern "C" dol_status dol_dtkp_fold_apply2(const dol_dtkp_fold *fold, const dol_
         if (f->n_out < 1) return fail(DOL_EUNSUPPORTED, "tables[%d] produces no symbol", t - 1);
         if (words.size() + static_cast<size_t>(f->n_out) + static_cast<size_t>(f->n_tuples) + 2 > 16000)
             return fail(DOL_EUNSUPPORTED, "the tables of the fold do not fit in LDS");
-        words[1 + 3 * t] = f->n_out;
-        words[2 + 3 * t] = static_cast<int32_t>(words.size());
+        words[1 + 4 * t] = f->n_out;
+        words[2 + 4 * t] = static_cast<int32_t>(words.size());
         words.insert(words.end(), f->h_col_ptr.begin(), f->h_col_ptr.begin() + f->n_out + 1);
-        words[3 + 3 * t] = static_cast<int32_t>(words.size());
+        words[3 + 4 * t] = static_cast<int32_t>(words.size());
         for (int64_t q = 0; q < f->n_tuples; ++q) {
             const uint32_t ij = f->h_col_ij[static_cast<size_t>(q)];
             words.push_back(static_cast<int32_t>((ij & 0xffffu) | (static_cast<uint32_t>(fos[ij >> 16]) << 16)));

@@ -344,6 +344,40 @@ def test_config4_fused_dtkp_fold(gp, dol, batch, n, k):
     np.testing.assert_array_equal(host(out3.proof_mask), host(prog.out.proof_mask))
 
 
+@pytest.mark.parametrize("k", [1, 3, 8])
+def test_fused_dtkp_fold_when_a_stage_brings_no_new_facts(dol, k):
+    """The fused fold with inputs whose facts are not new to the fold: facts below the ones already in the proofs (the
+    product over ascending facts is then redone, not continued), an input given twice (the same fact is idempotent, a
+    rival of it excludes the proof), an input that shares its exclusion group with an earlier one under other facts,
+    and one with new facts again.  Against the oracle's operator-by-operator composition, bit for bit."""
+    batch, nv = 70, 4
+    fact_sets = [8 + np.arange(nv), 4 + np.arange(nv), 8 + np.arange(nv), np.arange(nv), 12 + np.arange(nv), 16 + np.arange(nv)]
+    n_facts = 20
+    grp = (np.arange(n_facts) // nv).astype(np.int32)
+    grp[16:20] = grp[0:4]                    # the last input's facts are rivals of the fourth input's
+    fp = W.uniform01(77, batch * n_facts).astype(np.float32).reshape(batch, n_facts)
+    fp[:, 5] = fp[:, 6]                      # equal probabilities: ties decided by the masks
+    fp[3] = 0.0
+    sym = np.arange(nv, dtype=np.int32)
+    m, pp, pr = oracle.dtkp_init(fact_sets[0].astype(np.int32), fp, k)
+    syms, tables = sym, []
+    for t in range(1, len(fact_sets)):
+        dm, _, _ = oracle.dtkp_init(fact_sets[t].astype(np.int32), fp, k)
+        tab = W.sum_table(syms, sym)
+        syms, m, pp, pr = oracle.dtkp_apply2(oracle.dense_to_triples(tab), syms.size, nv, k, grp, fp, m, dm)
+        tables.append(dol.FnTable.create_dense(tab))
+    prov = dol.Prov(dol.DTKP, k, dev(fp), grp)
+    digits = [dol.Dist(sym, torch.empty((batch, nv), device="cuda")) for _ in fact_sets]
+    out = dol.Dist.empty(syms, batch, k=k)
+    g = W.normal(9, batch * syms.size).astype(np.float32).reshape(batch, -1)
+    gf = torch.empty((batch, n_facts), device="cuda")
+    dol.dtkp_fold_apply2(dol.DtkpFold(digits, [f.astype(np.int32) for f in fact_sets], tables, out, grad_out=dev(g), grad_fact_prob=gf), prov)
+    np.testing.assert_array_equal(host(out.proof_mask).view(np.uint64), m)
+    np.testing.assert_array_equal(host(out.proof_prob), pp)
+    assert_close(host(out.prob), pr, "fold tag prob")
+    assert_close(host(gf), oracle.dtkp_prob_bwd(m, fp, g), "fold gradient")
+
+
 # ---------------------------------------------------------------- config 5
 
 @pytest.mark.parametrize("batch,side,rounds", [(256, 32, 64), (33, 7, 20), (2, 3, 5)])
