@@ -125,6 +125,19 @@ std::string chain_source(const std::vector<int> &shape, int kL)
     o("  const long long wg = (long long)(xcd * per + (xcd < rem ? xcd : rem) + (id >> 3));\n");
     o("  const long long s_raw = wg * %d + q;\n  const bool live = s_raw < A.batch;\n  const long long s = live ? s_raw : A.batch - 1;\n", kSP);
     o("  float *base = lds + q * %d;\n", Y.stride);
+    // A stage's rows are addressed through an index the compiler cannot see through: every access of the stage is
+    // then that register plus a small immediate (one instruction), where a folded constant beyond the reach of the
+    // two-word LDS instructions' offset field would cost an address addition per access.
+    o("  const int qb = q * %d;\n", 4 * Y.stride);
+    {
+        bool used[64] = {};
+        used[0] = true;
+        for (int t = 1; t < n; ++t) { used[Y.w[t]] = true; used[ceil_div(Y.m[t - 1], kL)] = true; }
+        for (int x = 0; x < 64; ++x)
+            if (used[x]) o("  const int lw%d = l * %d;\n", x, 4 * x);
+    }
+    o("#define DOL_ROW(name, start, step) int name##_i = qb + 4 * (start) + lw##step; asm volatile(\"\" : \"+v\"(name##_i)); "
+      "float *name = reinterpret_cast<float *>(reinterpret_cast<char *>(lds) + name##_i)\n");
     // ---- zeros where a window may reach beyond what is written
     {
         int pos = 0;
@@ -158,15 +171,15 @@ std::string chain_source(const std::vector<int> &shape, int kL)
     // ---- forward sweep
     for (int t = 1; t < n; ++t) {
         const int nb = Y.nb[t], w = Y.w[t], win = w + nb - 1;
-        o("  {\n    const float *rp = base + %d + l * %d;\n", Y.off[t - 1] - (nb - 1), w);
-        for (int j = 0; j < nb; ++j) o("    const float d%d = base[%d];\n", j, Y.off_d + t * kNBR + j);
+        o("  {\n    DOL_ROW(rp, %d, %d); DOL_ROW(dp, %d, 0);\n", Y.off[t - 1] - (nb - 1), w, Y.off_d + t * kNBR);
+        for (int j = 0; j < nb; ++j) o("    const float d%d = dp[%d];\n", j, j);
         for (int k = 0; k < win; ++k) o("    const float r%d = __builtin_fabsf(rp[%d]);\n", k, k);
         for (int k = 0; k < w; ++k) {
             // column c = l * w + k: ascending i = c - j, one fma per tuple
             o("    float p%d = 0.0f;\n", k);
             for (int j = nb - 1; j >= 0; --j) o("    p%d = __builtin_fmaf(r%d, d%d, p%d);\n", k, k + (nb - 1) - j, j, k);
         }
-        o("    float *wp = base + %d + l * %d;\n", Y.off[t], w);
+        o("    DOL_ROW(wp, %d, %d);\n", Y.off[t], w);
         for (int k = 0; k < w; ++k) o("    wp[%d] = p%d <= 1.0f ? p%d : -1.0f;\n", k, k, k);
         o("  }\n  fence();\n");
     }
@@ -193,12 +206,12 @@ std::string chain_source(const std::vector<int> &shape, int kL)
     for (int t = n1; t >= 1; --t) {
         const int nb = Y.nb[t], m = Y.m[t - 1], v = ceil_div(m, kL), win = v + nb - 1;
         const int g_cur = (n1 - t) & 1 ? Y.off_g1 : Y.off_g0, g_nxt = (n1 - t) & 1 ? Y.off_g0 : Y.off_g1;
-        o("  {\n    const float *gp = base + %d + l * %d, *ap = base + %d + l * %d;\n", g_cur, v, Y.off[t - 1], v);
-        for (int j = 0; j < nb; ++j) o("    const float d%d = base[%d];\n", j, Y.off_d + t * kNBR + j);
+        o("  {\n    DOL_ROW(gp, %d, %d); DOL_ROW(ap, %d, %d); DOL_ROW(dp, %d, 0);\n", g_cur, v, Y.off[t - 1], v, Y.off_d + t * kNBR);
+        for (int j = 0; j < nb; ++j) o("    const float d%d = dp[%d];\n", j, j);
         for (int k = 0; k < win; ++k) o("    const float g%d = gp[%d];\n", k, k);
         for (int k = 0; k < v; ++k) o("    const float x%d = ap[%d];\n", k, k);
         for (int j = 0; j < nb; ++j) o("    float s%d = 0.0f;\n", j);
-        o("    float *wp = base + %d + l * %d;\n", g_nxt, v);
+        o("    DOL_ROW(wp, %d, %d);\n", g_nxt, v);
         for (int k = 0; k < v; ++k) {
             o("    { float acc = 0.0f;\n");
             for (int j = 0; j < nb; ++j) o("      acc = __builtin_fmaf(g%d, d%d, acc);\n", k + j, j);
@@ -215,9 +228,11 @@ std::string chain_source(const std::vector<int> &shape, int kL)
                 o("    %s base[%d + l] = 0.0f;\n", need - x >= kL ? "" : (std::string("if (l < ") + std::to_string(need - x) + ")").c_str(), g_nxt + x);
         }
         // the short operand's gradient: sum of the lanes' shares; it takes the place of the operand's row, which is spent
-        for (int j = 0; j < nb; ++j) o("    s%d = sum_lanes(s%d);\n", j, j);
+        // (the empty asm keeps the last addition in front of the branch, where it takes its operand straight from the
+        // other lane; inside the branch, with one lane live, it would need a separate move)
+        for (int j = 0; j < nb; ++j) o("    s%d = sum_lanes(s%d); asm volatile(\"\" : \"+v\"(s%d));\n", j, j, j);
         o("    if (l == %d) {\n", kL == 32 ? 16 : 0);
-        for (int j = 0; j < nb; ++j) o("      base[%d] = s%d;\n", Y.off_d + t * kNBR + j, j);
+        for (int j = 0; j < nb; ++j) o("      dp[%d] = s%d;\n", j, j);
         o("    }\n  }\n  fence();\n");
     }
     // ---- gradients out
