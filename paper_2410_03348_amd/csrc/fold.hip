@@ -607,7 +607,7 @@ extern "C" const char *dol_fold_kernel(const dol_fold *fold)
     static thread_local char name[64];
     FoldPlan P;
     if (fold_prepare(fold, P) != DOL_OK) return "";
-    if (fold_chain_ok(P.A.n, P.A.m, P.A.nb)) return "damp_fold_chain_kernel";
+    if (fold_chain_ok(P.A.n, P.A.m, P.A.nb, P.A.ld, P.A.ldo, P.A.ldg)) return "damp_fold_chain_kernel";
     if (P.wide) snprintf(name, sizeof name, "damp_fold4_kernel<%d, 32>", P.nbp);
     else snprintf(name, sizeof name, "damp_fold_kernel<%d>", P.nbp);
     return name;
@@ -619,7 +619,7 @@ extern "C" dol_status dol_fold_apply2(const dol_fold *fold, void *hip_stream)
     if (dol_status s = fold_prepare(fold, P)) return s;
     const FoldArgs &A = P.A;
     if (A.batch == 0) return DOL_OK;
-    if (fold_chain_ok(A.n, A.m, A.nb))      // the sweep written for this chain's shape
+    if (fold_chain_ok(A.n, A.m, A.nb, A.ld, A.ldo, A.ldg))      // the sweep written for this chain's shape
         return launch_fold_chain(A.n, A.m, A.nb, A.batch, A.in, A.ld, A.gin, A.out, A.ldo, A.target, A.gout, A.ldg, A.backward,
                                  static_cast<hipStream_t>(hip_stream));
     const unsigned grid = P.grid;

@@ -102,8 +102,9 @@ std::string chain_source(const std::vector<int> &shape, int kL)
     const int n = Y.n, n1 = n - 1;
     Src o;
     o("typedef unsigned long long u64;\n");
-    o("struct Args { int batch; int backward; const float *in[%d]; long long ld[%d]; float *gin[%d]; float *out; long long ldo; "
-      "const int *target; const float *gout; long long ldg; };\n", kFoldChainMax, kFoldChainMax, kFoldChainMax);
+    // (leading dimensions as 32-bit words: a row's offset is then one 32 x 32 -> 64 bit multiply-add)
+    o("struct Args { int batch; int backward; const float *in[%d]; int ld[%d]; float *gin[%d]; float *out; int ldo; "
+      "const int *target; const float *gout; int ldg; };\n", kFoldChainMax, kFoldChainMax, kFoldChainMax);
     o("__device__ __forceinline__ void fence() { __builtin_amdgcn_fence(__ATOMIC_RELEASE, \"wavefront\"); __builtin_amdgcn_wave_barrier(); "
       "__builtin_amdgcn_fence(__ATOMIC_ACQUIRE, \"wavefront\"); }\n");
     o("__device__ __forceinline__ float dppx(float x, int which) {\n"
@@ -123,7 +124,7 @@ std::string chain_source(const std::vector<int> &shape, int kL)
     // workgroups are dealt round-robin to the 8 XCDs: give every XCD a contiguous range of samples
     o("  const unsigned id = blockIdx.x, nwg = gridDim.x, xcd = id & 7u, per = nwg >> 3, rem = nwg & 7u;\n");
     o("  const long long wg = (long long)(xcd * per + (xcd < rem ? xcd : rem) + (id >> 3));\n");
-    o("  const long long s_raw = wg * %d + q;\n  const bool live = s_raw < A.batch;\n  const long long s = live ? s_raw : A.batch - 1;\n", kSP);
+    o("  const long long s_raw = wg * %d + q;\n  const bool live = s_raw < A.batch;\n  const int s = (int)(live ? s_raw : A.batch - 1);\n", kSP);
     o("  float *base = lds + q * %d;\n", Y.stride);
     // A stage's rows are addressed through an index the compiler cannot see through: every access of the stage is
     // then that register plus a small immediate (one instruction), where a folded constant beyond the reach of the
@@ -154,8 +155,8 @@ std::string chain_source(const std::vector<int> &shape, int kL)
         for (int t = 0; t < n; ++t) {
             const int cnt = t == 0 ? Y.m[0] : Y.nb[t];
             for (int x = 0; x < kSP * cnt; x += 64, ++slot) {
-                o("  float in%d = 0.0f; { const int e = lane + %d; if (e < %d) { const int qq = e / %d, i = e - qq * %d; long long ss = wg * %d + qq; "
-                  "ss = ss < A.batch ? ss : A.batch - 1; in%d = A.in[%d][ss * A.ld[%d] + i]; } }\n", slot, x, kSP * cnt, cnt, cnt, kSP, slot, t, t);
+                o("  float in%d = 0.0f; { const int e = lane + %d; if (e < %d) { const int qq = e / %d, i = e - qq * %d; long long sr = wg * %d + qq; "
+                  "const int ss = (int)(sr < A.batch ? sr : A.batch - 1); in%d = A.in[%d][(long long)ss * A.ld[%d] + i]; } }\n", slot, x, kSP * cnt, cnt, cnt, kSP, slot, t, t);
             }
         }
         slot = 0;
@@ -184,13 +185,13 @@ std::string chain_source(const std::vector<int> &shape, int kL)
         o("  }\n  fence();\n");
     }
     // ---- the result
-    o("  if (A.out && live) { float *os = A.out + s * A.ldo;\n");
+    o("  if (A.out && live) { float *os = A.out + (long long)s * A.ldo;\n");
     for (int x = 0; x < Y.m[n1]; x += kL)
         o("    %s os[%d + l] = __builtin_fabsf(base[%d + l]);\n", Y.m[n1] - x >= kL ? "" : (std::string("if (l < ") + std::to_string(Y.m[n1] - x) + ")").c_str(),
           x, Y.off[n1] + x);
     o("  }\n  if (!A.backward) return;\n");
     // ---- upstream gradient into the first gradient row, gated by the last stage's clamp
-    o("  { const int tgt = A.target ? A.target[s] : -1; const float *gs = A.gout + s * A.ldg;\n");
+    o("  { const int tgt = A.target ? A.target[s] : -1; const float *gs = A.gout + (long long)s * A.ldg;\n");
     for (int x = 0; x < Y.g_len; x += kL) {
         const bool whole = Y.g_len - x >= kL;
         o("    %s{ const int c = %d + l; float gv = 0.0f;\n", whole ? "" : (std::string("if (l < ") + std::to_string(Y.g_len - x) + ") ").c_str(), x);
@@ -216,8 +217,12 @@ std::string chain_source(const std::vector<int> &shape, int kL)
             o("    { float acc = 0.0f;\n");
             for (int j = 0; j < nb; ++j) o("      acc = __builtin_fmaf(g%d, d%d, acc);\n", k + j, j);
             // rows past the operand's last symbol hold 0; a row whose own sum was clamped (sign) passes no gradient on
-            if (t > 1) o("      wp[%d] = (l * %d + %d < %d && !(x%d < 0.0f)) ? acc : 0.0f;\n", k, v, k, m, k);
-            else o("      wp[%d] = l * %d + %d < %d ? acc : 0.0f;\n", k, v, k, m);
+            // (only the last lanes' last rows can lie past the end: the test is written where that can happen)
+            const bool past = (kL - 1) * v + k >= m;
+            if (t > 1 && past) o("      wp[%d] = (l * %d + %d < %d && !(x%d < 0.0f)) ? acc : 0.0f;\n", k, v, k, m, k);
+            else if (t > 1) o("      wp[%d] = !(x%d < 0.0f) ? acc : 0.0f;\n", k, k);
+            else if (past) o("      wp[%d] = l * %d + %d < %d ? acc : 0.0f;\n", k, v, k, m);
+            else o("      wp[%d] = acc;\n", k);
             for (int j = 0; j < nb; ++j) o("      s%d = __builtin_fmaf(g%d, __builtin_fabsf(x%d), s%d);\n", j, k + j, k, j);
             o("    }\n");
         }
@@ -239,13 +244,13 @@ std::string chain_source(const std::vector<int> &shape, int kL)
     o("  if (!live) return;\n");
     {
         const int g_fin = (n1 & 1) ? Y.off_g1 : Y.off_g0;        // after n - 1 swaps
-        o("  if (A.gin[0]) { float *dst = A.gin[0] + s * A.ld[0];\n");
+        o("  if (A.gin[0]) { float *dst = A.gin[0] + (long long)s * A.ld[0];\n");
         for (int x = 0; x < Y.m[0]; x += kL)
             o("    %s dst[%d + l] = base[%d + l];\n", Y.m[0] - x >= kL ? "" : (std::string("if (l < ") + std::to_string(Y.m[0] - x) + ")").c_str(), x,
               g_fin + x);
         o("  }\n");
         for (int t = 1; t < n; ++t)
-            o("  if (A.gin[%d] && l < %d) A.gin[%d][s * A.ld[%d] + l] = base[%d + l];\n", t, Y.nb[t], t, t, Y.off_d + t * kNBR);
+            o("  if (A.gin[%d] && l < %d) A.gin[%d][(long long)s * A.ld[%d] + l] = base[%d + l];\n", t, Y.nb[t], t, t, Y.off_d + t * kNBR);
     }
     o("}\n");
     return o.s;
@@ -260,20 +265,23 @@ struct ChainKernel {
 struct ChainArgs {
     int32_t batch, backward;
     const float *in[kFoldChainMax];
-    int64_t ld[kFoldChainMax];
+    int32_t ld[kFoldChainMax];
     float *gin[kFoldChainMax];
     float *out;
-    int64_t ldo;
+    int32_t ldo;
     const int32_t *target;
     const float *gout;
-    int64_t ldg;
+    int32_t ldg;
 };
 
 }  // namespace
 
-bool fold_chain_ok(int n, const int32_t *m, const int32_t *nb)
+bool fold_chain_ok(int n, const int32_t *m, const int32_t *nb, const int64_t *ld, int64_t ldo, int64_t ldg)
 {
     if (n < 2 || n > kFoldChainMax) return false;
+    for (int t = 0; t < n; ++t)
+        if (ld[t] > INT32_MAX) return false;
+    if (ldo > INT32_MAX || ldg > INT32_MAX) return false;
     std::vector<int> shape{n, m[0]};
     for (int t = 1; t < n; ++t) {
         if (nb[t] < 1 || nb[t] > kNBR) return false;
@@ -314,8 +322,8 @@ dol_status launch_fold_chain(int n, const int32_t *m, const int32_t *nb, int32_t
     }
     ChainArgs A{};
     A.batch = batch, A.backward = backward;
-    for (int t = 0; t < n; ++t) { A.in[t] = in[t]; A.ld[t] = ld[t]; A.gin[t] = gin ? gin[t] : nullptr; }
-    A.out = out, A.ldo = ldo, A.target = target, A.gout = gout, A.ldg = ldg;
+    for (int t = 0; t < n; ++t) { A.in[t] = in[t]; A.ld[t] = static_cast<int32_t>(ld[t]); A.gin[t] = gin ? gin[t] : nullptr; }
+    A.out = out, A.ldo = static_cast<int32_t>(ldo), A.target = target, A.gout = gout, A.ldg = static_cast<int32_t>(ldg);
     void *args[] = {&A};
     const unsigned grid = static_cast<unsigned>((static_cast<int64_t>(batch) + kSP - 1) / kSP);
     DOL_HIP(hipModuleLaunchKernel(fn, grid, 1, 1, 64, 1, 1, 0, st, args, nullptr));

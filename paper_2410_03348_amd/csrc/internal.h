@@ -253,7 +253,7 @@ dol_status jit_compile(const std::string &src, const char *name, hipModule_t *mo
 // A fold of convolution-shaped applies as code written for the chain's shape (fold_chain.hip): m[t] = symbols of the t-th
 // running Distribution, nb[t] = symbols of input t >= 1.
 constexpr int kFoldChainMax = 32;
-bool fold_chain_ok(int n, const int32_t *m, const int32_t *nb);
+bool fold_chain_ok(int n, const int32_t *m, const int32_t *nb, const int64_t *ld, int64_t ldo, int64_t ldg);
 dol_status launch_fold_chain(int n, const int32_t *m, const int32_t *nb, int32_t batch, const float *const *in, const int64_t *ld,
                              float *const *gin, float *out, int64_t ldo, const int32_t *target, const float *gout, int64_t ldg,
                              int32_t backward, hipStream_t st);
