@@ -167,6 +167,8 @@ damp_iterate_fwd_kernel(const ItFwdArgs A)
 struct ItBwdArgs {
     int32_t batch, na, nb, rounds, every;   // every: rounds per segment (the checkpoint interval)
     int32_t n_tuples, n_long;
+    int32_t shares_in_seg;                  // every tuple's share lives in a register during the sweep: the LDS words they
+                                            // are gathered through at the end take the place of the (then spent) segment
     const uint32_t *col_ptr, *col_ij, *rowa_ptr, *rowa_jc, *rowb_ptr, *rowb_pos, *long_rows;
     const float *e;
     int64_t lde;
@@ -213,8 +215,8 @@ damp_iterate_bwd_kernel(const ItBwdArgs A)
     float *seg = lds;
     float *gA = seg + static_cast<size_t>(A.every + 1) * na1, *gB = gA + na1;
     float *le = gB + na1;
-    float *share_buf = le + nb + 1;
-    float *red = share_buf + A.n_tuples;            // two arrays of T / 64
+    float *share_buf = A.shares_in_seg ? seg : le + nb + 1;
+    float *red = A.shares_in_seg ? le + nb + 1 : share_buf + A.n_tuples;    // two arrays of T / 64
     const int tid = threadIdx.x;
     const int64_t s = blockIdx.x;
     const int64_t plane = static_cast<int64_t>(A.batch) * na;
@@ -228,7 +230,8 @@ damp_iterate_bwd_kernel(const ItBwdArgs A)
         return;
     }
     for (int j = tid; j <= nb; j += T) le[j] = j < nb ? e_row[j] : 0.0f;
-    for (int q = tid; q < A.n_tuples; q += T) share_buf[q] = 0.0f;
+    if (!A.shares_in_seg)
+        for (int q = tid; q < A.n_tuples; q += T) share_buf[q] = 0.0f;
     for (int c = tid; c < na; c += T) gA[c] = gs[c];
     if (tid == 0) {
         gA[na] = 0.0f; gB[na] = 0.0f;
@@ -404,9 +407,21 @@ dol_status check_r0(const dol_dist *r0, const dol_dist *e, const dol_fn_table *f
 
 static size_t fwd_lds(const dol_fn_table *f) { return sizeof(float) * (2 * static_cast<size_t>(f->na) + f->nb + 3); }
 
+// Tuples of a thread's rows kept in registers by the launch shape chosen for a first operand of na symbols.
+static int cached_tuples(int32_t na) { return na <= 1024 ? 6 : 3; }
+
+// The shares of d loss / d e can wait in registers alone when no row has more tuples than the registers hold; the
+// words they are gathered through at the end then fit where the segment was.
+static bool shares_in_seg(const dol_fn_table *f, int32_t every)
+{
+    return f->max_rowa_len <= cached_tuples(f->na) && f->long_rows.n == 0 &&
+           static_cast<size_t>(f->n_tuples) <= (static_cast<size_t>(every) + 1) * (f->na + 1);
+}
+
 static size_t bwd_lds(const dol_fn_table *f, int32_t every)
 {
-    return sizeof(float) * ((static_cast<size_t>(every) + 3) * (f->na + 1) + f->nb + 1 + static_cast<size_t>(f->n_tuples) + 2 * 16);
+    const size_t shares = shares_in_seg(f, every) ? 0 : static_cast<size_t>(f->n_tuples);
+    return sizeof(float) * ((static_cast<size_t>(every) + 3) * (f->na + 1) + f->nb + 1 + shares + 2 * 16);
 }
 
 // Launch shape by the width of the first operand and the batch: threads per workgroup, columns per thread, tuples in
@@ -464,6 +479,7 @@ dol_status launch_iterate_bwd(const dol_dist *e, const dol_fn_table *f, int32_t 
     ItBwdArgs A{};
     A.batch = e->batch, A.na = f->na, A.nb = f->nb, A.rounds = rounds, A.every = every;
     A.n_tuples = static_cast<int32_t>(f->n_tuples), A.n_long = static_cast<int32_t>(f->long_rows.n);
+    A.shares_in_seg = shares_in_seg(f, every) ? 1 : 0;
     A.col_ptr = f->col_ptr.ptr, A.col_ij = f->col_ij.ptr, A.rowa_ptr = f->rowa_ptr.ptr, A.rowa_jc = f->rowa_jc.ptr;
     A.rowb_ptr = f->rowb_ptr.ptr, A.rowb_pos = f->rowb_pos.ptr, A.long_rows = f->long_rows.ptr;
     A.e = e->prob, A.lde = e->ld, A.hist = hist, A.r0 = r0, A.ldr = ldr, A.ckpt = ckpt;

@@ -132,8 +132,10 @@ static dol_status build_table(int32_t na, int32_t nb, std::vector<Tuple> &tup, d
         tb->conv_like = col[t] == static_cast<uint32_t>(tup[t].i + tup[t].j);
 
     std::vector<uint32_t> long_rows;
-    for (int32_t i = 0; i < na; ++i)
+    for (int32_t i = 0; i < na; ++i) {
         if (rowa_ptr[i + 1] - rowa_ptr[i] > static_cast<uint32_t>(kLongTableRow)) long_rows.push_back(static_cast<uint32_t>(i));
+        tb->max_rowa_len = std::max(tb->max_rowa_len, static_cast<int32_t>(rowa_ptr[i + 1] - rowa_ptr[i]));
+    }
     for (int32_t j = 0; j < nb; ++j)
         if (rowb_ptr[j + 1] - rowb_ptr[j] > static_cast<uint32_t>(kLongTableRow)) long_rows.push_back(static_cast<uint32_t>(na + j));
 
