@@ -56,16 +56,19 @@ __device__ __forceinline__ void load_cached_tags(Cached<N> &c, const float *le)
 }
 
 // pre of one column: sum over its tuples of |x[i]| * e[j], in list order, one fma each, starting from 0
-template <int N>
+// (TAILS = false: the table has no column or row of more than N tuples, so nothing lies behind the registers)
+template <int N, bool TAILS>
 __device__ __forceinline__ float col_pre(const Cached<N> &c, const uint32_t *__restrict__ list, const float *x,
                                          const float *le)
 {
     float acc = 0.0f;
 #pragma unroll
     for (int k = 0; k < N; ++k) acc = __builtin_fmaf(fabsf(x[c.t[k] & 0xffffu]), c.e[k], acc);
-    for (uint32_t q = c.q0 + N; q < c.q1; ++q) {
-        const uint32_t t = list[q];
-        acc = __builtin_fmaf(fabsf(x[t & 0xffffu]), le[t >> 16], acc);
+    if constexpr (TAILS) {
+        for (uint32_t q = c.q0 + N; q < c.q1; ++q) {
+            const uint32_t t = list[q];
+            acc = __builtin_fmaf(fabsf(x[t & 0xffffu]), le[t >> 16], acc);
+        }
     }
     return acc;
 }
@@ -90,7 +93,7 @@ struct ItFwdArgs {
 
 // One round from the row at `xc` into the row at `xn` (this thread's columns), then the workgroup's barrier.
 // ai[k][y] = element of the row that tuple y of column k reads; pre[k] = the column's unclamped sum.
-template <int T, int K, int CA>
+template <int T, int K, int CA, bool TAILS>
 __device__ __forceinline__ void iterate_round(const Cached<CA> (&col)[K], const uint32_t *__restrict__ list, const float *xc,
                                               float *xn, const float *le, int na, float (&pre)[K])
 {
@@ -98,13 +101,13 @@ __device__ __forceinline__ void iterate_round(const Cached<CA> (&col)[K], const 
 #pragma unroll
     for (int k = 0; k < K; ++k) {
         const int c = tid + T * k;
-        pre[k] = col_pre(col[k], list, xc, le);
+        pre[k] = col_pre<CA, TAILS>(col[k], list, xc, le);
         if (c < na) xn[c] = signed_tag(pre[k]);
     }
     lds_barrier();
 }
 
-template <int T, int K, int CA>
+template <int T, int K, int CA, bool TAILS>
 __global__ void __launch_bounds__(T)
 damp_iterate_fwd_kernel(const ItFwdArgs A)
 {
@@ -139,11 +142,11 @@ damp_iterate_fwd_kernel(const ItFwdArgs A)
     while (t < A.rounds) {
         const int stop = min(A.rounds, (t / stride + 1) * stride);
         for (; t + 1 < stop; t += 2) {
-            iterate_round<T, K, CA>(col, A.col_ij, x0, x1, le, na, pre);
-            iterate_round<T, K, CA>(col, A.col_ij, x1, x0, le, na, pre);
+            iterate_round<T, K, CA, TAILS>(col, A.col_ij, x0, x1, le, na, pre);
+            iterate_round<T, K, CA, TAILS>(col, A.col_ij, x1, x0, le, na, pre);
         }
         if (t < stop) {                     // an odd stretch: one more round, and the rows change names
-            iterate_round<T, K, CA>(col, A.col_ij, x0, x1, le, na, pre);
+            iterate_round<T, K, CA, TAILS>(col, A.col_ij, x0, x1, le, na, pre);
             float *sw = x0; x0 = x1; x1 = sw;
             ++t;
         }
@@ -206,8 +209,8 @@ __device__ __forceinline__ float block_sum(float x, float *red)
 // sign of seg[x][i] (the decision of the round that produced r_t) is the next gh; the first row of a segment comes
 // from a checkpoint and carries no decision, so its gradient is handed over ungated and gated after the next
 // segment has been replayed.
-template <int T, int K, int CA>
-__global__ void __launch_bounds__(T)
+template <int T, int K, int CA, bool TAILS>
+__global__ void __launch_bounds__(T, 4)                 // four wavefronts per SIMD at least: 128 registers per lane
 damp_iterate_bwd_kernel(const ItBwdArgs A)
 {
     extern __shared__ float lds[];
@@ -274,7 +277,7 @@ damp_iterate_bwd_kernel(const ItBwdArgs A)
                 for (int k = 0; k < K; ++k) {
                     const int c = tid + T * k;
                     if (c < na && seg[x * na1 + c] >= 1.0f)
-                        seg[x * na1 + c] = signed_tag(col_pre(col[k], A.col_ij, seg + (x - 1) * na1, le)) < 0.0f ? -1.0f : 1.0f;
+                        seg[x * na1 + c] = signed_tag(col_pre<CA, TAILS>(col[k], A.col_ij, seg + (x - 1) * na1, le)) < 0.0f ? -1.0f : 1.0f;
                 }
             }
             lds_barrier();
@@ -288,7 +291,7 @@ damp_iterate_bwd_kernel(const ItBwdArgs A)
 #pragma unroll
                 for (int k = 0; k < K; ++k) {
                     const int c = tid + T * k;
-                    if (c < na) x_nxt[c] = signed_tag(col_pre(col[k], A.col_ij, x_cur, le));
+                    if (c < na) x_nxt[c] = signed_tag(col_pre<CA, TAILS>(col[k], A.col_ij, x_cur, le));
                 }
                 lds_barrier();
             }
@@ -298,28 +301,31 @@ damp_iterate_bwd_kernel(const ItBwdArgs A)
         for (int c = tid; c < na; c += T)
             if (seg[len * na1 + c] < 0.0f) gA[c] = 0.0f;
         lds_barrier();
-        // ---- walk the segment backwards
-        for (int x = len - 1; x >= 0; --x) {
+        // ---- walk the segment backwards: one round reads the gradient row gin and writes gnx; with one row per thread two
+        // rounds per trip, so that the rows keep their names and the addresses of a thread's reads stay in registers
+        auto reverse_round = [&](int x, const float *gin, float *gnx) {
             const float *xr = seg + x * na1;
-            // rows with many tuples: the whole workgroup takes strided shares of the row
             float g_wide[K];
 #pragma unroll
             for (int k = 0; k < K; ++k) g_wide[k] = 0.0f;
-            for (int l = 0; l < n_long_a; ++l) {
-                const int i = static_cast<int>(A.long_rows[l]);
-                const float ri = fabsf(xr[i]);
-                float acc = 0.0f;
-                for (uint32_t q = A.rowa_ptr[i] + tid, q1 = A.rowa_ptr[i + 1]; q < q1; q += T) {
-                    const uint32_t tu = A.rowa_jc[q];
-                    const float ghc = gA[tu >> 16];
-                    acc = __builtin_fmaf(le[tu & 0xffffu], ghc, acc);
-                    share_buf[q] = __builtin_fmaf(ri, ghc, share_buf[q]);
-                }
-                const float tot = block_sum<T>(acc, red + red_sel * (T / kWave));
-                red_sel ^= 1;
+            if constexpr (TAILS) {
+                // rows with many tuples: the whole workgroup takes strided shares of the row
+                for (int l = 0; l < n_long_a; ++l) {
+                    const int i = static_cast<int>(A.long_rows[l]);
+                    const float ri = fabsf(xr[i]);
+                    float acc = 0.0f;
+                    for (uint32_t q = A.rowa_ptr[i] + tid, q1 = A.rowa_ptr[i + 1]; q < q1; q += T) {
+                        const uint32_t tu = A.rowa_jc[q];
+                        const float ghc = gin[tu >> 16];
+                        acc = __builtin_fmaf(le[tu & 0xffffu], ghc, acc);
+                        share_buf[q] = __builtin_fmaf(ri, ghc, share_buf[q]);
+                    }
+                    const float tot = block_sum<T>(acc, red + red_sel * (T / kWave));
+                    red_sel ^= 1;
 #pragma unroll
-                for (int k = 0; k < K; ++k)
-                    if (i == tid + T * k) g_wide[k] = tot;
+                    for (int k = 0; k < K; ++k)
+                        if (i == tid + T * k) g_wide[k] = tot;
+                }
             }
 #pragma unroll
             for (int k = 0; k < K; ++k) {
@@ -327,26 +333,38 @@ damp_iterate_bwd_kernel(const ItBwdArgs A)
                 const float xi = xr[min(i, na)];
                 const float ri = fabsf(xi);
                 float g = g_wide[k];
-                if (!wide[k]) {
+                if (!TAILS || !wide[k]) {
                     float g_odd = 0.0f;             // two chains of half the length
 #pragma unroll
                     for (int y = 0; y < CA; ++y) {  // row tuples are (j | column << 16)
-                        const float ghc = gA[rowa[k].t[y] >> 16];
+                        const float ghc = gin[rowa[k].t[y] >> 16];
                         if (y & 1) g_odd = __builtin_fmaf(rowa[k].e[y], ghc, g_odd);
                         else g = __builtin_fmaf(rowa[k].e[y], ghc, g);
                         share[k][y] = __builtin_fmaf(ri, ghc, share[k][y]);
                     }
                     g += g_odd;
-                    for (uint32_t q = rowa[k].q0 + CA; q < rowa[k].q1; ++q) {   // tuples past the registers
-                        const uint32_t tu = A.rowa_jc[q];
-                        const float ghc = gA[tu >> 16];
-                        g = __builtin_fmaf(le[tu & 0xffffu], ghc, g);
-                        share_buf[q] = __builtin_fmaf(ri, ghc, share_buf[q]);
+                    if constexpr (TAILS) {
+                        for (uint32_t q = rowa[k].q0 + CA; q < rowa[k].q1; ++q) {   // tuples past the registers
+                            const uint32_t tu = A.rowa_jc[q];
+                            const float ghc = gin[tu >> 16];
+                            g = __builtin_fmaf(le[tu & 0xffffu], ghc, g);
+                            share_buf[q] = __builtin_fmaf(ri, ghc, share_buf[q]);
+                        }
                     }
                 }
-                if (i < na) gB[i] = (x > 0 && xi < 0.0f) ? 0.0f : g;
+                if (i < na) gnx[i] = (x > 0 && xi < 0.0f) ? 0.0f : g;
             }
             lds_barrier();
+        };
+        int x = len - 1;
+        if constexpr (K == 1) {             // (with more rows per thread the two sets of addresses cost a wavefront per SIMD)
+            for (; x >= 1; x -= 2) {
+                reverse_round(x, gA, gB);
+                reverse_round(x - 1, gB, gA);
+            }
+        }
+        for (; x >= 0; --x) {
+            reverse_round(x, gA, gB);
             float *sw = gA; gA = gB; gB = sw;
         }
     }
@@ -410,6 +428,11 @@ static size_t fwd_lds(const dol_fn_table *f) { return sizeof(float) * (2 * stati
 // Tuples of a thread's rows kept in registers by the launch shape chosen for a first operand of na symbols.
 static int cached_tuples(int32_t na) { return na <= 1024 ? 6 : 3; }
 
+static bool has_tails(const dol_fn_table *f)
+{
+    return f->max_col_len > cached_tuples(f->na) || f->max_rowa_len > cached_tuples(f->na);
+}
+
 // The shares of d loss / d e can wait in registers alone when no row has more tuples than the registers hold; the
 // words they are gathered through at the end then fit where the segment was.
 static bool shares_in_seg(const dol_fn_table *f, int32_t every)
@@ -428,13 +451,19 @@ static size_t bwd_lds(const dol_fn_table *f, int32_t every)
 // registers.
 // (a batch that leaves units idle gets the widest workgroup: a round is then bound by the latency of its LDS reads
 // and barrier, which more wavefronts hide; a batch of several workgroups per unit gets two columns per thread)
-#define DOL_IT_DISPATCH(KERNEL, batch, na, lds, st, ...)                                                               \
+#define DOL_IT_SHAPES(KERNEL, TAILS, batch, na, lds, st, ...)                                                          \
     do {                                                                                                               \
-        if ((na) <= 512) hipLaunchKernelGGL((KERNEL<512, 1, 6>), grid, dim3(512), lds, st, __VA_ARGS__);               \
-        else if ((na) <= 1024 && (batch) <= 512) hipLaunchKernelGGL((KERNEL<1024, 1, 6>), grid, dim3(1024), lds, st, __VA_ARGS__); \
-        else if ((na) <= 1024) hipLaunchKernelGGL((KERNEL<512, 2, 6>), grid, dim3(512), lds, st, __VA_ARGS__);         \
-        else if ((na) <= 2048) hipLaunchKernelGGL((KERNEL<512, 4, 3>), grid, dim3(512), lds, st, __VA_ARGS__);         \
-        else hipLaunchKernelGGL((KERNEL<1024, 4, 3>), grid, dim3(1024), lds, st, __VA_ARGS__);                         \
+        if ((na) <= 512) hipLaunchKernelGGL((KERNEL<512, 1, 6, TAILS>), grid, dim3(512), lds, st, __VA_ARGS__);        \
+        else if ((na) <= 1024 && (batch) <= 512) hipLaunchKernelGGL((KERNEL<1024, 1, 6, TAILS>), grid, dim3(1024), lds, st, __VA_ARGS__); \
+        else if ((na) <= 1024) hipLaunchKernelGGL((KERNEL<512, 2, 6, TAILS>), grid, dim3(512), lds, st, __VA_ARGS__);  \
+        else if ((na) <= 2048) hipLaunchKernelGGL((KERNEL<512, 4, 3, TAILS>), grid, dim3(512), lds, st, __VA_ARGS__);  \
+        else hipLaunchKernelGGL((KERNEL<1024, 4, 3, TAILS>), grid, dim3(1024), lds, st, __VA_ARGS__);                  \
+    } while (0)
+// (tails: some column or row of the table has more tuples than the shape keeps in registers)
+#define DOL_IT_DISPATCH(KERNEL, tails, batch, na, lds, st, ...)                                                        \
+    do {                                                                                                               \
+        if (tails) DOL_IT_SHAPES(KERNEL, true, batch, na, lds, st, __VA_ARGS__);                                       \
+        else DOL_IT_SHAPES(KERNEL, false, batch, na, lds, st, __VA_ARGS__);                                            \
     } while (0)
 
 // (the reverse sweep may ask for more than 64 KB of LDS)
@@ -443,11 +472,16 @@ static hipError_t allow_lds(Kern kern) { return allow_dynamic_lds(reinterpret_ca
 
 static dol_status allow_big_lds()
 {
-    DOL_HIP(allow_lds(damp_iterate_bwd_kernel<512, 1, 6>));
-    DOL_HIP(allow_lds(damp_iterate_bwd_kernel<512, 2, 6>));
-    DOL_HIP(allow_lds(damp_iterate_bwd_kernel<512, 4, 3>));
-    DOL_HIP(allow_lds(damp_iterate_bwd_kernel<1024, 4, 3>));
-    DOL_HIP(allow_lds(damp_iterate_bwd_kernel<1024, 1, 6>));
+    DOL_HIP(allow_lds(damp_iterate_bwd_kernel<512, 1, 6, true>));
+    DOL_HIP(allow_lds(damp_iterate_bwd_kernel<512, 2, 6, true>));
+    DOL_HIP(allow_lds(damp_iterate_bwd_kernel<512, 4, 3, true>));
+    DOL_HIP(allow_lds(damp_iterate_bwd_kernel<1024, 4, 3, true>));
+    DOL_HIP(allow_lds(damp_iterate_bwd_kernel<1024, 1, 6, true>));
+    DOL_HIP(allow_lds(damp_iterate_bwd_kernel<512, 1, 6, false>));
+    DOL_HIP(allow_lds(damp_iterate_bwd_kernel<512, 2, 6, false>));
+    DOL_HIP(allow_lds(damp_iterate_bwd_kernel<512, 4, 3, false>));
+    DOL_HIP(allow_lds(damp_iterate_bwd_kernel<1024, 4, 3, false>));
+    DOL_HIP(allow_lds(damp_iterate_bwd_kernel<1024, 1, 6, false>));
     return DOL_OK;
 }
 
@@ -462,7 +496,7 @@ dol_status launch_iterate_fwd(const dol_dist *r0, const dol_dist *e, const dol_f
     A.r0 = r0->prob, A.ldr = r0->ld, A.e = e->prob, A.lde = e->ld;
     A.hist = hist, A.ckpt = ckpt, A.every = every > 0 ? every : rounds + 1, A.out = out, A.ldo = ldo;
     const dim3 grid(static_cast<unsigned>(r0->batch));
-    DOL_IT_DISPATCH(damp_iterate_fwd_kernel, r0->batch, f->na, lds, st, A);
+    DOL_IT_DISPATCH(damp_iterate_fwd_kernel, has_tails(f), r0->batch, f->na, lds, st, A);
     DOL_HIP(hipGetLastError());
     return DOL_OK;
 }
@@ -485,7 +519,7 @@ dol_status launch_iterate_bwd(const dol_dist *e, const dol_fn_table *f, int32_t 
     A.e = e->prob, A.lde = e->ld, A.hist = hist, A.r0 = r0, A.ldr = ldr, A.ckpt = ckpt;
     A.gout = grad_out, A.ldg = ldg, A.grad_r0 = grad_r0, A.grad_e = grad_e, A.ldge = e->ld;
     const dim3 grid(static_cast<unsigned>(e->batch));
-    DOL_IT_DISPATCH(damp_iterate_bwd_kernel, e->batch, f->na, lds, st, A);
+    DOL_IT_DISPATCH(damp_iterate_bwd_kernel, has_tails(f), e->batch, f->na, lds, st, A);
     DOL_HIP(hipGetLastError());
     return DOL_OK;
 }

@@ -398,8 +398,14 @@ class GridReachFused(Program):
 
     def __init__(self, w, device="cuda", ckpt_every=None):
         B, side = w["p"].shape[0], w["side"]
-        if ckpt_every is None:               # few samples: one workgroup per unit, longer stretches cost nothing;
-            ckpt_every = 16 if B <= 512 else 8   # many: 8 rounds of LDS leave room for two workgroups per unit
+        if ckpt_every is None:
+            if B <= 512:                     # few samples, one workgroup per unit: the fewest segments of at most 24 rounds
+                R0 = max(w["rounds"], 1)     # whose rows fit LDS (each segment costs a checkpoint and a refill)
+                ckpt_every = -(-R0 // -(-R0 // 24))
+                while ckpt_every > 8 and 4 * ((ckpt_every + 3) * (w["side"] ** 2 + 1) + w["edge_u"].size + 2) > 140 * 1024:
+                    ckpt_every -= 1
+            else:                            # many: 8 rounds of LDS leave room for more workgroups per unit
+                ckpt_every = 8
         self.batch, self.rounds, n = B, w["rounds"], side * side
         E = w["edge_u"].size
         self.E = E
