@@ -563,6 +563,26 @@ def iterate_backward_ckpt(r0: Dist, e: Dist, f: FnTable, rounds: int, ckpt_every
                                           _stream(stream)))
 
 
+_lib.dol_iterate_apply2_backward.argtypes = [C.POINTER(_Dist), C.POINTER(_Dist), C.c_void_p, C.c_int32, C.c_int32,
+                                             C.POINTER(_Dist), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p,
+                                             C.c_void_p, C.c_void_p]
+
+
+def iterate_apply2_backward(r0: Dist, e: Dist, f: FnTable, rounds: int, ckpt_every: int, out: Dist,
+                            ckpt: Optional[torch.Tensor], target_col: Optional[torch.Tensor], grad_out: Optional[torch.Tensor],
+                            grad_r0: Optional[torch.Tensor], grad_e: Optional[torch.Tensor], stream=None):
+    """Forward rounds and reverse sweep in one launch; exactly one of target_col (int32 [batch]) and grad_out."""
+    ldg = 0
+    if grad_out is not None:
+        assert grad_out.dtype == torch.float32 and grad_out.stride(1) == 1
+        ldg = max(int(grad_out.stride(0)), grad_out.shape[1])
+    if target_col is not None:
+        assert target_col.dtype == torch.int32 and target_col.is_contiguous()
+    assert grad_r0 is None or grad_r0.is_contiguous()
+    _check(_lib.dol_iterate_apply2_backward(r0.ref(), e.ref(), f._h, rounds, ckpt_every, out.ref(), _dptr(ckpt), _dptr(target_col),
+                                            _dptr(grad_out), ldg, _dptr(grad_r0), _dptr(grad_e), _stream(stream)))
+
+
 _lib.dol_iterate_backward_noalloc.argtypes = [C.POINTER(_Dist), C.POINTER(_Dist), C.c_void_p, C.c_int32, C.c_void_p,
                                               C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p]
 

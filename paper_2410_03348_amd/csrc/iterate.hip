@@ -108,10 +108,9 @@ __device__ __forceinline__ void iterate_round(const Cached<CA> (&col)[K], const 
 }
 
 template <int T, int K, int CA, bool TAILS>
-__global__ void __launch_bounds__(T)
-damp_iterate_fwd_kernel(const ItFwdArgs A)
+__device__ __forceinline__ void iterate_forward(const ItFwdArgs &A, float *lds)
 {
-    extern __shared__ float lds[];          // x (two rows of na + 1), e (nb + 1): each row ends with a zero
+    // lds: x (two rows of na + 1), e (nb + 1): each row ends with a zero
     const int na = A.na, nb = A.nb;
     float *x0 = lds, *x1 = lds + na + 1;
     float *le = lds + 2 * (na + 1);
@@ -165,6 +164,14 @@ damp_iterate_fwd_kernel(const ItFwdArgs A)
     }
 }
 
+template <int T, int K, int CA, bool TAILS>
+__global__ void __launch_bounds__(T)
+damp_iterate_fwd_kernel(const ItFwdArgs A)
+{
+    extern __shared__ float lds[];
+    iterate_forward<T, K, CA, TAILS>(A, lds);
+}
+
 // ---------------------------------------------------------------- backward
 
 struct ItBwdArgs {
@@ -179,8 +186,11 @@ struct ItBwdArgs {
     const float *r0;
     int64_t ldr;
     const float *ckpt;
-    const float *gout;
+    const float *gout;                      // upstream gradient w.r.t. r_rounds, or
     int64_t ldg;
+    const int32_t *target;                  // [batch]: the loss is -log r_rounds[target], read from `out`
+    const float *out;
+    int64_t ldo;
     float *grad_r0;                         // [batch, na] or nullptr
     float *grad_e;                          // [batch, ldge] or nullptr
     int64_t ldge;
@@ -210,10 +220,8 @@ __device__ __forceinline__ float block_sum(float x, float *red)
 // from a checkpoint and carries no decision, so its gradient is handed over ungated and gated after the next
 // segment has been replayed.
 template <int T, int K, int CA, bool TAILS>
-__global__ void __launch_bounds__(T, 4)                 // four wavefronts per SIMD at least: 128 registers per lane
-damp_iterate_bwd_kernel(const ItBwdArgs A)
+__device__ __forceinline__ void iterate_backward(const ItBwdArgs &A, float *lds)
 {
-    extern __shared__ float lds[];
     const int na = A.na, nb = A.nb, na1 = na + 1;
     float *seg = lds;
     float *gA = seg + static_cast<size_t>(A.every + 1) * na1, *gB = gA + na1;
@@ -227,7 +235,8 @@ damp_iterate_bwd_kernel(const ItBwdArgs A)
     const float *gs = A.gout + s * A.ldg;
     if (A.rounds == 0) {
         if (A.grad_r0)
-            for (int c = tid; c < na; c += T) A.grad_r0[s * na + c] = gs[c];
+            for (int c = tid; c < na; c += T)
+                A.grad_r0[s * na + c] = !A.target ? gs[c] : c == A.target[s] ? -1.0f / fmaxf(A.out[s * A.ldo + c], 1.17549435e-38f) : 0.0f;
         if (A.grad_e)
             for (int j = tid; j < nb; j += T) A.grad_e[s * A.ldge + j] = 0.0f;
         return;
@@ -235,7 +244,12 @@ damp_iterate_bwd_kernel(const ItBwdArgs A)
     for (int j = tid; j <= nb; j += T) le[j] = j < nb ? e_row[j] : 0.0f;
     if (!A.shares_in_seg)
         for (int q = tid; q < A.n_tuples; q += T) share_buf[q] = 0.0f;
-    for (int c = tid; c < na; c += T) gA[c] = gs[c];
+    if (A.target) {
+        const int tgt = A.target[s];
+        for (int c = tid; c < na; c += T) gA[c] = c == tgt ? -1.0f / fmaxf(A.out[s * A.ldo + c], 1.17549435e-38f) : 0.0f;
+    } else {
+        for (int c = tid; c < na; c += T) gA[c] = gs[c];
+    }
     if (tid == 0) {
         gA[na] = 0.0f; gB[na] = 0.0f;
         for (int x = 0; x <= A.every; ++x) seg[x * na1 + na] = 0.0f;
@@ -397,6 +411,26 @@ damp_iterate_bwd_kernel(const ItBwdArgs A)
     }
 }
 
+template <int T, int K, int CA, bool TAILS>
+__global__ void __launch_bounds__(T, 4)                 // four wavefronts per SIMD at least: 128 registers per lane
+damp_iterate_bwd_kernel(const ItBwdArgs A)
+{
+    extern __shared__ float lds[];
+    iterate_backward<T, K, CA, TAILS>(A, lds);
+}
+
+// Forward and reverse sweep in one launch: the tables are found in cache the second time, nothing waits for a second
+// launch, and a thread reads back only checkpoint and result entries that it wrote itself.
+template <int T, int K, int CA, bool TAILS>
+__global__ void __launch_bounds__(T, 4)
+damp_iterate_fwd_bwd_kernel(const ItFwdArgs F, const ItBwdArgs B)
+{
+    extern __shared__ float lds[];
+    iterate_forward<T, K, CA, TAILS>(F, lds);
+    __syncthreads();
+    iterate_backward<T, K, CA, TAILS>(B, lds);
+}
+
 // ---------------------------------------------------------------- host side
 
 dol_status check_iterate(const dol_dist *e, const dol_fn_table *f, int32_t rounds)
@@ -482,7 +516,42 @@ static dol_status allow_big_lds()
     DOL_HIP(allow_lds(damp_iterate_bwd_kernel<512, 4, 3, false>));
     DOL_HIP(allow_lds(damp_iterate_bwd_kernel<1024, 4, 3, false>));
     DOL_HIP(allow_lds(damp_iterate_bwd_kernel<1024, 1, 6, false>));
+    DOL_HIP(allow_lds(damp_iterate_fwd_bwd_kernel<512, 1, 6, true>));
+    DOL_HIP(allow_lds(damp_iterate_fwd_bwd_kernel<512, 2, 6, true>));
+    DOL_HIP(allow_lds(damp_iterate_fwd_bwd_kernel<512, 4, 3, true>));
+    DOL_HIP(allow_lds(damp_iterate_fwd_bwd_kernel<1024, 4, 3, true>));
+    DOL_HIP(allow_lds(damp_iterate_fwd_bwd_kernel<1024, 1, 6, true>));
+    DOL_HIP(allow_lds(damp_iterate_fwd_bwd_kernel<512, 1, 6, false>));
+    DOL_HIP(allow_lds(damp_iterate_fwd_bwd_kernel<512, 2, 6, false>));
+    DOL_HIP(allow_lds(damp_iterate_fwd_bwd_kernel<512, 4, 3, false>));
+    DOL_HIP(allow_lds(damp_iterate_fwd_bwd_kernel<1024, 4, 3, false>));
+    DOL_HIP(allow_lds(damp_iterate_fwd_bwd_kernel<1024, 1, 6, false>));
     return DOL_OK;
+}
+
+static ItFwdArgs fwd_args(const dol_dist *r0, const dol_dist *e, const dol_fn_table *f, int32_t rounds, float *hist, float *ckpt,
+                          int32_t every, float *out, int64_t ldo)
+{
+    ItFwdArgs A{};
+    A.batch = r0->batch, A.na = f->na, A.nb = f->nb, A.rounds = rounds;
+    A.col_ptr = f->col_ptr.ptr, A.col_ij = f->col_ij.ptr;
+    A.r0 = r0->prob, A.ldr = r0->ld, A.e = e->prob, A.lde = e->ld;
+    A.hist = hist, A.ckpt = ckpt, A.every = every > 0 ? every : rounds + 1, A.out = out, A.ldo = ldo;
+    return A;
+}
+
+static ItBwdArgs bwd_args(const dol_dist *e, const dol_fn_table *f, int32_t rounds, const float *hist, const float *r0, int64_t ldr,
+                          const float *ckpt, int32_t every, const float *grad_out, int64_t ldg, float *grad_r0, float *grad_e)
+{
+    ItBwdArgs A{};
+    A.batch = e->batch, A.na = f->na, A.nb = f->nb, A.rounds = rounds, A.every = every;
+    A.n_tuples = static_cast<int32_t>(f->n_tuples), A.n_long = static_cast<int32_t>(f->long_rows.n);
+    A.shares_in_seg = shares_in_seg(f, every) ? 1 : 0;
+    A.col_ptr = f->col_ptr.ptr, A.col_ij = f->col_ij.ptr, A.rowa_ptr = f->rowa_ptr.ptr, A.rowa_jc = f->rowa_jc.ptr;
+    A.rowb_ptr = f->rowb_ptr.ptr, A.rowb_pos = f->rowb_pos.ptr, A.long_rows = f->long_rows.ptr;
+    A.e = e->prob, A.lde = e->ld, A.hist = hist, A.r0 = r0, A.ldr = ldr, A.ckpt = ckpt;
+    A.gout = grad_out, A.ldg = ldg, A.grad_r0 = grad_r0, A.grad_e = grad_e, A.ldge = e->ld;
+    return A;
 }
 
 dol_status launch_iterate_fwd(const dol_dist *r0, const dol_dist *e, const dol_fn_table *f, int32_t rounds,
@@ -490,11 +559,7 @@ dol_status launch_iterate_fwd(const dol_dist *r0, const dol_dist *e, const dol_f
 {
     const size_t lds = fwd_lds(f);
     if (lds > 64 * 1024) return fail(DOL_EUNSUPPORTED, "the rows need %zu bytes of LDS, more than 65536", lds);
-    ItFwdArgs A{};
-    A.batch = r0->batch, A.na = f->na, A.nb = f->nb, A.rounds = rounds;
-    A.col_ptr = f->col_ptr.ptr, A.col_ij = f->col_ij.ptr;
-    A.r0 = r0->prob, A.ldr = r0->ld, A.e = e->prob, A.lde = e->ld;
-    A.hist = hist, A.ckpt = ckpt, A.every = every > 0 ? every : rounds + 1, A.out = out, A.ldo = ldo;
+    const ItFwdArgs A = fwd_args(r0, e, f, rounds, hist, ckpt, every, out, ldo);
     const dim3 grid(static_cast<unsigned>(r0->batch));
     DOL_IT_DISPATCH(damp_iterate_fwd_kernel, has_tails(f), r0->batch, f->na, lds, st, A);
     DOL_HIP(hipGetLastError());
@@ -510,16 +575,27 @@ dol_status launch_iterate_bwd(const dol_dist *e, const dol_fn_table *f, int32_t 
     if (lds > kItLdsMax)
         return fail(DOL_EUNSUPPORTED, "segments of %d rounds need %zu bytes of LDS, more than %zu", every, lds, kItLdsMax);
     if (dol_status s = allow_big_lds()) return s;
-    ItBwdArgs A{};
-    A.batch = e->batch, A.na = f->na, A.nb = f->nb, A.rounds = rounds, A.every = every;
-    A.n_tuples = static_cast<int32_t>(f->n_tuples), A.n_long = static_cast<int32_t>(f->long_rows.n);
-    A.shares_in_seg = shares_in_seg(f, every) ? 1 : 0;
-    A.col_ptr = f->col_ptr.ptr, A.col_ij = f->col_ij.ptr, A.rowa_ptr = f->rowa_ptr.ptr, A.rowa_jc = f->rowa_jc.ptr;
-    A.rowb_ptr = f->rowb_ptr.ptr, A.rowb_pos = f->rowb_pos.ptr, A.long_rows = f->long_rows.ptr;
-    A.e = e->prob, A.lde = e->ld, A.hist = hist, A.r0 = r0, A.ldr = ldr, A.ckpt = ckpt;
-    A.gout = grad_out, A.ldg = ldg, A.grad_r0 = grad_r0, A.grad_e = grad_e, A.ldge = e->ld;
+    const ItBwdArgs A = bwd_args(e, f, rounds, hist, r0, ldr, ckpt, every, grad_out, ldg, grad_r0, grad_e);
     const dim3 grid(static_cast<unsigned>(e->batch));
     DOL_IT_DISPATCH(damp_iterate_bwd_kernel, has_tails(f), e->batch, f->na, lds, st, A);
+    DOL_HIP(hipGetLastError());
+    return DOL_OK;
+}
+
+static dol_status launch_iterate_fwd_bwd(const dol_dist *r0, const dol_dist *e, const dol_fn_table *f, int32_t rounds, int32_t every,
+                                         float *out, int64_t ldo, float *ckpt, const int32_t *target, const float *grad_out,
+                                         int64_t ldg, float *grad_r0, float *grad_e, hipStream_t st)
+{
+    if (!f->rowb_pos.ptr && f->n_tuples > 0) return fail(DOL_EINVAL, "the table lacks the row cross-index of square tables");
+    const size_t lds = std::max(fwd_lds(f), bwd_lds(f, every));
+    if (lds > kItLdsMax)
+        return fail(DOL_EUNSUPPORTED, "segments of %d rounds need %zu bytes of LDS, more than %zu", every, lds, kItLdsMax);
+    if (dol_status s = allow_big_lds()) return s;
+    const ItFwdArgs F = fwd_args(r0, e, f, rounds, nullptr, ckpt, every, out, ldo);
+    ItBwdArgs B = bwd_args(e, f, rounds, nullptr, r0->prob, r0->ld, ckpt, every, grad_out, ldg, grad_r0, grad_e);
+    B.target = target, B.out = out, B.ldo = ldo;
+    const dim3 grid(static_cast<unsigned>(e->batch));
+    DOL_IT_DISPATCH(damp_iterate_fwd_bwd_kernel, has_tails(f), e->batch, f->na, lds, st, F, B);
     DOL_HIP(hipGetLastError());
     return DOL_OK;
 }
@@ -595,6 +671,29 @@ dol_status dol_iterate_backward_ckpt(const dol_dist *r0, const dol_dist *e, cons
     const int32_t every = std::max(1, std::min(ckpt_every, std::max(rounds, 1)));
     return launch_iterate_bwd(e, f, rounds, nullptr, r0->prob, r0->ld, ckpt, every, grad_out, grad_out_ld, grad_r0,
                               grad_e, static_cast<hipStream_t>(hip_stream));
+}
+
+dol_status dol_iterate_apply2_backward(const dol_dist *r0, const dol_dist *e, const dol_fn_table *f, int32_t rounds,
+                                       int32_t ckpt_every, dol_dist *out, float *ckpt, const int32_t *target_col,
+                                       const float *grad_out, int64_t grad_out_ld, float *grad_r0, float *grad_e,
+                                       void *hip_stream)
+{
+    if (dol_status st = check_iterate(e, f, rounds)) return st;
+    if (dol_status st = check_r0(r0, e, f)) return st;
+    if (ckpt_every < 1) return fail(DOL_EINVAL, "ckpt_every = %d, must be at least 1", ckpt_every);
+    if (!out) return fail(DOL_EINVAL, "out is NULL");
+    if (out->batch != r0->batch || out->n_sym != f->na || out->ld < out->n_sym)
+        return fail(DOL_ESHAPE, "out has %d x %d, the rounds produce %d x %d", out->batch, out->n_sym, r0->batch, f->na);
+    if (!target_col && !grad_out) return fail(DOL_EINVAL, "target_col and grad_out are both NULL");
+    if (target_col && grad_out) return fail(DOL_EINVAL, "target_col and grad_out are both given");
+    if (grad_out && grad_out_ld < f->na) return fail(DOL_ESHAPE, "grad_out_ld = %lld is smaller than %d", static_cast<long long>(grad_out_ld), f->na);
+    if (!grad_r0 && !grad_e) return fail(DOL_EINVAL, "grad_r0 and grad_e are both NULL");
+    if (r0->batch == 0 || f->na == 0) return DOL_OK;
+    if (!out->prob) return fail(DOL_EINVAL, "out.prob is NULL");
+    if (dol_iterate_ckpt_count(rounds, ckpt_every) > 0 && !ckpt) return fail(DOL_EINVAL, "ckpt is NULL");
+    const int32_t every = std::max(1, std::min(ckpt_every, std::max(rounds, 1)));
+    return launch_iterate_fwd_bwd(r0, e, f, rounds, every, out->prob, out->ld, ckpt, target_col, grad_out, grad_out_ld, grad_r0,
+                                  grad_e, static_cast<hipStream_t>(hip_stream));
 }
 
 }  // extern "C"

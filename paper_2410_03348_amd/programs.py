@@ -396,7 +396,7 @@ class GridReachFused(Program):
     the last round and a checkpoint every `ckpt_every` rounds leave the chip, the reverse sweep replays the rounds in
     between in LDS.  ckpt_every = 0: the full history goes through HBM instead (dol_iterate_apply2 / _backward)."""
 
-    def __init__(self, w, device="cuda", ckpt_every=None):
+    def __init__(self, w, device="cuda", ckpt_every=None, one_launch=False):
         B, side = w["p"].shape[0], w["side"]
         if ckpt_every is None:
             if B <= 512:                     # few samples, one workgroup per unit: the fewest segments of at most 24 rounds
@@ -438,6 +438,11 @@ class GridReachFused(Program):
             Launch("damp_iterate_fwd_kernel", fwd, 4 * B * (n + E + 1 + n), B * R * n_tup, "fwd"),     # r_0 and e in, r_R out
             Launch("damp_iterate_bwd_kernel", bwd, 4 * B * (n + 2 * (E + 1)), 2 * B * R * n_tup, "bwd"),  # gradient and e in, gradient of e out
         ]                                    # (what the sweeps keep of the rounds in between is not algorithmic)
+        if one_launch:                       # dol_iterate_apply2_backward: both sweeps in one launch
+            assert ckpt_every, "the one-launch form keeps checkpoints"
+            both = lambda: dol.iterate_apply2_backward(self.r0, self.edges, self.table, R, ckpt_every, self.out, self.ckpt,
+                                                       None, self.g_out, None, self.g_e)
+            self.launches = [Launch("damp_iterate_fwd_bwd_kernel", both, 4 * B * (3 * n + 3 * (E + 1)), 3 * B * R * n_tup, "fwd+bwd")]
         self.sample_ops = 2 * R * B
         self.min_bytes = 4 * B * (2 * E + 2 * n)
         self.flops = 2 * 3 * B * R * n_tup

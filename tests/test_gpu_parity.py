@@ -451,6 +451,47 @@ def test_config5_checkpointed_iteration(gp, dol, batch, side, rounds, every):
     assert ei.value.status == 1
 
 
+@pytest.mark.parametrize("batch,side,rounds,every", [(256, 32, 64, 22), (33, 7, 20, 6), (5, 4, 1, 8), (40, 12, 30, 30), (3, 3, 7, 2)])
+def test_config5_iteration_in_one_launch(gp, dol, batch, side, rounds, every):
+    """dol_iterate_apply2_backward: both sweeps in one launch.  With an upstream gradient: bit for bit the results of
+    the two separate calls.  With a target node per sample (loss = -log r[target]): against the oracle's sweeps fed
+    the gradient of that loss at the oracle's own result."""
+    w = W.config5(batch=batch, side=side, rounds=rounds, seed=side + 3)
+    two = gp.GridReachFused(w, ckpt_every=every)
+    two.step()
+    one = gp.GridReachFused(w, ckpt_every=every, one_launch=True)
+    assert len(one.launches) == 1
+    one.step()
+    np.testing.assert_array_equal(host(one.out.prob), host(two.out.prob))
+    np.testing.assert_array_equal(host(one.g_e), host(two.g_e))
+    if one.ckpt is not None:
+        np.testing.assert_array_equal(host(one.ckpt), host(two.ckpt))
+    n = side * side
+    g0a, g0b = torch.empty((batch, n), device="cuda"), torch.empty((batch, n), device="cuda")
+    dol.iterate_apply2_backward(one.r0, one.edges, one.table, rounds, every, one.out, one.ckpt, None, one.g_out, g0a, None)
+    dol.iterate_backward_ckpt(two.r0, two.edges, two.table, rounds, every, two.ckpt, two.g_out, g0b, None)
+    np.testing.assert_array_equal(host(g0a), host(g0b))
+    # a target node per sample
+    ref = OP.grid_reach_fwd_bwd(w)
+    near = np.array([r * side + c for r in range(side) for c in range(side) if r + c <= rounds], np.int32)   # reachable in time
+    target = near[np.arange(batch) * 7 % near.size]
+    r_t = ref["hist"][-1][np.arange(batch), target]
+    assert (r_t > 0).all()
+    g = np.zeros((batch, n), np.float32)
+    g[np.arange(batch), target] = -1.0 / np.maximum(r_t, np.float32(1.17549435e-38))
+    wd = {k: w[k] for k in ("side", "edge_u", "edge_v", "src", "rounds", "p")}
+    wd["g"] = g
+    want = OP.grid_reach_fwd_bwd(wd)["grad_p"]
+    ge = torch.empty_like(one.g_e)
+    dol.iterate_apply2_backward(one.r0, one.edges, one.table, rounds, every, one.out, one.ckpt, dev(target), None, None, ge)
+    assert_close(host(one.out.prob), ref["hist"][-1], "one-launch reach result")
+    assert_close(host(ge)[:, :w["p"].shape[1]], want, "one-launch reach grad from a target")
+    for args in ((None, None), (dev(target), one.g_out)):
+        with pytest.raises(dol.DolError) as ei:
+            dol.iterate_apply2_backward(one.r0, one.edges, one.table, rounds, every, one.out, one.ckpt, args[0], args[1], None, ge)
+        assert ei.value.status == 1
+
+
 def test_iterated_apply_passes_gradient_on_the_clamp_bound(dol):
     """Two nodes, one edge, a "stay" symbol of tag 1: with p = 0.5 the second round's sum at node 1 is exactly 1 and the
     clamp passes gradient (App. A.2), d r_2[1] / d p = 2; with p = 0.75 the clamp acts (0); with 0.25 nothing clamps (2).

@@ -1,6 +1,7 @@
 """dol_iterate_backward_noalloc (the entry point that allocates nothing) against dol_iterate_apply2_ckpt +
 dol_iterate_backward_ckpt, through the C ABI: two calls in a row, the second on a smaller input."""
 import ctypes as C
+import gc
 
 import numpy as np
 import pytest
@@ -36,13 +37,18 @@ def test_no_alloc_entry_point_matches_the_workspace_one():
         n, nb = side * side, prog.edges.n_sym
         g0 = torch.full((batch, n), -7.0, device="cuda")
         ge = torch.full((batch, nb), -7.0, device="cuda")
-        before = torch.cuda.memory_allocated()
-        st = lib.dol_iterate_backward_noalloc(prog.r0.ref(), prog.edges.ref(), prog.table._h, rounds,
-                                              C.c_void_p(prog.g_out.data_ptr()), prog.g_out.stride(0),
-                                              C.c_void_p(g0.data_ptr()), C.c_void_p(ge.data_ptr()), stream)
-        assert st == 0, dol.last_error()
-        torch.cuda.synchronize()
-        assert torch.cuda.memory_allocated() == before
+        gc.collect()                        # (tensors of earlier tests must not be released in between)
+        gc.disable()
+        try:
+            before = torch.cuda.memory_allocated()
+            st = lib.dol_iterate_backward_noalloc(prog.r0.ref(), prog.edges.ref(), prog.table._h, rounds,
+                                                  C.c_void_p(prog.g_out.data_ptr()), prog.g_out.stride(0),
+                                                  C.c_void_p(g0.data_ptr()), C.c_void_p(ge.data_ptr()), stream)
+            assert st == 0, dol.last_error()
+            torch.cuda.synchronize()
+            assert torch.cuda.memory_allocated() == before
+        finally:
+            gc.enable()
         np.testing.assert_array_equal(host(g0), want_g0)               # same kernels, same order: bit for bit
         np.testing.assert_array_equal(host(ge), want_ge)
     # beyond the built-in workspace: a clear error, outputs untouched
