@@ -107,8 +107,9 @@ __device__ __forceinline__ void iterate_round(const Cached<CA> (&col)[K], const 
     lds_barrier();
 }
 
-template <int T, int K, int CA, bool TAILS>
-__device__ __forceinline__ void iterate_forward(const ItFwdArgs &A, float *lds)
+// (PRE: the caller has already fetched the columns' tuples into `col`)
+template <int T, int K, int CA, bool TAILS, bool PRE = false>
+__device__ __forceinline__ void iterate_forward(const ItFwdArgs &A, float *lds, Cached<CA> (&col)[K])
 {
     // lds: x (two rows of na + 1), e (nb + 1): each row ends with a zero
     const int na = A.na, nb = A.nb;
@@ -126,9 +127,10 @@ __device__ __forceinline__ void iterate_forward(const ItFwdArgs &A, float *lds)
     }
     for (int j = tid; j < nb; j += T) le[j] = e_row[j];
     if (tid == 0) { x0[na] = 0.0f; x1[na] = 0.0f; le[nb] = 0.0f; }
-    Cached<CA> col[K];
+    if constexpr (!PRE) {
 #pragma unroll
-    for (int k = 0; k < K; ++k) load_cached(col[k], A.col_ptr, A.col_ij, tid + T * k, na, pack16(na, nb));
+        for (int k = 0; k < K; ++k) load_cached(col[k], A.col_ptr, A.col_ij, tid + T * k, na, pack16(na, nb));
+    }
     lds_barrier();
 #pragma unroll
     for (int k = 0; k < K; ++k) load_cached_tags<CA, false>(col[k], le);
@@ -169,7 +171,8 @@ __global__ void __launch_bounds__(T)
 damp_iterate_fwd_kernel(const ItFwdArgs A)
 {
     extern __shared__ float lds[];
-    iterate_forward<T, K, CA, TAILS>(A, lds);
+    Cached<CA> col[K];
+    iterate_forward<T, K, CA, TAILS>(A, lds, col);
 }
 
 // ---------------------------------------------------------------- backward
@@ -219,8 +222,8 @@ __device__ __forceinline__ float block_sum(float x, float *red)
 // sign of seg[x][i] (the decision of the round that produced r_t) is the next gh; the first row of a segment comes
 // from a checkpoint and carries no decision, so its gradient is handed over ungated and gated after the next
 // segment has been replayed.
-template <int T, int K, int CA, bool TAILS>
-__device__ __forceinline__ void iterate_backward(const ItBwdArgs &A, float *lds)
+template <int T, int K, int CA, bool TAILS, bool PRE = false>
+__device__ __forceinline__ void iterate_backward(const ItBwdArgs &A, float *lds, Cached<CA> (&col)[K], Cached<CA> (&rowa)[K])
 {
     const int na = A.na, nb = A.nb, na1 = na + 1;
     float *seg = lds;
@@ -254,13 +257,14 @@ __device__ __forceinline__ void iterate_backward(const ItBwdArgs &A, float *lds)
         gA[na] = 0.0f; gB[na] = 0.0f;
         for (int x = 0; x <= A.every; ++x) seg[x * na1 + na] = 0.0f;
     }
-    Cached<CA> col[K], rowa[K];
     bool wide[K];                           // this row is summed by the whole workgroup
     float share[K][CA];
 #pragma unroll
     for (int k = 0; k < K; ++k) {
-        load_cached(col[k], A.col_ptr, A.col_ij, tid + T * k, na, pack16(na, nb));
-        load_cached(rowa[k], A.rowa_ptr, A.rowa_jc, tid + T * k, na, pack16(nb, na));
+        if constexpr (!PRE) {
+            load_cached(col[k], A.col_ptr, A.col_ij, tid + T * k, na, pack16(na, nb));
+            load_cached(rowa[k], A.rowa_ptr, A.rowa_jc, tid + T * k, na, pack16(nb, na));
+        }
         wide[k] = rowa[k].q1 - rowa[k].q0 > static_cast<uint32_t>(kLongTableRow);
 #pragma unroll
         for (int x = 0; x < CA; ++x) share[k][x] = 0.0f;
@@ -416,7 +420,8 @@ __global__ void __launch_bounds__(T, 4)                 // four wavefronts per S
 damp_iterate_bwd_kernel(const ItBwdArgs A)
 {
     extern __shared__ float lds[];
-    iterate_backward<T, K, CA, TAILS>(A, lds);
+    Cached<CA> col[K], rowa[K];
+    iterate_backward<T, K, CA, TAILS>(A, lds, col, rowa);
 }
 
 // Forward and reverse sweep in one launch: the tables are found in cache the second time, nothing waits for a second
@@ -426,9 +431,17 @@ __global__ void __launch_bounds__(T, 4)
 damp_iterate_fwd_bwd_kernel(const ItFwdArgs F, const ItBwdArgs B)
 {
     extern __shared__ float lds[];
-    iterate_forward<T, K, CA, TAILS>(F, lds);
+    // both sweeps' tuples are fetched once, up front: the reverse sweep then starts without waiting for its tables
+    Cached<CA> col[K], rowa[K];
+    const int tid = threadIdx.x;
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        load_cached(col[k], F.col_ptr, F.col_ij, tid + T * k, F.na, pack16(F.na, F.nb));
+        load_cached(rowa[k], B.rowa_ptr, B.rowa_jc, tid + T * k, F.na, pack16(F.nb, F.na));
+    }
+    iterate_forward<T, K, CA, TAILS, true>(F, lds, col);
     __syncthreads();
-    iterate_backward<T, K, CA, TAILS>(B, lds);
+    iterate_backward<T, K, CA, TAILS, true>(B, lds, col, rowa);
 }
 
 // ---------------------------------------------------------------- host side
