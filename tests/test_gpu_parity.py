@@ -962,7 +962,7 @@ def test_dtkp_general_conjunction_union_filter(dol):
     np.testing.assert_array_equal(host(fo.prob), fpr)
 
 
-@pytest.mark.parametrize("which", ["chain", "fold", "hashed", "hashed-fused", "dtkp-fold", "reach-fused", "product",
+@pytest.mark.parametrize("which", ["chain", "fold", "hashed", "hashed-fused", "dtkp-fold", "reach-fused", "reach-one-launch", "hashed-merged", "product",
                                    "formula-damp", "formula-dtkp"])
 def test_hip_graph_replay_matches_eager(gp, which):
     """Every entry point issues only asynchronous launches once its symbol-side plans exist, so a whole step can be
@@ -975,6 +975,10 @@ def test_hip_graph_replay_matches_eager(gp, which):
         prog = gp.HashedPipeline(W.config3(batch=320, seed=5)); key = lambda: prog.ga
     elif which == "hashed-fused":
         prog = gp.HashedPipelineFused(W.config3(batch=320, seed=5)); key = lambda: prog.ga
+    elif which == "hashed-merged":
+        prog = gp.HashedPipelineMerged(W.config3(batch=320, seed=5)); key = lambda: prog.ga
+    elif which == "reach-one-launch":
+        prog = gp.GridReachFused(W.config5(batch=16, side=8, rounds=12, seed=5), one_launch=True); key = lambda: prog.grad_p
     elif which == "dtkp-fold":
         prog = gp.DtkpSumChainFused(W.config4(batch=200, seed=5), with_gradient=True); key = lambda: prog.grad_fact
     elif which == "product":
@@ -1032,13 +1036,15 @@ def test_large_batches_sampled_rows(gp, cfg, batch):
         assert_close(host(prog.out.prob)[idx], ref["out"], "fold forward, sampled rows")
         assert_close(host(prog.grad_p)[:, idx], ref["grad_p"], "fold gradient, sampled rows")
     elif cfg == 3:
-        prog = gp.HashedPipelineFused(w)
-        prog.step()
         ref = OP.hashed_pipeline_fwd_bwd(_rows_of(w, idx, dict(pa=0, pb=0, p2=0, g=0)))
-        assert_close(host(prog.o3.prob)[idx], ref["o3"], "hashed pipeline forward, sampled rows")
-        assert_close(host(prog.ga)[idx], ref["ga"], "hashed pipeline grad a, sampled rows")
-        assert_close(host(prog.gb)[idx], ref["gb"], "hashed pipeline grad b, sampled rows")
-        assert_close(host(prog.gp2)[idx], ref["gp2"], "hashed pipeline grad p2, sampled rows")
+        for cls in (gp.HashedPipelineMerged, gp.HashedPipelineFused):     # the bench's two launches; Apply, then Filter + Union
+            prog = cls(w)
+            prog.step()
+            assert_close(host(prog.o3.prob)[idx], ref["o3"], "hashed pipeline forward, sampled rows")
+            assert_close(host(prog.ga)[idx], ref["ga"], "hashed pipeline grad a, sampled rows")
+            assert_close(host(prog.gb)[idx], ref["gb"], "hashed pipeline grad b, sampled rows")
+            assert_close(host(prog.gp2)[idx], ref["gp2"], "hashed pipeline grad p2, sampled rows")
+            del prog
     elif cfg == 4:
         prog = gp.DtkpSumChainFused(w)
         prog.step()
@@ -1047,11 +1053,13 @@ def test_large_batches_sampled_rows(gp, cfg, batch):
         np.testing.assert_array_equal(host(prog.out.proof_prob)[idx], ref["pprob"])
         assert_close(host(prog.out.prob)[idx], ref["prob"], "dtkp fold, sampled rows")
     else:
-        prog = gp.GridReachFused(w)
-        prog.step()
         ref = OP.grid_reach_fwd_bwd(_rows_of(w, idx, dict(p=0, g=0)))
-        assert_close(host(prog.out.prob)[idx], ref["r"], "reachability, sampled rows")
-        assert_close(host(prog.grad_p)[idx], ref["grad_p"], "reachability gradient, sampled rows")
+        for one_launch in (True, False):                                   # the bench's single launch; the two sweeps apart
+            prog = gp.GridReachFused(w, one_launch=one_launch)
+            prog.step()
+            assert_close(host(prog.out.prob)[idx], ref["r"], "reachability, sampled rows")
+            assert_close(host(prog.grad_p)[idx], ref["grad_p"], "reachability gradient, sampled rows")
+            del prog
 
 
 # ---------------------------------------------------------------- Apply over K Distributions, unary Apply, ApplyIf
