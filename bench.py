@@ -302,9 +302,11 @@ def near_ties(cfg, w):
 
 def build_program(GP, cfg, wl, chain):
     if chain in ("fused", "two-sweeps"):
-        if cfg == 5:                         # the upstream gradient of this workload is an input: both sweeps in one launch
-            return GP.GridReachFused(wl, one_launch=chain == "fused")
-        fused = {2: GP.SumChainFused, 3: GP.HashedPipelineMerged, 4: GP.DtkpSumChainFused}
+        if cfg == 5:                         # the upstream gradient of these two workloads is an input: forward and
+            return GP.GridReachFused(wl, one_launch=chain == "fused")            # backward share a launch
+        if cfg == 3:
+            return GP.HashedPipelineMerged(wl, one_launch=chain == "fused")
+        fused = {2: GP.SumChainFused, 4: GP.DtkpSumChainFused}
         if cfg in fused:
             return fused[cfg](wl)
     return GP.make_program(cfg, wl)
@@ -378,9 +380,10 @@ def main():
                          "auto = graph for steps of several launches, plain launches for a single-launch step (a graph "
                          "replay of one kernel only adds its own submission gap)")
     ap.add_argument("--chain", default="fused", choices=["fused", "two-sweeps", "per-op"],
-                    help="configs 2-5: the fused entry points (dol_fold_apply2, dol_apply2_filter_union, dol_dtkp_fold_apply2, "
-                         "dol_iterate_apply2_backward); two-sweeps: the same with config 5 as dol_iterate_apply2_ckpt + "
-                         "dol_iterate_backward_ckpt; per-op: one dol_apply2 / dol_backward call per operator")
+                    help="configs 2-5: the fused entry points (dol_fold_apply2, dol_apply2_filter_union_forward_backward, "
+                         "dol_dtkp_fold_apply2, dol_iterate_apply2_backward); two-sweeps: the same with configs 3 and 5 as a forward "
+                         "and a backward launch (dol_apply2_filter_union + _backward, dol_iterate_apply2_ckpt + "
+                         "dol_iterate_backward_ckpt); per-op: one dol_apply2 / dol_backward call per operator")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--regions", type=int, default=5, help="timed regions; the step time is their median")
     ap.add_argument("--min-region-ms", type=float, default=20.0, help="a region repeats its steps until it lasts this long")

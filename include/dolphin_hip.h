@@ -182,6 +182,12 @@ typedef struct {
 dol_status dol_apply2_filter_union(const dol_apply_merge *m, void *hip_stream);
 dol_status dol_apply2_filter_union_backward(const dol_apply_merge *m, const float *grad_out, int64_t grad_out_ld, float *grad_a,
                                             float *grad_b, float *grad_c, int32_t accumulate, void *hip_stream);
+/* Both of the above in ONE launch, for an upstream gradient that does not depend on this call's result (as
+ * dol_fold_apply2 runs the loop of Fig. 2 both ways): out and saved are written as by dol_apply2_filter_union, the
+ * gradients as by dol_apply2_filter_union_backward, bit for bit.  saved must be given. */
+dol_status dol_apply2_filter_union_forward_backward(const dol_apply_merge *m, const float *grad_out, int64_t grad_out_ld,
+                                                    float *grad_a, float *grad_b, float *grad_c, int32_t accumulate,
+                                                    void *hip_stream);
 
 /* DTKP natural initialisation (App. A.1): symbol i of `d` gets the single proof {fact_of_sym[i]}.
  * fact_of_sym: host [d->n_sym].  Writes proof_mask, proof_prob and prob. */

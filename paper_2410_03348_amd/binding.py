@@ -368,6 +368,7 @@ class _ApplyMerge(C.Structure):
 _lib.dol_apply2_filter_union.argtypes = [C.POINTER(_ApplyMerge), C.c_void_p]
 _lib.dol_apply2_filter_union_backward.argtypes = [C.POINTER(_ApplyMerge), C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p,
                                                   C.c_void_p, C.c_int32, C.c_void_p]
+_lib.dol_apply2_filter_union_forward_backward.argtypes = _lib.dol_apply2_filter_union_backward.argtypes
 
 
 class ApplyMerge:
@@ -392,6 +393,15 @@ def apply2_filter_union_backward(m: ApplyMerge, grad_out: torch.Tensor, grad_a: 
     assert grad_out.dtype == torch.float32 and grad_out.stride(1) == 1
     _check(_lib.dol_apply2_filter_union_backward(C.byref(m.c), _dptr(grad_out), int(grad_out.stride(0)), _dptr(grad_a),
                                                  _dptr(grad_b), _dptr(grad_c), accumulate, _stream(stream)))
+
+
+def apply2_filter_union_forward_backward(m: ApplyMerge, grad_out: torch.Tensor, grad_a: Optional[torch.Tensor],
+                                         grad_b: Optional[torch.Tensor], grad_c: Optional[torch.Tensor], accumulate: int = 0,
+                                         stream=None):
+    """Forward and backward of union(filter(apply2(a, b, f)), c) in one launch (grad_out is an input)."""
+    assert grad_out.dtype == torch.float32 and grad_out.stride(1) == 1
+    _check(_lib.dol_apply2_filter_union_forward_backward(C.byref(m.c), _dptr(grad_out), int(grad_out.stride(0)), _dptr(grad_a),
+                                                         _dptr(grad_b), _dptr(grad_c), accumulate, _stream(stream)))
 
 
 def dtkp_init(d: Dist, fact_of_sym, prov: Prov, stream=None):

@@ -242,6 +242,24 @@ dol_status dol_apply2_filter_union_backward(const dol_apply_merge *m, const floa
                                        m->saved, accumulate, static_cast<hipStream_t>(hip_stream));
 }
 
+dol_status dol_apply2_filter_union_forward_backward(const dol_apply_merge *m, const float *grad_out, int64_t grad_out_ld,
+                                                    float *grad_a, float *grad_b, float *grad_c, int32_t accumulate,
+                                                    void *hip_stream)
+{
+    const UnionPlan *plan = nullptr;
+    if (dol_status st = check_apply_merge(m, &plan)) return st;
+    if (!grad_out) return fail(DOL_EINVAL, "grad_out is NULL");
+    if (!grad_a && !grad_b && !grad_c) return fail(DOL_EINVAL, "grad_a, grad_b and grad_c are all NULL");
+    if (!m->saved) return fail(DOL_EINVAL, "saved is NULL: the backward pass of this call reads the forward pass's clamp words");
+    auto off16 = [](const void *ptr) { return (reinterpret_cast<uintptr_t>(ptr) & 15u) != 0; };
+    if (grad_out_ld != plan->n_out || off16(grad_out) || off16(grad_a) || off16(grad_b) || off16(grad_c))
+        return fail(DOL_EUNSUPPORTED, "the one-launch form needs contiguous 16-byte aligned gradient tensors");
+    if (grad_a && grad_a == grad_b) return fail(DOL_EINVAL, "grad_a and grad_b are the same tensor");
+    if (m->a->batch == 0) return DOL_OK;
+    return launch_damp_table_merge_both(m->f, plan, m->a->batch, m->a->prob, m->b->prob, m->c->prob, m->out->prob, m->saved, grad_out,
+                                        grad_a, grad_b, grad_c, accumulate, static_cast<hipStream_t>(hip_stream));
+}
+
 dol_status dol_dtkp_init(dol_dist *d, const int32_t *fact_of_sym, const dol_prov *prov, void *hip_stream)
 {
     if (!is_dtkp(prov)) return fail(DOL_EINVAL, "dol_dtkp_init needs a DTKP provenance");

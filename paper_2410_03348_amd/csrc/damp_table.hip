@@ -40,7 +40,8 @@ constexpr int kJitMaxMergeOut = 512;   // merged launches keep the Apply's whole
 constexpr int64_t kJitMaxTuples = 16384;
 
 // (the last two: merged launches whose filter-union plan is `aligned`, see UnionPlan)
-enum { kSlotFwd = 0, kSlotBwd = 1, kSlotMergeFwd = 2, kSlotMergeBwd = 3, kSlotMergeFwdAligned = 4, kSlotMergeBwdAligned = 5, kSlots = 6 };
+enum { kSlotFwd = 0, kSlotBwd = 1, kSlotMergeFwd = 2, kSlotMergeBwd = 3, kSlotMergeFwdAligned = 4, kSlotMergeBwdAligned = 5, kSlotMergeBoth = 6,
+       kSlotMergeBothAligned = 7, kSlots = 8 };
 
 struct JitState {
     std::mutex mu;
@@ -134,7 +135,8 @@ void emit_tile_head(Src &o)
 
 // Forward.  merged: the kept symbols of the result are merged with a third Distribution c in the same launch
 // (out = union(filter(apply2(a, b)), c)); the Apply's own result then lives in LDS only.
-std::string forward_source(const dol_fn_table *f, bool merged, bool aligned = false)
+// (body: a device function over an LDS array handed in, for the kernel that runs both passes; returns its LDS floats in *lds_floats)
+std::string forward_source(const dol_fn_table *f, bool merged, bool aligned = false, bool body = false, int *lds_floats = nullptr)
 {
     const int na = f->na, nb = f->nb, S = f->n_out;
     const int pa = na + 4, pb = nb + 4;
@@ -143,15 +145,20 @@ std::string forward_source(const dol_fn_table *f, bool merged, bool aligned = fa
     const int in_floats = kJitTile * (pa + pb), out_floats = merged ? kJitTile * po : kJitWaves * kJitTile * po;
     const int stage_floats = std::max(in_floats, out_floats);
     Src o;
-    o.s = kPrologue;
-    if (merged)
+    if (!body) o.s = kPrologue;
+    if (lds_floats) *lds_floats = stage_floats + (merged ? kJitTile : 0);
+    if (body)
+        o("static __device__ __forceinline__ void damp_table_merge_fwd_body(float *lds, const float *__restrict__ a, const float *__restrict__ b, "
+          "const float *__restrict__ c, float *__restrict__ out, const int *__restrict__ ia, const int *__restrict__ ib, int *saved, "
+          "int batch, int n_tiles, int nc, int n3)\n{\n");
+    else if (merged)
         o("extern \"C\" __global__ void __launch_bounds__(%d) __attribute__((amdgpu_waves_per_eu(2, 2))) damp_table_merge_fwd_kernel(const float *__restrict__ a, const float *__restrict__ b, "
           "const float *__restrict__ c, float *__restrict__ out, const int *__restrict__ ia, const int *__restrict__ ib, int *__restrict__ saved, "
           "int batch, int n_tiles, int nc, int n3)\n{\n", kThreads);
     else
         o("extern \"C\" __global__ void __launch_bounds__(%d) __attribute__((amdgpu_waves_per_eu(2, 2))) damp_table_fwd_kernel(const float *__restrict__ a, const float *__restrict__ b, "
           "float *__restrict__ out, int batch, int n_tiles)\n{\n", kThreads);
-    o("  __shared__ __align__(16) float lds[%d];\n", stage_floats + (merged ? kJitTile : 0));
+    if (!body) o("  __shared__ __align__(16) float lds[%d];\n", stage_floats + (merged ? kJitTile : 0));
     o("  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // (a scalar: branches on it are uniform)\n");
     o("  float *sa = lds, *sb = lds + %d, *so = lds + wave * %d;\n", kJitTile * pa, merged ? 0 : kJitTile * po);
     if (merged) o("  int *sflag = reinterpret_cast<int *>(lds + %d);\n", stage_floats);
@@ -285,7 +292,7 @@ void emit_gh_store(Src &o, int c0, int c1, int g, int n_groups, const char *dst,
     }
 }
 
-std::string backward_source(const dol_fn_table *f, bool merged, bool aligned = false)
+std::string backward_source(const dol_fn_table *f, bool merged, bool aligned = false, bool body = false, int *lds_floats = nullptr)
 {
     const int na = f->na, nb = f->nb, S = f->n_out;
     const int pa = na + 4, pb = nb + 4, pg = kJitGroup + 4;
@@ -299,8 +306,14 @@ std::string backward_source(const dol_fn_table *f, bool merged, bool aligned = f
     const int ha = std::min(na, std::max(4, (na / 2 + 3) & ~3)), hb = std::min(nb, std::max(4, (nb / 2 + 3) & ~3));
     const int gh_per_thread = (kJitTile * (kJitGroup / 4) + kThreads - 1) / kThreads;
     Src o;
-    o.s = kPrologue;
-    if (merged)
+    if (!body) o.s = kPrologue;
+    if (lds_floats) *lds_floats = off_f + 4;
+    if (body)
+        o("static __device__ __forceinline__ void damp_table_merge_bwd_body(float *lds, const float *__restrict__ a, const float *__restrict__ b, "
+          "const float *__restrict__ c, const float *__restrict__ g, float *__restrict__ ga, float *__restrict__ gb, float *__restrict__ gc, "
+          "const int *__restrict__ ia, const int *__restrict__ ib, const int *__restrict__ ca, const int *__restrict__ cb, "
+          "const int *saved, int batch, int n_tiles, int nc, int n3, int accumulate)\n{\n");
+    else if (merged)
         o("extern \"C\" __global__ void __launch_bounds__(%d) __attribute__((amdgpu_waves_per_eu(2, 2))) damp_table_merge_bwd_kernel(const float *__restrict__ a, const float *__restrict__ b, "
           "const float *__restrict__ c, const float *__restrict__ g, float *__restrict__ ga, float *__restrict__ gb, float *__restrict__ gc, "
           "const int *__restrict__ ia, const int *__restrict__ ib, const int *__restrict__ ca, const int *__restrict__ cb, "
@@ -308,7 +321,7 @@ std::string backward_source(const dol_fn_table *f, bool merged, bool aligned = f
     else
         o("extern \"C\" __global__ void __launch_bounds__(%d) __attribute__((amdgpu_waves_per_eu(2, 2))) damp_table_bwd_kernel(const float *__restrict__ a, const float *__restrict__ b, "
           "const float *__restrict__ g, float *__restrict__ ga, float *__restrict__ gb, int batch, int n_tiles, int accumulate)\n{\n", kThreads);
-    o("  __shared__ __align__(16) float lds[%d];\n", off_f + 4);
+    if (!body) o("  __shared__ __align__(16) float lds[%d];\n", off_f + 4);
     o("  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // (a scalar: branches on it are uniform)\n");
     o("  float *sa = lds, *sb = lds + %d, *sg0 = lds + %d, *sg1 = lds + %d;\n", off_b, off_g, off_g + stage);
     o("  u32 *sm = reinterpret_cast<u32 *>(lds + %d);\n  int *flag = reinterpret_cast<int *>(lds + %d);\n", off_m, off_f);
@@ -463,6 +476,29 @@ std::string backward_source(const dol_fn_table *f, bool merged, bool aligned = f
     return o.s;
 }
 
+// Apply + Filter + Union forward and backward in one launch: the two bodies above over one LDS array.  The backward
+// body reads the per-sample clamp words the forward body has just written (other threads' words: the workgroup's
+// barrier between the two orders them).
+std::string both_source(const dol_fn_table *f, bool aligned)
+{
+    int lf = 0, lb = 0;
+    const std::string fwd = forward_source(f, true, aligned, true, &lf), bwd = backward_source(f, true, aligned, true, &lb);
+    Src o;
+    o.s = kPrologue;
+    o.s += fwd;
+    o.s += bwd;
+    o("extern \"C\" __global__ void __launch_bounds__(%d) __attribute__((amdgpu_waves_per_eu(2, 2))) damp_table_merge_fwd_bwd_kernel("
+      "const float *__restrict__ a, const float *__restrict__ b, const float *__restrict__ c, float *__restrict__ out, "
+      "const float *__restrict__ g, float *__restrict__ ga, float *__restrict__ gb, float *__restrict__ gc, const int *__restrict__ ia, "
+      "const int *__restrict__ ib, const int *__restrict__ ca, const int *__restrict__ cb, int *saved, int batch, int n_tiles, int nc, int n3, "
+      "int accumulate)\n{\n", kThreads);
+    o("  __shared__ __align__(16) float lds[%d];\n", std::max(lf, lb));
+    o("  damp_table_merge_fwd_body(lds, a, b, c, out, ia, ib, saved, batch, n_tiles, nc, n3);\n");
+    o("  __syncthreads();\n");
+    o("  damp_table_merge_bwd_body(lds, a, b, c, g, ga, gb, gc, ia, ib, ca, cb, saved, batch, n_tiles, nc, n3, accumulate);\n}\n");
+    return o.s;
+}
+
 }  // namespace
 
 dol_status jit_compile(const std::string &src, const char *name, hipModule_t *mod, hipFunction_t *fn)
@@ -523,14 +559,16 @@ JitState *state_of(const dol_fn_table *f)
 static dol_status kernel_of(const dol_fn_table *f, int slot, hipFunction_t *fn)
 {
     static const char *const names[kSlots] = {"damp_table_fwd_kernel", "damp_table_bwd_kernel", "damp_table_merge_fwd_kernel",
-                                              "damp_table_merge_bwd_kernel", "damp_table_merge_fwd_kernel", "damp_table_merge_bwd_kernel"};
+                                              "damp_table_merge_bwd_kernel", "damp_table_merge_fwd_kernel", "damp_table_merge_bwd_kernel",
+                                              "damp_table_merge_fwd_bwd_kernel", "damp_table_merge_fwd_bwd_kernel"};
     JitState *js = state_of(f);
     std::lock_guard<std::mutex> lock(js->mu);
     if (!js->tried[slot]) {
         js->tried[slot] = true;
         const std::string src = slot == kSlotFwd ? forward_source(f, false) : slot == kSlotBwd ? backward_source(f, false) :
                                 slot == kSlotMergeFwd ? forward_source(f, true) : slot == kSlotMergeBwd ? backward_source(f, true) :
-                                slot == kSlotMergeFwdAligned ? forward_source(f, true, true) : backward_source(f, true, true);
+                                slot == kSlotMergeFwdAligned ? forward_source(f, true, true) :
+                                slot == kSlotMergeBwdAligned ? backward_source(f, true, true) : both_source(f, slot == kSlotMergeBothAligned);
         js->status[slot] = jit_compile(src, names[slot], &js->mod[slot], &js->fn[slot]);
         if (js->status[slot] != DOL_OK) return js->status[slot];      // with the compiler's message
     } else if (js->status[slot] != DOL_OK) {
@@ -597,6 +635,19 @@ dol_status launch_damp_table_merge_bwd(const dol_fn_table *f, const UnionPlan *p
     int n_tiles = (batch + kJitTile - 1) / kJitTile, nc = p->nb, n3 = p->n_out;
     const int32_t *ia = p->d_ia.ptr, *ib = p->d_ib.ptr, *ca = p->d_ca.ptr, *cb = p->d_cb.ptr;
     void *args[] = {&a, &b, &c, &g, &ga, &gb, &gc, &ia, &ib, &ca, &cb, &saved, &batch, &n_tiles, &nc, &n3, &accumulate};
+    DOL_HIP(hipModuleLaunchKernel(fn, tile_grid(n_tiles), 1, 1, kThreads, 1, 1, 0, st, args, nullptr));
+    return DOL_OK;
+}
+
+dol_status launch_damp_table_merge_both(const dol_fn_table *f, const UnionPlan *p, int32_t batch, const float *a, const float *b,
+                                        const float *c, float *out, int32_t *saved, const float *g, float *ga, float *gb, float *gc,
+                                        int32_t accumulate, hipStream_t st)
+{
+    hipFunction_t fn = nullptr;
+    if (dol_status s = kernel_of(f, p->aligned ? kSlotMergeBothAligned : kSlotMergeBoth, &fn)) return s;
+    int n_tiles = (batch + kJitTile - 1) / kJitTile, nc = p->nb, n3 = p->n_out;
+    const int32_t *ia = p->d_ia.ptr, *ib = p->d_ib.ptr, *ca = p->d_ca.ptr, *cb = p->d_cb.ptr;
+    void *args[] = {&a, &b, &c, &out, &g, &ga, &gb, &gc, &ia, &ib, &ca, &cb, &saved, &batch, &n_tiles, &nc, &n3, &accumulate};
     DOL_HIP(hipModuleLaunchKernel(fn, tile_grid(n_tiles), 1, 1, kThreads, 1, 1, 0, st, args, nullptr));
     return DOL_OK;
 }

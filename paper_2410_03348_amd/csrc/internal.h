@@ -273,6 +273,9 @@ dol_status launch_damp_table_merge_fwd(const dol_fn_table *f, const UnionPlan *p
 dol_status launch_damp_table_merge_bwd(const dol_fn_table *f, const UnionPlan *p, int32_t batch, const float *a, const float *b,
                                        const float *c, const float *g, float *ga, float *gb, float *gc, const int32_t *saved,
                                        int32_t accumulate, hipStream_t st);
+dol_status launch_damp_table_merge_both(const dol_fn_table *f, const UnionPlan *p, int32_t batch, const float *a, const float *b,
+                                        const float *c, float *out, int32_t *saved, const float *g, float *ga, float *gb, float *gc,
+                                        int32_t accumulate, hipStream_t st);
 // Filter / Union on contiguous 16-byte aligned tensors (damp_rows.hip); *done = false: not taken
 dol_status launch_rows_gather(int32_t batch, int32_t n_in, int32_t n_out, const int32_t *src_col, const float *in,
                               int64_t ldi, float *out, int64_t ldo, int32_t accumulate, hipStream_t st, bool *done);

@@ -256,7 +256,7 @@ class HashedPipelineMerged(Program):
     """Config 3 through dol_apply2_filter_union: Apply, Filter and Union in one launch, their reverse in another;
     only the program's inputs and results touch HBM (plus one word per sample that says whether a clamp acted)."""
 
-    def __init__(self, w, device="cuda"):
+    def __init__(self, w, device="cuda", one_launch=False):
         B = w["pa"].shape[0]
         self.batch = B
         self.table = dol.FnTable.create_dense(w["table"])
@@ -281,6 +281,10 @@ class HashedPipelineMerged(Program):
                    lambda: dol.apply2_filter_union_backward(self.merge, self.g3, self.ga, self.gb, self.gp2),
                    4 * B * (n3 + 2 * (na + nb) + np2), 2 * B * n_tup, "bwd"),
         ]
+        if one_launch:                       # dol_apply2_filter_union_forward_backward: the gradient is an input
+            self.launches = [Launch("damp_table_merge_fwd_bwd_kernel",
+                                    lambda: dol.apply2_filter_union_forward_backward(self.merge, self.g3, self.ga, self.gb, self.gp2),
+                                    4 * B * (2 * (na + nb + np2) + 2 * n3), 3 * B * n_tup, "fwd+bwd")]
         self.sample_ops = 6 * B
         self.min_bytes = 4 * B * (2 * (na + nb + np2) + 2 * n3)
         self.flops = 2 * 3 * B * n_tup

@@ -229,6 +229,40 @@ def test_config3_apply_filter_union_in_one_launch(gp, dol, batch, na, nb, n_out,
     np.testing.assert_array_equal(host(gb), host(prog.gb))
 
 
+@pytest.mark.parametrize("batch,scale", [(16384, 1.0), (333, 12.0), (64, 1.0), (1, 1.0)])
+def test_config3_forward_and_backward_in_one_launch(gp, dol, batch, scale):
+    """dol_apply2_filter_union_forward_backward: the results of the two separate calls, bit for bit (clamp words included),
+    with samples in which clamps act (scale > 1) and without."""
+    w = W.config3(batch=batch, seed=21)
+    if scale != 1.0:
+        for key in ("pa", "pb", "p2"):
+            w.arrays[key] = np.minimum(w[key] * np.float32(scale), np.float32(1.0))
+    two = gp.HashedPipelineMerged(w)
+    two.step()
+    one = gp.HashedPipelineMerged(w, one_launch=True)
+    assert len(one.launches) == 1
+    for t in (one.o3.prob, one.ga, one.gb, one.gp2):
+        t.fill_(-3.0)
+    one.saved.fill_(-3)
+    one.step()
+    np.testing.assert_array_equal(host(one.o3.prob), host(two.o3.prob))
+    np.testing.assert_array_equal(host(one.saved), host(two.saved))
+    np.testing.assert_array_equal(host(one.ga), host(two.ga))
+    np.testing.assert_array_equal(host(one.gb), host(two.gb))
+    np.testing.assert_array_equal(host(one.gp2), host(two.gp2))
+    if scale != 1.0:
+        assert host(one.saved).any()
+    ref = OP.hashed_pipeline_fwd_bwd(w)
+    assert_close(host(one.o3.prob), ref["o3"], "one-launch forward")
+    if scale == 1.0:                          # (mixed-sign gradients over unnormalised tags cannot meet the absolute bar)
+        assert_close(host(one.ga), ref["ga"], "one-launch grad a")
+        assert_close(host(one.gp2), ref["gp2"], "one-launch grad c")
+    with pytest.raises(dol.DolError) as ei:   # the backward pass of this call needs the clamp words
+        dol.apply2_filter_union_forward_backward(dol.ApplyMerge(one.a, one.b, one.table, one.pred, one.p2, one.o3, None), one.g3,
+                                                 one.ga, one.gb, one.gp2)
+    assert ei.value.status == 1
+
+
 def test_apply_filter_union_rejects_what_it_cannot_take(dol):
     w = W.config3(batch=8, na=17, nb=33, n_out=40, seed=3)                     # symbol counts that are not multiples of 4
     f = dol.FnTable.create_dense(w["table"])
@@ -962,7 +996,7 @@ def test_dtkp_general_conjunction_union_filter(dol):
     np.testing.assert_array_equal(host(fo.prob), fpr)
 
 
-@pytest.mark.parametrize("which", ["chain", "fold", "hashed", "hashed-fused", "dtkp-fold", "reach-fused", "reach-one-launch", "hashed-merged", "product",
+@pytest.mark.parametrize("which", ["chain", "fold", "hashed", "hashed-fused", "dtkp-fold", "reach-fused", "reach-one-launch", "hashed-merged", "hashed-one-launch", "product",
                                    "formula-damp", "formula-dtkp"])
 def test_hip_graph_replay_matches_eager(gp, which):
     """Every entry point issues only asynchronous launches once its symbol-side plans exist, so a whole step can be
@@ -977,6 +1011,8 @@ def test_hip_graph_replay_matches_eager(gp, which):
         prog = gp.HashedPipelineFused(W.config3(batch=320, seed=5)); key = lambda: prog.ga
     elif which == "hashed-merged":
         prog = gp.HashedPipelineMerged(W.config3(batch=320, seed=5)); key = lambda: prog.ga
+    elif which == "hashed-one-launch":
+        prog = gp.HashedPipelineMerged(W.config3(batch=320, seed=5), one_launch=True); key = lambda: prog.ga
     elif which == "reach-one-launch":
         prog = gp.GridReachFused(W.config5(batch=16, side=8, rounds=12, seed=5), one_launch=True); key = lambda: prog.grad_p
     elif which == "dtkp-fold":
