@@ -111,10 +111,12 @@ __device__ __forceinline__ void iterate_round(const Cached<CA> (&col)[K], const 
 template <int T, int K, int CA, bool TAILS, bool PRE = false>
 __device__ __forceinline__ void iterate_forward(const ItFwdArgs &A, float *lds, Cached<CA> (&col)[K])
 {
-    // lds: x (two rows of na + 1), e (nb + 1): each row ends with a zero
-    const int na = A.na, nb = A.nb;
-    float *x0 = lds, *x1 = lds + na + 1;
-    float *le = lds + 2 * (na + 1);
+    // lds: x (two rows of na + 1), e (nb + 1): each row ends with a zero.  PRE (both sweeps in one launch): the layout of
+    // the reverse sweep instead, whose first two segment rows serve as x; the rounds of the last segment are then written
+    // row after row into that segment, where the reverse sweep finds them without replaying them.
+    const int na = A.na, nb = A.nb, na1 = na + 1;
+    float *x0 = lds, *x1 = lds + na1;
+    float *le = lds + (PRE ? A.every + 3 : 2) * na1;
     const int tid = threadIdx.x;
     const int64_t s = blockIdx.x;
     const int64_t plane = static_cast<int64_t>(A.batch) * na;
@@ -126,7 +128,11 @@ __device__ __forceinline__ void iterate_forward(const ItFwdArgs &A, float *lds, 
         if (A.rounds == 0 && A.out) A.out[s * A.ldo + c] = v;
     }
     for (int j = tid; j < nb; j += T) le[j] = e_row[j];
-    if (tid == 0) { x0[na] = 0.0f; x1[na] = 0.0f; le[nb] = 0.0f; }
+    if (tid == 0) {
+        x0[na] = 0.0f; x1[na] = 0.0f; le[nb] = 0.0f;
+        if constexpr (PRE)
+            for (int x = 2; x <= A.every; ++x) lds[x * na1 + na] = 0.0f;
+    }
     if constexpr (!PRE) {
 #pragma unroll
         for (int k = 0; k < K; ++k) load_cached(col[k], A.col_ptr, A.col_ij, tid + T * k, na, pack16(na, nb));
@@ -138,9 +144,10 @@ __device__ __forceinline__ void iterate_forward(const ItFwdArgs &A, float *lds, 
     // `every`-th with checkpoints, the last one always.  Inside a stretch a round is LDS reads, the fma chain, one
     // LDS write and the barrier; the two rows swap roles from round to round.
     const int stride = A.hist ? 1 : A.every;
+    const int t_keep = PRE && A.rounds > 0 ? (A.rounds - 1) / A.every * A.every : A.rounds;    // first round of the kept segment
     float pre[K];
     int t = 0, n_ckpt = 0;
-    while (t < A.rounds) {
+    while (t < t_keep) {
         const int stop = min(A.rounds, (t / stride + 1) * stride);
         for (; t + 1 < stop; t += 2) {
             iterate_round<T, K, CA, TAILS>(col, A.col_ij, x0, x1, le, na, pre);
@@ -161,6 +168,27 @@ __device__ __forceinline__ void iterate_forward(const ItFwdArgs &A, float *lds, 
             if (c < na) {
                 if (dst) dst[c] = v;
                 if (t == A.rounds && A.out) A.out[s * A.ldo + c] = v;
+            }
+        }
+    }
+    if constexpr (PRE) {
+        if (A.rounds > 0) {
+            if (x0 != lds) {                // r_t sits in the second row: every thread moves its own columns to the first
+#pragma unroll
+                for (int k = 0; k < K; ++k) {
+                    const int c = tid + T * k;
+                    if (c < na) lds[c] = x0[c];
+                }
+                lds_barrier();
+            }
+            for (; t < A.rounds; ++t) {
+                const int x = t - t_keep;
+                iterate_round<T, K, CA, TAILS>(col, A.col_ij, lds + x * na1, lds + (x + 1) * na1, le, na, pre);
+            }
+#pragma unroll
+            for (int k = 0; k < K; ++k) {
+                const int c = tid + T * k;
+                if (c < na && A.out) A.out[s * A.ldo + c] = fminf(pre[k], 1.0f);
             }
         }
     }
@@ -282,8 +310,9 @@ __device__ __forceinline__ void iterate_backward(const ItBwdArgs &A, float *lds,
     const int n_seg = (A.rounds + A.every - 1) / A.every;
     for (int sg = n_seg - 1; sg >= 0; --sg) {
         const int t0 = sg * A.every, len = min(A.every, A.rounds - t0);
-        // ---- the rounds of this segment into seg[0 .. len]
-        if (A.hist) {
+        // ---- the rounds of this segment into seg[0 .. len] (PRE: the forward sweep has left the last segment there)
+        if (PRE && sg == n_seg - 1) {
+        } else if (A.hist) {
             for (int x = 0; x <= len; ++x) {
                 const float *h = A.hist + (t0 + x) * plane + s * na;
                 for (int c = tid; c < na; c += T) seg[x * na1 + c] = h[c];
