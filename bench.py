@@ -102,9 +102,9 @@ def copy_rate(torch, mib=1024, reps=5):
     return round(2.0 * mib * (1 << 20) * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)
 
 
-def time_launches(prog, torch, repeats, min_pair_ms=2.0):
+def time_launches(prog, torch, repeats, min_pair_ms=4.0):
     """Average duration of every launch of a step: back-to-back launches between two HIP events on the launch
-    stream, as many as make the pair span min_pair_ms (at least `repeats`).
+    stream, as many as make the pair span min_pair_ms (at least `repeats`); the fastest of three such pairs.
     Returns {kernel: dict(launches, ms, bytes, macs)} summed over one step."""
     per_kernel = {}
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -122,7 +122,7 @@ def time_launches(prog, torch, repeats, min_pair_ms=2.0):
         l.call()
         first = pair(l, repeats)
         n = max(repeats, int(math.ceil(repeats * budget / max(first, 1e-6))))
-        ms = pair(l, n) / n if n > repeats else first / repeats
+        ms = min(pair(l, n) for _ in range(3)) / n if n > repeats else first / repeats     # (the fastest of three pairs)
         k = per_kernel.setdefault(l.kernel, dict(launches=0, ms=0.0, bytes=0, macs=0))
         k["launches"] += 1
         k["ms"] += ms

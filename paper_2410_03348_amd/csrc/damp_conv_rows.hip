@@ -22,7 +22,7 @@ namespace dol {
 namespace {
 
 constexpr int kRowsTile = 64;           // samples per workgroup
-constexpr size_t kRowsFewLdsFwd = 30 * 1024, kRowsFewLds = 48 * 1024;       // tiles of up to this much LDS run four wavefronts (several tiles
+constexpr size_t kRowsFewLdsFwd = 30 * 1024, kRowsFewLds = 40 * 1024;       // tiles of up to this much LDS run four wavefronts (several tiles
                                                 // share a compute unit), larger ones eight
 constexpr int kRowsMinBatch = 16384;    // below, 64-sample tiles leave most of the chip idle
 constexpr int kRowsMinM = 17, kRowsMaxM = 192;
