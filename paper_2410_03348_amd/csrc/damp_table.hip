@@ -22,6 +22,11 @@
 // most tuples of one column that share a second-operand symbol (and the same with the operands' roles swapped): a
 // tile whose samples all stay below 0.9999 by that bound cannot hold a clamped column and passes g through without
 // ever reading the forward result; any other tile recomputes pre with the forward code and gates with it.
+//
+// Merged forms (dol_apply2_filter_union and its reverse): the same kernels with Filter and Union folded into their
+// epilogues, so the Apply's result never leaves the chip; the forward pass leaves one word per sample saying whether
+// any clamp acted, and the reverse pass re-derives decisions only for tiles that hold such a sample.  The two merged
+// bodies are also emitted as device functions of one kernel (dol_apply2_filter_union_forward_backward).
 #include "internal.h"
 
 #include <hip/hiprtc.h>

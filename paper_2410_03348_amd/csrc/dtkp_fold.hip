@@ -6,7 +6,8 @@
 // fact probabilities once and the final Distribution once.  Optionally the gradient of the final tag
 // probabilities w.r.t. the fact probabilities follows in the same launch (lane f owns fact f).
 // Candidate order, proof probabilities, exclusion test and list order are those of dol_apply2, so the result is the
-// same bit for bit.
+// same bit for bit.  The sorted list of a column carries probabilities and the origin of each proof; masks are built
+// for the k winners only, and a stage whose input brings only new, higher facts (fresh_t below) never reads one.
 #include "dtkp_util.h"
 #include "wave_util.h"
 

@@ -4,9 +4,10 @@
 // halos (they are the operands of the backward pass), the short inputs, and two gradient rows.  HBM sees the
 // inputs once, the final Distribution once and the input gradients once.
 //
-// Two kernels share this layout idea: damp_fold4_kernel (four consecutive columns per lane, 16-byte LDS
-// accesses; the one normally launched) and damp_fold_kernel (one column per lane, 4-byte accesses; its rows need
-// no padding to multiples of four, so it still fits when the first does not).
+// Chains whose shape fits it run the kernel that fold_chain.hip writes for the shape; the kernels of this file serve
+// the others.  Two share this layout idea: damp_fold4_kernel (four consecutive columns per lane, 16-byte LDS
+// accesses) and damp_fold_kernel (one column per lane, 4-byte accesses; its rows need no padding to multiples of four,
+// so it still fits when the first does not).
 //
 // Arithmetic is that of the per-operator kernels: out[c] = min(1, sum over ascending i of a[i] * b[c-i]) with
 // one fma per tuple; gradients are gated by [pre <= 1], re-derived only for stages in which some lane saw
