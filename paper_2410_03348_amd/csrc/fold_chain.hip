@@ -8,10 +8,14 @@
 //   - the operand window of a block slides through registers: w + nb - 1 LDS reads feed w * nb multiply-adds;
 //   - no lane idles in a narrow stage and no stage pays for a fixed four-column granularity;
 //   - every LDS offset is an immediate, every loop is gone.
-// Everything a sample needs lives in its LDS region: the running Distributions acc_0 .. acc_{n-1} (operands of the
-// reverse sweep), the short inputs and two gradient rows.  A stage's result is kept as x = pre where pre <= 1 and -1
-// where the clamp acted: |x| is the tag (the absolute value is free in a multiply-add) and the sign is the clamp's
-// decision, read by the reverse sweep with the operand it needs anyway - no stage is ever summed twice.
+// The reverse sweep needs every running Distribution again, but a lane needs exactly the block it computed itself.  Two
+// forms of the code: every Distribution keeps a row of its own in the sample's LDS region (7.8 KB per sample for Sum-15),
+// or the blocks stay in their lanes' registers (63 per lane) and LDS holds two row buffers, the one a stage reads and the
+// one it writes (3.4 KB per sample, a dozen wavefronts on a compute unit instead of five); the launcher picks by the size
+// of the grid.  Beside the rows the region holds the short inputs and two gradient rows.
+// A stage's result is kept as x = pre where pre <= 1 and -1 where the
+// clamp acted: |x| is the tag (the absolute value is free in a multiply-add) and the sign is the clamp's decision, read
+// by the reverse sweep with the operand it needs anyway - no stage is ever summed twice.
 //
 // Arithmetic is that of dol_apply2 / dol_backward: out[c] = min(1, sum over ascending i of a[i] * b[c - i]), one
 // fused multiply-add per tuple from 0; gradients gated by [pre <= 1].
@@ -30,6 +34,11 @@ namespace {
 constexpr int kLanes = 16;
 constexpr int kNBR = 16;                // floats reserved per short input row
 constexpr size_t kChainLdsMax = 40 * 1024;   // per wavefront: at least four wavefronts per compute unit
+// From this many workgroups on, the form with the reverse sweep's operands in registers: less than half the LDS, so a
+// dozen wavefronts per compute unit instead of five (Sum-15: 20.3 against 28.8 us at 2048 workgroups, 252 against 341 us
+// at 32768).  Below, with one wavefront per SIMD, the form with every row in LDS is the faster one (14.4 against 15.3 us
+// at 1024 workgroups).
+constexpr int64_t kRegsFromWorkgroups = 1536;
 
 struct Src {
     std::string s;
@@ -47,15 +56,18 @@ struct Src {
 struct Layout {
     int n = 0;
     int m[kFoldChainMax] = {}, nb[kFoldChainMax] = {};
-    int w[kFoldChainMax] = {};          // columns of acc_t per lane (t >= 1)
-    int off[kFoldChainMax] = {};        // first value of acc_t inside a sample's region
+    int w[kFoldChainMax] = {};          // columns of acc_t per lane
+    int off[kFoldChainMax] = {};        // first value of acc_t inside a sample's region (in row buffer t & 1)
     int ext[kFoldChainMax] = {};        // entries of acc_t's row that are read (values, then zeros)
+    int buf = 0;                        // floats of one of the two row buffers
     int off_d = 0, off_g0 = 0, off_g1 = 0, g_len = 0, stride = 0;
 };
 
 int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
-Layout lay_out(const std::vector<int> &shape, int kL)
+// regs: the reverse sweep's operands stay in the registers of the lanes that computed them and LDS holds two row buffers;
+// otherwise every running Distribution keeps a row of its own in LDS.
+Layout lay_out(const std::vector<int> &shape, int kL, bool regs)
 {
     Layout Y;
     Y.n = shape[0];
@@ -65,14 +77,32 @@ Layout lay_out(const std::vector<int> &shape, int kL)
         Y.m[t] = Y.m[t - 1] + Y.nb[t] - 1;
         Y.w[t] = ceil_div(Y.m[t], kL);
     }
+    Y.w[0] = ceil_div(Y.m[0], kL);
     int pos = 0;
-    for (int t = 0; t < Y.n; ++t) {
-        const int halo = t + 1 < Y.n ? Y.nb[t + 1] - 1 : 0;       // the next stage reads nb - 1 entries before the row
-        int ext = std::max(Y.m[t], t >= 1 ? kL * Y.w[t] : 0);    // a stage writes whole blocks
-        if (t + 1 < Y.n) ext = std::max(ext, kL * Y.w[t + 1]);   // and the next one reads whole blocks
-        Y.off[t] = pos + halo;
-        Y.ext[t] = ext;
-        pos = Y.off[t] + ext;
+    if (regs) {
+        // Two row buffers: acc_t lives in buffer t & 1 while the next stage reads it.  A buffer holds a zero halo in front
+        // (the next stage reads nb - 1 entries before the row) and the widest extent any stage writes or reads.  Rows only
+        // grow, so what a buffer holds beyond the row it carries is an earlier, shorter row's zeros.
+        int halo = 0, extent = 0;
+        for (int t = 0; t < Y.n; ++t) {
+            if (t + 1 < Y.n) halo = std::max(halo, Y.nb[t + 1] - 1);
+            int ext = std::max(Y.m[t], t >= 1 ? kL * Y.w[t] : 0);    // a stage writes whole blocks
+            if (t + 1 < Y.n) ext = std::max(ext, kL * Y.w[t + 1]);   // and the next one reads whole blocks
+            Y.ext[t] = ext;
+            extent = std::max(extent, ext);
+        }
+        Y.buf = halo + extent;
+        for (int t = 0; t < Y.n; ++t) Y.off[t] = (t & 1) * Y.buf + halo;
+        pos = 2 * Y.buf;
+    } else {
+        for (int t = 0; t < Y.n; ++t) {
+            const int halo = t + 1 < Y.n ? Y.nb[t + 1] - 1 : 0;       // the next stage reads nb - 1 entries before the row
+            int ext = std::max(Y.m[t], t >= 1 ? kL * Y.w[t] : 0);    // a stage writes whole blocks
+            if (t + 1 < Y.n) ext = std::max(ext, kL * Y.w[t + 1]);   // and the next one reads whole blocks
+            Y.off[t] = pos + halo;
+            Y.ext[t] = ext;
+            pos = Y.off[t] + ext;
+        }
     }
     Y.off_d = pos;
     pos += Y.n * kNBR;
@@ -95,10 +125,10 @@ void emit_zero(Src &o, int start, int len, int kL)
     }
 }
 
-std::string chain_source(const std::vector<int> &shape, int kL)
+std::string chain_source(const std::vector<int> &shape, int kL, bool regs)
 {
     const int kSP = 64 / kL;
-    const Layout Y = lay_out(shape, kL);
+    const Layout Y = lay_out(shape, kL, regs);
     const int n = Y.n, n1 = n - 1;
     Src o;
     o("typedef unsigned long long u64;\n");
@@ -139,8 +169,11 @@ std::string chain_source(const std::vector<int> &shape, int kL)
     }
     o("#define DOL_ROW(name, start, step) int name##_i = qb + 4 * (start) + lw##step; asm volatile(\"\" : \"+v\"(name##_i)); "
       "float *name = reinterpret_cast<float *>(reinterpret_cast<char *>(lds) + name##_i)\n");
-    // ---- zeros where a window may reach beyond what is written
-    {
+    if (regs) {
+        // ---- both row buffers start as zeros (halos, and whatever lies beyond a row)
+        emit_zero(o, 0, 2 * Y.buf, kL);
+    } else {
+        // ---- zeros where a window may reach beyond what is written
         int pos = 0;
         for (int t = 0; t < n; ++t) {
             emit_zero(o, pos, Y.off[t] - pos, kL);                       // the halo in front of the row
@@ -169,6 +202,12 @@ std::string chain_source(const std::vector<int> &shape, int kL)
         }
     }
     o("  fence();\n");
+    // ---- a lane's own block of every running Distribution stays in registers for the reverse sweep (sign = clamp decision)
+    if (regs) {
+        for (int k = 0; k < Y.w[0]; ++k) o("  const float h0_%d = base[%d + l * %d + %d];\n", k, Y.off[0], Y.w[0], k);
+        for (int t = 1; t < n; ++t)
+            for (int k = 0; k < Y.w[t]; ++k) o("  float h%d_%d;\n", t, k);
+    }
     // ---- forward sweep
     for (int t = 1; t < n; ++t) {
         const int nb = Y.nb[t], w = Y.w[t], win = w + nb - 1;
@@ -181,7 +220,10 @@ std::string chain_source(const std::vector<int> &shape, int kL)
             for (int j = nb - 1; j >= 0; --j) o("    p%d = __builtin_fmaf(r%d, d%d, p%d);\n", k, k + (nb - 1) - j, j, k);
         }
         o("    DOL_ROW(wp, %d, %d);\n", Y.off[t], w);
-        for (int k = 0; k < w; ++k) o("    wp[%d] = p%d <= 1.0f ? p%d : -1.0f;\n", k, k, k);
+        for (int k = 0; k < w; ++k) {
+            if (regs) o("    h%d_%d = p%d <= 1.0f ? p%d : -1.0f; wp[%d] = h%d_%d;\n", t, k, k, k, k, t, k);
+            else o("    wp[%d] = p%d <= 1.0f ? p%d : -1.0f;\n", k, k, k);
+        }
         o("  }\n  fence();\n");
     }
     // ---- the result
@@ -207,10 +249,14 @@ std::string chain_source(const std::vector<int> &shape, int kL)
     for (int t = n1; t >= 1; --t) {
         const int nb = Y.nb[t], m = Y.m[t - 1], v = ceil_div(m, kL), win = v + nb - 1;
         const int g_cur = (n1 - t) & 1 ? Y.off_g1 : Y.off_g0, g_nxt = (n1 - t) & 1 ? Y.off_g0 : Y.off_g1;
-        o("  {\n    DOL_ROW(gp, %d, %d); DOL_ROW(ap, %d, %d); DOL_ROW(dp, %d, 0);\n", g_cur, v, Y.off[t - 1], v, Y.off_d + t * kNBR);
+        o("  {\n    DOL_ROW(gp, %d, %d); DOL_ROW(dp, %d, 0);\n", g_cur, v, Y.off_d + t * kNBR);
+        if (!regs) o("    DOL_ROW(ap, %d, %d);\n", Y.off[t - 1], v);
         for (int j = 0; j < nb; ++j) o("    const float d%d = dp[%d];\n", j, j);
         for (int k = 0; k < win; ++k) o("    const float g%d = gp[%d];\n", k, k);
-        for (int k = 0; k < v; ++k) o("    const float x%d = ap[%d];\n", k, k);
+        for (int k = 0; k < v; ++k) {
+            if (regs) o("    const float x%d = h%d_%d;\n", k, t - 1, k);
+            else o("    const float x%d = ap[%d];\n", k, k);
+        }
         for (int j = 0; j < nb; ++j) o("    float s%d = 0.0f;\n", j);
         o("    DOL_ROW(wp, %d, %d);\n", g_nxt, v);
         for (int k = 0; k < v; ++k) {
@@ -288,7 +334,7 @@ bool fold_chain_ok(int n, const int32_t *m, const int32_t *nb, const int64_t *ld
         shape.push_back(nb[t]);
     }
     if (m[0] < 1 || m[0] > 256) return false;
-    const Layout Y = lay_out(shape, kLanes);
+    const Layout Y = lay_out(shape, kLanes, false);
     return sizeof(float) * (64 / kLanes) * static_cast<size_t>(Y.stride) <= kChainLdsMax;
 }
 
@@ -301,6 +347,7 @@ dol_status launch_fold_chain(int n, const int32_t *m, const int32_t *nb, int32_t
     std::vector<int> shape{n, m[0]};
     for (int t = 1; t < n; ++t) shape.push_back(nb[t]);
     const int kL = kLanes, kSP = 64 / kL;
+    const bool regs = (static_cast<int64_t>(batch) + kSP - 1) / kSP >= kRegsFromWorkgroups;
     int dev = 0;
     DOL_HIP(hipGetDevice(&dev));
     hipFunction_t fn = nullptr;
@@ -308,11 +355,12 @@ dol_status launch_fold_chain(int n, const int32_t *m, const int32_t *nb, int32_t
         std::lock_guard<std::mutex> lock(mu);
         std::vector<int> keyed(shape);
         keyed.push_back(kL);
+        keyed.push_back(regs ? 1 : 0);
         auto key = std::make_pair(dev, keyed);
         auto it = cache.find(key);
         if (it == cache.end()) {
             ChainKernel k;
-            k.status = jit_compile(chain_source(shape, kL), "damp_fold_chain_kernel", &k.mod, &k.fn);
+            k.status = jit_compile(chain_source(shape, kL, regs), "damp_fold_chain_kernel", &k.mod, &k.fn);
             it = cache.emplace(key, k).first;
             if (k.status != DOL_OK) return k.status;                        // with the compiler's message
         } else if (it->second.status != DOL_OK) {

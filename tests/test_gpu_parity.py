@@ -81,9 +81,10 @@ def test_config2_sum_chain(gp, batch, n):
     assert_close(host(prog.grad_p), ref["grad_p"], "chain grad")
 
 
-@pytest.mark.parametrize("batch,n", [(4096, 15), (301, 15), (37, 4), (1, 2), (64, 32)])
+@pytest.mark.parametrize("batch,n", [(4096, 15), (301, 15), (37, 4), (1, 2), (64, 32), (6401, 15), (8192, 6)])
 def test_config2_fused_fold(gp, batch, n):
-    """dol_fold_apply2: the same results as the chain of per-operator calls, and as the oracle."""
+    """dol_fold_apply2: the same results as the chain of per-operator calls, and as the oracle.  The two largest batches
+    take the form of the kernel that keeps the reverse sweep's operands in registers."""
     w = W.config2(batch=batch, n_digits=n, seed=n + 100)
     ref = OP.sum_chain_fwd_bwd(w)
     prog = gp.SumChainFused(w)
@@ -96,10 +97,12 @@ def test_config2_fused_fold(gp, batch, n):
     np.testing.assert_array_equal(host(prog.out.prob), host(chain.accs[-1].prob))    # same arithmetic, bit for bit
 
 
-def test_fused_fold_with_clamping_and_explicit_gradient(dol):
+@pytest.mark.parametrize("B", [77, 6203])
+def test_fused_fold_with_clamping_and_explicit_gradient(dol, B):
     """Unnormalised tags drive several stages over 1; the fold must gate exactly like the per-operator path.
-    Also: explicit upstream gradient, padded leading dimensions, mixed operand widths, forward-only call."""
-    B, widths = 77, [7, 3, 10, 16, 2]
+    Also: explicit upstream gradient, padded leading dimensions, mixed operand widths, forward-only call.  The larger
+    batch takes the kernel's other form (history in registers)."""
+    widths = [7, 3, 10, 16, 2]
     ins = [(W.uniform01(10 + t, B * n) * 0.9).astype(np.float32).reshape(B, n) for t, n in enumerate(widths)]
     syms = [np.arange(n, dtype=np.int32) for n in widths]
     tabs, tris, accs, cur = [], [], [ins[0]], syms[0]
