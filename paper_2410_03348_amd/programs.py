@@ -406,7 +406,8 @@ class GridReachFused(Program):
             if B <= 512:                     # few samples, one workgroup per unit: the fewest segments of at most 24 rounds
                 R0 = max(w["rounds"], 1)     # whose rows fit LDS (each segment costs a checkpoint and a refill)
                 ckpt_every = -(-R0 // -(-R0 // 24))
-                while ckpt_every > 8 and 4 * ((ckpt_every + 3) * (w["side"] ** 2 + 1) + w["edge_u"].size + 2) > 140 * 1024:
+                row = next((r for r in (512, 1024, 2048) if side * side <= r), 4096) + 1     # floats between two rows in LDS
+                while ckpt_every > 8 and 4 * ((ckpt_every + 3) * row + w["edge_u"].size + 2) > 140 * 1024:
                     ckpt_every -= 1
             else:                            # many: 8 rounds of LDS leave room for more workgroups per unit
                 ckpt_every = 8
@@ -442,7 +443,9 @@ class GridReachFused(Program):
             Launch("damp_iterate_fwd_kernel", fwd, 4 * B * (n + E + 1 + n), B * R * n_tup, "fwd"),     # r_0 and e in, r_R out
             Launch("damp_iterate_bwd_kernel", bwd, 4 * B * (n + 2 * (E + 1)), 2 * B * R * n_tup, "bwd"),  # gradient and e in, gradient of e out
         ]                                    # (what the sweeps keep of the rounds in between is not algorithmic)
-        if one_launch:                       # dol_iterate_apply2_backward: both sweeps in one launch
+        # dol_iterate_apply2_backward: both sweeps in one launch.  (For a batch above 512 that call issues the same two
+        # kernels as the two calls above, back to back: the program then keeps the two calls, so each is timed by itself.)
+        if one_launch and B <= 512:
             assert ckpt_every, "the one-launch form keeps checkpoints"
             both = lambda: dol.iterate_apply2_backward(self.r0, self.edges, self.table, R, ckpt_every, self.out, self.ckpt,
                                                        None, self.g_out, None, self.g_e)

@@ -488,16 +488,17 @@ def test_config5_checkpointed_iteration(gp, dol, batch, side, rounds, every):
     assert ei.value.status == 1
 
 
-@pytest.mark.parametrize("batch,side,rounds,every", [(256, 32, 64, 22), (33, 7, 20, 6), (5, 4, 1, 8), (40, 12, 30, 30), (3, 3, 7, 2)])
+@pytest.mark.parametrize("batch,side,rounds,every", [(256, 32, 64, 22), (33, 7, 20, 6), (5, 4, 1, 8), (40, 12, 30, 30), (3, 3, 7, 2),
+                                                      (600, 7, 20, 6), (520, 32, 11, 8)])
 def test_config5_iteration_in_one_launch(gp, dol, batch, side, rounds, every):
-    """dol_iterate_apply2_backward: both sweeps in one launch.  With an upstream gradient: bit for bit the results of
+    """dol_iterate_apply2_backward: both sweeps in one launch (in two, issued by the one call, for batches above 512).  With an upstream gradient: bit for bit the results of
     the two separate calls.  With a target node per sample (loss = -log r[target]): against the oracle's sweeps fed
     the gradient of that loss at the oracle's own result."""
     w = W.config5(batch=batch, side=side, rounds=rounds, seed=side + 3)
     two = gp.GridReachFused(w, ckpt_every=every)
     two.step()
     one = gp.GridReachFused(w, ckpt_every=every, one_launch=True)
-    assert len(one.launches) == 1
+    assert len(one.launches) == (1 if batch <= 512 else 2)
     one.step()
     np.testing.assert_array_equal(host(one.out.prob), host(two.out.prob))
     np.testing.assert_array_equal(host(one.g_e), host(two.g_e))
@@ -624,6 +625,48 @@ def test_fused_iteration_with_long_rows(dol, long_a, long_b):
         dol.iterate_backward_ckpt(d0, de, f, rounds, every, ck, dev(g), g0c, gec)
         np.testing.assert_array_equal(host(gec), host(ge))
         np.testing.assert_array_equal(host(g0c), host(g0))
+
+
+@pytest.mark.parametrize("B,na", [(5, 300), (5, 700), (520, 700)])
+def test_fused_iteration_with_six_tuples_per_symbol(dol, B, na):
+    """Every column and every row of the table holds six tuples: the builds that keep six tuples in registers, without
+    tail loops, in each launch shape (one symbol per thread; 1024 threads; two symbols per thread for the larger
+    batch, whose combined call issues its two sweeps as two launches)."""
+    nb, rounds, every = 40, 10, 4
+    i = np.repeat(np.arange(na, dtype=np.int32), 6)
+    d = np.tile(np.arange(6, dtype=np.int32), na)
+    ti, tj, to = i, (i + 5 * d) % nb, (i + np.array([0, 1, 7, 31, 100, 211], np.int32)[d]) % na
+    order = np.lexsort((tj, ti))
+    tri = tuple(x[order].astype(np.int32) for x in (ti, tj, to))
+    assert np.bincount(tri[2], minlength=na).max() == 6 and np.bincount(tri[0]).max() == 6
+    r0 = (W.uniform01(1, B * na) * 0.5).astype(np.float32).reshape(B, na)
+    r0[:, 3] = 1.0
+    e = (W.uniform01(2, B * nb) * 0.45).astype(np.float32).reshape(B, nb)
+    hist = [r0]
+    for t in range(rounds):
+        hist.append(oracle.damp_apply2_fwd(tri, na, nb, hist[-1], e)[1])
+    assert (hist[-1] == 1.0).any() and (hist[-1] < 1.0).any()
+    g = np.abs(W.normal(3, B * na)).astype(np.float32).reshape(B, na)
+    want_ge, gr = np.zeros((B, nb), np.float64), g
+    for t in reversed(range(rounds)):
+        gr, ge = oracle.damp_apply2_bwd(tri, na, nb, hist[t], e, gr)
+        want_ge += ge
+    f = dol.FnTable.create_sparse(na, nb, *tri)
+    d0, de = dol.Dist(np.arange(na), dev(r0)), dol.Dist(np.arange(nb), dev(e))
+    n_ck = dol.iterate_ckpt_count(rounds, every)
+    out, ck = dol.Dist.empty(np.arange(na), B), torch.empty((n_ck, B, na), device="cuda")
+    g0, ge = torch.empty((B, na), device="cuda"), torch.empty((B, nb), device="cuda")
+    dol.iterate_apply2_ckpt(d0, de, f, rounds, every, out, ck)
+    dol.iterate_backward_ckpt(d0, de, f, rounds, every, ck, dev(g), g0, ge)
+    assert_close(host(out.prob), hist[-1], "six tuples: result")
+    np.testing.assert_array_equal(host(out.prob) == 1.0, hist[-1] == 1.0)
+    assert_close(host(g0), gr, "six tuples: gradient of r0")
+    assert_close(host(ge), want_ge, "six tuples: gradient of e")
+    out2, ck2 = dol.Dist.empty(np.arange(na), B), torch.empty_like(ck)
+    g0b, geb = torch.empty_like(g0), torch.empty_like(ge)
+    dol.iterate_apply2_backward(d0, de, f, rounds, every, out2, ck2, None, dev(g), g0b, geb)
+    for a, b in ((out2.prob, out.prob), (ck2, ck), (g0b, g0), (geb, ge)):
+        np.testing.assert_array_equal(host(a), host(b))
 
 
 def test_fused_iteration_with_more_than_1024_symbols(dol):
