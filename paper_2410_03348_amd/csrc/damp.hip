@@ -798,10 +798,63 @@ nll_grad_kernel(Rows R, const float *__restrict__ p, int64_t ld, const int32_t *
     });
 }
 
+// The same over a contiguous [batch, n] gradient, 16 bytes per store: a workgroup owns `rows` whole rows (a multiple of
+// four, so its piece starts on a 16-byte boundary; at most kNllRows), first puts every row's target and value in LDS
+// and then walks its piece without a division and without a load between the stores (a load's wait would also wait for
+// the stores before it).
+constexpr int kNllRows = 2048;
+
+__global__ void __launch_bounds__(kThreads)
+nll_grad_flat_kernel(int32_t batch, int32_t n, int32_t rows, const float *__restrict__ p, const int32_t *__restrict__ target,
+                     float *__restrict__ grad)
+{
+    __shared__ int32_t tg[kNllRows];
+    __shared__ float val[kNllRows];
+    const int64_t s0 = static_cast<int64_t>(blockIdx.x) * rows;
+    const int32_t rows_here = static_cast<int32_t>(min(static_cast<int64_t>(rows), batch - s0));
+    const int32_t n_here = rows_here * n;           // floats of this piece
+    const float *pp = p + s0 * n;
+    float *gg = grad + s0 * n;
+    for (int r = threadIdx.x; r < rows_here; r += kThreads) {
+        const int32_t t = target[s0 + r];
+        tg[r] = t;
+        val[r] = t >= 0 && t < n ? -1.0f / fmaxf(pp[static_cast<int64_t>(r) * n + t], 1.17549435e-38f) : 0.0f;
+    }
+    __syncthreads();
+    constexpr int kStep = 4 * kThreads;
+    const int32_t dr = kStep / n, dc = kStep - dr * n;
+    int32_t e = 4 * static_cast<int32_t>(threadIdx.x);
+    int32_t r = e / n, c = e - r * n;
+    for (; e < n_here; e += kStep) {
+        int32_t rr = r, cc = c;
+        float v[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            while (cc >= n) { cc -= n; ++rr; }      // (once at most per element, n >= 1)
+            v[k] = e + k < n_here && cc == tg[rr] ? val[rr] : 0.0f;
+            ++cc;
+        }
+        if (e + 3 < n_here) *reinterpret_cast<float4 *>(gg + e) = make_float4(v[0], v[1], v[2], v[3]);
+        else
+            for (int k = 0; e + k < n_here; ++k) gg[e + k] = v[k];
+        r += dr; c += dc;
+        if (c >= n) { c -= n; ++r; }
+    }
+}
+
 dol_status launch_nll_grad(int32_t batch, int32_t n, const float *p, int64_t ld, const int32_t *target, float *grad,
                            hipStream_t st)
 {
     if (batch == 0 || n == 0) return DOL_OK;
+    if (ld == n && reinterpret_cast<uintptr_t>(grad) % 16 == 0) {
+        const int32_t rows = std::min(kNllRows, std::max(4, (8192 / n + 3) / 4 * 4));
+        if (static_cast<int64_t>(rows) * n < (int64_t{1} << 30)) {
+            const unsigned grid = static_cast<unsigned>((static_cast<int64_t>(batch) + rows - 1) / rows);
+            hipLaunchKernelGGL(nll_grad_flat_kernel, dim3(grid), dim3(kThreads), 0, st, batch, n, rows, p, target, grad);
+            DOL_HIP(hipGetLastError());
+            return DOL_OK;
+        }
+    }
     const Rows R = rows_of(batch, n);
     hipLaunchKernelGGL(nll_grad_kernel, dim3(R.grid), dim3(kThreads), 0, st, R, p, ld, target, grad);
     DOL_HIP(hipGetLastError());

@@ -138,8 +138,8 @@ class SumChain(Program):
                          for t in range(1, self.n)]
         last = self.accs[-1]
         # harness side: d(-log p[target]) / d p
-        self.launches.append(Launch("nll_grad_kernel", lambda: dol.nll_grad(last, self.target, self.g_acc[-1]),
-                                    4 * self.batch * (1 + 2 * last.n_sym), 0, "bwd"))
+        self.launches.append(Launch("nll_grad_flat_kernel", lambda: dol.nll_grad(last, self.target, self.g_acc[-1]),
+                                    4 * self.batch * (2 + last.n_sym), 0, "bwd"))     # the target and its tag in, a row out
         for t in range(self.n - 1, 0, -1):
             ga = self.g_acc[t - 1] if t > 1 else self.grad_p[0]
             self.launches.append(_apply_bwd(self.records[t - 1], self.g_acc[t], ga, self.grad_p[t], n_tup[t - 1]))

@@ -97,6 +97,25 @@ def test_config2_fused_fold(gp, batch, n):
     np.testing.assert_array_equal(host(prog.out.prob), host(chain.accs[-1].prob))    # same arithmetic, bit for bit
 
 
+@pytest.mark.parametrize("batch,n,pad", [(1, 1, 0), (5, 3, 0), (1000, 19, 0), (4099, 136, 0), (333, 2050, 0), (70, 19, 5)])
+def test_nll_grad(dol, batch, n, pad):
+    """dol_nll_grad: -1 / max(p[target], FLT_MIN) at the target, zero elsewhere; rows that are not a multiple of 16 bytes,
+    a last workgroup with fewer rows, a padded tensor (the element-wise kernel), a tag of zero."""
+    p = W.uniform01(3, batch * n).astype(np.float32).reshape(batch, n)
+    target = (np.arange(batch) * 7 % n).astype(np.int32)
+    p[0, target[0]] = 0.0
+    buf = torch.full((batch, n + pad), 9.0, device="cuda")
+    buf[:, :n] = dev(p)
+    grad = torch.full((batch, n + pad), 7.0, device="cuda")
+    dol.nll_grad(dol.Dist(np.arange(n), buf[:, :n]), dev(target), grad[:, :n])
+    want = np.zeros((batch, n), np.float32)
+    want[np.arange(batch), target] = np.float32(-1.0) / np.maximum(p[np.arange(batch), target], np.float32(1.17549435e-38))
+    got = host(grad)
+    np.testing.assert_array_equal(got[:, :n] != 0, want != 0)
+    assert_close(got[:, :n], want, "nll gradient")
+    assert np.all(got[:, n:] == 7.0)
+
+
 @pytest.mark.parametrize("B", [77, 6203])
 def test_fused_fold_with_clamping_and_explicit_gradient(dol, B):
     """Unnormalised tags drive several stages over 1; the fold must gate exactly like the per-operator path.
