@@ -361,9 +361,10 @@ dol_status dol_iterate_apply2_ckpt(const dol_dist *r0, const dol_dist *e, const 
 dol_status dol_iterate_backward_ckpt(const dol_dist *r0, const dol_dist *e, const dol_fn_table *f, int32_t rounds,
                                      int32_t ckpt_every, const float *ckpt, const float *grad_out, int64_t grad_out_ld,
                                      float *grad_r0, float *grad_e, void *hip_stream);
-/* dol_iterate_apply2_ckpt and dol_iterate_backward_ckpt in ONE launch (as dol_fold_apply2 runs the loop of Fig. 2 both
+/* dol_iterate_apply2_ckpt and dol_iterate_backward_ckpt in ONE call (as dol_fold_apply2 runs the loop of Fig. 2 both
  * ways): the rounds forward, r_rounds into out and the checkpoints into ckpt, then the reverse sweep from the upstream
- * gradient.  Exactly one of target_col and grad_out is given: target_col, device [batch] with 0 <= . < na, makes the
+ * gradient.  Up to 512 samples the call is one launch (the last segment of rounds stays in LDS between the sweeps);
+ * above, it issues the two sweeps' kernels back to back on the stream.  Exactly one of target_col and grad_out is given: target_col, device [batch] with 0 <= . < na, makes the
  * loss -log r_rounds[target] (its gradient -1 / max(r, FLT_MIN) at the target, as dol_nll_grad); grad_out, device
  * [batch, grad_out_ld], is any gradient that does not depend on this call's result.  At least one of grad_r0 and
  * grad_e is given.  Results are those of the two separate calls, bit for bit. */

@@ -581,7 +581,8 @@ _lib.dol_iterate_apply2_backward.argtypes = [C.POINTER(_Dist), C.POINTER(_Dist),
 def iterate_apply2_backward(r0: Dist, e: Dist, f: FnTable, rounds: int, ckpt_every: int, out: Dist,
                             ckpt: Optional[torch.Tensor], target_col: Optional[torch.Tensor], grad_out: Optional[torch.Tensor],
                             grad_r0: Optional[torch.Tensor], grad_e: Optional[torch.Tensor], stream=None):
-    """Forward rounds and reverse sweep in one launch; exactly one of target_col (int32 [batch]) and grad_out."""
+    """Forward rounds and reverse sweep in one call (one launch up to 512 samples); exactly one of target_col (int32 [batch])
+    and grad_out."""
     ldg = 0
     if grad_out is not None:
         assert grad_out.dtype == torch.float32 and grad_out.stride(1) == 1

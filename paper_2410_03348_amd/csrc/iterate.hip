@@ -12,10 +12,15 @@
 // walking it backwards.  Inside LDS a round's result is kept as x = pre where pre <= 1 and -1 where the clamp acted:
 // |x| is the clamped tag and the sign is the clamp's decision, so the reverse sweep never re-derives a sum.
 //
-// dol_iterate_apply2_backward runs both sweeps in one launch (damp_iterate_fwd_bwd_kernel): the tables are fetched once,
-// and the forward sweep writes the rounds of its last segment where the reverse sweep starts, so that segment is not
-// replayed.  Every kernel is built twice: for tables with columns or rows longer than the tuples a thread keeps in
-// registers (TAILS) and for tables without, whose rounds then carry no tail loops and no workgroup-wide rows.
+// dol_iterate_apply2_backward runs both sweeps in one launch (damp_iterate_fwd_bwd_kernel) while the batch leaves units
+// idle: the tables are fetched once, and the forward sweep writes the rounds of its last segment where the reverse sweep
+// starts, so that segment is not replayed.  Larger batches get the two kernels back to back.  Every kernel is built for
+// tables with columns or rows longer than the tuples a thread keeps in registers (TAILS) and for tables without, whose
+// rounds then carry no tail loops and no workgroup-wide rows; and with five or six register slots per symbol.
+//
+// Rows in LDS lie a constant number of floats apart (the shape's threads times symbols per thread, plus one) and the
+// reverse sweep's rounds run in unrolled stretches of eight: every LDS access of a round is then an address the thread
+// computed once plus a constant carried by the instruction.
 //
 // The gradient w.r.t. e has one share per tuple and round.  A share belongs to the thread that owns the tuple's row
 // and is summed over the rounds in a register (or in the tuple's own LDS word); at the end the shares of every symbol
