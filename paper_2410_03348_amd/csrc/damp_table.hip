@@ -12,7 +12,8 @@
 // serves larger tables and padded or unaligned tensors.)  A column's tuples keep their ascending (i, j) order and
 // start from 0, so the sum is bit for bit the one dol_apply2 defines and the clamp decisions agree.
 //
-// Layout of a launch: a workgroup of four wavefronts owns a tile of 64 samples.  The tile's operand rows travel
+// Layout of a launch: a workgroup of four wavefronts owns a tile of 64 samples (of 32, half of the lanes idle, while
+// the batch would not give every compute unit two tiles of 64).  The tile's operand rows travel
 // HBM -> LDS with flat 16-byte loads (rows padded to a pitch of n + 4 floats, which keeps a lane's 16-byte reads of
 // its own row off its neighbours' banks), each lane pulls its sample's rows into registers, the wavefronts split
 // the work (forward: 64 output columns each; backward: half of the rows of one operand each), results go back
@@ -135,7 +136,7 @@ void emit_tile_head(Src &o)
     // (one tile per workgroup: inside a loop over tiles the compiler keeps every thread-constant offset of the body alive
     // across it, in registers the body needs)
     o("  {\n  const int tile = blockIdx.x;\n");
-    o("  const long long s0 = (long long)tile * %d;\n  const int valid = batch - s0 < %d ? (int)(batch - s0) : %d;\n", kJitTile, kJitTile, kJitTile);
+    o("  const long long s0 = (long long)tile * tile_rows;\n  const int valid = batch - s0 < tile_rows ? (int)(batch - s0) : tile_rows;\n");
 }
 
 // Forward.  merged: the kept symbols of the result are merged with a third Distribution c in the same launch
@@ -155,14 +156,14 @@ std::string forward_source(const dol_fn_table *f, bool merged, bool aligned = fa
     if (body)
         o("static __device__ __forceinline__ void damp_table_merge_fwd_body(float *lds, const float *__restrict__ a, const float *__restrict__ b, "
           "const float *__restrict__ c, float *__restrict__ out, const int *__restrict__ ia, const int *__restrict__ ib, int *saved, "
-          "int batch, int n_tiles, int nc, int n3)\n{\n");
+          "int batch, int tile_rows, int nc, int n3)\n{\n");
     else if (merged)
         o("extern \"C\" __global__ void __launch_bounds__(%d) __attribute__((amdgpu_waves_per_eu(2, 2))) damp_table_merge_fwd_kernel(const float *__restrict__ a, const float *__restrict__ b, "
           "const float *__restrict__ c, float *__restrict__ out, const int *__restrict__ ia, const int *__restrict__ ib, int *__restrict__ saved, "
-          "int batch, int n_tiles, int nc, int n3)\n{\n", kThreads);
+          "int batch, int tile_rows, int nc, int n3)\n{\n", kThreads);
     else
         o("extern \"C\" __global__ void __launch_bounds__(%d) __attribute__((amdgpu_waves_per_eu(2, 2))) damp_table_fwd_kernel(const float *__restrict__ a, const float *__restrict__ b, "
-          "float *__restrict__ out, int batch, int n_tiles)\n{\n", kThreads);
+          "float *__restrict__ out, int batch, int tile_rows)\n{\n", kThreads);
     if (!body) o("  __shared__ __align__(16) float lds[%d];\n", stage_floats + (merged ? kJitTile : 0));
     o("  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // (a scalar: branches on it are uniform)\n");
     o("  float *sa = lds, *sb = lds + %d, *so = lds + wave * %d;\n", kJitTile * pa, merged ? 0 : kJitTile * po);
@@ -317,15 +318,15 @@ std::string backward_source(const dol_fn_table *f, bool merged, bool aligned = f
         o("static __device__ __forceinline__ void damp_table_merge_bwd_body(float *lds, const float *__restrict__ a, const float *__restrict__ b, "
           "const float *__restrict__ c, const float *__restrict__ g, float *__restrict__ ga, float *__restrict__ gb, float *__restrict__ gc, "
           "const int *__restrict__ ia, const int *__restrict__ ib, const int *__restrict__ ca, const int *__restrict__ cb, "
-          "const int *saved, int batch, int n_tiles, int nc, int n3, int accumulate)\n{\n");
+          "const int *saved, int batch, int tile_rows, int nc, int n3, int accumulate)\n{\n");
     else if (merged)
         o("extern \"C\" __global__ void __launch_bounds__(%d) __attribute__((amdgpu_waves_per_eu(2, 2))) damp_table_merge_bwd_kernel(const float *__restrict__ a, const float *__restrict__ b, "
           "const float *__restrict__ c, const float *__restrict__ g, float *__restrict__ ga, float *__restrict__ gb, float *__restrict__ gc, "
           "const int *__restrict__ ia, const int *__restrict__ ib, const int *__restrict__ ca, const int *__restrict__ cb, "
-          "const int *__restrict__ saved, int batch, int n_tiles, int nc, int n3, int accumulate)\n{\n", kThreads);
+          "const int *__restrict__ saved, int batch, int tile_rows, int nc, int n3, int accumulate)\n{\n", kThreads);
     else
         o("extern \"C\" __global__ void __launch_bounds__(%d) __attribute__((amdgpu_waves_per_eu(2, 2))) damp_table_bwd_kernel(const float *__restrict__ a, const float *__restrict__ b, "
-          "const float *__restrict__ g, float *__restrict__ ga, float *__restrict__ gb, int batch, int n_tiles, int accumulate)\n{\n", kThreads);
+          "const float *__restrict__ g, float *__restrict__ ga, float *__restrict__ gb, int batch, int tile_rows, int accumulate)\n{\n", kThreads);
     if (!body) o("  __shared__ __align__(16) float lds[%d];\n", off_f + 4);
     o("  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // (a scalar: branches on it are uniform)\n");
     o("  float *sa = lds, *sb = lds + %d, *sg0 = lds + %d, *sg1 = lds + %d;\n", off_b, off_g, off_g + stage);
@@ -495,12 +496,12 @@ std::string both_source(const dol_fn_table *f, bool aligned)
     o("extern \"C\" __global__ void __launch_bounds__(%d) __attribute__((amdgpu_waves_per_eu(2, 2))) damp_table_merge_fwd_bwd_kernel("
       "const float *__restrict__ a, const float *__restrict__ b, const float *__restrict__ c, float *__restrict__ out, "
       "const float *__restrict__ g, float *__restrict__ ga, float *__restrict__ gb, float *__restrict__ gc, const int *__restrict__ ia, "
-      "const int *__restrict__ ib, const int *__restrict__ ca, const int *__restrict__ cb, int *saved, int batch, int n_tiles, int nc, int n3, "
+      "const int *__restrict__ ib, const int *__restrict__ ca, const int *__restrict__ cb, int *saved, int batch, int tile_rows, int nc, int n3, "
       "int accumulate)\n{\n", kThreads);
     o("  __shared__ __align__(16) float lds[%d];\n", std::max(lf, lb));
-    o("  damp_table_merge_fwd_body(lds, a, b, c, out, ia, ib, saved, batch, n_tiles, nc, n3);\n");
+    o("  damp_table_merge_fwd_body(lds, a, b, c, out, ia, ib, saved, batch, tile_rows, nc, n3);\n");
     o("  __syncthreads();\n");
-    o("  damp_table_merge_bwd_body(lds, a, b, c, g, ga, gb, gc, ia, ib, ca, cb, saved, batch, n_tiles, nc, n3, accumulate);\n}\n");
+    o("  damp_table_merge_bwd_body(lds, a, b, c, g, ga, gb, gc, ia, ib, ca, cb, saved, batch, tile_rows, nc, n3, accumulate);\n}\n");
     return o.s;
 }
 
@@ -548,6 +549,13 @@ namespace {
 
 unsigned tile_grid(int n_tiles) { return static_cast<unsigned>(n_tiles); }
 
+// Samples per workgroup.  The registers of these kernels allow two workgroups on a compute unit; a batch whose full
+// tiles number no more than the 256 units would leave every unit with one workgroup, its loads, arithmetic and stores
+// one after the other.  Such a batch is cut into half tiles (lanes 32 to 63 idle): two workgroups per unit overlap
+// (config 3 at B = 16384, both ways in one launch: 30.3 against 33.7 us).
+constexpr int32_t kHalfTileMaxBatch = 256 * kJitTile;
+int tile_rows_for(int32_t batch) { return batch <= kHalfTileMaxBatch ? kJitTile / 2 : kJitTile; }
+
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 JitState *state_of(const dol_fn_table *f)
@@ -592,8 +600,8 @@ dol_status launch_damp_table_fwd(const dol_fn_table *f, int32_t batch, const flo
     if (lda != f->na || ldb != f->nb || ldo != f->n_out || !aligned16(a) || !aligned16(b) || !aligned16(out)) return DOL_OK;
     hipFunction_t fn = nullptr;
     if (dol_status s = kernel_of(f, kSlotFwd, &fn)) return s;
-    int n_tiles = (batch + kJitTile - 1) / kJitTile;
-    void *args[] = {&a, &b, &out, &batch, &n_tiles};
+    int tile_rows = tile_rows_for(batch), n_tiles = (batch + tile_rows - 1) / tile_rows;
+    void *args[] = {&a, &b, &out, &batch, &tile_rows};
     DOL_HIP(hipModuleLaunchKernel(fn, tile_grid(n_tiles), 1, 1, kThreads, 1, 1, 0, st, args, nullptr));
     *done = true;
     return DOL_OK;
@@ -610,8 +618,8 @@ dol_status launch_damp_table_bwd(const dol_fn_table *f, int32_t batch, const flo
         return DOL_OK;
     hipFunction_t fn = nullptr;
     if (dol_status s = kernel_of(f, kSlotBwd, &fn)) return s;
-    int n_tiles = (batch + kJitTile - 1) / kJitTile;
-    void *args[] = {&a, &b, &g, &ga, &gb, &batch, &n_tiles, &accumulate};
+    int tile_rows = tile_rows_for(batch), n_tiles = (batch + tile_rows - 1) / tile_rows;
+    void *args[] = {&a, &b, &g, &ga, &gb, &batch, &tile_rows, &accumulate};
     DOL_HIP(hipModuleLaunchKernel(fn, tile_grid(n_tiles), 1, 1, kThreads, 1, 1, 0, st, args, nullptr));
     *done = true;
     return DOL_OK;
@@ -624,9 +632,9 @@ dol_status launch_damp_table_merge_fwd(const dol_fn_table *f, const UnionPlan *p
 {
     hipFunction_t fn = nullptr;
     if (dol_status s = kernel_of(f, p->aligned ? kSlotMergeFwdAligned : kSlotMergeFwd, &fn)) return s;
-    int n_tiles = (batch + kJitTile - 1) / kJitTile, nc = p->nb, n3 = p->n_out;
+    int tile_rows = tile_rows_for(batch), n_tiles = (batch + tile_rows - 1) / tile_rows, nc = p->nb, n3 = p->n_out;
     const int32_t *ia = p->d_ia.ptr, *ib = p->d_ib.ptr;
-    void *args[] = {&a, &b, &c, &out, &ia, &ib, &saved, &batch, &n_tiles, &nc, &n3};
+    void *args[] = {&a, &b, &c, &out, &ia, &ib, &saved, &batch, &tile_rows, &nc, &n3};
     DOL_HIP(hipModuleLaunchKernel(fn, tile_grid(n_tiles), 1, 1, kThreads, 1, 1, 0, st, args, nullptr));
     return DOL_OK;
 }
@@ -637,9 +645,9 @@ dol_status launch_damp_table_merge_bwd(const dol_fn_table *f, const UnionPlan *p
 {
     hipFunction_t fn = nullptr;
     if (dol_status s = kernel_of(f, p->aligned ? kSlotMergeBwdAligned : kSlotMergeBwd, &fn)) return s;
-    int n_tiles = (batch + kJitTile - 1) / kJitTile, nc = p->nb, n3 = p->n_out;
+    int tile_rows = tile_rows_for(batch), n_tiles = (batch + tile_rows - 1) / tile_rows, nc = p->nb, n3 = p->n_out;
     const int32_t *ia = p->d_ia.ptr, *ib = p->d_ib.ptr, *ca = p->d_ca.ptr, *cb = p->d_cb.ptr;
-    void *args[] = {&a, &b, &c, &g, &ga, &gb, &gc, &ia, &ib, &ca, &cb, &saved, &batch, &n_tiles, &nc, &n3, &accumulate};
+    void *args[] = {&a, &b, &c, &g, &ga, &gb, &gc, &ia, &ib, &ca, &cb, &saved, &batch, &tile_rows, &nc, &n3, &accumulate};
     DOL_HIP(hipModuleLaunchKernel(fn, tile_grid(n_tiles), 1, 1, kThreads, 1, 1, 0, st, args, nullptr));
     return DOL_OK;
 }
@@ -650,9 +658,9 @@ dol_status launch_damp_table_merge_both(const dol_fn_table *f, const UnionPlan *
 {
     hipFunction_t fn = nullptr;
     if (dol_status s = kernel_of(f, p->aligned ? kSlotMergeBothAligned : kSlotMergeBoth, &fn)) return s;
-    int n_tiles = (batch + kJitTile - 1) / kJitTile, nc = p->nb, n3 = p->n_out;
+    int tile_rows = tile_rows_for(batch), n_tiles = (batch + tile_rows - 1) / tile_rows, nc = p->nb, n3 = p->n_out;
     const int32_t *ia = p->d_ia.ptr, *ib = p->d_ib.ptr, *ca = p->d_ca.ptr, *cb = p->d_cb.ptr;
-    void *args[] = {&a, &b, &c, &out, &g, &ga, &gb, &gc, &ia, &ib, &ca, &cb, &saved, &batch, &n_tiles, &nc, &n3, &accumulate};
+    void *args[] = {&a, &b, &c, &out, &g, &ga, &gb, &gc, &ia, &ib, &ca, &cb, &saved, &batch, &tile_rows, &nc, &n3, &accumulate};
     DOL_HIP(hipModuleLaunchKernel(fn, tile_grid(n_tiles), 1, 1, kThreads, 1, 1, 0, st, args, nullptr));
     return DOL_OK;
 }
