@@ -869,7 +869,7 @@ def test_sum_tables_with_clamping(dol, na, nb, B):
 
 @pytest.mark.parametrize("na,nb,B", [(127, 10, 16384 + 37), (19, 10, 16384), (17, 16, 20001), (192, 16, 16385), (64, 4, 16401),
                                       (70, 1, 16390), (100, 8, 16384 + 63), (37, 3, 16387), (118, 10, 32768), (10, 10, 16389),
-                                      (3, 16, 16400), (1, 1, 16385), (16, 2, 16384)])
+                                      (3, 16, 16400), (1, 1, 16385), (16, 2, 16384), (127, 10, 40005), (30, 10, 70001)])
 def test_sum_tables_at_batches_that_fill_the_chip(dol, na, nb, B):
     """The same at batches where a lane owns a sample and a workgroup a tile of 64: whole tiles and a ragged last
     one, tiles that must re-derive the clamp decisions and (the second half of the batch) tiles that need not."""
