@@ -18,7 +18,9 @@
 // by the reverse sweep with the operand it needs anyway - no stage is ever summed twice.
 //
 // Arithmetic is that of dol_apply2 / dol_backward: out[c] = min(1, sum over ascending i of a[i] * b[c - i]), one
-// fused multiply-add per tuple from 0; gradients gated by [pre <= 1].
+// fused multiply-add per tuple from 0; gradients gated by [pre <= 1].  The gradient of a short operand is a sum over
+// the sample's 16 lanes per symbol: the lanes share the symbols out while they exchange (emit_scattered_sums), every
+// total ends in the lanes that store it, and the row leaves with one LDS write.
 #include "internal.h"
 
 #include <cstdarg>
@@ -35,8 +37,8 @@ constexpr int kLanes = 16;
 constexpr int kNBR = 16;                // floats reserved per short input row
 constexpr size_t kChainLdsMax = 40 * 1024;   // per wavefront: at least four wavefronts per compute unit
 // From this many workgroups on, the form with the reverse sweep's operands in registers: less than half the LDS, so a
-// dozen wavefronts per compute unit instead of five (Sum-15: 20.3 against 28.8 us at 2048 workgroups, 252 against 341 us
-// at 32768).  Below, with one wavefront per SIMD, the form with every row in LDS is the faster one (14.4 against 15.3 us
+// dozen wavefronts per compute unit instead of five (Sum-15: 18.2 against 25.7 us at 2048 workgroups, 224 against 307 us
+// at 32768).  Below, with one wavefront per SIMD, the form with every row in LDS is the faster one (12.6 against 13.3 us
 // at 1024 workgroups).
 constexpr int64_t kRegsFromWorkgroups = 1536;
 
@@ -125,6 +127,44 @@ void emit_zero(Src &o, int start, int len, int kL)
     }
 }
 
+// Sums of the n values s0 .. s<n-1> over the 16 lanes of a sample, each total ending in some lanes' s0: the four exchange
+// steps pair a lane with the lane whose number differs by 15, 7, 2 and 1 (together these reach all 16), and in every step
+// the two lanes of a pair share the values out - the one with the step's bit clear goes on with the first half, the other
+// with the second half, an odd value out with both - so a step costs three instructions per two values instead of two
+// per value.  which_sum(n) is the index of the total a lane ends up with, as an expression in l.
+void emit_scattered_sums(Src &o, int n)
+{
+    static const int which[4] = {3, 2, 1, 0}, bit[4] = {8, 4, 2, 1};
+    for (int st = 0; st < 4; ++st) {
+        const int h = n / 2;
+        for (int k = 0; k < h; ++k) {
+            o("    { const float lo = s%d + dppx(s%d, %d), hi = s%d + dppx(s%d, %d); s%d = (l & %d) ? hi : lo; }\n", k, k, which[st], k + h, k + h,
+              which[st], k, bit[st]);
+        }
+        if (n & 1) {
+            if (h > 0) o("    s%d = s%d + dppx(s%d, %d);\n", h, n - 1, n - 1, which[st]);
+            else o("    s0 += dppx(s0, %d);\n", which[st]);
+        }
+        n = h + (n & 1);
+    }
+}
+
+std::string which_sum(int n)
+{
+    static const int bit[4] = {8, 4, 2, 1};
+    std::vector<std::string> e(n);
+    for (int j = 0; j < n; ++j) e[j] = std::to_string(j);
+    for (int st = 0; st < 4; ++st) {
+        const int h = n / 2;
+        std::vector<std::string> f;
+        for (int k = 0; k < h; ++k) f.push_back("((l & " + std::to_string(bit[st]) + ") ? " + e[k + h] + " : " + e[k] + ")");
+        if (n & 1) f.push_back(e[n - 1]);
+        e = f;
+        n = h + (n & 1);
+    }
+    return e[0];
+}
+
 std::string chain_source(const std::vector<int> &shape, int kL, bool regs)
 {
     const int kSP = 64 / kL;
@@ -166,6 +206,11 @@ std::string chain_source(const std::vector<int> &shape, int kL, bool regs)
         for (int t = 1; t < n; ++t) { used[Y.w[t]] = true; used[ceil_div(Y.m[t - 1], kL)] = true; }
         for (int x = 0; x < 64; ++x)
             if (used[x]) o("  const int lw%d = l * %d;\n", x, 4 * x);
+        if (kL == 16) {     // which of a short operand's gradient sums a lane ends up with (see emit_scattered_sums)
+            bool len[kNBR + 1] = {};
+            for (int t = 1; t < n; ++t)
+                if (!len[Y.nb[t]]) { len[Y.nb[t]] = true; o("  const int jl%d = %s;\n", Y.nb[t], which_sum(Y.nb[t]).c_str()); }
+        }
     }
     o("#define DOL_ROW(name, start, step) int name##_i = qb + 4 * (start) + lw##step; asm volatile(\"\" : \"+v\"(name##_i)); "
       "float *name = reinterpret_cast<float *>(reinterpret_cast<char *>(lds) + name##_i)\n");
@@ -232,15 +277,21 @@ std::string chain_source(const std::vector<int> &shape, int kL, bool regs)
         o("    %s os[%d + l] = __builtin_fabsf(base[%d + l]);\n", Y.m[n1] - x >= kL ? "" : (std::string("if (l < ") + std::to_string(Y.m[n1] - x) + ")").c_str(),
           x, Y.off[n1] + x);
     o("  }\n  if (!A.backward) return;\n");
-    // ---- upstream gradient into the first gradient row, gated by the last stage's clamp
-    o("  { const int tgt = A.target ? A.target[s] : -1; const float *gs = A.gout + (long long)s * A.ldg;\n");
+    // ---- upstream gradient into the first gradient row, gated by the last stage's clamp.  With a target the row is
+    // zero but for one entry, which one lane works out (one division per sample instead of one per column)
+    o("  if (A.target) {\n");
+    for (int x = 0; x < Y.g_len; x += kL)
+        o("    %sbase[%d + l] = 0.0f;\n", Y.g_len - x >= kL ? "" : (std::string("if (l < ") + std::to_string(Y.g_len - x) + ") ").c_str(), Y.off_g0 + x);
+    o("    const int tgt = A.target[s];\n");
+    o("    if (l == 0 && tgt >= 0 && tgt < %d) { const float xv = base[%d + tgt];\n", Y.m[n1], Y.off[n1]);
+    o("      base[%d + tgt] = xv < 0.0f ? 0.0f : -1.0f / fmaxf(xv, 1.17549435e-38f); }\n", Y.off_g0);
+    o("  } else { const float *gs = A.gout + (long long)s * A.ldg;\n");
     for (int x = 0; x < Y.g_len; x += kL) {
         const bool whole = Y.g_len - x >= kL;
         o("    %s{ const int c = %d + l; float gv = 0.0f;\n", whole ? "" : (std::string("if (l < ") + std::to_string(Y.g_len - x) + ") ").c_str(), x);
         if (x < Y.m[n1]) {
             o("      if (c < %d) { const float xv = base[%d + c];\n", Y.m[n1], Y.off[n1]);
-            o("        if (A.target) gv = c == tgt ? -1.0f / fmaxf(__builtin_fabsf(xv), 1.17549435e-38f) : 0.0f; else gv = gs[c];\n");
-            o("        if (xv < 0.0f) gv = 0.0f; }\n");
+            o("        gv = xv < 0.0f ? 0.0f : gs[c]; }\n");
         }
         o("      base[%d + c] = gv; }\n", Y.off_g0);
     }
@@ -281,10 +332,15 @@ std::string chain_source(const std::vector<int> &shape, int kL, bool regs)
         // the short operand's gradient: sum of the lanes' shares; it takes the place of the operand's row, which is spent
         // (the empty asm keeps the last addition in front of the branch, where it takes its operand straight from the
         // other lane; inside the branch, with one lane live, it would need a separate move)
-        for (int j = 0; j < nb; ++j) o("    s%d = sum_lanes(s%d); asm volatile(\"\" : \"+v\"(s%d));\n", j, j, j);
-        o("    if (l == %d) {\n", kL == 32 ? 16 : 0);
-        for (int j = 0; j < nb; ++j) o("      dp[%d] = s%d;\n", j, j);
-        o("    }\n  }\n  fence();\n");
+        if (kL == 32) {
+            for (int j = 0; j < nb; ++j) o("    s%d = sum_lanes(s%d); asm volatile(\"\" : \"+v\"(s%d));\n", j, j, j);
+            o("    if (l == 16) {\n");
+            for (int j = 0; j < nb; ++j) o("      dp[%d] = s%d;\n", j, j);
+            o("    }\n  }\n  fence();\n");
+        } else {
+            emit_scattered_sums(o, nb);
+            o("    dp[jl%d] = s0;\n  }\n  fence();\n", nb);
+        }
     }
     // ---- gradients out
     o("  if (!live) return;\n");

@@ -116,12 +116,13 @@ def test_nll_grad(dol, batch, n, pad):
     assert np.all(got[:, n:] == 7.0)
 
 
+@pytest.mark.parametrize("widths", [[7, 3, 10, 16, 2], [5, 1, 9, 4, 13, 6, 11]])
 @pytest.mark.parametrize("B", [77, 6203])
-def test_fused_fold_with_clamping_and_explicit_gradient(dol, B):
+def test_fused_fold_with_clamping_and_explicit_gradient(dol, B, widths):
     """Unnormalised tags drive several stages over 1; the fold must gate exactly like the per-operator path.
     Also: explicit upstream gradient, padded leading dimensions, mixed operand widths, forward-only call.  The larger
-    batch takes the kernel's other form (history in registers)."""
-    widths = [7, 3, 10, 16, 2]
+    batch takes the kernel's other form (history in registers); the second list of widths covers second operands of
+    1, 4, 6, 9, 11 and 13 symbols (how the lanes share out a short operand's gradient sums depends on that count)."""
     ins = [(W.uniform01(10 + t, B * n) * 0.9).astype(np.float32).reshape(B, n) for t, n in enumerate(widths)]
     syms = [np.arange(n, dtype=np.int32) for n in widths]
     tabs, tris, accs, cur = [], [], [ins[0]], syms[0]
@@ -159,7 +160,7 @@ def test_fused_fold_with_clamping_and_explicit_gradient(dol, B):
     out2 = dol.Dist.empty(cur, B)
     dol.fold_apply2(dol.Fold(d_in, ftabs, out=out2))                  # forward only
     np.testing.assert_array_equal(host(out2.prob), host(out.prob))
-    hashed = dol.FnTable.create_dense(W.hashed_table(1, 7, 3, 9))
+    hashed = dol.FnTable.create_dense(W.hashed_table(1, widths[0], widths[1], 9))
     with pytest.raises(dol.DolError) as ei:
         dol.fold_apply2(dol.Fold(d_in[:2], [hashed], out=dol.Dist.empty(hashed.out_syms, B)))
     assert ei.value.status == 5
