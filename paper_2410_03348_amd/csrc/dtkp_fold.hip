@@ -84,6 +84,8 @@ __device__ __forceinline__ void dtkp_fold_stage(const DtkpFoldArgs &A, int64_t s
             }
         };
         // offer < 0: nothing to offer (below every slot, absent ones included)
+        // (the kept probabilities are in descending order and the offer equals none of them: the new list is the larger
+        // of the first and the offer, then the median of each neighbouring pair and the offer)
         auto insert_untied = [&](float offer, int id) {
             bool gt[K];
 #pragma unroll
@@ -91,7 +93,7 @@ __device__ __forceinline__ void dtkp_fold_stage(const DtkpFoldArgs &A, int64_t s
 #pragma unroll
             for (int y = K - 1; y >= 0; --y) {
                 const bool above = y > 0 ? gt[y - 1] : false;
-                tp[y] = above ? tp[y - 1] : gt[y] ? offer : tp[y];
+                tp[y] = y > 0 ? __builtin_amdgcn_fmed3f(tp[y - 1], tp[y], offer) : fmaxf(tp[0], offer);
                 tid_[y] = above ? tid_[y - 1] : gt[y] ? id : tid_[y];
             }
         };
