@@ -51,10 +51,10 @@ enum { kSlotFwd = 0, kSlotBwd = 1, kSlotMergeFwd = 2, kSlotMergeBwd = 3, kSlotMe
 
 struct JitState {
     std::mutex mu;
-    hipModule_t mod[kSlots] = {};
-    hipFunction_t fn[kSlots] = {};
-    dol_status status[kSlots] = {};
-    bool tried[kSlots] = {};
+    hipModule_t mod[2 * kSlots] = {};        // (the second half: the builds for tiles of 32 samples)
+    hipFunction_t fn[2 * kSlots] = {};
+    dol_status status[2 * kSlots] = {};
+    bool tried[2 * kSlots] = {};
     ~JitState()
     {
         for (hipModule_t m : mod)
@@ -131,12 +131,15 @@ const char *kPrologue =
     "__device__ __forceinline__ void wave_lds_fence() {\n"
     "  __builtin_amdgcn_fence(__ATOMIC_RELEASE, \"wavefront\"); __builtin_amdgcn_wave_barrier(); __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, \"wavefront\"); }\n";
 
+// Samples per tile of the source being written: 64, or 32 (half of the lanes idle) for the builds that small batches use.
+thread_local int t_tile_rows = 64;
+
 void emit_tile_head(Src &o)
 {
     // (one tile per workgroup: inside a loop over tiles the compiler keeps every thread-constant offset of the body alive
     // across it, in registers the body needs)
     o("  {\n  const int tile = blockIdx.x;\n");
-    o("  const long long s0 = (long long)tile * tile_rows;\n  const int valid = batch - s0 < tile_rows ? (int)(batch - s0) : tile_rows;\n");
+    o("  const long long s0 = (long long)tile * %d;\n  const int valid = batch - s0 < %d ? (int)(batch - s0) : %d;\n", t_tile_rows, t_tile_rows, t_tile_rows);
 }
 
 // Forward.  merged: the kept symbols of the result are merged with a third Distribution c in the same launch
@@ -156,14 +159,14 @@ std::string forward_source(const dol_fn_table *f, bool merged, bool aligned = fa
     if (body)
         o("static __device__ __forceinline__ void damp_table_merge_fwd_body(float *lds, const float *__restrict__ a, const float *__restrict__ b, "
           "const float *__restrict__ c, float *__restrict__ out, const int *__restrict__ ia, const int *__restrict__ ib, int *saved, "
-          "int batch, int tile_rows, int nc, int n3)\n{\n");
+          "int batch, int n_tiles, int nc, int n3)\n{\n");
     else if (merged)
         o("extern \"C\" __global__ void __launch_bounds__(%d) __attribute__((amdgpu_waves_per_eu(2, 2))) damp_table_merge_fwd_kernel(const float *__restrict__ a, const float *__restrict__ b, "
           "const float *__restrict__ c, float *__restrict__ out, const int *__restrict__ ia, const int *__restrict__ ib, int *__restrict__ saved, "
-          "int batch, int tile_rows, int nc, int n3)\n{\n", kThreads);
+          "int batch, int n_tiles, int nc, int n3)\n{\n", kThreads);
     else
         o("extern \"C\" __global__ void __launch_bounds__(%d) __attribute__((amdgpu_waves_per_eu(2, 2))) damp_table_fwd_kernel(const float *__restrict__ a, const float *__restrict__ b, "
-          "float *__restrict__ out, int batch, int tile_rows)\n{\n", kThreads);
+          "float *__restrict__ out, int batch, int n_tiles)\n{\n", kThreads);
     if (!body) o("  __shared__ __align__(16) float lds[%d];\n", stage_floats + (merged ? kJitTile : 0));
     o("  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // (a scalar: branches on it are uniform)\n");
     o("  float *sa = lds, *sb = lds + %d, *so = lds + wave * %d;\n", kJitTile * pa, merged ? 0 : kJitTile * po);
@@ -318,15 +321,15 @@ std::string backward_source(const dol_fn_table *f, bool merged, bool aligned = f
         o("static __device__ __forceinline__ void damp_table_merge_bwd_body(float *lds, const float *__restrict__ a, const float *__restrict__ b, "
           "const float *__restrict__ c, const float *__restrict__ g, float *__restrict__ ga, float *__restrict__ gb, float *__restrict__ gc, "
           "const int *__restrict__ ia, const int *__restrict__ ib, const int *__restrict__ ca, const int *__restrict__ cb, "
-          "const int *saved, int batch, int tile_rows, int nc, int n3, int accumulate)\n{\n");
+          "const int *saved, int batch, int n_tiles, int nc, int n3, int accumulate)\n{\n");
     else if (merged)
         o("extern \"C\" __global__ void __launch_bounds__(%d) __attribute__((amdgpu_waves_per_eu(2, 2))) damp_table_merge_bwd_kernel(const float *__restrict__ a, const float *__restrict__ b, "
           "const float *__restrict__ c, const float *__restrict__ g, float *__restrict__ ga, float *__restrict__ gb, float *__restrict__ gc, "
           "const int *__restrict__ ia, const int *__restrict__ ib, const int *__restrict__ ca, const int *__restrict__ cb, "
-          "const int *__restrict__ saved, int batch, int tile_rows, int nc, int n3, int accumulate)\n{\n", kThreads);
+          "const int *__restrict__ saved, int batch, int n_tiles, int nc, int n3, int accumulate)\n{\n", kThreads);
     else
         o("extern \"C\" __global__ void __launch_bounds__(%d) __attribute__((amdgpu_waves_per_eu(2, 2))) damp_table_bwd_kernel(const float *__restrict__ a, const float *__restrict__ b, "
-          "const float *__restrict__ g, float *__restrict__ ga, float *__restrict__ gb, int batch, int tile_rows, int accumulate)\n{\n", kThreads);
+          "const float *__restrict__ g, float *__restrict__ ga, float *__restrict__ gb, int batch, int n_tiles, int accumulate)\n{\n", kThreads);
     if (!body) o("  __shared__ __align__(16) float lds[%d];\n", off_f + 4);
     o("  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // (a scalar: branches on it are uniform)\n");
     o("  float *sa = lds, *sb = lds + %d, *sg0 = lds + %d, *sg1 = lds + %d;\n", off_b, off_g, off_g + stage);
@@ -496,12 +499,12 @@ std::string both_source(const dol_fn_table *f, bool aligned)
     o("extern \"C\" __global__ void __launch_bounds__(%d) __attribute__((amdgpu_waves_per_eu(2, 2))) damp_table_merge_fwd_bwd_kernel("
       "const float *__restrict__ a, const float *__restrict__ b, const float *__restrict__ c, float *__restrict__ out, "
       "const float *__restrict__ g, float *__restrict__ ga, float *__restrict__ gb, float *__restrict__ gc, const int *__restrict__ ia, "
-      "const int *__restrict__ ib, const int *__restrict__ ca, const int *__restrict__ cb, int *saved, int batch, int tile_rows, int nc, int n3, "
+      "const int *__restrict__ ib, const int *__restrict__ ca, const int *__restrict__ cb, int *saved, int batch, int n_tiles, int nc, int n3, "
       "int accumulate)\n{\n", kThreads);
     o("  __shared__ __align__(16) float lds[%d];\n", std::max(lf, lb));
-    o("  damp_table_merge_fwd_body(lds, a, b, c, out, ia, ib, saved, batch, tile_rows, nc, n3);\n");
+    o("  damp_table_merge_fwd_body(lds, a, b, c, out, ia, ib, saved, batch, n_tiles, nc, n3);\n");
     o("  __syncthreads();\n");
-    o("  damp_table_merge_bwd_body(lds, a, b, c, g, ga, gb, gc, ia, ib, ca, cb, saved, batch, tile_rows, nc, n3, accumulate);\n}\n");
+    o("  damp_table_merge_bwd_body(lds, a, b, c, g, ga, gb, gc, ia, ib, ca, cb, saved, batch, n_tiles, nc, n3, accumulate);\n}\n");
     return o.s;
 }
 
@@ -552,7 +555,8 @@ unsigned tile_grid(int n_tiles) { return static_cast<unsigned>(n_tiles); }
 // Samples per workgroup.  The registers of these kernels allow two workgroups on a compute unit; a batch whose full
 // tiles number no more than the 256 units would leave every unit with one workgroup, its loads, arithmetic and stores
 // one after the other.  Such a batch is cut into half tiles (lanes 32 to 63 idle): two workgroups per unit overlap
-// (config 3 at B = 16384, both ways in one launch: 30.3 against 33.7 us).
+// (config 3 at B = 16384, both ways in one launch: 29.0 against 33.7 us).  The tile's size is a constant of the code: a table
+// has a build for each size it has been launched at.
 constexpr int32_t kHalfTileMaxBatch = 256 * kJitTile;
 int tile_rows_for(int32_t batch) { return batch <= kHalfTileMaxBatch ? kJitTile / 2 : kJitTile; }
 
@@ -569,8 +573,9 @@ JitState *state_of(const dol_fn_table *f)
 }  // namespace
 
 // The kernel of `slot` for this table, built on first use.
-static dol_status kernel_of(const dol_fn_table *f, int slot, hipFunction_t *fn)
+static dol_status kernel_of(const dol_fn_table *f, int kind, int tile_rows, hipFunction_t *fn)
 {
+    const int slot = kind + (tile_rows == kJitTile ? 0 : kSlots);
     static const char *const names[kSlots] = {"damp_table_fwd_kernel", "damp_table_bwd_kernel", "damp_table_merge_fwd_kernel",
                                               "damp_table_merge_bwd_kernel", "damp_table_merge_fwd_kernel", "damp_table_merge_bwd_kernel",
                                               "damp_table_merge_fwd_bwd_kernel", "damp_table_merge_fwd_bwd_kernel"};
@@ -578,11 +583,13 @@ static dol_status kernel_of(const dol_fn_table *f, int slot, hipFunction_t *fn)
     std::lock_guard<std::mutex> lock(js->mu);
     if (!js->tried[slot]) {
         js->tried[slot] = true;
-        const std::string src = slot == kSlotFwd ? forward_source(f, false) : slot == kSlotBwd ? backward_source(f, false) :
-                                slot == kSlotMergeFwd ? forward_source(f, true) : slot == kSlotMergeBwd ? backward_source(f, true) :
-                                slot == kSlotMergeFwdAligned ? forward_source(f, true, true) :
-                                slot == kSlotMergeBwdAligned ? backward_source(f, true, true) : both_source(f, slot == kSlotMergeBothAligned);
-        js->status[slot] = jit_compile(src, names[slot], &js->mod[slot], &js->fn[slot]);
+        t_tile_rows = tile_rows;
+        const std::string src = kind == kSlotFwd ? forward_source(f, false) : kind == kSlotBwd ? backward_source(f, false) :
+                                kind == kSlotMergeFwd ? forward_source(f, true) : kind == kSlotMergeBwd ? backward_source(f, true) :
+                                kind == kSlotMergeFwdAligned ? forward_source(f, true, true) :
+                                kind == kSlotMergeBwdAligned ? backward_source(f, true, true) : both_source(f, kind == kSlotMergeBothAligned);
+        t_tile_rows = kJitTile;
+        js->status[slot] = jit_compile(src, names[kind], &js->mod[slot], &js->fn[slot]);
         if (js->status[slot] != DOL_OK) return js->status[slot];      // with the compiler's message
     } else if (js->status[slot] != DOL_OK) {
         return fail(js->status[slot], "the code of this function table did not build (see the first call's message)");
@@ -599,9 +606,9 @@ dol_status launch_damp_table_fwd(const dol_fn_table *f, int32_t batch, const flo
     if (!table_code_ok(f) || batch < 1) return DOL_OK;
     if (lda != f->na || ldb != f->nb || ldo != f->n_out || !aligned16(a) || !aligned16(b) || !aligned16(out)) return DOL_OK;
     hipFunction_t fn = nullptr;
-    if (dol_status s = kernel_of(f, kSlotFwd, &fn)) return s;
+    if (dol_status s = kernel_of(f, kSlotFwd, tile_rows_for(batch), &fn)) return s;
     int tile_rows = tile_rows_for(batch), n_tiles = (batch + tile_rows - 1) / tile_rows;
-    void *args[] = {&a, &b, &out, &batch, &tile_rows};
+    void *args[] = {&a, &b, &out, &batch, &n_tiles};
     DOL_HIP(hipModuleLaunchKernel(fn, tile_grid(n_tiles), 1, 1, kThreads, 1, 1, 0, st, args, nullptr));
     *done = true;
     return DOL_OK;
@@ -617,9 +624,9 @@ dol_status launch_damp_table_bwd(const dol_fn_table *f, int32_t batch, const flo
         !aligned16(gb))
         return DOL_OK;
     hipFunction_t fn = nullptr;
-    if (dol_status s = kernel_of(f, kSlotBwd, &fn)) return s;
+    if (dol_status s = kernel_of(f, kSlotBwd, tile_rows_for(batch), &fn)) return s;
     int tile_rows = tile_rows_for(batch), n_tiles = (batch + tile_rows - 1) / tile_rows;
-    void *args[] = {&a, &b, &g, &ga, &gb, &batch, &tile_rows, &accumulate};
+    void *args[] = {&a, &b, &g, &ga, &gb, &batch, &n_tiles, &accumulate};
     DOL_HIP(hipModuleLaunchKernel(fn, tile_grid(n_tiles), 1, 1, kThreads, 1, 1, 0, st, args, nullptr));
     *done = true;
     return DOL_OK;
@@ -631,10 +638,10 @@ dol_status launch_damp_table_merge_fwd(const dol_fn_table *f, const UnionPlan *p
                                        const float *c, float *out, int32_t *saved, hipStream_t st)
 {
     hipFunction_t fn = nullptr;
-    if (dol_status s = kernel_of(f, p->aligned ? kSlotMergeFwdAligned : kSlotMergeFwd, &fn)) return s;
+    if (dol_status s = kernel_of(f, p->aligned ? kSlotMergeFwdAligned : kSlotMergeFwd, tile_rows_for(batch), &fn)) return s;
     int tile_rows = tile_rows_for(batch), n_tiles = (batch + tile_rows - 1) / tile_rows, nc = p->nb, n3 = p->n_out;
     const int32_t *ia = p->d_ia.ptr, *ib = p->d_ib.ptr;
-    void *args[] = {&a, &b, &c, &out, &ia, &ib, &saved, &batch, &tile_rows, &nc, &n3};
+    void *args[] = {&a, &b, &c, &out, &ia, &ib, &saved, &batch, &n_tiles, &nc, &n3};
     DOL_HIP(hipModuleLaunchKernel(fn, tile_grid(n_tiles), 1, 1, kThreads, 1, 1, 0, st, args, nullptr));
     return DOL_OK;
 }
@@ -644,10 +651,10 @@ dol_status launch_damp_table_merge_bwd(const dol_fn_table *f, const UnionPlan *p
                                        int32_t accumulate, hipStream_t st)
 {
     hipFunction_t fn = nullptr;
-    if (dol_status s = kernel_of(f, p->aligned ? kSlotMergeBwdAligned : kSlotMergeBwd, &fn)) return s;
+    if (dol_status s = kernel_of(f, p->aligned ? kSlotMergeBwdAligned : kSlotMergeBwd, tile_rows_for(batch), &fn)) return s;
     int tile_rows = tile_rows_for(batch), n_tiles = (batch + tile_rows - 1) / tile_rows, nc = p->nb, n3 = p->n_out;
     const int32_t *ia = p->d_ia.ptr, *ib = p->d_ib.ptr, *ca = p->d_ca.ptr, *cb = p->d_cb.ptr;
-    void *args[] = {&a, &b, &c, &g, &ga, &gb, &gc, &ia, &ib, &ca, &cb, &saved, &batch, &tile_rows, &nc, &n3, &accumulate};
+    void *args[] = {&a, &b, &c, &g, &ga, &gb, &gc, &ia, &ib, &ca, &cb, &saved, &batch, &n_tiles, &nc, &n3, &accumulate};
     DOL_HIP(hipModuleLaunchKernel(fn, tile_grid(n_tiles), 1, 1, kThreads, 1, 1, 0, st, args, nullptr));
     return DOL_OK;
 }
@@ -657,10 +664,10 @@ dol_status launch_damp_table_merge_both(const dol_fn_table *f, const UnionPlan *
                                         int32_t accumulate, hipStream_t st)
 {
     hipFunction_t fn = nullptr;
-    if (dol_status s = kernel_of(f, p->aligned ? kSlotMergeBothAligned : kSlotMergeBoth, &fn)) return s;
+    if (dol_status s = kernel_of(f, p->aligned ? kSlotMergeBothAligned : kSlotMergeBoth, tile_rows_for(batch), &fn)) return s;
     int tile_rows = tile_rows_for(batch), n_tiles = (batch + tile_rows - 1) / tile_rows, nc = p->nb, n3 = p->n_out;
     const int32_t *ia = p->d_ia.ptr, *ib = p->d_ib.ptr, *ca = p->d_ca.ptr, *cb = p->d_cb.ptr;
-    void *args[] = {&a, &b, &c, &out, &g, &ga, &gb, &gc, &ia, &ib, &ca, &cb, &saved, &batch, &tile_rows, &nc, &n3, &accumulate};
+    void *args[] = {&a, &b, &c, &out, &g, &ga, &gb, &gc, &ia, &ib, &ca, &cb, &saved, &batch, &n_tiles, &nc, &n3, &accumulate};
     DOL_HIP(hipModuleLaunchKernel(fn, tile_grid(n_tiles), 1, 1, kThreads, 1, 1, 0, st, args, nullptr));
     return DOL_OK;
 }
