@@ -356,6 +356,12 @@ dol_status dol_iterate_backward(const dol_dist *e, const dol_fn_table *f, int32_
                                 const float *grad_out, int64_t grad_out_ld, float *grad_r0, float *grad_e,
                                 void *hip_stream);
 int32_t dol_iterate_ckpt_count(int32_t rounds, int32_t ckpt_every);
+/* A checkpoint interval for `rounds` rounds of f over `batch` samples: the fewest segments whose rows fit the LDS a
+ * workgroup of the reverse sweep gets (a whole compute unit's while the batch leaves units idle, its share of one
+ * otherwise).  Host only, no device work; 1 when f is NULL or rounds <= 1.  Any interval >= 1 that fits is valid for the
+ * calls below; this is the one the library's own measurements favour (App. B, Fig. 9: the recursion with a fixed round
+ * count). */
+int32_t dol_iterate_ckpt_every(const dol_fn_table *f, int32_t batch, int32_t rounds);
 dol_status dol_iterate_apply2_ckpt(const dol_dist *r0, const dol_dist *e, const dol_fn_table *f, int32_t rounds,
                                    int32_t ckpt_every, dol_dist *out, float *ckpt, void *hip_stream);
 dol_status dol_iterate_backward_ckpt(const dol_dist *r0, const dol_dist *e, const dol_fn_table *f, int32_t rounds,

@@ -544,6 +544,8 @@ def iterate_backward(e: Dist, f: FnTable, rounds: int, hist: torch.Tensor, grad_
 
 _lib.dol_iterate_ckpt_count.argtypes = [C.c_int32, C.c_int32]
 _lib.dol_iterate_ckpt_count.restype = C.c_int32
+_lib.dol_iterate_ckpt_every.argtypes = [C.c_void_p, C.c_int32, C.c_int32]
+_lib.dol_iterate_ckpt_every.restype = C.c_int32
 _lib.dol_iterate_apply2_ckpt.argtypes = [C.POINTER(_Dist), C.POINTER(_Dist), C.c_void_p, C.c_int32, C.c_int32,
                                          C.POINTER(_Dist), C.c_void_p, C.c_void_p]
 _lib.dol_iterate_backward_ckpt.argtypes = [C.POINTER(_Dist), C.POINTER(_Dist), C.c_void_p, C.c_int32, C.c_int32,
@@ -552,6 +554,11 @@ _lib.dol_iterate_backward_ckpt.argtypes = [C.POINTER(_Dist), C.POINTER(_Dist), C
 
 def iterate_ckpt_count(rounds: int, ckpt_every: int) -> int:
     return int(_lib.dol_iterate_ckpt_count(rounds, ckpt_every))
+
+
+def iterate_ckpt_every(f: FnTable, batch: int, rounds: int) -> int:
+    """The checkpoint interval the library favours for this table, batch and round count."""
+    return int(_lib.dol_iterate_ckpt_every(f._h, batch, rounds))
 
 
 def iterate_apply2_ckpt(r0: Dist, e: Dist, f: FnTable, rounds: int, ckpt_every: int, out: Dist,

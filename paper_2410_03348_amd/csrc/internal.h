@@ -94,6 +94,7 @@ struct dol_fn_table {
     int64_t n_tuples = 0;
     int32_t max_col_len = 0;             // most tuples landing in one column
     int32_t max_rowa_len = 0;            // most tuples of one symbol of the first operand
+    int32_t n_long_rowa = 0;               // first-operand rows among long_rows
     bool sum_like = false;               // every column's tuples have i ascending by 1 and j descending by 1
     bool conv_like = false;              // all na*nb tuples admitted and tuple (i, j) lands in column i + j:
                                          // the operator is a discrete convolution of the two tag rows

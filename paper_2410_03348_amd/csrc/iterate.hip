@@ -636,11 +636,12 @@ static dol_status launch_shape(const ItShape &sh, int32_t batch, size_t lds, hip
 
 static size_t fwd_lds(const dol_fn_table *f, const ItShape &sh) { return sizeof(float) * (2 * sh.row() + f->nb + 1); }
 
-// The shares of d loss / d e can wait in registers alone when no row has more tuples than the registers hold; the
-// words they are gathered through at the end then fit where the segment was.
+// The shares of d loss / d e can wait in registers alone when no row of the first operand has more tuples than the
+// registers hold (a long row of e only matters when the shares are gathered); the words they are gathered through at
+// the end then fit where the segment was.
 static bool shares_in_seg(const dol_fn_table *f, const ItShape &sh, int32_t every)
 {
-    return static_cast<int>(f->max_rowa_len) <= sh.CA && f->long_rows.n == 0 &&
+    return static_cast<int>(f->max_rowa_len) <= sh.CA && f->n_long_rowa == 0 &&
            static_cast<size_t>(f->n_tuples) <= (static_cast<size_t>(every) + 1) * sh.row();
 }
 
@@ -767,6 +768,21 @@ dol_status dol_iterate_backward(const dol_dist *e, const dol_fn_table *f, int32_
     if (grad_out_ld < f->na) return fail(DOL_ESHAPE, "grad_out_ld = %lld is smaller than %d", static_cast<long long>(grad_out_ld), f->na);
     return launch_iterate_bwd(e, f, rounds, hist, nullptr, 0, nullptr, hist_segment(f, e->batch, rounds), grad_out, grad_out_ld,
                               grad_r0, grad_e, static_cast<hipStream_t>(hip_stream));
+}
+
+int32_t dol_iterate_ckpt_every(const dol_fn_table *f, int32_t batch, int32_t rounds)
+{
+    if (!f || rounds <= 1 || f->na <= 0) return 1;
+    const ItShape sh = pick_shape(f, batch, true);
+    // a batch that leaves units idle: one workgroup has a unit's LDS to itself; else as many workgroups as fill a
+    // unit's 32 wavefronts share it
+    const size_t sharers = batch <= kOneLaunchBatch ? 1 : std::max(1, 32 / (sh.T / kWave));
+    const size_t budget = batch <= kOneLaunchBatch ? kItLdsMax - 4096 : kItLdsMax / sharers - 1024;
+    for (int32_t n_seg = 1; n_seg <= rounds; ++n_seg) {
+        const int32_t every = (rounds + n_seg - 1) / n_seg;
+        if (bwd_lds(f, sh, every) <= budget) return every;
+    }
+    return 1;
 }
 
 int32_t dol_iterate_ckpt_count(int32_t rounds, int32_t ckpt_every)

@@ -133,7 +133,7 @@ static dol_status build_table(int32_t na, int32_t nb, std::vector<Tuple> &tup, d
 
     std::vector<uint32_t> long_rows;
     for (int32_t i = 0; i < na; ++i) {
-        if (rowa_ptr[i + 1] - rowa_ptr[i] > static_cast<uint32_t>(kLongTableRow)) long_rows.push_back(static_cast<uint32_t>(i));
+        if (rowa_ptr[i + 1] - rowa_ptr[i] > static_cast<uint32_t>(kLongTableRow)) { long_rows.push_back(static_cast<uint32_t>(i)); ++tb->n_long_rowa; }
         tb->max_rowa_len = std::max(tb->max_rowa_len, static_cast<int32_t>(rowa_ptr[i + 1] - rowa_ptr[i]));
     }
     for (int32_t j = 0; j < nb; ++j)

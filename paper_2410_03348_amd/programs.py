@@ -402,19 +402,12 @@ class GridReachFused(Program):
 
     def __init__(self, w, device="cuda", ckpt_every=None, one_launch=False):
         B, side = w["p"].shape[0], w["side"]
-        if ckpt_every is None:
-            if B <= 512:                     # few samples, one workgroup per unit: the fewest segments of at most 24 rounds
-                R0 = max(w["rounds"], 1)     # whose rows fit LDS (each segment costs a checkpoint and a refill)
-                ckpt_every = -(-R0 // -(-R0 // 24))
-                row = next((r for r in (512, 1024, 2048) if side * side <= r), 4096) + 1     # floats between two rows in LDS
-                while ckpt_every > 8 and 4 * ((ckpt_every + 3) * row + w["edge_u"].size + 2) > 140 * 1024:
-                    ckpt_every -= 1
-            else:                            # many: 8 rounds of LDS leave room for more workgroups per unit
-                ckpt_every = 8
         self.batch, self.rounds, n = B, w["rounds"], side * side
         E = w["edge_u"].size
         self.E = E
         self.table = dol.FnTable.create_sparse(n, E + 1, w["tri_i"], w["tri_j"], w["tri_o"])
+        if ckpt_every is None:               # the fewest segments whose rows fit the LDS a workgroup gets at this batch
+            ckpt_every = dol.iterate_ckpt_every(self.table, B, max(w["rounds"], 1))
         n_tup = int(w["tri_i"].size)
         pe = torch.ones((B, E + 1), dtype=torch.float32, device=device)
         pe[:, :E] = _dev(w["p"], device)

@@ -478,7 +478,7 @@ def test_config5_fused_iteration(gp, dol, batch, side, rounds):
 
 
 @pytest.mark.parametrize("batch,side,rounds,every", [(256, 32, 64, 8), (256, 32, 64, 16), (33, 7, 20, 6), (33, 7, 20, 1),
-                                                      (2, 3, 5, 5), (2, 3, 5, 9), (5, 4, 1, 3), (3, 3, 0, 2), (7, 32, 64, 30)])
+                                                      (2, 3, 5, 5), (2, 3, 5, 9), (5, 4, 1, 3), (3, 3, 0, 2), (7, 32, 64, 30), (9, 32, 64, 32)])
 def test_config5_checkpointed_iteration(gp, dol, batch, side, rounds, every):
     """dol_iterate_apply2_ckpt / dol_iterate_backward_ckpt: only the last round and a checkpoint every `every` rounds
     leave the chip; the reverse sweep replays the rounds in between.  Same results as the oracle, and bit for bit
@@ -493,6 +493,7 @@ def test_config5_checkpointed_iteration(gp, dol, batch, side, rounds, every):
     assert_close(host(prog.grad_p), ref["grad_p"], "checkpointed reach grad")
     n_ck = dol.iterate_ckpt_count(rounds, every)
     assert n_ck == max(0, -(-rounds // every) - 1)
+    assert 1 <= dol.iterate_ckpt_every(prog.table, batch, rounds) <= max(rounds, 1)
     for x in range(n_ck):                                                   # the checkpoints are rounds of the history
         assert_close(host(prog.ckpt[x]), ref["hist"][(x + 1) * every], "checkpoint %d" % x)
     full = gp.GridReachFused(w, ckpt_every=0)
@@ -508,7 +509,7 @@ def test_config5_checkpointed_iteration(gp, dol, batch, side, rounds, every):
     assert ei.value.status == 1
 
 
-@pytest.mark.parametrize("batch,side,rounds,every", [(256, 32, 64, 22), (33, 7, 20, 6), (5, 4, 1, 8), (40, 12, 30, 30), (3, 3, 7, 2),
+@pytest.mark.parametrize("batch,side,rounds,every", [(256, 32, 64, 22), (256, 32, 64, 32), (33, 7, 20, 6), (5, 4, 1, 8), (40, 12, 30, 30), (3, 3, 7, 2),
                                                       (600, 7, 20, 6), (520, 32, 11, 8)])
 def test_config5_iteration_in_one_launch(gp, dol, batch, side, rounds, every):
     """dol_iterate_apply2_backward: both sweeps in one launch (in two, issued by the one call, for batches above 512).  With an upstream gradient: bit for bit the results of
