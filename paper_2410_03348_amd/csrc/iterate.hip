@@ -131,6 +131,49 @@ __device__ __forceinline__ uint32_t fixed_offset(uint32_t x)
     return x;
 }
 
+// `len` rounds inside LDS: row x + 1 (of `rows`, whose LDS address is rows_at) from row x, for x = 0 .. len - 1, a barrier
+// after each; pre[k] = the unclamped sums of the last round.  Eight rounds per trip: the row is then a constant on the
+// LDS instruction and the addresses of a thread's operands stay in registers.
+template <int T, int K, int CA, bool TAILS>
+__device__ __forceinline__ void rounds_in_rows(const float *rows, uint32_t rows_at, int len, const Cached<CA> (&col)[K],
+                                               const uint32_t *__restrict__ list, const float *le, float (&pre)[K])
+{
+    constexpr int RS = T * K + 1, U = 8;
+    constexpr uint32_t RB = RS * sizeof(float);
+    const int tid = threadIdx.x;
+    for (int xb = 0; xb < len; xb += U) {
+        const uint32_t base = rows_at + xb * RB;
+        uint32_t src[K][CA], dst[K];
+#pragma unroll
+        for (int k = 0; k < K; ++k) {
+            dst[k] = fixed_offset(base + static_cast<uint32_t>(tid + T * k) * 4u);
+#pragma unroll
+            for (int y = 0; y < CA; ++y) src[k][y] = fixed_offset(base + (col[k].t[y] & 0xffffu) * 4u);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (xb + u < len) {
+#pragma unroll
+                for (int k = 0; k < K; ++k) {
+                    float acc = 0.0f;
+#pragma unroll
+                    for (int y = 0; y < CA; ++y) acc = __builtin_fmaf(fabsf(lds_at(src[k][y] + u * RB)), col[k].e[y], acc);
+                    if constexpr (TAILS) {
+                        const float *x_cur = rows + (xb + u) * RS;
+                        for (uint32_t q = col[k].q0 + CA; q < col[k].q1; ++q) {
+                            const uint32_t tu = list[q];
+                            acc = __builtin_fmaf(fabsf(x_cur[tu & 0xffffu]), le[tu >> 16], acc);
+                        }
+                    }
+                    pre[k] = acc;
+                    lds_put(dst[k] + (u + 1) * RB, signed_tag(acc));
+                }
+                lds_barrier();
+            }
+        }
+    }
+}
+
 // ---------------------------------------------------------------- forward
 
 // One round from the row at `xc` into the row at `xn` (this thread's columns), then the workgroup's barrier.
@@ -217,10 +260,7 @@ __device__ __forceinline__ void iterate_forward(const ItFwdArgs &A, float *lds, 
                 for (int k = 0; k < K; ++k) seg[tid + T * k] = x0[tid + T * k];
                 lds_barrier();
             }
-            for (; t < A.rounds; ++t) {
-                const int x = t - t_keep;
-                iterate_round<T, K, CA, TAILS>(col, A.col_ij, seg + x * RS, seg + (x + 1) * RS, le, pre);
-            }
+            rounds_in_rows<T, K, CA, TAILS>(seg, lds_address(seg), A.rounds - t, col, A.col_ij, le, pre);
 #pragma unroll
             for (int k = 0; k < K; ++k) {
                 const int c = tid + T * k;
@@ -338,10 +378,9 @@ __device__ __forceinline__ void iterate_backward(const ItBwdArgs &A, float *lds,
     for (int l = 0; l < A.n_long; ++l) n_long_a += static_cast<int>(A.long_rows[l]) < na;
     int red_sel = 0;
     lds_barrier();                          // e is staged
-    // addresses in the first row of LDS: of the symbols a column's tuples read, of the columns a row's tuples read, of
-    // the thread's own symbols
+    // addresses in the first row of LDS: of the columns a row's tuples read, of the thread's own symbols
     const uint32_t lds0 = lds_address(lds);
-    uint32_t col_at[K][CA], row_at[K][CA], own_at[K];
+    uint32_t row_at[K][CA], own_at[K];
 #pragma unroll
     for (int k = 0; k < K; ++k) {
         load_cached_tags<CA, false>(col[k], le);
@@ -349,7 +388,6 @@ __device__ __forceinline__ void iterate_backward(const ItBwdArgs &A, float *lds,
         own_at[k] = fixed_offset(lds0 + static_cast<uint32_t>(tid + T * k) * 4u);
 #pragma unroll
         for (int y = 0; y < CA; ++y) {
-            col_at[k][y] = fixed_offset(lds0 + (col[k].t[y] & 0xffffu) * 4u);
             row_at[k][y] = fixed_offset(lds0 + (rowa[k].t[y] >> 16) * 4u);
         }
     }
@@ -379,37 +417,8 @@ __device__ __forceinline__ void iterate_backward(const ItBwdArgs &A, float *lds,
             const float *first = sg == 0 ? A.r0 + s * A.ldr : A.ckpt + (sg - 1) * plane + s * na;
             for (int c = tid; c < na; c += T) seg[c] = first[c];
             lds_barrier();
-            for (int xb = 0; xb < len; xb += U) {
-                const uint32_t base = (2 + xb) * RB;            // seg[xb]
-                uint32_t src[K][CA], dst[K];
-#pragma unroll
-                for (int k = 0; k < K; ++k) {
-                    dst[k] = fixed_offset(own_at[k] + base);
-#pragma unroll
-                    for (int y = 0; y < CA; ++y) src[k][y] = fixed_offset(col_at[k][y] + base);
-                }
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    if (xb + u < len) {
-#pragma unroll
-                        for (int k = 0; k < K; ++k) {
-                            float acc = 0.0f;
-#pragma unroll
-                            for (int y = 0; y < CA; ++y)
-                                acc = __builtin_fmaf(fabsf(lds_at(src[k][y] + u * RB)), col[k].e[y], acc);
-                            if constexpr (TAILS) {
-                                const float *x_cur = seg + (xb + u) * RS;
-                                for (uint32_t q = col[k].q0 + CA; q < col[k].q1; ++q) {
-                                    const uint32_t tu = A.col_ij[q];
-                                    acc = __builtin_fmaf(fabsf(x_cur[tu & 0xffffu]), le[tu >> 16], acc);
-                                }
-                            }
-                            lds_put(dst[k] + (u + 1) * RB, signed_tag(acc));
-                        }
-                        lds_barrier();
-                    }
-                }
-            }
+            float pre[K];
+            rounds_in_rows<T, K, CA, TAILS>(seg, lds_address(seg), len, col, A.col_ij, le, pre);
         }
         // ---- the gradient handed over by the later segment (or the upstream gradient), in G[0], meets the decision of
         // this segment's last round and goes where that round looks for it
