@@ -12,11 +12,11 @@
 // serves larger tables and padded or unaligned tensors.)  A column's tuples keep their ascending (i, j) order and
 // start from 0, so the sum is bit for bit the one dol_apply2 defines and the clamp decisions agree.
 //
-// Layout of a launch: a workgroup of four wavefronts owns a tile of 64 samples (of 32, half of the lanes idle, while
-// the batch would not give every compute unit two tiles of 64).  The tile's operand rows travel
+// Layout of a launch: a workgroup of four wavefronts owns a tile of 64 samples (batches too small to give every compute
+// unit two such tiles: eight wavefronts, or tiles of 32 samples; see build_for).  The tile's operand rows travel
 // HBM -> LDS with flat 16-byte loads (rows padded to a pitch of n + 4 floats, which keeps a lane's 16-byte reads of
 // its own row off its neighbours' banks), each lane pulls its sample's rows into registers, the wavefronts split
-// the work (forward: 64 output columns each; backward: half of the rows of one operand each), results go back
+// the work (forward: 64 output columns at a time each; backward: half of the rows of one operand each), results go back
 // through LDS and leave as flat 16-byte stores.
 //
 // Backward needs gh = g * [pre <= 1].  For tags in [0, 1] a column's sum is bounded by max(a) * sum(b) * M, M = the
@@ -38,7 +38,7 @@
 namespace dol {
 
 constexpr int kJitTile = 64;            // samples per tile = lanes per wavefront
-constexpr int kJitWaves = 4;
+constexpr int kJitWavesLarge = 4;       // wavefronts per workgroup: four, or eight in the builds for small batches
 constexpr int kJitGroup = 64;           // output columns a wavefront takes at a time
 constexpr int kJitMaxSym = 64;          // operand rows live in registers
 constexpr int kJitMaxOut = 1024;
@@ -51,10 +51,10 @@ enum { kSlotFwd = 0, kSlotBwd = 1, kSlotMergeFwd = 2, kSlotMergeBwd = 3, kSlotMe
 
 struct JitState {
     std::mutex mu;
-    hipModule_t mod[2 * kSlots] = {};        // (the second half: the builds for tiles of 32 samples)
-    hipFunction_t fn[2 * kSlots] = {};
-    dol_status status[2 * kSlots] = {};
-    bool tried[2 * kSlots] = {};
+    hipModule_t mod[3 * kSlots] = {};        // (a table has up to three builds of each kernel, see build_for)
+    hipFunction_t fn[3 * kSlots] = {};
+    dol_status status[3 * kSlots] = {};
+    bool tried[3 * kSlots] = {};
     ~JitState()
     {
         for (hipModule_t m : mod)
@@ -85,7 +85,10 @@ struct Src {
     }
 };
 
-constexpr int kThreads = kJitTile * kJitWaves;
+// Wavefronts per workgroup and samples per tile of the source being written.
+thread_local int t_waves = kJitWavesLarge, t_tile_rows = kJitTile;
+#define kJitWaves t_waves
+#define kThreads (kJitTile * t_waves)
 
 // Declares r0 .. r{n-1} and fills them from the lane's row of the staged tile (pitch n + 4 floats).
 void emit_row_to_regs(Src &o, const char *r, const char *tile, int n)
@@ -131,9 +134,6 @@ const char *kPrologue =
     "__device__ __forceinline__ void wave_lds_fence() {\n"
     "  __builtin_amdgcn_fence(__ATOMIC_RELEASE, \"wavefront\"); __builtin_amdgcn_wave_barrier(); __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, \"wavefront\"); }\n";
 
-// Samples per tile of the source being written: 64, or 32 (half of the lanes idle) for the builds that small batches use.
-thread_local int t_tile_rows = 64;
-
 void emit_tile_head(Src &o)
 {
     // (one tile per workgroup: inside a loop over tiles the compiler keeps every thread-constant offset of the body alive
@@ -149,8 +149,8 @@ std::string forward_source(const dol_fn_table *f, bool merged, bool aligned = fa
 {
     const int na = f->na, nb = f->nb, S = f->n_out;
     const int pa = na + 4, pb = nb + 4;
-    const int n_groups = (S + kJitGroup - 1) / kJitGroup;
-    const int po = merged ? S + 4 : kJitGroup + 4;     // pitch of the result stage: the whole tile, or a wavefront's group
+    const int fcols = kJitGroup * kJitWavesLarge / kJitWaves;       // columns a wavefront takes at a time: 64, or 32 of eight wavefronts
+    const int po = merged ? S + 4 : fcols + 4;         // pitch of the result stage: the whole tile, or a wavefront's columns
     const int in_floats = kJitTile * (pa + pb), out_floats = merged ? kJitTile * po : kJitWaves * kJitTile * po;
     const int stage_floats = std::max(in_floats, out_floats);
     Src o;
@@ -182,8 +182,8 @@ std::string forward_source(const dol_fn_table *f, bool merged, bool aligned = fa
     emit_row_to_regs(o, "a", "sa", na);
     emit_row_to_regs(o, "b", "sb", nb);
     o("  __syncthreads();\n");                  // the staged rows are spent: their LDS becomes the result stage
-    for (int g = 0; g < n_groups; ++g) {
-        const int c0 = g * kJitGroup, c1 = std::min(S, c0 + kJitGroup);
+    for (int g = 0; g * fcols < S; ++g) {
+        const int c0 = g * fcols, c1 = std::min(S, c0 + fcols);
         o("  if (wave == %d) {\n", g % kJitWaves);
         emit_columns(o, f, c0, c1, "    ");
         for (int c = c0; c < c1; c += 4)
@@ -311,8 +311,10 @@ std::string backward_source(const dol_fn_table *f, bool merged, bool aligned = f
     const int stage = std::max(kJitTile * pg, kJitTile * std::max(pa, pb));
     const int off_m = off_g + 2 * stage, off_u = off_m + kJitTile * n_groups * 2;
     const int off_x = off_u + (merged ? kJitTile * n_groups * 2 : 0), off_f = off_x + (merged ? 2 * S : 0);
-    // wavefronts 0, 1: the first and the second half of the rows of a (they keep b); 2, 3: the same for b
-    const int ha = std::min(na, std::max(4, (na / 2 + 3) & ~3)), hb = std::min(nb, std::max(4, (nb / 2 + 3) & ~3));
+    // the first half of the wavefronts share out the rows of a (they keep b), the second half those of b: two or four
+    // parts each, multiples of four rows
+    const int parts = kJitWaves / 2;
+    const int ha = std::min(na, std::max(4, (na / parts + 3) & ~3)), hb = std::min(nb, std::max(4, (nb / parts + 3) & ~3));
     const int gh_per_thread = (kJitTile * (kJitGroup / 4) + kThreads - 1) / kThreads;
     Src o;
     if (!body) o.s = kPrologue;
@@ -402,9 +404,9 @@ std::string backward_source(const dol_fn_table *f, bool merged, bool aligned = f
     // The four roles.  Every role runs the same sequence of workgroup barriers and takes part in the same flat
     // copies; only the multiply-adds differ.  While a group's multiply-adds run, the next group's loads are in flight.
     for (int w = 0; w < kJitWaves; ++w) {
-        const bool is_a = w < 2;
-        const int n = is_a ? na : nb, h = is_a ? ha : hb;
-        const int r0 = (w & 1) ? h : 0, r1 = (w & 1) ? n : h;
+        const bool is_a = w < parts;
+        const int n = is_a ? na : nb, h = is_a ? ha : hb, part = w % parts;
+        const int r0 = std::min(n, part * h), r1 = part + 1 == parts ? n : std::min(n, (part + 1) * h);
         const char *acc = is_a ? "x" : "y";
         o("  %sif (wave == %d) {\n", w ? "else " : "", w);
         for (int r = r0; r < r1; ++r) o("    float %s%d = 0.0f;\n", acc, r);
@@ -552,13 +554,23 @@ namespace {
 
 unsigned tile_grid(int n_tiles) { return static_cast<unsigned>(n_tiles); }
 
-// Samples per workgroup.  The registers of these kernels allow two workgroups on a compute unit; a batch whose full
-// tiles number no more than the 256 units would leave every unit with one workgroup, its loads, arithmetic and stores
-// one after the other.  Such a batch is cut into half tiles (lanes 32 to 63 idle): two workgroups per unit overlap
-// (config 3 at B = 16384, both ways in one launch: 29.0 against 33.7 us).  The tile's size is a constant of the code: a table
-// has a build for each size it has been launched at.
-constexpr int32_t kHalfTileMaxBatch = 256 * kJitTile;
-int tile_rows_for(int32_t batch) { return batch <= kHalfTileMaxBatch ? kJitTile / 2 : kJitTile; }
+// How a batch is cut up.  The registers of these kernels allow two wavefronts on a SIMD, and the chip has 256 compute
+// units.  With tiles of 64 samples and four wavefronts to a tile, a batch of up to 256 tiles leaves every unit with one
+// wavefront per SIMD and the tile's loads, arithmetic and stores one after the other.  Such a batch gets a build of its
+// own: up to 128 tiles' worth of samples are cut into tiles of 32 (half of the lanes idle, twice the workgroups), more
+// keep tiles of 64 and give each to eight wavefronts, which share its columns (rows, in the reverse pass) out finer.
+// Config 3 in one launch: 22.7 us at B = 8192 (tiles of 32; 23.2 with eight wavefronts), 27.3 us at B = 16384 (eight
+// wavefronts; 28.9 in tiles of 32, 32.2 in the build for large batches).
+struct JitBuild {
+    int rows, waves;        // samples per tile, wavefronts per workgroup
+    int variant;            // which of the table's builds
+};
+JitBuild build_for(int32_t batch)
+{
+    if (batch > 256 * kJitTile) return {kJitTile, kJitWavesLarge, 0};
+    if (batch > 128 * kJitTile) return {kJitTile, 2 * kJitWavesLarge, 1};
+    return {kJitTile / 2, kJitWavesLarge, 2};
+}
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -573,9 +585,9 @@ JitState *state_of(const dol_fn_table *f)
 }  // namespace
 
 // The kernel of `slot` for this table, built on first use.
-static dol_status kernel_of(const dol_fn_table *f, int kind, int tile_rows, hipFunction_t *fn)
+static dol_status kernel_of(const dol_fn_table *f, int kind, const JitBuild &bd, hipFunction_t *fn)
 {
-    const int slot = kind + (tile_rows == kJitTile ? 0 : kSlots);
+    const int slot = kind + bd.variant * kSlots;
     static const char *const names[kSlots] = {"damp_table_fwd_kernel", "damp_table_bwd_kernel", "damp_table_merge_fwd_kernel",
                                               "damp_table_merge_bwd_kernel", "damp_table_merge_fwd_kernel", "damp_table_merge_bwd_kernel",
                                               "damp_table_merge_fwd_bwd_kernel", "damp_table_merge_fwd_bwd_kernel"};
@@ -583,12 +595,12 @@ static dol_status kernel_of(const dol_fn_table *f, int kind, int tile_rows, hipF
     std::lock_guard<std::mutex> lock(js->mu);
     if (!js->tried[slot]) {
         js->tried[slot] = true;
-        t_tile_rows = tile_rows;
+        t_tile_rows = bd.rows, t_waves = bd.waves;
         const std::string src = kind == kSlotFwd ? forward_source(f, false) : kind == kSlotBwd ? backward_source(f, false) :
                                 kind == kSlotMergeFwd ? forward_source(f, true) : kind == kSlotMergeBwd ? backward_source(f, true) :
                                 kind == kSlotMergeFwdAligned ? forward_source(f, true, true) :
                                 kind == kSlotMergeBwdAligned ? backward_source(f, true, true) : both_source(f, kind == kSlotMergeBothAligned);
-        t_tile_rows = kJitTile;
+        t_tile_rows = kJitTile, t_waves = kJitWavesLarge;
         js->status[slot] = jit_compile(src, names[kind], &js->mod[slot], &js->fn[slot]);
         if (js->status[slot] != DOL_OK) return js->status[slot];      // with the compiler's message
     } else if (js->status[slot] != DOL_OK) {
@@ -606,10 +618,11 @@ dol_status launch_damp_table_fwd(const dol_fn_table *f, int32_t batch, const flo
     if (!table_code_ok(f) || batch < 1) return DOL_OK;
     if (lda != f->na || ldb != f->nb || ldo != f->n_out || !aligned16(a) || !aligned16(b) || !aligned16(out)) return DOL_OK;
     hipFunction_t fn = nullptr;
-    if (dol_status s = kernel_of(f, kSlotFwd, tile_rows_for(batch), &fn)) return s;
-    int tile_rows = tile_rows_for(batch), n_tiles = (batch + tile_rows - 1) / tile_rows;
+    if (dol_status s = kernel_of(f, kSlotFwd, build_for(batch), &fn)) return s;
+    const JitBuild bd = build_for(batch);
+    int n_tiles = (batch + bd.rows - 1) / bd.rows;
     void *args[] = {&a, &b, &out, &batch, &n_tiles};
-    DOL_HIP(hipModuleLaunchKernel(fn, tile_grid(n_tiles), 1, 1, kThreads, 1, 1, 0, st, args, nullptr));
+    DOL_HIP(hipModuleLaunchKernel(fn, tile_grid(n_tiles), 1, 1, kJitTile * bd.waves, 1, 1, 0, st, args, nullptr));
     *done = true;
     return DOL_OK;
 }
@@ -624,10 +637,11 @@ dol_status launch_damp_table_bwd(const dol_fn_table *f, int32_t batch, const flo
         !aligned16(gb))
         return DOL_OK;
     hipFunction_t fn = nullptr;
-    if (dol_status s = kernel_of(f, kSlotBwd, tile_rows_for(batch), &fn)) return s;
-    int tile_rows = tile_rows_for(batch), n_tiles = (batch + tile_rows - 1) / tile_rows;
+    if (dol_status s = kernel_of(f, kSlotBwd, build_for(batch), &fn)) return s;
+    const JitBuild bd = build_for(batch);
+    int n_tiles = (batch + bd.rows - 1) / bd.rows;
     void *args[] = {&a, &b, &g, &ga, &gb, &batch, &n_tiles, &accumulate};
-    DOL_HIP(hipModuleLaunchKernel(fn, tile_grid(n_tiles), 1, 1, kThreads, 1, 1, 0, st, args, nullptr));
+    DOL_HIP(hipModuleLaunchKernel(fn, tile_grid(n_tiles), 1, 1, kJitTile * bd.waves, 1, 1, 0, st, args, nullptr));
     *done = true;
     return DOL_OK;
 }
@@ -638,11 +652,12 @@ dol_status launch_damp_table_merge_fwd(const dol_fn_table *f, const UnionPlan *p
                                        const float *c, float *out, int32_t *saved, hipStream_t st)
 {
     hipFunction_t fn = nullptr;
-    if (dol_status s = kernel_of(f, p->aligned ? kSlotMergeFwdAligned : kSlotMergeFwd, tile_rows_for(batch), &fn)) return s;
-    int tile_rows = tile_rows_for(batch), n_tiles = (batch + tile_rows - 1) / tile_rows, nc = p->nb, n3 = p->n_out;
+    if (dol_status s = kernel_of(f, p->aligned ? kSlotMergeFwdAligned : kSlotMergeFwd, build_for(batch), &fn)) return s;
+    const JitBuild bd = build_for(batch);
+    int n_tiles = (batch + bd.rows - 1) / bd.rows, nc = p->nb, n3 = p->n_out;
     const int32_t *ia = p->d_ia.ptr, *ib = p->d_ib.ptr;
     void *args[] = {&a, &b, &c, &out, &ia, &ib, &saved, &batch, &n_tiles, &nc, &n3};
-    DOL_HIP(hipModuleLaunchKernel(fn, tile_grid(n_tiles), 1, 1, kThreads, 1, 1, 0, st, args, nullptr));
+    DOL_HIP(hipModuleLaunchKernel(fn, tile_grid(n_tiles), 1, 1, kJitTile * bd.waves, 1, 1, 0, st, args, nullptr));
     return DOL_OK;
 }
 
@@ -651,11 +666,12 @@ dol_status launch_damp_table_merge_bwd(const dol_fn_table *f, const UnionPlan *p
                                        int32_t accumulate, hipStream_t st)
 {
     hipFunction_t fn = nullptr;
-    if (dol_status s = kernel_of(f, p->aligned ? kSlotMergeBwdAligned : kSlotMergeBwd, tile_rows_for(batch), &fn)) return s;
-    int tile_rows = tile_rows_for(batch), n_tiles = (batch + tile_rows - 1) / tile_rows, nc = p->nb, n3 = p->n_out;
+    if (dol_status s = kernel_of(f, p->aligned ? kSlotMergeBwdAligned : kSlotMergeBwd, build_for(batch), &fn)) return s;
+    const JitBuild bd = build_for(batch);
+    int n_tiles = (batch + bd.rows - 1) / bd.rows, nc = p->nb, n3 = p->n_out;
     const int32_t *ia = p->d_ia.ptr, *ib = p->d_ib.ptr, *ca = p->d_ca.ptr, *cb = p->d_cb.ptr;
     void *args[] = {&a, &b, &c, &g, &ga, &gb, &gc, &ia, &ib, &ca, &cb, &saved, &batch, &n_tiles, &nc, &n3, &accumulate};
-    DOL_HIP(hipModuleLaunchKernel(fn, tile_grid(n_tiles), 1, 1, kThreads, 1, 1, 0, st, args, nullptr));
+    DOL_HIP(hipModuleLaunchKernel(fn, tile_grid(n_tiles), 1, 1, kJitTile * bd.waves, 1, 1, 0, st, args, nullptr));
     return DOL_OK;
 }
 
@@ -664,11 +680,12 @@ dol_status launch_damp_table_merge_both(const dol_fn_table *f, const UnionPlan *
                                         int32_t accumulate, hipStream_t st)
 {
     hipFunction_t fn = nullptr;
-    if (dol_status s = kernel_of(f, p->aligned ? kSlotMergeBothAligned : kSlotMergeBoth, tile_rows_for(batch), &fn)) return s;
-    int tile_rows = tile_rows_for(batch), n_tiles = (batch + tile_rows - 1) / tile_rows, nc = p->nb, n3 = p->n_out;
+    if (dol_status s = kernel_of(f, p->aligned ? kSlotMergeBothAligned : kSlotMergeBoth, build_for(batch), &fn)) return s;
+    const JitBuild bd = build_for(batch);
+    int n_tiles = (batch + bd.rows - 1) / bd.rows, nc = p->nb, n3 = p->n_out;
     const int32_t *ia = p->d_ia.ptr, *ib = p->d_ib.ptr, *ca = p->d_ca.ptr, *cb = p->d_cb.ptr;
     void *args[] = {&a, &b, &c, &out, &g, &ga, &gb, &gc, &ia, &ib, &ca, &cb, &saved, &batch, &n_tiles, &nc, &n3, &accumulate};
-    DOL_HIP(hipModuleLaunchKernel(fn, tile_grid(n_tiles), 1, 1, kThreads, 1, 1, 0, st, args, nullptr));
+    DOL_HIP(hipModuleLaunchKernel(fn, tile_grid(n_tiles), 1, 1, kJitTile * bd.waves, 1, 1, 0, st, args, nullptr));
     return DOL_OK;
 }
 

@@ -207,7 +207,7 @@ def test_config3_fused_filter_union(gp, batch, na, nb, n_out):
     np.testing.assert_array_equal(host(prog.gp2), host(per_op.gp2))
 
 
-@pytest.mark.parametrize("batch,na,nb,n_out,scale", [(16384, 64, 64, 256, 1.0), (16421, 64, 64, 256, 6.0), (1000, 64, 64, 256, 1.0), (333, 64, 64, 256, 12.0),
+@pytest.mark.parametrize("batch,na,nb,n_out,scale", [(16384, 64, 64, 256, 1.0), (16421, 64, 64, 256, 6.0), (12301, 64, 64, 256, 6.0), (1000, 64, 64, 256, 1.0), (333, 64, 64, 256, 12.0),
                                                       (65, 32, 16, 64, 9.0), (1, 16, 16, 8, 1.0), (200, 64, 64, 128, 30.0),
                                                       (130, 4, 64, 8, 3.0)])
 def test_config3_apply_filter_union_in_one_launch(gp, dol, batch, na, nb, n_out, scale):
@@ -252,7 +252,7 @@ def test_config3_apply_filter_union_in_one_launch(gp, dol, batch, na, nb, n_out,
     np.testing.assert_array_equal(host(gb), host(prog.gb))
 
 
-@pytest.mark.parametrize("batch,scale", [(16384, 1.0), (16421, 6.0), (333, 12.0), (64, 1.0), (1, 1.0)])
+@pytest.mark.parametrize("batch,scale", [(16384, 1.0), (16421, 6.0), (12301, 6.0), (333, 12.0), (64, 1.0), (1, 1.0)])
 def test_config3_forward_and_backward_in_one_launch(gp, dol, batch, scale):
     """dol_apply2_filter_union_forward_backward: the results of the two separate calls, bit for bit (clamp words included),
     with samples in which clamps act (scale > 1) and without."""
