@@ -349,7 +349,9 @@ dol_status dol_dtkp_fold_apply2(const dol_dtkp_fold *fold, const dol_prov *prov,
  *
  * The gradient w.r.t. e is summed in a fixed order (no atomics): two runs give the same bits.
  * DOL_EUNSUPPORTED when the table is not square, an operand has more than 4096 symbols, or the rows (for the
- * reverse sweep: ckpt_every + 3 rows of na tags, e, and one word per tuple) do not fit in 160 KB of LDS. */
+ * reverse sweep: ckpt_every + 3 rows of na tags, na rounded up to 512, 1024, 2048 or 4096, plus e; and one word per
+ * tuple when a symbol of the first operand has more tuples than a thread keeps in registers) do not fit in 160 KB of
+ * LDS.  dol_iterate_ckpt_every gives an interval that fits. */
 dol_status dol_iterate_apply2(const dol_dist *r0, const dol_dist *e, const dol_fn_table *f, int32_t rounds, float *hist,
                               void *hip_stream);
 dol_status dol_iterate_backward(const dol_dist *e, const dol_fn_table *f, int32_t rounds, const float *hist,
