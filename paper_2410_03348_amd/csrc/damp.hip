@@ -439,6 +439,77 @@ damp_apply2_bwd_kernel(Rows R, BwdTable T, const float *__restrict__ a, int64_t 
     });
 }
 
+// The same with the gated gradient row in LDS: one workgroup per sample first works out gh[c] = g[c] * [pre(c) <= 1] for
+// every column ONCE (a column's sum is re-derived only where out == 1), then every symbol of a and b adds up its tuples
+// from that row, in the order of its list.  The kernel above re-derives a column's decision for every tuple that reads
+// it: with many results at the clamp (the later rounds of a reachability sweep) that is most of its time.  Rows of more
+// than kLongTableRow tuples are summed by the whole workgroup: strided partial sums in list order, then the
+// wavefronts' totals in a fixed order.
+constexpr int kBwdStagedThreads = 1024;
+
+__global__ void __launch_bounds__(kBwdStagedThreads)
+damp_apply2_bwd_staged_kernel(BwdTable T, int32_t S, int32_t n_long, const uint32_t *__restrict__ long_rows,
+                              const float *__restrict__ a, int64_t lda, const float *__restrict__ b, int64_t ldb,
+                              const float *__restrict__ out, int64_t ldo, const float *__restrict__ g, int64_t ldg,
+                              float *__restrict__ ga, float *__restrict__ gb, int32_t accumulate)
+{
+    extern __shared__ float gh[];           // [S], then one float per wavefront
+    float *red = gh + S;
+    const int tid = threadIdx.x;
+    const int64_t s = blockIdx.x;
+    const float *ar = a + s * lda, *br = b + s * ldb, *outr = out + s * ldo, *gr = g + s * ldg;
+    for (int c = tid; c < S; c += kBwdStagedThreads)
+        gh[c] = gated_grad(gr[c], outr[c], ar, br, T.col_ptr, T.col_ij, static_cast<uint32_t>(c));
+    __syncthreads();
+    for (int x = tid; x < T.na + T.nb; x += kBwdStagedThreads) {
+        const bool is_a = x < T.na;
+        if (is_a ? !ga : !gb) continue;
+        const int r = is_a ? x : x - T.na;
+        const uint32_t *ent = is_a ? T.rowa_jc : T.rowb_ic;
+        const float *other = is_a ? br : ar;
+        const uint32_t q0 = (is_a ? T.rowa_ptr : T.rowb_ptr)[r], q1 = (is_a ? T.rowa_ptr : T.rowb_ptr)[r + 1];
+        if (q1 - q0 > static_cast<uint32_t>(kLongTableRow)) continue;
+        float acc = 0.0f;
+        for (uint32_t q = q0; q < q1; ++q) {
+            const uint32_t e = ent[q];
+            acc = __builtin_fmaf(gh[e >> 16], other[e & 0xffffu], acc);
+        }
+        float *dst = is_a ? ga + s * lda + r : gb + s * ldb + r;
+        *dst = (is_a ? (accumulate & 1) : (accumulate & 2)) ? *dst + acc : acc;
+    }
+    for (int l = 0; l < n_long; ++l) {
+        const int x = static_cast<int>(long_rows[l]);
+        const bool is_a = x < T.na;
+        if (is_a ? !ga : !gb) continue;     // (the same for every thread)
+        const int r = is_a ? x : x - T.na;
+        const uint32_t *ent = is_a ? T.rowa_jc : T.rowb_ic;
+        const float *other = is_a ? br : ar;
+        const uint32_t q0 = (is_a ? T.rowa_ptr : T.rowb_ptr)[r], q1 = (is_a ? T.rowa_ptr : T.rowb_ptr)[r + 1];
+        float acc = 0.0f;
+        for (uint32_t q = q0 + tid; q < q1; q += kBwdStagedThreads) {
+            const uint32_t e = ent[q];
+            acc = __builtin_fmaf(gh[e >> 16], other[e & 0xffffu], acc);
+        }
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) acc += __shfl_xor(acc, d, kWave);
+        __syncthreads();                    // (the last row's totals have been read)
+        if ((tid & (kWave - 1)) == 0) red[tid / kWave] = acc;
+        __syncthreads();
+        if (tid == 0) {
+            float tot = 0.0f;
+            for (int w = 0; w < kBwdStagedThreads / kWave; ++w) tot += red[w];
+            float *dst = is_a ? ga + s * lda + r : gb + s * ldb + r;
+            *dst = (is_a ? (accumulate & 1) : (accumulate & 2)) ? *dst + tot : tot;
+        }
+    }
+}
+
+// Tables the staged kernel takes: enough symbols to give a workgroup per sample its work, a result row that fits LDS.
+bool apply2_bwd_staged(const dol_fn_table *f)
+{
+    return f->n_out >= 256 && f->na + f->nb >= 1024 && sizeof(float) * (f->n_out + kBwdStagedThreads / kWave) <= kStageMaxBytes;
+}
+
 // Gradient of row i of a from the dense map, one j at a time (ascending j, the order of the row's tuple list), and
 // the row's shares gh * a[i] of the gradient of b (added to pb where SHARES).  `clamped`: some column of the sample may
 // sit at the clamp, so `out` has to be looked at.  Empty map entries read element 0 and count as 0.
@@ -642,6 +713,15 @@ dol_status launch_damp_apply2_bwd(const dol_fn_table *f, int32_t batch, const fl
                                    b, ldb, out, ldo, g, ldg, ga, gb, accumulate)
         DOL_DISPATCH_NBP(f->byj_nbp, CALL)
 #undef CALL
+    }
+    else if (apply2_bwd_staged(f)) {
+        const size_t lds = sizeof(float) * (f->n_out + kBwdStagedThreads / kWave);
+        if (lds > 64 * 1024) DOL_HIP(allow_dynamic_lds(reinterpret_cast<const void *>(damp_apply2_bwd_staged_kernel), kStageMaxBytes));
+        hipLaunchKernelGGL(damp_apply2_bwd_staged_kernel, dim3(static_cast<unsigned>(batch)), dim3(kBwdStagedThreads), lds, st, T,
+                           f->n_out, static_cast<int32_t>(f->long_rows.n), f->long_rows.ptr, a, lda, b, ldb, out, ldo, g, ldg, ga, gb,
+                           accumulate);
+        DOL_HIP(hipGetLastError());
+        return DOL_OK;
     }
     else
         hipLaunchKernelGGL(damp_apply2_bwd_kernel, dim3(R.grid), dim3(kThreads), 0, st, R, T, a, lda, b, ldb, out, ldo, g,

@@ -36,7 +36,9 @@ static int pad_row(int n) { return ((n + 31) / 64) * 64 + 32; }
 // LDS and narrow enough to fit.
 bool staged_fwd_ok(const dol_fn_table *f)
 {
-    return std::max(f->na, f->nb) >= kStageMinRow && sizeof(float) * (static_cast<size_t>(f->na) + f->nb + 4) <= kStageMaxBytes;
+    // (rows of a thousand tags already: one round of reachability over a 32 x 32 grid, 1 024 x 1 985 symbols, at B=256
+    // takes 7.6 us through LDS against 9.7 us with cached gathers)
+    return std::max(f->na, f->nb) >= kStageMinRow / 2 && sizeof(float) * (static_cast<size_t>(f->na) + f->nb + 4) <= kStageMaxBytes;
 }
 
 // Tables walked through their per-j map whose first operand's row is worth staging in LDS, and fits.
@@ -54,7 +56,7 @@ std::string damp_kernel_name(const dol_fn_table *f, bool backward, int64_t batch
 {
     if (!conv_path_ok(f)) {
         if (table_code_ok(f)) return backward ? "damp_table_bwd_kernel" : "damp_table_fwd_kernel";
-        if (backward) return f->lds_bwd_ok ? "damp_lds_bwd_kernel" : !f->byj_ok ? "damp_apply2_bwd_kernel" : f->na + f->nb > 1024 ? "damp_byj_bwd_row_kernel" : "damp_byj_bwd_kernel";
+        if (backward) return f->lds_bwd_ok ? "damp_lds_bwd_kernel" : !f->byj_ok ? (apply2_bwd_staged(f) ? "damp_apply2_bwd_staged_kernel" : "damp_apply2_bwd_kernel") : f->na + f->nb > 1024 ? "damp_byj_bwd_row_kernel" : "damp_byj_bwd_kernel";
         return f->lds_fwd_ok ? "damp_lds_fwd_kernel" : f->byj_fwd ? (byj_fwd_staged_ok(f) ? "damp_byj_fwd_staged_kernel" : "damp_byj_fwd_kernel") :
                staged_fwd_ok(f) ? "damp_apply2_fwd_staged_kernel" : "damp_apply2_fwd_kernel";
     }

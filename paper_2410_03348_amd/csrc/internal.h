@@ -231,6 +231,7 @@ bool staged_fwd_ok(const dol_fn_table *f);   // forward through the kernel that 
 std::string damp_kernel_name(const dol_fn_table *f, bool backward, int64_t batch = 0);
 // Large batches of contiguous, 16-byte aligned tensors (damp_conv_rows.hip); false: the call was not taken.
 bool conv_rows_ok(const dol_fn_table *f, int64_t batch, bool backward);
+bool apply2_bwd_staged(const dol_fn_table *f);       // the tuple-list backward stages the gated gradient row in LDS
 bool launch_damp_conv_rows_fwd(const dol_fn_table *f, int32_t batch, const float *a, int64_t lda, const float *b, int64_t ldb,
                                float *out, int64_t ldo, hipStream_t st, dol_status *status);
 bool launch_damp_conv_rows_bwd(const dol_fn_table *f, int32_t batch, const float *a, int64_t lda, const float *b, int64_t ldb,

@@ -916,6 +916,55 @@ def check_sum_table(dol, na, nb, B, calm_from=None, kernel=None):
     assert_close(host(gb), wb, "sum bwd b alone")
 
 
+@pytest.mark.parametrize("B", [3, 70])
+def test_tuple_list_backward_with_the_gradient_row_staged(dol, B):
+    """A sparse table of 700 x 600 symbols onto 400 with a long row in either operand, tags large enough to put many
+    results on the clamp: dol_backward through the kernel that works out the gated gradient row once per sample, with
+    accumulation, one-sided calls and the decisions on the clamp compared with the oracle's."""
+    na, nb, S = 700, 600, 400
+    ti, tj, to = [], [], []
+    for i in range(na):                                 # a few tuples per symbol of a
+        for d in range(3):
+            ti.append(i); tj.append((i * 7 + d * 131) % (nb - 1) + 1); to.append((i * 3 + d * 17) % S)
+    for j in range(1, nb):                              # row 5 of a meets every symbol of b, symbol 0 of b every symbol of a
+        ti.append(5); tj.append(j); to.append((j * 11) % S)
+    for i in range(na):
+        ti.append(i); tj.append(0); to.append((i * 13 + 1) % S)
+    keys = sorted(set(zip(ti, tj)))
+    first = {}
+    for i, j, o in zip(ti, tj, to):
+        first.setdefault((i, j), o)
+    tri = tuple(np.asarray(x, np.int32) for x in ([k[0] for k in keys], [k[1] for k in keys], [first[k] for k in keys]))
+    a = (W.uniform01(1, B * na) * 0.9).astype(np.float32).reshape(B, na)
+    b = (W.uniform01(2, B * nb) * 0.5).astype(np.float32).reshape(B, nb)
+    b[:, 0] = 1.0
+    f = dol.FnTable.create_sparse(na, nb, *tri)
+    assert f.kernel_bwd == "damp_apply2_bwd_staged_kernel", f.kernel_bwd
+    syms, want, pre32, _ = oracle.damp_apply2_fwd(tri, na, nb, a, b, want_pre=True)
+    assert (pre32 > 1.0).mean() > 0.1 and (pre32 <= 1.0).mean() > 0.1
+    da, db = dol.Dist(np.arange(na), dev(a)), dol.Dist(np.arange(nb), dev(b))
+    do = dol.Dist.empty(syms, B)
+    dol.apply2(da, db, f, None, do)
+    np.testing.assert_array_equal(host(do.prob) == 1.0, pre32 >= 1.0)
+    g = np.abs(W.normal(3, B * syms.size)).astype(np.float32).reshape(B, -1)
+    wa, wb = oracle.damp_apply2_bwd(tri, na, nb, a, b, g)
+    ga, gb = torch.empty_like(da.prob), torch.empty_like(db.prob)
+    rec = dol.OpRecord(dol.OP_APPLY2, da, db, do, f=f)
+    dol.backward(rec, dev(g), ga, gb)
+    assert_close(host(ga), wa, "staged bwd a")
+    assert_close(host(gb), wb, "staged bwd b")
+    dol.backward(dol.OpRecord(dol.OP_APPLY2, da, db, do, f=f, accumulate=3), dev(g), ga, gb)
+    assert_close(host(ga), 2.0 * wa.astype(np.float64), "staged bwd a accumulated")
+    assert_close(host(gb), 2.0 * wb.astype(np.float64), "staged bwd b accumulated")
+    ga2, gb2 = torch.empty_like(ga), torch.empty_like(gb)
+    dol.backward(rec, dev(g), ga2, None)
+    dol.backward(rec, dev(g), None, gb2)
+    ga3, gb3 = torch.empty_like(ga), torch.empty_like(gb)
+    dol.backward(rec, dev(g), ga3, gb3)
+    np.testing.assert_array_equal(host(ga2), host(ga3))            # a fixed summation order: the same bits on every run
+    np.testing.assert_array_equal(host(gb2), host(gb3))
+
+
 def test_union_and_filter_edge_cases(dol):
     B = 50
     sa, sb = np.array([1, 4, 6, 8, 9], np.int32), np.array([0, 4, 9, 12], np.int32)
