@@ -100,8 +100,26 @@ struct TopK {
         return pa > pb || (pa == pb && ma < mb);
     }
 
+    // (a proof's probability is a function of its mask, so a candidate whose probability equals none of the kept ones is
+    // none of the kept proofs and ranks among them by probability alone: the kept list, sorted, takes it in through one
+    // max and K - 1 medians, and no mask is compared)
     __device__ __forceinline__ void insert(uint64_t mask, float prob)
     {
+        bool tie = false;
+#pragma unroll
+        for (int x = 0; x < K; ++x) tie |= (prob == p[x]);
+        if (!tie) {
+            bool gt[K];
+#pragma unroll
+            for (int x = 0; x < K; ++x) gt[x] = prob > p[x];
+#pragma unroll
+            for (int x = K - 1; x >= 0; --x) {
+                const bool above = x > 0 ? gt[x - 1] : false;
+                m[x] = above ? m[x - 1] : gt[x] ? mask : m[x];
+                p[x] = x > 0 ? __builtin_amdgcn_fmed3f(p[x - 1], p[x], prob) : fmaxf(p[0], prob);
+            }
+            return;
+        }
         bool dup = false;
 #pragma unroll
         for (int x = 0; x < K; ++x) dup |= (m[x] == mask);
