@@ -15,7 +15,7 @@ constexpr size_t kScratchFloats = size_t(4) << 20;     // 16 MiB per device, hel
 
 // One copy per device.  Host code never uses this name as an address: the address on the current device comes from
 // hipGetSymbolAddress (scratch_address) and is what the launches receive.
-__device__ __align__(256) float scratch[kScratchFloats];
+static __device__ __align__(256) float scratch[kScratchFloats];
 
 dol_status scratch_address(float **ptr)
 {
